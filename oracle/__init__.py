@@ -1,0 +1,140 @@
+"""ctypes wrapper around the plain-C CPU oracle (oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the
+benchmark's cpu_baseline leg.  It does not import, and is not imported by,
+the GPU package.  All arrays are host numpy arrays in the paper's
+channel-major layouts; results are float64 unless stated.
+"""
+import ctypes
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile oracle.c with gcc (OpenMP) into oracle/liboracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared",
+               "-std=c11", "-Wall", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_count_bad_neighbors.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise RuntimeError(f"{name} failed with status {rc}")
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def count_bad_neighbors(nbr, N) -> int:
+    nbr = _i32(nbr)
+    B, K, N_ = nbr.shape
+    assert N_ == N
+    return int(_load().oracle_count_bad_neighbors(_p(nbr), B, N, K))
+
+
+def flexconv_fwd(feat, pos, nbr, theta, bias, l_range=None):
+    """Returns float64 out [B,Dout,N] (columns outside l_range are zero)."""
+    feat, pos, theta, bias, nbr = _f32(feat), _f32(pos), _f32(theta), _f32(bias), _i32(nbr)
+    B, Din, N = feat.shape
+    K = nbr.shape[1]
+    Dout = theta.shape[2]
+    assert pos.shape == (B, 3, N) and nbr.shape == (B, K, N)
+    assert theta.shape == (3, Din, Dout) and bias.shape == (Din, Dout)
+    assert count_bad_neighbors(nbr, N) == 0
+    l0, l1 = (0, N) if l_range is None else l_range
+    out = np.zeros((B, Dout, N), np.float64)
+    _check(_load().oracle_flexconv_fwd(_p(feat), _p(pos), _p(nbr), _p(theta), _p(bias), _p(out),
+                                       B, N, K, Din, Dout, int(l0), int(l1)), "oracle_flexconv_fwd")
+    return out
+
+
+def flexconv_bwd(feat, pos, nbr, theta, bias, grad_out, l_range=None,
+                 want_feat=True, want_params=True):
+    """Returns (grad_feat [B,Din,N], grad_theta [3,Din,Dout], grad_bias [Din,Dout]) in float64."""
+    feat, pos, theta, bias, nbr = _f32(feat), _f32(pos), _f32(theta), _f32(bias), _i32(nbr)
+    grad_out = _f32(grad_out)
+    B, Din, N = feat.shape
+    K = nbr.shape[1]
+    Dout = theta.shape[2]
+    assert grad_out.shape == (B, Dout, N)
+    assert count_bad_neighbors(nbr, N) == 0
+    l0, l1 = (0, N) if l_range is None else l_range
+    gf = np.zeros((B, Din, N), np.float64) if want_feat else None
+    gt = np.zeros((3, Din, Dout), np.float64) if want_params else None
+    gb = np.zeros((Din, Dout), np.float64) if want_params else None
+    _check(_load().oracle_flexconv_bwd(_p(feat), _p(pos), _p(nbr), _p(theta), _p(bias), _p(grad_out),
+                                       _p(gf), _p(gt), _p(gb), B, N, K, Din, Dout, int(l0), int(l1)),
+           "oracle_flexconv_bwd")
+    return gf, gt, gb
+
+
+def flexconv_grad_feat_at(pos, nbr, theta, bias, grad_out, targets):
+    """grad_feat rows at flat targets (b*N+m): float64 [len(targets), Din]."""
+    pos, theta, bias, nbr, grad_out = _f32(pos), _f32(theta), _f32(bias), _i32(nbr), _f32(grad_out)
+    B, K, N = nbr.shape
+    _, Din, Dout = theta.shape
+    assert count_bad_neighbors(nbr, N) == 0
+    targets = np.ascontiguousarray(targets, dtype=np.int64)
+    out = np.zeros((targets.size, Din), np.float64)
+    _check(_load().oracle_flexconv_grad_feat_at(_p(pos), _p(nbr), _p(theta), _p(bias), _p(grad_out),
+                                                _p(targets), ctypes.c_int64(targets.size), _p(out),
+                                                B, N, K, Din, Dout), "oracle_flexconv_grad_feat_at")
+    return out
+
+
+def flexpool_fwd(feat, nbr, l_range=None):
+    """Returns (out float32 [B,C,N], argmax int32 [B,C,N])."""
+    feat, nbr = _f32(feat), _i32(nbr)
+    B, C, N = feat.shape
+    K = nbr.shape[1]
+    assert count_bad_neighbors(nbr, N) == 0
+    l0, l1 = (0, N) if l_range is None else l_range
+    out = np.zeros((B, C, N), np.float32)
+    arg = np.zeros((B, C, N), np.int32)
+    _check(_load().oracle_flexpool_fwd(_p(feat), _p(nbr), _p(out), _p(arg), B, N, K, C, int(l0), int(l1)),
+           "oracle_flexpool_fwd")
+    return out, arg
+
+
+def flexpool_bwd(grad_out, argmax, l_range=None):
+    """Returns grad_feat float64 [B,C,N]."""
+    grad_out, argmax = _f32(grad_out), _i32(argmax)
+    B, C, N = grad_out.shape
+    assert argmax.shape == (B, C, N)
+    assert argmax.min() >= 0 and argmax.max() < N
+    l0, l1 = (0, N) if l_range is None else l_range
+    gf = np.zeros((B, C, N), np.float64)
+    _check(_load().oracle_flexpool_bwd(_p(grad_out), _p(argmax), _p(gf), B, N, C, int(l0), int(l1)),
+           "oracle_flexpool_bwd")
+    return gf

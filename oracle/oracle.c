@@ -1,0 +1,295 @@
+/*
+ * CPU oracle for the flex-convolution layer and flex-max-pooling.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU
+ * library is checked against.  It shares no code with the HIP path and is
+ * called only from tests, the smoke check and the benchmark's CPU-baseline
+ * leg.  Nothing in the product path may call it.
+ *
+ * Everything is evaluated straight from the definitions, in double precision
+ * (inputs are the caller's float32 arrays, promoted element by element):
+ *
+ *   flex-conv forward   Eq.(4) (neighbourhood convolution: a plain sum over
+ *                       the K neighbours and the input channels) with the
+ *                       weight function of Eq.(6) (scalar product of a
+ *                       learnable theta with the position difference, plus a
+ *                       learnable bias; one parameter set per (c, c') pair,
+ *                       as the filter-bank signature of Eq.(5) implies).
+ *   flex-conv backward  the transposes of that bilinear map (the paper
+ *                       asserts differentiability in Sec. 3.1 and prints no
+ *                       formulas; they are derived here by differentiating
+ *                       the forward sum term by term).
+ *   flex-max-pool       Sec. 4.1: maximum over each point's neighbourhood,
+ *                       no subsampling; the forward pass also records which
+ *                       point won (Table 1's pooling memory is output plus a
+ *                       same-sized table; Sec. 4.2 notes the prepared
+ *                       intermediate), the backward pass routes by it.
+ *
+ * Readings of points the paper leaves open:
+ *   - position difference is (neighbour - centre), the orientation used in
+ *     the caption of Fig. 2; Eq.(6) writes (centre - neighbour), which is the
+ *     same layer with theta negated;
+ *   - no normalisation by K, no output bias, no activation (Eq.(4) has none);
+ *   - whether a point is its own neighbour is decided by the index tensor;
+ *   - duplicate indices contribute once per occurrence;
+ *   - pooling ties: among the neighbours attaining the maximum, the LOWEST
+ *     POINT INDEX wins (independent of slot order); -0 == +0 is a tie; the
+ *     output value is the winner's float bit pattern; NaN is unsupported;
+ *   - gradients overwrite their output arrays.
+ *
+ * Layouts (paper / channel-major): feat [B,Din,N], pos [B,3,N],
+ * nbr int32 [B,K,N] (per-cloud point indices in [0,N)), theta [3,Din,Dout],
+ * bias [Din,Dout], out / grad_out [B,Dout,N].
+ *
+ * Every routine takes a range [l_begin, l_end) of CENTRE points to process;
+ * the full result uses [0, N).  Ranged calls exist so a bounded share of a
+ * large workload can be timed; each centre's work is independent.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * (brute force via dense weight tensors, regular-grid reduction to ordinary
+ * correlation incl. Prewitt and box blur, theta = 0, translation invariance,
+ * finite differences, adjoint identities, grid max-pool).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define IDX3(a, b, c, nb, nc) ((((int64_t)(a)) * (nb) + (b)) * (int64_t)(nc) + (c))
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Range check of the index tensor: returns the number of entries outside [0,N). */
+int64_t oracle_count_bad_neighbors(const int32_t *nbr, int B, int N, int K)
+{
+    int64_t bad = 0;
+    for (int64_t i = 0; i < (int64_t)B * K * N; ++i)
+        bad += (nbr[i] < 0 || nbr[i] >= N);
+    return bad;
+}
+
+/* ---------------------------------------------------------------------------
+ * Flex-conv forward, Eq.(4) with Eq.(6):
+ *   out[b,o,l] = sum_k sum_c ( <theta[:,c,o], pos[b,:,n] - pos[b,:,l]> + bias[c,o] ) * feat[b,c,n],
+ *   n = nbr[b,k,l].
+ * out is double [B,Dout,N]; only columns l in [l_begin,l_end) are written.
+ * ------------------------------------------------------------------------- */
+int oracle_flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
+                        const float *theta, const float *bias, double *out,
+                        int B, int N, int K, int Din, int Dout, int l_begin, int l_end)
+{
+    if (!feat || !pos || !nbr || !theta || !bias || !out) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return 2;
+    if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc(sizeof(double) * Dout);
+#pragma omp for collapse(2) schedule(static)
+        for (int b = 0; b < B; ++b)
+            for (int l = l_begin; l < l_end; ++l) {
+                for (int o = 0; o < Dout; ++o) acc[o] = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    const int n = nbr[IDX3(b, k, l, K, N)];
+                    const double dx = (double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)];
+                    const double dy = (double)pos[IDX3(b, 1, n, 3, N)] - (double)pos[IDX3(b, 1, l, 3, N)];
+                    const double dz = (double)pos[IDX3(b, 2, n, 3, N)] - (double)pos[IDX3(b, 2, l, 3, N)];
+                    for (int c = 0; c < Din; ++c) {
+                        const double f = (double)feat[IDX3(b, c, n, Din, N)];
+                        const float *tx = theta + IDX3(0, c, 0, Din, Dout);
+                        const float *ty = theta + IDX3(1, c, 0, Din, Dout);
+                        const float *tz = theta + IDX3(2, c, 0, Din, Dout);
+                        const float *tb = bias + (int64_t)c * Dout;
+                        for (int o = 0; o < Dout; ++o) {
+                            const double w = (double)tx[o] * dx + (double)ty[o] * dy + (double)tz[o] * dz + (double)tb[o];
+                            acc[o] += w * f;
+                        }
+                    }
+                }
+                for (int o = 0; o < Dout; ++o) out[IDX3(b, o, l, Dout, N)] = acc[o];
+            }
+        free(acc);
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Flex-conv backward.  With g = grad_out and w(b,l,k,c,o) the weight above:
+ *   grad_feat [b,c,m] = sum over all (l,k) with nbr[b,k,l] = m of  sum_o w(b,l,k,c,o) * g[b,o,l]
+ *   grad_theta[d,c,o] = sum_b sum_l sum_k (pos[b,d,n]-pos[b,d,l]) * feat[b,c,n] * g[b,o,l]
+ *   grad_bias [c,o]   = sum_b sum_l sum_k                          feat[b,c,n] * g[b,o,l]
+ * Any of the three outputs may be NULL (skipped).  Outputs are double and are
+ * overwritten.  Only centres l in [l_begin,l_end) contribute.
+ * ------------------------------------------------------------------------- */
+int oracle_flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
+                        const float *theta, const float *bias, const float *grad_out,
+                        double *grad_feat, double *grad_theta, double *grad_bias,
+                        int B, int N, int K, int Din, int Dout, int l_begin, int l_end)
+{
+    if (!feat || !pos || !nbr || !theta || !bias || !grad_out) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return 2;
+    if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
+    const int64_t n_theta = (int64_t)3 * Din * Dout, n_bias = (int64_t)Din * Dout;
+    if (grad_feat) memset(grad_feat, 0, sizeof(double) * (size_t)B * Din * N);
+    if (grad_theta) memset(grad_theta, 0, sizeof(double) * (size_t)n_theta);
+    if (grad_bias) memset(grad_bias, 0, sizeof(double) * (size_t)n_bias);
+#pragma omp parallel
+    {
+        /* per-thread parameter-gradient accumulators, merged at the end */
+        double *gt = (double *)calloc((size_t)n_theta, sizeof(double));
+        double *gb = (double *)calloc((size_t)n_bias, sizeof(double));
+        double *g = (double *)malloc(sizeof(double) * Dout);
+#pragma omp for collapse(2) schedule(static)
+        for (int b = 0; b < B; ++b)
+            for (int l = l_begin; l < l_end; ++l) {
+                for (int o = 0; o < Dout; ++o) g[o] = (double)grad_out[IDX3(b, o, l, Dout, N)];
+                for (int k = 0; k < K; ++k) {
+                    const int n = nbr[IDX3(b, k, l, K, N)];
+                    const double dx = (double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)];
+                    const double dy = (double)pos[IDX3(b, 1, n, 3, N)] - (double)pos[IDX3(b, 1, l, 3, N)];
+                    const double dz = (double)pos[IDX3(b, 2, n, 3, N)] - (double)pos[IDX3(b, 2, l, 3, N)];
+                    for (int c = 0; c < Din; ++c) {
+                        const double f = (double)feat[IDX3(b, c, n, Din, N)];
+                        const float *tx = theta + IDX3(0, c, 0, Din, Dout);
+                        const float *ty = theta + IDX3(1, c, 0, Din, Dout);
+                        const float *tz = theta + IDX3(2, c, 0, Din, Dout);
+                        const float *tb = bias + (int64_t)c * Dout;
+                        double *gtx = gt + IDX3(0, c, 0, Din, Dout);
+                        double *gty = gt + IDX3(1, c, 0, Din, Dout);
+                        double *gtz = gt + IDX3(2, c, 0, Din, Dout);
+                        double *gbb = gb + (int64_t)c * Dout;
+                        double s = 0.0;
+                        for (int o = 0; o < Dout; ++o) {
+                            const double w = (double)tx[o] * dx + (double)ty[o] * dy + (double)tz[o] * dz + (double)tb[o];
+                            s += w * g[o];
+                            const double fg = f * g[o];
+                            gtx[o] += dx * fg;
+                            gty[o] += dy * fg;
+                            gtz[o] += dz * fg;
+                            gbb[o] += fg;
+                        }
+                        if (grad_feat) {
+#pragma omp atomic
+                            grad_feat[IDX3(b, c, n, Din, N)] += s;
+                        }
+                    }
+                }
+            }
+#pragma omp critical
+        {
+            if (grad_theta) for (int64_t i = 0; i < n_theta; ++i) grad_theta[i] += gt[i];
+            if (grad_bias) for (int64_t i = 0; i < n_bias; ++i) grad_bias[i] += gb[i];
+        }
+        free(gt); free(gb); free(g);
+    }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * grad_feat of flex-conv at selected target points only (for sampled parity
+ * at sizes where the full backward is too slow).  targets[i] = b*N + m.
+ * out is double [n_targets, Din].  Every edge (l,k) of every centre is
+ * scanned; an edge contributes when its neighbour is a listed target.
+ * ------------------------------------------------------------------------- */
+int oracle_flexconv_grad_feat_at(const float *pos, const int32_t *nbr,
+                                 const float *theta, const float *bias, const float *grad_out,
+                                 const int64_t *targets, int64_t n_targets, double *out,
+                                 int B, int N, int K, int Din, int Dout)
+{
+    if (!pos || !nbr || !theta || !bias || !grad_out || !targets || !out) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0 || n_targets < 0) return 2;
+    /* slot[b*N+m] = row of `out` (or -1) */
+    int64_t *slot = (int64_t *)malloc(sizeof(int64_t) * (size_t)B * N);
+    if (!slot) return 6;
+    for (int64_t i = 0; i < (int64_t)B * N; ++i) slot[i] = -1;
+    for (int64_t i = 0; i < n_targets; ++i) {
+        if (targets[i] < 0 || targets[i] >= (int64_t)B * N || slot[targets[i]] != -1) { free(slot); return 2; }
+        slot[targets[i]] = i;
+    }
+    memset(out, 0, sizeof(double) * (size_t)n_targets * Din);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l)
+            for (int k = 0; k < K; ++k) {
+                const int n = nbr[IDX3(b, k, l, K, N)];
+                const int64_t row = slot[(int64_t)b * N + n];
+                if (row < 0) continue;
+                const double dx = (double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)];
+                const double dy = (double)pos[IDX3(b, 1, n, 3, N)] - (double)pos[IDX3(b, 1, l, 3, N)];
+                const double dz = (double)pos[IDX3(b, 2, n, 3, N)] - (double)pos[IDX3(b, 2, l, 3, N)];
+                for (int c = 0; c < Din; ++c) {
+                    double s = 0.0;
+                    for (int o = 0; o < Dout; ++o) {
+                        const double w = (double)theta[IDX3(0, c, o, Din, Dout)] * dx
+                                       + (double)theta[IDX3(1, c, o, Din, Dout)] * dy
+                                       + (double)theta[IDX3(2, c, o, Din, Dout)] * dz
+                                       + (double)bias[(int64_t)c * Dout + o];
+                        s += w * (double)grad_out[IDX3(b, o, l, Dout, N)];
+                    }
+#pragma omp atomic
+                    out[row * Din + c] += s;
+                }
+            }
+    free(slot);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Flex-max-pool forward (Sec. 4.1): out[b,c,l] = max_k feat[b,c,nbr[b,k,l]],
+ * argmax[b,c,l] = index of the winning point (lowest point index on ties).
+ * out is float (a bit copy of the winning input).
+ * ------------------------------------------------------------------------- */
+int oracle_flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *argmax,
+                        int B, int N, int K, int C, int l_begin, int l_end)
+{
+    if (!feat || !nbr || !out || !argmax) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || C <= 0) return 2;
+    if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int l = l_begin; l < l_end; ++l)
+            for (int c = 0; c < C; ++c) {
+                int best = nbr[IDX3(b, 0, l, K, N)];
+                float bv = feat[IDX3(b, c, best, C, N)];
+                for (int k = 1; k < K; ++k) {
+                    const int n = nbr[IDX3(b, k, l, K, N)];
+                    const float v = feat[IDX3(b, c, n, C, N)];
+                    if (v > bv || (v == bv && n < best)) { bv = v; best = n; }
+                }
+                out[IDX3(b, c, l, C, N)] = bv;
+                argmax[IDX3(b, c, l, C, N)] = best;
+            }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Flex-max-pool backward: grad_feat[b,c,m] = sum of grad_out[b,c,l] over the
+ * centres l (in [l_begin,l_end)) whose recorded winner is m; zero elsewhere.
+ * grad_feat is double [B,C,N], overwritten.
+ * ------------------------------------------------------------------------- */
+int oracle_flexpool_bwd(const float *grad_out, const int32_t *argmax, double *grad_feat,
+                        int B, int N, int C, int l_begin, int l_end)
+{
+    if (!grad_out || !argmax || !grad_feat) return 1;
+    if (B <= 0 || N <= 0 || C <= 0) return 2;
+    if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
+    memset(grad_feat, 0, sizeof(double) * (size_t)B * C * N);
+    /* one (b,c) row per iteration: rows are independent, so no atomics */
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < C; ++c)
+            for (int l = l_begin; l < l_end; ++l) {
+                const int m = argmax[IDX3(b, c, l, C, N)];
+                grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out[IDX3(b, c, l, C, N)];
+            }
+    return 0;
+}

@@ -1,0 +1,73 @@
+"""Plant plausible mistakes in a COPY of the oracle (CPU only) and check that the
+pins notice each one.  The copy is compiled into a temp dir; oracle/ is untouched."""
+import ctypes
+import os
+import subprocess
+import numpy as np
+import pytest
+
+import oracle
+import test_oracle_conv as tc
+import test_oracle_pool as tp
+
+SRC = open(os.path.join(os.path.dirname(oracle.__file__), "oracle.c")).read()
+
+FWD_PINS = [lambda: tc.test_fwd_bruteforce_dense_weight_tensor(0, 2, 11, 3, 3, 2),
+            tc.test_fwd_grid_reduces_to_2d_correlation,
+            lambda: tc.test_fwd_named_image_operators("prewitt_x", (1, 0, 0), 0.0),
+            lambda: tc.test_fwd_named_image_operators("blur", (0, 0, 0), 1.0 / 9.0),
+            tc.test_fwd_theta_zero_is_bias_weighted_neighbour_sum]
+BWD_PINS = [tc.test_bwd_bruteforce_dense, tc.test_bwd_finite_differences_full_jacobian,
+            tc.test_bwd_adjoint_identities_cfg0, tc.test_bwd_grad_feat_at_matches_full]
+POOL_PINS = [tp.test_pool_fwd_bruteforce_with_ties, tp.test_pool_fwd_invariants,
+             tp.test_pool_fwd_k1_identity_and_constant_feature, tp.test_pool_bwd_bruteforce_and_mass,
+             tp.test_pool_bwd_is_adjoint_of_selection]
+
+# (name, text to replace, replacement, occurrence index or None for all, pins that must catch it)
+MUTATIONS = [
+    ("fwd_sign_dx", "(double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)]",
+     "(double)pos[IDX3(b, 0, l, 3, N)] - (double)pos[IDX3(b, 0, n, 3, N)]", 0, FWD_PINS),
+    ("fwd_drop_bias", " + (double)tb[o];\n                            acc[o] += w * f;",
+     ";\n                            acc[o] += w * f;", 0, FWD_PINS),
+    ("fwd_drop_z", "+ (double)tz[o] * dz + (double)tb[o];\n                            acc[o]",
+     "+ (double)tb[o];\n                            acc[o]", 0, FWD_PINS),
+    ("fwd_feat_of_centre", "const double f = (double)feat[IDX3(b, c, n, Din, N)];\n                        const float *tx = theta + IDX3(0, c, 0, Din, Dout);\n                        const float *ty = theta + IDX3(1, c, 0, Din, Dout);\n                        const float *tz = theta + IDX3(2, c, 0, Din, Dout);\n                        const float *tb = bias + (int64_t)c * Dout;\n                        for (int o = 0; o < Dout; ++o) {\n                            const double w",
+     "const double f = (double)feat[IDX3(b, c, l, Din, N)];\n                        const float *tx = theta + IDX3(0, c, 0, Din, Dout);\n                        const float *ty = theta + IDX3(1, c, 0, Din, Dout);\n                        const float *tz = theta + IDX3(2, c, 0, Din, Dout);\n                        const float *tb = bias + (int64_t)c * Dout;\n                        for (int o = 0; o < Dout; ++o) {\n                            const double w", 0, FWD_PINS),
+    ("nbr_layout_transposed", "nbr[IDX3(b, k, l, K, N)]", "nbr[((int64_t)b * N + l) * K + k]", None, FWD_PINS),
+    ("bwd_gfeat_to_centre", "grad_feat[IDX3(b, c, n, Din, N)] += s;", "grad_feat[IDX3(b, c, l, Din, N)] += s;", 0, BWD_PINS),
+    ("bwd_gtheta_xy_swapped", "gtx[o] += dx * fg;", "gtx[o] += dy * fg;", 0, BWD_PINS),
+    ("bwd_gbias_uses_weight", "gbb[o] += fg;", "gbb[o] += w * fg;", 0, BWD_PINS),
+    ("bwd_at_wrong_g_column", "s += w * (double)grad_out[IDX3(b, o, l, Dout, N)];",
+     "s += w * (double)grad_out[IDX3(b, o, n, Dout, N)];", 0, BWD_PINS),
+    ("pool_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 0, POOL_PINS),
+    ("pool_min_instead_of_max", "if (v > bv || (v == bv && n < best))", "if (v < bv || (v == bv && n < best))", 0, POOL_PINS),
+    ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
+]
+
+
+def _replace(text, old, new, which):
+    assert old in text, old
+    if which is None:
+        return text.replace(old, new)
+    parts = text.split(old)
+    assert which < len(parts) - 1
+    return old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
+
+
+@pytest.mark.parametrize("name,old,new,which,pins", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, which, pins):
+    src = tmp_path / "mut.c"
+    lib = tmp_path / "libmut.so"
+    src.write_text(_replace(SRC, old, new, which))
+    subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(lib), str(src)], check=True)
+    mut = ctypes.CDLL(str(lib))
+    mut.oracle_count_bad_neighbors.restype = ctypes.c_int64
+    oracle._load()
+    monkeypatch.setattr(oracle, "_lib", mut)
+    caught = 0
+    for pin in pins:
+        try:
+            pin()
+        except (AssertionError, RuntimeError):
+            caught += 1
+    assert caught >= 1, f"mutation {name} slipped through every pin"
