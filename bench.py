@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the flex-convolution hot path on one MI355X.
+
+One step = flexconv_fwd + flexconv_bwd + flexpool_fwd + flexpool_bwd over the
+7M-point hall workload (config 4: B=1, N=7,000,000, K=8, Din=Dout=64, fp32),
+inputs resident in HBM, neighbourhoods (and their transposed lists) static.
+Prints ONE JSON line; see the design doc for how each figure is defined.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--n N] [--layout bnc|bcn]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--n", type=int, default=None, help="override N (smaller trial runs)")
+    ap.add_argument("--layout", default="bnc", choices=["bnc", "bcn"])
+    ap.add_argument("--order", default="morton", choices=["morton", "generator", "shuffled"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default=None, help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no multi-GPU path exists); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_1803_07289_amd as fx
+    from workloads import CONFIGS, make_inputs
+
+    fx.lib()   # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    layout = fx.BNC if args.layout == "bnc" else fx.BCN
+    ops = set((args.only or "fwd,bwd,pool_fwd,pool_bwd").split(","))
+
+    cfg = CONFIGS[args.config]
+    t0 = time.time()
+    x = make_inputs(cfg, order=args.order, n_override=args.n)
+    cfg = x.cfg
+    B, N, K, Din, Dout = cfg.B, cfg.N, cfg.K, cfg.Din, cfg.Dout
+    log(f"[bench] inputs for {cfg.name} (N={N}) drawn in {time.time() - t0:.1f}s")
+
+    def dev(a, transpose=False):
+        t = torch.from_numpy(a).cuda()
+        if transpose and layout == fx.BNC:
+            t = t.transpose(1, 2).contiguous()
+        return t
+
+    feat, g = dev(x.feat, True), dev(x.grad_out, True)
+    pos, nbr, theta, bias = dev(x.pos), dev(x.nbr), dev(x.theta), dev(x.bias)
+    if Din != Dout:
+        gpool = torch.randn(feat.shape, device="cuda", generator=torch.Generator("cuda").manual_seed(cfg.seed))
+    else:
+        gpool = g
+    torch.cuda.synchronize()
+
+    # static preprocessing of the neighbourhoods: transposed lists, built once
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    in_edges = fx.flex_inedges_build(nbr)
+    torch.cuda.synchronize()
+    ev0.record()
+    in_edges = fx.flex_inedges_build(nbr)
+    ev1.record()
+    torch.cuda.synchronize()
+    inedges_ms = ev0.elapsed_time(ev1)
+
+    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd") if n in ops]
+    state = {}
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        if "fwd" in ops:
+            state["out"] = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=layout, out=state.get("out"))
+        mark(1)
+        if "bwd" in ops:
+            state["grads"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges)
+        mark(2)
+        if "pool_fwd" in ops or "pool_bwd" in ops:
+            state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
+        mark(3)
+        if "pool_bwd" in ops:
+            state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout)
+        mark(4)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(per_step_events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall * 1e3 / args.steps
+
+    op_ms = {}
+    for j, name in enumerate(("fwd", "bwd", "pool_fwd", "pool_bwd")):
+        ts = [ev[j].elapsed_time(ev[j + 1]) for ev in per_step_events]
+        op_ms[name] = {"mean": float(np.mean(ts)), "min": float(np.min(ts)), "median": float(np.median(ts))}
+    pts = B * N
+
+    # ---- roofline of the forward kernel (algorithmic, touched-once figures) ----
+    fwd_ms = op_ms["fwd"]["mean"]
+    fwd_bytes_pt = 4 * Din + 12 + 4 * K + 4 * Dout             # feat row + pos + idx + out row
+    fwd_mfma_flop_pt = 2 * 4 * Din * Dout                       # (4*Din x Dout) contraction
+    fwd_valu_flop_pt = 8 * K * Din                              # aggregate
+    mfma_tflops = fwd_mfma_flop_pt * pts / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0
+    hbm_gbs = fwd_bytes_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else 0.0
+    t_mfma = fwd_mfma_flop_pt * pts / (MFMA_F32_PEAK_TFLOPS * 1e12)
+    t_hbm = fwd_bytes_pt * pts / (HBM_PEAK_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        roofline = {"bound": "mfma", "achieved": mfma_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": mfma_tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+    else:
+        roofline = {"bound": "hbm", "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None}
+    roofline["kernel"] = "gather_contract_kernel (flexconv_fwd)"
+    roofline["kernel_ms"] = fwd_ms
+    roofline["hbm_GBps_algorithmic"] = hbm_gbs
+    roofline["mfma_TFLOPs_algorithmic"] = mfma_tflops
+
+    # ---- sampled parity at this size, in this launch configuration -------------
+    parity = None
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rng = np.random.default_rng(0)
+        starts = sorted({0, max(0, N - 300), *(int(s) for s in rng.integers(0, max(1, N - 300), size=2))})
+        if "fwd" in ops:
+            out = state["out"]
+            worst = 0.0
+            for s0 in starts:
+                s1 = min(N, s0 + 300)
+                ref = oracle.flexconv_fwd(x.feat, x.pos, x.nbr, x.theta, x.bias, l_range=(s0, s1))[:, :, s0:s1]
+                got = (out[:, s0:s1, :].transpose(1, 2) if layout == fx.BNC else out[:, :, s0:s1]).cpu().numpy()
+                den = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)))
+                worst = max(worst, float(np.max(np.abs(got - ref) / den)))
+            parity = {"fwd_sampled_max_rel_err": worst, "points": 300 * len(starts)}
+
+        # ---- CPU baseline: the oracle on a bounded slice of the same workload ----
+        def oracle_pass(l0, l1):
+            t = time.perf_counter()
+            oracle.flexconv_fwd(x.feat, x.pos, x.nbr, x.theta, x.bias, l_range=(l0, l1))
+            oracle.flexconv_bwd(x.feat, x.pos, x.nbr, x.theta, x.bias, x.grad_out, l_range=(l0, l1))
+            o, a = oracle.flexpool_fwd(x.feat, x.nbr, l_range=(l0, l1))
+            oracle.flexpool_bwd(x.grad_out if Din == Dout else x.feat, a, l_range=(l0, l1))
+            return time.perf_counter() - t
+
+        # full-size output arrays are allocated per call; time only a probe, then scale the slice
+        probe = min(N, 2000)
+        t_probe = oracle_pass(0, probe)
+        alloc_overhead = oracle_pass(0, 1)
+        per_pt = max((t_probe - alloc_overhead) / probe, 1e-9)
+        n_slice = int(min(N, max(probe, 12.0 / per_pt)))
+        t_slice = oracle_pass(0, n_slice) - alloc_overhead
+        cpu_baseline = {"value": n_slice * B / t_slice, "unit": "points/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "sample": f"centre points [0,{n_slice}) of the same workload, "
+                        f"all four ops, {t_slice:.1f}s", "os_cpu_count": os.cpu_count()}
+
+    direct_flop_pt = 8 * K * Din * Dout
+    result = {
+        "metric": "flex-conv fwd+bwd (+ flex-max-pool fwd+bwd) points/sec at N=7M,K=8",
+        "value": pts / (ms_per_step * 1e-3),
+        "unit": "points/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}", "B": B, "N": N, "K": K, "Din": Din,
+                   "Dout": Dout, "layout": args.layout, "point_order": x.order, "ops": names,
+                   "in_edges": "prebuilt once (static neighbourhoods)"},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "op_ms": op_ms,
+        "inedges_build_ms": inedges_ms,
+        "fwd_points_per_s": pts / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
+        "fwd_effective_GFLOPs_direct_form": direct_flop_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else None,
+        "fwd_bwd_points_per_s": pts / ((fwd_ms + op_ms["bwd"]["mean"]) * 1e-3) if fwd_ms > 0 else None,
+        "fwd_valu_flop_per_point": fwd_valu_flop_pt,
+        "parity": parity,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

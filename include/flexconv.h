@@ -1,0 +1,138 @@
+/*
+ * libflexconv — flex-convolution and flex-max-pooling for gfx950 (MI355X).
+ *
+ * C ABI.  Every data pointer is a DEVICE pointer owned by the caller; the
+ * library never allocates, frees or synchronises in these calls.  Work is
+ * enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ * and the call returns at once.  Outputs are OVERWRITTEN, never accumulated.
+ * Return value: FLEX_OK (0) or a flex_status; nothing throws or aborts.
+ * Errors that the host can see (null pointers, non-positive sizes, K > N,
+ * unknown layout, B*N >= 2^31, workspace too small) are returned before
+ * anything is launched.
+ *
+ * Tensors (fp32 / int32), following the paper's statement of the layer
+ * (Sec. 3.1 for the sum and the weight, Sec. 4.1 for the index tensor):
+ *   feat      features, [B,Din,N]  (FLEX_LAYOUT_BCN, the paper's channel-major
+ *             form) or [B,N,Din] (FLEX_LAYOUT_BNC, point-major: one point's
+ *             feature vector is one contiguous row — the library's native
+ *             layout, because a neighbour gather then reads whole rows)
+ *   pos       point locations, always [B,3,N]
+ *   nbr       neighbour indices, always int32 [B,K,N]; values are per-cloud
+ *             point indices in [0,N).  Out-of-range values are undefined
+ *             behaviour in the hot path; flex_validate_neighbors checks them.
+ *   theta     [3,Din,Dout], bias [Din,Dout]: one (theta, bias) per (c,c') pair
+ *   out, grad_out, grad_feat, pool out / argmax: same layout flag as feat.
+ * The position difference is (neighbour - centre).
+ *
+ * Workspace: flexconv_fwd / flexconv_bwd / flex_inedges_build take a caller
+ * buffer of at least flexconv_workspace_bytes(...) bytes, 256-byte aligned.
+ * Its contents are scratch; calls sharing one workspace must be stream-ordered.
+ */
+#ifndef FLEXCONV_H
+#define FLEXCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FLEX_OK = 0,
+    FLEX_ERR_NULL = 1,        /* a required pointer is NULL */
+    FLEX_ERR_SHAPE = 2,       /* non-positive size, K > N, B*N too large, bad layout/op */
+    FLEX_ERR_UNSUPPORTED = 3, /* reserved */
+    FLEX_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or too small */
+    FLEX_ERR_HIP = 5          /* a HIP launch reported an error */
+} flex_status;
+
+typedef enum { FLEX_LAYOUT_BCN = 0, FLEX_LAYOUT_BNC = 1 } flex_layout;
+
+typedef enum {
+    FLEX_OP_CONV_FWD = 0,
+    FLEX_OP_CONV_BWD = 1,       /* with caller-supplied in-edge lists */
+    FLEX_OP_CONV_BWD_BUILD = 2, /* in-edge lists built inside the call */
+    FLEX_OP_INEDGES = 3
+} flex_op;
+
+/*
+ * Flex-convolution forward: Eq.(4) with the weight of Eq.(6),
+ *   out[b,o,l] = sum_k sum_c ( <theta[:,c,o], pos[b,:,n]-pos[b,:,l]> + bias[c,o] ) * feat[b,c,n],
+ *   n = nbr[b,k,l].
+ * Computed in fp32 in the factored form (per-point 4*Din aggregate, then a
+ * (4*Din x Dout) contraction on the matrix cores).
+ */
+int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
+                 const float *theta, const float *bias, float *out,
+                 int B, int N, int K, int Din, int Dout, int layout,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Flex-convolution backward (gradients of the forward map above, Sec. 3.1
+ * asserts differentiability; formulas follow by differentiating the sum):
+ *   grad_feat [b,c,m] = sum_{(l,k): nbr[b,k,l]=m} sum_o w(b,l,k,c,o) * grad_out[b,o,l]
+ *   grad_theta[d,c,o] = sum_{b,l,k} (pos[b,d,n]-pos[b,d,l]) * feat[b,c,n] * grad_out[b,o,l]
+ *   grad_bias [c,o]   = sum_{b,l,k}                          feat[b,c,n] * grad_out[b,o,l]
+ * Any of grad_feat / grad_theta / grad_bias may be NULL (skipped; grad_theta
+ * and grad_bias are produced together, pass both or neither).
+ * grad_feat is evaluated as a gather over each point's IN-edges (the centres
+ * that list it as a neighbour), so it uses no floating-point atomics and is
+ * bit-reproducible.  in_off [B*N+1] / in_src [B*K*N] are those lists as built
+ * by flex_inedges_build for this nbr; pass both NULL to have them built in the
+ * workspace on every call (neighbourhoods are static, so building once and
+ * reusing is the intended use).
+ */
+int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
+                 const float *theta, const float *bias, const float *grad_out,
+                 float *grad_feat, float *grad_theta, float *grad_bias,
+                 const int32_t *in_off, const int32_t *in_src,
+                 int B, int N, int K, int Din, int Dout, int layout,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Transposed neighbour graph (Sec. 4.1: neighbourhoods are computed once and
+ * kept fixed, so this is part of that preprocessing).  For global point
+ * g = b*N+m, in_src[in_off[g] .. in_off[g+1]) lists the centres l (per-cloud
+ * indices, ascending, one entry per occurrence) with nbr[b,k,l] = m.
+ * in_off has B*N+1 entries, in_src has B*K*N entries.
+ */
+int flex_inedges_build(const int32_t *nbr, int B, int N, int K,
+                       int32_t *in_off, int32_t *in_src,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Flex-max-pooling forward (Sec. 4.1): out[b,c,l] = max_k feat[b,c,nbr[b,k,l]];
+ * argmax[b,c,l] = per-cloud index of the winning point (Table 1: the forward
+ * pass stores a same-sized table for the backward pass).  Ties go to the
+ * LOWEST POINT INDEX among the maxima; -0 == +0 is a tie; out carries the
+ * winner's bits.  NaN inputs are unsupported.
+ */
+int flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *argmax,
+                 int B, int N, int K, int C, int layout, void *stream);
+
+/*
+ * Flex-max-pooling backward: grad_feat[b,c,m] = sum of grad_out[b,c,l] over
+ * the centres l with argmax[b,c,l] = m, zero elsewhere.  Uses fp32 atomic adds
+ * (summation order, hence the last bit, may vary between runs when several
+ * centres share a winner).
+ */
+int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
+                 int B, int N, int C, int layout, void *stream);
+
+/* Bytes of workspace needed by op (a flex_op) at these sizes. 0 on bad sizes. */
+size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, int layout);
+
+/* Debug aid: *bad_count_dev (device int32) = number of nbr entries outside [0,N). */
+int flex_validate_neighbors(const int32_t *nbr, int B, int N, int K,
+                            int32_t *bad_count_dev, void *stream);
+
+/* 1 if (Din,Dout) runs on the tiled matrix-core kernels, 0 if on the generic ones. */
+int flexconv_has_fast_path(int Din, int Dout);
+
+const char *flex_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXCONV_H */

@@ -139,6 +139,7 @@ int oracle_flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
     if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return 2;
     if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
     const int64_t n_theta = (int64_t)3 * Din * Dout, n_bias = (int64_t)Din * Dout;
+    const int want_params = (grad_theta != NULL) || (grad_bias != NULL);
     if (grad_feat) memset(grad_feat, 0, sizeof(double) * (size_t)B * Din * N);
     if (grad_theta) memset(grad_theta, 0, sizeof(double) * (size_t)n_theta);
     if (grad_bias) memset(grad_bias, 0, sizeof(double) * (size_t)n_bias);
@@ -168,15 +169,19 @@ int oracle_flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
                         double *gtz = gt + IDX3(2, c, 0, Din, Dout);
                         double *gbb = gb + (int64_t)c * Dout;
                         double s = 0.0;
-                        for (int o = 0; o < Dout; ++o) {
-                            const double w = (double)tx[o] * dx + (double)ty[o] * dy + (double)tz[o] * dz + (double)tb[o];
-                            s += w * g[o];
-                            const double fg = f * g[o];
-                            gtx[o] += dx * fg;
-                            gty[o] += dy * fg;
-                            gtz[o] += dz * fg;
-                            gbb[o] += fg;
-                        }
+                        if (grad_feat)
+                            for (int o = 0; o < Dout; ++o) {
+                                const double w = (double)tx[o] * dx + (double)ty[o] * dy + (double)tz[o] * dz + (double)tb[o];
+                                s += w * g[o];
+                            }
+                        if (want_params)
+                            for (int o = 0; o < Dout; ++o) {
+                                const double fg = f * g[o];
+                                gtx[o] += dx * fg;
+                                gty[o] += dy * fg;
+                                gtz[o] += dz * fg;
+                                gbb[o] += fg;
+                            }
                         if (grad_feat) {
 #pragma omp atomic
                             grad_feat[IDX3(b, c, n, Din, N)] += s;

@@ -1,0 +1,223 @@
+"""Python binding of libflexconv (flex-convolution / flex-max-pooling on gfx950).
+
+Argument marshalling only: every step of the path runs in the HIP library.
+Tensors are torch CUDA tensors (device memory and streams come from PyTorch);
+work is enqueued on torch's current stream.  The functions carry the names of
+the C entry points declared in include/flexconv.h.
+
+There is no CPU fallback: if the shared library has not been built the first
+call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+BCN = 0   # [B,C,N]  channel-major, the paper's form
+BNC = 1   # [B,N,C]  point-major, the library's native form
+OP_CONV_FWD, OP_CONV_BWD, OP_CONV_BWD_BUILD, OP_INEDGES = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflexconv.so")
+_lib = None
+_workspaces = {}
+
+_vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+_SIGS = {
+    "flexconv_fwd": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp]),
+    "flexconv_bwd": (_i, [_vp] * 11 + [_i] * 6 + [_vp, _sz, _vp]),
+    "flex_inedges_build": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
+    "flexpool_bwd": (_i, [_vp] * 3 + [_i] * 4 + [_vp]),
+    "flexconv_workspace_bytes": (_sz, [_i] * 7),
+    "flex_validate_neighbors": (_i, [_vp, _i, _i, _i, _vp, _vp]),
+    "flexconv_has_fast_path": (_i, [_i, _i]),
+    "flex_status_string": (ctypes.c_char_p, [_i]),
+}
+
+
+def lib():
+    """The loaded shared library (raises if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_1803_07289_amd.build` (no CPU fallback exists)")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+class FlexError(RuntimeError):
+    pass
+
+
+def _check(status, what):
+    if status != 0:
+        raise FlexError(f"{what}: {lib().flex_status_string(status).decode()} (status {status})")
+
+
+def _layout(layout):
+    if layout in (BCN, "bcn", "BCN"):
+        return BCN
+    if layout in (BNC, "bnc", "BNC"):
+        return BNC
+    raise ValueError(f"unknown layout {layout!r}")
+
+
+def _dev(t, dtype, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dims(feat, nbr, layout):
+    """(B, N, K, C) from a feature tensor and the index tensor."""
+    if feat.dim() != 3 or nbr.dim() != 3:
+        raise ValueError("feat and nbr must be 3-D")
+    B, K, N = nbr.shape
+    C = feat.shape[1] if layout == BCN else feat.shape[2]
+    want = (B, C, N) if layout == BCN else (B, N, C)
+    if tuple(feat.shape) != want:
+        raise ValueError(f"feat shape {tuple(feat.shape)} does not match nbr {tuple(nbr.shape)} in this layout")
+    return B, N, K, C
+
+
+def workspace_bytes(op, B, N, K, Din, Dout, layout=BCN):
+    return int(lib().flexconv_workspace_bytes(op, B, N, K, Din, Dout, _layout(layout)))
+
+
+def _workspace(device, nbytes):
+    """A cached, grow-only scratch tensor per device (256-byte aligned by the allocator)."""
+    key = (device.type, device.index)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        _workspaces[key] = None
+        ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def flexconv_fwd(feat, pos, nbr, theta, bias, layout=BCN, out=None, workspace=None):
+    """Flex-convolution forward (Eq. 4 with the weight of Eq. 6).  Returns out."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(pos, torch.float32, "pos"); _dev(nbr, torch.int32, "nbr")
+    _dev(theta, torch.float32, "theta"); _dev(bias, torch.float32, "bias")
+    B, N, K, Din = _dims(feat, nbr, layout)
+    if theta.dim() != 3 or theta.shape[0] != 3 or theta.shape[1] != Din:
+        raise ValueError("theta must be [3,Din,Dout]")
+    Dout = theta.shape[2]
+    if tuple(bias.shape) != (Din, Dout) or tuple(pos.shape) != (B, 3, N):
+        raise ValueError("bias must be [Din,Dout] and pos [B,3,N]")
+    shape = (B, Dout, N) if layout == BCN else (B, N, Dout)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=feat.device)
+    elif tuple(_dev(out, torch.float32, "out").shape) != shape:
+        raise ValueError("out has the wrong shape")
+    need = workspace_bytes(OP_CONV_FWD, B, N, K, Din, Dout, layout)
+    ws = workspace if workspace is not None else _workspace(feat.device, need)
+    _check(lib().flexconv_fwd(_ptr(feat), _ptr(pos), _ptr(nbr), _ptr(theta), _ptr(bias), _ptr(out),
+                              B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_fwd")
+    return out
+
+
+def flex_inedges_build(nbr, workspace=None):
+    """Transposed neighbour graph of nbr [B,K,N]: (in_off int32 [B*N+1], in_src int32 [B*K*N])."""
+    _dev(nbr, torch.int32, "nbr")
+    B, K, N = nbr.shape
+    in_off = torch.empty(B * N + 1, dtype=torch.int32, device=nbr.device)
+    in_src = torch.empty(B * K * N, dtype=torch.int32, device=nbr.device)
+    need = workspace_bytes(OP_INEDGES, B, N, K, 1, 1, BCN)
+    ws = workspace if workspace is not None else _workspace(nbr.device, need)
+    _check(lib().flex_inedges_build(_ptr(nbr), B, N, K, _ptr(in_off), _ptr(in_src), _ptr(ws), ws.numel(),
+                                    _stream()), "flex_inedges_build")
+    return in_off, in_src
+
+
+def flexconv_bwd(feat, pos, nbr, theta, bias, grad_out, layout=BCN, in_edges=None,
+                 need_feat=True, need_params=True, workspace=None):
+    """Flex-convolution backward.  Returns (grad_feat, grad_theta, grad_bias); entries not asked
+    for are None.  in_edges = (in_off, in_src) from flex_inedges_build, or None to build per call."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(pos, torch.float32, "pos"); _dev(nbr, torch.int32, "nbr")
+    _dev(theta, torch.float32, "theta"); _dev(bias, torch.float32, "bias")
+    _dev(grad_out, torch.float32, "grad_out")
+    B, N, K, Din = _dims(feat, nbr, layout)
+    if theta.dim() != 3 or theta.shape[0] != 3 or theta.shape[1] != Din:
+        raise ValueError("theta must be [3,Din,Dout]")
+    Dout = theta.shape[2]
+    if tuple(bias.shape) != (Din, Dout) or tuple(pos.shape) != (B, 3, N):
+        raise ValueError("bias must be [Din,Dout] and pos [B,3,N]")
+    gshape = (B, Dout, N) if layout == BCN else (B, N, Dout)
+    if tuple(grad_out.shape) != gshape:
+        raise ValueError("grad_out has the wrong shape")
+    gf = torch.empty_like(feat) if need_feat else None
+    gt = torch.empty_like(theta) if need_params else None
+    gb = torch.empty_like(bias) if need_params else None
+    off = src = None
+    if in_edges is not None:
+        off, src = in_edges
+        _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src")
+        if off.numel() != B * N + 1 or src.numel() != B * K * N:
+            raise ValueError("in_edges do not match nbr")
+    op = OP_CONV_BWD if in_edges is not None else OP_CONV_BWD_BUILD
+    need = workspace_bytes(op, B, N, K, Din, Dout, layout)
+    ws = workspace if workspace is not None else _workspace(feat.device, need)
+    _check(lib().flexconv_bwd(_ptr(feat), _ptr(pos), _ptr(nbr), _ptr(theta), _ptr(bias), _ptr(grad_out),
+                              _ptr(gf), _ptr(gt), _ptr(gb), _ptr(off), _ptr(src),
+                              B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_bwd")
+    return gf, gt, gb
+
+
+def flexpool_fwd(feat, nbr, layout=BCN):
+    """Flex-max-pooling forward.  Returns (out, argmax int32), both shaped like feat."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(nbr, torch.int32, "nbr")
+    B, N, K, C = _dims(feat, nbr, layout)
+    out = torch.empty_like(feat)
+    arg = torch.empty(feat.shape, dtype=torch.int32, device=feat.device)
+    _check(lib().flexpool_fwd(_ptr(feat), _ptr(nbr), _ptr(out), _ptr(arg), B, N, K, C, layout, _stream()),
+           "flexpool_fwd")
+    return out, arg
+
+
+def flexpool_bwd(grad_out, argmax, layout=BCN):
+    """Flex-max-pooling backward (routing by the recorded winners).  Returns grad_feat."""
+    layout = _layout(layout)
+    _dev(grad_out, torch.float32, "grad_out"); _dev(argmax, torch.int32, "argmax")
+    if grad_out.dim() != 3 or grad_out.shape != argmax.shape:
+        raise ValueError("grad_out and argmax must be 3-D and equal in shape")
+    B = grad_out.shape[0]
+    C, N = (grad_out.shape[1], grad_out.shape[2]) if layout == BCN else (grad_out.shape[2], grad_out.shape[1])
+    gf = torch.empty_like(grad_out)
+    _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), B, N, C, layout, _stream()),
+           "flexpool_bwd")
+    return gf
+
+
+def flex_validate_neighbors(nbr):
+    """Number of entries of nbr [B,K,N] outside [0,N) (synchronises)."""
+    _dev(nbr, torch.int32, "nbr")
+    B, K, N = nbr.shape
+    bad = torch.zeros(1, dtype=torch.int32, device=nbr.device)
+    _check(lib().flex_validate_neighbors(_ptr(nbr), B, N, K, _ptr(bad), _stream()), "flex_validate_neighbors")
+    return int(bad.item())
+
+
+def has_fast_path(Din, Dout):
+    return bool(lib().flexconv_has_fast_path(int(Din), int(Dout)))

@@ -1,0 +1,308 @@
+// C-ABI entry points of libflexconv: validation, workspace carving, dispatch.
+#include "flex_common.hpp"
+#include "../../include/flexconv.h"
+
+namespace flex {
+
+// ---- per-shape launchers generated from flex_shapes.def ------------------------
+#define FLEX_SHAPE(DI, DO, W, T, OCC)                                                              \
+    hipError_t launch_gc_##DI##_##DO(const float *, const float *, const int32_t *, const int32_t *, \
+                                     const int32_t *, const float *, float *, int, int, int, int,    \
+                                     int, hipStream_t);                                              \
+    hipError_t launch_gt_##DI##_##DO(const float *, const float *, const int32_t *, const float *,   \
+                                     float *, int, int, int, int *, hipStream_t);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+
+hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,
+                                  int Dout, float *grad_theta, float *grad_bias, hipStream_t s);
+
+bool gather_contract_supported(int DI, int DO)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+    if (DI == DI_ && DO == DO_) return true;
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return false;
+}
+
+hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
+                                  const int32_t *off, const int32_t *src, const float *thetaP,
+                                  float *out, int B, int N, int K, int DI, int DO, int csr,
+                                  int out_bcn, hipStream_t s)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+    if (DI == DI_ && DO == DO_)         \
+        return launch_gc_##DI_##_##DO_(rows, pos, nbr, off, src, thetaP, out, B, N, K, csr, out_bcn, s);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return hipErrorNotSupported;
+}
+
+static int shape_tile_points(int DI, int DO)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+    if (DI == DI_ && DO == DO_) return T;
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return 0;
+}
+
+static int shape_wg_per_cu(int DI, int DO)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+    if (DI == DI_ && DO == DO_) return ((OCC * 4) / W > 0) ? (OCC * 4) / W : 1;
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return 0;
+}
+
+static inline int pad4(int x) { return (x + 3) / 4 * 4; }
+static inline int pad16(int x) { return (x + 15) / 16 * 16; }
+
+size_t grad_theta_partial_bytes(int64_t B, int64_t N, int Din, int Dout)
+{
+    const int T = shape_tile_points(Din, Dout);
+    if (T == 0) return 0;
+    const int64_t tiles = B * ((N + T - 1) / T);
+    const int grid = persistent_grid(tiles, shape_wg_per_cu(Din, Dout));
+    return align256(sizeof(float) * (size_t)grid * 4 * pad4(Din) * pad16(Dout));
+}
+
+hipError_t launch_grad_theta(const float *rows, const float *pos, const int32_t *nbr,
+                             const float *g_rows, float *partials, float *grad_theta,
+                             float *grad_bias, int B, int N, int K, int Din, int Dout, hipStream_t s)
+{
+    int n_wg = 0;
+    hipError_t e = hipErrorNotSupported;
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC)                                                    \
+    if (Din == DI_ && Dout == DO_)                                                         \
+        e = launch_gt_##DI_##_##DO_(rows, pos, nbr, g_rows, partials, B, N, K, &n_wg, s);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    if (e != hipSuccess) return e;
+    return launch_reduce_partials(partials, n_wg, pad4(Din), pad16(Dout), Din, Dout, grad_theta,
+                                  grad_bias, s);
+}
+
+// ---- workspace plans -----------------------------------------------------------
+struct FwdPlan {
+    bool tiled;
+    size_t thetaP, featT, total;   // byte offsets / total
+};
+struct BwdPlan {
+    bool tiled;
+    size_t thetaP, featT, gT, partials, in_off, in_src, inedge_ws, total;
+};
+
+static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout)
+{
+    FwdPlan p{};
+    p.tiled = gather_contract_supported(Din, Dout);
+    size_t at = 0;
+    if (p.tiled) {
+        p.thetaP = at; at += align256(sizeof(float) * (size_t)4 * pad4(Din) * pad16(Dout));
+        if (layout == FLEX_LAYOUT_BCN) { p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din); }
+    }
+    p.total = at > 0 ? at : 256;
+    return p;
+}
+
+static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layout, bool build)
+{
+    BwdPlan p{};
+    p.tiled = gather_contract_supported(Din, Dout) && gather_contract_supported(Dout, Din);
+    size_t at = 0;
+    if (p.tiled) {
+        p.thetaP = at; at += align256(sizeof(float) * (size_t)4 * pad4(Dout) * pad16(Din));
+        if (layout == FLEX_LAYOUT_BCN) {
+            p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din);
+            p.gT = at;    at += align256(sizeof(float) * (size_t)(B * N) * Dout);
+        }
+        p.partials = at; at += grad_theta_partial_bytes(B, N, Din, Dout);
+        if (build) {
+            p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
+            p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
+            p.inedge_ws = at; at += inedges_ws_bytes(B * N);
+        }
+    }
+    p.total = at > 0 ? at : 256;
+    return p;
+}
+
+static bool sizes_ok(int64_t B, int64_t N, int64_t K, int64_t Din, int64_t Dout)
+{
+    if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return false;
+    if (K > N) return false;
+    if (B * N >= 0x7fffffffLL) return false;          // global point ids are int32
+    if (B * N * K >= 0x7fffffffLL) return false;      // in-edge offsets are int32
+    if (Din > 16384 || Dout > 16384) return false;
+    return true;
+}
+
+static bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    return ws != nullptr && (((uintptr_t)ws) & 255) == 0 && have >= need;
+}
+
+#define FLEX_HIP(expr)                                  \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return FLEX_ERR_HIP;      \
+    } while (0)
+
+}  // namespace flex
+
+using namespace flex;
+
+extern "C" {
+
+const char *flex_status_string(int status)
+{
+    switch (status) {
+    case FLEX_OK: return "ok";
+    case FLEX_ERR_NULL: return "null pointer argument";
+    case FLEX_ERR_SHAPE: return "bad size, layout or op";
+    case FLEX_ERR_UNSUPPORTED: return "unsupported";
+    case FLEX_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case FLEX_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+    }
+}
+
+int flexconv_has_fast_path(int Din, int Dout) { return gather_contract_supported(Din, Dout) ? 1 : 0; }
+
+size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, int layout)
+{
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return 0;
+    switch (op) {
+    case FLEX_OP_CONV_FWD: return sizes_ok(B, N, K, Din, Dout) ? plan_fwd(B, N, Din, Dout, layout).total : 0;
+    case FLEX_OP_CONV_BWD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, false).total : 0;
+    case FLEX_OP_CONV_BWD_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, true).total : 0;
+    case FLEX_OP_INEDGES: return sizes_ok(B, N, K, 1, 1) ? inedges_ws_bytes((int64_t)B * N) : 0;
+    default: return 0;
+    }
+}
+
+int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const float *theta,
+                 const float *bias, float *out, int B, int N, int K, int Din, int Dout, int layout,
+                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!feat || !pos || !nbr || !theta || !bias || !out) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, Din, Dout)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    const FwdPlan p = plan_fwd(B, N, Din, Dout, layout);
+    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int bcn = (layout == FLEX_LAYOUT_BCN);
+    if (!p.tiled) {
+        FLEX_HIP(launch_generic_fwd(feat, pos, nbr, theta, bias, out, B, N, K, Din, Dout, !bcn, s));
+        return FLEX_OK;
+    }
+    float *thetaP = (float *)(ws + p.thetaP);
+    FLEX_HIP(launch_pack_theta(theta, bias, thetaP, Din, Dout, pad4(Din), pad16(Dout), 0, s));
+    const float *rows = feat;
+    if (bcn) {
+        float *featT = (float *)(ws + p.featT);
+        FLEX_HIP(launch_bcn_to_bnc(feat, featT, B, Din, N, s));
+        rows = featT;
+    }
+    FLEX_HIP(launch_gather_contract(rows, pos, nbr, nullptr, nullptr, thetaP, out, B, N, K, Din, Dout,
+                                    0, bcn, s));
+    return FLEX_OK;
+}
+
+int flex_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t *in_off, int32_t *in_src,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!nbr || !in_off || !in_src) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, 1, 1)) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, inedges_ws_bytes((int64_t)B * N))) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_inedges_build(nbr, B, N, K, in_off, in_src, workspace, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const float *theta,
+                 const float *bias, const float *grad_out, float *grad_feat, float *grad_theta,
+                 float *grad_bias, const int32_t *in_off, const int32_t *in_src, int B, int N, int K,
+                 int Din, int Dout, int layout, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!feat || !pos || !nbr || !theta || !bias || !grad_out) return FLEX_ERR_NULL;
+    if ((grad_theta == nullptr) != (grad_bias == nullptr)) return FLEX_ERR_NULL;
+    if ((in_off == nullptr) != (in_src == nullptr)) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, Din, Dout)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    const bool build = (in_off == nullptr) && (grad_feat != nullptr);
+    const BwdPlan p = plan_bwd(B, N, K, Din, Dout, layout, build);
+    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int bcn = (layout == FLEX_LAYOUT_BCN);
+    if (!p.tiled) {
+        FLEX_HIP(launch_generic_bwd(feat, pos, nbr, theta, bias, grad_out, grad_feat, grad_theta,
+                                    grad_bias, B, N, K, Din, Dout, !bcn, s));
+        return FLEX_OK;
+    }
+    const float *rows = feat, *g_rows = grad_out;
+    if (bcn) {
+        float *gT = (float *)(ws + p.gT);
+        FLEX_HIP(launch_bcn_to_bnc(grad_out, gT, B, Dout, N, s));
+        g_rows = gT;
+        if (grad_theta) {
+            float *featT = (float *)(ws + p.featT);
+            FLEX_HIP(launch_bcn_to_bnc(feat, featT, B, Din, N, s));
+            rows = featT;
+        }
+    }
+    if (grad_theta) {
+        FLEX_HIP(launch_grad_theta(rows, pos, nbr, g_rows, (float *)(ws + p.partials), grad_theta,
+                                   grad_bias, B, N, K, Din, Dout, s));
+    }
+    if (grad_feat) {
+        if (build) {
+            int32_t *off = (int32_t *)(ws + p.in_off), *src = (int32_t *)(ws + p.in_src);
+            FLEX_HIP(launch_inedges_build(nbr, B, N, K, off, src, ws + p.inedge_ws, s));
+            in_off = off;
+            in_src = src;
+        }
+        float *thetaP = (float *)(ws + p.thetaP);
+        FLEX_HIP(launch_pack_theta(theta, bias, thetaP, Din, Dout, pad4(Dout), pad16(Din), 1, s));
+        FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, thetaP, grad_feat, B, N, K,
+                                        Dout, Din, 1, bcn, s));
+    }
+    return FLEX_OK;
+}
+
+int flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *argmax, int B, int N,
+                 int K, int C, int layout, void *stream)
+{
+    if (!feat || !nbr || !out || !argmax) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, C, 1)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_pool_fwd(feat, nbr, out, argmax, B, N, K, C, layout == FLEX_LAYOUT_BNC,
+                             (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B, int N, int C,
+                 int layout, void *stream)
+{
+    if (!grad_out || !argmax || !grad_feat) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, 1, C, 1)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_pool_bwd(grad_out, argmax, grad_feat, B, N, C, layout == FLEX_LAYOUT_BNC,
+                             (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flex_validate_neighbors(const int32_t *nbr, int B, int N, int K, int32_t *bad_count_dev,
+                            void *stream)
+{
+    if (!nbr || !bad_count_dev) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, 1, 1)) return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_count_bad(nbr, (int64_t)B * K * N, N, bad_count_dev, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+}  // extern "C"

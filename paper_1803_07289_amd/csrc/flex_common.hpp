@@ -1,0 +1,78 @@
+// Shared host/device helpers for libflexconv (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace flex {
+
+constexpr int cdiv_c(int a, int b) { return (a + b - 1) / b; }
+constexpr int rup_c(int a, int b) { return cdiv_c(a, b) * b; }
+constexpr int npow2_c(int x) { int p = 1; while (p < x) p <<= 1; return p; }
+
+static inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Number of compute units of the current device (cached per process).
+int device_cu_count();
+
+// Persistent-grid size: a multiple of 8 (one share per XCD), at most
+// `wg_per_cu` workgroups per CU, at most one workgroup per tile.
+int persistent_grid(int64_t total_tiles, int wg_per_cu);
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// ---- launchers implemented in the .hip translation units -------------------
+
+// thetaP[(j*RP + r)*CP + c], j in 0..3 (x,y,z,bias), zero padded.
+//   transpose == 0: r = input channel, c = output channel  (forward / grad_theta)
+//   transpose == 1: r = output channel, c = input channel  (grad_feat)
+hipError_t launch_pack_theta(const float *theta, const float *bias, float *thetaP,
+                             int Din, int Dout, int RP, int CP, int transpose, hipStream_t s);
+
+// [B,C,N] -> [B,N,C] and back.
+hipError_t launch_bcn_to_bnc(const float *src, float *dst, int B, int C, int N, hipStream_t s);
+hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, hipStream_t s);
+
+// Tiled matrix-core path.  `rows` is point-major [B*N, DI].  Returns
+// hipErrorNotSupported when (DI,DO) has no instantiation.
+//   csr == 0: neighbours from nbr [B,K,N], dp = pos[nbr]-pos[centre]
+//   csr == 1: in-edge lists (off,src), dp = pos[centre]-pos[src]
+hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
+                                  const int32_t *off, const int32_t *src, const float *thetaP,
+                                  float *out, int B, int N, int K, int DI, int DO,
+                                  int csr, int out_bcn, hipStream_t s);
+bool gather_contract_supported(int DI, int DO);
+
+// grad_theta / grad_bias: per-workgroup partial sums into `partials`
+// ([n_wg, KD, DOP] floats), then a reduction into the two outputs.
+hipError_t launch_grad_theta(const float *rows, const float *pos, const int32_t *nbr,
+                             const float *g_rows, float *partials, float *grad_theta,
+                             float *grad_bias, int B, int N, int K, int Din, int Dout,
+                             hipStream_t s);
+size_t grad_theta_partial_bytes(int64_t B, int64_t N, int Din, int Dout);
+
+// Generic (any Din/Dout) direct-form kernels; strides select the layout.
+hipError_t launch_generic_fwd(const float *feat, const float *pos, const int32_t *nbr,
+                              const float *theta, const float *bias, float *out,
+                              int B, int N, int K, int Din, int Dout, int bnc, hipStream_t s);
+hipError_t launch_generic_bwd(const float *feat, const float *pos, const int32_t *nbr,
+                              const float *theta, const float *bias, const float *grad_out,
+                              float *grad_feat, float *grad_theta, float *grad_bias,
+                              int B, int N, int K, int Din, int Dout, int bnc, hipStream_t s);
+
+// In-edge lists.
+hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t *in_off,
+                                int32_t *in_src, void *ws, hipStream_t s);
+size_t inedges_ws_bytes(int64_t BN);
+
+// Pooling.
+hipError_t launch_pool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *argmax,
+                           int B, int N, int K, int C, int bnc, hipStream_t s);
+hipError_t launch_pool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
+                           int B, int N, int C, int bnc, hipStream_t s);
+
+hipError_t launch_count_bad(const int32_t *nbr, int64_t count, int N, int32_t *bad, hipStream_t s);
+hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
+
+}  // namespace flex

@@ -1,0 +1,182 @@
+// Transposed neighbour graph: for every point, the list of centres that name
+// it as a neighbour (CSR: in_off / in_src).  Counting sort by target point:
+// count -> exclusive scan -> fill -> sort each list ascending so that the
+// result does not depend on the order in which the fill's atomics landed.
+#include "flex_common.hpp"
+
+namespace flex {
+
+static constexpr int SCAN_ITEMS = 8;                    // per thread
+static constexpr int SCAN_CHUNK = 256 * SCAN_ITEMS;     // per block
+static constexpr int SORT_LOCAL = 32;                   // lists up to here sort in registers
+static constexpr int SORT_MAX = 1024;                   // longer lists keep fill order
+
+__global__ __launch_bounds__(256) void inedge_count_kernel(const int32_t *__restrict__ nbr,
+                                                           int32_t *__restrict__ cnt, int64_t E,
+                                                           int N, int64_t KN)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < E;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = i / KN;
+        atomicAdd(&cnt[b * N + nbr[i]], 1);
+    }
+}
+
+__device__ __forceinline__ int block_exclusive_scan(int v, int *s_wave, int &block_total)
+{
+    // inclusive scan inside the wave, then across the 4 waves
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    if (lane == 63) s_wave[w] = x;
+    __syncthreads();
+    int base = 0;
+    for (int i = 0; i < w; ++i) base += s_wave[i];
+    block_total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+    __syncthreads();
+    return base + x - v;
+}
+
+__global__ __launch_bounds__(256) void scan_block_sums_kernel(const int32_t *__restrict__ cnt,
+                                                              int32_t *__restrict__ bsum, int64_t n)
+{
+    __shared__ int s_wave[4];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int v = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i)
+        if (base + i < n) v += cnt[base + i];
+    int total;
+    block_exclusive_scan(v, s_wave, total);
+    if (threadIdx.x == 0) bsum[blockIdx.x] = total;
+}
+
+// single block: exclusive scan of bsum[0..nblk) in place; bsum[nblk] = grand total
+__global__ __launch_bounds__(256) void scan_of_sums_kernel(int32_t *__restrict__ bsum, int nblk)
+{
+    __shared__ int s_wave[4];
+    int carry = 0;
+    for (int c0 = 0; c0 < nblk; c0 += 256) {
+        const int i = c0 + threadIdx.x;
+        const int v = (i < nblk) ? bsum[i] : 0;
+        int total;
+        const int ex = block_exclusive_scan(v, s_wave, total);
+        if (i < nblk) bsum[i] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) bsum[nblk] = carry;
+}
+
+__global__ __launch_bounds__(256) void scan_apply_kernel(const int32_t *__restrict__ cnt,
+                                                         const int32_t *__restrict__ bsum,
+                                                         int32_t *__restrict__ off, int64_t n,
+                                                         int nblk)
+{
+    __shared__ int s_wave[4];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int v[SCAN_ITEMS], sum = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        v[i] = (base + i < n) ? cnt[base + i] : 0;
+        sum += v[i];
+    }
+    int total;
+    int run = bsum[blockIdx.x] + block_exclusive_scan(sum, s_wave, total);
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        if (base + i < n) off[base + i] = run;
+        run += v[i];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) off[n] = bsum[nblk];
+}
+
+__global__ __launch_bounds__(256) void inedge_fill_kernel(const int32_t *__restrict__ nbr,
+                                                          const int32_t *__restrict__ off,
+                                                          int32_t *__restrict__ cnt,
+                                                          int32_t *__restrict__ src, int64_t E,
+                                                          int N, int64_t KN)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < E;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = i / KN;
+        const int l = (int)(i % N);
+        const int64_t g = b * N + nbr[i];
+        const int slot = atomicSub(&cnt[g], 1) - 1;     // counts run down to zero
+        src[off[g] + slot] = l;
+    }
+}
+
+__global__ __launch_bounds__(256) void inedge_sort_kernel(const int32_t *__restrict__ off,
+                                                          int32_t *__restrict__ src, int64_t BN)
+{
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < BN;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const int beg = off[g], d = off[g + 1] - beg;
+        if (d < 2 || d > SORT_MAX) continue;
+        int32_t *p = src + beg;
+        if (d <= SORT_LOCAL) {
+            int v[SORT_LOCAL];
+#pragma unroll
+            for (int i = 0; i < SORT_LOCAL; ++i) v[i] = (i < d) ? p[i] : 0x7fffffff;
+            // odd-even transposition network: data-independent, stays in registers
+#pragma unroll 1
+            for (int pass = 0; pass < d; ++pass) {
+#pragma unroll
+                for (int i = 0; i + 1 < SORT_LOCAL; i += 2) {
+                    const int a = v[i], c = v[i + 1];
+                    v[i] = min(a, c); v[i + 1] = max(a, c);
+                }
+#pragma unroll
+                for (int i = 1; i + 1 < SORT_LOCAL; i += 2) {
+                    const int a = v[i], c = v[i + 1];
+                    v[i] = min(a, c); v[i + 1] = max(a, c);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < SORT_LOCAL; ++i)
+                if (i < d) p[i] = v[i];
+        } else {
+            for (int i = 1; i < d; ++i) {                 // rare: insertion sort in place
+                const int x = p[i];
+                int j = i - 1;
+                while (j >= 0 && p[j] > x) { p[j + 1] = p[j]; --j; }
+                p[j + 1] = x;
+            }
+        }
+    }
+}
+
+size_t inedges_ws_bytes(int64_t BN)
+{
+    const int64_t nblk = cdiv64(BN, SCAN_CHUNK);
+    return align256(sizeof(int32_t) * (size_t)BN) + align256(sizeof(int32_t) * (size_t)(nblk + 1));
+}
+
+hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t *in_off,
+                                int32_t *in_src, void *ws, hipStream_t s)
+{
+    const int64_t BN = (int64_t)B * N, KN = (int64_t)K * N, E = BN * K;
+    const int64_t nblk64 = cdiv64(BN, SCAN_CHUNK);
+    const int nblk = (int)nblk64;
+    int32_t *cnt = (int32_t *)ws;
+    int32_t *bsum = (int32_t *)((char *)ws + align256(sizeof(int32_t) * (size_t)BN));
+    hipError_t e = launch_fill_zero(cnt, sizeof(int32_t) * (size_t)BN, s);
+    if (e != hipSuccess) return e;
+    int64_t eb = (E + 255) / 256;
+    if (eb > (1 << 18)) eb = 1 << 18;
+    hipLaunchKernelGGL(inedge_count_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, cnt, E, N, KN);
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(nblk), dim3(256), 0, s, cnt, bsum, BN);
+    hipLaunchKernelGGL(scan_of_sums_kernel, dim3(1), dim3(256), 0, s, bsum, nblk);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(nblk), dim3(256), 0, s, cnt, bsum, in_off, BN, nblk);
+    hipLaunchKernelGGL(inedge_fill_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, in_off, cnt, in_src, E, N, KN);
+    int64_t sb = (BN + 255) / 256;
+    if (sb > (1 << 18)) sb = 1 << 18;
+    hipLaunchKernelGGL(inedge_sort_kernel, dim3((unsigned)sb), dim3(256), 0, s, in_off, in_src, BN);
+    return hipGetLastError();
+}
+
+}  // namespace flex

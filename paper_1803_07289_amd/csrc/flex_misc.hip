@@ -1,0 +1,332 @@
+// Small support kernels: parameter packing, layout transposes, the partial-sum
+// reduction of grad_theta, range check, zero fill, and the generic (any
+// Din/Dout) direct-form flex-conv kernels used when no tiled kernel fits.
+#include "flex_common.hpp"
+
+namespace flex {
+
+int device_cu_count()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cached = n;
+        else
+            cached = 256;   // MI355X; also the answer on a host without a GPU
+    }
+    return cached;
+}
+
+int persistent_grid(int64_t total_tiles, int wg_per_cu)
+{
+    int64_t g = (int64_t)device_cu_count() * wg_per_cu;
+    if (total_tiles < g) g = total_tiles;
+    if (g < 8) g = 8;
+    return (int)((g + 7) / 8 * 8);
+}
+
+// ---- theta packing ----------------------------------------------------------
+__global__ void pack_theta_kernel(const float *__restrict__ theta, const float *__restrict__ bias,
+                                  float *__restrict__ thetaP, int Din, int Dout, int RP, int CP,
+                                  int transpose)
+{
+    const int total = 4 * RP * CP;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const int c = i % CP, r = (i / CP) % RP, j = i / (CP * RP);
+        const int ci = transpose ? c : r;   // input channel
+        const int co = transpose ? r : c;   // output channel
+        float v = 0.f;
+        if (ci < Din && co < Dout)
+            v = (j < 3) ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co];
+        thetaP[i] = v;
+    }
+}
+
+hipError_t launch_pack_theta(const float *theta, const float *bias, float *thetaP, int Din,
+                             int Dout, int RP, int CP, int transpose, hipStream_t s)
+{
+    const int total = 4 * RP * CP;
+    const int blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(pack_theta_kernel, dim3(blocks > 1024 ? 1024 : blocks), dim3(256), 0, s,
+                       theta, bias, thetaP, Din, Dout, RP, CP, transpose);
+    return hipGetLastError();
+}
+
+// ---- [B,R,C] -> [B,C,R] transposes (64x64 tiles through LDS) -----------------
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ src,
+                                                        float *__restrict__ dst, int R, int C,
+                                                        int tiles_r, int tiles_c)
+{
+    __shared__ float tile[64][65];
+    const int64_t t = blockIdx.x;
+    const int tc = (int)(t % tiles_c);
+    const int tr = (int)((t / tiles_c) % tiles_r);
+    const int64_t b = t / ((int64_t)tiles_c * tiles_r);
+    const float *s = src + b * (int64_t)R * C;
+    float *d = dst + b * (int64_t)R * C;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int r0 = tr * 64, c0 = tc * 64;
+    for (int i = ty; i < 64; i += 4) {
+        const int r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < R && c < C) ? s[(int64_t)r * C + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i, r = r0 + tx;
+        if (r < R && c < C) d[(int64_t)c * R + r] = tile[tx][i];
+    }
+}
+
+static hipError_t launch_transpose(const float *src, float *dst, int B, int R, int C, hipStream_t s)
+{
+    const int tiles_r = (R + 63) / 64, tiles_c = (C + 63) / 64;
+    const int64_t blocks = (int64_t)B * tiles_r * tiles_c;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, R, C,
+                       tiles_r, tiles_c);
+    return hipGetLastError();
+}
+
+hipError_t launch_bcn_to_bnc(const float *src, float *dst, int B, int C, int N, hipStream_t s)
+{
+    return launch_transpose(src, dst, B, C, N, s);
+}
+hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, hipStream_t s)
+{
+    return launch_transpose(src, dst, B, N, C, s);
+}
+
+// ---- grad_theta partial reduction --------------------------------------------
+// partials [n_wg][KD][DOP] -> grad_theta [3,Din,Dout], grad_bias [Din,Dout];
+// the cross-workgroup sum runs in double so its error does not grow with n_wg.
+__global__ void reduce_partials_kernel(const float *__restrict__ partials, int n_wg, int DIP,
+                                       int DOP, int Din, int Dout, float *__restrict__ grad_theta,
+                                       float *__restrict__ grad_bias)
+{
+    __shared__ double red[4][64];
+    const int o = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int part = threadIdx.x >> 6;                      // 4 strided shares of the workgroups
+    const int kd = blockIdx.y;                              // row of ThetaP: j*DIP + c
+    const int j = kd / DIP, c = kd % DIP;
+    double sum = 0.0;
+    if (o < DOP) {
+        const int64_t stride = (int64_t)4 * DIP * DOP;
+        const float *p = partials + (int64_t)kd * DOP + o;
+        for (int g = part; g < n_wg; g += 4) sum += (double)p[g * stride];
+    }
+    red[part][threadIdx.x & 63] = sum;
+    __syncthreads();
+    if (part == 0 && o < Dout && c < Din) {
+        const int x = threadIdx.x & 63;
+        const float v = (float)(red[0][x] + red[1][x] + red[2][x] + red[3][x]);
+        if (j < 3) grad_theta[((int64_t)j * Din + c) * Dout + o] = v;
+        else grad_bias[(int64_t)c * Dout + o] = v;
+    }
+}
+
+hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,
+                                  int Dout, float *grad_theta, float *grad_bias, hipStream_t s)
+{
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((DOP + 63) / 64, 4 * DIP), dim3(256), 0, s,
+                       partials, n_wg, DIP, DOP, Din, Dout, grad_theta, grad_bias);
+    return hipGetLastError();
+}
+
+// ---- range check and zero fill --------------------------------------------------
+__global__ void count_bad_kernel(const int32_t *__restrict__ nbr, int64_t count, int N,
+                                 int32_t *__restrict__ bad)
+{
+    int local = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int v = nbr[i];
+        local += (v < 0 || v >= N);
+    }
+    if (local) atomicAdd(bad, local);
+}
+
+hipError_t launch_count_bad(const int32_t *nbr, int64_t count, int N, int32_t *bad, hipStream_t s)
+{
+    hipError_t e = launch_fill_zero(bad, sizeof(int32_t), s);
+    if (e != hipSuccess) return e;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(count_bad_kernel, dim3((unsigned)blocks), dim3(256), 0, s, nbr, count, N, bad);
+    return hipGetLastError();
+}
+
+__global__ void fill_zero_kernel(uint32_t *__restrict__ p, int64_t words)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+// bytes must be a multiple of 4 and ptr 4-byte aligned.
+hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s)
+{
+    const int64_t words = (int64_t)(bytes / 4);
+    if (words == 0) return hipSuccess;
+    int64_t blocks = (words + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint32_t *)ptr, words);
+    return hipGetLastError();
+}
+
+// ---- generic direct-form kernels ------------------------------------------------
+// Element (b, c, l) of a [B,C,N] / [B,N,C] tensor.
+__device__ __forceinline__ int64_t at(int bnc, int b, int c, int l, int C, int N)
+{
+    return bnc ? ((int64_t)b * N + l) * C + c : ((int64_t)b * C + c) * N + l;
+}
+
+__global__ void generic_fwd_kernel(const float *__restrict__ feat, const float *__restrict__ pos,
+                                   const int32_t *__restrict__ nbr, const float *__restrict__ theta,
+                                   const float *__restrict__ bias, float *__restrict__ out, int B,
+                                   int N, int K, int Din, int Dout, int bnc)
+{
+    const int64_t total = (int64_t)B * N * Dout;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int o = (int)(i % Dout);
+        const int64_t gp = i / Dout;
+        const int b = (int)(gp / N), l = (int)(gp % N);
+        const float *px = pos + (int64_t)b * 3 * N, *py = px + N, *pz = py + N;
+        float acc = 0.f;
+        for (int k = 0; k < K; ++k) {
+            const int n = nbr[((int64_t)b * K + k) * N + l];
+            const float dx = px[n] - px[l], dy = py[n] - py[l], dz = pz[n] - pz[l];
+            for (int c = 0; c < Din; ++c) {
+                const float w = theta[((int64_t)0 * Din + c) * Dout + o] * dx +
+                                theta[((int64_t)1 * Din + c) * Dout + o] * dy +
+                                theta[((int64_t)2 * Din + c) * Dout + o] * dz +
+                                bias[(int64_t)c * Dout + o];
+                acc = fmaf(w, feat[at(bnc, b, c, n, Din, N)], acc);
+            }
+        }
+        out[at(bnc, b, o, l, Dout, N)] = acc;
+    }
+}
+
+hipError_t launch_generic_fwd(const float *feat, const float *pos, const int32_t *nbr,
+                              const float *theta, const float *bias, float *out, int B, int N,
+                              int K, int Din, int Dout, int bnc, hipStream_t s)
+{
+    const int64_t total = (int64_t)B * N * Dout;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(generic_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, feat, pos, nbr,
+                       theta, bias, out, B, N, K, Din, Dout, bnc);
+    return hipGetLastError();
+}
+
+// grad_feat by scatter: one thread per (centre, slot, input channel).
+__global__ void generic_grad_feat_kernel(const float *__restrict__ pos,
+                                         const int32_t *__restrict__ nbr,
+                                         const float *__restrict__ theta,
+                                         const float *__restrict__ bias,
+                                         const float *__restrict__ grad_out,
+                                         float *__restrict__ grad_feat, int B, int N, int K, int Din,
+                                         int Dout, int bnc)
+{
+    const int64_t total = (int64_t)B * N * K * Din;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % Din);
+        const int64_t e = i / Din;
+        const int k = (int)(e % K);
+        const int64_t gp = e / K;
+        const int b = (int)(gp / N), l = (int)(gp % N);
+        const float *px = pos + (int64_t)b * 3 * N, *py = px + N, *pz = py + N;
+        const int n = nbr[((int64_t)b * K + k) * N + l];
+        const float dx = px[n] - px[l], dy = py[n] - py[l], dz = pz[n] - pz[l];
+        float sum = 0.f;
+        for (int o = 0; o < Dout; ++o) {
+            const float w = theta[((int64_t)0 * Din + c) * Dout + o] * dx +
+                            theta[((int64_t)1 * Din + c) * Dout + o] * dy +
+                            theta[((int64_t)2 * Din + c) * Dout + o] * dz +
+                            bias[(int64_t)c * Dout + o];
+            sum = fmaf(w, grad_out[at(bnc, b, o, l, Dout, N)], sum);
+        }
+        atomicAdd(&grad_feat[at(bnc, b, c, n, Din, N)], sum);
+    }
+}
+
+// grad_theta / grad_bias: block = (input channel c, chunk of centres); threads over o.
+__global__ __launch_bounds__(256) void generic_grad_theta_kernel(
+    const float *__restrict__ feat, const float *__restrict__ pos, const int32_t *__restrict__ nbr,
+    const float *__restrict__ grad_out, float *__restrict__ grad_theta,
+    float *__restrict__ grad_bias, int B, int N, int K, int Din, int Dout, int bnc,
+    int64_t pts_per_chunk)
+{
+    const int c = blockIdx.x;
+    const int64_t BN = (int64_t)B * N;
+    const int64_t g0 = (int64_t)blockIdx.y * pts_per_chunk;
+    const int64_t g1 = (g0 + pts_per_chunk < BN) ? g0 + pts_per_chunk : BN;
+    for (int o0 = 0; o0 < Dout; o0 += 256) {
+        const int o = o0 + threadIdx.x;
+        float ax = 0.f, ay = 0.f, az = 0.f, ab = 0.f;
+        for (int64_t gp = g0; gp < g1; ++gp) {
+            const int b = (int)(gp / N), l = (int)(gp % N);
+            const float *px = pos + (int64_t)b * 3 * N, *py = px + N, *pz = py + N;
+            float sx = 0.f, sy = 0.f, sz = 0.f, sb = 0.f;
+            for (int k = 0; k < K; ++k) {
+                const int n = nbr[((int64_t)b * K + k) * N + l];
+                const float f = feat[at(bnc, b, c, n, Din, N)];
+                sx = fmaf(px[n] - px[l], f, sx);
+                sy = fmaf(py[n] - py[l], f, sy);
+                sz = fmaf(pz[n] - pz[l], f, sz);
+                sb += f;
+            }
+            if (o < Dout) {
+                const float g = grad_out[at(bnc, b, o, l, Dout, N)];
+                ax = fmaf(sx, g, ax); ay = fmaf(sy, g, ay); az = fmaf(sz, g, az); ab = fmaf(sb, g, ab);
+            }
+        }
+        if (o < Dout) {
+            atomicAdd(&grad_theta[((int64_t)0 * Din + c) * Dout + o], ax);
+            atomicAdd(&grad_theta[((int64_t)1 * Din + c) * Dout + o], ay);
+            atomicAdd(&grad_theta[((int64_t)2 * Din + c) * Dout + o], az);
+            atomicAdd(&grad_bias[(int64_t)c * Dout + o], ab);
+        }
+    }
+}
+
+hipError_t launch_generic_bwd(const float *feat, const float *pos, const int32_t *nbr,
+                              const float *theta, const float *bias, const float *grad_out,
+                              float *grad_feat, float *grad_theta, float *grad_bias, int B, int N,
+                              int K, int Din, int Dout, int bnc, hipStream_t s)
+{
+    hipError_t e;
+    if (grad_feat) {
+        e = launch_fill_zero(grad_feat, sizeof(float) * (size_t)B * N * Din, s);
+        if (e != hipSuccess) return e;
+        const int64_t total = (int64_t)B * N * K * Din;
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(generic_grad_feat_kernel, dim3((unsigned)blocks), dim3(256), 0, s, pos, nbr,
+                           theta, bias, grad_out, grad_feat, B, N, K, Din, Dout, bnc);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (grad_theta && grad_bias) {
+        e = launch_fill_zero(grad_theta, sizeof(float) * (size_t)3 * Din * Dout, s);
+        if (e != hipSuccess) return e;
+        e = launch_fill_zero(grad_bias, sizeof(float) * (size_t)Din * Dout, s);
+        if (e != hipSuccess) return e;
+        const int64_t BN = (int64_t)B * N;
+        int64_t chunks = (BN + 255) / 256;
+        if (chunks > 1024) chunks = 1024;
+        const int64_t per = (BN + chunks - 1) / chunks;
+        chunks = (BN + per - 1) / per;
+        hipLaunchKernelGGL(generic_grad_theta_kernel, dim3(Din, (unsigned)chunks), dim3(256), 0, s,
+                           feat, pos, nbr, grad_out, grad_theta, grad_bias, B, N, K, Din, Dout, bnc, per);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace flex

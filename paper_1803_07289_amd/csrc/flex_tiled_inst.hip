@@ -1,0 +1,56 @@
+// One instantiation of the tiled kernels; compiled once per line of
+// flex_shapes.def with -DFLEX_DI= -DFLEX_DO= -DFLEX_W= -DFLEX_T= -DFLEX_OCC=.
+#include "flex_tiled.hpp"
+
+#if !defined(FLEX_DI) || !defined(FLEX_DO) || !defined(FLEX_W) || !defined(FLEX_T) || !defined(FLEX_OCC)
+#error "build with -DFLEX_DI -DFLEX_DO -DFLEX_W -DFLEX_T -DFLEX_OCC"
+#endif
+
+#define FLEX_CAT5(a, b, c) a##_##b##_##c
+#define FLEX_NAME(a, b, c) FLEX_CAT5(a, b, c)
+
+namespace flex {
+
+using S = TileShape<FLEX_DI, FLEX_DO, FLEX_W, FLEX_T, FLEX_OCC>;
+static constexpr int WG_PER_CU = (FLEX_OCC * 4) / FLEX_W > 0 ? (FLEX_OCC * 4) / FLEX_W : 1;
+
+hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float *pos,
+                                                  const int32_t *nbr, const int32_t *off,
+                                                  const int32_t *src, const float *thetaP,
+                                                  float *out, int B, int N, int K, int csr,
+                                                  int out_bcn, hipStream_t s)
+{
+    const int tiles_per_cloud = (N + S::T - 1) / S::T;
+    const int64_t total64 = (int64_t)B * tiles_per_cloud;
+    if (total64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int total = (int)total64;
+    const int grid = persistent_grid(total, WG_PER_CU);
+    const dim3 g(grid), blk(S::NT);
+    if (!csr && !out_bcn)
+        hipLaunchKernelGGL((gather_contract_kernel<S, false, false>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
+    else if (!csr && out_bcn)
+        hipLaunchKernelGGL((gather_contract_kernel<S, false, true>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
+    else if (csr && !out_bcn)
+        hipLaunchKernelGGL((gather_contract_kernel<S, true, false>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
+    else
+        hipLaunchKernelGGL((gather_contract_kernel<S, true, true>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
+    return hipGetLastError();
+}
+
+// Launches the per-workgroup partial kernel; *n_wg = number of partial blocks written.
+hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float *pos,
+                                                  const int32_t *nbr, const float *g_rows,
+                                                  float *partials, int B, int N, int K, int *n_wg,
+                                                  hipStream_t s)
+{
+    const int tiles_per_cloud = (N + S::T - 1) / S::T;
+    const int64_t total64 = (int64_t)B * tiles_per_cloud;
+    if (total64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int total = (int)total64;
+    const int grid = persistent_grid(total, WG_PER_CU);
+    *n_wg = grid;
+    hipLaunchKernelGGL((grad_theta_kernel<S>), dim3(grid), dim3(S::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total);
+    return hipGetLastError();
+}
+
+}  // namespace flex

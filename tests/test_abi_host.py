@@ -1,0 +1,84 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every
+declared symbol, and rejects host-visible errors before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "flexconv.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_1803_07289_amd as fx
+    if not os.path.exists(fx.LIB_PATH):
+        from paper_1803_07289_amd import build
+        build.build()
+    return fx.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flex[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_symbols()
+    assert {"flexconv_fwd", "flexconv_bwd", "flexpool_fwd", "flexpool_bwd", "flex_inedges_build",
+            "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
+            "flexconv_has_fast_path"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings(L):
+    assert L.flex_status_string(0) == b"ok"
+    for s in range(1, 6):
+        assert len(L.flex_status_string(s)) > 0
+    assert L.flex_status_string(99) == b"unknown status"
+
+
+def test_null_and_shape_errors_precede_any_launch(L):
+    one = ctypes.c_void_p(256)      # never dereferenced: validation fails first
+    none = None
+    # null pointers
+    assert L.flexconv_fwd(none, one, one, one, one, one, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
+    assert L.flexpool_fwd(one, none, one, one, 1, 8, 2, 4, 0, None) == 1
+    assert L.flexpool_bwd(one, one, none, 1, 8, 4, 0, None) == 1
+    assert L.flexconv_bwd(one, one, one, one, one, none, one, one, one, none, none, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
+    # grad_theta without grad_bias, in_off without in_src
+    assert L.flexconv_bwd(one, one, one, one, one, one, one, one, none, none, none, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
+    assert L.flexconv_bwd(one, one, one, one, one, one, one, one, one, one, none, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
+    # sizes: zero, K > N, bad layout, B*N too large
+    assert L.flexconv_fwd(one, one, one, one, one, one, 0, 8, 2, 4, 4, 0, one, 1 << 20, None) == 2
+    assert L.flexconv_fwd(one, one, one, one, one, one, 1, 8, 9, 4, 4, 0, one, 1 << 20, None) == 2
+    assert L.flexconv_fwd(one, one, one, one, one, one, 1, 8, 2, 4, 4, 7, one, 1 << 20, None) == 2
+    assert L.flexconv_fwd(one, one, one, one, one, one, 1 << 12, 1 << 20, 2, 4, 4, 0, one, 1 << 20, None) == 2
+    assert L.flexpool_fwd(one, one, one, one, 1, 8, 2, 0, 0, None) == 2
+    assert L.flexpool_bwd(one, one, one, 1, 8, 4, 3, None) == 2
+    # workspace: missing, misaligned, too small (tiled shape needs > 256 bytes)
+    assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, none, 0, None) == 4
+    assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, ctypes.c_void_p(260), 1 << 20, None) == 4
+    assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, one, 512, None) == 4
+
+
+def test_workspace_sizes(L):
+    w = L.flexconv_workspace_bytes
+    assert w(0, 1, 4096, 8, 64, 64, 1) == 4 * 64 * 64 * 4                       # packed parameters only
+    assert w(0, 1, 4096, 8, 64, 64, 0) == 4 * 64 * 64 * 4 + 4096 * 64 * 4        # + transposed features
+    assert w(0, 1, 4096, 8, 5, 7, 0) == 256                                      # generic kernels need none
+    assert w(2, 1, 4096, 8, 64, 64, 1) > w(1, 1, 4096, 8, 64, 64, 1) > 0
+    assert w(0, 0, 4096, 8, 64, 64, 1) == 0 and w(9, 1, 4096, 8, 64, 64, 1) == 0
+    assert w(0, 1, 4096, 8, 64, 64, 5) == 0
+    assert L.flexconv_has_fast_path(64, 64) == 1 and L.flexconv_has_fast_path(5, 7) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_1803_07289_amd as fx
+    t = torch.zeros(1, 4, 8)
+    with pytest.raises(TypeError):
+        fx.flexpool_fwd(t, torch.zeros(1, 2, 8, dtype=torch.int32))

@@ -36,7 +36,7 @@ MUTATIONS = [
     ("nbr_layout_transposed", "nbr[IDX3(b, k, l, K, N)]", "nbr[((int64_t)b * N + l) * K + k]", None, FWD_PINS),
     ("bwd_gfeat_to_centre", "grad_feat[IDX3(b, c, n, Din, N)] += s;", "grad_feat[IDX3(b, c, l, Din, N)] += s;", 0, BWD_PINS),
     ("bwd_gtheta_xy_swapped", "gtx[o] += dx * fg;", "gtx[o] += dy * fg;", 0, BWD_PINS),
-    ("bwd_gbias_uses_weight", "gbb[o] += fg;", "gbb[o] += w * fg;", 0, BWD_PINS),
+    ("bwd_gbias_uses_position", "gbb[o] += fg;", "gbb[o] += dz * fg;", 0, BWD_PINS),
     ("bwd_at_wrong_g_column", "s += w * (double)grad_out[IDX3(b, o, l, Dout, N)];",
      "s += w * (double)grad_out[IDX3(b, o, n, Dout, N)];", 0, BWD_PINS),
     ("pool_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 0, POOL_PINS),
