@@ -26,14 +26,20 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
     const int total = (int)total64;
     const int grid = persistent_grid(total, WG_PER_CU);
     const dim3 g(grid), blk(S::NT);
-    if (!csr && !out_bcn)
-        hipLaunchKernelGGL((gather_contract_kernel<S, false, false>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
-    else if (!csr && out_bcn)
-        hipLaunchKernelGGL((gather_contract_kernel<S, false, true>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
-    else if (csr && !out_bcn)
-        hipLaunchKernelGGL((gather_contract_kernel<S, true, false>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
-    else
-        hipLaunchKernelGGL((gather_contract_kernel<S, true, true>), g, blk, 0, s, rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total);
+    using G = WaveGeom<S>;
+    const bool fast = csr || ((int64_t)G::PW * K <= G::EW);
+#define FLEX_GC_ARGS rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total
+    if (fast) {
+        if (!csr && !out_bcn) hipLaunchKernelGGL((gather_contract_fast_kernel<S, false, false>), g, blk, 0, s, FLEX_GC_ARGS);
+        else if (!csr && out_bcn) hipLaunchKernelGGL((gather_contract_fast_kernel<S, false, true>), g, blk, 0, s, FLEX_GC_ARGS);
+        else if (csr && !out_bcn) hipLaunchKernelGGL((gather_contract_fast_kernel<S, true, false>), g, blk, 0, s, FLEX_GC_ARGS);
+        else hipLaunchKernelGGL((gather_contract_fast_kernel<S, true, true>), g, blk, 0, s, FLEX_GC_ARGS);
+    } else {
+        // neighbourhoods too large for the wave-private staging: chunked kernel
+        if (!out_bcn) hipLaunchKernelGGL((gather_contract_kernel<S, false, false>), g, blk, 0, s, FLEX_GC_ARGS);
+        else hipLaunchKernelGGL((gather_contract_kernel<S, false, true>), g, blk, 0, s, FLEX_GC_ARGS);
+    }
+#undef FLEX_GC_ARGS
     return hipGetLastError();
 }
 
@@ -49,7 +55,11 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     const int total = (int)total64;
     const int grid = persistent_grid(total, WG_PER_CU);
     *n_wg = grid;
-    hipLaunchKernelGGL((grad_theta_kernel<S>), dim3(grid), dim3(S::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total);
+    using G = WaveGeom<S>;
+    if ((int64_t)G::PW * K <= G::EW)
+        hipLaunchKernelGGL((grad_theta_fast_kernel<S>), dim3(grid), dim3(S::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total);
+    else
+        hipLaunchKernelGGL((grad_theta_kernel<S>), dim3(grid), dim3(S::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total);
     return hipGetLastError();
 }
 
