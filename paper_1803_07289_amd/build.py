@@ -26,7 +26,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 def shapes():
     out = []
     for line in open(os.path.join(CSRC, "flex_shapes.def")):
-        m = re.match(r"\s*FLEX_SHAPE\(\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*\)", line)
+        m = re.match(r"\s*FLEX_SHAPE\(\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*\)", line)
         if m:
             out.append(tuple(int(x) for x in m.groups()))
     return out
@@ -36,10 +36,10 @@ def _jobs():
     jobs = []
     for name in ("flex_api", "flex_misc", "flex_pool", "flex_inedges"):
         jobs.append((os.path.join(CSRC, name + ".hip"), os.path.join(OBJ, name + ".o"), []))
-    for (di, do, w, t, occ) in shapes():
+    for (di, do, w, t, occ, ws) in shapes():
         jobs.append((os.path.join(CSRC, "flex_tiled_inst.hip"),
                      os.path.join(OBJ, f"flex_tiled_{di}_{do}.o"),
-                     [f"-DFLEX_DI={di}", f"-DFLEX_DO={do}", f"-DFLEX_W={w}", f"-DFLEX_T={t}", f"-DFLEX_OCC={occ}"]))
+                     [f"-DFLEX_DI={di}", f"-DFLEX_DO={do}", f"-DFLEX_W={w}", f"-DFLEX_T={t}", f"-DFLEX_OCC={occ}", f"-DFLEX_WS={ws}"]))
     return jobs
 
 

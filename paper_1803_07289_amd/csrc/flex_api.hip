@@ -5,7 +5,7 @@
 namespace flex {
 
 // ---- per-shape launchers generated from flex_shapes.def ------------------------
-#define FLEX_SHAPE(DI, DO, W, T, OCC)                                                              \
+#define FLEX_SHAPE(DI, DO, W, T, OCC, WS)                                                             \
     hipError_t launch_gc_##DI##_##DO(const float *, const float *, const int32_t *, const int32_t *, \
                                      const int32_t *, const float *, float *, int, int, int, int,    \
                                      int, hipStream_t);                                              \
@@ -19,7 +19,7 @@ hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int 
 
 bool gather_contract_supported(int DI, int DO)
 {
-#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_) return true;
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
@@ -31,7 +31,7 @@ hipError_t launch_gather_contract(const float *rows, const float *pos, const int
                                   float *out, int B, int N, int K, int DI, int DO, int csr,
                                   int out_bcn, hipStream_t s)
 {
-#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_)         \
         return launch_gc_##DI_##_##DO_(rows, pos, nbr, off, src, thetaP, out, B, N, K, csr, out_bcn, s);
 #include "flex_shapes.def"
@@ -41,7 +41,7 @@ hipError_t launch_gather_contract(const float *rows, const float *pos, const int
 
 static int shape_tile_points(int DI, int DO)
 {
-#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_) return T;
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
@@ -50,7 +50,7 @@ static int shape_tile_points(int DI, int DO)
 
 static int shape_wg_per_cu(int DI, int DO)
 {
-#define FLEX_SHAPE(DI_, DO_, W, T, OCC) \
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_) return ((OCC * 4) / W > 0) ? (OCC * 4) / W : 1;
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
@@ -75,7 +75,7 @@ hipError_t launch_grad_theta(const float *rows, const float *pos, const int32_t 
 {
     int n_wg = 0;
     hipError_t e = hipErrorNotSupported;
-#define FLEX_SHAPE(DI_, DO_, W, T, OCC)                                                    \
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS)                                                    \
     if (Din == DI_ && Dout == DO_)                                                         \
         e = launch_gt_##DI_##_##DO_(rows, pos, nbr, g_rows, partials, B, N, K, &n_wg, s);
 #include "flex_shapes.def"

@@ -456,20 +456,17 @@ __device__ __forceinline__ void load_row(float (&f)[S::VEC], const float *__rest
     }
 }
 
-// acc[j][v] += e.d[j] * f[v]  (j = x,y,z,1).  With 4-lane blocks that stay inside one
+// acc[v][j] += d[j] * f[v]  (j = x,y,z,1; acc[v] is the 4-float accumulator of channel v).  With 4-lane blocks that stay inside one
 // gathered row this is sixteen 4x4 outer products per wave: one
 // v_mfma_f32_4x4x1_16b_f32 per float of the lane (A = the lane's component of
 // (dx,dy,dz,1), B = the feature), which runs on the matrix pipe instead of
 // sixteen vector FMAs.  `dpc` is that component, already selected for this lane.
 template <class S>
-__device__ __forceinline__ void fma_row(float (&acc)[4][S::VEC], float dpc, const float (&f)[S::VEC])
+__device__ __forceinline__ void fma_row(v4f (&acc)[S::VEC], float dpc, const float (&f)[S::VEC])
 {
 #pragma unroll
-    for (int v = 0; v < S::VEC; ++v) {
-        v4f c = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-        c = __builtin_amdgcn_mfma_f32_4x4x1f32(dpc, f[v], c, 0, 0, 0);
-        acc[0][v] = c.x; acc[1][v] = c.y; acc[2][v] = c.z; acc[3][v] = c.w;
-    }
+    for (int v = 0; v < S::VEC; ++v)
+        acc[v] = __builtin_amdgcn_mfma_f32_4x4x1f32(dpc, f[v], acc[v], 0, 0, 0);
 }
 
 // What a wave carries from one tile to the next.
@@ -481,7 +478,7 @@ struct Prefetch {
 
 // Aggregate of this wave's PW points -> acc (registers).  s_w: wave-private staging.
 template <class S, bool CSR>
-__device__ __forceinline__ void wave_aggregate(float (&acc)[WaveGeom<S>::PASSES][4][S::VEC], WaveStage<S> *s_w,
+__device__ __forceinline__ void wave_aggregate(v4f (&acc)[WaveGeom<S>::PASSES][S::VEC], WaveStage<S> *s_w,
                                                Prefetch<S> &pf, const float *__restrict__ rows,
                                                const float *__restrict__ px, const float *__restrict__ py,
                                                const float *__restrict__ pz,
@@ -496,9 +493,7 @@ __device__ __forceinline__ void wave_aggregate(float (&acc)[WaveGeom<S>::PASSES]
 #pragma unroll
     for (int p = 0; p < G::PASSES; ++p)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int v = 0; v < S::VEC; ++v) acc[p][j][v] = 0.f;
+        for (int v = 0; v < S::VEC; ++v) acc[p][v] = v4f{0.f, 0.f, 0.f, 0.f};
 
     // CSR: in-edge offsets of the wave's points, wave-uniform (lane j of pf.off holds offset j)
     int offs[G::PW + 1];
@@ -616,7 +611,7 @@ __device__ __forceinline__ void wave_aggregate(float (&acc)[WaveGeom<S>::PASSES]
 
 // Writes this wave's PW rows of the aggregate tile.
 template <class S, int AST>
-__device__ __forceinline__ void wave_store_aggregate(float *s_A, const float (&acc)[WaveGeom<S>::PASSES][4][S::VEC])
+__device__ __forceinline__ void wave_store_aggregate(float *s_A, const v4f (&acc)[WaveGeom<S>::PASSES][S::VEC])
 {
     using G = WaveGeom<S>;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -629,10 +624,10 @@ __device__ __forceinline__ void wave_store_aggregate(float *s_A, const float (&a
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 if constexpr (S::VEC == 4) {
-                    v4f v = {acc[p][jj][0], acc[p][jj][1], acc[p][jj][2], acc[p][jj][3]};
+                    v4f v = {acc[p][0][jj], acc[p][1][jj], acc[p][2][jj], acc[p][3][jj]};
                     *reinterpret_cast<v4f *>(row + jj * S::DIP) = v;
                 } else {
-                    row[jj * S::DIP] = acc[p][jj][0];
+                    row[jj * S::DIP] = acc[p][0][jj];
                 }
             }
         }
@@ -735,7 +730,7 @@ void gather_contract_fast_kernel(const float *__restrict__ rows, const float *__
         float *sA = s_A[buf];
 
         {
-            float agg[G::PASSES][4][S::VEC];
+            v4f agg[G::PASSES][S::VEC];
             wave_aggregate<S, CSR>(agg, &s_e[w], pf, rows, px, py, pz, src, b * N, l0 + w * G::PW, N, K);
             wave_store_aggregate<S, AST>(sA, agg);
         }
@@ -871,7 +866,7 @@ void grad_theta_fast_kernel(const float *__restrict__ rows, const float *__restr
                 gv[i] = g_rows[((int64_t)b * N + l0 + j) * S::DO + o];
         }
         {
-            float agg[G::PASSES][4][S::VEC];
+            v4f agg[G::PASSES][S::VEC];
             wave_aggregate<S, false>(agg, &s_e[w], pf, rows, px, py, pz, nullptr, b * N, l0 + w * G::PW, N, K);
             wave_store_aggregate<S, AST>(sA, agg);
         }

@@ -1,9 +1,12 @@
 // One instantiation of the tiled kernels; compiled once per line of
-// flex_shapes.def with -DFLEX_DI= -DFLEX_DO= -DFLEX_W= -DFLEX_T= -DFLEX_OCC=.
+// flex_shapes.def with -DFLEX_DI= -DFLEX_DO= -DFLEX_W= -DFLEX_T= -DFLEX_OCC= -DFLEX_WS=.
 #include "flex_tiled.hpp"
+#if FLEX_WS
+#include "flex_ws.hpp"
+#endif
 
-#if !defined(FLEX_DI) || !defined(FLEX_DO) || !defined(FLEX_W) || !defined(FLEX_T) || !defined(FLEX_OCC)
-#error "build with -DFLEX_DI -DFLEX_DO -DFLEX_W -DFLEX_T -DFLEX_OCC"
+#if !defined(FLEX_DI) || !defined(FLEX_DO) || !defined(FLEX_W) || !defined(FLEX_T) || !defined(FLEX_OCC) || !defined(FLEX_WS)
+#error "build with -DFLEX_DI -DFLEX_DO -DFLEX_W -DFLEX_T -DFLEX_OCC -DFLEX_WS"
 #endif
 
 #define FLEX_CAT5(a, b, c) a##_##b##_##c
@@ -25,10 +28,27 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
     if (total64 > 0x7fffffff) return hipErrorInvalidValue;
     const int total = (int)total64;
     const int grid = persistent_grid(total, WG_PER_CU);
+#define FLEX_GC_ARGS rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total
+#if FLEX_WS
+    {
+        using W = WsGeom<S>;
+        if (csr || (int64_t)W::PW * K <= W::EW) {
+            const int tpc = (N + W::T - 1) / W::T;
+            const int tot = B * tpc;
+            const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
+#define FLEX_WS_ARGS rows, pos, nbr, off, src, thetaP, out, N, K, tpc, tot
+            if (!csr && !out_bcn) hipLaunchKernelGGL((gather_contract_ws_kernel<S, false, false>), g, blk, 0, s, FLEX_WS_ARGS);
+            else if (!csr && out_bcn) hipLaunchKernelGGL((gather_contract_ws_kernel<S, false, true>), g, blk, 0, s, FLEX_WS_ARGS);
+            else if (csr && !out_bcn) hipLaunchKernelGGL((gather_contract_ws_kernel<S, true, false>), g, blk, 0, s, FLEX_WS_ARGS);
+            else hipLaunchKernelGGL((gather_contract_ws_kernel<S, true, true>), g, blk, 0, s, FLEX_WS_ARGS);
+#undef FLEX_WS_ARGS
+            return hipGetLastError();
+        }
+    }
+#endif
     const dim3 g(grid), blk(S::NT);
     using G = WaveGeom<S>;
     const bool fast = csr || ((int64_t)G::PW * K <= G::EW);
-#define FLEX_GC_ARGS rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total
     if (fast) {
         if (!csr && !out_bcn) hipLaunchKernelGGL((gather_contract_fast_kernel<S, false, false>), g, blk, 0, s, FLEX_GC_ARGS);
         else if (!csr && out_bcn) hipLaunchKernelGGL((gather_contract_fast_kernel<S, false, true>), g, blk, 0, s, FLEX_GC_ARGS);
@@ -55,6 +75,18 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     const int total = (int)total64;
     const int grid = persistent_grid(total, WG_PER_CU);
     *n_wg = grid;
+#if FLEX_WS
+    {
+        using W = WsGeom<S>;
+        if ((int64_t)W::PW * K <= W::EW) {
+            const int tpc = (N + W::T - 1) / W::T;
+            const int tot = B * tpc;
+            *n_wg = persistent_grid(tot, W::WG_PER_CU);
+            hipLaunchKernelGGL((grad_theta_ws_kernel<S>), dim3(*n_wg), dim3(W::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
+            return hipGetLastError();
+        }
+    }
+#endif
     using G = WaveGeom<S>;
     if ((int64_t)G::PW * K <= G::EW)
         hipLaunchKernelGGL((grad_theta_fast_kernel<S>), dim3(grid), dim3(S::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total);

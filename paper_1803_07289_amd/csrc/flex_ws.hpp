@@ -1,0 +1,586 @@
+// Wave-specialised flex-convolution kernels (gfx950, wave64).
+//
+// A workgroup is W PRODUCER waves plus W CONSUMER waves (W = S::WAVES; 16 waves
+// per CU in total, i.e. 16/(2W) workgroups).  Producers gather neighbour rows
+// and build the per-point aggregate A (see flex_tiled.hpp for the factoring),
+// consumers contract it with the packed parameters on the matrix cores.  The
+// aggregate tile is double-buffered in LDS and the two halves meet at one
+// workgroup barrier per tile, so tile k+1 is being gathered while tile k is
+// being contracted:
+//
+//   producers, iteration k:   request rows / positions of tile k+1 and the
+//                             neighbour ids of tile k+2;  finish tile k (its
+//                             rows were requested one iteration ago) -> A[k%2];
+//                             barrier
+//   consumers, iteration k:   barrier;  out[tile k] = A[k%2] * ThetaP
+//
+// Only consumers keep the parameter fragments in registers, producers spend
+// theirs on two tiles' worth of loads in flight; both fit 128 VGPRs, i.e. 4
+// waves per SIMD.  Every memory latency on the producer side has a full barrier
+// interval (one tile contraction) to complete.  With W = 4 two workgroups share
+// a CU and drift apart, so one group's barrier / store phase is covered by the
+// other group's contraction.
+//
+// Limits (the host falls back to the kernels of flex_tiled.hpp otherwise):
+// one gather pass per producer wave, fixed-K lists with PW*K <= 64 staged
+// entries; in-edge lists (CSR) of any length (entries past the first 64 of a
+// wave, or past the first 8 of a point, are fetched synchronously).
+#pragma once
+#include "flex_tiled.hpp"
+
+namespace flex {
+
+template <class S>
+struct WsGeom {
+    static constexpr int NP = S::WAVES, NC = S::WAVES;   // producer / consumer waves
+    static constexpr int NT = 64 * (NP + NC);
+    static constexpr int WG_PER_CU = 16 / (NP + NC);
+    static constexpr int T = S::T;                       // points per tile
+    static constexpr int PW = T / NP;                    // points per producer wave
+    static constexpr int GPW = 64 / S::LPR;              // row groups per wave
+    static constexpr int EW = 64;                        // staged entries per producer wave
+    static constexpr int U = 8;                          // rows in flight per lane
+    static constexpr int AST = S::KD + 4;
+    static_assert(T % NP == 0 && GPW >= PW, "one gather pass per producer wave");
+    static_assert(PW * 16 <= EW, "K <= 16 always fits the staging");
+    static_assert(S::LPR % 4 == 0, "4-lane blocks stay inside one row");
+    static constexpr int NS = S::DOP / 16;               // 16-wide output slices
+    static constexpr int NB = T / 16;                    // 16-point blocks
+    static constexpr int NITEMS = NS * NB;
+    static_assert(NITEMS % NC == 0 || NC % NITEMS == 0, "items per consumer wave");
+    static constexpr int IPW = cdiv_c(NITEMS, NC);
+    static_assert(IPW == 1 || NS % NC == 0 || NC % NS == 0, "slice split");
+};
+
+template <class S>
+struct WsStage {
+    int row[WsGeom<S>::EW];
+    v4f dp[WsGeom<S>::EW];
+};
+
+struct TileRef {
+    bool valid;
+    int b, l0;
+};
+
+__device__ __forceinline__ TileRef tile_ref(const TileSchedule &sc, int k, int tiles_per_cloud, int T)
+{
+    TileRef r;
+    const int tile = sc.first + k * sc.step;
+    r.valid = (tile < sc.end) && (sc.first < sc.end);
+    const int tc = r.valid ? tile : 0;
+    r.b = tc / tiles_per_cloud;
+    r.l0 = (tc - r.b * tiles_per_cloud) * T;
+    return r;
+}
+
+// ---------------------------------------------------------------------------
+// Producer side
+// ---------------------------------------------------------------------------
+template <class S, bool CSR>
+struct Producer {
+    using G = WsGeom<S>;
+    // loop-carried registers
+    int id_next;                 // entry `lane` of the tile to be issued next (neighbour / source id)
+    int off_use, off_issue, off_pref;   // CSR: lane j <= PW holds in-edge offset j of the wave's points
+    float pa[3], pb[3];          // raw positions (entry / centre) of the newest tile in flight
+    float f[2][G::U][S::VEC];    // rows in flight, two tiles deep
+    int lo[2], hi[2], cnt[2];    // group's entry range and staged count of those tiles
+    unsigned onmask[2];          // which of the U rows in flight are real
+
+    const float *rows, *pos;
+    const int32_t *nbr, *off, *src;
+    int N, K, lane, pw, grp, t, dsel;
+    bool lane_on;
+    WsStage<S> *st;              // this wave's two staging buffers
+
+    __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *nbr_,
+                                         const int32_t *off_, const int32_t *src_, int N_, int K_,
+                                         WsStage<S> *st_, int pw_)
+    {
+        rows = rows_; pos = pos_; nbr = nbr_; off = off_; src = src_; N = N_; K = K_; st = st_; pw = pw_;
+        lane = threadIdx.x & 63;
+        grp = lane / S::LPR; t = lane % S::LPR; dsel = lane & 3;
+        lane_on = (S::VEC * t) < S::DI;
+        id_next = 0; off_use = off_issue = off_pref = 0;
+        pa[0] = pa[1] = pa[2] = pb[0] = pb[1] = pb[2] = 0.f;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            lo[p] = hi[p] = cnt[p] = 0; onmask[p] = 0u;
+#pragma unroll
+            for (int u = 0; u < G::U; ++u)
+#pragma unroll
+                for (int v = 0; v < S::VEC; ++v) f[p][u][v] = 0.f;
+        }
+    }
+
+    // first point of this wave in tile r (cloud-local index)
+    __device__ __forceinline__ int lw0(const TileRef &r) const { return r.l0 + pw * G::PW; }
+
+    // CSR: request the in-edge offsets of this wave's points in tile r
+    __device__ __forceinline__ int load_offsets(const TileRef &r) const
+    {
+        if (!r.valid) return 0;
+        const int l = lw0(r);
+        const int npw = max(0, min(G::PW, N - l));
+        const int64_t g0 = (int64_t)r.b * N + min(l, N);
+        return off[g0 + min(lane, npw)];
+    }
+
+    // request entry `lane` of tile r: fixed-K neighbour id, or CSR source id (needs its offsets)
+    __device__ __forceinline__ int load_id(const TileRef &r, int offs) const
+    {
+        int v = 0;
+        if (!r.valid) return 0;
+        if constexpr (!CSR) {
+            if (lane < G::PW * K) {
+                const int k = lane / G::PW, l = lw0(r) + (lane % G::PW);
+                if (l < N) v = nbr[((int64_t)r.b * K + k) * N + l];
+            }
+        } else {
+            const int e0 = __builtin_amdgcn_readlane(offs, 0), e1 = __builtin_amdgcn_readlane(offs, G::PW);
+            if (e0 + lane < e1) v = src[e0 + lane];
+        }
+        return v;
+    }
+
+    __device__ __forceinline__ const float *row_ptr(int rid, bool on, int rowbase) const
+    {
+        // lanes without a real row read the cloud's row 0 (always mapped); their value is discarded
+        return rows + (int64_t)(on ? rid : rowbase) * S::DI + (lane_on ? S::VEC * t : 0);
+    }
+
+    template <int P>
+    __device__ __forceinline__ void request_rows(int first, int stride, int end, int rowbase)
+    {
+        int rid[G::U];
+        unsigned m = 0u;
+#pragma unroll
+        for (int u = 0; u < G::U; ++u) {
+            const int i = first + u * stride;
+            const bool on = i < end;
+            rid[u] = st[P].row[on ? i : 0];
+            if (on && lane_on) m |= (1u << u);
+        }
+        onmask[P] = m;
+#pragma unroll
+        for (int u = 0; u < G::U; ++u) {
+            const float *p = row_ptr(rid[u], (m >> u) & 1u, rowbase);
+            if constexpr (S::VEC == 4) {
+                const v4f v = *reinterpret_cast<const v4f *>(p);
+                f[P][u][0] = v.x; f[P][u][1] = v.y; f[P][u][2] = v.z; f[P][u][3] = v.w;
+            } else {
+                f[P][u][0] = *p;
+            }
+        }
+    }
+
+    template <int P>
+    __device__ __forceinline__ void accumulate_rows(v4f (&acc)[S::VEC], int first, int stride, int end)
+    {
+#pragma unroll
+        for (int u = 0; u < G::U; ++u) {
+            const int i = first + u * stride;
+            const bool on = (onmask[P] >> u) & 1u;
+            float fv[S::VEC];
+#pragma unroll
+            for (int v = 0; v < S::VEC; ++v) fv[v] = on ? f[P][u][v] : 0.f;
+            // the matrix op ignores EXEC: lanes without an entry feed 0 * 0
+            const float dpc = (i < end) ? reinterpret_cast<const float *>(&st[P].dp[i < end ? i : 0])[dsel] : 0.f;
+            fma_row<S>(acc, dpc, fv);
+        }
+    }
+
+    // group's entry range inside the staged chunk [c0, c0+cnt) of tile r
+    __device__ __forceinline__ void group_range(const TileRef &r, int offs, int c0, int cnt_, int &lo_, int &hi_,
+                                                int &stride) const
+    {
+        const bool act = r.valid && (grp < G::PW) && (lw0(r) + grp < N);
+        if constexpr (CSR) {
+            int a = __builtin_amdgcn_readlane(offs, 0), b = __builtin_amdgcn_readlane(offs, 1);
+#pragma unroll
+            for (int j = 1; j < G::PW; ++j)
+                if (grp == j) { a = __builtin_amdgcn_readlane(offs, j); b = __builtin_amdgcn_readlane(offs, j + 1); }
+            lo_ = max(a, c0) - c0;
+            hi_ = min(b, c0 + cnt_) - c0;
+            stride = 1;
+        } else {
+            lo_ = grp;
+            hi_ = grp + K * G::PW;
+            stride = G::PW;
+        }
+        if (!act || hi_ < lo_) hi_ = lo_;
+    }
+
+    // raw positions for the staged entry `lane` of tile r (entry id in `id`), chunk starting at edge c0
+    __device__ __forceinline__ void request_positions(const TileRef &r, int offs, int c0, int cnt_, int id,
+                                                      float (&pa)[3], float (&pb)[3])
+    {
+        pa[0] = pa[1] = pa[2] = pb[0] = pb[1] = pb[2] = 0.f;
+        if (lane < cnt_) {
+            int pj;
+            if constexpr (CSR) {
+                pj = 0;
+#pragma unroll
+                for (int j = 1; j < G::PW; ++j) pj += (__builtin_amdgcn_readlane(offs, j) <= c0 + lane) ? 1 : 0;
+            } else {
+                pj = lane % G::PW;
+            }
+            const float *px = pos + (int64_t)r.b * 3 * N, *py = px + N, *pz = py + N;
+            const int l = min(lw0(r) + pj, N - 1);
+            pa[0] = px[id]; pa[1] = py[id]; pa[2] = pz[id];
+            pb[0] = px[l]; pb[1] = py[l]; pb[2] = pz[l];
+        }
+    }
+
+    template <int P>
+    __device__ __forceinline__ void publish_dp(int cnt_, const float (&pa)[3], const float (&pb)[3])
+    {
+        if (lane < cnt_) {
+            const float sg = CSR ? -1.f : 1.f;   // CSR: centre - source
+            st[P].dp[lane] = v4f{sg * (pa[0] - pb[0]), sg * (pa[1] - pb[1]), sg * (pa[2] - pb[2]), 1.f};
+        }
+        wave_lds_sync();
+    }
+
+    // Start tile r in buffer P: stage its ids, request positions and the first U rows per point.
+    // `id` holds entry `lane`, `offs` its offsets (CSR).
+    template <int P>
+    __device__ __forceinline__ void issue(const TileRef &r, int id, int offs)
+    {
+        const int rowbase = r.b * N;
+        if constexpr (CSR) {
+            const int e0 = __builtin_amdgcn_readlane(offs, 0), e1 = __builtin_amdgcn_readlane(offs, G::PW);
+            cnt[P] = r.valid ? min(G::EW, e1 - e0) : 0;
+        } else {
+            cnt[P] = r.valid ? G::PW * K : 0;
+        }
+        if (lane < cnt[P]) st[P].row[lane] = rowbase + id;
+        wave_lds_sync();
+        const int c0 = CSR ? __builtin_amdgcn_readlane(offs, 0) : 0;
+        request_positions(r, offs, c0, cnt[P], id, pa, pb);
+        int stride;
+        group_range(r, offs, c0, cnt[P], lo[P], hi[P], stride);
+        request_rows<P>(lo[P], stride, hi[P], rowbase);
+    }
+
+    // Turn the positions of the tile in buffer P (requested by issue<P>) into staged differences.
+    // Must run before the next issue<>() reuses the position registers.
+    template <int P>
+    __device__ __forceinline__ void stage_dp() { publish_dp<P>(cnt[P], pa, pb); }
+
+    // Finish tile r (buffer P, issued one iteration ago): aggregate -> sA rows of this wave.
+    template <int P>
+    __device__ __forceinline__ void finish(const TileRef &r, int offs, float *sA)
+    {
+        v4f acc[S::VEC];
+#pragma unroll
+        for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+        const int rowbase = r.b * N;
+        const int stride = CSR ? 1 : G::PW;
+
+        accumulate_rows<P>(acc, lo[P], stride, hi[P]);
+        // a point with more than U staged entries: the rest synchronously
+        for (int i0 = lo[P] + G::U * stride; i0 < hi[P]; i0 += G::U * stride) {
+            request_rows<P>(i0, stride, hi[P], rowbase);
+            accumulate_rows<P>(acc, i0, stride, hi[P]);
+        }
+        if constexpr (CSR) {
+            // in-edges past the first staged chunk of this wave: whole chunks synchronously
+            const int e0 = __builtin_amdgcn_readlane(offs, 0), e1 = __builtin_amdgcn_readlane(offs, G::PW);
+            for (int c0 = e0 + G::EW; c0 < e1; c0 += G::EW) {
+                wave_lds_sync();
+                const int c = min(G::EW, e1 - c0);
+                const int id = (lane < c) ? src[c0 + lane] : 0;
+                if (lane < c) st[P].row[lane] = rowbase + id;
+                wave_lds_sync();
+                float qa[3], qb[3];
+                request_positions(r, offs, c0, c, id, qa, qb);
+                int l2, h2, s2;
+                group_range(r, offs, c0, c, l2, h2, s2);
+                request_rows<P>(l2, 1, h2, rowbase);
+                publish_dp<P>(c, qa, qb);
+                accumulate_rows<P>(acc, l2, 1, h2);
+                for (int i0 = l2 + G::U; i0 < h2; i0 += G::U) {
+                    request_rows<P>(i0, 1, h2, rowbase);
+                    accumulate_rows<P>(acc, i0, 1, h2);
+                }
+            }
+        }
+        wave_lds_sync();   // this staging buffer is rewritten two issues from now
+
+        if (grp < G::PW && (S::VEC * t) < S::DIP) {
+            float *row = sA + (pw * G::PW + grp) * G::AST + S::VEC * t;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                if constexpr (S::VEC == 4) {
+                    *reinterpret_cast<v4f *>(row + jj * S::DIP) = v4f{acc[0][jj], acc[1][jj], acc[2][jj], acc[3][jj]};
+                } else {
+                    row[jj * S::DIP] = acc[0][jj];
+                }
+            }
+        }
+    }
+};
+
+// One producer iteration for tile k living in buffer P.
+template <int P, class S, bool CSR, class Extra>
+__device__ __forceinline__ bool producer_step(Producer<S, CSR> &Pr, const TileSchedule &sc, int k,
+                                              int tiles_per_cloud, float (*s_A)[S::T * WsGeom<S>::AST],
+                                              Extra &&extra)
+{
+    using G = WsGeom<S>;
+    const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+    if (!r.valid) return false;
+    const TileRef rn = tile_ref(sc, k + 1, tiles_per_cloud, G::T);
+    const TileRef rnn = tile_ref(sc, k + 2, tiles_per_cloud, G::T);
+    Pr.template stage_dp<P>();          // positions of tile k -> staged differences
+    extra(k, r, 1);                     // park extra data of tile k in LDS
+    // tile k+1 goes in flight behind tile k
+    const int off_k = Pr.off_use;
+    const int id_issue = Pr.id_next;
+    if constexpr (CSR) {
+        Pr.off_use = Pr.off_issue;
+        Pr.off_issue = Pr.off_pref;
+        Pr.off_pref = Pr.load_offsets(tile_ref(sc, k + 3, tiles_per_cloud, G::T));
+    }
+    extra(k + 1, rn, 0);                // request extra data of tile k+1
+    Pr.template issue<P ^ 1>(rn, id_issue, Pr.off_use);
+    Pr.id_next = Pr.load_id(rnn, Pr.off_issue);
+    Pr.template finish<P>(r, off_k, s_A[P]);
+    __syncthreads();                    // tile k is complete in s_A[P]
+    return true;
+}
+
+// Runs the producer role for every tile of this workgroup; `extra(k, r, phase)` lets the
+// grad_theta kernel move its grad_out tile (phase 0: request for tile k, phase 1: park in LDS).
+template <class S, bool CSR, class Extra>
+__device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSchedule &sc, int tiles_per_cloud,
+                                              float (*s_A)[S::T * WsGeom<S>::AST], Extra &&extra)
+{
+    using G = WsGeom<S>;
+    // prologue: ids of tile 0 and 1, offsets up to tile 2, tile 0 in flight
+    const TileRef r0 = tile_ref(sc, 0, tiles_per_cloud, G::T), r1 = tile_ref(sc, 1, tiles_per_cloud, G::T);
+    if constexpr (CSR) {
+        Pr.off_use = Pr.load_offsets(r0);
+        Pr.off_issue = Pr.load_offsets(r1);
+        Pr.off_pref = Pr.load_offsets(tile_ref(sc, 2, tiles_per_cloud, G::T));
+    }
+    const int id0 = Pr.load_id(r0, Pr.off_use);
+    Pr.id_next = Pr.load_id(r1, Pr.off_issue);
+    extra(0, r0, 0);
+    Pr.template issue<0>(r0, id0, Pr.off_use);
+    for (int k = 0;; k += 2) {
+        if (!producer_step<0>(Pr, sc, k, tiles_per_cloud, s_A, extra)) break;
+        if (!producer_step<1>(Pr, sc, k + 1, tiles_per_cloud, s_A, extra)) break;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// out[l][:] = A[l][:] * ThetaP   (forward; grad_feat when CSR)
+// ---------------------------------------------------------------------------
+template <class S, bool CSR, bool OUT_BCN>
+__global__ __launch_bounds__(WsGeom<S>::NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                               const int32_t *__restrict__ nbr, const int32_t *__restrict__ off,
+                               const int32_t *__restrict__ src, const float *__restrict__ thetaP,
+                               float *__restrict__ out, int N, int K, int tiles_per_cloud, int total_tiles)
+{
+    using G = WsGeom<S>;
+    __shared__ __attribute__((aligned(16))) float s_A[2][G::T * G::AST];
+    __shared__ WsStage<S> s_st[G::NP][2];
+
+    const int w = threadIdx.x >> 6;
+    const TileSchedule sc(total_tiles);
+
+    if (w < G::NP) {
+        Producer<S, CSR> P;
+        P.init(rows, pos, nbr, off, src, N, K, s_st[w], w);
+        producer_loop<S, CSR>(P, sc, tiles_per_cloud, s_A, [](int, const TileRef &, int) {});
+        return;
+    }
+
+    // ---- consumer ----
+    constexpr int KS = S::KD / 16;
+    constexpr int NCH = (G::IPW == 1) ? 2 : 1;
+    const int cw = w - G::NP;
+    const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
+    // item = (slice, block); consumer cw owns items cw, cw+NC, ... ; all share one slice
+    constexpr int NSL = (G::NS < G::NC) ? G::NS : G::NC;
+    static_assert(G::NS <= G::NC || G::IPW * G::NC == G::NITEMS, "slices");
+    const int slice = cw % G::NS;
+    static_assert(G::NS <= G::NC, "one parameter slice per consumer wave");
+    (void)NSL;
+
+    float th[S::KD / 4];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            th[4 * s + i] = thetaP[(int64_t)(16 * s + 4 * q + i) * S::DOP + slice * 16 + r16];
+
+    for (int k = 0;; ++k) {
+        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+        if (!r.valid) break;
+        __syncthreads();                  // tile k is complete in s_A[k&1]
+        const float *sA = s_A[k & 1];
+        const int npts = min(G::T, N - r.l0);
+
+        v4f acc[G::IPW][NCH];
+#pragma unroll
+        for (int it = 0; it < G::IPW; ++it)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            v4f bf[G::IPW];
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it) {
+                const int idx = cw + it * G::NC;
+                const int blk = idx / G::NS;
+                bf[it] = v4f{0.f, 0.f, 0.f, 0.f};
+                if (idx < G::NITEMS)
+                    bf[it] = *reinterpret_cast<const v4f *>(&sA[(blk * 16 + r16) * G::AST + 16 * s + 4 * q]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int it = 0; it < G::IPW; ++it)
+                    acc[it][s % NCH] = __builtin_amdgcn_mfma_f32_16x16x4f32(th[4 * s + i], bf[it][i],
+                                                                            acc[it][s % NCH], 0, 0, 0);
+        }
+#pragma unroll
+        for (int it = 0; it < G::IPW; ++it) {
+            const int idx = cw + it * G::NC;
+            if (idx >= G::NITEMS) continue;
+            const int blk = idx / G::NS;
+            v4f d = acc[it][0];
+            if constexpr (NCH == 2) d += acc[it][1];
+            const int pt = blk * 16 + r16;
+            const int o = slice * 16 + 4 * q;
+            if (pt < npts) {
+                if constexpr (OUT_BCN) {
+                    float *dst = out + ((int64_t)r.b * S::DO + o) * N + (r.l0 + pt);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
+                } else {
+                    float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * S::DO + o;
+                    if constexpr (S::DO % 4 == 0) {
+                        if (o < S::DO) *reinterpret_cast<v4f *>(dst) = d;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (o + i < S::DO) dst[i] = d[i];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-workgroup partial of  gradTheta[kd][o] = sum_l A[l][kd] * g[l][o]
+// ---------------------------------------------------------------------------
+template <class S>
+__global__ __launch_bounds__(WsGeom<S>::NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                          const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
+                          float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles)
+{
+    using G = WsGeom<S>;
+    constexpr int GST = S::DOP + 16;
+    __shared__ __attribute__((aligned(16))) float s_A[2][G::T * G::AST];
+    __shared__ __attribute__((aligned(16))) float s_G[2][G::T * GST];
+    __shared__ WsStage<S> s_st[G::NP][2];
+
+    const int w = threadIdx.x >> 6;
+    const TileSchedule sc(total_tiles);
+
+    if (w < G::NP) {
+        // producers also move the grad_out tile: T*DOP floats over their 64*NP threads
+        constexpr int PT = 64 * G::NP;
+        constexpr int GPT = cdiv_c(G::T * S::DOP, PT);
+        float gv[GPT];
+        const int ptid = threadIdx.x;     // 0..64*NP-1
+        Producer<S, false> P;
+        P.init(rows, pos, nbr, nullptr, nullptr, N, K, s_st[w], w);
+        producer_loop<S, false>(P, sc, tiles_per_cloud, s_A, [&](int k, const TileRef &r, int phase) {
+            if (phase == 0) {
+#pragma unroll
+                for (int i = 0; i < GPT; ++i) {
+                    const int idx = ptid + i * PT;
+                    const int j = idx / S::DOP, o = idx % S::DOP;
+                    gv[i] = 0.f;
+                    if (r.valid && idx < G::T * S::DOP && r.l0 + j < N && o < S::DO)
+                        gv[i] = g_rows[((int64_t)r.b * N + r.l0 + j) * S::DO + o];
+                }
+            } else {
+                float *sG = s_G[k & 1];
+#pragma unroll
+                for (int i = 0; i < GPT; ++i) {
+                    const int idx = ptid + i * PT;
+                    if (idx < G::T * S::DOP) sG[(idx / S::DOP) * GST + (idx % S::DOP)] = gv[i];
+                }
+            }
+        });
+        return;
+    }
+
+    // ---- consumer: owns MBW x NBW 16x16 blocks of the (KD x DOP) partial ----
+    constexpr int MB = S::KD / 16, NB2 = S::DOP / 16;
+    constexpr int WN = (NB2 < G::NC) ? NB2 : G::NC;
+    static_assert(G::NC % WN == 0 && NB2 % WN == 0, "wave grid");
+    constexpr int WM = G::NC / WN;
+    constexpr int NBW = NB2 / WN;
+    constexpr int MBW = cdiv_c(MB, WM);
+    const int cw = w - G::NP;
+    const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
+    const int wn = cw % WN, wm = cw / WN;
+
+    v4f acc[MBW][NBW];
+#pragma unroll
+    for (int c = 0; c < MBW; ++c)
+#pragma unroll
+        for (int a = 0; a < NBW; ++a) acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    for (int k = 0;; ++k) {
+        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+        if (!r.valid) break;
+        __syncthreads();
+        const float *sA = s_A[k & 1], *sG = s_G[k & 1];
+#pragma unroll
+        for (int s = 0; s < G::T / 4; ++s) {
+            const int row = 4 * s + q;
+            float af[MBW], gf[NBW];
+#pragma unroll
+            for (int c = 0; c < MBW; ++c) {
+                const int mb = wm + c * WM;
+                af[c] = (mb < MB) ? sA[row * G::AST + mb * 16 + r16] : 0.f;
+            }
+#pragma unroll
+            for (int a = 0; a < NBW; ++a) gf[a] = sG[row * GST + (wn + a * WN) * 16 + r16];
+#pragma unroll
+            for (int c = 0; c < MBW; ++c)
+#pragma unroll
+                for (int a = 0; a < NBW; ++a)
+                    acc[c][a] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[c], gf[a], acc[c][a], 0, 0, 0);
+        }
+    }
+
+    float *dst = partials + (int64_t)blockIdx.x * S::KD * S::DOP;
+#pragma unroll
+    for (int c = 0; c < MBW; ++c) {
+        const int mb = wm + c * WM;
+        if (mb >= MB) continue;
+#pragma unroll
+        for (int a = 0; a < NBW; ++a) {
+            const int nb = wn + a * WN;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                dst[(int64_t)(mb * 16 + 4 * q + i) * S::DOP + nb * 16 + r16] = acc[c][a][i];
+        }
+    }
+}
+
+}  // namespace flex
