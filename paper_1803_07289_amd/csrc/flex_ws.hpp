@@ -402,7 +402,6 @@ void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__re
 
     // ---- consumer ----
     constexpr int KS = S::KD / 16;
-    constexpr int NCH = (G::IPW == 1) ? 2 : 1;
     const int cw = w - G::NP;
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
     // item = (slice, block); consumer cw owns items cw, cw+NC, ... ; all share one slice
@@ -419,43 +418,52 @@ void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__re
         for (int i = 0; i < 4; ++i)
             th[4 * s + i] = thetaP[(int64_t)(16 * s + 4 * q + i) * S::DOP + slice * 16 + r16];
 
+    // consumers beyond the item count only keep the barriers company
+    const bool active = cw < G::NITEMS;
+    int a_off[G::IPW];                    // LDS float offset of this lane's 16-byte fragment, depth step 0
+#pragma unroll
+    for (int it = 0; it < G::IPW; ++it) {
+        const int idx = active ? cw + it * G::NC : 0;
+        a_off[it] = ((idx / G::NS) * 16 + r16) * G::AST + 4 * q;
+    }
+
     for (int k = 0;; ++k) {
         const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
         if (!r.valid) break;
         __syncthreads();                  // tile k is complete in s_A[k&1]
+        if (!active) continue;
         const float *sA = s_A[k & 1];
         const int npts = min(G::T, N - r.l0);
 
-        v4f acc[G::IPW][NCH];
+        // four independent accumulation chains per item (one per depth lane i), fragments one step ahead
+        v4f acc[G::IPW][4];
+        v4f bf[G::IPW];
 #pragma unroll
-        for (int it = 0; it < G::IPW; ++it)
+        for (int it = 0; it < G::IPW; ++it) {
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < 4; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
+            bf[it] = *reinterpret_cast<const v4f *>(&sA[a_off[it]]);
+        }
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            v4f bf[G::IPW];
+            v4f nx[G::IPW];
 #pragma unroll
-            for (int it = 0; it < G::IPW; ++it) {
-                const int idx = cw + it * G::NC;
-                const int blk = idx / G::NS;
-                bf[it] = v4f{0.f, 0.f, 0.f, 0.f};
-                if (idx < G::NITEMS)
-                    bf[it] = *reinterpret_cast<const v4f *>(&sA[(blk * 16 + r16) * G::AST + 16 * s + 4 * q]);
-            }
+            for (int it = 0; it < G::IPW; ++it)
+                nx[it] = (s + 1 < KS) ? *reinterpret_cast<const v4f *>(&sA[a_off[it] + 16 * (s + 1)]) : bf[it];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int it = 0; it < G::IPW; ++it)
-                    acc[it][s % NCH] = __builtin_amdgcn_mfma_f32_16x16x4f32(th[4 * s + i], bf[it][i],
-                                                                            acc[it][s % NCH], 0, 0, 0);
+                    acc[it][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(th[4 * s + i], bf[it][i], acc[it][i], 0, 0, 0);
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it) bf[it] = nx[it];
         }
 #pragma unroll
         for (int it = 0; it < G::IPW; ++it) {
             const int idx = cw + it * G::NC;
             if (idx >= G::NITEMS) continue;
             const int blk = idx / G::NS;
-            v4f d = acc[it][0];
-            if constexpr (NCH == 2) d += acc[it][1];
+            const v4f d = (acc[it][0] + acc[it][1]) + (acc[it][2] + acc[it][3]);
             const int pt = blk * 16 + r16;
             const int o = slice * 16 + 4 * q;
             if (pt < npts) {
