@@ -64,7 +64,7 @@ def count_bad_neighbors(nbr, N) -> int:
 
 
 def flexconv_fwd(feat, pos, nbr, theta, bias, l_range=None):
-    """Returns float64 out [B,Dout,N] (columns outside l_range are zero)."""
+    """Returns float64 out [B,Dout,L]: all N columns, or columns l_range=(l0,l1) only."""
     feat, pos, theta, bias, nbr = _f32(feat), _f32(pos), _f32(theta), _f32(bias), _i32(nbr)
     B, Din, N = feat.shape
     K = nbr.shape[1]
@@ -73,7 +73,7 @@ def flexconv_fwd(feat, pos, nbr, theta, bias, l_range=None):
     assert theta.shape == (3, Din, Dout) and bias.shape == (Din, Dout)
     assert count_bad_neighbors(nbr, N) == 0
     l0, l1 = (0, N) if l_range is None else l_range
-    out = np.zeros((B, Dout, N), np.float64)
+    out = np.zeros((B, Dout, l1 - l0), np.float64)
     _check(_load().oracle_flexconv_fwd(_p(feat), _p(pos), _p(nbr), _p(theta), _p(bias), _p(out),
                                        B, N, K, Din, Dout, int(l0), int(l1)), "oracle_flexconv_fwd")
     return out
@@ -114,14 +114,14 @@ def flexconv_grad_feat_at(pos, nbr, theta, bias, grad_out, targets):
 
 
 def flexpool_fwd(feat, nbr, l_range=None):
-    """Returns (out float32 [B,C,N], argmax int32 [B,C,N])."""
+    """Returns (out float32, argmax int32), both [B,C,L]: all N columns or l_range only."""
     feat, nbr = _f32(feat), _i32(nbr)
     B, C, N = feat.shape
     K = nbr.shape[1]
     assert count_bad_neighbors(nbr, N) == 0
     l0, l1 = (0, N) if l_range is None else l_range
-    out = np.zeros((B, C, N), np.float32)
-    arg = np.zeros((B, C, N), np.int32)
+    out = np.zeros((B, C, l1 - l0), np.float32)
+    arg = np.zeros((B, C, l1 - l0), np.int32)
     _check(_load().oracle_flexpool_fwd(_p(feat), _p(nbr), _p(out), _p(arg), B, N, K, C, int(l0), int(l1)),
            "oracle_flexpool_fwd")
     return out, arg
@@ -132,8 +132,9 @@ def flexpool_bwd(grad_out, argmax, l_range=None):
     grad_out, argmax = _f32(grad_out), _i32(argmax)
     B, C, N = grad_out.shape
     assert argmax.shape == (B, C, N)
-    assert argmax.min() >= 0 and argmax.max() < N
     l0, l1 = (0, N) if l_range is None else l_range
+    if l1 > l0:
+        assert argmax[:, :, l0:l1].min() >= 0 and argmax[:, :, l0:l1].max() < N
     gf = np.zeros((B, C, N), np.float64)
     _check(_load().oracle_flexpool_bwd(_p(grad_out), _p(argmax), _p(gf), B, N, C, int(l0), int(l1)),
            "oracle_flexpool_bwd")

@@ -43,7 +43,11 @@
  *
  * Every routine takes a range [l_begin, l_end) of CENTRE points to process;
  * the full result uses [0, N).  Ranged calls exist so a bounded share of a
- * large workload can be timed; each centre's work is independent.
+ * large workload can be timed or checked; each centre's work is independent.
+ * Per-centre outputs (flex-conv out, pool out / argmax) are compact: their last
+ * axis has L = l_end - l_begin columns, column l - l_begin.  Scattered outputs
+ * (grad_feat of either layer) keep N columns and are ACCUMULATED into, so the
+ * caller passes them zero-filled (the Python wrapper does).
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (brute force via dense weight tensors, regular-grid reduction to ordinary
@@ -82,7 +86,7 @@ int64_t oracle_count_bad_neighbors(const int32_t *nbr, int B, int N, int K)
  * Flex-conv forward, Eq.(4) with Eq.(6):
  *   out[b,o,l] = sum_k sum_c ( <theta[:,c,o], pos[b,:,n] - pos[b,:,l]> + bias[c,o] ) * feat[b,c,n],
  *   n = nbr[b,k,l].
- * out is double [B,Dout,N]; only columns l in [l_begin,l_end) are written.
+ * out is double [B,Dout,L], L = l_end - l_begin.
  * ------------------------------------------------------------------------- */
 int oracle_flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
                         const float *theta, const float *bias, double *out,
@@ -115,7 +119,7 @@ int oracle_flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
                         }
                     }
                 }
-                for (int o = 0; o < Dout; ++o) out[IDX3(b, o, l, Dout, N)] = acc[o];
+                for (int o = 0; o < Dout; ++o) out[IDX3(b, o, l - l_begin, Dout, l_end - l_begin)] = acc[o];
             }
         free(acc);
     }
@@ -127,8 +131,9 @@ int oracle_flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
  *   grad_feat [b,c,m] = sum over all (l,k) with nbr[b,k,l] = m of  sum_o w(b,l,k,c,o) * g[b,o,l]
  *   grad_theta[d,c,o] = sum_b sum_l sum_k (pos[b,d,n]-pos[b,d,l]) * feat[b,c,n] * g[b,o,l]
  *   grad_bias [c,o]   = sum_b sum_l sum_k                          feat[b,c,n] * g[b,o,l]
- * Any of the three outputs may be NULL (skipped).  Outputs are double and are
- * overwritten.  Only centres l in [l_begin,l_end) contribute.
+ * Any of the three outputs may be NULL (skipped).  Outputs are double.
+ * grad_theta / grad_bias are overwritten; grad_feat [B,Din,N] is accumulated
+ * into (pass it zero-filled).  Only centres l in [l_begin,l_end) contribute.
  * ------------------------------------------------------------------------- */
 int oracle_flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
                         const float *theta, const float *bias, const float *grad_out,
@@ -140,7 +145,6 @@ int oracle_flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
     if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
     const int64_t n_theta = (int64_t)3 * Din * Dout, n_bias = (int64_t)Din * Dout;
     const int want_params = (grad_theta != NULL) || (grad_bias != NULL);
-    if (grad_feat) memset(grad_feat, 0, sizeof(double) * (size_t)B * Din * N);
     if (grad_theta) memset(grad_theta, 0, sizeof(double) * (size_t)n_theta);
     if (grad_bias) memset(grad_bias, 0, sizeof(double) * (size_t)n_bias);
 #pragma omp parallel
@@ -251,7 +255,7 @@ int oracle_flexconv_grad_feat_at(const float *pos, const int32_t *nbr,
 /* ---------------------------------------------------------------------------
  * Flex-max-pool forward (Sec. 4.1): out[b,c,l] = max_k feat[b,c,nbr[b,k,l]],
  * argmax[b,c,l] = index of the winning point (lowest point index on ties).
- * out is float (a bit copy of the winning input).
+ * out is float (a bit copy of the winning input); out / argmax are [B,C,L].
  * ------------------------------------------------------------------------- */
 int oracle_flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *argmax,
                         int B, int N, int K, int C, int l_begin, int l_end)
@@ -270,16 +274,17 @@ int oracle_flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32
                     const float v = feat[IDX3(b, c, n, C, N)];
                     if (v > bv || (v == bv && n < best)) { bv = v; best = n; }
                 }
-                out[IDX3(b, c, l, C, N)] = bv;
-                argmax[IDX3(b, c, l, C, N)] = best;
+                out[IDX3(b, c, l - l_begin, C, l_end - l_begin)] = bv;
+                argmax[IDX3(b, c, l - l_begin, C, l_end - l_begin)] = best;
             }
     return 0;
 }
 
 /* ---------------------------------------------------------------------------
  * Flex-max-pool backward: grad_feat[b,c,m] = sum of grad_out[b,c,l] over the
- * centres l (in [l_begin,l_end)) whose recorded winner is m; zero elsewhere.
- * grad_feat is double [B,C,N], overwritten.
+ * centres l (in [l_begin,l_end)) whose recorded winner is m.  grad_out and
+ * argmax are full [B,C,N] tensors; grad_feat is double [B,C,N], accumulated
+ * into (pass it zero-filled).
  * ------------------------------------------------------------------------- */
 int oracle_flexpool_bwd(const float *grad_out, const int32_t *argmax, double *grad_feat,
                         int B, int N, int C, int l_begin, int l_end)
@@ -287,7 +292,6 @@ int oracle_flexpool_bwd(const float *grad_out, const int32_t *argmax, double *gr
     if (!grad_out || !argmax || !grad_feat) return 1;
     if (B <= 0 || N <= 0 || C <= 0) return 2;
     if (l_begin < 0 || l_end > N || l_begin > l_end) return 2;
-    memset(grad_feat, 0, sizeof(double) * (size_t)B * C * N);
     /* one (b,c) row per iteration: rows are independent, so no atomics */
 #pragma omp parallel for collapse(2) schedule(static)
     for (int b = 0; b < B; ++b)

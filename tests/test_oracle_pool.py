@@ -111,3 +111,17 @@ def test_pool_bwd_is_adjoint_of_selection():
     lhs = (out.astype(np.float64) * g.astype(np.float64)).sum()
     rhs = (gf * feat.astype(np.float64)).sum()
     assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+
+
+def test_pool_range_arguments():
+    rng = np.random.default_rng(6)
+    B, C, N, K = 2, 3, 29, 4
+    feat = rng.standard_normal((B, C, N)).astype(np.float32)
+    nbr = rng.integers(0, N, size=(B, K, N)).astype(np.int32)
+    g = rng.standard_normal((B, C, N)).astype(np.float32)
+    out, arg = oracle.flexpool_fwd(feat, nbr)
+    po, pa = oracle.flexpool_fwd(feat, nbr, l_range=(7, 19))
+    assert np.array_equal(po, out[:, :, 7:19]) and np.array_equal(pa, arg[:, :, 7:19])
+    full = oracle.flexpool_bwd(g, arg)
+    parts = oracle.flexpool_bwd(g, arg, l_range=(0, 7)) + oracle.flexpool_bwd(g, arg, l_range=(7, N))
+    np.testing.assert_allclose(parts, full, rtol=1e-13, atol=1e-13)
