@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--order", default="morton", choices=["morton", "generator", "shuffled"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None, help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device copies of the feature tensor (known size) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against them")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no multi-GPU path exists); use --gpus 1")
@@ -102,8 +105,15 @@ def main():
             state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
         mark(3)
         if "pool_bwd" in ops:
-            state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout)
+            state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
         mark(4)
+
+    if args.calibrate_copy:
+        scratch = torch.empty_like(feat)
+        for _ in range(3):
+            scratch.copy_(feat)          # reads and writes feat.numel()*4 bytes, contiguous
+        torch.cuda.synchronize()
+        del scratch
 
     for _ in range(args.warmup):
         step()

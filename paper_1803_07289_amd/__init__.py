@@ -28,7 +28,7 @@ _SIGS = {
     "flexconv_bwd": (_i, [_vp] * 11 + [_i] * 6 + [_vp, _sz, _vp]),
     "flex_inedges_build": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
-    "flexpool_bwd": (_i, [_vp] * 3 + [_i] * 4 + [_vp]),
+    "flexpool_bwd": (_i, [_vp] * 5 + [_i] * 5 + [_vp]),
     "flexconv_workspace_bytes": (_sz, [_i] * 7),
     "flex_validate_neighbors": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "flexconv_has_fast_path": (_i, [_i, _i]),
@@ -196,17 +196,28 @@ def flexpool_fwd(feat, nbr, layout=BCN):
     return out, arg
 
 
-def flexpool_bwd(grad_out, argmax, layout=BCN):
-    """Flex-max-pooling backward (routing by the recorded winners).  Returns grad_feat."""
+def flexpool_bwd(grad_out, argmax, layout=BCN, in_edges=None, K=None):
+    """Flex-max-pooling backward (routing by the recorded winners).  Returns grad_feat.
+    in_edges = (in_off, in_src) of the forward pass's nbr selects the atomic-free gather form."""
     layout = _layout(layout)
     _dev(grad_out, torch.float32, "grad_out"); _dev(argmax, torch.int32, "argmax")
     if grad_out.dim() != 3 or grad_out.shape != argmax.shape:
         raise ValueError("grad_out and argmax must be 3-D and equal in shape")
     B = grad_out.shape[0]
     C, N = (grad_out.shape[1], grad_out.shape[2]) if layout == BCN else (grad_out.shape[2], grad_out.shape[1])
+    off = src = None
+    k = 1
+    if in_edges is not None:
+        off, src = in_edges
+        _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src")
+        if off.numel() != B * N + 1 or src.numel() % (B * N) != 0:
+            raise ValueError("in_edges do not match the tensors")
+        k = src.numel() // (B * N)
+        if K is not None and K != k:
+            raise ValueError("in_edges were built for a different K")
     gf = torch.empty_like(grad_out)
-    _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), B, N, C, layout, _stream()),
-           "flexpool_bwd")
+    _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), _ptr(off), _ptr(src), B, N, k, C, layout,
+                              _stream()), "flexpool_bwd")
     return gf
 
 

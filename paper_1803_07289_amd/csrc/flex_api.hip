@@ -285,14 +285,20 @@ int flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *arg
     return FLEX_OK;
 }
 
-int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B, int N, int C,
-                 int layout, void *stream)
+int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
+                 const int32_t *in_off, const int32_t *in_src, int B, int N, int K, int C, int layout,
+                 void *stream)
 {
     if (!grad_out || !argmax || !grad_feat) return FLEX_ERR_NULL;
-    if (!sizes_ok(B, N, 1, C, 1)) return FLEX_ERR_SHAPE;
+    if ((in_off == nullptr) != (in_src == nullptr)) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, in_off ? K : 1, C, 1)) return FLEX_ERR_SHAPE;
     if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
-    FLEX_HIP(launch_pool_bwd(grad_out, argmax, grad_feat, B, N, C, layout == FLEX_LAYOUT_BNC,
-                             (hipStream_t)stream));
+    if (in_off)
+        FLEX_HIP(launch_pool_bwd_gather(grad_out, argmax, in_off, in_src, grad_feat, B, N, C,
+                                        layout == FLEX_LAYOUT_BNC, (hipStream_t)stream));
+    else
+        FLEX_HIP(launch_pool_bwd(grad_out, argmax, grad_feat, B, N, C, layout == FLEX_LAYOUT_BNC,
+                                 (hipStream_t)stream));
     return FLEX_OK;
 }
 

@@ -71,6 +71,9 @@ hipError_t launch_pool_fwd(const float *feat, const int32_t *nbr, float *out, in
                            int B, int N, int K, int C, int bnc, hipStream_t s);
 hipError_t launch_pool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
                            int B, int N, int C, int bnc, hipStream_t s);
+hipError_t launch_pool_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
+                                  const int32_t *in_src, float *grad_feat, int B, int N, int C, int bnc,
+                                  hipStream_t s);
 
 hipError_t launch_count_bad(const int32_t *nbr, int64_t count, int N, int32_t *bad, hipStream_t s);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);

@@ -1,7 +1,8 @@
 // Transposed neighbour graph: for every point, the list of centres that name
 // it as a neighbour (CSR: in_off / in_src).  Counting sort by target point:
 // count -> exclusive scan -> fill -> sort each list ascending so that the
-// result does not depend on the order in which the fill's atomics landed.
+// result does not depend on the order in which the fill's atomics landed (and
+// so that repeated sources sit next to each other).
 #include "flex_common.hpp"
 
 namespace flex {
@@ -9,7 +10,6 @@ namespace flex {
 static constexpr int SCAN_ITEMS = 8;                    // per thread
 static constexpr int SCAN_CHUNK = 256 * SCAN_ITEMS;     // per block
 static constexpr int SORT_LOCAL = 32;                   // lists up to here sort in registers
-static constexpr int SORT_MAX = 1024;                   // longer lists keep fill order
 
 __global__ __launch_bounds__(256) void inedge_count_kernel(const int32_t *__restrict__ nbr,
                                                            int32_t *__restrict__ cnt, int64_t E,
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void inedge_sort_kernel(const int32_t *__restr
     for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < BN;
          g += (int64_t)gridDim.x * blockDim.x) {
         const int beg = off[g], d = off[g + 1] - beg;
-        if (d < 2 || d > SORT_MAX) continue;
+        if (d < 2) continue;
         int32_t *p = src + beg;
         if (d <= SORT_LOCAL) {
             int v[SORT_LOCAL];
@@ -139,12 +139,31 @@ __global__ __launch_bounds__(256) void inedge_sort_kernel(const int32_t *__restr
 #pragma unroll
             for (int i = 0; i < SORT_LOCAL; ++i)
                 if (i < d) p[i] = v[i];
-        } else {
+        } else if (d <= 256) {
             for (int i = 1; i < d; ++i) {                 // rare: insertion sort in place
                 const int x = p[i];
                 int j = i - 1;
                 while (j >= 0 && p[j] > x) { p[j + 1] = p[j]; --j; }
                 p[j + 1] = x;
+            }
+        } else {
+            // very rare (a point named by hundreds of centres): heapsort in place, O(d log d)
+            auto sift = [&](int root, int end) {
+                const int x = p[root];
+                for (;;) {
+                    int child = 2 * root + 1;
+                    if (child >= end) break;
+                    if (child + 1 < end && p[child + 1] > p[child]) ++child;
+                    if (p[child] <= x) break;
+                    p[root] = p[child];
+                    root = child;
+                }
+                p[root] = x;
+            };
+            for (int i = d / 2 - 1; i >= 0; --i) sift(i, d);
+            for (int end = d - 1; end > 0; --end) {
+                const int x = p[end]; p[end] = p[0]; p[0] = x;
+                sift(0, end);
             }
         }
     }

@@ -12,18 +12,31 @@ __device__ __forceinline__ void take(float v, int n, float &bv, int &bn)
     if (v > bv || (v == bv && n < bn)) { bv = v; bn = n; }
 }
 
-// Point-major, C % 4 == 0: one thread per (point, 4 channels).
+// Blocks are dealt to the 8 XCDs round-robin by block id; giving each XCD one
+// contiguous eighth of the point tiles keeps a neighbourhood's rows in one L2.
+__device__ __forceinline__ int64_t xcd_tile(int64_t total_tiles)
+{
+    const int64_t per_xcd = (total_tiles + 7) >> 3;
+    const int64_t slot = blockIdx.x >> 3;
+    const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + slot;
+    return (slot < per_xcd && tile < total_tiles) ? tile : -1;
+}
+static inline unsigned xcd_grid(int64_t total_tiles) { return (unsigned)(((total_tiles + 7) >> 3) << 3); }
+
+// Point-major, C % 4 == 0: one thread per (point, 4 channels); a block owns PT consecutive points.
 __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restrict__ feat,
                                                             const int32_t *__restrict__ nbr,
                                                             float *__restrict__ out,
-                                                            int32_t *__restrict__ argmax, int B,
-                                                            int N, int K, int C4)
+                                                            int32_t *__restrict__ argmax, int64_t BN,
+                                                            int N, int K, int C4, int PT,
+                                                            int64_t total_tiles)
 {
-    const int64_t total = (int64_t)B * N * C4;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const int c4 = (int)(i % C4);
-        const int64_t gp = i / C4;
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    for (int i = threadIdx.x; i < PT * C4; i += 256) {
+        const int c4 = i % C4;
+        const int64_t gp = tile * PT + i / C4;
+        if (gp >= BN) break;
         const int b = (int)(gp / N), l = (int)(gp % N);
         const int32_t *nb = nbr + (int64_t)b * K * N + l;
         const v4f *rows = reinterpret_cast<const v4f *>(feat) + (int64_t)b * N * C4 + c4;
@@ -40,8 +53,8 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
             take(v.w, n, v3, b3);
         }
         const v4f bv = {v0, v1, v2, v3};
-        reinterpret_cast<v4f *>(out)[i] = bv;
-        reinterpret_cast<int4 *>(argmax)[i] = make_int4(b0, b1, b2, b3);
+        reinterpret_cast<v4f *>(out)[gp * C4 + c4] = bv;
+        reinterpret_cast<int4 *>(argmax)[gp * C4 + c4] = make_int4(b0, b1, b2, b3);
     }
 }
 
@@ -75,11 +88,11 @@ hipError_t launch_pool_fwd(const float *feat, const int32_t *nbr, float *out, in
                            int B, int N, int K, int C, int bnc, hipStream_t s)
 {
     if (bnc && (C % 4 == 0)) {
-        const int64_t total = (int64_t)B * N * (C / 4);
-        int64_t blocks = (total + 255) / 256;
-        if (blocks > (1 << 20)) blocks = 1 << 20;
-        hipLaunchKernelGGL(pool_fwd_bnc4_kernel, dim3((unsigned)blocks), dim3(256), 0, s, feat, nbr,
-                           out, argmax, B, N, K, C / 4);
+        const int C4 = C / 4;
+        const int PT = C4 >= 256 ? 1 : 256 / C4;
+        const int64_t BN = (int64_t)B * N, tiles = (BN + PT - 1) / PT;
+        hipLaunchKernelGGL(pool_fwd_bnc4_kernel, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr,
+                           out, argmax, BN, N, K, C4, PT, tiles);
     } else {
         const int64_t total = (int64_t)B * N * C;
         int64_t blocks = (total + 255) / 256;
@@ -105,6 +118,88 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const float *__restrict__
         else     { const int64_t bc = i / N; dst = bc * N + m; }
         atomicAdd(&grad_feat[dst], grad_out[i]);
     }
+}
+
+// Gather form of the backward pass over in-edge lists (sorted, so repeats are adjacent; no
+// atomics, fixed summation order):
+// grad_feat[m][c] = sum over centres l that list m of (argmax[l][c] == m ? grad_out[l][c] : 0).
+__global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
+    const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
+    float *__restrict__ grad_feat, int64_t BN, int N, int C4, int PT, int64_t total_tiles)
+{
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    for (int i = threadIdx.x; i < PT * C4; i += 256) {
+        const int c4 = i % C4;
+        const int64_t gp = tile * PT + i / C4;
+        if (gp >= BN) break;
+        const int64_t b = gp / N;
+        const int m = (int)(gp - b * N);
+        const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + b * N * C4 + c4;
+        const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + b * N * C4 + c4;
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        const int e1 = in_off[gp + 1];
+        int prev = -1;
+        for (int e = in_off[gp]; e < e1; ++e) {
+            const int64_t l = in_src[e];
+            if ((int)l == prev) continue;     // a centre that lists m twice still routes one gradient
+            prev = (int)l;
+            const int4 a = a4[l * C4];
+            const v4f g = g4[l * C4];
+            acc.x += (a.x == m) ? g.x : 0.f;
+            acc.y += (a.y == m) ? g.y : 0.f;
+            acc.z += (a.z == m) ? g.z : 0.f;
+            acc.w += (a.w == m) ? g.w : 0.f;
+        }
+        reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4] = acc;
+    }
+}
+
+__global__ __launch_bounds__(256) void pool_bwd_gather_generic_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
+    const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
+    float *__restrict__ grad_feat, int B, int N, int C, int bnc)
+{
+    const int64_t total = (int64_t)B * N * C;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int64_t b; int c, m;
+        if (bnc) { c = (int)(i % C); const int64_t gp = i / C; b = gp / N; m = (int)(gp % N); }
+        else     { m = (int)(i % N); const int64_t bc = i / N; b = bc / C; c = (int)(bc % C); }
+        const int64_t gp = b * N + m;
+        float acc = 0.f;
+        const int e1 = in_off[gp + 1];
+        int prev = -1;
+        for (int e = in_off[gp]; e < e1; ++e) {
+            const int64_t l = in_src[e];
+            if ((int)l == prev) continue;
+            prev = (int)l;
+            const int64_t at = bnc ? (b * N + l) * C + c : (b * C + c) * N + l;
+            if (argmax[at] == m) acc += grad_out[at];
+        }
+        grad_feat[i] = acc;
+    }
+}
+
+hipError_t launch_pool_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
+                                  const int32_t *in_src, float *grad_feat, int B, int N, int C, int bnc,
+                                  hipStream_t s)
+{
+    if (bnc && (C % 4 == 0)) {
+        const int C4 = C / 4;
+        const int PT = C4 >= 256 ? 1 : 256 / C4;
+        const int64_t BN = (int64_t)B * N, tiles = (BN + PT - 1) / PT;
+        hipLaunchKernelGGL(pool_bwd_gather_bnc4_kernel, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+                           argmax, in_off, in_src, grad_feat, BN, N, C4, PT, tiles);
+    } else {
+        const int64_t total = (int64_t)B * N * C;
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > (1 << 20)) blocks = 1 << 20;
+        hipLaunchKernelGGL(pool_bwd_gather_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                           grad_out, argmax, in_off, in_src, grad_feat, B, N, C, bnc);
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_pool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B,

@@ -47,7 +47,8 @@ def test_null_and_shape_errors_precede_any_launch(L):
     # null pointers
     assert L.flexconv_fwd(none, one, one, one, one, one, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
     assert L.flexpool_fwd(one, none, one, one, 1, 8, 2, 4, 0, None) == 1
-    assert L.flexpool_bwd(one, one, none, 1, 8, 4, 0, None) == 1
+    assert L.flexpool_bwd(one, one, none, none, none, 1, 8, 1, 4, 0, None) == 1
+    assert L.flexpool_bwd(one, one, one, one, none, 1, 8, 1, 4, 0, None) == 1
     assert L.flexconv_bwd(one, one, one, one, one, none, one, one, one, none, none, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
     # grad_theta without grad_bias, in_off without in_src
     assert L.flexconv_bwd(one, one, one, one, one, one, one, one, none, none, none, 1, 8, 2, 4, 4, 0, one, 1 << 20, None) == 1
@@ -58,7 +59,7 @@ def test_null_and_shape_errors_precede_any_launch(L):
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 8, 2, 4, 4, 7, one, 1 << 20, None) == 2
     assert L.flexconv_fwd(one, one, one, one, one, one, 1 << 12, 1 << 20, 2, 4, 4, 0, one, 1 << 20, None) == 2
     assert L.flexpool_fwd(one, one, one, one, 1, 8, 2, 0, 0, None) == 2
-    assert L.flexpool_bwd(one, one, one, 1, 8, 4, 3, None) == 2
+    assert L.flexpool_bwd(one, one, one, none, none, 1, 8, 1, 4, 3, None) == 2
     # workspace: missing, misaligned, too small (tiled shape needs > 256 bytes)
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, none, 0, None) == 4
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, ctypes.c_void_p(260), 1 << 20, None) == 4

@@ -83,8 +83,11 @@ def test_full_size_config(ci):
         assert bool((po >= feat).all())
         del gathered
         gp = bnc(x.grad_out) if x.grad_out is not None and Din == Dout else torch.randn_like(feat)
-        pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC)
+        pool_edges = edges if "conv_bwd" in cfg.runs else fx.flex_inedges_build(nbr)
+        pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC, in_edges=pool_edges)     # the form bench.py times
+        pg_scatter = fx.flexpool_bwd(gp, pa, layout=fx.BNC)
         torch.cuda.synchronize()
+        assert float((pg - pg_scatter).abs().max()) <= 1e-4 * float(gp.abs().max()) * K
         # mass conservation per (cloud, channel) and exact rows on a sample
         m_got, m_ref = pg.double().sum(1).cpu().numpy(), gp.double().sum(1).cpu().numpy()
         assert np.abs(m_got - m_ref).max() <= 1e-6 * gp.double().abs().sum(1).max().item()
