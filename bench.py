@@ -89,8 +89,11 @@ def main():
 
     names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd") if n in ops]
     state = {}
+    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd")
 
     def step(events=None):
+        """One pass of the hot path.  flexconv_bwd is issued as two calls (parameter gradients,
+        then feature gradient: the same kernels as one call) so that each gets its own events."""
         def mark(i):
             if events is not None:
                 events[i].record()
@@ -99,14 +102,20 @@ def main():
             state["out"] = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=layout, out=state.get("out"))
         mark(1)
         if "bwd" in ops:
-            state["grads"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges)
+            _, gt, gb = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
+                                        need_feat=False)
         mark(2)
+        if "bwd" in ops:
+            gf, _, _ = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
+                                       need_params=False)
+            state["grads"] = (gf, gt, gb)
+        mark(3)
         if "pool_fwd" in ops or "pool_bwd" in ops:
             state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
-        mark(3)
+        mark(4)
         if "pool_bwd" in ops:
             state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
-        mark(4)
+        mark(5)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(feat)
@@ -118,7 +127,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -128,30 +137,56 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     op_ms = {}
-    for j, name in enumerate(("fwd", "bwd", "pool_fwd", "pool_bwd")):
+    for j, name in enumerate(OPS):
         ts = [ev[j].elapsed_time(ev[j + 1]) for ev in per_step_events]
         op_ms[name] = {"mean": float(np.mean(ts)), "min": float(np.min(ts)), "median": float(np.median(ts))}
     pts = B * N
 
-    # ---- roofline of the forward kernel (algorithmic, touched-once figures) ----
+    # ---- rooflines (algorithmic, touched-once figures) ----------
+    # conv kernels: factored flops, all on the matrix pipe (aggregate 8*K*Din + contraction 2*4Din*Dout)
+    conv_flop_pt = 8 * K * Din + 2 * 4 * Din * Dout
+    conv_bytes_pt = {"fwd": 4 * Din + 12 + 4 * K + 4 * Dout,
+                     "bwd_params": 4 * Din + 12 + 4 * K + 4 * Dout,
+                     "bwd_feat": 4 * Dout + 12 + 4 * (K + 1) + 4 * Din}
+    pool_bytes_pt = {"pool_fwd": 4 * Din + 4 * K + 8 * Din, "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din}
+    kernel_of = {"fwd": "gather_contract_ws_kernel<.., false, ..> (flexconv_fwd)",
+                 "bwd_params": "grad_theta_ws_kernel (flexconv_bwd, parameter gradients)",
+                 "bwd_feat": "gather_contract_ws_kernel<.., true, ..> (flexconv_bwd, feature gradient)",
+                 "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
+                 "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)"}
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
+    # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
+    measured_traffic = {"fwd": 4.636e9, "bwd_params": 5.482e9, "bwd_feat": 4.842e9,
+                        "pool_fwd": 5.758e9, "pool_bwd": 5.945e9}
+    default_workload = (cfg.index == 4 and N == 7_000_000 and layout == fx.BNC and x.order == "morton")
+
+    def roof(name):
+        ms = op_ms[name]["mean"]
+        if ms <= 0:
+            return None
+        traffic = measured_traffic.get(name) if default_workload else None
+        if name in conv_bytes_pt:
+            tfl = conv_flop_pt * pts / (ms * 1e-3) / 1e12
+            gbs = conv_bytes_pt[name] * pts / (ms * 1e-3) / 1e9
+            t_mfma = conv_flop_pt * pts / (MFMA_F32_PEAK_TFLOPS * 1e12)
+            t_hbm = conv_bytes_pt[name] * pts / (HBM_PEAK_GBS * 1e9)
+            if t_mfma >= t_hbm:
+                r = {"bound": "mfma", "achieved": tfl, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tfl / MFMA_F32_PEAK_TFLOPS}
+            else:
+                r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+            r["hbm_GBps_algorithmic"] = gbs
+        else:
+            gbs = pool_bytes_pt[name] * pts / (ms * 1e-3) / 1e9
+            r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+        r.update({"traffic": traffic, "kernel": kernel_of[name], "kernel_ms": ms})
+        return r
+
+    rooflines = {n: roof(n) for n in OPS if op_ms[n]["mean"] > 1e-2}
+    dominant = max(rooflines, key=lambda n: rooflines[n]["kernel_ms"]) if rooflines else None
+    roofline = rooflines.get(dominant)
     fwd_ms = op_ms["fwd"]["mean"]
-    fwd_bytes_pt = 4 * Din + 12 + 4 * K + 4 * Dout             # feat row + pos + idx + out row
-    fwd_mfma_flop_pt = 2 * 4 * Din * Dout                       # (4*Din x Dout) contraction
-    fwd_valu_flop_pt = 8 * K * Din                              # aggregate
-    mfma_tflops = fwd_mfma_flop_pt * pts / (fwd_ms * 1e-3) / 1e12 if fwd_ms > 0 else 0.0
-    hbm_gbs = fwd_bytes_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else 0.0
-    t_mfma = fwd_mfma_flop_pt * pts / (MFMA_F32_PEAK_TFLOPS * 1e12)
-    t_hbm = fwd_bytes_pt * pts / (HBM_PEAK_GBS * 1e9)
-    if t_mfma >= t_hbm:
-        roofline = {"bound": "mfma", "achieved": mfma_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": mfma_tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None}
-    else:
-        roofline = {"bound": "hbm", "achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": hbm_gbs / HBM_PEAK_GBS, "traffic": None}
-    roofline["kernel"] = "gather_contract_kernel (flexconv_fwd)"
-    roofline["kernel_ms"] = fwd_ms
-    roofline["hbm_GBps_algorithmic"] = hbm_gbs
-    roofline["mfma_TFLOPs_algorithmic"] = mfma_tflops
+    bwd_ms = op_ms["bwd_params"]["mean"] + op_ms["bwd_feat"]["mean"]
 
     # ---- sampled parity at this size, in this launch configuration -------------
     parity = None
@@ -210,12 +245,12 @@ def main():
                    "in_edges": "prebuilt once (static neighbourhoods)"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "rooflines_all": rooflines,
         "op_ms": op_ms,
         "inedges_build_ms": inedges_ms,
         "fwd_points_per_s": pts / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
         "fwd_effective_GFLOPs_direct_form": direct_flop_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else None,
-        "fwd_bwd_points_per_s": pts / ((fwd_ms + op_ms["bwd"]["mean"]) * 1e-3) if fwd_ms > 0 else None,
-        "fwd_valu_flop_per_point": fwd_valu_flop_pt,
+        "fwd_bwd_points_per_s": pts / ((fwd_ms + bwd_ms) * 1e-3) if fwd_ms > 0 and bwd_ms > 0 else None,
         "parity": parity,
     }
     print(json.dumps(result), flush=True)
