@@ -1,5 +1,6 @@
 // C-ABI entry points of libflexconv: validation, workspace carving, dispatch.
 #include "flex_common.hpp"
+#include <stdlib.h>
 #include "../../include/flexconv.h"
 
 namespace flex {
@@ -7,8 +8,9 @@ namespace flex {
 // ---- per-shape launchers generated from flex_shapes.def ------------------------
 #define FLEX_SHAPE(DI, DO, W, T, OCC, WS)                                                             \
     hipError_t launch_gc_##DI##_##DO(const float *, const float *, const int32_t *, const int32_t *, \
-                                     const int32_t *, const float *, float *, int, int, int, int,    \
-                                     int, hipStream_t);                                              \
+                                     const int32_t *, const void *, int, float *, int, int, int,     \
+                                     int, int, hipStream_t);                                         \
+    int theta_format_##DI##_##DO(int, int);                                                          \
     hipError_t launch_gt_##DI##_##DO(const float *, const float *, const int32_t *, const float *,   \
                                      float *, int, int, int, int *, hipStream_t);
 #include "flex_shapes.def"
@@ -27,16 +29,53 @@ bool gather_contract_supported(int DI, int DO)
 }
 
 hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
-                                  const int32_t *off, const int32_t *src, const float *thetaP,
-                                  float *out, int B, int N, int K, int DI, int DO, int csr,
-                                  int out_bcn, hipStream_t s)
+                                  const int32_t *off, const int32_t *src, const void *thetaP,
+                                  int theta_fmt, float *out, int B, int N, int K, int DI, int DO,
+                                  int csr, int out_bcn, hipStream_t s)
 {
 #define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_)         \
-        return launch_gc_##DI_##_##DO_(rows, pos, nbr, off, src, thetaP, out, B, N, K, csr, out_bcn, s);
+        return launch_gc_##DI_##_##DO_(rows, pos, nbr, off, src, thetaP, theta_fmt, out, B, N, K, csr, out_bcn, s);
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
     return hipErrorNotSupported;
+}
+
+int gather_contract_theta_format(int DI, int DO, int K, int csr)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
+    if (DI == DI_ && DO == DO_) return theta_format_##DI_##_##DO_(K, csr);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return 0;
+}
+
+bool contract_in_fp32()
+{
+    static const bool f32 = [] {
+        const char *v = getenv("FLEX_CONTRACT");
+        return v != nullptr && v[0] == 'f' && v[1] == '3' && v[2] == '2' && v[3] == 0;
+    }();
+    return f32;
+}
+
+// Packs (theta, bias) for launch_gather_contract in the format that kernel wants.
+static hipError_t pack_for_contract(const float *theta, const float *bias, void *thetaP, int Din,
+                                    int Dout, int transpose, int fmt, hipStream_t s)
+{
+    const int RP = transpose ? (Dout + 3) / 4 * 4 : (Din + 3) / 4 * 4;
+    const int CP = transpose ? (Din + 15) / 16 * 16 : (Dout + 15) / 16 * 16;
+    if (fmt) return launch_pack_theta_f16(theta, bias, thetaP, Din, Dout, RP, CP, transpose, s);
+    return launch_pack_theta(theta, bias, (float *)thetaP, Din, Dout, RP, CP, transpose, s);
+}
+
+// Workspace bytes of the packed parameters in either format (rows padded to 4, columns to 16).
+static size_t theta_ws_bytes(int rows, int cols)
+{
+    const int RP = (rows + 3) / 4 * 4, CP = (cols + 15) / 16 * 16;
+    const size_t f32 = align256(sizeof(float) * (size_t)4 * RP * CP);
+    const size_t f16 = theta_f16_bytes(RP, CP);
+    return f32 > f16 ? f32 : f16;
 }
 
 static int shape_tile_points(int DI, int DO)
@@ -101,7 +140,7 @@ static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout)
     p.tiled = gather_contract_supported(Din, Dout);
     size_t at = 0;
     if (p.tiled) {
-        p.thetaP = at; at += align256(sizeof(float) * (size_t)4 * pad4(Din) * pad16(Dout));
+        p.thetaP = at; at += theta_ws_bytes(Din, Dout);
         if (layout == FLEX_LAYOUT_BCN) { p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din); }
     }
     p.total = at > 0 ? at : 256;
@@ -114,7 +153,7 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
     p.tiled = gather_contract_supported(Din, Dout) && gather_contract_supported(Dout, Din);
     size_t at = 0;
     if (p.tiled) {
-        p.thetaP = at; at += align256(sizeof(float) * (size_t)4 * pad4(Dout) * pad16(Din));
+        p.thetaP = at; at += theta_ws_bytes(Dout, Din);
         if (layout == FLEX_LAYOUT_BCN) {
             p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din);
             p.gT = at;    at += align256(sizeof(float) * (size_t)(B * N) * Dout);
@@ -200,16 +239,17 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
         FLEX_HIP(launch_generic_fwd(feat, pos, nbr, theta, bias, out, B, N, K, Din, Dout, !bcn, s));
         return FLEX_OK;
     }
-    float *thetaP = (float *)(ws + p.thetaP);
-    FLEX_HIP(launch_pack_theta(theta, bias, thetaP, Din, Dout, pad4(Din), pad16(Dout), 0, s));
+    void *thetaP = ws + p.thetaP;
+    const int fmt = gather_contract_theta_format(Din, Dout, K, 0);
+    FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 0, fmt, s));
     const float *rows = feat;
     if (bcn) {
         float *featT = (float *)(ws + p.featT);
         FLEX_HIP(launch_bcn_to_bnc(feat, featT, B, Din, N, s));
         rows = featT;
     }
-    FLEX_HIP(launch_gather_contract(rows, pos, nbr, nullptr, nullptr, thetaP, out, B, N, K, Din, Dout,
-                                    0, bcn, s));
+    FLEX_HIP(launch_gather_contract(rows, pos, nbr, nullptr, nullptr, thetaP, fmt, out, B, N, K, Din,
+                                    Dout, 0, bcn, s));
     return FLEX_OK;
 }
 
@@ -266,10 +306,11 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
             in_off = off;
             in_src = src;
         }
-        float *thetaP = (float *)(ws + p.thetaP);
-        FLEX_HIP(launch_pack_theta(theta, bias, thetaP, Din, Dout, pad4(Dout), pad16(Din), 1, s));
-        FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, thetaP, grad_feat, B, N, K,
-                                        Dout, Din, 1, bcn, s));
+        void *thetaP = ws + p.thetaP;
+        const int fmt = gather_contract_theta_format(Dout, Din, K, 1);
+        FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 1, fmt, s));
+        FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, thetaP, fmt, grad_feat, B, N,
+                                        K, Dout, Din, 1, bcn, s));
     }
     return FLEX_OK;
 }

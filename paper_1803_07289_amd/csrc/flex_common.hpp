@@ -21,6 +21,8 @@ int device_cu_count();
 int persistent_grid(int64_t total_tiles, int wg_per_cu);
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
 // ---- launchers implemented in the .hip translation units -------------------
 
@@ -30,6 +32,14 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 hipError_t launch_pack_theta(const float *theta, const float *bias, float *thetaP,
                              int Din, int Dout, int RP, int CP, int transpose, hipStream_t s);
 
+// Split-half (f16 hi/lo) fragment form of the same matrix for the wave-specialised
+// kernels; layout documented at pack_theta_f16_kernel.  RP = padded rows per j, CP =
+// padded columns (multiple of 16).
+hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *thetaF, int Din,
+                                 int Dout, int RP, int CP, int transpose, hipStream_t s);
+size_t theta_f16_exp_offset(int RP, int CP);
+size_t theta_f16_bytes(int RP, int CP);
+
 // [B,C,N] -> [B,N,C] and back.
 hipError_t launch_bcn_to_bnc(const float *src, float *dst, int B, int C, int N, hipStream_t s);
 hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, hipStream_t s);
@@ -38,11 +48,18 @@ hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, 
 // hipErrorNotSupported when (DI,DO) has no instantiation.
 //   csr == 0: neighbours from nbr [B,K,N], dp = pos[nbr]-pos[centre]
 //   csr == 1: in-edge lists (off,src), dp = pos[centre]-pos[src]
+//   theta_fmt: what thetaP holds, as answered by gather_contract_theta_format for the same
+//   (DI, DO, K, csr): 0 = fp32 ThetaP (launch_pack_theta), 1 = split-half fragments
+//   (launch_pack_theta_f16).
 hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
-                                  const int32_t *off, const int32_t *src, const float *thetaP,
-                                  float *out, int B, int N, int K, int DI, int DO,
+                                  const int32_t *off, const int32_t *src, const void *thetaP,
+                                  int theta_fmt, float *out, int B, int N, int K, int DI, int DO,
                                   int csr, int out_bcn, hipStream_t s);
 bool gather_contract_supported(int DI, int DO);
+int gather_contract_theta_format(int DI, int DO, int K, int csr);
+// true when the environment asks for the fp32 matrix op in the wave-specialised kernels
+// (FLEX_CONTRACT=f32; read once).  For A/B measurements; both forms meet the same tolerance.
+bool contract_in_fp32();
 
 // grad_theta / grad_bias: per-workgroup partial sums into `partials`
 // ([n_wg, KD, DOP] floats), then a reduction into the two outputs.

@@ -54,6 +54,76 @@ hipError_t launch_pack_theta(const float *theta, const float *bias, float *theta
     return hipGetLastError();
 }
 
+// ---- theta packing for the split-half contraction ---------------------------------
+// The wave-specialised kernels contract on the f16 matrix cores with every fp32
+// operand x carried as two halves of x * 2^e:  hi = half(x 2^e), lo = half(x 2^e - hi),
+// and the three products hi*hi + hi*lo + lo*hi (error ~2^-22 per product, the level
+// of fp32 rounding).  For the parameters one exponent serves the whole matrix: it puts
+// the largest magnitude into [2^14, 2^15), so entries down to 2^-17 of it keep a
+// normal low half.
+// Buffer layout (halves), the operand fragments of v_mfma_f32_16x16x32_f16 in the order
+// a wave loads them:
+//   thetaF[(((part*NS + slice)*KS + step)*64 + lane)*8 + e]
+//       = part( ThetaP[32*step + 8*(lane>>4) + e][16*slice + (lane&15)] * 2^e_theta )
+// with NS = CP/16 slices, KS = KDP/32 depth steps, rows >= 4*RP and padding zero; the
+// int32 exponent e_theta follows at byte offset theta_f16_exp_offset(RP, CP).
+__global__ __launch_bounds__(1024) void pack_theta_f16_kernel(const float *__restrict__ theta,
+                                                              const float *__restrict__ bias,
+                                                              _Float16 *__restrict__ thetaF, int Din,
+                                                              int Dout, int RP, int CP, int transpose,
+                                                              int exp_offset_bytes)
+{
+    __shared__ float s_max[1024];
+    const int n_theta = 3 * Din * Dout, n_all = 4 * Din * Dout;
+    float m = 0.f;
+    for (int i = threadIdx.x; i < n_all; i += 1024)
+        m = fmaxf(m, fabsf(i < n_theta ? theta[i] : bias[i - n_theta]));
+    s_max[threadIdx.x] = m;
+    __syncthreads();
+    for (int d = 512; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + d]);
+        __syncthreads();
+    }
+    m = s_max[0];
+    int ex = 0;
+    if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ex); ex = 15 - ex; }
+    if (threadIdx.x == 0) *reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes) = ex;
+
+    const int KD = 4 * RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
+    const int per_part = NS * KS * 64 * 8;
+    for (int i = threadIdx.x; i < per_part; i += 1024) {
+        const int e = i & 7, lane = (i >> 3) & 63, step = (i >> 9) % KS, slice = (i >> 9) / KS;
+        const int kd = 32 * step + 8 * (lane >> 4) + e, col = 16 * slice + (lane & 15);
+        float v = 0.f;
+        if (kd < KD) {
+            const int j = kd / RP, r = kd % RP;
+            const int ci = transpose ? col : r, co = transpose ? r : col;
+            if (ci < Din && co < Dout)
+                v = (j < 3) ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co];
+        }
+        const float vs = ldexpf(v, ex);
+        const _Float16 hi = (_Float16)vs;
+        const _Float16 lo = (_Float16)(vs - (float)hi);
+        thetaF[i] = hi;
+        thetaF[per_part + i] = lo;
+    }
+}
+
+size_t theta_f16_exp_offset(int RP, int CP)
+{
+    const int KDP = (4 * RP + 31) / 32 * 32;
+    return align256(sizeof(_Float16) * (size_t)2 * CP * KDP);
+}
+size_t theta_f16_bytes(int RP, int CP) { return theta_f16_exp_offset(RP, CP) + 256; }
+
+hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *thetaF, int Din,
+                                 int Dout, int RP, int CP, int transpose, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_theta_f16_kernel, dim3(1), dim3(1024), 0, s, theta, bias,
+                       (_Float16 *)thetaF, Din, Dout, RP, CP, transpose, (int)theta_f16_exp_offset(RP, CP));
+    return hipGetLastError();
+}
+
 // ---- [B,R,C] -> [B,C,R] transposes (64x64 tiles through LDS) -----------------
 __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ src,
                                                         float *__restrict__ dst, int R, int C,

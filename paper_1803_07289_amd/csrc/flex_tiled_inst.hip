@@ -17,18 +17,29 @@ namespace flex {
 using S = TileShape<FLEX_DI, FLEX_DO, FLEX_W, FLEX_T, FLEX_OCC>;
 static constexpr int WG_PER_CU = (FLEX_OCC * 4) / FLEX_W > 0 ? (FLEX_OCC * 4) / FLEX_W : 1;
 
+// 1 if this (shape, K, list form) runs the wave-specialised kernel with the split-half
+// contraction, i.e. wants the parameters from launch_pack_theta_f16; 0: fp32 ThetaP.
+int FLEX_NAME(theta_format, FLEX_DI, FLEX_DO)(int K, int csr)
+{
+#if FLEX_WS
+    using W = WsGeom<S>;
+    if (!contract_in_fp32() && (csr || (int64_t)W::PW * K <= W::EW)) return 1;
+#endif
+    (void)K; (void)csr;
+    return 0;
+}
+
 hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float *pos,
                                                   const int32_t *nbr, const int32_t *off,
-                                                  const int32_t *src, const float *thetaP,
-                                                  float *out, int B, int N, int K, int csr,
-                                                  int out_bcn, hipStream_t s)
+                                                  const int32_t *src, const void *thetaP,
+                                                  int theta_fmt, float *out, int B, int N, int K,
+                                                  int csr, int out_bcn, hipStream_t s)
 {
     const int tiles_per_cloud = (N + S::T - 1) / S::T;
     const int64_t total64 = (int64_t)B * tiles_per_cloud;
     if (total64 > 0x7fffffff) return hipErrorInvalidValue;
     const int total = (int)total64;
     const int grid = persistent_grid(total, WG_PER_CU);
-#define FLEX_GC_ARGS rows, pos, nbr, off, src, thetaP, out, N, K, tiles_per_cloud, total
 #if FLEX_WS
     {
         using W = WsGeom<S>;
@@ -36,16 +47,26 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
             const int tpc = (N + W::T - 1) / W::T;
             const int tot = B * tpc;
             const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
-#define FLEX_WS_ARGS rows, pos, nbr, off, src, thetaP, out, N, K, tpc, tot
-            if (!csr && !out_bcn) hipLaunchKernelGGL((gather_contract_ws_kernel<S, false, false>), g, blk, 0, s, FLEX_WS_ARGS);
-            else if (!csr && out_bcn) hipLaunchKernelGGL((gather_contract_ws_kernel<S, false, true>), g, blk, 0, s, FLEX_WS_ARGS);
-            else if (csr && !out_bcn) hipLaunchKernelGGL((gather_contract_ws_kernel<S, true, false>), g, blk, 0, s, FLEX_WS_ARGS);
-            else hipLaunchKernelGGL((gather_contract_ws_kernel<S, true, true>), g, blk, 0, s, FLEX_WS_ARGS);
+            const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
+#define FLEX_WS_ARGS rows, pos, nbr, off, src, thetaP, exp_off, out, N, K, tpc, tot
+#define FLEX_WS_LAUNCH(CSR_, BCN_)                                                                          \
+    do {                                                                                                    \
+        if (theta_fmt) hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, true>), g, blk, 0, s, FLEX_WS_ARGS); \
+        else hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, false>), g, blk, 0, s, FLEX_WS_ARGS);          \
+    } while (0)
+            if (!csr && !out_bcn) FLEX_WS_LAUNCH(false, false);
+            else if (!csr && out_bcn) FLEX_WS_LAUNCH(false, true);
+            else if (csr && !out_bcn) FLEX_WS_LAUNCH(true, false);
+            else FLEX_WS_LAUNCH(true, true);
+#undef FLEX_WS_LAUNCH
 #undef FLEX_WS_ARGS
             return hipGetLastError();
         }
     }
 #endif
+    if (theta_fmt) return hipErrorInvalidValue;   // the single-role kernels take fp32 ThetaP only
+    const float *thetaF32 = reinterpret_cast<const float *>(thetaP);
+#define FLEX_GC_ARGS rows, pos, nbr, off, src, thetaF32, out, N, K, tiles_per_cloud, total
     const dim3 g(grid), blk(S::NT);
     using G = WaveGeom<S>;
     const bool fast = csr || ((int64_t)G::PW * K <= G::EW);

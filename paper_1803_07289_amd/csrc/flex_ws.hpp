@@ -50,7 +50,31 @@ struct WsGeom {
     static_assert(NITEMS % NC == 0 || NC % NITEMS == 0, "items per consumer wave");
     static constexpr int IPW = cdiv_c(NITEMS, NC);
     static_assert(IPW == 1 || NS % NC == 0 || NC % NS == 0, "slice split");
+    // split-half aggregate tile: per point [hi: KDP halves][lo: KDP halves][16 B pad]
+    static constexpr int KDP = rup_c(S::KD, 32);         // depth padded to the f16 matrix op
+    static constexpr int KS2 = KDP / 32;                 // depth steps of v_mfma_f32_16x16x32_f16
+    static constexpr int ARS = 4 * KDP + 16;             // row stride in bytes (= 16 mod 128: 16-byte reads of
+                                                         // 8 consecutive rows hit distinct banks)
+    static constexpr int ROWB_F32 = 4 * AST;
+    static constexpr int ROWB = ARS > ROWB_F32 ? ARS : ROWB_F32;
 };
+
+// max over the LPR lanes of a gathered row's lane group (all lanes of the wave take part)
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+template <int LPR>
+__device__ __forceinline__ float group_max(float m)
+{
+    m = fmaxf(m, dpp_move<0xB1>(m));                           // quad_perm [1,0,3,2]
+    m = fmaxf(m, dpp_move<0x4E>(m));                           // quad_perm [2,3,0,1]
+    if constexpr (LPR >= 8) m = fmaxf(m, dpp_move<0x141>(m));  // row_half_mirror
+    if constexpr (LPR >= 16) m = fmaxf(m, dpp_move<0x140>(m)); // row_mirror
+    if constexpr (LPR >= 32) m = fmaxf(m, __shfl_xor(m, 16));
+    return m;
+}
 
 template <class S>
 struct WsStage {
@@ -270,8 +294,10 @@ struct Producer {
     __device__ __forceinline__ void stage_dp() { publish_dp<P>(cnt[P], pa, pb); }
 
     // Finish tile r (buffer P, issued one iteration ago): aggregate -> sA rows of this wave.
-    template <int P>
-    __device__ __forceinline__ void finish(const TileRef &r, int offs, float *sA)
+    // F16 == false: fp32 rows of AST floats.  F16 == true: split-half rows (WsGeom::ARS bytes)
+    // scaled per point by 2^e, e stored in sE[point] (see pack_theta_f16_kernel for the split).
+    template <int P, bool F16>
+    __device__ __forceinline__ void finish(const TileRef &r, int offs, char *sA, int *sE)
     {
         v4f acc[S::VEC];
 #pragma unroll
@@ -309,14 +335,47 @@ struct Producer {
         }
         wave_lds_sync();   // this staging buffer is rewritten two issues from now
 
-        if (grp < G::PW && (S::VEC * t) < S::DIP) {
-            float *row = sA + (pw * G::PW + grp) * G::AST + S::VEC * t;
+        const bool writer = grp < G::PW && (S::VEC * t) < S::DIP;
+        if constexpr (!F16) {
+            if (writer) {
+                float *row = reinterpret_cast<float *>(sA) + (pw * G::PW + grp) * G::AST + S::VEC * t;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                if constexpr (S::VEC == 4) {
-                    *reinterpret_cast<v4f *>(row + jj * S::DIP) = v4f{acc[0][jj], acc[1][jj], acc[2][jj], acc[3][jj]};
-                } else {
-                    row[jj * S::DIP] = acc[0][jj];
+                for (int jj = 0; jj < 4; ++jj) {
+                    if constexpr (S::VEC == 4) {
+                        *reinterpret_cast<v4f *>(row + jj * S::DIP) = v4f{acc[0][jj], acc[1][jj], acc[2][jj], acc[3][jj]};
+                    } else {
+                        row[jj * S::DIP] = acc[0][jj];
+                    }
+                }
+            }
+        } else {
+            // per-point exponent: the largest |A| of the row lands in [2^14, 2^15)
+            float m = 0.f;
+#pragma unroll
+            for (int v = 0; v < S::VEC; ++v)
+                m = fmaxf(fmaxf(m, fmaxf(fabsf(acc[v][0]), fabsf(acc[v][1]))), fmaxf(fabsf(acc[v][2]), fabsf(acc[v][3])));
+            m = group_max<S::LPR>(m);
+            const int e = 15 - __builtin_amdgcn_frexp_expf(m);
+            if (writer) {
+                const int pt = pw * G::PW + grp;
+                if (t == 0) sE[pt] = e;
+                char *row = sA + pt * G::ARS + 2 * S::VEC * t;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    _Float16 h[S::VEC], l[S::VEC];
+#pragma unroll
+                    for (int v = 0; v < S::VEC; ++v) {
+                        const float x = __builtin_ldexpf(acc[v][jj], e);
+                        h[v] = (_Float16)x;
+                        l[v] = (_Float16)(x - (float)h[v]);
+                    }
+                    if constexpr (S::VEC == 4) {
+                        *reinterpret_cast<h4 *>(row + 2 * jj * S::DIP) = h4{h[0], h[1], h[2], h[3]};
+                        *reinterpret_cast<h4 *>(row + 2 * (G::KDP + jj * S::DIP)) = h4{l[0], l[1], l[2], l[3]};
+                    } else {
+                        *reinterpret_cast<_Float16 *>(row + 2 * jj * S::DIP) = h[0];
+                        *reinterpret_cast<_Float16 *>(row + 2 * (G::KDP + jj * S::DIP)) = l[0];
+                    }
                 }
             }
         }
@@ -324,10 +383,9 @@ struct Producer {
 };
 
 // One producer iteration for tile k living in buffer P.
-template <int P, class S, bool CSR, class Extra>
+template <int P, bool F16, class S, bool CSR, class Extra>
 __device__ __forceinline__ bool producer_step(Producer<S, CSR> &Pr, const TileSchedule &sc, int k,
-                                              int tiles_per_cloud, float (*s_A)[S::T * WsGeom<S>::AST],
-                                              Extra &&extra)
+                                              int tiles_per_cloud, char *s_A, int *s_E, Extra &&extra)
 {
     using G = WsGeom<S>;
     const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
@@ -347,16 +405,16 @@ __device__ __forceinline__ bool producer_step(Producer<S, CSR> &Pr, const TileSc
     extra(k + 1, rn, 0);                // request extra data of tile k+1
     Pr.template issue<P ^ 1>(rn, id_issue, Pr.off_use);
     Pr.id_next = Pr.load_id(rnn, Pr.off_issue);
-    Pr.template finish<P>(r, off_k, s_A[P]);
-    __syncthreads();                    // tile k is complete in s_A[P]
+    Pr.template finish<P, F16>(r, off_k, s_A + P * (G::T * G::ROWB), s_E + P * G::T);
+    __syncthreads();                    // tile k is complete in buffer P
     return true;
 }
 
 // Runs the producer role for every tile of this workgroup; `extra(k, r, phase)` lets the
 // grad_theta kernel move its grad_out tile (phase 0: request for tile k, phase 1: park in LDS).
-template <class S, bool CSR, class Extra>
+template <bool F16, class S, bool CSR, class Extra>
 __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSchedule &sc, int tiles_per_cloud,
-                                              float (*s_A)[S::T * WsGeom<S>::AST], Extra &&extra)
+                                              char *s_A, int *s_E, Extra &&extra)
 {
     using G = WsGeom<S>;
     // prologue: ids of tile 0 and 1, offsets up to tile 2, tile 0 in flight
@@ -371,118 +429,200 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
     extra(0, r0, 0);
     Pr.template issue<0>(r0, id0, Pr.off_use);
     for (int k = 0;; k += 2) {
-        if (!producer_step<0>(Pr, sc, k, tiles_per_cloud, s_A, extra)) break;
-        if (!producer_step<1>(Pr, sc, k + 1, tiles_per_cloud, s_A, extra)) break;
+        if (!producer_step<0, F16>(Pr, sc, k, tiles_per_cloud, s_A, s_E, extra)) break;
+        if (!producer_step<1, F16>(Pr, sc, k + 1, tiles_per_cloud, s_A, s_E, extra)) break;
     }
 }
 
 // ---------------------------------------------------------------------------
 // out[l][:] = A[l][:] * ThetaP   (forward; grad_feat when CSR)
+//
+// F16 == true (the default): the contraction runs on the f16 matrix cores in split-half
+// form (three v_mfma_f32_16x16x32_f16 per 16x16x32 block: hi*hi, lo*hi, hi*lo, fp32
+// accumulation).  On gfx950 the fp32 matrix op shares the vector ALU's data path, so a
+// consumer wave contracting in fp32 stalls the producers' vector work on the same SIMD;
+// the f16 matrix pipe runs beside it.  thetaP is then the fragment buffer written by
+// pack_theta_f16_kernel and theta_exp_off the byte offset of its exponent.
+// F16 == false: fp32 matrix op on the fp32 ThetaP (kept for comparison).
 // ---------------------------------------------------------------------------
-template <class S, bool CSR, bool OUT_BCN>
+template <class S, bool CSR, bool OUT_BCN, bool F16>
 __global__ __launch_bounds__(WsGeom<S>::NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                                const int32_t *__restrict__ nbr, const int32_t *__restrict__ off,
-                               const int32_t *__restrict__ src, const float *__restrict__ thetaP,
-                               float *__restrict__ out, int N, int K, int tiles_per_cloud, int total_tiles)
+                               const int32_t *__restrict__ src, const void *__restrict__ thetaP,
+                               int theta_exp_off, float *__restrict__ out, int N, int K,
+                               int tiles_per_cloud, int total_tiles)
 {
     using G = WsGeom<S>;
-    __shared__ __attribute__((aligned(16))) float s_A[2][G::T * G::AST];
+    constexpr int ROWB = F16 ? G::ARS : G::ROWB_F32;
+    __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
+    __shared__ int s_E[2 * G::T];
     __shared__ WsStage<S> s_st[G::NP][2];
 
     const int w = threadIdx.x >> 6;
     const TileSchedule sc(total_tiles);
 
+    if constexpr (F16 && G::KDP > S::KD) {
+        // depth padding of both tile buffers: never written again, must read as zero
+        constexpr int PADH = G::KDP - S::KD;
+        for (int i = threadIdx.x; i < 2 * G::T * 2 * PADH; i += G::NT) {
+            const int e = i % PADH, part = (i / PADH) & 1, row = i / (2 * PADH);
+            *reinterpret_cast<_Float16 *>(s_A + (row / G::T) * (G::T * G::ROWB) + (row % G::T) * ROWB +
+                                          2 * (part * G::KDP + S::KD + e)) = (_Float16)0.f;
+        }
+        // ordered before the first consumer read by the barrier every thread passes for tile 0
+    }
+
     if (w < G::NP) {
         Producer<S, CSR> P;
         P.init(rows, pos, nbr, off, src, N, K, s_st[w], w);
-        producer_loop<S, CSR>(P, sc, tiles_per_cloud, s_A, [](int, const TileRef &, int) {});
+        producer_loop<F16>(P, sc, tiles_per_cloud, s_A, s_E, [](int, const TileRef &, int) {});
         return;
     }
 
     // ---- consumer ----
-    constexpr int KS = S::KD / 16;
     const int cw = w - G::NP;
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
     // item = (slice, block); consumer cw owns items cw, cw+NC, ... ; all share one slice
-    constexpr int NSL = (G::NS < G::NC) ? G::NS : G::NC;
     static_assert(G::NS <= G::NC || G::IPW * G::NC == G::NITEMS, "slices");
     const int slice = cw % G::NS;
     static_assert(G::NS <= G::NC, "one parameter slice per consumer wave");
-    (void)NSL;
-
-    float th[S::KD / 4];
-#pragma unroll
-    for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            th[4 * s + i] = thetaP[(int64_t)(16 * s + 4 * q + i) * S::DOP + slice * 16 + r16];
-
     // consumers beyond the item count only keep the barriers company
     const bool active = cw < G::NITEMS;
-    int a_off[G::IPW];                    // LDS float offset of this lane's 16-byte fragment, depth step 0
-#pragma unroll
-    for (int it = 0; it < G::IPW; ++it) {
-        const int idx = active ? cw + it * G::NC : 0;
-        a_off[it] = ((idx / G::NS) * 16 + r16) * G::AST + 4 * q;
-    }
 
-    for (int k = 0;; ++k) {
-        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-        if (!r.valid) break;
-        __syncthreads();                  // tile k is complete in s_A[k&1]
-        if (!active) continue;
-        const float *sA = s_A[k & 1];
+    auto store_item = [&](const TileRef &r, int it, v4f d) {
+        const int idx = cw + it * G::NC;
+        if (idx >= G::NITEMS) return;
         const int npts = min(G::T, N - r.l0);
-
-        // four independent accumulation chains per item (one per depth lane i), fragments one step ahead
-        v4f acc[G::IPW][4];
-        v4f bf[G::IPW];
+        const int pt = (idx / G::NS) * 16 + r16;
+        const int o = slice * 16 + 4 * q;
+        if (pt < npts) {
+            if constexpr (OUT_BCN) {
+                float *dst = out + ((int64_t)r.b * S::DO + o) * N + (r.l0 + pt);
 #pragma unroll
-        for (int it = 0; it < G::IPW; ++it) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
-            bf[it] = *reinterpret_cast<const v4f *>(&sA[a_off[it]]);
-        }
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            v4f nx[G::IPW];
-#pragma unroll
-            for (int it = 0; it < G::IPW; ++it)
-                nx[it] = (s + 1 < KS) ? *reinterpret_cast<const v4f *>(&sA[a_off[it] + 16 * (s + 1)]) : bf[it];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int it = 0; it < G::IPW; ++it)
-                    acc[it][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(th[4 * s + i], bf[it][i], acc[it][i], 0, 0, 0);
-#pragma unroll
-            for (int it = 0; it < G::IPW; ++it) bf[it] = nx[it];
-        }
-#pragma unroll
-        for (int it = 0; it < G::IPW; ++it) {
-            const int idx = cw + it * G::NC;
-            if (idx >= G::NITEMS) continue;
-            const int blk = idx / G::NS;
-            const v4f d = (acc[it][0] + acc[it][1]) + (acc[it][2] + acc[it][3]);
-            const int pt = blk * 16 + r16;
-            const int o = slice * 16 + 4 * q;
-            if (pt < npts) {
-                if constexpr (OUT_BCN) {
-                    float *dst = out + ((int64_t)r.b * S::DO + o) * N + (r.l0 + pt);
+                for (int i = 0; i < 4; ++i)
+                    if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
+            } else {
+                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * S::DO + o;
+                if constexpr (S::DO % 4 == 0) {
+                    if (o < S::DO) *reinterpret_cast<v4f *>(dst) = d;
+                } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
-                } else {
-                    float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * S::DO + o;
-                    if constexpr (S::DO % 4 == 0) {
-                        if (o < S::DO) *reinterpret_cast<v4f *>(dst) = d;
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (o + i < S::DO) dst[i] = d[i];
-                    }
+                        if (o + i < S::DO) dst[i] = d[i];
                 }
             }
+        }
+    };
+
+    if constexpr (F16) {
+        constexpr int KS2 = G::KS2;
+        // parameter fragments (matrix A operand: row = output channel r16, depth 32*s + 8*q + e)
+        h8 thH[KS2], thL[KS2];
+        {
+            const _Float16 *tf = reinterpret_cast<const _Float16 *>(thetaP);
+            constexpr int PER_PART = G::NS * KS2 * 64 * 8;
+#pragma unroll
+            for (int s = 0; s < KS2; ++s) {
+                const int at = ((slice * KS2 + s) * 64 + lane) * 8;
+                thH[s] = *reinterpret_cast<const h8 *>(tf + at);
+                thL[s] = *reinterpret_cast<const h8 *>(tf + PER_PART + at);
+            }
+        }
+        const int e_theta = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off);
+
+        int a_off[G::IPW];                // byte offset of this lane's 16-byte fragment (hi part, step 0)
+#pragma unroll
+        for (int it = 0; it < G::IPW; ++it) {
+            const int idx = active ? cw + it * G::NC : 0;
+            a_off[it] = ((idx / G::NS) * 16 + r16) * G::ARS + 16 * q;
+        }
+
+        for (int k = 0;; ++k) {
+            const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+            if (!r.valid) break;
+            __syncthreads();              // tile k is complete in buffer k&1
+            if (!active) continue;
+            const char *sA = s_A + (k & 1) * (G::T * G::ROWB);
+            const int *sE = s_E + (k & 1) * G::T;
+
+            // three independent accumulation chains per item: hi*hi, lo*hi, hi*lo
+            v4f acc[G::IPW][3];
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS2; ++s) {
+#pragma unroll
+                for (int it = 0; it < G::IPW; ++it) {
+                    const h8 bh = *reinterpret_cast<const h8 *>(sA + a_off[it] + 64 * s);
+                    const h8 bl = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP + 64 * s);
+                    acc[it][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bh, acc[it][0], 0, 0, 0);
+                    acc[it][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[s], bh, acc[it][1], 0, 0, 0);
+                    acc[it][2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl, acc[it][2], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it) {
+                const int idx = active ? cw + it * G::NC : 0;
+                const int back = -(sE[(idx / G::NS) * 16 + r16] + e_theta);   // undo both scalings
+                v4f d = acc[it][0] + (acc[it][1] + acc[it][2]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], back);
+                store_item(r, it, d);
+            }
+        }
+    } else {
+        constexpr int KS = S::KD / 16;
+        const float *th_src = reinterpret_cast<const float *>(thetaP);
+        float th[S::KD / 4];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                th[4 * s + i] = th_src[(int64_t)(16 * s + 4 * q + i) * S::DOP + slice * 16 + r16];
+
+        int a_off[G::IPW];                // LDS float offset of this lane's 16-byte fragment, depth step 0
+#pragma unroll
+        for (int it = 0; it < G::IPW; ++it) {
+            const int idx = active ? cw + it * G::NC : 0;
+            a_off[it] = ((idx / G::NS) * 16 + r16) * G::AST + 4 * q;
+        }
+
+        for (int k = 0;; ++k) {
+            const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+            if (!r.valid) break;
+            __syncthreads();              // tile k is complete in buffer k&1
+            if (!active) continue;
+            const float *sA = reinterpret_cast<const float *>(s_A + (k & 1) * (G::T * G::ROWB));
+
+            // four independent accumulation chains per item (one per depth lane i), fragments one step ahead
+            v4f acc[G::IPW][4];
+            v4f bf[G::IPW];
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
+                bf[it] = *reinterpret_cast<const v4f *>(&sA[a_off[it]]);
+            }
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                v4f nx[G::IPW];
+#pragma unroll
+                for (int it = 0; it < G::IPW; ++it)
+                    nx[it] = (s + 1 < KS) ? *reinterpret_cast<const v4f *>(&sA[a_off[it] + 16 * (s + 1)]) : bf[it];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int it = 0; it < G::IPW; ++it)
+                        acc[it][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(th[4 * s + i], bf[it][i], acc[it][i], 0, 0, 0);
+#pragma unroll
+                for (int it = 0; it < G::IPW; ++it) bf[it] = nx[it];
+            }
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it)
+                store_item(r, it, (acc[it][0] + acc[it][1]) + (acc[it][2] + acc[it][3]));
         }
     }
 }
@@ -498,7 +638,7 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
 {
     using G = WsGeom<S>;
     constexpr int GST = S::DOP + 16;
-    __shared__ __attribute__((aligned(16))) float s_A[2][G::T * G::AST];
+    __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
     __shared__ __attribute__((aligned(16))) float s_G[2][G::T * GST];
     __shared__ WsStage<S> s_st[G::NP][2];
 
@@ -513,7 +653,7 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
         const int ptid = threadIdx.x;     // 0..64*NP-1
         Producer<S, false> P;
         P.init(rows, pos, nbr, nullptr, nullptr, N, K, s_st[w], w);
-        producer_loop<S, false>(P, sc, tiles_per_cloud, s_A, [&](int k, const TileRef &r, int phase) {
+        producer_loop<false>(P, sc, tiles_per_cloud, s_A, nullptr, [&](int k, const TileRef &r, int phase) {
             if (phase == 0) {
 #pragma unroll
                 for (int i = 0; i < GPT; ++i) {
@@ -556,7 +696,7 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
         const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
         if (!r.valid) break;
         __syncthreads();
-        const float *sA = s_A[k & 1], *sG = s_G[k & 1];
+        const float *sA = reinterpret_cast<const float *>(s_A + (k & 1) * (G::T * G::ROWB)), *sG = s_G[k & 1];
 #pragma unroll
         for (int s = 0; s < G::T / 4; ++s) {
             const int row = 4 * s + q;
