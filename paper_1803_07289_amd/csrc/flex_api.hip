@@ -59,6 +59,18 @@ bool contract_in_fp32()
     return f32;
 }
 
+int lean_producer_mode()
+{
+    static const int mode = [] {
+        const char *v = getenv("FLEX_PRODUCER");
+        if (v == nullptr) return 2;
+        if (v[0] == 's') return 0;
+        if (v[0] == 'l') return 1;
+        return 2;
+    }();
+    return mode;
+}
+
 // Packs (theta, bias) for launch_gather_contract in the format that kernel wants.
 static hipError_t pack_for_contract(const float *theta, const float *bias, void *thetaP, int Din,
                                     int Dout, int transpose, int fmt, hipStream_t s)

@@ -60,6 +60,10 @@ int gather_contract_theta_format(int DI, int DO, int K, int csr);
 // true when the environment asks for the fp32 matrix op in the wave-specialised kernels
 // (FLEX_CONTRACT=f32; read once).  For A/B measurements; both forms meet the same tolerance.
 bool contract_in_fp32();
+// Producer choice for the fixed-K forward (FLEX_PRODUCER, read once; for A/B measurements):
+// 0 "staged" = LDS-staged producer, 1 "lean" = lean producers, one per consumer wave,
+// 2 (default) = lean producers, three per consumer wave where the shape allows.
+int lean_producer_mode();
 
 // grad_theta / grad_bias: per-workgroup partial sums into `partials`
 // ([n_wg, KD, DOP] floats), then a reduction into the two outputs.

@@ -54,6 +54,28 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
         if (theta_fmt) hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, true>), g, blk, 0, s, FLEX_WS_ARGS); \
         else hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, false>), g, blk, 0, s, FLEX_WS_ARGS);          \
     } while (0)
+            // lean producer: fixed-K tensor, K in whole batches of 8, 32-bit byte offsets inside a cloud
+            const bool lean = !csr && theta_fmt && lean_producer_mode() != 0 && (K % 8 == 0) &&
+                              (int64_t)K * N * 4 < (1ll << 32) && (int64_t)N * S::DI * 4 < (1ll << 32) &&
+                              (int64_t)N * 12 < (1ll << 32);
+            if (lean) {
+                // 3 producer waves per consumer wave where 16 waves hold them and the items divide evenly
+                constexpr bool WIDE_OK = (S::WAVES * 4 <= 16) && (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
+                constexpr int PMX = WIDE_OK ? 3 : 1;
+                const bool wide = PMX > 1 && lean_producer_mode() != 1;
+                using WL = WsGeom<S, PMX>;
+                const int tl = wide ? WL::T : W::T;
+                const int tpcl = (N + tl - 1) / tl;
+                const int totl = B * tpcl;
+                const dim3 gl(persistent_grid(totl, wide ? WL::WG_PER_CU : W::WG_PER_CU)), bl(wide ? WL::NT : W::NT);
+#define FLEX_LEAN_ARGS rows, pos, nbr, thetaP, exp_off, out, N, K, tpcl, totl
+                if (wide && !out_bcn) hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+                else if (wide) hipLaunchKernelGGL((gather_contract_lean_kernel<S, true, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+                else if (!out_bcn) hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+                else hipLaunchKernelGGL((gather_contract_lean_kernel<S, true, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+#undef FLEX_LEAN_ARGS
+                return hipGetLastError();
+            }
             if (!csr && !out_bcn) FLEX_WS_LAUNCH(false, false);
             else if (!csr && out_bcn) FLEX_WS_LAUNCH(false, true);
             else if (csr && !out_bcn) FLEX_WS_LAUNCH(true, false);

@@ -30,12 +30,12 @@
 
 namespace flex {
 
-template <class S>
+template <class S, int PM = 1>
 struct WsGeom {
-    static constexpr int NP = S::WAVES, NC = S::WAVES;   // producer / consumer waves
+    static constexpr int NP = S::WAVES * PM, NC = S::WAVES;   // producer / consumer waves
     static constexpr int NT = 64 * (NP + NC);
     static constexpr int WG_PER_CU = 16 / (NP + NC);
-    static constexpr int T = S::T;                       // points per tile
+    static constexpr int T = S::T * PM;                  // points per tile
     static constexpr int PW = T / NP;                    // points per producer wave
     static constexpr int GPW = 64 / S::LPR;              // row groups per wave
     static constexpr int EW = 64;                        // staged entries per producer wave
@@ -74,6 +74,51 @@ __device__ __forceinline__ float group_max(float m)
     if constexpr (LPR >= 16) m = fmaxf(m, dpp_move<0x140>(m)); // row_mirror
     if constexpr (LPR >= 32) m = fmaxf(m, __shfl_xor(m, 16));
     return m;
+}
+
+// Writes one point's aggregate (this lane: channels VEC*t.., all four j) as split-half rows:
+// the row is scaled by 2^e so that its largest magnitude lands in [2^14, 2^15), e goes to sE[pt].
+// Every lane of the wave calls this (the row maximum is taken across the lane group).
+// max(m, |a|, |b|) for finite inputs, m >= 0 (one v_max3_f32 with |.| source modifiers)
+__device__ __forceinline__ float fmax3_abs(float m, float a, float b)
+{
+    return __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
+}
+
+template <class S>
+__device__ __forceinline__ void store_split_rows(const v4f (&acc)[S::VEC], char *sA, int *sE, int pt, int t,
+                                                 bool writer)
+{
+    using G = WsGeom<S>;   // row format only: the same for every producer multiple
+    float m = 0.f;
+#pragma unroll
+    for (int v = 0; v < S::VEC; ++v) {
+        m = fmax3_abs(m, acc[v][0], acc[v][1]);
+        m = fmax3_abs(m, acc[v][2], acc[v][3]);
+    }
+    m = group_max<S::LPR>(m);
+    const int e = 15 - __builtin_amdgcn_frexp_expf(m);
+    if (writer) {
+        if (t == 0) sE[pt] = e;
+        char *row = sA + pt * G::ARS + 2 * S::VEC * t;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            _Float16 h[S::VEC], l[S::VEC];
+#pragma unroll
+            for (int v = 0; v < S::VEC; ++v) {
+                const float x = __builtin_ldexpf(acc[v][jj], e);
+                h[v] = (_Float16)x;
+                l[v] = (_Float16)__builtin_fmaf((float)h[v], -1.f, x);
+            }
+            if constexpr (S::VEC == 4) {
+                *reinterpret_cast<h4 *>(row + 2 * jj * S::DIP) = h4{h[0], h[1], h[2], h[3]};
+                *reinterpret_cast<h4 *>(row + 2 * (G::KDP + jj * S::DIP)) = h4{l[0], l[1], l[2], l[3]};
+            } else {
+                *reinterpret_cast<_Float16 *>(row + 2 * jj * S::DIP) = h[0];
+                *reinterpret_cast<_Float16 *>(row + 2 * (G::KDP + jj * S::DIP)) = l[0];
+            }
+        }
+    }
 }
 
 template <class S>
@@ -349,35 +394,7 @@ struct Producer {
                 }
             }
         } else {
-            // per-point exponent: the largest |A| of the row lands in [2^14, 2^15)
-            float m = 0.f;
-#pragma unroll
-            for (int v = 0; v < S::VEC; ++v)
-                m = fmaxf(fmaxf(m, fmaxf(fabsf(acc[v][0]), fabsf(acc[v][1]))), fmaxf(fabsf(acc[v][2]), fabsf(acc[v][3])));
-            m = group_max<S::LPR>(m);
-            const int e = 15 - __builtin_amdgcn_frexp_expf(m);
-            if (writer) {
-                const int pt = pw * G::PW + grp;
-                if (t == 0) sE[pt] = e;
-                char *row = sA + pt * G::ARS + 2 * S::VEC * t;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    _Float16 h[S::VEC], l[S::VEC];
-#pragma unroll
-                    for (int v = 0; v < S::VEC; ++v) {
-                        const float x = __builtin_ldexpf(acc[v][jj], e);
-                        h[v] = (_Float16)x;
-                        l[v] = (_Float16)(x - (float)h[v]);
-                    }
-                    if constexpr (S::VEC == 4) {
-                        *reinterpret_cast<h4 *>(row + 2 * jj * S::DIP) = h4{h[0], h[1], h[2], h[3]};
-                        *reinterpret_cast<h4 *>(row + 2 * (G::KDP + jj * S::DIP)) = h4{l[0], l[1], l[2], l[3]};
-                    } else {
-                        *reinterpret_cast<_Float16 *>(row + 2 * jj * S::DIP) = h[0];
-                        *reinterpret_cast<_Float16 *>(row + 2 * (G::KDP + jj * S::DIP)) = l[0];
-                    }
-                }
-            }
+            store_split_rows<S>(acc, sA, sE, pw * G::PW + grp, t, writer);
         }
     }
 };
@@ -435,6 +452,155 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 }
 
 // ---------------------------------------------------------------------------
+// Lean producer for the fixed-K neighbour tensor (K a multiple of 8, every per-cloud byte
+// offset below 2^32).  Nothing is staged in LDS: each lane of a row group loads its
+// point's neighbour ids itself (a broadcast read), turns them into 32-bit row offsets,
+// and lane i of every 4-lane block loads component i (x, y, z) of the neighbour's
+// position directly, so the (dx,dy,dz,1) operand of the 4x4x1 matrix op is formed in
+// registers.  Tail points are clamped to the cloud's last point (computed, never stored).
+//
+// The work of a wave is a stream of batches, one batch = 8 neighbours of the wave's points
+// of one tile (K/8 batches per tile).  Eight rows per lane are in flight at all times: as
+// soon as row u of batch m has been accumulated, its registers receive row u of batch
+// m+1; the ids of batch m+2 are requested at the start of batch m.  Batches past the
+// workgroup's last tile repeat that tile (loaded, never used).
+// ---------------------------------------------------------------------------
+template <class S, int PM>
+struct LeanProducer {
+    using G = WsGeom<S, PM>;
+    static constexpr int U = 8;
+    static constexpr bool FULL = (S::LPR * S::VEC == S::DI);   // every lane of a group reads real channels
+
+    const float *rows, *pos;
+    const int32_t *nbr;
+    int N, K, KB, pw, grp, t;
+    bool lane_on;
+    unsigned lane_off, csel;     // byte offset of the lane's channels in a row; position component 0..2
+    float dmul, dfix;            // dp component = (pn - pc)*dmul + dfix  (block lane 3: the constant 1)
+    int first, step, count, tiles_per_cloud;   // this workgroup's tiles: first + i*step, i < count
+
+    __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *nbr_, int N_,
+                                         int K_, int pw_, const TileSchedule &sc, int tiles_per_cloud_)
+    {
+        rows = rows_; pos = pos_; nbr = nbr_; N = N_; K = K_; KB = K_ / U; pw = pw_;
+        const int lane = threadIdx.x & 63;
+        grp = lane / S::LPR; t = lane % S::LPR;
+        lane_on = (S::VEC * t) < S::DI;
+        lane_off = lane_on ? 4u * S::VEC * t : 0u;       // lanes past the row read its start, value unused
+        const int dsel = lane & 3;
+        csel = dsel < 3 ? dsel : 2;
+        dmul = dsel < 3 ? 1.f : 0.f;
+        dfix = dsel < 3 ? 0.f : 1.f;
+        first = sc.first; step = sc.step; tiles_per_cloud = tiles_per_cloud_;
+        count = (sc.first < sc.end) ? (sc.end - sc.first + sc.step - 1) / sc.step : 0;
+    }
+
+    struct Batch {
+        int b;          // cloud
+        int l;          // this lane's point (clamped into the cloud)
+        int k0;         // first neighbour slot
+    };
+    // batch m of this workgroup (m clamped to the last one)
+    __device__ __forceinline__ Batch batch(int m) const
+    {
+        const int last = count * KB - 1;
+        m = min(m, last);
+        const int i = m / KB;
+        const int tile = first + i * step;
+        Batch x;
+        x.b = tile / tiles_per_cloud;
+        x.l = min((tile - x.b * tiles_per_cloud) * G::T + pw * G::PW + (grp % G::PW), N - 1);
+        x.k0 = (m - i * KB) * U;
+        return x;
+    }
+
+    __device__ __forceinline__ void load_ids(int (&id)[U], float &pc, const Batch &x) const
+    {
+        const char *base = reinterpret_cast<const char *>(nbr + (int64_t)x.b * K * N);
+        const unsigned o = 4u * ((unsigned)x.k0 * (unsigned)N + (unsigned)x.l);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            id[u] = *reinterpret_cast<const int32_t *>(base + (o + 4u * (unsigned)u * (unsigned)N));
+        const char *pb = reinterpret_cast<const char *>(pos + (int64_t)x.b * 3 * N);
+        pc = *reinterpret_cast<const float *>(pb + 4u * (csel * (unsigned)N + (unsigned)x.l));
+    }
+
+    __device__ __forceinline__ void load_row(float (&fr)[S::VEC], float &pnr, int id, const char *rb,
+                                             const char *pb) const
+    {
+        const unsigned n = (unsigned)id;
+        pnr = *reinterpret_cast<const float *>(pb + 4u * (csel * (unsigned)N + n));
+        const char *p = rb + (n * (4u * S::DI) + lane_off);
+        if constexpr (S::VEC == 4) {
+            const v4f v = *reinterpret_cast<const v4f *>(p);
+            fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
+        } else {
+            fr[0] = *reinterpret_cast<const float *>(p);
+        }
+    }
+
+    // the producer role for every tile of this workgroup
+    __device__ __forceinline__ void run(char *s_A, int *s_E)
+    {
+        if (count == 0) return;
+        float f[U][S::VEC], pn[U];
+        int idn[U];              // ids of the batch after the one whose rows are in flight
+        float pc_cur, pc_rows, pc_ids;   // centre component: batch being accumulated / in flight / of idn
+        {
+            // prologue: rows of batch 0 in flight, ids of batch 1 requested
+            int id0[U];
+            const Batch x0 = batch(0);
+            load_ids(id0, pc_rows, x0);
+            load_ids(idn, pc_ids, batch(1));
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * S::DI);
+            const char *pb = reinterpret_cast<const char *>(pos + (int64_t)x0.b * 3 * N);
+#pragma unroll
+            for (int u = 0; u < U; ++u) load_row(f[u], pn[u], id0[u], rb, pb);
+        }
+        const int total = count * KB;
+        int kb = 0, tile_i = 0;
+        v4f acc[S::VEC];
+#pragma unroll
+        for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+
+        for (int m = 0; m < total; ++m) {
+            // ids of batch m+1 are here; those of batch m+2 go in flight
+            int idc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) idc[u] = idn[u];
+            pc_cur = pc_rows;
+            pc_rows = pc_ids;
+            const Batch x1 = batch(m + 1);
+            load_ids(idn, pc_ids, batch(m + 2));
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * S::DI);
+            const char *pb = reinterpret_cast<const char *>(pos + (int64_t)x1.b * 3 * N);
+
+            const float c = dfix - pc_cur * dmul;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float dpc = fmaf(pn[u], dmul, c);
+                float fv[S::VEC];
+#pragma unroll
+                for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
+                fma_row<S>(acc, dpc, fv);
+                load_row(f[u], pn[u], idc[u], rb, pb);     // row u of batch m+1 takes the freed registers
+            }
+
+            if (++kb == KB) {
+                kb = 0;
+                const int P = tile_i & 1;
+                store_split_rows<S>(acc, s_A + P * (G::T * G::ROWB), s_E + P * G::T, pw * G::PW + grp, t,
+                                    grp < G::PW && (S::VEC * t) < S::DIP);
+#pragma unroll
+                for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                ++tile_i;
+                __syncthreads();        // tile complete in buffer P
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
 // out[l][:] = A[l][:] * ThetaP   (forward; grad_feat when CSR)
 //
 // F16 == true (the default): the contraction runs on the f16 matrix cores in split-half
@@ -445,6 +611,139 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 // pack_theta_f16_kernel and theta_exp_off the byte offset of its exponent.
 // F16 == false: fp32 matrix op on the fp32 ThetaP (kept for comparison).
 // ---------------------------------------------------------------------------
+// One consumer wave of the split-half contraction: out tile = A tile * Theta for every tile of
+// the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
+template <class S, class G, bool OUT_BCN>
+__device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ thetaP, int theta_exp_off,
+                                             float *__restrict__ out, int N, const TileSchedule &sc,
+                                             int tiles_per_cloud, const char *s_A, const int *s_E)
+{
+    const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
+    // item = (slice, block); consumer cw owns items cw, cw+NC, ... ; all share one slice
+    static_assert(G::NS <= G::NC, "one parameter slice per consumer wave");
+    const int slice = cw % G::NS;
+    const bool active = cw < G::NITEMS;   // consumers beyond the item count only keep the barriers company
+
+    auto store_item = [&](const TileRef &r, int it, v4f d) {
+        const int idx = cw + it * G::NC;
+        if (idx >= G::NITEMS) return;
+        const int npts = min(G::T, N - r.l0);
+        const int pt = (idx / G::NS) * 16 + r16;
+        const int o = slice * 16 + 4 * q;
+        if (pt < npts) {
+            if constexpr (OUT_BCN) {
+                float *dst = out + ((int64_t)r.b * S::DO + o) * N + (r.l0 + pt);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
+            } else {
+                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * S::DO + o;
+                if constexpr (S::DO % 4 == 0) {
+                    if (o < S::DO) *reinterpret_cast<v4f *>(dst) = d;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (o + i < S::DO) dst[i] = d[i];
+                }
+            }
+        }
+    };
+
+    constexpr int KS2 = G::KS2;
+    // parameter fragments (matrix A operand: row = output channel r16, depth 32*s + 8*q + e)
+    h8 thH[KS2], thL[KS2];
+    {
+        const _Float16 *tf = reinterpret_cast<const _Float16 *>(thetaP);
+        constexpr int PER_PART = G::NS * KS2 * 64 * 8;
+#pragma unroll
+        for (int s = 0; s < KS2; ++s) {
+            const int at = ((slice * KS2 + s) * 64 + lane) * 8;
+            thH[s] = *reinterpret_cast<const h8 *>(tf + at);
+            thL[s] = *reinterpret_cast<const h8 *>(tf + PER_PART + at);
+        }
+    }
+    const int e_theta = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off);
+
+    int a_off[G::IPW];                // byte offset of this lane's 16-byte fragment (hi part, step 0)
+#pragma unroll
+    for (int it = 0; it < G::IPW; ++it) {
+        const int idx = active ? cw + it * G::NC : 0;
+        a_off[it] = ((idx / G::NS) * 16 + r16) * G::ARS + 16 * q;
+    }
+
+    for (int k = 0;; ++k) {
+        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+        if (!r.valid) break;
+        __syncthreads();              // tile k is complete in buffer k&1
+        if (!active) continue;
+        const char *sA = s_A + (k & 1) * (G::T * G::ROWB);
+        const int *sE = s_E + (k & 1) * G::T;
+
+        // items one after the other; three independent accumulation chains each: hi*hi, lo*hi, hi*lo
+#pragma unroll
+        for (int it = 0; it < G::IPW; ++it) {
+            v4f acc[3];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) acc[c] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < KS2; ++s) {
+                const h8 bh = *reinterpret_cast<const h8 *>(sA + a_off[it] + 64 * s);
+                const h8 bl = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP + 64 * s);
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bh, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[s], bh, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl, acc[2], 0, 0, 0);
+            }
+            const int idx = active ? cw + it * G::NC : 0;
+            const int back = -(sE[(idx / G::NS) * 16 + r16] + e_theta);   // undo both scalings
+            v4f d = acc[0] + (acc[1] + acc[2]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], back);
+            store_item(r, it, d);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Forward with the lean producers: NP = PM * S::WAVES producer waves feed S::WAVES consumer
+// waves (PM = 3: twelve gathering waves and four contracting ones per 1024-thread
+// workgroup, 48-point tiles, one workgroup per CU).  The gather is latency-bound, so what
+// counts is how many rows the CU has in flight; the f16 contraction is cheap enough for a
+// quarter of the waves.
+// ---------------------------------------------------------------------------
+template <class S, bool OUT_BCN, int PM>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                 const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
+                                 int theta_exp_off, float *__restrict__ out, int N, int K,
+                                 int tiles_per_cloud, int total_tiles)
+{
+    using G = WsGeom<S, PM>;
+    __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
+    __shared__ int s_E[2 * G::T];
+
+    const int w = threadIdx.x >> 6;
+    const TileSchedule sc(total_tiles);
+
+    if constexpr (G::KDP > S::KD) {
+        // depth padding of both tile buffers: never written again, must read as zero
+        constexpr int PADH = G::KDP - S::KD;
+        for (int i = threadIdx.x; i < 2 * G::T * 2 * PADH; i += G::NT) {
+            const int e = i % PADH, part = (i / PADH) & 1, row = i / (2 * PADH);
+            *reinterpret_cast<_Float16 *>(s_A + (row / G::T) * (G::T * G::ROWB) + (row % G::T) * G::ARS +
+                                          2 * (part * G::KDP + S::KD + e)) = (_Float16)0.f;
+        }
+        // ordered before the first consumer read by the barrier every thread passes for tile 0
+    }
+
+    if (w < G::NP) {
+        LeanProducer<S, PM> P;
+        P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
+        P.run(s_A, s_E);
+        return;
+    }
+    consumer_f16<S, G, OUT_BCN>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
+}
+
 template <class S, bool CSR, bool OUT_BCN, bool F16>
 __global__ __launch_bounds__(WsGeom<S>::NT) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
@@ -516,63 +815,7 @@ void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__re
     };
 
     if constexpr (F16) {
-        constexpr int KS2 = G::KS2;
-        // parameter fragments (matrix A operand: row = output channel r16, depth 32*s + 8*q + e)
-        h8 thH[KS2], thL[KS2];
-        {
-            const _Float16 *tf = reinterpret_cast<const _Float16 *>(thetaP);
-            constexpr int PER_PART = G::NS * KS2 * 64 * 8;
-#pragma unroll
-            for (int s = 0; s < KS2; ++s) {
-                const int at = ((slice * KS2 + s) * 64 + lane) * 8;
-                thH[s] = *reinterpret_cast<const h8 *>(tf + at);
-                thL[s] = *reinterpret_cast<const h8 *>(tf + PER_PART + at);
-            }
-        }
-        const int e_theta = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off);
-
-        int a_off[G::IPW];                // byte offset of this lane's 16-byte fragment (hi part, step 0)
-#pragma unroll
-        for (int it = 0; it < G::IPW; ++it) {
-            const int idx = active ? cw + it * G::NC : 0;
-            a_off[it] = ((idx / G::NS) * 16 + r16) * G::ARS + 16 * q;
-        }
-
-        for (int k = 0;; ++k) {
-            const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-            if (!r.valid) break;
-            __syncthreads();              // tile k is complete in buffer k&1
-            if (!active) continue;
-            const char *sA = s_A + (k & 1) * (G::T * G::ROWB);
-            const int *sE = s_E + (k & 1) * G::T;
-
-            // three independent accumulation chains per item: hi*hi, lo*hi, hi*lo
-            v4f acc[G::IPW][3];
-#pragma unroll
-            for (int it = 0; it < G::IPW; ++it)
-#pragma unroll
-                for (int c = 0; c < 3; ++c) acc[it][c] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS2; ++s) {
-#pragma unroll
-                for (int it = 0; it < G::IPW; ++it) {
-                    const h8 bh = *reinterpret_cast<const h8 *>(sA + a_off[it] + 64 * s);
-                    const h8 bl = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP + 64 * s);
-                    acc[it][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bh, acc[it][0], 0, 0, 0);
-                    acc[it][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[s], bh, acc[it][1], 0, 0, 0);
-                    acc[it][2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl, acc[it][2], 0, 0, 0);
-                }
-            }
-#pragma unroll
-            for (int it = 0; it < G::IPW; ++it) {
-                const int idx = active ? cw + it * G::NC : 0;
-                const int back = -(sE[(idx / G::NS) * 16 + r16] + e_theta);   // undo both scalings
-                v4f d = acc[it][0] + (acc[it][1] + acc[it][2]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], back);
-                store_item(r, it, d);
-            }
-        }
+        consumer_f16<S, G, OUT_BCN>(cw, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
     } else {
         constexpr int KS = S::KD / 16;
         const float *th_src = reinterpret_cast<const float *>(thetaP);
