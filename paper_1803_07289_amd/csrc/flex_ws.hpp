@@ -92,10 +92,10 @@ __device__ __forceinline__ void store_split_rows(const v4f (&acc)[S::VEC], char 
     using G = WsGeom<S>;   // row format only: the same for every producer multiple
     float m = 0.f;
 #pragma unroll
-    for (int v = 0; v < S::VEC; ++v) {
-        m = fmax3_abs(m, acc[v][0], acc[v][1]);
-        m = fmax3_abs(m, acc[v][2], acc[v][3]);
-    }
+    for (int v = 0; v < S::VEC; ++v)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            m = __builtin_amdgcn_fmed3f(m, __builtin_fabsf(acc[v][jj]), __builtin_inff());   // max(m, |a|), one op
     m = group_max<S::LPR>(m);
     const int e = 15 - __builtin_amdgcn_frexp_expf(m);
     if (writer) {
@@ -103,19 +103,24 @@ __device__ __forceinline__ void store_split_rows(const v4f (&acc)[S::VEC], char 
         char *row = sA + pt * G::ARS + 2 * S::VEC * t;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
-            _Float16 h[S::VEC], l[S::VEC];
-#pragma unroll
-            for (int v = 0; v < S::VEC; ++v) {
-                const float x = __builtin_ldexpf(acc[v][jj], e);
-                h[v] = (_Float16)x;
-                l[v] = (_Float16)__builtin_fmaf((float)h[v], -1.f, x);
-            }
             if constexpr (S::VEC == 4) {
-                *reinterpret_cast<h4 *>(row + 2 * jj * S::DIP) = h4{h[0], h[1], h[2], h[3]};
-                *reinterpret_cast<h4 *>(row + 2 * (G::KDP + jj * S::DIP)) = h4{l[0], l[1], l[2], l[3]};
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                h2 h[2], l[2];
+#pragma unroll
+                for (int p2 = 0; p2 < 2; ++p2) {
+                    const f2 x = {__builtin_ldexpf(acc[2 * p2][jj], e), __builtin_ldexpf(acc[2 * p2 + 1][jj], e)};
+                    h[p2] = __builtin_convertvector(x, h2);
+                    const f2 back = __builtin_convertvector(h[p2], f2);
+                    l[p2] = __builtin_convertvector(x - back, h2);
+                }
+                *reinterpret_cast<h4 *>(row + 2 * jj * S::DIP) = h4{h[0][0], h[0][1], h[1][0], h[1][1]};
+                *reinterpret_cast<h4 *>(row + 2 * (G::KDP + jj * S::DIP)) = h4{l[0][0], l[0][1], l[1][0], l[1][1]};
             } else {
-                *reinterpret_cast<_Float16 *>(row + 2 * jj * S::DIP) = h[0];
-                *reinterpret_cast<_Float16 *>(row + 2 * (G::KDP + jj * S::DIP)) = l[0];
+                const float x = __builtin_ldexpf(acc[0][jj], e);
+                const _Float16 h = (_Float16)x;
+                *reinterpret_cast<_Float16 *>(row + 2 * jj * S::DIP) = h;
+                *reinterpret_cast<_Float16 *>(row + 2 * (G::KDP + jj * S::DIP)) = (_Float16)(x - (float)h);
             }
         }
     }
@@ -470,14 +475,22 @@ struct LeanProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
     static constexpr bool FULL = (S::LPR * S::VEC == S::DI);   // every lane of a group reads real channels
+    static_assert(G::PW == 4, "entry layout below: 4 points x 8 neighbours per batch");
 
     const float *rows, *pos;
     const int32_t *nbr;
-    int N, K, KB, pw, grp, t;
-    bool lane_on;
-    unsigned lane_off, csel;     // byte offset of the lane's channels in a row; position component 0..2
-    float dmul, dfix;            // dp component = (pn - pc)*dmul + dfix  (block lane 3: the constant 1)
+    int N, K, KB, pw;
     int first, step, count, tiles_per_cloud;   // this workgroup's tiles: first + i*step, i < count
+    // compute layout: lane = (row group grp, lane t inside the row)
+    int grp, t;
+    bool lane_on;
+    unsigned lane_off;           // byte offset of the lane's channels in a row
+    int perm_id, perm_dp;        // ds_bpermute byte addresses of entry (k = 0, g) in the entry layout
+    // entry layout: lane = (entry e = lane>>2 of 16, component c = lane&3); register half h holds the
+    // entries 16h+e, entry i = (neighbour slot i>>2, point i&3)
+    int e_g, e_k;                // point and slot (within half 0) of this lane's entry
+    unsigned e_col;              // position component to read: x, y, z (lane 3 reads z, value unused)
+    float e_mul, e_fix;          // dp component = (pn - pc)*e_mul + e_fix   (component lane 3: the constant 1)
 
     __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *nbr_, int N_,
                                          int K_, int pw_, const TileSchedule &sc, int tiles_per_cloud_)
@@ -487,50 +500,64 @@ struct LeanProducer {
         grp = lane / S::LPR; t = lane % S::LPR;
         lane_on = (S::VEC * t) < S::DI;
         lane_off = lane_on ? 4u * S::VEC * t : 0u;       // lanes past the row read its start, value unused
-        const int dsel = lane & 3;
-        csel = dsel < 3 ? dsel : 2;
-        dmul = dsel < 3 ? 1.f : 0.f;
-        dfix = dsel < 3 ? 0.f : 1.f;
+        const int g = grp % G::PW, dsel = lane & 3;
+        perm_id = 4 * (4 * g);
+        perm_dp = 4 * (4 * g + dsel);
+        e_g = (lane >> 2) & 3;
+        e_k = lane >> 4;
+        const int c = lane & 3;
+        e_col = c < 3 ? c : 2;
+        e_mul = c < 3 ? 1.f : 0.f;
+        e_fix = c < 3 ? 0.f : 1.f;
         first = sc.first; step = sc.step; tiles_per_cloud = tiles_per_cloud_;
         count = (sc.first < sc.end) ? (sc.end - sc.first + sc.step - 1) / sc.step : 0;
     }
 
     struct Batch {
         int b;          // cloud
-        int l;          // this lane's point (clamped into the cloud)
+        int lw0;        // first point of this wave in the tile
         int k0;         // first neighbour slot
     };
     // batch m of this workgroup (m clamped to the last one)
     __device__ __forceinline__ Batch batch(int m) const
     {
-        const int last = count * KB - 1;
-        m = min(m, last);
+        m = min(m, count * KB - 1);
         const int i = m / KB;
         const int tile = first + i * step;
         Batch x;
         x.b = tile / tiles_per_cloud;
-        x.l = min((tile - x.b * tiles_per_cloud) * G::T + pw * G::PW + (grp % G::PW), N - 1);
+        x.lw0 = (tile - x.b * tiles_per_cloud) * G::T + pw * G::PW;
         x.k0 = (m - i * KB) * U;
         return x;
     }
 
-    __device__ __forceinline__ void load_ids(int (&id)[U], float &pc, const Batch &x) const
+    // entry layout: neighbour ids of both halves
+    __device__ __forceinline__ void load_ids(int (&id)[2], const Batch &x) const
     {
         const char *base = reinterpret_cast<const char *>(nbr + (int64_t)x.b * K * N);
-        const unsigned o = 4u * ((unsigned)x.k0 * (unsigned)N + (unsigned)x.l);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            id[u] = *reinterpret_cast<const int32_t *>(base + (o + 4u * (unsigned)u * (unsigned)N));
+        const unsigned l = (unsigned)min(x.lw0 + e_g, N - 1);
+        const unsigned o = 4u * ((unsigned)(x.k0 + e_k) * (unsigned)N + l);
+        id[0] = *reinterpret_cast<const int32_t *>(base + o);
+        id[1] = *reinterpret_cast<const int32_t *>(base + (o + 16u * (unsigned)N));
+    }
+    // entry layout: position component of the neighbours (both halves) and of the centre
+    __device__ __forceinline__ void load_pos(float (&pn)[2], float &pc, const int (&id)[2], const Batch &x) const
+    {
         const char *pb = reinterpret_cast<const char *>(pos + (int64_t)x.b * 3 * N);
-        pc = *reinterpret_cast<const float *>(pb + 4u * (csel * (unsigned)N + (unsigned)x.l));
+        const unsigned col = e_col * (unsigned)N;
+        pn[0] = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)id[0]));
+        pn[1] = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)id[1]));
+        pc = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)min(x.lw0 + e_g, N - 1)));
+    }
+    // entry layout -> compute layout: value of entry (slot u, this lane's point), component lane `base`
+    __device__ __forceinline__ int spread(const int (&v)[2], int base, int u) const
+    {
+        return __builtin_amdgcn_ds_bpermute(base + 64 * (u & 3), v[u >> 2]);
     }
 
-    __device__ __forceinline__ void load_row(float (&fr)[S::VEC], float &pnr, int id, const char *rb,
-                                             const char *pb) const
+    __device__ __forceinline__ void load_row(float (&fr)[S::VEC], int id, const char *rb) const
     {
-        const unsigned n = (unsigned)id;
-        pnr = *reinterpret_cast<const float *>(pb + 4u * (csel * (unsigned)N + n));
-        const char *p = rb + (n * (4u * S::DI) + lane_off);
+        const char *p = rb + ((unsigned)id * (4u * S::DI) + lane_off);
         if constexpr (S::VEC == 4) {
             const v4f v = *reinterpret_cast<const v4f *>(p);
             fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
@@ -543,19 +570,19 @@ struct LeanProducer {
     __device__ __forceinline__ void run(char *s_A, int *s_E)
     {
         if (count == 0) return;
-        float f[U][S::VEC], pn[U];
-        int idn[U];              // ids of the batch after the one whose rows are in flight
-        float pc_cur, pc_rows, pc_ids;   // centre component: batch being accumulated / in flight / of idn
+        float f[U][S::VEC];      // rows in flight (compute layout)
+        int idn[2];              // entry layout: ids of the batch after the one whose rows are in flight
+        float pn[2], pc;         // entry layout: positions for the batch whose rows are in flight
         {
-            // prologue: rows of batch 0 in flight, ids of batch 1 requested
-            int id0[U];
+            // prologue: rows and positions of batch 0 in flight, ids of batch 1 requested
+            int id0[2];
             const Batch x0 = batch(0);
-            load_ids(id0, pc_rows, x0);
-            load_ids(idn, pc_ids, batch(1));
+            load_ids(id0, x0);
+            load_ids(idn, batch(1));
+            load_pos(pn, pc, id0, x0);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * S::DI);
-            const char *pb = reinterpret_cast<const char *>(pos + (int64_t)x0.b * 3 * N);
 #pragma unroll
-            for (int u = 0; u < U; ++u) load_row(f[u], pn[u], id0[u], rb, pb);
+            for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
         }
         const int total = count * KB;
         int kb = 0, tile_i = 0;
@@ -564,26 +591,29 @@ struct LeanProducer {
         for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
 
         for (int m = 0; m < total; ++m) {
-            // ids of batch m+1 are here; those of batch m+2 go in flight
+            // position differences of batch m, entry layout -> this lane's component per slot
+            int dpe[2];
+            dpe[0] = __float_as_int(fmaf(pn[0] - pc, e_mul, e_fix));
+            dpe[1] = __float_as_int(fmaf(pn[1] - pc, e_mul, e_fix));
+            // ids of batch m+1 are here: their positions and (below) rows go in flight; ids of batch m+2 too
+            const Batch x1 = batch(m + 1);
             int idc[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) idc[u] = idn[u];
-            pc_cur = pc_rows;
-            pc_rows = pc_ids;
-            const Batch x1 = batch(m + 1);
-            load_ids(idn, pc_ids, batch(m + 2));
+            for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
+            load_pos(pn, pc, idn, x1);
+            load_ids(idn, batch(m + 2));
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * S::DI);
-            const char *pb = reinterpret_cast<const char *>(pos + (int64_t)x1.b * 3 * N);
+            float dpc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) dpc[u] = __int_as_float(spread(dpe, perm_dp, u));
 
-            const float c = dfix - pc_cur * dmul;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float dpc = fmaf(pn[u], dmul, c);
                 float fv[S::VEC];
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                fma_row<S>(acc, dpc, fv);
-                load_row(f[u], pn[u], idc[u], rb, pb);     // row u of batch m+1 takes the freed registers
+                fma_row<S>(acc, dpc[u], fv);
+                load_row(f[u], idc[u], rb);     // row u of batch m+1 takes the freed registers
             }
 
             if (++kb == KB) {
@@ -600,17 +630,6 @@ struct LeanProducer {
     }
 };
 
-// ---------------------------------------------------------------------------
-// out[l][:] = A[l][:] * ThetaP   (forward; grad_feat when CSR)
-//
-// F16 == true (the default): the contraction runs on the f16 matrix cores in split-half
-// form (three v_mfma_f32_16x16x32_f16 per 16x16x32 block: hi*hi, lo*hi, hi*lo, fp32
-// accumulation).  On gfx950 the fp32 matrix op shares the vector ALU's data path, so a
-// consumer wave contracting in fp32 stalls the producers' vector work on the same SIMD;
-// the f16 matrix pipe runs beside it.  thetaP is then the fragment buffer written by
-// pack_theta_f16_kernel and theta_exp_off the byte offset of its exponent.
-// F16 == false: fp32 matrix op on the fp32 ThetaP (kept for comparison).
-// ---------------------------------------------------------------------------
 // One consumer wave of the split-half contraction: out tile = A tile * Theta for every tile of
 // the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
 template <class S, class G, bool OUT_BCN>
