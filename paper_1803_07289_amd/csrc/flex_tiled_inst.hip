@@ -119,6 +119,18 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     const int grid = persistent_grid(total, WG_PER_CU);
     *n_wg = grid;
 #if FLEX_WS
+    if constexpr (S::WAVES == 4 && S::T == 16) {
+        // lean producers + bf16 matrix cores: fixed-K tensor in whole batches of 8, 32-bit offsets in a cloud
+        using WL = WsGeom<S, 2>;
+        if (!contract_in_fp32() && lean_producer_mode() != 0 && (K % 8 == 0) &&
+            (int64_t)K * N * 4 < (1ll << 32) && (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32)) {
+            const int tpc = (N + WL::T - 1) / WL::T;
+            const int tot = B * tpc;
+            *n_wg = persistent_grid(tot, 1);
+            hipLaunchKernelGGL((grad_theta_lean_kernel<S>), dim3(*n_wg), dim3(WL::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
+            return hipGetLastError();
+        }
+    }
     {
         using W = WsGeom<S>;
         if ((int64_t)W::PW * K <= W::EW) {

@@ -566,8 +566,19 @@ struct LeanProducer {
         }
     }
 
-    // the producer role for every tile of this workgroup
-    __device__ __forceinline__ void run(char *s_A, int *s_E)
+    // cloud and first point (of this wave) of the workgroup's tile i, i clamped to the last one
+    __device__ __forceinline__ void tile_coords(int i, int &b, int &lw0) const
+    {
+        const int tile = first + min(i, count - 1) * step;
+        b = tile / tiles_per_cloud;
+        lw0 = (tile - b * tiles_per_cloud) * G::T + pw * G::PW;
+    }
+
+    // The producer role for every tile of this workgroup.  fin(acc, i) parks the finished aggregate of
+    // the workgroup's tile i (this lane: channels VEC*t.. of point pw*PW+grp, all four j) in LDS; the
+    // workgroup barrier that hands the tile to the consumers follows it.
+    template <class Fin>
+    __device__ __forceinline__ void run(Fin &&fin)
     {
         if (count == 0) return;
         float f[U][S::VEC];      // rows in flight (compute layout)
@@ -618,13 +629,11 @@ struct LeanProducer {
 
             if (++kb == KB) {
                 kb = 0;
-                const int P = tile_i & 1;
-                store_split_rows<S>(acc, s_A + P * (G::T * G::ROWB), s_E + P * G::T, pw * G::PW + grp, t,
-                                    grp < G::PW && (S::VEC * t) < S::DIP);
+                fin(acc, tile_i);
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
                 ++tile_i;
-                __syncthreads();        // tile complete in buffer P
+                __syncthreads();        // tile complete in buffer tile_i & 1
             }
         }
     }
@@ -757,7 +766,11 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
     if (w < G::NP) {
         LeanProducer<S, PM> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
-        P.run(s_A, s_E);
+        P.run([&](const v4f (&acc)[S::VEC], int i) {
+            const int buf = i & 1;
+            store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
+                                P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+        });
         return;
     }
     consumer_f16<S, G, OUT_BCN>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
@@ -975,6 +988,204 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
 #pragma unroll
                 for (int a = 0; a < NBW; ++a)
                     acc[c][a] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[c], gf[a], acc[c][a], 0, 0, 0);
+        }
+    }
+
+    float *dst = partials + (int64_t)blockIdx.x * S::KD * S::DOP;
+#pragma unroll
+    for (int c = 0; c < MBW; ++c) {
+        const int mb = wm + c * WM;
+        if (mb >= MB) continue;
+#pragma unroll
+        for (int a = 0; a < NBW; ++a) {
+            const int nb = wn + a * WN;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                dst[(int64_t)(mb * 16 + 4 * q + i) * S::DOP + nb * 16 + r16] = acc[c][a][i];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Parameter gradients with the lean producers and the bf16 matrix cores.
+//   partial[kd][o] = sum over the workgroup's points of A[pt][kd] * g[pt][o]
+// contracts over POINTS, so no per-point scaling can be taken out of the sum; instead every
+// fp32 value is carried as three bf16 pieces by truncation (x = h + m + l exactly: 3 x 8
+// significand bits, bf16 has fp32's exponent range, nothing to scale) and six products
+// h*h, h*m, m*h, h*l, l*h, m*m go through v_mfma_f32_16x16x32_bf16 (dropped terms ~2^-24).
+// Both tiles sit point-major in LDS, [pt][h: W][m: W][l: W] bf16; the matrix operands want
+// 8 consecutive points per lane, which ds_read_b64_tr_b16 delivers: in a group of 16 lanes,
+// lane i supplies the address of 4 consecutive columns of one row and lane j receives
+// column j%4 of the rows supplied by lanes j/4, j/4+4, j/4+8, j/4+12.
+// Eight producer waves (32-point tiles) feed four consumer waves that keep a 2x2 split of
+// the (4*Din x Dout) partial in accumulators over the whole persistent loop.
+// ---------------------------------------------------------------------------
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+// row stride of a three-piece bf16 tile of W columns: = 32 mod 128 bytes, so the four rows one
+// 16-lane group reads (32 bytes each) and the rows four lane groups write fall on distinct banks
+constexpr int bf3_stride(int W) { return 6 * W + ((32 - (6 * W) % 128) + 128) % 128; }
+
+// x -> (h, m, l) by truncation, two values at a time, packed as bf16 pairs (first value low)
+__device__ __forceinline__ void split_bf3(float x0, float x1, unsigned &h, unsigned &m, unsigned &l)
+{
+    const unsigned b0 = __float_as_uint(x0), b1 = __float_as_uint(x1);
+    const float r0 = x0 - __uint_as_float(b0 & 0xffff0000u), r1 = x1 - __uint_as_float(b1 & 0xffff0000u);
+    const unsigned c0 = __float_as_uint(r0), c1 = __float_as_uint(r1);
+    const float s0 = r0 - __uint_as_float(c0 & 0xffff0000u), s1 = r1 - __uint_as_float(c1 & 0xffff0000u);
+    h = (b0 >> 16) | (b1 & 0xffff0000u);
+    m = (c0 >> 16) | (c1 & 0xffff0000u);
+    l = (__float_as_uint(s0) >> 16) | (__float_as_uint(s1) & 0xffff0000u);
+}
+
+// operand fragment: 8 consecutive points (p0..p0+7 given by the lane's group) of column col0 + lane%16
+__device__ __forceinline__ bf8 read_tr_frag(const char *tile, int stride, int p0, int byte_col0, int j16)
+{
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+    const char *a = tile + (p0 + (j16 >> 2)) * stride + byte_col0 + 8 * (j16 & 3);
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(__attribute__((address_space(3))) char *)a);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(__attribute__((address_space(3))) char *)(a + 4 * stride));
+    const v8s v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf8, v);
+}
+
+template <class S>
+__global__ __launch_bounds__((WsGeom<S, 2>::NT)) __attribute__((amdgpu_waves_per_eu(3, 4)))
+void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                            const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
+                            float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles)
+{
+    using G = WsGeom<S, 2>;
+    static_assert(G::T == 32, "one 32-point depth step of the matrix op per tile");
+    constexpr int AS = bf3_stride(S::KD), GS = bf3_stride(S::DOP);
+    __shared__ __attribute__((aligned(16))) char s_A[2][G::T * AS];
+    __shared__ __attribute__((aligned(16))) char s_G[2][G::T * GS];
+
+    const int w = threadIdx.x >> 6;
+    const TileSchedule sc(total_tiles);
+
+    if (w < G::NP) {
+        LeanProducer<S, 2> P;
+        P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
+        // grad_out tile: T*DOP/4 four-float chunks over the producer threads, one tile ahead in registers
+        constexpr int CPR = S::DOP / 4;                      // chunks per point
+        constexpr int NCH = cdiv_c(G::T * CPR, 64 * G::NP);  // chunks per thread
+        v4f gv[NCH];
+        auto load_g = [&](int i) {
+            int b, lw0;
+            P.tile_coords(i, b, lw0);
+            const int l0 = lw0 - P.pw * G::PW;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int ch = threadIdx.x + c * 64 * G::NP;
+                const int pt = ch / CPR, o = 4 * (ch % CPR);
+                gv[c] = v4f{0.f, 0.f, 0.f, 0.f};
+                if (ch < G::T * CPR && l0 + pt < N) {        // points past the cloud contribute nothing
+                    const float *src = g_rows + ((int64_t)b * N + l0 + pt) * S::DO + o;
+                    if constexpr (S::DO % 4 == 0) {
+                        if (o < S::DO) gv[c] = *reinterpret_cast<const v4f *>(src);
+                    } else {
+#pragma unroll
+                        for (int i2 = 0; i2 < 4; ++i2)
+                            if (o + i2 < S::DO) gv[c][i2] = src[i2];
+                    }
+                }
+            }
+        };
+        if (P.count > 0) load_g(0);
+        P.run([&](const v4f (&acc)[S::VEC], int i) {
+            const int buf = i & 1;
+            // aggregate rows, three bf16 pieces
+            if (P.grp < G::PW && (S::VEC * P.t) < S::DIP) {
+                char *row = s_A[buf] + (P.pw * G::PW + P.grp) * AS + 2 * S::VEC * P.t;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    char *d = row + 2 * jj * S::DIP;
+                    if constexpr (S::VEC == 4) {
+                        unsigned h0, m0, l0, h1, m1, l1;
+                        split_bf3(acc[0][jj], acc[1][jj], h0, m0, l0);
+                        split_bf3(acc[2][jj], acc[3][jj], h1, m1, l1);
+                        *reinterpret_cast<uint2 *>(d) = make_uint2(h0, h1);
+                        *reinterpret_cast<uint2 *>(d + 2 * S::KD) = make_uint2(m0, m1);
+                        *reinterpret_cast<uint2 *>(d + 4 * S::KD) = make_uint2(l0, l1);
+                    } else {
+                        unsigned h, m, l;
+                        split_bf3(acc[0][jj], 0.f, h, m, l);
+                        *reinterpret_cast<unsigned short *>(d) = (unsigned short)h;
+                        *reinterpret_cast<unsigned short *>(d + 2 * S::KD) = (unsigned short)m;
+                        *reinterpret_cast<unsigned short *>(d + 4 * S::KD) = (unsigned short)l;
+                    }
+                }
+            }
+            // grad_out rows of this tile (requested one tile ago), then the next tile's go in flight
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int ch = threadIdx.x + c * 64 * G::NP;
+                if (ch < G::T * CPR) {
+                    char *d = s_G[buf] + (ch / CPR) * GS + 2 * 4 * (ch % CPR);
+                    unsigned h0, m0, l0, h1, m1, l1;
+                    split_bf3(gv[c][0], gv[c][1], h0, m0, l0);
+                    split_bf3(gv[c][2], gv[c][3], h1, m1, l1);
+                    *reinterpret_cast<uint2 *>(d) = make_uint2(h0, h1);
+                    *reinterpret_cast<uint2 *>(d + 2 * S::DOP) = make_uint2(m0, m1);
+                    *reinterpret_cast<uint2 *>(d + 4 * S::DOP) = make_uint2(l0, l1);
+                }
+            }
+            load_g(i + 1);
+        });
+        return;
+    }
+
+    // ---- consumer: owns MBW x NBW 16x16 blocks of the (KD x DOP) partial ----
+    constexpr int MB = S::KD / 16, NB2 = S::DOP / 16;
+    constexpr int WN = (NB2 >= 2) ? 2 : 1;
+    static_assert(G::NC % WN == 0 && NB2 % WN == 0, "wave grid");
+    constexpr int WM = G::NC / WN;
+    constexpr int NBW = NB2 / WN;
+    constexpr int MBW = cdiv_c(MB, WM);
+    const int cw = w - G::NP;
+    const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
+    const int wn = cw % WN, wm = cw / WN;
+
+    v4f acc[MBW][NBW];
+#pragma unroll
+    for (int c = 0; c < MBW; ++c)
+#pragma unroll
+        for (int a = 0; a < NBW; ++a) acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    for (int k = 0;; ++k) {
+        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+        if (!r.valid) break;
+        __syncthreads();
+        const char *sA = s_A[k & 1], *sG = s_G[k & 1];
+        bf8 gH[NBW], gM[NBW], gL[NBW];
+#pragma unroll
+        for (int a = 0; a < NBW; ++a) {
+            const int col = 2 * 16 * (wn + a * WN);
+            gH[a] = read_tr_frag(sG, GS, 8 * q, col, r16);
+            gM[a] = read_tr_frag(sG, GS, 8 * q, col + 2 * S::DOP, r16);
+            gL[a] = read_tr_frag(sG, GS, 8 * q, col + 4 * S::DOP, r16);
+        }
+#pragma unroll
+        for (int c = 0; c < MBW; ++c) {
+            const int mb = wm + c * WM;
+            if (mb >= MB) continue;
+            const int col = 2 * 16 * mb;
+            const bf8 aH = read_tr_frag(sA, AS, 8 * q, col, r16);
+            const bf8 aM = read_tr_frag(sA, AS, 8 * q, col + 2 * S::KD, r16);
+            const bf8 aL = read_tr_frag(sA, AS, 8 * q, col + 4 * S::KD, r16);
+#define FLEX_BF_MFMA(X, Y)                                                                         \
+    _Pragma("unroll") for (int a = 0; a < NBW; ++a)                                               \
+        acc[c][a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(X, Y[a], acc[c][a], 0, 0, 0)
+            FLEX_BF_MFMA(aL, gH);   // small terms first
+            FLEX_BF_MFMA(aH, gL);
+            FLEX_BF_MFMA(aM, gM);
+            FLEX_BF_MFMA(aM, gH);
+            FLEX_BF_MFMA(aH, gM);
+            FLEX_BF_MFMA(aH, gH);
+#undef FLEX_BF_MFMA
         }
     }
 
