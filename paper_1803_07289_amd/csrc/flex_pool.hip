@@ -24,6 +24,8 @@ __device__ __forceinline__ int64_t xcd_tile(int64_t total_tiles)
 static inline unsigned xcd_grid(int64_t total_tiles) { return (unsigned)(((total_tiles + 7) >> 3) << 3); }
 
 // Point-major, C % 4 == 0: one thread per (point, 4 channels); a block owns PT consecutive points.
+// The gather is latency-bound, so a thread first requests the ids of 8 neighbours, then their 8
+// rows (16 bytes each), and only then compares: 8 rows per lane are in flight instead of one.
 __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restrict__ feat,
                                                             const int32_t *__restrict__ nbr,
                                                             float *__restrict__ out,
@@ -31,6 +33,7 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
                                                             int N, int K, int C4, int PT,
                                                             int64_t total_tiles)
 {
+    constexpr int U = 8;
     const int64_t tile = xcd_tile(total_tiles);
     if (tile < 0) return;
     for (int i = threadIdx.x; i < PT * C4; i += 256) {
@@ -40,17 +43,26 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
         const int b = (int)(gp / N), l = (int)(gp % N);
         const int32_t *nb = nbr + (int64_t)b * K * N + l;
         const v4f *rows = reinterpret_cast<const v4f *>(feat) + (int64_t)b * N * C4 + c4;
-        int n = nb[0];
-        const v4f first = rows[(int64_t)n * C4];
-        float v0 = first.x, v1 = first.y, v2 = first.z, v3 = first.w;
-        int b0 = n, b1 = n, b2 = n, b3 = n;
-        for (int k = 1; k < K; ++k) {
-            n = nb[(int64_t)k * N];
-            const v4f v = rows[(int64_t)n * C4];
-            take(v.x, n, v0, b0);
-            take(v.y, n, v1, b1);
-            take(v.z, n, v2, b2);
-            take(v.w, n, v3, b3);
+        float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+        int b0 = 0, b1 = 0, b2 = 0, b3 = 0;
+        for (int k0 = 0; k0 < K; k0 += U) {
+            int n[U];
+            v4f v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) n[u] = nb[(int64_t)min(k0 + u, K - 1) * N];   // past K: the last slot again
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = rows[(int64_t)n[u] * C4];
+            if (k0 == 0) {
+                v0 = v[0].x; v1 = v[0].y; v2 = v[0].z; v3 = v[0].w;
+                b0 = b1 = b2 = b3 = n[0];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {      // a repeated (value, index) pair never changes the winner
+                take(v[u].x, n[u], v0, b0);
+                take(v[u].y, n[u], v1, b1);
+                take(v[u].z, n[u], v2, b2);
+                take(v[u].w, n[u], v3, b3);
+            }
         }
         const v4f bv = {v0, v1, v2, v3};
         reinterpret_cast<v4f *>(out)[gp * C4 + c4] = bv;
@@ -123,11 +135,15 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const float *__restrict__
 // Gather form of the backward pass over in-edge lists (sorted, so repeats are adjacent; no
 // atomics, fixed summation order):
 // grad_feat[m][c] = sum over centres l that list m of (argmax[l][c] == m ? grad_out[l][c] : 0).
+// Entries are taken four at a time: their ids first, then the eight rows (winner table and
+// gradient), so that a lane has 128 bytes in flight instead of 32 (eight at a time is slower:
+// the mean in-degree is K, so most of a second batch would be padding).
 __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
     float *__restrict__ grad_feat, int64_t BN, int N, int C4, int PT, int64_t total_tiles)
 {
+    constexpr int U = 4;
     const int64_t tile = xcd_tile(total_tiles);
     if (tile < 0) return;
     for (int i = threadIdx.x; i < PT * C4; i += 256) {
@@ -139,18 +155,26 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
         const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + b * N * C4 + c4;
         const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + b * N * C4 + c4;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
-        const int e1 = in_off[gp + 1];
+        const int e0 = in_off[gp], e1 = in_off[gp + 1];
         int prev = -1;
-        for (int e = in_off[gp]; e < e1; ++e) {
-            const int64_t l = in_src[e];
-            if ((int)l == prev) continue;     // a centre that lists m twice still routes one gradient
-            prev = (int)l;
-            const int4 a = a4[l * C4];
-            const v4f g = g4[l * C4];
-            acc.x += (a.x == m) ? g.x : 0.f;
-            acc.y += (a.y == m) ? g.y : 0.f;
-            acc.z += (a.z == m) ? g.z : 0.f;
-            acc.w += (a.w == m) ? g.w : 0.f;
+        for (int e = e0; e < e1; e += U) {
+            int l[U];
+            int4 a[U];
+            v4f g[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) l[u] = in_src[min(e + u, e1 - 1)];     // past the end: the last entry again
+#pragma unroll
+            for (int u = 0; u < U; ++u) { a[u] = a4[(int64_t)l[u] * C4]; g[u] = g4[(int64_t)l[u] * C4]; }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // a centre that lists m twice (adjacent entries, also the repeats past the end) routes one gradient
+                const bool fresh = l[u] != prev;
+                prev = l[u];
+                acc.x += (fresh && a[u].x == m) ? g[u].x : 0.f;
+                acc.y += (fresh && a[u].y == m) ? g[u].y : 0.f;
+                acc.z += (fresh && a[u].z == m) ? g[u].z : 0.f;
+                acc.w += (fresh && a[u].w == m) ? g[u].w : 0.f;
+            }
         }
         reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4] = acc;
     }
