@@ -28,6 +28,10 @@
 #pragma once
 #include "flex_tiled.hpp"
 
+#ifndef FLEX_LEAN_VALU_AGG
+#define FLEX_LEAN_VALU_AGG 1
+#endif
+
 namespace flex {
 
 template <class S, int PM = 1>
@@ -476,6 +480,10 @@ struct LeanProducer {
     static constexpr int U = 8;
     static constexpr bool FULL = (S::LPR * S::VEC == S::DI);   // every lane of a group reads real channels
     static_assert(G::PW == 4, "entry layout below: 4 points x 8 neighbours per batch");
+    // The aggregate runs on the vector ALU: the fp32 4x4x1 matrix op would need fewer issue slots, but
+    // it holds both the vector ALU and the f16/bf16 matrix pipe of the SIMD while it executes, so the
+    // consumers' matrix ops could never overlap the producers' work.
+    static constexpr bool VALU_AGG = FLEX_LEAN_VALU_AGG;
 
     const float *rows, *pos;
     const int32_t *nbr;
@@ -623,7 +631,19 @@ struct LeanProducer {
                 float fv[S::VEC];
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                fma_row<S>(acc, dpc[u], fv);
+                if constexpr (VALU_AGG) {
+                    // the four lanes of a block hold (dx, dy, dz, 1): broadcast inside the quad
+                    const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
+#pragma unroll
+                    for (int v = 0; v < S::VEC; ++v) {
+                        acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                        acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                        acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                        acc[v][3] += fv[v];
+                    }
+                } else {
+                    fma_row<S>(acc, dpc[u], fv);
+                }
                 load_row(f[u], idc[u], rb);     // row u of batch m+1 takes the freed registers
             }
 
