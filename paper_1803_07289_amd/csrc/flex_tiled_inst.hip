@@ -76,6 +76,26 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
 #undef FLEX_LEAN_ARGS
                 return hipGetLastError();
             }
+            // feature gradient: lean in-edge producers under the same conditions
+            const bool lean_csr = csr && theta_fmt && lean_producer_mode() != 0 &&
+                                  (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32);
+            if (lean_csr) {
+                constexpr bool WIDE_OK = (S::WAVES * 4 <= 16) && (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
+                constexpr int PMX = WIDE_OK ? 3 : 1;
+                const bool wide = PMX > 1 && lean_producer_mode() != 1;
+                using WL = WsGeom<S, PMX>;
+                const int tl = wide ? WL::T : W::T;
+                const int tpcl = (N + tl - 1) / tl;
+                const int totl = B * tpcl;
+                const dim3 gl(persistent_grid(totl, wide ? WL::WG_PER_CU : W::WG_PER_CU)), bl(wide ? WL::NT : W::NT);
+#define FLEX_LEAN_ARGS rows, pos, off, src, thetaP, exp_off, out, N, tpcl, totl
+                if (wide && !out_bcn) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+                else if (wide) hipLaunchKernelGGL((grad_feat_lean_kernel<S, true, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+                else if (!out_bcn) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+                else hipLaunchKernelGGL((grad_feat_lean_kernel<S, true, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+#undef FLEX_LEAN_ARGS
+                return hipGetLastError();
+            }
             if (!csr && !out_bcn) FLEX_WS_LAUNCH(false, false);
             else if (!csr && out_bcn) FLEX_WS_LAUNCH(false, true);
             else if (csr && !out_bcn) FLEX_WS_LAUNCH(true, false);

@@ -659,6 +659,211 @@ struct LeanProducer {
     }
 };
 
+// ---------------------------------------------------------------------------
+// Lean producer over in-edge lists (feature gradient): the rows are grad_out rows of the
+// centres that list a point, dp = pos[point] - pos[centre].  Same machinery as LeanProducer
+// (entry-layout loads, ds_bpermute spread, rolling 8-row window, vector-ALU aggregate); a
+// batch is list slots 8*bi .. 8*bi+7 of each of the wave's 4 points, a tile takes
+// max(1, ceil(longest list / 8)) batches, which differs from wave to wave and tile to tile.
+// Slots past a list's end gather the point's own row with dp = (0,0,0,0), i.e. add nothing.
+// The list bounds of the next tile are requested when a wave's id cursor enters a tile.
+// ---------------------------------------------------------------------------
+template <class S, int PM>
+struct LeanCsrProducer {
+    using G = WsGeom<S, PM>;
+    static constexpr int U = 8;
+    static constexpr bool FULL = (S::LPR * S::VEC == S::DI);
+    static_assert(G::PW == 4, "entry layout: 4 points x 8 list slots per batch");
+
+    const float *rows, *pos;
+    const int32_t *off, *src;
+    int N, pw;
+    int first, step, count, tiles_per_cloud;
+    int grp, t;
+    bool lane_on;
+    unsigned lane_off;
+    int perm_id, perm_dp;
+    int e_g, e_k;
+    unsigned e_col;
+    float e_mul, e_fix;
+
+    __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *off_,
+                                         const int32_t *src_, int N_, int pw_, const TileSchedule &sc,
+                                         int tiles_per_cloud_)
+    {
+        rows = rows_; pos = pos_; off = off_; src = src_; N = N_; pw = pw_;
+        const int lane = threadIdx.x & 63;
+        grp = lane / S::LPR; t = lane % S::LPR;
+        lane_on = (S::VEC * t) < S::DI;
+        lane_off = lane_on ? 4u * S::VEC * t : 0u;
+        const int g = grp % G::PW, dsel = lane & 3;
+        perm_id = 4 * (4 * g);
+        perm_dp = 4 * (4 * g + dsel);
+        e_g = (lane >> 2) & 3;
+        e_k = lane >> 4;
+        const int c = lane & 3;
+        e_col = c < 3 ? c : 2;
+        e_mul = c < 3 ? 1.f : 0.f;
+        e_fix = c < 3 ? 0.f : 1.f;
+        first = sc.first; step = sc.step; tiles_per_cloud = tiles_per_cloud_;
+        count = (sc.first < sc.end) ? (sc.end - sc.first + sc.step - 1) / sc.step : 0;
+    }
+
+    // what the later pipeline stages need to know about a batch
+    struct Desc {
+        int b, lw0;      // cloud, first point of this wave in the tile
+        bool last;       // last batch of its tile: the aggregate is complete after it
+        bool real;       // false past the workgroup's last tile (loaded, never used)
+        int valid0, valid1;   // entry layout: does this lane's entry (half 0 / 1) exist
+    };
+
+    // walks the batches in order; entry-layout list bounds of the current and the next tile
+    struct Cursor {
+        int i, bi, nb;           // tile (index into the workgroup's tiles), batch in tile, batches of the tile
+        int b, lw0;
+        int lo, deg;             // this lane's point: start and length of its list
+        int lo_n, hi_n;          // next tile: list bounds of this lane's point (in flight)
+    };
+
+    __device__ __forceinline__ void tile_coords(int i, int &b, int &lw0) const
+    {
+        const int tile = first + min(i, count - 1) * step;
+        b = tile / tiles_per_cloud;
+        lw0 = (tile - b * tiles_per_cloud) * G::T + pw * G::PW;
+    }
+    __device__ __forceinline__ void request_bounds(int i, int &lo_n, int &hi_n) const
+    {
+        int b, lw0;
+        tile_coords(i, b, lw0);
+        const int64_t gp = (int64_t)b * N + min(lw0 + e_g, N - 1);
+        lo_n = off[gp];
+        hi_n = off[gp + 1];
+    }
+    // the cursor takes the bounds requested for tile i (they must be in lo_n / hi_n) and requests tile i+1's
+    __device__ __forceinline__ void enter_tile(Cursor &c, int i) const
+    {
+        c.i = i; c.bi = 0;
+        tile_coords(i, c.b, c.lw0);
+        c.lo = c.lo_n;
+        c.deg = (c.lw0 + e_g < N) ? c.hi_n - c.lo_n : 0;      // points past the cloud have no list
+        const int d = max(max(__builtin_amdgcn_readlane(c.deg, 0), __builtin_amdgcn_readlane(c.deg, 4)),
+                          max(__builtin_amdgcn_readlane(c.deg, 8), __builtin_amdgcn_readlane(c.deg, 12)));
+        c.nb = max(1, (d + U - 1) / U);
+        request_bounds(i + 1, c.lo_n, c.hi_n);
+    }
+    // entry-layout ids of the cursor's batch + its descriptor; then the cursor moves on
+    __device__ __forceinline__ void fetch(Cursor &c, int (&id)[2], Desc &d) const
+    {
+        d.b = c.b; d.lw0 = c.lw0;
+        d.real = c.i < count;
+        d.last = c.bi == c.nb - 1;
+        const int s0 = U * c.bi + e_k, s1 = s0 + 4;
+        d.valid0 = d.real && s0 < c.deg;
+        d.valid1 = d.real && s1 < c.deg;
+        const int self = min(c.lw0 + e_g, N - 1);
+        id[0] = self; id[1] = self;
+        if (d.valid0) id[0] = src[c.lo + s0];
+        if (d.valid1) id[1] = src[c.lo + s1];
+        if (++c.bi == c.nb) enter_tile(c, c.i + 1);
+    }
+    __device__ __forceinline__ void load_pos(float (&pn)[2], float &pc, const int (&id)[2], const Desc &d) const
+    {
+        const char *pb = reinterpret_cast<const char *>(pos + (int64_t)d.b * 3 * N);
+        const unsigned col = e_col * (unsigned)N;
+        pn[0] = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)id[0]));
+        pn[1] = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)id[1]));
+        pc = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)min(d.lw0 + e_g, N - 1)));
+    }
+    __device__ __forceinline__ int spread(const int (&v)[2], int base, int u) const
+    {
+        return __builtin_amdgcn_ds_bpermute(base + 64 * (u & 3), v[u >> 2]);
+    }
+    __device__ __forceinline__ void load_row(float (&fr)[S::VEC], int id, const char *rb) const
+    {
+        const char *p = rb + ((unsigned)id * (4u * S::DI) + lane_off);
+        if constexpr (S::VEC == 4) {
+            const v4f v = *reinterpret_cast<const v4f *>(p);
+            fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
+        } else {
+            fr[0] = *reinterpret_cast<const float *>(p);
+        }
+    }
+    // position difference of this lane's entries (point - centre), zero for missing entries
+    __device__ __forceinline__ void dp_entries(int (&dpe)[2], const float (&pn)[2], float pc, const Desc &d) const
+    {
+        dpe[0] = d.valid0 ? __float_as_int(fmaf(pc - pn[0], e_mul, e_fix)) : 0;
+        dpe[1] = d.valid1 ? __float_as_int(fmaf(pc - pn[1], e_mul, e_fix)) : 0;
+    }
+
+    template <class Fin>
+    __device__ __forceinline__ void run(Fin &&fin)
+    {
+        if (count == 0) return;
+        float f[U][S::VEC];      // rows of the batch being accumulated / next batch (compute layout)
+        int idn[2];              // entry layout: ids of the batch after the one whose rows are in flight
+        float pn[2], pc;         // entry layout: positions for the batch whose rows are in flight
+        Desc d0, d1;             // batch whose rows are in flight; batch of idn
+        Cursor c;
+        {
+            request_bounds(0, c.lo_n, c.hi_n);
+            enter_tile(c, 0);
+            int id0[2];
+            fetch(c, id0, d0);
+            fetch(c, idn, d1);
+            load_pos(pn, pc, id0, d0);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * S::DI);
+#pragma unroll
+            for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
+        }
+        int tile_i = 0;
+        v4f acc[S::VEC];
+#pragma unroll
+        for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+
+        while (d0.real) {
+            int dpe[2];
+            dp_entries(dpe, pn, pc, d0);
+            const bool last = d0.last;
+            // batch d1: positions and (below) rows go in flight; the cursor's batch: ids
+            int idc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
+            load_pos(pn, pc, idn, d1);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * S::DI);
+            d0 = d1;
+            fetch(c, idn, d1);
+            float dpc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) dpc[u] = __int_as_float(spread(dpe, perm_dp, u));
+
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float fv[S::VEC];
+#pragma unroll
+                for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
+                const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
+                const float one = dpp_move<0xFF>(dpc[u]);    // 1 for a real entry, 0 for a missing one
+#pragma unroll
+                for (int v = 0; v < S::VEC; ++v) {
+                    acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                    acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                    acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                    acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                }
+                load_row(f[u], idc[u], rb);
+            }
+
+            if (last) {
+                fin(acc, tile_i);
+#pragma unroll
+                for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                ++tile_i;
+                __syncthreads();        // tile complete in buffer tile_i & 1
+            }
+        }
+    }
+};
+
 // One consumer wave of the split-half contraction: out tile = A tile * Theta for every tile of
 // the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
 template <class S, class G, bool OUT_BCN>
@@ -786,6 +991,43 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
     if (w < G::NP) {
         LeanProducer<S, PM> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
+        P.run([&](const v4f (&acc)[S::VEC], int i) {
+            const int buf = i & 1;
+            store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
+                                P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+        });
+        return;
+    }
+    consumer_f16<S, G, OUT_BCN>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
+}
+
+// Feature gradient with the lean in-edge producers (same consumers as the forward kernel).
+template <class S, bool OUT_BCN, int PM>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                           const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                           const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
+                           int N, int tiles_per_cloud, int total_tiles)
+{
+    using G = WsGeom<S, PM>;
+    __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
+    __shared__ int s_E[2 * G::T];
+
+    const int w = threadIdx.x >> 6;
+    const TileSchedule sc(total_tiles);
+
+    if constexpr (G::KDP > S::KD) {
+        constexpr int PADH = G::KDP - S::KD;
+        for (int i = threadIdx.x; i < 2 * G::T * 2 * PADH; i += G::NT) {
+            const int e = i % PADH, part = (i / PADH) & 1, row = i / (2 * PADH);
+            *reinterpret_cast<_Float16 *>(s_A + (row / G::T) * (G::T * G::ROWB) + (row % G::T) * G::ARS +
+                                          2 * (part * G::KDP + S::KD + e)) = (_Float16)0.f;
+        }
+    }
+
+    if (w < G::NP) {
+        LeanCsrProducer<S, PM> P;
+        P.init(rows, pos, off, src, N, w, sc, tiles_per_cloud);
         P.run([&](const v4f (&acc)[S::VEC], int i) {
             const int buf = i & 1;
             store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
