@@ -141,7 +141,7 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
 #if FLEX_WS
     if constexpr (S::WAVES == 4 && S::T == 16) {
         // lean producers + bf16 matrix cores: fixed-K tensor in whole batches of 8, 32-bit offsets in a cloud
-        using WL = WsGeom<S, 2>;
+        using WL = WsGeom<S, 2, 2>;
         if (!contract_in_fp32() && lean_producer_mode() != 0 && (K % 8 == 0) &&
             (int64_t)K * N * 4 < (1ll << 32) && (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32)) {
             const int tpc = (N + WL::T - 1) / WL::T;

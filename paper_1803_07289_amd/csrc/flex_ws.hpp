@@ -34,9 +34,9 @@
 
 namespace flex {
 
-template <class S, int PM = 1>
+template <class S, int PM = 1, int CM = 1>
 struct WsGeom {
-    static constexpr int NP = S::WAVES * PM, NC = S::WAVES;   // producer / consumer waves
+    static constexpr int NP = S::WAVES * PM, NC = S::WAVES * CM;   // producer / consumer waves
     static constexpr int NT = 64 * (NP + NC);
     static constexpr int WG_PER_CU = 16 / (NP + NC);
     static constexpr int T = S::T * PM;                  // points per tile
@@ -1279,7 +1279,7 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
 // 8 consecutive points per lane, which ds_read_b64_tr_b16 delivers: in a group of 16 lanes,
 // lane i supplies the address of 4 consecutive columns of one row and lane j receives
 // column j%4 of the rows supplied by lanes j/4, j/4+4, j/4+8, j/4+12.
-// Eight producer waves (32-point tiles) feed four consumer waves that keep a 2x2 split of
+// Eight producer waves (32-point tiles) feed eight consumer waves that keep a 4x2 split of
 // the (4*Din x Dout) partial in accumulators over the whole persistent loop.
 // ---------------------------------------------------------------------------
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
@@ -1314,12 +1314,12 @@ __device__ __forceinline__ bf8 read_tr_frag(const char *tile, int stride, int p0
 }
 
 template <class S>
-__global__ __launch_bounds__((WsGeom<S, 2>::NT)) __attribute__((amdgpu_waves_per_eu(3, 4)))
+__global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                             const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
                             float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles)
 {
-    using G = WsGeom<S, 2>;
+    using G = WsGeom<S, 2, 2>;
     static_assert(G::T == 32, "one 32-point depth step of the matrix op per tile");
     constexpr int AS = bf3_stride(S::KD), GS = bf3_stride(S::DOP);
     __shared__ __attribute__((aligned(16))) char s_A[2][G::T * AS];
@@ -1411,15 +1411,25 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
     const int wn = cw % WN, wm = cw / WN;
 
-    v4f acc[MBW][NBW];
+    // The matrix op's internal accumulation rounds toward zero, a bias that would grow with the
+    // thousands of tiles a workgroup sums; so its accumulators (acc) only ever hold FLUSH tiles and
+    // are then added to the running totals (tot) on the vector ALU, which rounds to nearest.
+    constexpr int FLUSH = 8;
+    v4f acc[MBW][NBW], tot[MBW][NBW];
 #pragma unroll
     for (int c = 0; c < MBW; ++c)
 #pragma unroll
-        for (int a = 0; a < NBW; ++a) acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int a = 0; a < NBW; ++a) { acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f}; tot[c][a] = v4f{0.f, 0.f, 0.f, 0.f}; }
 
     for (int k = 0;; ++k) {
         const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
         if (!r.valid) break;
+        if (k % FLUSH == 0 && k > 0) {
+#pragma unroll
+            for (int c = 0; c < MBW; ++c)
+#pragma unroll
+                for (int a = 0; a < NBW; ++a) { tot[c][a] += acc[c][a]; acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f}; }
+        }
         __syncthreads();
         const char *sA = s_A[k & 1], *sG = s_G[k & 1];
         bf8 gH[NBW], gM[NBW], gL[NBW];
@@ -1459,9 +1469,10 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
 #pragma unroll
         for (int a = 0; a < NBW; ++a) {
             const int nb = wn + a * WN;
+            const v4f sum = tot[c][a] + acc[c][a];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                dst[(int64_t)(mb * 16 + 4 * q + i) * S::DOP + nb * 16 + r16] = acc[c][a][i];
+                dst[(int64_t)(mb * 16 + 4 * q + i) * S::DOP + nb * 16 + r16] = sum[i];
         }
     }
 }
