@@ -19,7 +19,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense f16 / bf16 matrix
+# HBM bytes per launch of each entry point's kernel on the default workload (rocprofv3 counters,
+# profiles/flexconv_cfg4_hbm_traffic.md)
+MEASURED_TRAFFIC = {"fwd": 4.073e9, "bwd_params": 4.087e9, "bwd_feat": 4.094e9,
+                    "pool_fwd": 5.765e9, "pool_bwd": 5.953e9}
 
 
 def log(*a):
@@ -143,21 +147,25 @@ def main():
     pts = B * N
 
     # ---- rooflines (algorithmic, touched-once figures) ----------
-    # conv kernels: factored flops, all on the matrix pipe (aggregate 8*K*Din + contraction 2*4Din*Dout)
-    conv_flop_pt = 8 * K * Din + 2 * 4 * Din * Dout
-    conv_bytes_pt = {"fwd": 4 * Din + 12 + 4 * K + 4 * Dout,
-                     "bwd_params": 4 * Din + 12 + 4 * K + 4 * Dout,
-                     "bwd_feat": 4 * Dout + 12 + 4 * (K + 1) + 4 * Din}
-    pool_bytes_pt = {"pool_fwd": 4 * Din + 4 * K + 8 * Din, "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din}
-    kernel_of = {"fwd": "gather_contract_ws_kernel<.., false, ..> (flexconv_fwd)",
-                 "bwd_params": "grad_theta_ws_kernel (flexconv_bwd, parameter gradients)",
-                 "bwd_feat": "gather_contract_ws_kernel<.., true, ..> (flexconv_bwd, feature gradient)",
+    # Every kernel of the path is bound by HBM: the contractions run on the f16 / bf16 matrix cores in
+    # split form (3 resp. 6 matrix ops per fp32-equivalent product), whose time at the published dense
+    # peak (2.5 PFLOP/s) stays below the time the touched-once bytes need at 8 TB/s.
+    conv_flop_pt = 8 * K * Din + 2 * 4 * Din * Dout          # factored form, fp32-equivalent
+    issued_matrix_flop_pt = {"fwd": 3 * 2 * 4 * Din * Dout, "bwd_params": 6 * 2 * 4 * Din * Dout,
+                             "bwd_feat": 3 * 2 * 4 * Din * Dout}
+    bytes_pt = {"fwd": 4 * Din + 12 + 4 * K + 4 * Dout,
+                "bwd_params": 4 * Din + 12 + 4 * K + 4 * Dout,
+                "bwd_feat": 4 * Dout + 12 + 4 * (K + 1) + 4 * Din,
+                "pool_fwd": 4 * Din + 4 * K + 8 * Din,
+                "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din}
+    kernel_of = {"fwd": "gather_contract_lean_kernel (flexconv_fwd)",
+                 "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
+                 "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
                  "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
-    measured_traffic = {"fwd": 4.636e9, "bwd_params": 5.482e9, "bwd_feat": 4.842e9,
-                        "pool_fwd": 5.758e9, "pool_bwd": 5.945e9}
+    measured_traffic = MEASURED_TRAFFIC
     default_workload = (cfg.index == 4 and N == 7_000_000 and layout == fx.BNC and x.order == "morton")
 
     def roof(name):
@@ -165,21 +173,13 @@ def main():
         if ms <= 0:
             return None
         traffic = measured_traffic.get(name) if default_workload else None
-        if name in conv_bytes_pt:
-            tfl = conv_flop_pt * pts / (ms * 1e-3) / 1e12
-            gbs = conv_bytes_pt[name] * pts / (ms * 1e-3) / 1e9
-            t_mfma = conv_flop_pt * pts / (MFMA_F32_PEAK_TFLOPS * 1e12)
-            t_hbm = conv_bytes_pt[name] * pts / (HBM_PEAK_GBS * 1e9)
-            if t_mfma >= t_hbm:
-                r = {"bound": "mfma", "achieved": tfl, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tfl / MFMA_F32_PEAK_TFLOPS}
-            else:
-                r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
-            r["hbm_GBps_algorithmic"] = gbs
-        else:
-            gbs = pool_bytes_pt[name] * pts / (ms * 1e-3) / 1e9
-            r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
-        r.update({"traffic": traffic, "kernel": kernel_of[name], "kernel_ms": ms})
+        gbs = bytes_pt[name] * pts / (ms * 1e-3) / 1e9
+        r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+             "traffic": traffic, "kernel": kernel_of[name], "kernel_ms": ms}
+        if name in issued_matrix_flop_pt:
+            r["fp32_equivalent_TFLOPs"] = conv_flop_pt * pts / (ms * 1e-3) / 1e12
+            r["issued_matrix_TFLOPs"] = issued_matrix_flop_pt[name] * pts / (ms * 1e-3) / 1e12
+            r["issued_matrix_frac_of_f16_peak"] = r["issued_matrix_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
         return r
 
     rooflines = {n: roof(n) for n in OPS if op_ms[n]["mean"] > 1e-2}
