@@ -68,8 +68,9 @@ def test_null_and_shape_errors_precede_any_launch(L):
 
 def test_workspace_sizes(L):
     w = L.flexconv_workspace_bytes
-    assert w(0, 1, 4096, 8, 64, 64, 1) == 4 * 64 * 64 * 4                       # packed parameters only
-    assert w(0, 1, 4096, 8, 64, 64, 0) == 4 * 64 * 64 * 4 + 4096 * 64 * 4        # + transposed features
+    packed = 4 * 64 * 64 * 4 + 256       # parameters (fp32 form = both f16 halves) + the exponent's slot
+    assert w(0, 1, 4096, 8, 64, 64, 1) == packed                                 # packed parameters only
+    assert w(0, 1, 4096, 8, 64, 64, 0) == packed + 4096 * 64 * 4                 # + transposed features
     assert w(0, 1, 4096, 8, 5, 7, 0) == 256                                      # generic kernels need none
     assert w(2, 1, 4096, 8, 64, 64, 1) > w(1, 1, 4096, 8, 64, 64, 1) > 0
     assert w(0, 0, 4096, 8, 64, 64, 1) == 0 and w(9, 1, 4096, 8, 64, 64, 1) == 0
