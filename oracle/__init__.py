@@ -139,3 +139,31 @@ def flexpool_bwd(grad_out, argmax, l_range=None):
     _check(_load().oracle_flexpool_bwd(_p(grad_out), _p(argmax), _p(gf), B, N, C, int(l0), int(l1)),
            "oracle_flexpool_bwd")
     return gf
+
+
+def flexupsample_fwd(feat_small, sel, nbr, l_range=None):
+    """Flex-upsampling: feat_small [B,C,Ns], sel int32 [B,Ns] (indices in the larger layer),
+    nbr int32 [B,K,Nf].  Returns (out float32, argmax int32), both [B,C,L]."""
+    feat_small, sel, nbr = _f32(feat_small), _i32(sel), _i32(nbr)
+    B, C, Ns = feat_small.shape
+    _, K, Nf = nbr.shape
+    assert sel.shape == (B, Ns)
+    assert count_bad_neighbors(nbr, Nf) == 0
+    l0, l1 = (0, Nf) if l_range is None else l_range
+    out = np.zeros((B, C, l1 - l0), np.float32)
+    arg = np.zeros((B, C, l1 - l0), np.int32)
+    _check(_load().oracle_flexupsample_fwd(_p(feat_small), _p(sel), _p(nbr), _p(out), _p(arg),
+                                           B, Ns, Nf, K, C, int(l0), int(l1)), "oracle_flexupsample_fwd")
+    return out, arg
+
+
+def flexupsample_bwd(grad_out, argmax, sel):
+    """Returns grad_small float64 [B,C,Ns]."""
+    grad_out, argmax, sel = _f32(grad_out), _i32(argmax), _i32(sel)
+    B, C, Nf = grad_out.shape
+    Ns = sel.shape[1]
+    assert argmax.shape == (B, C, Nf) and sel.shape == (B, Ns)
+    gs = np.zeros((B, C, Ns), np.float64)
+    _check(_load().oracle_flexupsample_bwd(_p(grad_out), _p(argmax), _p(sel), _p(gs), B, Ns, Nf, C),
+           "oracle_flexupsample_bwd")
+    return gs

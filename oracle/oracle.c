@@ -49,7 +49,7 @@
  * (grad_feat of either layer) keep N columns and are ACCUMULATED into, so the
  * caller passes them zero-filled (the Python wrapper does).
  *
- * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * Parity pins: every function here (flex-upsampling included) is pinned by tests/test_oracle_*.py
  * (brute force via dense weight tensors, regular-grid reduction to ordinary
  * correlation incl. Prewitt and box blur, theta = 0, translation invariance,
  * finite differences, adjoint identities, grid max-pool).
@@ -300,5 +300,88 @@ int oracle_flexpool_bwd(const float *grad_out, const int32_t *argmax, double *gr
                 const int m = argmax[IDX3(b, c, l, C, N)];
                 grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out[IDX3(b, c, l, C, N)];
             }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Flex-upsampling forward (Sec. 4.1, last paragraph before the architecture): the
+ * features of the selected points are copied into the larger layer, every other
+ * point starts at zero, then flex-max-pooling runs over the larger layer's
+ * neighbourhoods.  sel[b,j] is the index, in the larger layer, of the smaller
+ * layer's point j (distinct within a cloud).  Taken in exactly those steps:
+ * a zero-filled [B,C,Nf] array, the copy, then the neighbourhood maximum with the
+ * pooling layer's tie rule (lowest point index; -0 == +0 ties).
+ * out / argmax are [B,C,L] for the centres [l_begin,l_end) of the larger layer;
+ * argmax holds larger-layer point indices.
+ * Returns 2 on bad sizes or a sel entry out of range, 3 on a repeated sel entry.
+ * ------------------------------------------------------------------------- */
+int oracle_flexupsample_fwd(const float *feat_small, const int32_t *sel, const int32_t *nbr,
+                            float *out, int32_t *argmax, int B, int Ns, int Nf, int K, int C,
+                            int l_begin, int l_end)
+{
+    if (!feat_small || !sel || !nbr || !out || !argmax) return 1;
+    if (B <= 0 || Ns <= 0 || Nf <= 0 || K <= 0 || C <= 0 || Ns > Nf) return 2;
+    if (l_begin < 0 || l_end > Nf || l_begin > l_end) return 2;
+    float *dense = (float *)calloc((size_t)B * C * Nf, sizeof(float));
+    unsigned char *taken = (unsigned char *)calloc((size_t)B * Nf, 1);
+    if (!dense || !taken) { free(dense); free(taken); return 6; }
+    int rc = 0;
+    for (int b = 0; b < B && rc == 0; ++b)
+        for (int j = 0; j < Ns; ++j) {
+            const int m = sel[(int64_t)b * Ns + j];
+            if (m < 0 || m >= Nf) { rc = 2; break; }
+            if (taken[(int64_t)b * Nf + m]) { rc = 3; break; }
+            taken[(int64_t)b * Nf + m] = 1;
+            for (int c = 0; c < C; ++c) dense[IDX3(b, c, m, C, Nf)] = feat_small[IDX3(b, c, j, C, Ns)];
+        }
+    if (rc == 0) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int b = 0; b < B; ++b)
+            for (int l = l_begin; l < l_end; ++l)
+                for (int c = 0; c < C; ++c) {
+                    int best = nbr[IDX3(b, 0, l, K, Nf)];
+                    float bv = dense[IDX3(b, c, best, C, Nf)];
+                    for (int k = 1; k < K; ++k) {
+                        const int n = nbr[IDX3(b, k, l, K, Nf)];
+                        const float v = dense[IDX3(b, c, n, C, Nf)];
+                        if (v > bv || (v == bv && n < best)) { bv = v; best = n; }
+                    }
+                    out[IDX3(b, c, l - l_begin, C, l_end - l_begin)] = bv;
+                    argmax[IDX3(b, c, l - l_begin, C, l_end - l_begin)] = best;
+                }
+    }
+    free(dense); free(taken);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------
+ * Flex-upsampling backward: the pooling step routes grad_out[b,c,l] to the winner
+ * recorded in argmax (a larger-layer point); the copy step hands a selected point's
+ * gradient to the smaller layer's point it came from, and the gradient of a point
+ * that was only zero-filled is dropped.
+ *   grad_small[b,c,j] = sum of grad_out[b,c,l] over centres l with argmax[b,c,l] = sel[b,j]
+ * grad_small is double [B,C,Ns], overwritten.
+ * ------------------------------------------------------------------------- */
+int oracle_flexupsample_bwd(const float *grad_out, const int32_t *argmax, const int32_t *sel,
+                            double *grad_small, int B, int Ns, int Nf, int C)
+{
+    if (!grad_out || !argmax || !sel || !grad_small) return 1;
+    if (B <= 0 || Ns <= 0 || Nf <= 0 || C <= 0 || Ns > Nf) return 2;
+    double *dense = (double *)calloc((size_t)B * C * Nf, sizeof(double));   /* gradient of the larger layer */
+    if (!dense) return 6;
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < C; ++c)
+            for (int l = 0; l < Nf; ++l) {
+                const int m = argmax[IDX3(b, c, l, C, Nf)];
+                if (m < 0 || m >= Nf) { free(dense); return 2; }
+                dense[IDX3(b, c, m, C, Nf)] += (double)grad_out[IDX3(b, c, l, C, Nf)];
+            }
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < Ns; ++j) {
+            const int m = sel[(int64_t)b * Ns + j];
+            if (m < 0 || m >= Nf) { free(dense); return 2; }
+            for (int c = 0; c < C; ++c) grad_small[IDX3(b, c, j, C, Ns)] = dense[IDX3(b, c, m, C, Nf)];
+        }
+    free(dense);
     return 0;
 }

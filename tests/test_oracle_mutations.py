@@ -9,6 +9,7 @@ import pytest
 import oracle
 import test_oracle_conv as tc
 import test_oracle_pool as tp
+import test_oracle_upsample as tu
 
 SRC = open(os.path.join(os.path.dirname(oracle.__file__), "oracle.c")).read()
 
@@ -22,6 +23,9 @@ BWD_PINS = [tc.test_bwd_bruteforce_dense, tc.test_bwd_finite_differences_full_ja
 POOL_PINS = [tp.test_pool_fwd_bruteforce_with_ties, tp.test_pool_fwd_invariants,
              tp.test_pool_fwd_k1_identity_and_constant_feature, tp.test_pool_bwd_bruteforce_and_mass,
              tp.test_pool_bwd_is_adjoint_of_selection]
+
+UP_PINS = [tu.test_upsample_fwd_bruteforce_with_ties, tu.test_upsample_fwd_is_zero_fill_then_pool,
+           tu.test_upsample_grid_is_zero_insertion_then_3x3_max, tu.test_upsample_bwd_bruteforce_mass_and_composition]
 
 # (name, text to replace, replacement, occurrence index or None for all, pins that must catch it)
 MUTATIONS = [
@@ -41,6 +45,11 @@ MUTATIONS = [
      "s += w * (double)grad_out[IDX3(b, o, n, Dout, N)];", 0, BWD_PINS),
     ("pool_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 0, POOL_PINS),
     ("pool_min_instead_of_max", "if (v > bv || (v == bv && n < best))", "if (v < bv || (v == bv && n < best))", 0, POOL_PINS),
+    ("upsample_copy_to_own_index", "dense[IDX3(b, c, m, C, Nf)] = feat_small[IDX3(b, c, j, C, Ns)];",
+     "dense[IDX3(b, c, j, C, Nf)] = feat_small[IDX3(b, c, j, C, Ns)];", 0, UP_PINS),
+    ("upsample_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 1, UP_PINS),
+    ("upsample_bwd_reads_own_index", "grad_small[IDX3(b, c, j, C, Ns)] = dense[IDX3(b, c, m, C, Nf)];",
+     "grad_small[IDX3(b, c, j, C, Ns)] = dense[IDX3(b, c, j, C, Nf)];", 0, UP_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
