@@ -53,7 +53,8 @@ typedef enum {
     FLEX_OP_CONV_FWD = 0,
     FLEX_OP_CONV_BWD = 1,       /* with caller-supplied in-edge lists */
     FLEX_OP_CONV_BWD_BUILD = 2, /* in-edge lists built inside the call */
-    FLEX_OP_INEDGES = 3
+    FLEX_OP_INEDGES = 3,
+    FLEX_OP_UPSAMPLE = 4        /* flexupsample_fwd / flex_validate_selection; N = points of the larger layer */
 } flex_op;
 
 /*
@@ -127,6 +128,39 @@ int flexpool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *arg
 int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
                  const int32_t *in_off, const int32_t *in_src,
                  int B, int N, int K, int C, int layout, void *stream);
+
+/*
+ * Flex-upsampling forward (Sec. 4.1): the features of the smaller layer's points are copied
+ * to their points in the larger layer, every other point of the larger layer starts at zero,
+ * and flex-max-pooling runs over the larger layer's neighbourhoods:
+ *   dense[b,c,m] = feat_small[b,c,j] if m = sel[b,j], else 0
+ *   out[b,c,l]   = max_k dense[b,c,nbr[b,k,l]],  argmax[b,c,l] = the winning larger-layer point
+ * (pooling's tie rule: lowest point index among the maxima; a zero-filled point can win).
+ * feat_small [B,C,Ns] or [B,Ns,C]; sel int32 [B,Ns], distinct indices in [0,Nf) per cloud
+ * (undefined result otherwise; flex_validate_selection checks); nbr int32 [B,K,Nf];
+ * out / argmax [B,C,Nf] or [B,Nf,C].  The zero-filled tensor is never materialised; the
+ * workspace (flexconv_workspace_bytes(FLEX_OP_UPSAMPLE, B, Nf, ...)) holds an inverse map.
+ */
+int flexupsample_fwd(const float *feat_small, const int32_t *sel, const int32_t *nbr,
+                     float *out, int32_t *argmax, int B, int Ns, int Nf, int K, int C, int layout,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Flex-upsampling backward: the pooling step routes grad_out[b,c,l] to the recorded winner,
+ * the copy step hands a selected point's gradient to the smaller layer's point it came
+ * from; what a zero-filled point won is dropped:
+ *   grad_small[b,c,j] = sum of grad_out[b,c,l] over centres l with argmax[b,c,l] = sel[b,j].
+ * Evaluated as a gather over the in-edge lists of the larger layer's nbr (in_off / in_src
+ * from flex_inedges_build, required): no atomics, fixed summation order.
+ */
+int flexupsample_bwd(const float *grad_out, const int32_t *argmax, const int32_t *sel,
+                     const int32_t *in_off, const int32_t *in_src, float *grad_small,
+                     int B, int Ns, int Nf, int K, int C, int layout, void *stream);
+
+/* Debug aid: *bad_count_dev (device int32) = number of sel entries outside [0,Nf) or repeating
+ * another entry of their cloud.  Workspace as for flexupsample_fwd. */
+int flex_validate_selection(const int32_t *sel, int B, int Ns, int Nf, int32_t *bad_count_dev,
+                            void *workspace, size_t workspace_bytes, void *stream);
 
 /* Bytes of workspace needed by op (a flex_op) at these sizes. 0 on bad sizes. */
 size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, int layout);

@@ -15,7 +15,7 @@ import torch
 
 BCN = 0   # [B,C,N]  channel-major, the paper's form
 BNC = 1   # [B,N,C]  point-major, the library's native form
-OP_CONV_FWD, OP_CONV_BWD, OP_CONV_BWD_BUILD, OP_INEDGES = 0, 1, 2, 3
+OP_CONV_FWD, OP_CONV_BWD, OP_CONV_BWD_BUILD, OP_INEDGES, OP_UPSAMPLE = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexconv.so")
@@ -29,6 +29,9 @@ _SIGS = {
     "flex_inedges_build": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
     "flexpool_bwd": (_i, [_vp] * 5 + [_i] * 5 + [_vp]),
+    "flexupsample_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp, _sz, _vp]),
+    "flexupsample_bwd": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
+    "flex_validate_selection": (_i, [_vp, _i, _i, _i, _vp, _vp, _sz, _vp]),
     "flexconv_workspace_bytes": (_sz, [_i] * 7),
     "flex_validate_neighbors": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "flexconv_has_fast_path": (_i, [_i, _i]),
@@ -219,6 +222,69 @@ def flexpool_bwd(grad_out, argmax, layout=BCN, in_edges=None, K=None):
     _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), _ptr(off), _ptr(src), B, N, k, C, layout,
                               _stream()), "flexpool_bwd")
     return gf
+
+
+def _up_dims(small, sel, layout):
+    if small.dim() != 3 or sel.dim() != 2:
+        raise ValueError("the smaller layer's tensor must be 3-D and sel 2-D")
+    B, Ns = sel.shape
+    C = small.shape[1] if layout == BCN else small.shape[2]
+    want = (B, C, Ns) if layout == BCN else (B, Ns, C)
+    if tuple(small.shape) != want:
+        raise ValueError(f"tensor shape {tuple(small.shape)} does not match sel {tuple(sel.shape)} in this layout")
+    return B, Ns, C
+
+
+def flexupsample_fwd(feat_small, sel, nbr, layout=BCN, workspace=None):
+    """Flex-upsampling forward (Sec. 4.1): copy the smaller layer's features to their points sel
+    [B,Ns] of the larger layer, zero elsewhere, flex-max-pool over nbr [B,K,Nf].
+    Returns (out, argmax int32), shaped [B,C,Nf] / [B,Nf,C]."""
+    layout = _layout(layout)
+    _dev(feat_small, torch.float32, "feat_small"); _dev(sel, torch.int32, "sel"); _dev(nbr, torch.int32, "nbr")
+    B, Ns, C = _up_dims(feat_small, sel, layout)
+    if nbr.dim() != 3 or nbr.shape[0] != B:
+        raise ValueError("nbr must be [B,K,Nf]")
+    K, Nf = nbr.shape[1], nbr.shape[2]
+    shape = (B, C, Nf) if layout == BCN else (B, Nf, C)
+    out = torch.empty(shape, dtype=torch.float32, device=feat_small.device)
+    arg = torch.empty(shape, dtype=torch.int32, device=feat_small.device)
+    need = workspace_bytes(OP_UPSAMPLE, B, Nf, K, C, 1, layout)
+    ws = workspace if workspace is not None else _workspace(feat_small.device, need)
+    _check(lib().flexupsample_fwd(_ptr(feat_small), _ptr(sel), _ptr(nbr), _ptr(out), _ptr(arg), B, Ns, Nf, K, C,
+                                  layout, _ptr(ws), ws.numel(), _stream()), "flexupsample_fwd")
+    return out, arg
+
+
+def flexupsample_bwd(grad_out, argmax, sel, in_edges, layout=BCN):
+    """Flex-upsampling backward.  in_edges = (in_off, in_src) of the larger layer's nbr.
+    Returns grad_small shaped [B,C,Ns] / [B,Ns,C]."""
+    layout = _layout(layout)
+    _dev(grad_out, torch.float32, "grad_out"); _dev(argmax, torch.int32, "argmax"); _dev(sel, torch.int32, "sel")
+    if grad_out.dim() != 3 or grad_out.shape != argmax.shape or sel.dim() != 2:
+        raise ValueError("grad_out and argmax must be 3-D and equal in shape, sel 2-D")
+    B, Ns = sel.shape
+    C, Nf = (grad_out.shape[1], grad_out.shape[2]) if layout == BCN else (grad_out.shape[2], grad_out.shape[1])
+    off, src = in_edges
+    _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src")
+    if grad_out.shape[0] != B or off.numel() != B * Nf + 1 or src.numel() % (B * Nf) != 0:
+        raise ValueError("in_edges do not match the tensors")
+    k = src.numel() // (B * Nf)
+    gs = torch.empty((B, C, Ns) if layout == BCN else (B, Ns, C), dtype=torch.float32, device=grad_out.device)
+    _check(lib().flexupsample_bwd(_ptr(grad_out), _ptr(argmax), _ptr(sel), _ptr(off), _ptr(src), _ptr(gs),
+                                  B, Ns, Nf, k, C, layout, _stream()), "flexupsample_bwd")
+    return gs
+
+
+def flex_validate_selection(sel, Nf, workspace=None):
+    """Number of entries of sel [B,Ns] outside [0,Nf) or repeating another entry of their cloud (synchronises)."""
+    _dev(sel, torch.int32, "sel")
+    B, Ns = sel.shape
+    bad = torch.zeros(1, dtype=torch.int32, device=sel.device)
+    need = workspace_bytes(OP_UPSAMPLE, B, Nf, 1, 1, 1, BCN)
+    ws = workspace if workspace is not None else _workspace(sel.device, need)
+    _check(lib().flex_validate_selection(_ptr(sel), B, Ns, Nf, _ptr(bad), _ptr(ws), ws.numel(), _stream()),
+           "flex_validate_selection")
+    return int(bad.item())
 
 
 def flex_validate_neighbors(nbr):

@@ -231,6 +231,7 @@ size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, 
     case FLEX_OP_CONV_BWD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, false).total : 0;
     case FLEX_OP_CONV_BWD_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, true).total : 0;
     case FLEX_OP_INEDGES: return sizes_ok(B, N, K, 1, 1) ? inedges_ws_bytes((int64_t)B * N) : 0;
+    case FLEX_OP_UPSAMPLE: return sizes_ok(B, N, 1, 1, 1) ? align256(sizeof(int32_t) * (size_t)B * N) : 0;
     default: return 0;
     }
 }
@@ -352,6 +353,46 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
     else
         FLEX_HIP(launch_pool_bwd(grad_out, argmax, grad_feat, B, N, C, layout == FLEX_LAYOUT_BNC,
                                  (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexupsample_fwd(const float *feat_small, const int32_t *sel, const int32_t *nbr, float *out,
+                     int32_t *argmax, int B, int Ns, int Nf, int K, int C, int layout, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    if (!feat_small || !sel || !nbr || !out || !argmax) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, Nf, K, C, 1) || Ns <= 0 || Ns > Nf) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, align256(sizeof(int32_t) * (size_t)B * Nf))) return FLEX_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *inv = (int32_t *)workspace;
+    FLEX_HIP(launch_upsample_inv(sel, inv, B, Ns, Nf, s));
+    FLEX_HIP(launch_upsample_fwd(feat_small, inv, nbr, out, argmax, B, Ns, Nf, K, C, layout == FLEX_LAYOUT_BNC, s));
+    return FLEX_OK;
+}
+
+int flexupsample_bwd(const float *grad_out, const int32_t *argmax, const int32_t *sel,
+                     const int32_t *in_off, const int32_t *in_src, float *grad_small, int B, int Ns,
+                     int Nf, int K, int C, int layout, void *stream)
+{
+    if (!grad_out || !argmax || !sel || !in_off || !in_src || !grad_small) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, Nf, K, C, 1) || Ns <= 0 || Ns > Nf) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_upsample_bwd(grad_out, argmax, sel, in_off, in_src, grad_small, B, Ns, Nf, C,
+                                 layout == FLEX_LAYOUT_BNC, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flex_validate_selection(const int32_t *sel, int B, int Ns, int Nf, int32_t *bad_count_dev,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!sel || !bad_count_dev) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, Nf, 1, 1, 1) || Ns <= 0 || Ns > Nf) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, align256(sizeof(int32_t) * (size_t)B * Nf))) return FLEX_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *inv = (int32_t *)workspace;
+    FLEX_HIP(launch_upsample_inv(sel, inv, B, Ns, Nf, s));
+    FLEX_HIP(launch_upsample_check_sel(sel, inv, B, Ns, Nf, bad_count_dev, s));
     return FLEX_OK;
 }
 

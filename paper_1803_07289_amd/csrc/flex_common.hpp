@@ -96,6 +96,17 @@ hipError_t launch_pool_bwd_gather(const float *grad_out, const int32_t *argmax, 
                                   const int32_t *in_src, float *grad_feat, int B, int N, int C, int bnc,
                                   hipStream_t s);
 
+// Flex-upsampling: inverse selection map (inv[b*Nf + sel[b,j]] = j, -1 elsewhere), pooling through it,
+// routing back over the larger layer's in-edge lists, and a check of the selection (out of range / repeated).
+hipError_t launch_upsample_inv(const int32_t *sel, int32_t *inv, int B, int Ns, int Nf, hipStream_t s);
+hipError_t launch_upsample_fwd(const float *feat_small, const int32_t *inv, const int32_t *nbr, float *out,
+                               int32_t *argmax, int B, int Ns, int Nf, int K, int C, int bnc, hipStream_t s);
+hipError_t launch_upsample_bwd(const float *grad_out, const int32_t *argmax, const int32_t *sel,
+                               const int32_t *in_off, const int32_t *in_src, float *grad_small, int B, int Ns,
+                               int Nf, int C, int bnc, hipStream_t s);
+hipError_t launch_upsample_check_sel(const int32_t *sel, const int32_t *inv, int B, int Ns, int Nf, int32_t *bad,
+                                     hipStream_t s);
+
 hipError_t launch_count_bad(const int32_t *nbr, int64_t count, int N, int32_t *bad, hipStream_t s);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 
