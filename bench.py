@@ -37,10 +37,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--n", type=int, default=None, help="override N (smaller trial runs)")
+    ap.add_argument("--k", type=int, default=None, help="override K (neighbourhood-size sweeps)")
     ap.add_argument("--layout", default="bnc", choices=["bnc", "bcn"])
     ap.add_argument("--order", default="morton", choices=["morton", "generator", "shuffled"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default=None, help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd)")
+    ap.add_argument("--only", default=None,
+                    help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; upsample = flex-upsampling from a "
+                         "quarter of the points, not part of the default step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the feature tensor (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against them")
@@ -61,6 +64,8 @@ def main():
     ops = set((args.only or "fwd,bwd,pool_fwd,pool_bwd").split(","))
 
     cfg = CONFIGS[args.config]
+    if args.k is not None:
+        cfg = type(cfg)(**{**cfg.__dict__, "K": int(args.k), "name": cfg.name + f"_K{args.k}"})
     t0 = time.time()
     x = make_inputs(cfg, order=args.order, n_override=args.n)
     cfg = x.cfg
@@ -91,9 +96,16 @@ def main():
     torch.cuda.synchronize()
     inedges_ms = ev0.elapsed_time(ev1)
 
-    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd") if n in ops]
+    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample") if n in ops]
     state = {}
-    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd")
+    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd")
+    if "upsample" in ops:
+        # the smaller layer: a seeded quarter of the points (a decoder stage raises the resolution 4x)
+        Ns = max(1, N // 4)
+        sel_np = np.stack([np.sort(np.random.default_rng([cfg.seed, 300 + b]).permutation(N)[:Ns]) for b in range(B)])
+        sel = torch.from_numpy(sel_np.astype(np.int32)).cuda()
+        idx = sel.long()[:, :, None].expand(B, Ns, Din) if layout == fx.BNC else sel.long()[:, None, :].expand(B, Din, Ns)
+        feat_small = torch.gather(feat, 1 if layout == fx.BNC else 2, idx).contiguous()
 
     def step(events=None):
         """One pass of the hot path.  flexconv_bwd is issued as two calls (parameter gradients,
@@ -120,6 +132,12 @@ def main():
         if "pool_bwd" in ops:
             state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
         mark(5)
+        if "upsample" in ops:
+            state["up"] = fx.flexupsample_fwd(feat_small, sel, nbr, layout=layout)
+        mark(6)
+        if "upsample" in ops:
+            state["up_grad"] = fx.flexupsample_bwd(gpool, state["up"][1], sel, in_edges, layout=layout)
+        mark(7)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(feat)
@@ -131,7 +149,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -157,16 +175,22 @@ def main():
                 "bwd_params": 4 * Din + 12 + 4 * K + 4 * Dout,
                 "bwd_feat": 4 * Dout + 12 + 4 * (K + 1) + 4 * Din,
                 "pool_fwd": 4 * Din + 4 * K + 8 * Din,
-                "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din}
+                "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din,
+                # per point of the larger layer, smaller layer = a quarter of it: rows of the smaller layer,
+                # sel, inverse map (written, read), ids, out + winners / gradient + winners, lists, smaller rows
+                "upsample_fwd": Din + 1 + 8 + 4 * K + 8 * Din,
+                "upsample_bwd": 8 * Din + 1 + 4 * (K + 1) + Din}
     kernel_of = {"fwd": "gather_contract_lean_kernel (flexconv_fwd)",
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
-                 "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)"}
+                 "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)",
+                 "upsample_fwd": "upsample_fwd_bnc4_kernel (flexupsample_fwd)",
+                 "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
     measured_traffic = MEASURED_TRAFFIC
-    default_workload = (cfg.index == 4 and N == 7_000_000 and layout == fx.BNC and x.order == "morton")
+    default_workload = (cfg.index == 4 and N == 7_000_000 and K == 8 and layout == fx.BNC and x.order == "morton")
 
     def roof(name):
         ms = op_ms[name]["mean"]

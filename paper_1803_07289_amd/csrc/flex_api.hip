@@ -10,7 +10,7 @@ namespace flex {
     hipError_t launch_gc_##DI##_##DO(const float *, const float *, const int32_t *, const int32_t *, \
                                      const int32_t *, const void *, int, float *, int, int, int,     \
                                      int, int, hipStream_t);                                         \
-    int theta_format_##DI##_##DO(int, int);                                                          \
+    int theta_format_##DI##_##DO(int, int, int);                                                        \
     hipError_t launch_gt_##DI##_##DO(const float *, const float *, const int32_t *, const float *,   \
                                      float *, int, int, int, int *, hipStream_t);
 #include "flex_shapes.def"
@@ -41,10 +41,10 @@ hipError_t launch_gather_contract(const float *rows, const float *pos, const int
     return hipErrorNotSupported;
 }
 
-int gather_contract_theta_format(int DI, int DO, int K, int csr)
+int gather_contract_theta_format(int DI, int DO, int N, int K, int csr)
 {
 #define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
-    if (DI == DI_ && DO == DO_) return theta_format_##DI_##_##DO_(K, csr);
+    if (DI == DI_ && DO == DO_) return theta_format_##DI_##_##DO_(N, K, csr);
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
     return 0;
@@ -253,7 +253,7 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
         return FLEX_OK;
     }
     void *thetaP = ws + p.thetaP;
-    const int fmt = gather_contract_theta_format(Din, Dout, K, 0);
+    const int fmt = gather_contract_theta_format(Din, Dout, N, K, 0);
     FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 0, fmt, s));
     const float *rows = feat;
     if (bcn) {
@@ -320,7 +320,7 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
             in_src = src;
         }
         void *thetaP = ws + p.thetaP;
-        const int fmt = gather_contract_theta_format(Dout, Din, K, 1);
+        const int fmt = gather_contract_theta_format(Dout, Din, N, K, 1);
         FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 1, fmt, s));
         FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, thetaP, fmt, grad_feat, B, N,
                                         K, Dout, Din, 1, bcn, s));

@@ -49,14 +49,14 @@ hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, 
 //   csr == 0: neighbours from nbr [B,K,N], dp = pos[nbr]-pos[centre]
 //   csr == 1: in-edge lists (off,src), dp = pos[centre]-pos[src]
 //   theta_fmt: what thetaP holds, as answered by gather_contract_theta_format for the same
-//   (DI, DO, K, csr): 0 = fp32 ThetaP (launch_pack_theta), 1 = split-half fragments
+//   (DI, DO, N, K, csr): 0 = fp32 ThetaP (launch_pack_theta), 1 = split-half fragments
 //   (launch_pack_theta_f16).
 hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
                                   const int32_t *off, const int32_t *src, const void *thetaP,
                                   int theta_fmt, float *out, int B, int N, int K, int DI, int DO,
                                   int csr, int out_bcn, hipStream_t s);
 bool gather_contract_supported(int DI, int DO);
-int gather_contract_theta_format(int DI, int DO, int K, int csr);
+int gather_contract_theta_format(int DI, int DO, int N, int K, int csr);
 // true when the environment asks for the fp32 matrix op in the wave-specialised kernels
 // (FLEX_CONTRACT=f32; read once).  For A/B measurements; both forms meet the same tolerance.
 bool contract_in_fp32();

@@ -19,13 +19,20 @@ static constexpr int WG_PER_CU = (FLEX_OCC * 4) / FLEX_W > 0 ? (FLEX_OCC * 4) / 
 
 // 1 if this (shape, K, list form) runs the wave-specialised kernel with the split-half
 // contraction, i.e. wants the parameters from launch_pack_theta_f16; 0: fp32 ThetaP.
-int FLEX_NAME(theta_format, FLEX_DI, FLEX_DO)(int K, int csr)
+// the lean fixed-K producers take this neighbour tensor: whole batches of 8, 32-bit byte offsets in a cloud
+static bool lean_fixed_ok(int N, int K)
+{
+    return lean_producer_mode() != 0 && (K % 8 == 0) && (int64_t)K * N * 4 < (1ll << 32) &&
+           (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32);
+}
+
+int FLEX_NAME(theta_format, FLEX_DI, FLEX_DO)(int N, int K, int csr)
 {
 #if FLEX_WS
     using W = WsGeom<S>;
-    if (!contract_in_fp32() && (csr || (int64_t)W::PW * K <= W::EW)) return 1;
+    if (!contract_in_fp32() && (csr || (int64_t)W::PW * K <= W::EW || lean_fixed_ok(N, K))) return 1;
 #endif
-    (void)K; (void)csr;
+    (void)N; (void)K; (void)csr;
     return 0;
 }
 
@@ -43,7 +50,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
 #if FLEX_WS
     {
         using W = WsGeom<S>;
-        if (csr || (int64_t)W::PW * K <= W::EW) {
+        if (csr || (int64_t)W::PW * K <= W::EW || (theta_fmt && lean_fixed_ok(N, K))) {
             const int tpc = (N + W::T - 1) / W::T;
             const int tot = B * tpc;
             const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
@@ -55,9 +62,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
         else hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, false>), g, blk, 0, s, FLEX_WS_ARGS);          \
     } while (0)
             // lean producer: fixed-K tensor, K in whole batches of 8, 32-bit byte offsets inside a cloud
-            const bool lean = !csr && theta_fmt && lean_producer_mode() != 0 && (K % 8 == 0) &&
-                              (int64_t)K * N * 4 < (1ll << 32) && (int64_t)N * S::DI * 4 < (1ll << 32) &&
-                              (int64_t)N * 12 < (1ll << 32);
+            const bool lean = !csr && theta_fmt && lean_fixed_ok(N, K);
             if (lean) {
                 // 3 producer waves per consumer wave where 16 waves hold them and the items divide evenly
                 constexpr bool WIDE_OK = (S::WAVES * 4 <= 16) && (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
@@ -142,8 +147,7 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     if constexpr (S::WAVES == 4 && S::T == 16) {
         // lean producers + bf16 matrix cores: fixed-K tensor in whole batches of 8, 32-bit offsets in a cloud
         using WL = WsGeom<S, 2, 2>;
-        if (!contract_in_fp32() && lean_producer_mode() != 0 && (K % 8 == 0) &&
-            (int64_t)K * N * 4 < (1ll << 32) && (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32)) {
+        if (!contract_in_fp32() && lean_fixed_ok(N, K)) {
             const int tpc = (N + WL::T - 1) / WL::T;
             const int tot = B * tpc;
             *n_wg = persistent_grid(tot, 1);
