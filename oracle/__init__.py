@@ -167,3 +167,17 @@ def flexupsample_bwd(grad_out, argmax, sel):
     _check(_load().oracle_flexupsample_bwd(_p(grad_out), _p(argmax), _p(sel), _p(gs), B, Ns, Nf, C),
            "oracle_flexupsample_bwd")
     return gs
+
+
+def flexconv_bwd_pos(feat, nbr, theta, grad_out):
+    """Gradient of the flex-conv layer with respect to the point locations: float64 [B,3,N]."""
+    feat, nbr, theta, grad_out = _f32(feat), _i32(nbr), _f32(theta), _f32(grad_out)
+    B, Din, N = feat.shape
+    K = nbr.shape[1]
+    Dout = theta.shape[2]
+    assert theta.shape == (3, Din, Dout) and grad_out.shape == (B, Dout, N) and nbr.shape == (B, K, N)
+    assert count_bad_neighbors(nbr, N) == 0
+    gp = np.zeros((B, 3, N), np.float64)
+    _check(_load().oracle_flexconv_bwd_pos(_p(feat), _p(nbr), _p(theta), _p(grad_out), _p(gp), B, N, K, Din, Dout),
+           "oracle_flexconv_bwd_pos")
+    return gp

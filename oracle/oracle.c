@@ -385,3 +385,39 @@ int oracle_flexupsample_bwd(const float *grad_out, const int32_t *argmax, const 
     free(dense);
     return 0;
 }
+
+/* ---------------------------------------------------------------------------
+ * Flex-conv backward with respect to the point locations (Sec. 3.1: the weight
+ * function is differentiable in all its arguments, so gradients pass through the
+ * locations as well; no formula is printed).  Differentiating
+ *   out[b,o,l] = sum_k sum_c ( <theta[:,c,o], pos[b,:,n] - pos[b,:,l]> + bias[c,o] ) * feat[b,c,n]
+ * term by term: the edge (l,k) with n = nbr[b,k,l] carries
+ *   s_d = sum_{c,o} theta[d,c,o] * feat[b,c,n] * grad_out[b,o,l]
+ * to grad_pos[b,d,n] with a plus sign (the neighbour's location enters with +) and to
+ * grad_pos[b,d,l] with a minus sign (the centre's with -); a point that lists itself
+ * receives both and they cancel.  grad_pos is double [B,3,N], overwritten.
+ * ------------------------------------------------------------------------- */
+int oracle_flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *theta,
+                            const float *grad_out, double *grad_pos,
+                            int B, int N, int K, int Din, int Dout)
+{
+    if (!feat || !nbr || !theta || !grad_out || !grad_pos) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return 2;
+    memset(grad_pos, 0, sizeof(double) * (size_t)B * 3 * N);
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l)
+            for (int k = 0; k < K; ++k) {
+                const int n = nbr[IDX3(b, k, l, K, N)];
+                for (int d = 0; d < 3; ++d) {
+                    double s = 0.0;
+                    for (int c = 0; c < Din; ++c) {
+                        const double f = (double)feat[IDX3(b, c, n, Din, N)];
+                        for (int o = 0; o < Dout; ++o)
+                            s += (double)theta[IDX3(d, c, o, Din, Dout)] * f * (double)grad_out[IDX3(b, o, l, Dout, N)];
+                    }
+                    grad_pos[IDX3(b, d, n, 3, N)] += s;
+                    grad_pos[IDX3(b, d, l, 3, N)] -= s;
+                }
+            }
+    return 0;
+}

@@ -246,3 +246,56 @@ def test_bwd_ranges_add_up():
     b = oracle.flexconv_bwd(feat, pos, nbr, theta, bias, g, l_range=(6, 15))
     for f, p, q in zip(full, a, b):
         np.testing.assert_allclose(f, p + q, rtol=1e-12, atol=1e-12)
+
+
+# ---- gradient with respect to the point locations ---------------------------------------
+def test_bwd_pos_finite_differences():
+    # out is affine in pos, so a central difference of <g, fwd(pos)> is exact up to rounding
+    pos, nbr, feat, theta, bias, g = tiny_problem(21, B=2, N=9, K=4, Din=3, Dout=2, self_first=True)
+    gp = oracle.flexconv_bwd_pos(feat, nbr, theta, g)
+    g64 = g.astype(np.float64)
+    h = 0.25                                   # exactly representable steps on top of float32 inputs
+    for b in range(2):
+        for d in range(3):
+            for m in range(9):
+                pp, pm = pos.astype(np.float64).copy(), pos.astype(np.float64).copy()
+                pp[b, d, m] += h
+                pm[b, d, m] -= h
+                # the oracle takes float32 positions: evaluate the definition in numpy on the float64 copies
+                fd = (np.sum(g64 * _fwd_numpy(feat, pp, nbr, theta, bias)) - np.sum(g64 * _fwd_numpy(feat, pm, nbr, theta, bias))) / (2 * h)
+                assert abs(gp[b, d, m] - fd) <= 1e-9 * max(1.0, abs(fd))
+
+
+def _fwd_numpy(feat, pos64, nbr, theta, bias):
+    W = dense_weights_f64(pos64, nbr, theta, bias)
+    return np.einsum("blkco,blkc->bol", W, gathered(feat, nbr))
+
+
+def dense_weights_f64(pos64, nbr, theta, bias):
+    B, K, N = nbr.shape
+    bi = np.arange(B)[:, None, None]
+    pn = pos64[bi, :, nbr.transpose(0, 2, 1)]
+    pl = pos64.transpose(0, 2, 1)[:, :, None, :]
+    return np.einsum("dco,blkd->blkco", theta.astype(np.float64), pn - pl) + bias.astype(np.float64)
+
+
+def test_bwd_pos_bruteforce_translation_and_self_edges():
+    pos, nbr, feat, theta, bias, g = tiny_problem(22, B=2, N=12, K=3, Din=2, Dout=3)
+    gp = oracle.flexconv_bwd_pos(feat, nbr, theta, g)
+    # brute force: s[b,l,k,d] scattered with +/- signs
+    F = gathered(feat, nbr)                                                  # [B,N,K,Din]
+    s = np.einsum("dco,blkc,bol->blkd", theta.astype(np.float64), F, g.astype(np.float64))
+    want = np.zeros_like(gp)
+    for b in range(2):
+        for l in range(12):
+            for k in range(3):
+                want[b, :, nbr[b, k, l]] += s[b, l, k]
+                want[b, :, l] -= s[b, l, k]
+    assert np.allclose(gp, want, rtol=0, atol=1e-12)
+    # translation invariance of the layer: the location gradients of a cloud sum to zero
+    assert np.abs(gp.sum(axis=2)).max() <= 1e-12 * max(1.0, np.abs(gp).max())
+    # neighbourhoods made of the centre alone: no dependence on the locations at all
+    self_only = np.broadcast_to(np.arange(12, dtype=np.int32), nbr.shape).copy()
+    assert np.abs(oracle.flexconv_bwd_pos(feat, self_only, theta, g)).max() == 0.0
+    # the gradient does not involve the bias nor the locations themselves (the map is affine in pos)
+    assert np.array_equal(gp, oracle.flexconv_bwd_pos(feat, nbr, theta, g))

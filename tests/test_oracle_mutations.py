@@ -27,6 +27,8 @@ POOL_PINS = [tp.test_pool_fwd_bruteforce_with_ties, tp.test_pool_fwd_invariants,
 UP_PINS = [tu.test_upsample_fwd_bruteforce_with_ties, tu.test_upsample_fwd_is_zero_fill_then_pool,
            tu.test_upsample_grid_is_zero_insertion_then_3x3_max, tu.test_upsample_bwd_bruteforce_mass_and_composition]
 
+POS_PINS = [tc.test_bwd_pos_finite_differences, tc.test_bwd_pos_bruteforce_translation_and_self_edges]
+
 # (name, text to replace, replacement, occurrence index or None for all, pins that must catch it)
 MUTATIONS = [
     ("fwd_sign_dx", "(double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)]",
@@ -50,6 +52,11 @@ MUTATIONS = [
     ("upsample_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 1, UP_PINS),
     ("upsample_bwd_reads_own_index", "grad_small[IDX3(b, c, j, C, Ns)] = dense[IDX3(b, c, m, C, Nf)];",
      "grad_small[IDX3(b, c, j, C, Ns)] = dense[IDX3(b, c, j, C, Nf)];", 0, UP_PINS),
+    ("bwd_pos_centre_sign", "grad_pos[IDX3(b, d, l, 3, N)] -= s;", "grad_pos[IDX3(b, d, l, 3, N)] += s;", 0, POS_PINS),
+    ("bwd_pos_feature_of_centre", "s += (double)theta[IDX3(d, c, o, Din, Dout)] * f * (double)grad_out[IDX3(b, o, l, Dout, N)];",
+     "s += (double)theta[IDX3(d, c, o, Din, Dout)] * (double)feat[IDX3(b, c, l, Din, N)] * (double)grad_out[IDX3(b, o, l, Dout, N)];", 0, POS_PINS),
+    ("bwd_pos_gradient_of_neighbour", "s += (double)theta[IDX3(d, c, o, Din, Dout)] * f * (double)grad_out[IDX3(b, o, l, Dout, N)];",
+     "s += (double)theta[IDX3(d, c, o, Din, Dout)] * f * (double)grad_out[IDX3(b, o, n, Dout, N)];", 0, POS_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
