@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
                     help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; upsample = flex-upsampling from a "
-                         "quarter of the points, not part of the default step)")
+                         "quarter of the points, bwd_pos = location gradient; neither is part of the default step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the feature tensor (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against them")
@@ -96,9 +96,9 @@ def main():
     torch.cuda.synchronize()
     inedges_ms = ev0.elapsed_time(ev1)
 
-    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample") if n in ops]
+    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos") if n in ops]
     state = {}
-    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd")
+    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos")
     if "upsample" in ops:
         # the smaller layer: a seeded quarter of the points (a decoder stage raises the resolution 4x)
         Ns = max(1, N // 4)
@@ -138,6 +138,9 @@ def main():
         if "upsample" in ops:
             state["up_grad"] = fx.flexupsample_bwd(gpool, state["up"][1], sel, in_edges, layout=layout)
         mark(7)
+        if "bwd_pos" in ops:
+            state["grad_pos"] = fx.flexconv_bwd_pos(feat, nbr, theta, g, layout=layout, in_edges=in_edges)
+        mark(8)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(feat)
@@ -149,7 +152,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(9)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -179,14 +182,17 @@ def main():
                 # per point of the larger layer, smaller layer = a quarter of it: rows of the smaller layer,
                 # sel, inverse map (written, read), ids, out + winners / gradient + winners, lists, smaller rows
                 "upsample_fwd": Din + 1 + 8 + 4 * K + 8 * Din,
-                "upsample_bwd": 8 * Din + 1 + 4 * (K + 1) + Din}
+                "upsample_bwd": 8 * Din + 1 + 4 * (K + 1) + Din,
+                # two passes: each reads features and upstream gradient once, ids / lists, writes 3 floats
+                "bwd_pos": 2 * (4 * Din + 4 * Dout) + 4 * K + 4 * (K + 1) + 12 + 24}
     kernel_of = {"fwd": "gather_contract_lean_kernel (flexconv_fwd)",
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
                  "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)",
                  "upsample_fwd": "upsample_fwd_bnc4_kernel (flexupsample_fwd)",
-                 "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)"}
+                 "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)",
+                 "bwd_pos": "grad_pos_kernel x2 (flexconv_bwd_pos: centre term, neighbour term)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
     measured_traffic = MEASURED_TRAFFIC

@@ -54,7 +54,9 @@ typedef enum {
     FLEX_OP_CONV_BWD = 1,       /* with caller-supplied in-edge lists */
     FLEX_OP_CONV_BWD_BUILD = 2, /* in-edge lists built inside the call */
     FLEX_OP_INEDGES = 3,
-    FLEX_OP_UPSAMPLE = 4        /* flexupsample_fwd / flex_validate_selection; N = points of the larger layer */
+    FLEX_OP_UPSAMPLE = 4,       /* flexupsample_fwd / flex_validate_selection; N = points of the larger layer */
+    FLEX_OP_CONV_BWD_POS = 5,       /* flexconv_bwd_pos with caller-supplied in-edge lists */
+    FLEX_OP_CONV_BWD_POS_BUILD = 6  /* in-edge lists built inside the call */
 } flex_op;
 
 /*
@@ -90,6 +92,22 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
                  const int32_t *in_off, const int32_t *in_src,
                  int B, int N, int K, int Din, int Dout, int layout,
                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Flex-convolution backward with respect to the point locations (Sec. 3.1: the weight is
+ * differentiable in all its arguments, so gradients reach the locations too).  Every edge
+ * (l,k), n = nbr[b,k,l], carries s_d = sum_{c,o} theta[d,c,o] * feat[b,c,n] * grad_out[b,o,l]
+ * to grad_pos[b,d,n] with + and to grad_pos[b,d,l] with -.  grad_pos is [B,3,N] like pos,
+ * overwritten.  Evaluated from plain neighbourhood sums (of feat over each point's neighbours, of
+ * grad_out over the centres that list it) and one small contraction per point, without
+ * floating-point atomics when the shape has a matrix-core kernel (flexconv_has_fast_path and K
+ * a multiple of 8); otherwise by a direct kernel with fp32 atomic adds (summation order, hence
+ * the last bits, may vary).  in_off / in_src as for flexconv_bwd (NULL: built in the workspace).
+ */
+int flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *theta, const float *grad_out,
+                     const int32_t *in_off, const int32_t *in_src, float *grad_pos,
+                     int B, int N, int K, int Din, int Dout, int layout,
+                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Transposed neighbour graph (Sec. 4.1: neighbourhoods are computed once and

@@ -404,6 +404,8 @@ int oracle_flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *
     if (!feat || !nbr || !theta || !grad_out || !grad_pos) return 1;
     if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return 2;
     memset(grad_pos, 0, sizeof(double) * (size_t)B * 3 * N);
+    /* clouds are independent; inside a cloud the edges are taken one after the other */
+#pragma omp parallel for schedule(static)
     for (int b = 0; b < B; ++b)
         for (int l = 0; l < N; ++l)
             for (int k = 0; k < K; ++k) {

@@ -16,6 +16,7 @@ import torch
 BCN = 0   # [B,C,N]  channel-major, the paper's form
 BNC = 1   # [B,N,C]  point-major, the library's native form
 OP_CONV_FWD, OP_CONV_BWD, OP_CONV_BWD_BUILD, OP_INEDGES, OP_UPSAMPLE = 0, 1, 2, 3, 4
+OP_CONV_BWD_POS, OP_CONV_BWD_POS_BUILD = 5, 6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexconv.so")
@@ -29,6 +30,7 @@ _SIGS = {
     "flex_inedges_build": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
     "flexpool_bwd": (_i, [_vp] * 5 + [_i] * 5 + [_vp]),
+    "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexupsample_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexupsample_bwd": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "flex_validate_selection": (_i, [_vp, _i, _i, _i, _vp, _vp, _sz, _vp]),
@@ -185,6 +187,32 @@ def flexconv_bwd(feat, pos, nbr, theta, bias, grad_out, layout=BCN, in_edges=Non
                               _ptr(gf), _ptr(gt), _ptr(gb), _ptr(off), _ptr(src),
                               B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_bwd")
     return gf, gt, gb
+
+
+def flexconv_bwd_pos(feat, nbr, theta, grad_out, layout=BCN, in_edges=None, workspace=None):
+    """Gradient of the flex-convolution with respect to the point locations: [B,3,N] like pos."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(nbr, torch.int32, "nbr"); _dev(theta, torch.float32, "theta")
+    _dev(grad_out, torch.float32, "grad_out")
+    B, N, K, Din = _dims(feat, nbr, layout)
+    if theta.dim() != 3 or theta.shape[0] != 3 or theta.shape[1] != Din:
+        raise ValueError("theta must be [3,Din,Dout]")
+    Dout = theta.shape[2]
+    if tuple(grad_out.shape) != ((B, Dout, N) if layout == BCN else (B, N, Dout)):
+        raise ValueError("grad_out has the wrong shape")
+    off = src = None
+    if in_edges is not None:
+        off, src = in_edges
+        _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src")
+        if off.numel() != B * N + 1 or src.numel() != B * K * N:
+            raise ValueError("in_edges do not match nbr")
+    gp = torch.empty((B, 3, N), dtype=torch.float32, device=feat.device)
+    op = OP_CONV_BWD_POS if in_edges is not None else OP_CONV_BWD_POS_BUILD
+    need = workspace_bytes(op, B, N, K, Din, Dout, layout)
+    ws = workspace if workspace is not None else _workspace(feat.device, need)
+    _check(lib().flexconv_bwd_pos(_ptr(feat), _ptr(nbr), _ptr(theta), _ptr(grad_out), _ptr(off), _ptr(src), _ptr(gp),
+                                  B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_bwd_pos")
+    return gp
 
 
 def flexpool_fwd(feat, nbr, layout=BCN):

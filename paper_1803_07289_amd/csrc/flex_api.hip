@@ -10,7 +10,11 @@ namespace flex {
     hipError_t launch_gc_##DI##_##DO(const float *, const float *, const int32_t *, const int32_t *, \
                                      const int32_t *, const void *, int, float *, int, int, int,     \
                                      int, int, hipStream_t);                                         \
-    int theta_format_##DI##_##DO(int, int, int);                                                        \
+    int theta_format_##DI##_##DO(int, int, int);                                                       \
+    bool gp_ok_##DI##_##DO(int, int);                                                                 \
+    hipError_t launch_gp_##DI##_##DO(const float *, const int32_t *, const int32_t *, const int32_t *, \
+                                     const void *, const float *, float *, float, int, int, int, int,  \
+                                     int, hipStream_t);                                                        \
     hipError_t launch_gt_##DI##_##DO(const float *, const float *, const int32_t *, const float *,   \
                                      float *, int, int, int, int *, hipStream_t);
 #include "flex_shapes.def"
@@ -48,6 +52,27 @@ int gather_contract_theta_format(int DI, int DO, int N, int K, int csr)
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
     return 0;
+}
+
+bool grad_pos_supported(int DI, int DO, int N, int K)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
+    if (DI == DI_ && DO == DO_) return gp_ok_##DI_##_##DO_(N, K);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return false;
+}
+
+hipError_t launch_grad_pos_term(const float *rows, const int32_t *nbr, const int32_t *off, const int32_t *src,
+                                const void *thetaF, const float *dot_rows, float *grad_pos, float sign,
+                                int accumulate, int B, int N, int K, int DI, int DO, int csr, hipStream_t s)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS)                                                               \
+    if (DI == DI_ && DO == DO_)                                                                           \
+        return launch_gp_##DI_##_##DO_(rows, nbr, off, src, thetaF, dot_rows, grad_pos, sign, accumulate, B, N, K, csr, s);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return hipErrorNotSupported;
 }
 
 bool contract_in_fp32()
@@ -181,6 +206,34 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
     return p;
 }
 
+struct PosPlan {
+    bool lean;
+    size_t thetaC, thetaN, featT, gT, in_off, in_src, inedge_ws, total;
+};
+static inline int pad32(int x) { return (x + 31) / 32 * 32; }
+
+static PosPlan plan_pos(int64_t B, int64_t N, int K, int Din, int Dout, int layout, bool build)
+{
+    PosPlan p{};
+    p.lean = grad_pos_supported(Din, Dout, (int)N, K) && grad_pos_supported(Dout, Din, (int)N, K);
+    size_t at = 0;
+    if (p.lean) {
+        p.thetaC = at; at += theta_pos_bytes(pad32(pad4(Din)), pad16(Dout));
+        p.thetaN = at; at += theta_pos_bytes(pad32(pad4(Dout)), pad16(Din));
+        if (layout == FLEX_LAYOUT_BCN) {
+            p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din);
+            p.gT = at;    at += align256(sizeof(float) * (size_t)(B * N) * Dout);
+        }
+        if (build) {
+            p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
+            p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
+            p.inedge_ws = at; at += inedges_ws_bytes(B * N);
+        }
+    }
+    p.total = at > 0 ? at : 256;
+    return p;
+}
+
 static bool sizes_ok(int64_t B, int64_t N, int64_t K, int64_t Din, int64_t Dout)
 {
     if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return false;
@@ -231,6 +284,8 @@ size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, 
     case FLEX_OP_CONV_BWD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, false).total : 0;
     case FLEX_OP_CONV_BWD_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, true).total : 0;
     case FLEX_OP_INEDGES: return sizes_ok(B, N, K, 1, 1) ? inedges_ws_bytes((int64_t)B * N) : 0;
+    case FLEX_OP_CONV_BWD_POS: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, false).total : 0;
+    case FLEX_OP_CONV_BWD_POS_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, true).total : 0;
     case FLEX_OP_UPSAMPLE: return sizes_ok(B, N, 1, 1, 1) ? align256(sizeof(int32_t) * (size_t)B * N) : 0;
     default: return 0;
     }
@@ -353,6 +408,46 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
     else
         FLEX_HIP(launch_pool_bwd(grad_out, argmax, grad_feat, B, N, C, layout == FLEX_LAYOUT_BNC,
                                  (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *theta, const float *grad_out,
+                     const int32_t *in_off, const int32_t *in_src, float *grad_pos, int B, int N, int K,
+                     int Din, int Dout, int layout, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!feat || !nbr || !theta || !grad_out || !grad_pos) return FLEX_ERR_NULL;
+    if ((in_off == nullptr) != (in_src == nullptr)) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, Din, Dout)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    const bool build = in_off == nullptr;
+    const PosPlan p = plan_pos(B, N, K, Din, Dout, layout, build);
+    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int bcn = (layout == FLEX_LAYOUT_BCN);
+    if (!p.lean) {
+        FLEX_HIP(launch_generic_bwd_pos(feat, nbr, theta, grad_out, grad_pos, B, N, K, Din, Dout, !bcn, s));
+        return FLEX_OK;
+    }
+    const float *rows = feat, *g_rows = grad_out;
+    if (bcn) {
+        FLEX_HIP(launch_bcn_to_bnc(feat, (float *)(ws + p.featT), B, Din, N, s));
+        FLEX_HIP(launch_bcn_to_bnc(grad_out, (float *)(ws + p.gT), B, Dout, N, s));
+        rows = (const float *)(ws + p.featT);
+        g_rows = (const float *)(ws + p.gT);
+    }
+    if (build) {
+        int32_t *off = (int32_t *)(ws + p.in_off), *src = (int32_t *)(ws + p.in_src);
+        FLEX_HIP(launch_inedges_build(nbr, B, N, K, off, src, ws + p.inedge_ws, s));
+        in_off = off;
+        in_src = src;
+    }
+    void *thC = ws + p.thetaC, *thN = ws + p.thetaN;
+    FLEX_HIP(launch_pack_theta_pos(theta, thC, Din, Dout, pad32(pad4(Din)), pad16(Dout), 0, s));
+    FLEX_HIP(launch_pack_theta_pos(theta, thN, Din, Dout, pad32(pad4(Dout)), pad16(Din), 1, s));
+    // centre term: -<(sum_k feat[n_k(x)])^T theta_d, grad_out[x]>, then neighbour term added on top
+    FLEX_HIP(launch_grad_pos_term(rows, nbr, nullptr, nullptr, thC, g_rows, grad_pos, -1.f, 0, B, N, K, Din, Dout, 0, s));
+    FLEX_HIP(launch_grad_pos_term(g_rows, nullptr, in_off, in_src, thN, rows, grad_pos, 1.f, 1, B, N, K, Dout, Din, 1, s));
     return FLEX_OK;
 }
 

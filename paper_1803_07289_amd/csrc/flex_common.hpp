@@ -40,6 +40,21 @@ hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *th
 size_t theta_f16_exp_offset(int RP, int CP);
 size_t theta_f16_bytes(int RP, int CP);
 
+// Location gradient (flex_ws.hpp grad_pos_kernel): Theta_d fragments and one term of the gradient.
+// launch_grad_pos_term returns hipErrorNotSupported when (DI, DO, N, K) has no lean kernel.
+hipError_t launch_pack_theta_pos(const float *theta, void *thetaF, int Din, int Dout, int KDP, int CP,
+                                 int transpose, hipStream_t s);
+size_t theta_pos_exp_offset(int KDP, int CP);
+size_t theta_pos_bytes(int KDP, int CP);
+hipError_t launch_grad_pos_term(const float *rows, const int32_t *nbr, const int32_t *off, const int32_t *src,
+                                const void *thetaF, const float *dot_rows, float *grad_pos, float sign,
+                                int accumulate, int B, int N, int K, int DI, int DO, int csr, hipStream_t s);
+bool grad_pos_supported(int DI, int DO, int N, int K);
+// direct-form fallback for any shape (fp32 atomics)
+hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const float *theta,
+                                  const float *grad_out, float *grad_pos, int B, int N, int K, int Din,
+                                  int Dout, int bnc, hipStream_t s);
+
 // [B,C,N] -> [B,N,C] and back.
 hipError_t launch_bcn_to_bnc(const float *src, float *dst, int B, int C, int N, hipStream_t s);
 hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, hipStream_t s);

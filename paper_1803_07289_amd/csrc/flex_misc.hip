@@ -124,6 +124,62 @@ hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *th
     return hipGetLastError();
 }
 
+// ---- theta fragments for the location-gradient kernel --------------------------------
+// Theta_d = theta[d] (transpose == 0: depth = input channel, columns = output channel) or its
+// transpose (transpose == 1), d = x, y, z, split-half with one exponent for all three:
+//   thetaF[((((2*d + part)*NS + slice)*KS + step)*64 + lane)*8 + e]
+//       = part( Theta_d[32*step + 8*(lane>>4) + e][16*slice + (lane&15)] * 2^e_theta ),
+// NS = CP/16, KS = KDP/32, zero outside the matrix; int32 e_theta at theta_pos_exp_offset(KDP, CP).
+__global__ __launch_bounds__(1024) void pack_theta_pos_f16_kernel(const float *__restrict__ theta,
+                                                                  _Float16 *__restrict__ thetaF, int Din,
+                                                                  int Dout, int KDP, int CP, int transpose,
+                                                                  int exp_offset_bytes)
+{
+    __shared__ float s_max[1024];
+    const int n_theta = 3 * Din * Dout;
+    float m = 0.f;
+    for (int i = threadIdx.x; i < n_theta; i += 1024) m = fmaxf(m, fabsf(theta[i]));
+    s_max[threadIdx.x] = m;
+    __syncthreads();
+    for (int d = 512; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + d]);
+        __syncthreads();
+    }
+    m = s_max[0];
+    int ex = 0;
+    if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ex); ex = 15 - ex; }
+    if (threadIdx.x == 0) *reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes) = ex;
+
+    const int KS = KDP / 32, NS = CP / 16;
+    const int per_part = NS * KS * 64 * 8;
+    const int depth = transpose ? Dout : Din, cols = transpose ? Din : Dout;
+    for (int i = threadIdx.x; i < 3 * per_part; i += 1024) {
+        const int d = i / per_part, j = i % per_part;
+        const int e = j & 7, lane = (j >> 3) & 63, step = (j >> 9) % KS, slice = (j >> 9) / KS;
+        const int kd = 32 * step + 8 * (lane >> 4) + e, col = 16 * slice + (lane & 15);
+        float v = 0.f;
+        if (kd < depth && col < cols) {
+            const int ci = transpose ? col : kd, co = transpose ? kd : col;
+            v = theta[((int64_t)d * Din + ci) * Dout + co];
+        }
+        const float vs = ldexpf(v, ex);
+        const _Float16 hi = (_Float16)vs;
+        thetaF[(2 * d) * per_part + j] = hi;
+        thetaF[(2 * d + 1) * per_part + j] = (_Float16)(vs - (float)hi);
+    }
+}
+
+size_t theta_pos_exp_offset(int KDP, int CP) { return align256(sizeof(_Float16) * (size_t)6 * CP * KDP); }
+size_t theta_pos_bytes(int KDP, int CP) { return theta_pos_exp_offset(KDP, CP) + 256; }
+
+hipError_t launch_pack_theta_pos(const float *theta, void *thetaF, int Din, int Dout, int KDP, int CP,
+                                 int transpose, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_theta_pos_f16_kernel, dim3(1), dim3(1024), 0, s, theta, (_Float16 *)thetaF, Din,
+                       Dout, KDP, CP, transpose, (int)theta_pos_exp_offset(KDP, CP));
+    return hipGetLastError();
+}
+
 // ---- [B,R,C] -> [B,C,R] transposes (64x64 tiles through LDS) -----------------
 __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ src,
                                                         float *__restrict__ dst, int R, int C,
@@ -397,6 +453,55 @@ hipError_t launch_generic_bwd(const float *feat, const float *pos, const int32_t
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// ---- location gradient, direct form (any shape) -------------------------------------
+// one thread per edge (b, l, k): s_d = sum_{c,o} theta[d,c,o] feat[c,n] g[o,l]; +s_d to n, -s_d to l
+__global__ __launch_bounds__(256) void generic_bwd_pos_kernel(const float *__restrict__ feat,
+                                                              const int32_t *__restrict__ nbr,
+                                                              const float *__restrict__ theta,
+                                                              const float *__restrict__ grad_out,
+                                                              float *__restrict__ grad_pos, int B, int N, int K,
+                                                              int Din, int Dout, int bnc)
+{
+    const int64_t total = (int64_t)B * K * N;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int l = (int)(i % N);
+        const int64_t bk = i / N;
+        const int b = (int)(bk / K);
+        const int n = nbr[i];
+        if (n == l) continue;                       // a self edge adds and subtracts the same value
+        float s[3] = {0.f, 0.f, 0.f};
+        for (int c = 0; c < Din; ++c) {
+            const float f = feat[at(bnc, b, c, n, Din, N)];
+            float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+            for (int o = 0; o < Dout; ++o) {
+                const float g = grad_out[at(bnc, b, o, l, Dout, N)];
+                t0 = fmaf(theta[((int64_t)0 * Din + c) * Dout + o], g, t0);
+                t1 = fmaf(theta[((int64_t)1 * Din + c) * Dout + o], g, t1);
+                t2 = fmaf(theta[((int64_t)2 * Din + c) * Dout + o], g, t2);
+            }
+            s[0] = fmaf(f, t0, s[0]); s[1] = fmaf(f, t1, s[1]); s[2] = fmaf(f, t2, s[2]);
+        }
+        for (int d = 0; d < 3; ++d) {
+            atomicAdd(&grad_pos[((int64_t)b * 3 + d) * N + n], s[d]);
+            atomicAdd(&grad_pos[((int64_t)b * 3 + d) * N + l], -s[d]);
+        }
+    }
+}
+
+hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const float *theta,
+                                  const float *grad_out, float *grad_pos, int B, int N, int K, int Din,
+                                  int Dout, int bnc, hipStream_t s)
+{
+    hipError_t e = launch_fill_zero(grad_pos, sizeof(float) * (size_t)B * 3 * N, s);
+    if (e != hipSuccess) return e;
+    const int64_t total = (int64_t)B * K * N;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(generic_bwd_pos_kernel, dim3((unsigned)blocks), dim3(256), 0, s, feat, nbr, theta,
+                       grad_out, grad_pos, B, N, K, Din, Dout, bnc);
+    return hipGetLastError();
 }
 
 }  // namespace flex

@@ -174,4 +174,41 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     return hipGetLastError();
 }
 
+// One term of the location gradient; false / hipErrorNotSupported when this shape has no kernel for it.
+bool FLEX_NAME(gp_ok, FLEX_DI, FLEX_DO)(int N, int K)
+{
+#if FLEX_WS
+    if constexpr (S::WAVES == 4 && S::T == 16 && PosGeom<S>::FITS)
+        return !contract_in_fp32() && lean_fixed_ok(N, K);
+#endif
+    (void)N; (void)K;
+    return false;
+}
+
+hipError_t FLEX_NAME(launch_gp, FLEX_DI, FLEX_DO)(const float *rows, const int32_t *nbr, const int32_t *off,
+                                                  const int32_t *src, const void *thetaF,
+                                                  const float *dot_rows, float *grad_pos, float sign,
+                                                  int accumulate, int B, int N, int K, int csr, hipStream_t s)
+{
+#if FLEX_WS
+    if constexpr (S::WAVES == 4 && S::T == 16 && PosGeom<S>::FITS) {
+        constexpr bool WIDE_OK = (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
+        constexpr int PMX = WIDE_OK ? 3 : 1;
+        using WL = WsGeom<S, PMX>;
+        const int tpc = (N + WL::T - 1) / WL::T;
+        const int tot = B * tpc;
+        const dim3 g(persistent_grid(tot, WL::WG_PER_CU)), blk(WL::NT);
+        const int exp_off = (int)theta_pos_exp_offset(PosGeom<S>::KDP, S::DOP);
+        if (csr)
+            hipLaunchKernelGGL((grad_pos_kernel<S, true, PMX>), g, blk, 0, s, rows, nbr, off, src, thetaF, exp_off,
+                               dot_rows, grad_pos, sign, accumulate, N, K, tpc, tot);
+        else
+            hipLaunchKernelGGL((grad_pos_kernel<S, false, PMX>), g, blk, 0, s, rows, nbr, off, src, thetaF, exp_off,
+                               dot_rows, grad_pos, sign, accumulate, N, K, tpc, tot);
+        return hipGetLastError();
+    }
+#endif
+    return hipErrorNotSupported;
+}
+
 }  // namespace flex

@@ -474,7 +474,9 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 // m+1; the ids of batch m+2 are requested at the start of batch m.  Batches past the
 // workgroup's last tile repeat that tile (loaded, never used).
 // ---------------------------------------------------------------------------
-template <class S, int PM>
+// SUM == true: only the plain neighbour sum (component j = 3 of the aggregate) is formed; no positions
+// are read (used by the location-gradient kernels).
+template <class S, int PM, bool SUM = false>
 struct LeanProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
@@ -598,7 +600,8 @@ struct LeanProducer {
             const Batch x0 = batch(0);
             load_ids(id0, x0);
             load_ids(idn, batch(1));
-            load_pos(pn, pc, id0, x0);
+            pn[0] = pn[1] = pc = 0.f;
+            if constexpr (!SUM) load_pos(pn, pc, id0, x0);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * S::DI);
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
@@ -619,19 +622,22 @@ struct LeanProducer {
             int idc[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
-            load_pos(pn, pc, idn, x1);
+            if constexpr (!SUM) load_pos(pn, pc, idn, x1);
             load_ids(idn, batch(m + 2));
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * S::DI);
             float dpc[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) dpc[u] = __int_as_float(spread(dpe, perm_dp, u));
+            for (int u = 0; u < U; ++u) dpc[u] = SUM ? 0.f : __int_as_float(spread(dpe, perm_dp, u));
 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float fv[S::VEC];
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                if constexpr (VALU_AGG) {
+                if constexpr (SUM) {
+#pragma unroll
+                    for (int v = 0; v < S::VEC; ++v) acc[v][3] += fv[v];
+                } else if constexpr (VALU_AGG) {
                     // the four lanes of a block hold (dx, dy, dz, 1): broadcast inside the quad
                     const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
 #pragma unroll
@@ -668,7 +674,7 @@ struct LeanProducer {
 // Slots past a list's end gather the point's own row with dp = (0,0,0,0), i.e. add nothing.
 // The list bounds of the next tile are requested when a wave's id cursor enters a tile.
 // ---------------------------------------------------------------------------
-template <class S, int PM>
+template <class S, int PM, bool SUM = false>
 struct LeanCsrProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
@@ -791,8 +797,13 @@ struct LeanCsrProducer {
     // position difference of this lane's entries (point - centre), zero for missing entries
     __device__ __forceinline__ void dp_entries(int (&dpe)[2], const float (&pn)[2], float pc, const Desc &d) const
     {
-        dpe[0] = d.valid0 ? __float_as_int(fmaf(pc - pn[0], e_mul, e_fix)) : 0;
-        dpe[1] = d.valid1 ? __float_as_int(fmaf(pc - pn[1], e_mul, e_fix)) : 0;
+        if constexpr (SUM) {     // every component lane carries the entry's weight: 1 if it exists
+            dpe[0] = d.valid0 ? __float_as_int(1.f) : 0;
+            dpe[1] = d.valid1 ? __float_as_int(1.f) : 0;
+        } else {
+            dpe[0] = d.valid0 ? __float_as_int(fmaf(pc - pn[0], e_mul, e_fix)) : 0;
+            dpe[1] = d.valid1 ? __float_as_int(fmaf(pc - pn[1], e_mul, e_fix)) : 0;
+        }
     }
 
     template <class Fin>
@@ -810,7 +821,8 @@ struct LeanCsrProducer {
             int id0[2];
             fetch(c, id0, d0);
             fetch(c, idn, d1);
-            load_pos(pn, pc, id0, d0);
+            pn[0] = pn[1] = pc = 0.f;
+            if constexpr (!SUM) load_pos(pn, pc, id0, d0);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * S::DI);
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
@@ -828,7 +840,7 @@ struct LeanCsrProducer {
             int idc[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
-            load_pos(pn, pc, idn, d1);
+            if constexpr (!SUM) load_pos(pn, pc, idn, d1);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * S::DI);
             d0 = d1;
             fetch(c, idn, d1);
@@ -841,14 +853,19 @@ struct LeanCsrProducer {
                 float fv[S::VEC];
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
-                const float one = dpp_move<0xFF>(dpc[u]);    // 1 for a real entry, 0 for a missing one
+                if constexpr (SUM) {
 #pragma unroll
-                for (int v = 0; v < S::VEC; ++v) {
-                    acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
-                    acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
-                    acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
-                    acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                    for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(dpc[u], fv[v], acc[v][3]);
+                } else {
+                    const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
+                    const float one = dpp_move<0xFF>(dpc[u]);    // 1 for a real entry, 0 for a missing one
+#pragma unroll
+                    for (int v = 0; v < S::VEC; ++v) {
+                        acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                        acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                        acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                        acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                    }
                 }
                 load_row(f[u], idc[u], rb);
             }
@@ -1473,6 +1490,170 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 dst[(int64_t)(mb * 16 + 4 * q + i) * S::DOP + nb * 16 + r16] = sum[i];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Gradient with respect to the point locations.  With Fsum[x] = sum_k feat[n_k(x)] and
+// Gsum[x] = sum over the centres l that list x of grad_out[l] (plain neighbourhood sums),
+//   grad_pos[d][x] = <feat[x], theta_d Gsum[x]>  -  <Fsum[x]^T theta_d, grad_out[x]>,   d = x, y, z,
+// which follows from differentiating the forward sum edge by edge (the neighbour's location
+// enters the weight with +, the centre's with -).  One kernel serves both terms:
+//   sums  = lean producers in SUM mode (fixed-K tensor, or in-edge lists when CSR),
+//   R_d   = sums x Theta_d on the f16 matrix cores, split-half as in the forward kernel
+//           (consumer wave d holds all of Theta_d: every 16-column slice, hi and lo),
+//   value = <R_d[x], dot_rows[x]>, reduced inside the wave, times sign, written or added to
+//           grad_pos [B,3,N].
+// The centre term runs first (rows = feat, Theta_d = theta[d], dot rows = grad_out, sign -, overwrite),
+// the neighbour term second (rows = grad_out, Theta_d = theta[d]^T, dot rows = feat, sign +, accumulate).
+// thetaF: fragments [d][part][slice][step][lane][8] of Theta_d scaled by 2^e, e at theta_exp_off.
+// ---------------------------------------------------------------------------
+template <class S>
+struct PosGeom {
+    static constexpr int KDP = rup_c(S::DIP, 32);      // contraction depth = gathered width, padded
+    static constexpr int KS2 = KDP / 32;
+    static constexpr int ARS = 4 * KDP + 16;           // row: [hi: KDP halves][lo: KDP halves][pad]
+    static constexpr int NS = S::DOP / 16;
+    static constexpr bool FITS = NS * KS2 * 8 <= 64 && S::VEC == 4;   // Theta_d fragments of one wave in 64 VGPRs
+};
+
+template <class S, bool CSR, int PM>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__ nbr,
+                     const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                     const void *__restrict__ thetaF, int theta_exp_off, const float *__restrict__ dot_rows,
+                     float *__restrict__ grad_pos, float sign, int accumulate, int N, int K,
+                     int tiles_per_cloud, int total_tiles)
+{
+    using G = WsGeom<S, PM>;
+    using PG = PosGeom<S>;
+    static_assert(PG::FITS, "shape too wide for the location-gradient kernel");
+    static_assert(G::NC >= 3, "one consumer wave per coordinate");
+    __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * PG::ARS];
+    __shared__ int s_E[2 * G::T];
+
+    const int w = threadIdx.x >> 6;
+    const TileSchedule sc(total_tiles);
+
+    if constexpr (PG::KDP > S::DIP) {
+        constexpr int PADH = PG::KDP - S::DIP;   // depth padding: never written again, must read as zero
+        for (int i = threadIdx.x; i < 2 * G::T * 2 * PADH; i += G::NT) {
+            const int e = i % PADH, part = (i / PADH) & 1, row = i / (2 * PADH);
+            *reinterpret_cast<_Float16 *>(s_A + row * PG::ARS + 2 * (part * PG::KDP + S::DIP + e)) = (_Float16)0.f;
+        }
+    }
+
+    if (w < G::NP) {
+        auto park = [&](const v4f (&acc)[S::VEC], int i, int pt, int t, bool writer) {
+            // the neighbour sum of one point (this lane: channels 4t..4t+3) as a scaled split-half row
+            float m = 0.f;
+#pragma unroll
+            for (int v = 0; v < S::VEC; ++v) m = __builtin_amdgcn_fmed3f(m, __builtin_fabsf(acc[v][3]), __builtin_inff());
+            m = group_max<S::LPR>(m);
+            const int e = 15 - __builtin_amdgcn_frexp_expf(m);
+            if (writer) {
+                const int buf = i & 1;
+                if (t == 0) s_E[buf * G::T + pt] = e;
+                char *row = s_A + (buf * G::T + pt) * PG::ARS + 2 * S::VEC * t;
+                _Float16 h[4], l[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = __builtin_ldexpf(acc[v][3], e);
+                    h[v] = (_Float16)x;
+                    l[v] = (_Float16)(x - (float)h[v]);
+                }
+                *reinterpret_cast<h4 *>(row) = h4{h[0], h[1], h[2], h[3]};
+                *reinterpret_cast<h4 *>(row + 2 * PG::KDP) = h4{l[0], l[1], l[2], l[3]};
+            }
+        };
+        if constexpr (CSR) {
+            LeanCsrProducer<S, PM, true> P;
+            P.init(rows, nullptr, off, src, N, w, sc, tiles_per_cloud);
+            P.run([&](const v4f (&acc)[S::VEC], int i) {
+                park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+            });
+        } else {
+            LeanProducer<S, PM, true> P;
+            P.init(rows, nullptr, nbr, N, K, w, sc, tiles_per_cloud);
+            P.run([&](const v4f (&acc)[S::VEC], int i) {
+                park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+            });
+        }
+        return;
+    }
+
+    // ---- consumer wave d = coordinate; waves beyond the third only keep the barriers company ----
+    const int d = w - G::NP;
+    const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
+    const bool active = d < 3;
+    h8 thH[PG::NS][PG::KS2], thL[PG::NS][PG::KS2];
+    {
+        const _Float16 *tf = reinterpret_cast<const _Float16 *>(thetaF);
+        constexpr int PER_PART = PG::NS * PG::KS2 * 64 * 8;
+        const int dd = active ? d : 0;
+#pragma unroll
+        for (int sl = 0; sl < PG::NS; ++sl)
+#pragma unroll
+            for (int s = 0; s < PG::KS2; ++s) {
+                const int at = ((sl * PG::KS2 + s) * 64 + lane) * 8;
+                thH[sl][s] = *reinterpret_cast<const h8 *>(tf + (2 * dd) * PER_PART + at);
+                thL[sl][s] = *reinterpret_cast<const h8 *>(tf + (2 * dd + 1) * PER_PART + at);
+            }
+    }
+    const int e_theta = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaF) + theta_exp_off);
+
+    for (int k = 0;; ++k) {
+        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
+        if (!r.valid) break;
+        __syncthreads();              // tile k is complete in buffer k&1
+        if (!active) continue;
+        const char *sA = s_A + (k & 1) * (G::T * PG::ARS);
+        const int *sE = s_E + (k & 1) * G::T;
+#pragma unroll
+        for (int blk = 0; blk < G::T / 16; ++blk) {
+            const int pt = blk * 16 + r16;
+            const int l = r.l0 + pt;
+            const bool on = l < N;
+            const char *arow = sA + pt * PG::ARS + 16 * q;
+            h8 bh[PG::KS2], bl[PG::KS2];
+#pragma unroll
+            for (int s = 0; s < PG::KS2; ++s) {
+                bh[s] = *reinterpret_cast<const h8 *>(arow + 64 * s);
+                bl[s] = *reinterpret_cast<const h8 *>(arow + 2 * PG::KDP + 64 * s);
+            }
+            const float *yrow = dot_rows + ((int64_t)r.b * N + (on ? l : 0)) * S::DO;
+            float part = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < PG::NS; ++sl) {
+                v4f acc[3];
+#pragma unroll
+                for (int c = 0; c < 3; ++c) acc[c] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < PG::KS2; ++s) {
+                    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[sl][s], bh[s], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[sl][s], bh[s], acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[sl][s], bl[s], acc[2], 0, 0, 0);
+                }
+                const v4f rd = acc[0] + (acc[1] + acc[2]);      // R_d[pt][16 sl + 4 q + i], still scaled
+                const int o = 16 * sl + 4 * q;
+                v4f y = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (S::DO % 4 == 0) {
+                    if (o < S::DO) y = *reinterpret_cast<const v4f *>(yrow + o);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (o + i < S::DO) y[i] = yrow[o + i];
+                }
+                part += (rd[0] * y[0] + rd[1] * y[1]) + (rd[2] * y[2] + rd[3] * y[3]);
+            }
+            part = __builtin_ldexpf(part, -(sE[pt] + e_theta));   // undo both scalings
+            part += __shfl_xor(part, 16, 64);
+            part += __shfl_xor(part, 32, 64);
+            if (q == 0 && on) {
+                float *dst = grad_pos + ((int64_t)r.b * 3 + d) * N + l;
+                *dst = accumulate ? *dst + sign * part : sign * part;
+            }
         }
     }
 }

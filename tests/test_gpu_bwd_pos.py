@@ -1,0 +1,60 @@
+"""GPU parity for the flex-conv gradient with respect to the point locations."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1803_07289_amd as fx
+from gpu_util import TOL, dev, to_layout, say
+from helpers import rel_err
+from test_gpu_parity import random_problem
+from workloads import CONFIGS, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    # B, N, K, Din, Dout
+    (1, 1000, 8, 64, 64),      # matrix-core kernels, several tiles + ragged tail
+    (2, 77, 8, 32, 32),
+    (1, 300, 16, 64, 32),
+    (2, 100, 8, 32, 64),
+    (1, 257, 8, 9, 64),        # Din = 9: no matrix-core kernel for this width -> direct kernel
+    (1, 130, 5, 64, 64),       # K not a multiple of 8 -> direct kernel
+    (2, 150, 6, 5, 7),
+    (1, 64, 1, 32, 32),
+]
+
+
+@pytest.mark.parametrize("layout", [fx.BNC, fx.BCN], ids=["bnc", "bcn"])
+@pytest.mark.parametrize("B,N,K,Din,Dout", SHAPES)
+def test_bwd_pos_matches_oracle(B, N, K, Din, Dout, layout):
+    say(f"bwd_pos B={B} N={N} K={K} Din={Din} Dout={Dout} layout={layout}")
+    pos, nbr, feat, theta, bias, g = random_problem(40 + N, B, N, K, Din, Dout)
+    ref = oracle.flexconv_bwd_pos(feat, nbr, theta, g)
+    dnbr = dev(nbr)
+    a = (to_layout(feat, layout), dnbr, dev(theta), to_layout(g, layout))
+    gp = fx.flexconv_bwd_pos(*a, layout=layout)
+    gp2 = fx.flexconv_bwd_pos(*a, layout=layout, in_edges=fx.flex_inedges_build(dnbr))
+    torch.cuda.synchronize()
+    assert rel_err(gp.cpu().numpy(), ref) <= TOL
+    assert rel_err(gp2.cpu().numpy(), ref) <= TOL
+    # translation invariance of the layer: a cloud's location gradients sum to zero
+    assert float(gp.double().sum(dim=2).abs().max()) <= 1e-3 * float(gp.double().abs().sum(dim=2).max() + 1e-30)
+
+
+def test_bwd_pos_config1_and_directional_derivative():
+    cfg = CONFIGS[1]
+    x = make_inputs(cfg)
+    ref = oracle.flexconv_bwd_pos(x.feat, x.nbr, x.theta, x.grad_out)
+    feat, nbr, theta, g = to_layout(x.feat, fx.BNC), dev(x.nbr), dev(x.theta), to_layout(x.grad_out, fx.BNC)
+    gp = fx.flexconv_bwd_pos(feat, nbr, theta, g, layout=fx.BNC)
+    torch.cuda.synchronize()
+    assert rel_err(gp.cpu().numpy(), ref) <= TOL
+    # <grad_pos, dpos> equals the change of <g, fwd> along dpos (the layer is affine in pos): tie to the forward kernel
+    pos, bias = dev(x.pos), dev(x.bias)
+    dpos = torch.randn(pos.shape, device="cuda", generator=torch.Generator("cuda").manual_seed(3)) * 0.01
+    f1 = fx.flexconv_fwd(feat, pos + dpos, nbr, theta, bias, layout=fx.BNC).double()
+    f0 = fx.flexconv_fwd(feat, pos - dpos, nbr, theta, bias, layout=fx.BNC).double()
+    lhs = float(((f1 - f0) * g.double()).sum()) / 2.0
+    rhs = float((gp.double() * dpos.double()).sum())
+    assert abs(lhs - rhs) <= 2e-3 * max(abs(lhs), abs(rhs), 1e-12)
