@@ -1530,7 +1530,9 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
     using PG = PosGeom<S>;
     static_assert(PG::FITS, "shape too wide for the location-gradient kernel");
     static_assert(G::NC >= 3, "one consumer wave per coordinate");
+    constexpr int YST = S::DOP + 4;   // floats per parked dot row (= 16 bytes mod 128: conflict-free 16-byte reads)
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * PG::ARS];
+    __shared__ __attribute__((aligned(16))) float s_Y[2 * G::T * YST];
     __shared__ int s_E[2 * G::T];
 
     const int w = threadIdx.x >> 6;
@@ -1567,17 +1569,61 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
                 *reinterpret_cast<h4 *>(row + 2 * PG::KDP) = h4{l[0], l[1], l[2], l[3]};
             }
         };
+        // the tile's dot rows travel with it: requested one tile ahead (registers), parked beside the sums
+        constexpr int CPR = S::DOP / 4;                      // four-float chunks per point
+        constexpr int NCH = cdiv_c(G::T * CPR, 64 * G::NP);  // chunks per producer thread
+        v4f yv[NCH];
+        auto load_y = [&](int b, int l0) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int ch = threadIdx.x + c * 64 * G::NP;
+                const int pt = ch / CPR, o = 4 * (ch % CPR);
+                yv[c] = v4f{0.f, 0.f, 0.f, 0.f};
+                if (ch < G::T * CPR && l0 + pt < N) {
+                    const float *srcp = dot_rows + ((int64_t)b * N + l0 + pt) * S::DO + o;
+                    if constexpr (S::DO % 4 == 0) {
+                        if (o < S::DO) yv[c] = *reinterpret_cast<const v4f *>(srcp);
+                    } else {
+#pragma unroll
+                        for (int i2 = 0; i2 < 4; ++i2)
+                            if (o + i2 < S::DO) yv[c][i2] = srcp[i2];
+                    }
+                }
+            }
+        };
+        auto park_y = [&](int i) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int ch = threadIdx.x + c * 64 * G::NP;
+                if (ch < G::T * CPR)
+                    *reinterpret_cast<v4f *>(&s_Y[((i & 1) * G::T + ch / CPR) * YST + 4 * (ch % CPR)]) = yv[c];
+            }
+        };
         if constexpr (CSR) {
             LeanCsrProducer<S, PM, true> P;
             P.init(rows, nullptr, off, src, N, w, sc, tiles_per_cloud);
+            auto coords = [&](int i, int &b, int &l0) { int lw0; P.tile_coords(i, b, lw0); l0 = lw0 - P.pw * G::PW; };
+            int b0, l00;
+            if (P.count > 0) { coords(0, b0, l00); load_y(b0, l00); }
             P.run([&](const v4f (&acc)[S::VEC], int i) {
                 park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+                park_y(i);
+                int b, l0;
+                coords(i + 1, b, l0);
+                load_y(b, l0);
             });
         } else {
             LeanProducer<S, PM, true> P;
             P.init(rows, nullptr, nbr, N, K, w, sc, tiles_per_cloud);
+            auto coords = [&](int i, int &b, int &l0) { int lw0; P.tile_coords(i, b, lw0); l0 = lw0 - P.pw * G::PW; };
+            int b0, l00;
+            if (P.count > 0) { coords(0, b0, l00); load_y(b0, l00); }
             P.run([&](const v4f (&acc)[S::VEC], int i) {
                 park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+                park_y(i);
+                int b, l0;
+                coords(i + 1, b, l0);
+                load_y(b, l0);
             });
         }
         return;
@@ -1609,6 +1655,7 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
         __syncthreads();              // tile k is complete in buffer k&1
         if (!active) continue;
         const char *sA = s_A + (k & 1) * (G::T * PG::ARS);
+        const float *sY = s_Y + (k & 1) * (G::T * YST);
         const int *sE = s_E + (k & 1) * G::T;
 #pragma unroll
         for (int blk = 0; blk < G::T / 16; ++blk) {
@@ -1622,7 +1669,7 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
                 bh[s] = *reinterpret_cast<const h8 *>(arow + 64 * s);
                 bl[s] = *reinterpret_cast<const h8 *>(arow + 2 * PG::KDP + 64 * s);
             }
-            const float *yrow = dot_rows + ((int64_t)r.b * N + (on ? l : 0)) * S::DO;
+            const float *yrow = sY + pt * YST;      // zero past the row's width and past the cloud
             float part = 0.f;
 #pragma unroll
             for (int sl = 0; sl < PG::NS; ++sl) {
@@ -1636,15 +1683,7 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
                     acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[sl][s], bl[s], acc[2], 0, 0, 0);
                 }
                 const v4f rd = acc[0] + (acc[1] + acc[2]);      // R_d[pt][16 sl + 4 q + i], still scaled
-                const int o = 16 * sl + 4 * q;
-                v4f y = {0.f, 0.f, 0.f, 0.f};
-                if constexpr (S::DO % 4 == 0) {
-                    if (o < S::DO) y = *reinterpret_cast<const v4f *>(yrow + o);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (o + i < S::DO) y[i] = yrow[o + i];
-                }
+                const v4f y = *reinterpret_cast<const v4f *>(yrow + 16 * sl + 4 * q);
                 part += (rd[0] * y[0] + rd[1] * y[1]) + (rd[2] * y[2] + rd[3] * y[3]);
             }
             part = __builtin_ldexpf(part, -(sE[pt] + e_theta));   // undo both scalings
