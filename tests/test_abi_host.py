@@ -29,7 +29,8 @@ def test_every_declared_symbol_is_exported(L):
     names = declared_symbols()
     assert {"flexconv_fwd", "flexconv_bwd", "flexpool_fwd", "flexpool_bwd", "flex_inedges_build",
             "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
-            "flexconv_has_fast_path"} <= set(names)
+            "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
+            "flexconv_bwd_pos"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -64,6 +65,33 @@ def test_null_and_shape_errors_precede_any_launch(L):
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, none, 0, None) == 4
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, ctypes.c_void_p(260), 1 << 20, None) == 4
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, one, 512, None) == 4
+
+
+def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
+    one, none = ctypes.c_void_p(256), None
+    big = 1 << 30
+    # flexupsample_fwd(feat_small, sel, nbr, out, argmax, B, Ns, Nf, K, C, layout, ws, ws_bytes, stream)
+    assert L.flexupsample_fwd(one, none, one, one, one, 1, 4, 16, 2, 8, 0, one, big, None) == 1
+    assert L.flexupsample_fwd(one, one, one, one, one, 1, 17, 16, 2, 8, 0, one, big, None) == 2    # Ns > Nf
+    assert L.flexupsample_fwd(one, one, one, one, one, 1, 0, 16, 2, 8, 0, one, big, None) == 2
+    assert L.flexupsample_fwd(one, one, one, one, one, 1, 4, 16, 2, 8, 2, one, big, None) == 2     # layout
+    assert L.flexupsample_fwd(one, one, one, one, one, 1, 4, 16, 2, 8, 0, none, 0, None) == 4
+    assert L.flexupsample_fwd(one, one, one, one, one, 1, 4, 1 << 20, 2, 8, 0, one, 1024, None) == 4
+    # flexupsample_bwd(grad_out, argmax, sel, in_off, in_src, grad_small, B, Ns, Nf, K, C, layout, stream)
+    assert L.flexupsample_bwd(one, one, one, none, one, one, 1, 4, 16, 2, 8, 0, None) == 1          # lists are required
+    assert L.flexupsample_bwd(one, one, one, one, one, one, 1, 4, 16, 2, 0, 0, None) == 2
+    # flex_validate_selection(sel, B, Ns, Nf, bad, ws, ws_bytes, stream)
+    assert L.flex_validate_selection(one, 1, 4, 16, none, one, big, None) == 1
+    assert L.flex_validate_selection(one, 1, 4, 16, one, one, 16, None) == 4
+    # flexconv_bwd_pos(feat, nbr, theta, grad_out, in_off, in_src, grad_pos, B, N, K, Din, Dout, layout, ws, ws_bytes, stream)
+    assert L.flexconv_bwd_pos(one, one, none, one, none, none, one, 1, 8, 2, 4, 4, 0, one, big, None) == 1
+    assert L.flexconv_bwd_pos(one, one, one, one, one, none, one, 1, 8, 2, 4, 4, 0, one, big, None) == 1   # in_off without in_src
+    assert L.flexconv_bwd_pos(one, one, one, one, none, none, one, 1, 8, 9, 4, 4, 0, one, big, None) == 2  # K > N
+    assert L.flexconv_bwd_pos(one, one, one, one, none, none, one, 1, 64, 8, 64, 64, 1, one, 256, None) == 4
+    w = L.flexconv_workspace_bytes
+    assert w(4, 2, 1000, 1, 1, 1, 0) == 8192                   # inverse map: 4 bytes per larger-layer point, 256-aligned
+    assert w(6, 1, 4096, 8, 64, 64, 1) > w(5, 1, 4096, 8, 64, 64, 1) > 256    # lists built inside the call cost workspace
+    assert w(5, 1, 4096, 8, 5, 7, 1) == 256                    # direct kernel: nothing needed
 
 
 def test_workspace_sizes(L):

@@ -42,6 +42,10 @@ SHAPES = [
     (1, 100, 4, 128, 64),
     (1, 200, 40, 64, 64),      # K larger than one staging chunk
     (1, 64, 1, 32, 32),        # K = 1
+    (1, 8, 8, 64, 64),         # one partial tile, every point a neighbour of every point
+    (3, 17, 8, 64, 64),        # three clouds, each a single ragged tile
+    (1, 48, 16, 64, 64),       # exactly one tile of the widest kernel, two batches
+    (2, 49, 8, 32, 32),        # one point past a tile
     (2, 150, 6, 5, 7),         # no tiled kernel: generic path
     (1, 90, 4, 20, 16),        # generic path, Din % 4 == 0
 ]
