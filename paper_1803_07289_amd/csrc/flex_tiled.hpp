@@ -48,6 +48,7 @@ struct __attribute__((aligned(16))) Edge {
 // that tiles in flight on one XCD (and its private L2) are spatial neighbours.
 struct TileSchedule {
     int first, end, step;
+    TileSchedule() = default;
     __device__ __forceinline__ TileSchedule(int total_tiles)
     {
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;

@@ -152,6 +152,39 @@ __device__ __forceinline__ TileRef tile_ref(const TileSchedule &sc, int k, int t
     return r;
 }
 
+// Walks a workgroup's tiles (sc.first, sc.first + sc.step, ... below sc.end) and keeps the cloud and the
+// tile's index inside its cloud up to date by additions: a wave issues about one instruction per five
+// clocks whatever its kind, so a division per tile (some twenty scalar instructions) is not free.
+struct TileWalk {
+    int tile, end, step, tpc;
+    int step_b, step_t;          // the stride in whole clouds and the rest in tiles
+    int b, tic;                  // cloud, tile inside the cloud
+    __device__ __forceinline__ TileWalk(const TileSchedule &sc, int tiles_per_cloud)
+        : tile(sc.first), end(sc.end), step(sc.step), tpc(tiles_per_cloud)
+    {
+        const int t0 = sc.first < sc.end ? sc.first : 0;
+        b = t0 / tpc;
+        tic = t0 - b * tpc;
+        step_b = step / tpc;
+        step_t = step - step_b * tpc;
+    }
+    __device__ __forceinline__ bool valid() const { return tile < end; }
+    __device__ __forceinline__ bool has_next() const { return tile + step < end; }
+    // one stride on if go (selects, no branches)
+    __device__ __forceinline__ void next_if(bool go)
+    {
+        tile += go ? step : 0;
+        tic += go ? step_t : 0;
+        b += go ? step_b : 0;
+        const bool wrap = tic >= tpc;
+        tic -= wrap ? tpc : 0;
+        b += wrap ? 1 : 0;
+    }
+    __device__ __forceinline__ void next() { next_if(true); }
+    // stays on the last tile instead of walking past it
+    __device__ __forceinline__ void next_clamped() { next_if(has_next()); }
+};
+
 // ---------------------------------------------------------------------------
 // Producer side
 // ---------------------------------------------------------------------------
@@ -490,7 +523,8 @@ struct LeanProducer {
     const float *rows, *pos;
     const int32_t *nbr;
     int N, K, KB, pw;
-    int first, step, count, tiles_per_cloud;   // this workgroup's tiles: first + i*step, i < count
+    int count, tiles_per_cloud;  // tiles of this workgroup
+    TileSchedule sched;
     // compute layout: lane = (row group grp, lane t inside the row)
     int grp, t;
     bool lane_on;
@@ -519,7 +553,7 @@ struct LeanProducer {
         e_col = c < 3 ? c : 2;
         e_mul = c < 3 ? 1.f : 0.f;
         e_fix = c < 3 ? 0.f : 1.f;
-        first = sc.first; step = sc.step; tiles_per_cloud = tiles_per_cloud_;
+        sched = sc; tiles_per_cloud = tiles_per_cloud_;
         count = (sc.first < sc.end) ? (sc.end - sc.first + sc.step - 1) / sc.step : 0;
     }
 
@@ -528,17 +562,22 @@ struct LeanProducer {
         int lw0;        // first point of this wave in the tile
         int k0;         // first neighbour slot
     };
-    // batch m of this workgroup (m clamped to the last one)
-    __device__ __forceinline__ Batch batch(int m) const
+    // Walks the workgroup's batches in order (KB per tile) and stops on the last one.
+    struct BatchWalk {
+        TileWalk tw;
+        int kb;
+        __device__ __forceinline__ BatchWalk(const TileSchedule &sc, int tpc) : tw(sc, tpc), kb(0) {}
+    };
+    __device__ __forceinline__ Batch get(const BatchWalk &c) const
     {
-        m = min(m, count * KB - 1);
-        const int i = m / KB;
-        const int tile = first + i * step;
-        Batch x;
-        x.b = tile / tiles_per_cloud;
-        x.lw0 = (tile - x.b * tiles_per_cloud) * G::T + pw * G::PW;
-        x.k0 = (m - i * KB) * U;
-        return x;
+        return Batch{c.tw.b, c.tw.tic * G::T + pw * G::PW, c.kb * U};
+    }
+    __device__ __forceinline__ void advance(BatchWalk &c) const
+    {
+        const bool in_tile = c.kb + 1 < KB;
+        const bool go = !in_tile && c.tw.has_next();
+        c.kb = in_tile ? c.kb + 1 : (go ? 0 : c.kb);
+        c.tw.next_if(go);
     }
 
     // entry layout: neighbour ids of both halves
@@ -576,17 +615,18 @@ struct LeanProducer {
         }
     }
 
-    // cloud and first point (of this wave) of the workgroup's tile i, i clamped to the last one
-    __device__ __forceinline__ void tile_coords(int i, int &b, int &lw0) const
+    // cloud and first point (of this wave) of the workgroup's first tile
+    __device__ __forceinline__ void first_coords(int &b, int &lw0) const
     {
-        const int tile = first + min(i, count - 1) * step;
-        b = tile / tiles_per_cloud;
-        lw0 = (tile - b * tiles_per_cloud) * G::T + pw * G::PW;
+        const TileWalk tw(sched, tiles_per_cloud);
+        b = tw.b;
+        lw0 = tw.tic * G::T + pw * G::PW;
     }
 
-    // The producer role for every tile of this workgroup.  fin(acc, i) parks the finished aggregate of
-    // the workgroup's tile i (this lane: channels VEC*t.. of point pw*PW+grp, all four j) in LDS; the
-    // workgroup barrier that hands the tile to the consumers follows it.
+    // The producer role for every tile of this workgroup.  fin(acc, i, nb, nlw0) parks the finished
+    // aggregate of the workgroup's tile i (this lane: channels VEC*t.. of point pw*PW+grp, all four j)
+    // in LDS; (nb, nlw0) = cloud and this wave's first point of tile i+1 (of tile i again after the last
+    // one).  The workgroup barrier that hands the tile to the consumers follows it.
     template <class Fin>
     __device__ __forceinline__ void run(Fin &&fin)
     {
@@ -594,12 +634,16 @@ struct LeanProducer {
         float f[U][S::VEC];      // rows in flight (compute layout)
         int idn[2];              // entry layout: ids of the batch after the one whose rows are in flight
         float pn[2], pc;         // entry layout: positions for the batch whose rows are in flight
+        BatchWalk walk(sched, tiles_per_cloud);
+        Batch x1;                // batch m+1 at the top of iteration m
         {
             // prologue: rows and positions of batch 0 in flight, ids of batch 1 requested
             int id0[2];
-            const Batch x0 = batch(0);
+            const Batch x0 = get(walk);
+            advance(walk);
+            x1 = get(walk);
             load_ids(id0, x0);
-            load_ids(idn, batch(1));
+            load_ids(idn, x1);
             pn[0] = pn[1] = pc = 0.f;
             if constexpr (!SUM) load_pos(pn, pc, id0, x0);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * S::DI);
@@ -618,13 +662,16 @@ struct LeanProducer {
             dpe[0] = __float_as_int(fmaf(pn[0] - pc, e_mul, e_fix));
             dpe[1] = __float_as_int(fmaf(pn[1] - pc, e_mul, e_fix));
             // ids of batch m+1 are here: their positions and (below) rows go in flight; ids of batch m+2 too
-            const Batch x1 = batch(m + 1);
             int idc[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
             if constexpr (!SUM) load_pos(pn, pc, idn, x1);
-            load_ids(idn, batch(m + 2));
+            advance(walk);
+            const Batch x2 = get(walk);
+            load_ids(idn, x2);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * S::DI);
+            const int nb = x1.b, nlw0 = x1.lw0;
+            x1 = x2;
             float dpc[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) dpc[u] = SUM ? 0.f : __int_as_float(spread(dpe, perm_dp, u));
@@ -655,7 +702,7 @@ struct LeanProducer {
 
             if (++kb == KB) {
                 kb = 0;
-                fin(acc, tile_i);
+                fin(acc, tile_i, nb, nlw0);
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
                 ++tile_i;
@@ -684,7 +731,8 @@ struct LeanCsrProducer {
     const float *rows, *pos;
     const int32_t *off, *src;
     int N, pw;
-    int first, step, count, tiles_per_cloud;
+    int count, tiles_per_cloud;
+    TileSchedule sched;
     int grp, t;
     bool lane_on;
     unsigned lane_off;
@@ -711,7 +759,7 @@ struct LeanCsrProducer {
         e_col = c < 3 ? c : 2;
         e_mul = c < 3 ? 1.f : 0.f;
         e_fix = c < 3 ? 0.f : 1.f;
-        first = sc.first; step = sc.step; tiles_per_cloud = tiles_per_cloud_;
+        sched = sc; tiles_per_cloud = tiles_per_cloud_;
         count = (sc.first < sc.end) ? (sc.end - sc.first + sc.step - 1) / sc.step : 0;
     }
 
@@ -729,33 +777,37 @@ struct LeanCsrProducer {
         int b, lw0;
         int lo, deg;             // this lane's point: start and length of its list
         int lo_n, hi_n;          // next tile: list bounds of this lane's point (in flight)
+        TileWalk tw;             // the tile those bounds belong to (the last tile again past the end)
+        __device__ __forceinline__ Cursor(const TileSchedule &sc, int tpc) : tw(sc, tpc) {}
     };
 
-    __device__ __forceinline__ void tile_coords(int i, int &b, int &lw0) const
+    __device__ __forceinline__ void first_coords(int &b, int &lw0) const
     {
-        const int tile = first + min(i, count - 1) * step;
-        b = tile / tiles_per_cloud;
-        lw0 = (tile - b * tiles_per_cloud) * G::T + pw * G::PW;
+        const TileWalk tw(sched, tiles_per_cloud);
+        b = tw.b;
+        lw0 = tw.tic * G::T + pw * G::PW;
     }
-    __device__ __forceinline__ void request_bounds(int i, int &lo_n, int &hi_n) const
+    // list bounds of this lane's point in the walk's tile
+    __device__ __forceinline__ void request_bounds(Cursor &c) const
     {
-        int b, lw0;
-        tile_coords(i, b, lw0);
-        const int64_t gp = (int64_t)b * N + min(lw0 + e_g, N - 1);
-        lo_n = off[gp];
-        hi_n = off[gp + 1];
+        const int64_t gp = (int64_t)c.tw.b * N + min(c.tw.tic * G::T + pw * G::PW + e_g, N - 1);
+        c.lo_n = off[gp];
+        c.hi_n = off[gp + 1];
     }
-    // the cursor takes the bounds requested for tile i (they must be in lo_n / hi_n) and requests tile i+1's
+    // the cursor takes the bounds requested for tile i (in lo_n / hi_n, the walk stands on that tile) and
+    // requests tile i+1's
     __device__ __forceinline__ void enter_tile(Cursor &c, int i) const
     {
         c.i = i; c.bi = 0;
-        tile_coords(i, c.b, c.lw0);
+        c.b = c.tw.b;
+        c.lw0 = c.tw.tic * G::T + pw * G::PW;
         c.lo = c.lo_n;
         c.deg = (c.lw0 + e_g < N) ? c.hi_n - c.lo_n : 0;      // points past the cloud have no list
         const int d = max(max(__builtin_amdgcn_readlane(c.deg, 0), __builtin_amdgcn_readlane(c.deg, 4)),
                           max(__builtin_amdgcn_readlane(c.deg, 8), __builtin_amdgcn_readlane(c.deg, 12)));
         c.nb = max(1, (d + U - 1) / U);
-        request_bounds(i + 1, c.lo_n, c.hi_n);
+        c.tw.next_clamped();
+        request_bounds(c);
     }
     // entry-layout ids of the cursor's batch + its descriptor; then the cursor moves on
     __device__ __forceinline__ void fetch(Cursor &c, int (&id)[2], Desc &d) const
@@ -814,9 +866,9 @@ struct LeanCsrProducer {
         int idn[2];              // entry layout: ids of the batch after the one whose rows are in flight
         float pn[2], pc;         // entry layout: positions for the batch whose rows are in flight
         Desc d0, d1;             // batch whose rows are in flight; batch of idn
-        Cursor c;
+        Cursor c(sched, tiles_per_cloud);
         {
-            request_bounds(0, c.lo_n, c.hi_n);
+            request_bounds(c);
             enter_tile(c, 0);
             int id0[2];
             fetch(c, id0, d0);
@@ -871,7 +923,7 @@ struct LeanCsrProducer {
             }
 
             if (last) {
-                fin(acc, tile_i);
+                fin(acc, tile_i, d0.b, d0.lw0);      // d0: first batch of the next tile by now
 #pragma unroll
                 for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
                 ++tile_i;
@@ -941,9 +993,9 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
         a_off[it] = ((idx / G::NS) * 16 + r16) * G::ARS + 16 * q;
     }
 
-    for (int k = 0;; ++k) {
-        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-        if (!r.valid) break;
+    TileWalk tw(sc, tiles_per_cloud);
+    for (int k = 0; tw.valid(); ++k, tw.next()) {
+        const TileRef r{true, tw.b, tw.tic * G::T};
         __syncthreads();              // tile k is complete in buffer k&1
         if (!active) continue;
         const char *sA = s_A + (k & 1) * (G::T * G::ROWB);
@@ -1008,7 +1060,7 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
     if (w < G::NP) {
         LeanProducer<S, PM> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
-        P.run([&](const v4f (&acc)[S::VEC], int i) {
+        P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
             store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
                                 P.grp < G::PW && (S::VEC * P.t) < S::DIP);
@@ -1045,7 +1097,7 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
     if (w < G::NP) {
         LeanCsrProducer<S, PM> P;
         P.init(rows, pos, off, src, N, w, sc, tiles_per_cloud);
-        P.run([&](const v4f (&acc)[S::VEC], int i) {
+        P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
             store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
                                 P.grp < G::PW && (S::VEC * P.t) < S::DIP);
@@ -1144,9 +1196,9 @@ void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__re
             a_off[it] = ((idx / G::NS) * 16 + r16) * G::AST + 4 * q;
         }
 
-        for (int k = 0;; ++k) {
-            const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-            if (!r.valid) break;
+        TileWalk tw(sc, tiles_per_cloud);
+        for (int k = 0; tw.valid(); ++k, tw.next()) {
+            const TileRef r{true, tw.b, tw.tic * G::T};
             __syncthreads();              // tile k is complete in buffer k&1
             if (!active) continue;
             const float *sA = reinterpret_cast<const float *>(s_A + (k & 1) * (G::T * G::ROWB));
@@ -1246,9 +1298,9 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
 #pragma unroll
         for (int a = 0; a < NBW; ++a) acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    for (int k = 0;; ++k) {
-        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-        if (!r.valid) break;
+    TileWalk tw(sc, tiles_per_cloud);
+    for (int k = 0; tw.valid(); ++k, tw.next()) {
+        const TileRef r{true, tw.b, tw.tic * G::T};
         __syncthreads();
         const float *sA = reinterpret_cast<const float *>(s_A + (k & 1) * (G::T * G::ROWB)), *sG = s_G[k & 1];
 #pragma unroll
@@ -1352,9 +1404,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
         constexpr int CPR = S::DOP / 4;                      // chunks per point
         constexpr int NCH = cdiv_c(G::T * CPR, 64 * G::NP);  // chunks per thread
         v4f gv[NCH];
-        auto load_g = [&](int i) {
-            int b, lw0;
-            P.tile_coords(i, b, lw0);
+        auto load_g = [&](int b, int lw0) {
             const int l0 = lw0 - P.pw * G::PW;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
@@ -1373,8 +1423,12 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
                 }
             }
         };
-        if (P.count > 0) load_g(0);
-        P.run([&](const v4f (&acc)[S::VEC], int i) {
+        if (P.count > 0) {
+            int b0, lw00;
+            P.first_coords(b0, lw00);
+            load_g(b0, lw00);
+        }
+        P.run([&](const v4f (&acc)[S::VEC], int i, int nb, int nlw0) {
             const int buf = i & 1;
             // aggregate rows, three bf16 pieces
             if (P.grp < G::PW && (S::VEC * P.t) < S::DIP) {
@@ -1412,7 +1466,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
                     *reinterpret_cast<uint2 *>(d + 4 * S::DOP) = make_uint2(l0, l1);
                 }
             }
-            load_g(i + 1);
+            load_g(nb, nlw0);
         });
         return;
     }
@@ -1438,9 +1492,9 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
 #pragma unroll
         for (int a = 0; a < NBW; ++a) { acc[c][a] = v4f{0.f, 0.f, 0.f, 0.f}; tot[c][a] = v4f{0.f, 0.f, 0.f, 0.f}; }
 
-    for (int k = 0;; ++k) {
-        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-        if (!r.valid) break;
+    TileWalk tw(sc, tiles_per_cloud);
+    for (int k = 0; tw.valid(); ++k, tw.next()) {
+        const TileRef r{true, tw.b, tw.tic * G::T};
         if (k % FLUSH == 0 && k > 0) {
 #pragma unroll
             for (int c = 0; c < MBW; ++c)
@@ -1602,28 +1656,28 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
         if constexpr (CSR) {
             LeanCsrProducer<S, PM, true> P;
             P.init(rows, nullptr, off, src, N, w, sc, tiles_per_cloud);
-            auto coords = [&](int i, int &b, int &l0) { int lw0; P.tile_coords(i, b, lw0); l0 = lw0 - P.pw * G::PW; };
-            int b0, l00;
-            if (P.count > 0) { coords(0, b0, l00); load_y(b0, l00); }
-            P.run([&](const v4f (&acc)[S::VEC], int i) {
+            if (P.count > 0) {
+                int b0, lw00;
+                P.first_coords(b0, lw00);
+                load_y(b0, lw00 - P.pw * G::PW);
+            }
+            P.run([&](const v4f (&acc)[S::VEC], int i, int nb, int nlw0) {
                 park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
                 park_y(i);
-                int b, l0;
-                coords(i + 1, b, l0);
-                load_y(b, l0);
+                load_y(nb, nlw0 - P.pw * G::PW);
             });
         } else {
             LeanProducer<S, PM, true> P;
             P.init(rows, nullptr, nbr, N, K, w, sc, tiles_per_cloud);
-            auto coords = [&](int i, int &b, int &l0) { int lw0; P.tile_coords(i, b, lw0); l0 = lw0 - P.pw * G::PW; };
-            int b0, l00;
-            if (P.count > 0) { coords(0, b0, l00); load_y(b0, l00); }
-            P.run([&](const v4f (&acc)[S::VEC], int i) {
+            if (P.count > 0) {
+                int b0, lw00;
+                P.first_coords(b0, lw00);
+                load_y(b0, lw00 - P.pw * G::PW);
+            }
+            P.run([&](const v4f (&acc)[S::VEC], int i, int nb, int nlw0) {
                 park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
                 park_y(i);
-                int b, l0;
-                coords(i + 1, b, l0);
-                load_y(b, l0);
+                load_y(nb, nlw0 - P.pw * G::PW);
             });
         }
         return;
@@ -1649,9 +1703,9 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
     }
     const int e_theta = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaF) + theta_exp_off);
 
-    for (int k = 0;; ++k) {
-        const TileRef r = tile_ref(sc, k, tiles_per_cloud, G::T);
-        if (!r.valid) break;
+    TileWalk tw(sc, tiles_per_cloud);
+    for (int k = 0; tw.valid(); ++k, tw.next()) {
+        const TileRef r{true, tw.b, tw.tic * G::T};
         __syncthreads();              // tile k is complete in buffer k&1
         if (!active) continue;
         const char *sA = s_A + (k & 1) * (G::T * PG::ARS);
