@@ -646,9 +646,14 @@ struct LeanProducer {
             load_ids(idn, x1);
             pn[0] = pn[1] = pc = 0.f;
             if constexpr (!SUM) load_pos(pn, pc, id0, x0);
+            // The rows must be the youngest loads in flight when the loop is entered, as they are at the
+            // end of every iteration: the wait at the loop top (for positions and ids) is one instruction
+            // for both ways in, and a load issued after the rows would turn it into a wait for the rows.
+            __builtin_amdgcn_sched_barrier(0);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * S::DI);
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
+            __builtin_amdgcn_sched_barrier(0);
         }
         const int total = count * KB;
         int kb = 0, tile_i = 0;
@@ -698,6 +703,7 @@ struct LeanProducer {
                     fma_row<S>(acc, dpc[u], fv);
                 }
                 load_row(f[u], idc[u], rb);     // row u of batch m+1 takes the freed registers
+                __builtin_amdgcn_sched_barrier(0);   // keep this shape: one row consumed, one requested
             }
 
             if (++kb == KB) {
@@ -875,9 +881,11 @@ struct LeanCsrProducer {
             fetch(c, idn, d1);
             pn[0] = pn[1] = pc = 0.f;
             if constexpr (!SUM) load_pos(pn, pc, id0, d0);
+            __builtin_amdgcn_sched_barrier(0);      // rows youngest, as at the end of every iteration
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * S::DI);
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
+            __builtin_amdgcn_sched_barrier(0);
         }
         int tile_i = 0;
         v4f acc[S::VEC];
@@ -920,6 +928,10 @@ struct LeanCsrProducer {
                     }
                 }
                 load_row(f[u], idc[u], rb);
+                // keep the loop's shape: the scheduler would otherwise collect the eight loads at the end
+                // of the iteration and wait for all of them at its start (no row would be in flight
+                // while the previous ones are accumulated)
+                __builtin_amdgcn_sched_barrier(0);
             }
 
             if (last) {
