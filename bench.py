@@ -43,7 +43,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
                     help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; upsample = flex-upsampling from a "
-                         "quarter of the points, bwd_pos = location gradient; neither is part of the default step)")
+                         "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
+                         "quarter of the points; none of them is part of the default step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the feature tensor (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against them")
@@ -96,16 +97,19 @@ def main():
     torch.cuda.synchronize()
     inedges_ms = ev0.elapsed_time(ev1)
 
-    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos") if n in ops]
+    names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos", "pool_sub") if n in ops]
     state = {}
-    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos")
-    if "upsample" in ops:
+    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
+           "pool_sub_fwd", "pool_sub_bwd")
+    if "upsample" in ops or "pool_sub" in ops:
         # the smaller layer: a seeded quarter of the points (a decoder stage raises the resolution 4x)
         Ns = max(1, N // 4)
         sel_np = np.stack([np.sort(np.random.default_rng([cfg.seed, 300 + b]).permutation(N)[:Ns]) for b in range(B)])
         sel = torch.from_numpy(sel_np.astype(np.int32)).cuda()
         idx = sel.long()[:, :, None].expand(B, Ns, Din) if layout == fx.BNC else sel.long()[:, None, :].expand(B, Din, Ns)
         feat_small = torch.gather(feat, 1 if layout == fx.BNC else 2, idx).contiguous()
+        g_small = torch.gather(gpool, 1 if layout == fx.BNC else 2, idx).contiguous()
+        sub_edges = fx.flex_inedges_build_sub(nbr, sel) if "pool_sub" in ops else None
 
     def step(events=None):
         """One pass of the hot path.  flexconv_bwd is issued as two calls (parameter gradients,
@@ -141,6 +145,13 @@ def main():
         if "bwd_pos" in ops:
             state["grad_pos"] = fx.flexconv_bwd_pos(feat, nbr, theta, g, layout=layout, in_edges=in_edges)
         mark(8)
+        if "pool_sub" in ops:
+            state["pool_sub"] = fx.flexpool_sub_fwd(feat, nbr, sel, layout=layout)
+        mark(9)
+        if "pool_sub" in ops:
+            state["pool_sub_grad"] = fx.flexpool_sub_bwd(g_small, state["pool_sub"][1], N, layout=layout,
+                                                         in_edges=sub_edges)
+        mark(10)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(feat)
@@ -152,7 +163,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(9)] for _ in range(args.steps)]
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(11)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -184,7 +195,12 @@ def main():
                 "upsample_fwd": Din + 1 + 8 + 4 * K + 8 * Din,
                 "upsample_bwd": 8 * Din + 1 + 4 * (K + 1) + Din,
                 # two passes: each reads features and upstream gradient once, ids / lists, writes 3 floats
-                "bwd_pos": 2 * (4 * Din + 4 * Dout) + 4 * K + 4 * (K + 1) + 12 + 24}
+                "bwd_pos": 2 * (4 * Din + 4 * Dout) + 4 * K + 4 * (K + 1) + 12 + 24,
+                # per point before subsampling, a quarter kept: the features once (every row is somebody's
+                # neighbour), ids of the kept centres, sel, out + winners of the kept / their gradient +
+                # winners, lists over the kept centres, the full-size gradient written
+                "pool_sub_fwd": 4 * Din + K + 1 + 2 * Din,
+                "pool_sub_bwd": 2 * Din + (K + 4) + 4 * Din}
     kernel_of = {"fwd": "gather_contract_lean_kernel (flexconv_fwd)",
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
@@ -192,7 +208,9 @@ def main():
                  "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)",
                  "upsample_fwd": "upsample_fwd_bnc4_kernel (flexupsample_fwd)",
                  "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)",
-                 "bwd_pos": "grad_pos_kernel x2 (flexconv_bwd_pos: centre term, neighbour term)"}
+                 "bwd_pos": "grad_pos_kernel x2 (flexconv_bwd_pos: centre term, neighbour term)",
+                 "pool_sub_fwd": "pool_fwd_bnc4_kernel<SUB> (flexpool_sub_fwd)",
+                 "pool_sub_bwd": "pool_bwd_gather_bnc4_kernel<SUB> (flexpool_sub_bwd)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
     measured_traffic = MEASURED_TRAFFIC

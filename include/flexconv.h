@@ -148,6 +148,42 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
                  int B, int N, int K, int C, int layout, void *stream);
 
 /*
+ * Flex-max-pooling with subsampling, forward (Sec. 4.1: pooling runs before the subsampling step;
+ * Sec. 5: the last layer of an encoder stage, which keeps a quarter of the points).  The result
+ * is that of flexpool_fwd restricted to the kept centres, and only those are evaluated:
+ *   out[b,c,j] = max_k feat[b,c,nbr[b,k,sel[b,j]]],  argmax[b,c,j] = the winning point, an index
+ *   into the N points before subsampling (pooling's tie rule).
+ * feat [B,C,N] or [B,N,C]; nbr int32 [B,K,N]; sel int32 [B,Ns], indices in [0,N) (an entry
+ * outside is clamped into the range); out / argmax [B,C,Ns] or [B,Ns,C].
+ */
+int flexpool_sub_fwd(const float *feat, const int32_t *nbr, const int32_t *sel, float *out,
+                     int32_t *argmax, int B, int N, int Ns, int K, int C, int layout, void *stream);
+
+/*
+ * Flex-max-pooling with subsampling, backward: grad_feat[b,c,m] = sum of grad_out[b,c,j] over
+ * the kept centres j with argmax[b,c,j] = m, zero elsewhere; grad_feat [B,C,N] or [B,N,C] is
+ * overwritten.  Two forms, as for flexpool_bwd:
+ *   in_off / in_src NULL: zero fill + fp32 atomic adds (K is ignored);
+ *   in_off / in_src given: the lists flex_inedges_build_sub made for (nbr, sel) of the forward
+ *     pass (same K): every point sums over the kept centres that list it.  No atomics, fixed
+ *     order, several times faster.
+ */
+int flexpool_sub_bwd(const float *grad_out, const int32_t *argmax,
+                     const int32_t *in_off, const int32_t *in_src, float *grad_feat,
+                     int B, int N, int Ns, int K, int C, int layout, void *stream);
+
+/*
+ * Transposed neighbour lists restricted to kept centres (static per layer, like the neighbour
+ * tensor itself, Sec. 4.1): for every point m of the N, the ascending row numbers j in [0,Ns) of
+ * the kept centres sel[b,j] whose neighbourhood names m, once per naming slot.
+ * in_off int32 [B*N+1], in_src int32 [B*K*Ns]; workspace as for flex_inedges_build
+ * (flexconv_workspace_bytes(FLEX_OP_INEDGES, B, N, ...)).
+ */
+int flex_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
+                           int32_t *in_off, int32_t *in_src,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Flex-upsampling forward (Sec. 4.1): the features of the smaller layer's points are copied
  * to their points in the larger layer, every other point of the larger layer starts at zero,
  * and flex-max-pooling runs over the larger layer's neighbourhoods:

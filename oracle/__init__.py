@@ -141,6 +141,33 @@ def flexpool_bwd(grad_out, argmax, l_range=None):
     return gf
 
 
+def flexpool_sub_fwd(feat, nbr, sel):
+    """Flex-max-pooling then subsampling: feat [B,C,N], nbr [B,K,N], sel int32 [B,Ns].
+    Returns (out float32, argmax int32), both [B,C,Ns]."""
+    feat, nbr, sel = _f32(feat), _i32(nbr), _i32(sel)
+    B, C, N = feat.shape
+    K = nbr.shape[1]
+    Ns = sel.shape[1]
+    assert sel.shape == (B, Ns) and nbr.shape == (B, K, N)
+    assert count_bad_neighbors(nbr, N) == 0
+    out = np.zeros((B, C, Ns), np.float32)
+    arg = np.zeros((B, C, Ns), np.int32)
+    _check(_load().oracle_flexpool_sub_fwd(_p(feat), _p(nbr), _p(sel), _p(out), _p(arg), B, N, Ns, K, C),
+           "oracle_flexpool_sub_fwd")
+    return out, arg
+
+
+def flexpool_sub_bwd(grad_out, argmax, sel, N):
+    """Backward of flexpool_sub_fwd: grad_out / argmax [B,C,Ns], sel [B,Ns].  Returns grad_feat float64 [B,C,N]."""
+    grad_out, argmax, sel = _f32(grad_out), _i32(argmax), _i32(sel)
+    B, C, Ns = grad_out.shape
+    assert argmax.shape == (B, C, Ns) and sel.shape == (B, Ns)
+    gf = np.zeros((B, C, N), np.float64)
+    _check(_load().oracle_flexpool_sub_bwd(_p(grad_out), _p(argmax), _p(sel), _p(gf), B, int(N), Ns, C),
+           "oracle_flexpool_sub_bwd")
+    return gf
+
+
 def flexupsample_fwd(feat_small, sel, nbr, l_range=None):
     """Flex-upsampling: feat_small [B,C,Ns], sel int32 [B,Ns] (indices in the larger layer),
     nbr int32 [B,K,Nf].  Returns (out float32, argmax int32), both [B,C,L]."""

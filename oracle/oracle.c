@@ -387,6 +387,88 @@ int oracle_flexupsample_bwd(const float *grad_out, const int32_t *argmax, const 
 }
 
 /* ---------------------------------------------------------------------------
+ * Flex-max-pooling with subsampling (Sec. 4.1: pooling is applied before the
+ * subsampling step; Sec. 5: the layer that ends an encoder stage).  Taken in
+ * the paper's order: the neighbourhood maximum at EVERY point (pooling's tie
+ * rule), then the columns of the kept points sel[b,j] are copied out.
+ * out / argmax are [B,C,Ns]; argmax holds indices into the N points.
+ * ------------------------------------------------------------------------- */
+int oracle_flexpool_sub_fwd(const float *feat, const int32_t *nbr, const int32_t *sel,
+                            float *out, int32_t *argmax, int B, int N, int Ns, int K, int C)
+{
+    if (!feat || !nbr || !sel || !out || !argmax) return 1;
+    if (B <= 0 || N <= 0 || Ns <= 0 || K <= 0 || C <= 0 || Ns > N) return 2;
+    float *pooled = (float *)malloc(sizeof(float) * (size_t)B * C * N);
+    int32_t *winner = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * C * N);
+    if (!pooled || !winner) { free(pooled); free(winner); return 6; }
+    int rc = 0;
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l)
+            for (int c = 0; c < C; ++c) {
+                int best = nbr[IDX3(b, 0, l, K, N)];
+                float bv = feat[IDX3(b, c, best, C, N)];
+                for (int k = 1; k < K; ++k) {
+                    const int n = nbr[IDX3(b, k, l, K, N)];
+                    const float v = feat[IDX3(b, c, n, C, N)];
+                    if (v > bv || (v == bv && n < best)) { bv = v; best = n; }
+                }
+                pooled[IDX3(b, c, l, C, N)] = bv;
+                winner[IDX3(b, c, l, C, N)] = best;
+            }
+    for (int b = 0; b < B && rc == 0; ++b)
+        for (int j = 0; j < Ns; ++j) {
+            const int l = sel[(int64_t)b * Ns + j];
+            if (l < 0 || l >= N) { rc = 2; break; }
+            for (int c = 0; c < C; ++c) {
+                out[IDX3(b, c, j, C, Ns)] = pooled[IDX3(b, c, l, C, N)];
+                argmax[IDX3(b, c, j, C, Ns)] = winner[IDX3(b, c, l, C, N)];
+            }
+        }
+    free(pooled); free(winner);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------
+ * Backward of pooling with subsampling, in reverse order of the forward steps:
+ * the subsampling step hands grad_out[b,c,j] to column sel[b,j] of the pooled
+ * tensor's gradient (a point that was not kept gets zero; a point kept twice gets
+ * both), the pooling step routes every column to its recorded winner.  The winner
+ * of a kept centre is argmax[b,c,j] (the forward pass stores the table for the kept
+ * centres only).  grad_feat is double [B,C,N], overwritten.
+ * ------------------------------------------------------------------------- */
+int oracle_flexpool_sub_bwd(const float *grad_out, const int32_t *argmax, const int32_t *sel,
+                            double *grad_feat, int B, int N, int Ns, int C)
+{
+    if (!grad_out || !argmax || !sel || !grad_feat) return 1;
+    if (B <= 0 || N <= 0 || Ns <= 0 || C <= 0 || Ns > N) return 2;
+    double *gpooled = (double *)calloc((size_t)B * C * N, sizeof(double));
+    int32_t *winner = (int32_t *)malloc(sizeof(int32_t) * (size_t)B * C * N);
+    if (!gpooled || !winner) { free(gpooled); free(winner); return 6; }
+    for (int64_t i = 0; i < (int64_t)B * C * N; ++i) winner[i] = -1;
+    int rc = 0;
+    for (int b = 0; b < B && rc == 0; ++b)
+        for (int j = 0; j < Ns; ++j) {
+            const int l = sel[(int64_t)b * Ns + j];
+            if (l < 0 || l >= N) { rc = 2; break; }
+            for (int c = 0; c < C; ++c) {
+                gpooled[IDX3(b, c, l, C, N)] += (double)grad_out[IDX3(b, c, j, C, Ns)];
+                winner[IDX3(b, c, l, C, N)] = argmax[IDX3(b, c, j, C, Ns)];
+            }
+        }
+    memset(grad_feat, 0, sizeof(double) * (size_t)B * C * N);
+    for (int b = 0; b < B && rc == 0; ++b)
+        for (int c = 0; c < C && rc == 0; ++c)
+            for (int l = 0; l < N; ++l) {
+                const int m = winner[IDX3(b, c, l, C, N)];
+                if (m == -1) continue;                       /* not kept: no gradient arrives */
+                if (m < 0 || m >= N) { rc = 2; break; }
+                grad_feat[IDX3(b, c, m, C, N)] += gpooled[IDX3(b, c, l, C, N)];
+            }
+    free(gpooled); free(winner);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------
  * Flex-conv backward with respect to the point locations (Sec. 3.1: the weight
  * function is differentiable in all its arguments, so gradients pass through the
  * locations as well; no formula is printed).  Differentiating

@@ -31,6 +31,9 @@ _SIGS = {
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
     "flexpool_bwd": (_i, [_vp] * 5 + [_i] * 5 + [_vp]),
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
+    "flexpool_sub_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
+    "flexpool_sub_bwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
+    "flex_inedges_build_sub": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "flexupsample_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexupsample_bwd": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "flex_validate_selection": (_i, [_vp, _i, _i, _i, _vp, _vp, _sz, _vp]),
@@ -249,6 +252,63 @@ def flexpool_bwd(grad_out, argmax, layout=BCN, in_edges=None, K=None):
     gf = torch.empty_like(grad_out)
     _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), _ptr(off), _ptr(src), B, N, k, C, layout,
                               _stream()), "flexpool_bwd")
+    return gf
+
+
+def flexpool_sub_fwd(feat, nbr, sel, layout=BCN):
+    """Flex-max-pooling with subsampling (Sec. 4.1 / 5): the pooled rows of the kept centres sel [B,Ns]
+    only.  Returns (out, argmax int32), shaped [B,C,Ns] / [B,Ns,C]; argmax indexes the N input points."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(nbr, torch.int32, "nbr"); _dev(sel, torch.int32, "sel")
+    B, N, K, C = _dims(feat, nbr, layout)
+    if sel.dim() != 2 or sel.shape[0] != B:
+        raise ValueError("sel must be [B,Ns]")
+    Ns = sel.shape[1]
+    shape = (B, C, Ns) if layout == BCN else (B, Ns, C)
+    out = torch.empty(shape, dtype=torch.float32, device=feat.device)
+    arg = torch.empty(shape, dtype=torch.int32, device=feat.device)
+    _check(lib().flexpool_sub_fwd(_ptr(feat), _ptr(nbr), _ptr(sel), _ptr(out), _ptr(arg), B, N, Ns, K, C, layout,
+                                  _stream()), "flexpool_sub_fwd")
+    return out, arg
+
+
+def flex_inedges_build_sub(nbr, sel, workspace=None):
+    """Transposed neighbour lists over the kept centres sel [B,Ns] of nbr [B,K,N]: (in_off [B*N+1],
+    in_src [B*K*Ns]) for flexpool_sub_bwd.  Static per layer: build once."""
+    _dev(nbr, torch.int32, "nbr"); _dev(sel, torch.int32, "sel")
+    B, K, N = nbr.shape
+    if sel.dim() != 2 or sel.shape[0] != B:
+        raise ValueError("sel must be [B,Ns]")
+    Ns = sel.shape[1]
+    off = torch.empty(B * N + 1, dtype=torch.int32, device=nbr.device)
+    src = torch.empty(B * K * Ns, dtype=torch.int32, device=nbr.device)
+    need = workspace_bytes(OP_INEDGES, B, N, K, 1, 1, BCN)
+    ws = workspace if workspace is not None else _workspace(nbr.device, need)
+    _check(lib().flex_inedges_build_sub(_ptr(nbr), _ptr(sel), B, N, Ns, K, _ptr(off), _ptr(src), _ptr(ws),
+                                        ws.numel(), _stream()), "flex_inedges_build_sub")
+    return off, src
+
+
+def flexpool_sub_bwd(grad_out, argmax, N, layout=BCN, in_edges=None):
+    """Backward of flexpool_sub_fwd.  Returns grad_feat [B,C,N] / [B,N,C].  in_edges = (in_off, in_src) from
+    flex_inedges_build_sub(nbr, sel) selects the atomic-free gather form."""
+    layout = _layout(layout)
+    _dev(grad_out, torch.float32, "grad_out"); _dev(argmax, torch.int32, "argmax")
+    if grad_out.dim() != 3 or grad_out.shape != argmax.shape:
+        raise ValueError("grad_out and argmax must be 3-D and equal in shape")
+    B = grad_out.shape[0]
+    C, Ns = (grad_out.shape[1], grad_out.shape[2]) if layout == BCN else (grad_out.shape[2], grad_out.shape[1])
+    off = src = None
+    k = 1
+    if in_edges is not None:
+        off, src = in_edges
+        _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src")
+        if off.numel() != B * N + 1 or src.numel() % (B * Ns) != 0:
+            raise ValueError("in_edges do not match the tensors")
+        k = src.numel() // (B * Ns)
+    gf = torch.empty((B, C, N) if layout == BCN else (B, N, C), dtype=torch.float32, device=grad_out.device)
+    _check(lib().flexpool_sub_bwd(_ptr(grad_out), _ptr(argmax), _ptr(off), _ptr(src), _ptr(gf),
+                                  B, N, Ns, k, C, layout, _stream()), "flexpool_sub_bwd")
     return gf
 
 

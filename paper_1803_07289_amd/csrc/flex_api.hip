@@ -411,6 +411,45 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
     return FLEX_OK;
 }
 
+int flexpool_sub_fwd(const float *feat, const int32_t *nbr, const int32_t *sel, float *out,
+                     int32_t *argmax, int B, int N, int Ns, int K, int C, int layout, void *stream)
+{
+    if (!feat || !nbr || !sel || !out || !argmax) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, C, 1) || Ns <= 0 || Ns > N) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_pool_sub_fwd(feat, nbr, sel, out, argmax, B, N, Ns, K, C, layout == FLEX_LAYOUT_BNC,
+                                 (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexpool_sub_bwd(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
+                     const int32_t *in_src, float *grad_feat, int B, int N, int Ns, int K, int C,
+                     int layout, void *stream)
+{
+    if (!grad_out || !argmax || !grad_feat) return FLEX_ERR_NULL;
+    if ((in_off == nullptr) != (in_src == nullptr)) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, in_off ? K : 1, C, 1) || Ns <= 0 || Ns > N) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    const int bnc = layout == FLEX_LAYOUT_BNC;
+    if (in_off)
+        FLEX_HIP(launch_pool_sub_bwd_gather(grad_out, argmax, in_off, in_src, grad_feat, B, N, Ns, C, bnc, s));
+    else
+        FLEX_HIP(launch_pool_sub_bwd(grad_out, argmax, grad_feat, B, N, Ns, C, bnc, s));
+    return FLEX_OK;
+}
+
+int flex_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
+                           int32_t *in_off, int32_t *in_src, void *workspace, size_t workspace_bytes,
+                           void *stream)
+{
+    if (!nbr || !sel || !in_off || !in_src) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, 1, 1) || Ns <= 0 || Ns > N) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, inedges_ws_bytes((int64_t)B * N))) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_inedges_build_sub(nbr, sel, B, N, Ns, K, in_off, in_src, workspace, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
 int flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *theta, const float *grad_out,
                      const int32_t *in_off, const int32_t *in_src, float *grad_pos, int B, int N, int K,
                      int Din, int Dout, int layout, void *workspace, size_t workspace_bytes, void *stream)

@@ -100,6 +100,8 @@ hipError_t launch_generic_bwd(const float *feat, const float *pos, const int32_t
 // In-edge lists.
 hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t *in_off,
                                 int32_t *in_src, void *ws, hipStream_t s);
+hipError_t launch_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
+                                    int32_t *in_off, int32_t *in_src, void *ws, hipStream_t s);
 size_t inedges_ws_bytes(int64_t BN);
 
 // Pooling.
@@ -113,6 +115,13 @@ hipError_t launch_pool_bwd_gather(const float *grad_out, const int32_t *argmax, 
 
 // Flex-upsampling: inverse selection map (inv[b*Nf + sel[b,j]] = j, -1 elsewhere), pooling through it,
 // routing back over the larger layer's in-edge lists, and a check of the selection (out of range / repeated).
+hipError_t launch_pool_sub_fwd(const float *feat, const int32_t *nbr, const int32_t *sel, float *out,
+                               int32_t *argmax, int B, int N, int Ns, int K, int C, int bnc, hipStream_t s);
+hipError_t launch_pool_sub_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B,
+                               int N, int L, int C, int bnc, hipStream_t s);
+hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
+                                      const int32_t *in_src, float *grad_feat, int B, int N, int L, int C,
+                                      int bnc, hipStream_t s);
 hipError_t launch_upsample_inv(const int32_t *sel, int32_t *inv, int B, int Ns, int Nf, hipStream_t s);
 hipError_t launch_upsample_fwd(const float *feat_small, const int32_t *inv, const int32_t *nbr, float *out,
                                int32_t *argmax, int B, int Ns, int Nf, int K, int C, int bnc, hipStream_t s);

@@ -22,6 +22,47 @@ __global__ __launch_bounds__(256) void inedge_count_kernel(const int32_t *__rest
     }
 }
 
+// Lists over a subset of the centres (pooling with subsampling): edge i = (cloud b, slot k, kept
+// centre j) names point nbr[b, k, sel[b,j]]; the lists hold j.  Entries of sel outside [0,N) are clamped.
+__device__ __forceinline__ int64_t sub_edge_target(const int32_t *__restrict__ nbr, const int32_t *__restrict__ sel,
+                                                   int64_t i, int N, int Ns, int K, int &j)
+{
+    const int64_t KNs = (int64_t)K * Ns;
+    const int64_t b = i / KNs, r = i - b * KNs;
+    const int k = (int)(r / Ns);
+    j = (int)(r - (int64_t)k * Ns);
+    const int l = min(max(sel[b * Ns + j], 0), N - 1);
+    return b * N + nbr[(b * K + k) * N + l];
+}
+
+__global__ __launch_bounds__(256) void inedge_sub_count_kernel(const int32_t *__restrict__ nbr,
+                                                               const int32_t *__restrict__ sel,
+                                                               int32_t *__restrict__ cnt, int64_t E, int N,
+                                                               int Ns, int K)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < E;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int j;
+        atomicAdd(&cnt[sub_edge_target(nbr, sel, i, N, Ns, K, j)], 1);
+    }
+}
+
+__global__ __launch_bounds__(256) void inedge_sub_fill_kernel(const int32_t *__restrict__ nbr,
+                                                              const int32_t *__restrict__ sel,
+                                                              const int32_t *__restrict__ off,
+                                                              int32_t *__restrict__ cnt,
+                                                              int32_t *__restrict__ src, int64_t E, int N,
+                                                              int Ns, int K)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < E;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int j;
+        const int64_t g = sub_edge_target(nbr, sel, i, N, Ns, K, j);
+        const int slot = atomicSub(&cnt[g], 1) - 1;
+        src[off[g] + slot] = j;
+    }
+}
+
 __device__ __forceinline__ int block_exclusive_scan(int v, int *s_wave, int &block_total)
 {
     // inclusive scan inside the wave, then across the 4 waves
@@ -178,7 +219,15 @@ size_t inedges_ws_bytes(int64_t BN)
 hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t *in_off,
                                 int32_t *in_src, void *ws, hipStream_t s)
 {
-    const int64_t BN = (int64_t)B * N, KN = (int64_t)K * N, E = BN * K;
+    return launch_inedges_build_sub(nbr, nullptr, B, N, N, K, in_off, in_src, ws, s);
+}
+
+// sel == nullptr: every point is a centre (Ns = N); else the centres are the kept points sel[b, 0..Ns)
+// and the lists hold their row numbers j
+hipError_t launch_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
+                                    int32_t *in_off, int32_t *in_src, void *ws, hipStream_t s)
+{
+    const int64_t BN = (int64_t)B * N, KN = (int64_t)K * N, E = (int64_t)B * K * (sel ? Ns : N);
     const int64_t nblk64 = cdiv64(BN, SCAN_CHUNK);
     const int nblk = (int)nblk64;
     int32_t *cnt = (int32_t *)ws;
@@ -187,11 +236,18 @@ hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t
     if (e != hipSuccess) return e;
     int64_t eb = (E + 255) / 256;
     if (eb > (1 << 18)) eb = 1 << 18;
-    hipLaunchKernelGGL(inedge_count_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, cnt, E, N, KN);
+    if (sel)
+        hipLaunchKernelGGL(inedge_sub_count_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, sel, cnt, E, N, Ns, K);
+    else
+        hipLaunchKernelGGL(inedge_count_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, cnt, E, N, KN);
     hipLaunchKernelGGL(scan_block_sums_kernel, dim3(nblk), dim3(256), 0, s, cnt, bsum, BN);
     hipLaunchKernelGGL(scan_of_sums_kernel, dim3(1), dim3(256), 0, s, bsum, nblk);
     hipLaunchKernelGGL(scan_apply_kernel, dim3(nblk), dim3(256), 0, s, cnt, bsum, in_off, BN, nblk);
-    hipLaunchKernelGGL(inedge_fill_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, in_off, cnt, in_src, E, N, KN);
+    if (sel)
+        hipLaunchKernelGGL(inedge_sub_fill_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, sel, in_off, cnt, in_src,
+                           E, N, Ns, K);
+    else
+        hipLaunchKernelGGL(inedge_fill_kernel, dim3((unsigned)eb), dim3(256), 0, s, nbr, in_off, cnt, in_src, E, N, KN);
     int64_t sb = (BN + 255) / 256;
     if (sb > (1 << 18)) sb = 1 << 18;
     hipLaunchKernelGGL(inedge_sort_kernel, dim3((unsigned)sb), dim3(256), 0, s, in_off, in_src, BN);

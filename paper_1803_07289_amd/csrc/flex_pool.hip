@@ -26,11 +26,14 @@ static inline unsigned xcd_grid(int64_t total_tiles) { return (unsigned)(((total
 // Point-major, C % 4 == 0: one thread per (point, 4 channels); a block owns PT consecutive points.
 // The gather is latency-bound, so a thread first requests the ids of 8 neighbours, then their 8
 // rows (16 bytes each), and only then compares: 8 rows per lane are in flight instead of one.
+// SUB: pooling with subsampling, only the kept centres sel[b,j] are evaluated (BN = B*Ns output rows).
+template <bool SUB>
 __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restrict__ feat,
                                                             const int32_t *__restrict__ nbr,
+                                                            const int32_t *__restrict__ sel,
                                                             float *__restrict__ out,
                                                             int32_t *__restrict__ argmax, int64_t BN,
-                                                            int N, int K, int C4, int PT,
+                                                            int N, int Ns, int K, int C4, int PT,
                                                             int64_t total_tiles)
 {
     constexpr int U = 8;
@@ -40,7 +43,9 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
         const int c4 = i % C4;
         const int64_t gp = tile * PT + i / C4;
         if (gp >= BN) break;
-        const int b = (int)(gp / N), l = (int)(gp % N);
+        int b, l;
+        if constexpr (SUB) { b = (int)(gp / Ns); l = min(max(sel[gp], 0), N - 1); }
+        else { b = (int)(gp / N); l = (int)(gp % N); }
         const int32_t *nb = nbr + (int64_t)b * K * N + l;
         const v4f *rows = reinterpret_cast<const v4f *>(feat) + (int64_t)b * N * C4 + c4;
         float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
@@ -71,18 +76,21 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
 }
 
 // Any C, either layout: one thread per output element.
+// sel == nullptr: every point is a centre (L = N); else the centres are sel[b, 0..L).
 __global__ __launch_bounds__(256) void pool_fwd_generic_kernel(const float *__restrict__ feat,
                                                                const int32_t *__restrict__ nbr,
+                                                               const int32_t *__restrict__ sel,
                                                                float *__restrict__ out,
                                                                int32_t *__restrict__ argmax, int B,
-                                                               int N, int K, int C, int bnc)
+                                                               int N, int L, int K, int C, int bnc)
 {
-    const int64_t total = (int64_t)B * N * C;
+    const int64_t total = (int64_t)B * L * C;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
         int b, c, l;
-        if (bnc) { c = (int)(i % C); const int64_t gp = i / C; b = (int)(gp / N); l = (int)(gp % N); }
-        else     { l = (int)(i % N); const int64_t bc = i / N; b = (int)(bc / C); c = (int)(bc % C); }
+        if (bnc) { c = (int)(i % C); const int64_t gp = i / C; b = (int)(gp / L); l = (int)(gp % L); }
+        else     { l = (int)(i % L); const int64_t bc = i / L; b = (int)(bc / C); c = (int)(bc % C); }
+        if (sel) l = min(max(sel[(int64_t)b * L + l], 0), N - 1);
         const int32_t *nb = nbr + (int64_t)b * K * N + l;
         int bn = nb[0];
         float bv = bnc ? feat[((int64_t)b * N + bn) * C + c] : feat[((int64_t)b * C + c) * N + bn];
@@ -103,31 +111,53 @@ hipError_t launch_pool_fwd(const float *feat, const int32_t *nbr, float *out, in
         const int C4 = C / 4;
         const int PT = C4 >= 256 ? 1 : 256 / C4;
         const int64_t BN = (int64_t)B * N, tiles = (BN + PT - 1) / PT;
-        hipLaunchKernelGGL(pool_fwd_bnc4_kernel, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr,
-                           out, argmax, BN, N, K, C4, PT, tiles);
+        hipLaunchKernelGGL(pool_fwd_bnc4_kernel<false>, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr,
+                           (const int32_t *)nullptr, out, argmax, BN, N, N, K, C4, PT, tiles);
     } else {
         const int64_t total = (int64_t)B * N * C;
         int64_t blocks = (total + 255) / 256;
         if (blocks > (1 << 20)) blocks = 1 << 20;
         hipLaunchKernelGGL(pool_fwd_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, feat, nbr,
-                           out, argmax, B, N, K, C, bnc);
+                           (const int32_t *)nullptr, out, argmax, B, N, N, K, C, bnc);
     }
     return hipGetLastError();
 }
 
+// Pooling with subsampling: out / argmax hold the Ns kept centres sel[b,j] only.
+hipError_t launch_pool_sub_fwd(const float *feat, const int32_t *nbr, const int32_t *sel, float *out,
+                               int32_t *argmax, int B, int N, int Ns, int K, int C, int bnc, hipStream_t s)
+{
+    if (bnc && (C % 4 == 0)) {
+        const int C4 = C / 4;
+        const int PT = C4 >= 256 ? 1 : 256 / C4;
+        const int64_t BNs = (int64_t)B * Ns, tiles = (BNs + PT - 1) / PT;
+        hipLaunchKernelGGL(pool_fwd_bnc4_kernel<true>, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr, sel,
+                           out, argmax, BNs, N, Ns, K, C4, PT, tiles);
+    } else {
+        const int64_t total = (int64_t)B * Ns * C;
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > (1 << 20)) blocks = 1 << 20;
+        hipLaunchKernelGGL(pool_fwd_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, feat, nbr, sel,
+                           out, argmax, B, N, Ns, K, C, bnc);
+    }
+    return hipGetLastError();
+}
+
+// grad_out / argmax have L rows per cloud (L = N, or the kept centres of a subsampled pooling),
+// grad_feat has N.
 __global__ __launch_bounds__(256) void pool_bwd_kernel(const float *__restrict__ grad_out,
                                                        const int32_t *__restrict__ argmax,
-                                                       float *__restrict__ grad_feat, int B, int N,
+                                                       float *__restrict__ grad_feat, int B, int N, int L,
                                                        int C, int bnc)
 {
-    const int64_t total = (int64_t)B * N * C;
+    const int64_t total = (int64_t)B * L * C;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
         const int m = argmax[i];
         int64_t dst;
-        if (bnc) { const int c = (int)(i % C); const int64_t gp = i / C; const int64_t b = gp / N;
+        if (bnc) { const int c = (int)(i % C); const int64_t gp = i / C; const int64_t b = gp / L;
                    dst = (b * N + m) * C + c; }
-        else     { const int64_t bc = i / N; dst = bc * N + m; }
+        else     { const int64_t bc = i / L; dst = bc * N + m; }
         atomicAdd(&grad_feat[dst], grad_out[i]);
     }
 }
@@ -138,12 +168,14 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const float *__restrict__
 // Entries are taken four at a time: their ids first, then the eight rows (winner table and
 // gradient), so that a lane has 128 bytes in flight instead of 32 (eight at a time is slower:
 // the mean in-degree is K, so most of a second batch would be padding).
+template <int U>
 __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
-    float *__restrict__ grad_feat, int64_t BN, int N, int C4, int PT, int64_t total_tiles)
+    float *__restrict__ grad_feat, int64_t BN, int N, int L, int C4, int PT, int64_t total_tiles)
 {
-    constexpr int U = 4;
+    // L = rows of grad_out / argmax per cloud: N, or the kept centres of a subsampled pooling (the lists
+    // then hold row numbers among the kept centres).  U = entries per batch: about half the mean list length.
     const int64_t tile = xcd_tile(total_tiles);
     if (tile < 0) return;
     for (int i = threadIdx.x; i < PT * C4; i += 256) {
@@ -152,8 +184,8 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
         if (gp >= BN) break;
         const int64_t b = gp / N;
         const int m = (int)(gp - b * N);
-        const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + b * N * C4 + c4;
-        const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + b * N * C4 + c4;
+        const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + b * L * C4 + c4;
+        const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + b * L * C4 + c4;
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         const int e0 = in_off[gp], e1 = in_off[gp + 1];
         int prev = -1;
@@ -183,7 +215,7 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
 __global__ __launch_bounds__(256) void pool_bwd_gather_generic_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
-    float *__restrict__ grad_feat, int B, int N, int C, int bnc)
+    float *__restrict__ grad_feat, int B, int N, int L, int C, int bnc)
 {
     const int64_t total = (int64_t)B * N * C;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
@@ -199,7 +231,7 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_generic_kernel(
             const int64_t l = in_src[e];
             if ((int)l == prev) continue;
             prev = (int)l;
-            const int64_t at = bnc ? (b * N + l) * C + c : (b * C + c) * N + l;
+            const int64_t at = bnc ? (b * L + l) * C + c : (b * C + c) * L + l;
             if (argmax[at] == m) acc += grad_out[at];
         }
         grad_feat[i] = acc;
@@ -210,18 +242,30 @@ hipError_t launch_pool_bwd_gather(const float *grad_out, const int32_t *argmax, 
                                   const int32_t *in_src, float *grad_feat, int B, int N, int C, int bnc,
                                   hipStream_t s)
 {
+    return launch_pool_sub_bwd_gather(grad_out, argmax, in_off, in_src, grad_feat, B, N, N, C, bnc, s);
+}
+
+// L rows of grad_out / argmax per cloud, lists over them for each of the N points
+hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
+                                      const int32_t *in_src, float *grad_feat, int B, int N, int L, int C,
+                                      int bnc, hipStream_t s)
+{
     if (bnc && (C % 4 == 0)) {
         const int C4 = C / 4;
         const int PT = C4 >= 256 ? 1 : 256 / C4;
         const int64_t BN = (int64_t)B * N, tiles = (BN + PT - 1) / PT;
-        hipLaunchKernelGGL(pool_bwd_gather_bnc4_kernel, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
-                           argmax, in_off, in_src, grad_feat, BN, N, C4, PT, tiles);
+        if (2 * (int64_t)L <= N)     // lists a quarter as long (subsampling keeps a quarter of the centres)
+            hipLaunchKernelGGL(pool_bwd_gather_bnc4_kernel<2>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+                               argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tiles);
+        else
+            hipLaunchKernelGGL(pool_bwd_gather_bnc4_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+                               argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tiles);
     } else {
         const int64_t total = (int64_t)B * N * C;
         int64_t blocks = (total + 255) / 256;
         if (blocks > (1 << 20)) blocks = 1 << 20;
         hipLaunchKernelGGL(pool_bwd_gather_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                           grad_out, argmax, in_off, in_src, grad_feat, B, N, C, bnc);
+                           grad_out, argmax, in_off, in_src, grad_feat, B, N, L, C, bnc);
     }
     return hipGetLastError();
 }
@@ -229,13 +273,20 @@ hipError_t launch_pool_bwd_gather(const float *grad_out, const int32_t *argmax, 
 hipError_t launch_pool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B,
                            int N, int C, int bnc, hipStream_t s)
 {
+    return launch_pool_sub_bwd(grad_out, argmax, grad_feat, B, N, N, C, bnc, s);
+}
+
+// scatter form for L source rows per cloud (atomics)
+hipError_t launch_pool_sub_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B,
+                               int N, int L, int C, int bnc, hipStream_t s)
+{
     hipError_t e = launch_fill_zero(grad_feat, sizeof(float) * (size_t)B * N * C, s);
     if (e != hipSuccess) return e;
-    const int64_t total = (int64_t)B * N * C;
+    const int64_t total = (int64_t)B * L * C;
     int64_t blocks = (total + 255) / 256;
     if (blocks > (1 << 20)) blocks = 1 << 20;
     hipLaunchKernelGGL(pool_bwd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, grad_out, argmax,
-                       grad_feat, B, N, C, bnc);
+                       grad_feat, B, N, L, C, bnc);
     return hipGetLastError();
 }
 

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(L):
     assert {"flexconv_fwd", "flexconv_bwd", "flexpool_fwd", "flexpool_bwd", "flex_inedges_build",
             "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
             "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
-            "flexconv_bwd_pos"} <= set(names)
+            "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -80,6 +80,18 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
     # flexupsample_bwd(grad_out, argmax, sel, in_off, in_src, grad_small, B, Ns, Nf, K, C, layout, stream)
     assert L.flexupsample_bwd(one, one, one, none, one, one, 1, 4, 16, 2, 8, 0, None) == 1          # lists are required
     assert L.flexupsample_bwd(one, one, one, one, one, one, 1, 4, 16, 2, 0, 0, None) == 2
+    # flexpool_sub_fwd(feat, nbr, sel, out, argmax, B, N, Ns, K, C, layout, stream)
+    assert L.flexpool_sub_fwd(one, one, none, one, one, 1, 16, 4, 2, 8, 0, None) == 1
+    assert L.flexpool_sub_fwd(one, one, one, one, one, 1, 16, 17, 2, 8, 0, None) == 2               # Ns > N
+    assert L.flexpool_sub_fwd(one, one, one, one, one, 1, 16, 4, 2, 8, 5, None) == 2                # layout
+    # flexpool_sub_bwd(grad_out, argmax, in_off, in_src, grad_feat, B, N, Ns, K, C, layout, stream)
+    assert L.flexpool_sub_bwd(one, one, one, none, one, 1, 16, 4, 2, 8, 0, None) == 1               # in_off without in_src
+    assert L.flexpool_sub_bwd(one, one, none, none, none, 1, 16, 4, 2, 8, 0, None) == 1
+    assert L.flexpool_sub_bwd(one, one, none, none, one, 1, 16, 0, 2, 8, 0, None) == 2
+    # flex_inedges_build_sub(nbr, sel, B, N, Ns, K, in_off, in_src, ws, ws_bytes, stream)
+    assert L.flex_inedges_build_sub(one, none, 1, 16, 4, 2, one, one, one, big, None) == 1
+    assert L.flex_inedges_build_sub(one, one, 1, 16, 17, 2, one, one, one, big, None) == 2
+    assert L.flex_inedges_build_sub(one, one, 1, 16, 4, 2, one, one, one, 16, None) == 4
     # flex_validate_selection(sel, B, Ns, Nf, bad, ws, ws_bytes, stream)
     assert L.flex_validate_selection(one, 1, 4, 16, none, one, big, None) == 1
     assert L.flex_validate_selection(one, 1, 4, 16, one, one, 16, None) == 4

@@ -10,6 +10,7 @@ import oracle
 import test_oracle_conv as tc
 import test_oracle_pool as tp
 import test_oracle_upsample as tu
+import test_oracle_pool_sub as ts
 
 SRC = open(os.path.join(os.path.dirname(oracle.__file__), "oracle.c")).read()
 
@@ -26,6 +27,9 @@ POOL_PINS = [tp.test_pool_fwd_bruteforce_with_ties, tp.test_pool_fwd_invariants,
 
 UP_PINS = [tu.test_upsample_fwd_bruteforce_with_ties, tu.test_upsample_fwd_is_zero_fill_then_pool,
            tu.test_upsample_grid_is_zero_insertion_then_3x3_max, tu.test_upsample_bwd_bruteforce_mass_and_composition]
+
+SUB_PINS = [ts.test_pool_sub_fwd_bruteforce_with_ties, ts.test_pool_sub_fwd_grid_is_3x3_maxpool_stride2,
+            ts.test_pool_sub_bwd_bruteforce_mass_and_repeats, ts.test_pool_sub_bwd_is_directional_derivative]
 
 POS_PINS = [tc.test_bwd_pos_finite_differences, tc.test_bwd_pos_bruteforce_translation_and_self_edges]
 
@@ -57,6 +61,11 @@ MUTATIONS = [
      "s += (double)theta[IDX3(d, c, o, Din, Dout)] * (double)feat[IDX3(b, c, l, Din, N)] * (double)grad_out[IDX3(b, o, l, Dout, N)];", 0, POS_PINS),
     ("bwd_pos_gradient_of_neighbour", "s += (double)theta[IDX3(d, c, o, Din, Dout)] * f * (double)grad_out[IDX3(b, o, l, Dout, N)];",
      "s += (double)theta[IDX3(d, c, o, Din, Dout)] * f * (double)grad_out[IDX3(b, o, n, Dout, N)];", 0, POS_PINS),
+    ("pool_sub_reads_row_j", "out[IDX3(b, c, j, C, Ns)] = pooled[IDX3(b, c, l, C, N)];",
+     "out[IDX3(b, c, j, C, Ns)] = pooled[IDX3(b, c, j, C, N)];", 0, SUB_PINS),
+    ("pool_sub_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 2, SUB_PINS),
+    ("pool_sub_bwd_to_kept_centre", "grad_feat[IDX3(b, c, m, C, N)] += gpooled[IDX3(b, c, l, C, N)];",
+     "grad_feat[IDX3(b, c, l, C, N)] += gpooled[IDX3(b, c, l, C, N)];", 0, SUB_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
