@@ -205,12 +205,12 @@ def main():
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
-                 "pool_bwd": "pool_bwd_gather_bnc4_kernel (flexpool_bwd)",
+                 "pool_bwd": "pool_bwd_gather_row16_kernel (flexpool_bwd)",
                  "upsample_fwd": "upsample_fwd_bnc4_kernel (flexupsample_fwd)",
                  "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)",
                  "bwd_pos": "grad_pos_kernel x2 (flexconv_bwd_pos: centre term, neighbour term)",
-                 "pool_sub_fwd": "pool_fwd_bnc4_kernel<SUB> (flexpool_sub_fwd)",
-                 "pool_sub_bwd": "pool_bwd_gather_bnc4_kernel<SUB> (flexpool_sub_bwd)"}
+                 "pool_sub_fwd": "pool_fwd_bnc4_kernel<true> (flexpool_sub_fwd)",
+                 "pool_sub_bwd": "pool_bwd_gather_row16_kernel<2> (flexpool_sub_bwd)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
     measured_traffic = MEASURED_TRAFFIC

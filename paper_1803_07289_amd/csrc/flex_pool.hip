@@ -76,6 +76,13 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
 }
 
 // Any C, either layout: one thread per output element.
+// value of lane SRC of the caller's 16-lane row (all 16 lanes must be active)
+template <int SRC>
+__device__ __forceinline__ int row_bcast(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, 0x150 + SRC, 0xf, 0xf, true);   // row_newbcast:SRC
+}
+
 // sel == nullptr: every point is a centre (L = N); else the centres are sel[b, 0..L).
 __global__ __launch_bounds__(256) void pool_fwd_generic_kernel(const float *__restrict__ feat,
                                                                const int32_t *__restrict__ nbr,
@@ -212,6 +219,71 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
     }
 }
 
+// Gather form for C % 64 == 0 (a point's lanes fill whole 16-lane rows).  In the kernel above all 16
+// lanes of a point load the same list entries; every memory instruction costs the texture path the same
+// however few distinct bytes it fetches, and the backward pass issues many.  Here lane t of a row loads
+// list entry t, one instruction for up to 16 entries, and DPP row broadcasts on the vector ALU hand them
+// round (the same change does nothing for the forward pass, which is bound by HBM, not by instructions).
+// U = entries whose rows are requested together.
+template <int U>
+__global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
+    const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
+    float *__restrict__ grad_feat, int64_t BN, int N, int L, int C4, int PT, int64_t total_tiles)
+{
+    static_assert(U == 2 || U == 4, "batches tile the 16 entries of one load");
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    const int t16 = threadIdx.x & 15;
+    for (int i = threadIdx.x; i < PT * C4; i += 256) {
+        const int c4 = i % C4;
+        const int64_t gp = tile * PT + i / C4;
+        if (gp >= BN) break;
+        const int64_t b = gp / N;
+        const int m = (int)(gp - b * N);
+        const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + b * L * C4 + c4;
+        const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + b * L * C4 + c4;
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        const int bound = in_off[gp + (t16 & 1)];
+        const int e0 = row_bcast<0>(bound), e1 = row_bcast<1>(bound);
+        int prev = -1;
+        for (int e = e0; e < e1; e += 16) {
+            const int mine = in_src[min(e + t16, e1 - 1)];               // past the end: the last entry again
+            auto batch = [&](const int (&l)[U]) {
+                int4 a[U];
+                v4f g[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) { a[u] = a4[(int64_t)l[u] * C4]; g[u] = g4[(int64_t)l[u] * C4]; }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    // a centre that lists m twice (adjacent entries, also the repeats past the end) routes one gradient
+                    const bool fresh = l[u] != prev;
+                    prev = l[u];
+                    acc.x += (fresh && a[u].x == m) ? g[u].x : 0.f;
+                    acc.y += (fresh && a[u].y == m) ? g[u].y : 0.f;
+                    acc.z += (fresh && a[u].z == m) ? g[u].z : 0.f;
+                    acc.w += (fresh && a[u].w == m) ? g[u].w : 0.f;
+                }
+            };
+#define FLEX_POOL_BATCH(J)                                                                               \
+            if (e + (J) * U < e1) {                                                                          \
+                if constexpr (U == 4) {                                                                      \
+                    const int l[U] = {row_bcast<((J) * U) & 15>(mine), row_bcast<((J) * U + 1) & 15>(mine),   \
+                                      row_bcast<((J) * U + 2) & 15>(mine), row_bcast<((J) * U + 3) & 15>(mine)}; \
+                    batch(l);                                                                                \
+                } else {                                                                                     \
+                    const int l[U] = {row_bcast<((J) * U) & 15>(mine), row_bcast<((J) * U + 1) & 15>(mine)};   \
+                    batch(l);                                                                                \
+                }                                                                                            \
+            }
+            FLEX_POOL_BATCH(0) FLEX_POOL_BATCH(1) FLEX_POOL_BATCH(2) FLEX_POOL_BATCH(3)
+            if constexpr (U == 2) { FLEX_POOL_BATCH(4) FLEX_POOL_BATCH(5) FLEX_POOL_BATCH(6) FLEX_POOL_BATCH(7) }
+#undef FLEX_POOL_BATCH
+        }
+        reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4] = acc;
+    }
+}
+
 __global__ __launch_bounds__(256) void pool_bwd_gather_generic_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
@@ -254,7 +326,13 @@ hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argm
         const int C4 = C / 4;
         const int PT = C4 >= 256 ? 1 : 256 / C4;
         const int64_t BN = (int64_t)B * N, tiles = (BN + PT - 1) / PT;
-        if (2 * (int64_t)L <= N)     // lists a quarter as long (subsampling keeps a quarter of the centres)
+        if (C4 % 16 == 0 && 2 * (int64_t)L <= N)
+            hipLaunchKernelGGL(pool_bwd_gather_row16_kernel<2>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+                               argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tiles);
+        else if (C4 % 16 == 0)
+            hipLaunchKernelGGL(pool_bwd_gather_row16_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+                               argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tiles);
+        else if (2 * (int64_t)L <= N)     // lists a quarter as long (subsampling keeps a quarter of the centres)
             hipLaunchKernelGGL(pool_bwd_gather_bnc4_kernel<2>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
                                argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tiles);
         else
