@@ -148,6 +148,32 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
                  int B, int N, int K, int C, int layout, void *stream);
 
 /*
+ * 1x1 convolution composed into a flex-convolution (Sec. 5: a ResNet block chains a 1x1
+ * convolution and flex-convolutions; the paper names no bias in the 1x1 step and no activation
+ * between it and the next step, and this entry point assumes neither).  With mid = W feat,
+ * W [Dmid,Din0], the next layer flexconv(theta [3,Dmid,Dout], bias [Dmid,Dout]) over mid equals a
+ * flex-convolution over feat itself with
+ *   theta_c[d,c0,o] = sum_c W[c,c0] theta[d,c,o],   bias_c[c0,o] = sum_c W[c,c0] bias[c,o],
+ * because the weight function is linear in its parameters.  The 1x1 output (a [B,Dmid,N] tensor
+ * written and gathered again) is never formed: call flexconv_fwd / flexconv_bwd with
+ * (theta_c [3,Din0,Dout], bias_c [Din0,Dout]).  All arrays device fp32, overwritten.
+ */
+int flexconv_compose_1x1(const float *W, const float *theta, const float *bias,
+                         float *theta_c, float *bias_c, int Din0, int Dmid, int Dout, void *stream);
+
+/*
+ * Backward through the composition.  flexconv_bwd with the composed parameters returns grad_feat
+ * of the block's input directly, and grad_theta_c / grad_bias_c; this call turns those into
+ *   grad_W[c,c0]      = sum_{d,o} theta[d,c,o] grad_theta_c[d,c0,o] + sum_o bias[c,o] grad_bias_c[c0,o]
+ *   grad_theta[d,c,o] = sum_c0 W[c,c0] grad_theta_c[d,c0,o],  grad_bias[c,o] = sum_c0 W[c,c0] grad_bias_c[c0,o]
+ * (grad_W [Dmid,Din0], grad_theta [3,Dmid,Dout], grad_bias [Dmid,Dout], overwritten).
+ */
+int flexconv_compose_1x1_bwd(const float *W, const float *theta, const float *bias,
+                             const float *grad_theta_c, const float *grad_bias_c,
+                             float *grad_W, float *grad_theta, float *grad_bias,
+                             int Din0, int Dmid, int Dout, void *stream);
+
+/*
  * Flex-max-pooling with subsampling, forward (Sec. 4.1: pooling runs before the subsampling step;
  * Sec. 5: the last layer of an encoder stage, which keeps a quarter of the points).  The result
  * is that of flexpool_fwd restricted to the kept centres, and only those are evaluated:

@@ -208,3 +208,37 @@ def flexconv_bwd_pos(feat, nbr, theta, grad_out):
     _check(_load().oracle_flexconv_bwd_pos(_p(feat), _p(nbr), _p(theta), _p(grad_out), _p(gp), B, N, K, Din, Dout),
            "oracle_flexconv_bwd_pos")
     return gp
+
+
+def block_fwd(feat, pos, nbr, W, theta, bias):
+    """1x1 convolution (W [Dmid,Din0], no bias) then flex-convolution (theta [3,Dmid,Dout], bias [Dmid,Dout]).
+    Returns float64 out [B,Dout,N]."""
+    feat, pos, W, theta, bias, nbr = _f32(feat), _f32(pos), _f32(W), _f32(theta), _f32(bias), _i32(nbr)
+    B, Din0, N = feat.shape
+    K = nbr.shape[1]
+    Dmid, Dout = theta.shape[1], theta.shape[2]
+    assert W.shape == (Dmid, Din0) and bias.shape == (Dmid, Dout) and pos.shape == (B, 3, N)
+    assert count_bad_neighbors(nbr, N) == 0
+    out = np.zeros((B, Dout, N), np.float64)
+    _check(_load().oracle_block_fwd(_p(feat), _p(pos), _p(nbr), _p(W), _p(theta), _p(bias), _p(out),
+                                    B, N, K, Din0, Dmid, Dout), "oracle_block_fwd")
+    return out
+
+
+def block_bwd(feat, pos, nbr, W, theta, bias, grad_out):
+    """Backward of block_fwd.  Returns (grad_feat [B,Din0,N], grad_W [Dmid,Din0], grad_theta [3,Dmid,Dout],
+    grad_bias [Dmid,Dout]) in float64."""
+    feat, pos, W, theta, bias, nbr = _f32(feat), _f32(pos), _f32(W), _f32(theta), _f32(bias), _i32(nbr)
+    grad_out = _f32(grad_out)
+    B, Din0, N = feat.shape
+    K = nbr.shape[1]
+    Dmid, Dout = theta.shape[1], theta.shape[2]
+    assert W.shape == (Dmid, Din0) and bias.shape == (Dmid, Dout) and grad_out.shape == (B, Dout, N)
+    assert count_bad_neighbors(nbr, N) == 0
+    gf = np.zeros((B, Din0, N), np.float64)
+    gW = np.zeros((Dmid, Din0), np.float64)
+    gt = np.zeros((3, Dmid, Dout), np.float64)
+    gb = np.zeros((Dmid, Dout), np.float64)
+    _check(_load().oracle_block_bwd(_p(feat), _p(pos), _p(nbr), _p(W), _p(theta), _p(bias), _p(grad_out),
+                                    _p(gf), _p(gW), _p(gt), _p(gb), B, N, K, Din0, Dmid, Dout), "oracle_block_bwd")
+    return gf, gW, gt, gb

@@ -505,3 +505,125 @@ int oracle_flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *
             }
     return 0;
 }
+
+/* ---------------------------------------------------------------------------
+ * First two operations of the encoder's ResNet block (Sec. 5: 1x1-convolution, then
+ * flex-convolution).  The paper names no bias for the 1x1 step and no activation between
+ * the two, and none is applied here:
+ *   mid[b,c,n] = sum_c0 W[c,c0] * feat[b,c0,n]                          (1x1 convolution)
+ *   out[b,o,l] = sum_k sum_c ( <theta[:,c,o], pos[b,:,n]-pos[b,:,l]> + bias[c,o] ) * mid[b,c,n],
+ *                n = nbr[b,k,l]                                          (Eq.(4) with Eq.(6))
+ * taken in exactly these two steps, mid kept in double.  W is [Dmid,Din0]; out double [B,Dout,N].
+ * ------------------------------------------------------------------------- */
+int oracle_block_fwd(const float *feat, const float *pos, const int32_t *nbr, const float *W,
+                     const float *theta, const float *bias, double *out,
+                     int B, int N, int K, int Din0, int Dmid, int Dout)
+{
+    if (!feat || !pos || !nbr || !W || !theta || !bias || !out) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || Din0 <= 0 || Dmid <= 0 || Dout <= 0) return 2;
+    double *mid = (double *)malloc(sizeof(double) * (size_t)B * Dmid * N);
+    if (!mid) return 6;
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < Dmid; ++c)
+            for (int n = 0; n < N; ++n) {
+                double s = 0.0;
+                for (int c0 = 0; c0 < Din0; ++c0)
+                    s += (double)W[(int64_t)c * Din0 + c0] * (double)feat[IDX3(b, c0, n, Din0, N)];
+                mid[IDX3(b, c, n, Dmid, N)] = s;
+            }
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l)
+            for (int o = 0; o < Dout; ++o) {
+                double acc = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    const int n = nbr[IDX3(b, k, l, K, N)];
+                    const double dx = (double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)];
+                    const double dy = (double)pos[IDX3(b, 1, n, 3, N)] - (double)pos[IDX3(b, 1, l, 3, N)];
+                    const double dz = (double)pos[IDX3(b, 2, n, 3, N)] - (double)pos[IDX3(b, 2, l, 3, N)];
+                    for (int c = 0; c < Dmid; ++c) {
+                        const double w = (double)theta[IDX3(0, c, o, Dmid, Dout)] * dx +
+                                         (double)theta[IDX3(1, c, o, Dmid, Dout)] * dy +
+                                         (double)theta[IDX3(2, c, o, Dmid, Dout)] * dz +
+                                         (double)bias[(int64_t)c * Dout + o];
+                        acc += w * mid[IDX3(b, c, n, Dmid, N)];
+                    }
+                }
+                out[IDX3(b, o, l, Dout, N)] = acc;
+            }
+    free(mid);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Backward of that block, by the chain rule through the two steps (the paper prints no
+ * formulas): with g = grad_out and the edge weight w(c,o) as above,
+ *   grad_mid[b,c,n]    = sum over edges (l,k) with nbr[b,k,l] = n of sum_o w(c,o) * g[b,o,l]
+ *   grad_theta[d,c,o]  = sum over edges of dp_d * mid[b,c,n] * g[b,o,l]
+ *   grad_bias[c,o]     = sum over edges of mid[b,c,n] * g[b,o,l]
+ *   grad_W[c,c0]       = sum_{b,n} grad_mid[b,c,n] * feat[b,c0,n]
+ *   grad_feat[b,c0,n]  = sum_c W[c,c0] * grad_mid[b,c,n]
+ * All outputs double, overwritten: grad_feat [B,Din0,N], grad_W [Dmid,Din0],
+ * grad_theta [3,Dmid,Dout], grad_bias [Dmid,Dout].
+ * ------------------------------------------------------------------------- */
+int oracle_block_bwd(const float *feat, const float *pos, const int32_t *nbr, const float *W,
+                     const float *theta, const float *bias, const float *grad_out,
+                     double *grad_feat, double *grad_W, double *grad_theta, double *grad_bias,
+                     int B, int N, int K, int Din0, int Dmid, int Dout)
+{
+    if (!feat || !pos || !nbr || !W || !theta || !bias || !grad_out) return 1;
+    if (!grad_feat || !grad_W || !grad_theta || !grad_bias) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || Din0 <= 0 || Dmid <= 0 || Dout <= 0) return 2;
+    double *mid = (double *)malloc(sizeof(double) * (size_t)B * Dmid * N);
+    double *gmid = (double *)calloc((size_t)B * Dmid * N, sizeof(double));
+    if (!mid || !gmid) { free(mid); free(gmid); return 6; }
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < Dmid; ++c)
+            for (int n = 0; n < N; ++n) {
+                double s = 0.0;
+                for (int c0 = 0; c0 < Din0; ++c0)
+                    s += (double)W[(int64_t)c * Din0 + c0] * (double)feat[IDX3(b, c0, n, Din0, N)];
+                mid[IDX3(b, c, n, Dmid, N)] = s;
+            }
+    memset(grad_theta, 0, sizeof(double) * (size_t)3 * Dmid * Dout);
+    memset(grad_bias, 0, sizeof(double) * (size_t)Dmid * Dout);
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l)
+            for (int k = 0; k < K; ++k) {
+                const int n = nbr[IDX3(b, k, l, K, N)];
+                const double dp[3] = {(double)pos[IDX3(b, 0, n, 3, N)] - (double)pos[IDX3(b, 0, l, 3, N)],
+                                      (double)pos[IDX3(b, 1, n, 3, N)] - (double)pos[IDX3(b, 1, l, 3, N)],
+                                      (double)pos[IDX3(b, 2, n, 3, N)] - (double)pos[IDX3(b, 2, l, 3, N)]};
+                for (int c = 0; c < Dmid; ++c) {
+                    const double m = mid[IDX3(b, c, n, Dmid, N)];
+                    double s = 0.0;
+                    for (int o = 0; o < Dout; ++o) {
+                        const double g = (double)grad_out[IDX3(b, o, l, Dout, N)];
+                        const double w = (double)theta[IDX3(0, c, o, Dmid, Dout)] * dp[0] +
+                                         (double)theta[IDX3(1, c, o, Dmid, Dout)] * dp[1] +
+                                         (double)theta[IDX3(2, c, o, Dmid, Dout)] * dp[2] +
+                                         (double)bias[(int64_t)c * Dout + o];
+                        s += w * g;
+                        for (int d = 0; d < 3; ++d) grad_theta[IDX3(d, c, o, Dmid, Dout)] += dp[d] * m * g;
+                        grad_bias[(int64_t)c * Dout + o] += m * g;
+                    }
+                    gmid[IDX3(b, c, n, Dmid, N)] += s;
+                }
+            }
+    for (int c = 0; c < Dmid; ++c)
+        for (int c0 = 0; c0 < Din0; ++c0) {
+            double s = 0.0;
+            for (int b = 0; b < B; ++b)
+                for (int n = 0; n < N; ++n) s += gmid[IDX3(b, c, n, Dmid, N)] * (double)feat[IDX3(b, c0, n, Din0, N)];
+            grad_W[(int64_t)c * Din0 + c0] = s;
+        }
+    for (int b = 0; b < B; ++b)
+        for (int c0 = 0; c0 < Din0; ++c0)
+            for (int n = 0; n < N; ++n) {
+                double s = 0.0;
+                for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * gmid[IDX3(b, c, n, Dmid, N)];
+                grad_feat[IDX3(b, c0, n, Din0, N)] = s;
+            }
+    free(mid); free(gmid);
+    return 0;
+}

@@ -31,6 +31,8 @@ _SIGS = {
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
     "flexpool_bwd": (_i, [_vp] * 5 + [_i] * 5 + [_vp]),
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
+    "flexconv_compose_1x1": (_i, [_vp] * 5 + [_i] * 3 + [_vp]),
+    "flexconv_compose_1x1_bwd": (_i, [_vp] * 8 + [_i] * 3 + [_vp]),
     "flexpool_sub_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
     "flexpool_sub_bwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
     "flex_inedges_build_sub": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
@@ -253,6 +255,40 @@ def flexpool_bwd(grad_out, argmax, layout=BCN, in_edges=None, K=None):
     _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), _ptr(off), _ptr(src), B, N, k, C, layout,
                               _stream()), "flexpool_bwd")
     return gf
+
+
+def flexconv_compose_1x1(W, theta, bias):
+    """Parameters of the flex-convolution that equals `1x1 convolution W [Dmid,Din0] (no bias), then
+    flexconv(theta [3,Dmid,Dout], bias [Dmid,Dout])` (Sec. 5 block).  Returns (theta_c [3,Din0,Dout], bias_c [Din0,Dout])."""
+    _dev(W, torch.float32, "W"); _dev(theta, torch.float32, "theta"); _dev(bias, torch.float32, "bias")
+    Dmid, Din0 = W.shape
+    if theta.dim() != 3 or theta.shape[0] != 3 or theta.shape[1] != Dmid or tuple(bias.shape) != (Dmid, theta.shape[2]):
+        raise ValueError("theta must be [3,Dmid,Dout] and bias [Dmid,Dout] for W [Dmid,Din0]")
+    Dout = theta.shape[2]
+    W, theta, bias = W.contiguous(), theta.contiguous(), bias.contiguous()
+    tc = torch.empty((3, Din0, Dout), dtype=torch.float32, device=W.device)
+    bc = torch.empty((Din0, Dout), dtype=torch.float32, device=W.device)
+    _check(lib().flexconv_compose_1x1(_ptr(W), _ptr(theta), _ptr(bias), _ptr(tc), _ptr(bc), Din0, Dmid, Dout, _stream()),
+           "flexconv_compose_1x1")
+    return tc, bc
+
+
+def flexconv_compose_1x1_bwd(W, theta, bias, grad_theta_c, grad_bias_c):
+    """Gradients of (W, theta, bias) from those of the composed parameters.  Returns (grad_W, grad_theta, grad_bias)."""
+    for t, n in ((W, "W"), (theta, "theta"), (bias, "bias"), (grad_theta_c, "grad_theta_c"), (grad_bias_c, "grad_bias_c")):
+        _dev(t, torch.float32, n)
+    Dmid, Din0 = W.shape
+    Dout = theta.shape[2]
+    if tuple(theta.shape) != (3, Dmid, Dout) or tuple(bias.shape) != (Dmid, Dout) or \
+            tuple(grad_theta_c.shape) != (3, Din0, Dout) or tuple(grad_bias_c.shape) != (Din0, Dout):
+        raise ValueError("shapes do not match W [Dmid,Din0]")
+    W, theta, bias = W.contiguous(), theta.contiguous(), bias.contiguous()
+    grad_theta_c, grad_bias_c = grad_theta_c.contiguous(), grad_bias_c.contiguous()
+    gW, gt, gb = torch.empty_like(W), torch.empty_like(theta), torch.empty_like(bias)
+    _check(lib().flexconv_compose_1x1_bwd(_ptr(W), _ptr(theta), _ptr(bias), _ptr(grad_theta_c), _ptr(grad_bias_c),
+                                          _ptr(gW), _ptr(gt), _ptr(gb), Din0, Dmid, Dout, _stream()),
+           "flexconv_compose_1x1_bwd")
+    return gW, gt, gb
 
 
 def flexpool_sub_fwd(feat, nbr, sel, layout=BCN):

@@ -411,6 +411,31 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
     return FLEX_OK;
 }
 
+int flexconv_compose_1x1(const float *W, const float *theta, const float *bias, float *theta_c, float *bias_c,
+                         int Din0, int Dmid, int Dout, void *stream)
+{
+    if (!W || !theta || !bias || !theta_c || !bias_c) return FLEX_ERR_NULL;
+    if (Din0 <= 0 || Dmid <= 0 || Dout <= 0 || Din0 > 16384 || Dmid > 16384 ||
+        Dout > 16384)
+        return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_compose_1x1(W, theta, bias, theta_c, bias_c, Din0, Dmid, Dout, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexconv_compose_1x1_bwd(const float *W, const float *theta, const float *bias, const float *grad_theta_c,
+                             const float *grad_bias_c, float *grad_W, float *grad_theta, float *grad_bias,
+                             int Din0, int Dmid, int Dout, void *stream)
+{
+    if (!W || !theta || !bias || !grad_theta_c || !grad_bias_c || !grad_W || !grad_theta || !grad_bias)
+        return FLEX_ERR_NULL;
+    if (Din0 <= 0 || Dmid <= 0 || Dout <= 0 || Din0 > 16384 || Dmid > 16384 ||
+        Dout > 16384)
+        return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_compose_1x1_bwd(W, theta, bias, grad_theta_c, grad_bias_c, grad_W, grad_theta, grad_bias, Din0,
+                                    Dmid, Dout, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
 int flexpool_sub_fwd(const float *feat, const int32_t *nbr, const int32_t *sel, float *out,
                      int32_t *argmax, int B, int N, int Ns, int K, int C, int layout, void *stream)
 {

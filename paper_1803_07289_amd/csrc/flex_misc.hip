@@ -504,4 +504,78 @@ hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const f
     return hipGetLastError();
 }
 
+// ---- 1x1 convolution composed into the flex-convolution parameters (Sec. 5 block) ----------
+// P = [theta; bias] as four [D x Dout] slabs j = 0..3.  Parameter-sized work (a few MFLOP): one thread
+// per output element, sums in double.
+__device__ __forceinline__ const float *slab(const float *theta, const float *bias, int j, int D, int Dout)
+{
+    return j < 3 ? theta + (int64_t)j * D * Dout : bias;
+}
+
+// Pc[j][c0][o] = sum_c W[c][c0] * P[j][c][o]
+__global__ __launch_bounds__(256) void compose_1x1_kernel(const float *__restrict__ W, const float *__restrict__ theta,
+                                                          const float *__restrict__ bias, float *__restrict__ theta_c,
+                                                          float *__restrict__ bias_c, int Din0, int Dmid, int Dout)
+{
+    const int total = 4 * Din0 * Dout;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const int o = i % Dout, c0 = (i / Dout) % Din0, j = i / (Dout * Din0);
+        const float *P = slab(theta, bias, j, Dmid, Dout);
+        double s = 0.0;
+        for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * (double)P[(int64_t)c * Dout + o];
+        float *dst = j < 3 ? theta_c + (int64_t)j * Din0 * Dout : bias_c;
+        dst[(int64_t)c0 * Dout + o] = (float)s;
+    }
+}
+
+// gP[j][c][o] = sum_c0 W[c][c0] * gPc[j][c0][o]     (first 4*Dmid*Dout threads' worth of items)
+// gW[c][c0]   = sum_{j,o} P[j][c][o] * gPc[j][c0][o] (the Dmid*Din0 items after them)
+__global__ __launch_bounds__(256) void compose_1x1_bwd_kernel(const float *__restrict__ W, const float *__restrict__ theta,
+                                                              const float *__restrict__ bias,
+                                                              const float *__restrict__ gtheta_c,
+                                                              const float *__restrict__ gbias_c, float *__restrict__ gW,
+                                                              float *__restrict__ gtheta, float *__restrict__ gbias,
+                                                              int Din0, int Dmid, int Dout)
+{
+    const int nP = 4 * Dmid * Dout, total = nP + Dmid * Din0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        if (i < nP) {
+            const int o = i % Dout, c = (i / Dout) % Dmid, j = i / (Dout * Dmid);
+            const float *G = slab(gtheta_c, gbias_c, j, Din0, Dout);
+            double s = 0.0;
+            for (int c0 = 0; c0 < Din0; ++c0) s += (double)W[(int64_t)c * Din0 + c0] * (double)G[(int64_t)c0 * Dout + o];
+            float *dst = j < 3 ? gtheta + (int64_t)j * Dmid * Dout : gbias;
+            dst[(int64_t)c * Dout + o] = (float)s;
+        } else {
+            const int k = i - nP, c0 = k % Din0, c = k / Din0;
+            double s = 0.0;
+            for (int j = 0; j < 4; ++j) {
+                const float *P = slab(theta, bias, j, Dmid, Dout) + (int64_t)c * Dout;
+                const float *G = slab(gtheta_c, gbias_c, j, Din0, Dout) + (int64_t)c0 * Dout;
+                for (int o = 0; o < Dout; ++o) s += (double)P[o] * (double)G[o];
+            }
+            gW[(int64_t)c * Din0 + c0] = (float)s;
+        }
+    }
+}
+
+hipError_t launch_compose_1x1(const float *W, const float *theta, const float *bias, float *theta_c, float *bias_c,
+                              int Din0, int Dmid, int Dout, hipStream_t s)
+{
+    const int total = 4 * Din0 * Dout;
+    hipLaunchKernelGGL(compose_1x1_kernel, dim3((total + 255) / 256), dim3(256), 0, s, W, theta, bias, theta_c, bias_c,
+                       Din0, Dmid, Dout);
+    return hipGetLastError();
+}
+
+hipError_t launch_compose_1x1_bwd(const float *W, const float *theta, const float *bias, const float *gtheta_c,
+                                  const float *gbias_c, float *gW, float *gtheta, float *gbias, int Din0, int Dmid,
+                                  int Dout, hipStream_t s)
+{
+    const int total = 4 * Dmid * Dout + Dmid * Din0;
+    hipLaunchKernelGGL(compose_1x1_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, W, theta, bias, gtheta_c,
+                       gbias_c, gW, gtheta, gbias, Din0, Dmid, Dout);
+    return hipGetLastError();
+}
+
 }  // namespace flex

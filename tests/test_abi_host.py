@@ -22,7 +22,7 @@ def L():
 def declared_symbols():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(flex[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(flex[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(L):
@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported(L):
     assert {"flexconv_fwd", "flexconv_bwd", "flexpool_fwd", "flexpool_bwd", "flex_inedges_build",
             "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
             "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
-            "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub"} <= set(names)
+            "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub",
+            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -80,6 +81,11 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
     # flexupsample_bwd(grad_out, argmax, sel, in_off, in_src, grad_small, B, Ns, Nf, K, C, layout, stream)
     assert L.flexupsample_bwd(one, one, one, none, one, one, 1, 4, 16, 2, 8, 0, None) == 1          # lists are required
     assert L.flexupsample_bwd(one, one, one, one, one, one, 1, 4, 16, 2, 0, 0, None) == 2
+    # flexconv_compose_1x1(W, theta, bias, theta_c, bias_c, Din0, Dmid, Dout, stream)
+    assert L.flexconv_compose_1x1(one, one, none, one, one, 8, 8, 8, None) == 1
+    assert L.flexconv_compose_1x1(one, one, one, one, one, 0, 8, 8, None) == 2
+    assert L.flexconv_compose_1x1_bwd(one, one, one, one, one, one, one, none, 8, 8, 8, None) == 1
+    assert L.flexconv_compose_1x1_bwd(one, one, one, one, one, one, one, one, 8, 1 << 20, 8, None) == 2
     # flexpool_sub_fwd(feat, nbr, sel, out, argmax, B, N, Ns, K, C, layout, stream)
     assert L.flexpool_sub_fwd(one, one, none, one, one, 1, 16, 4, 2, 8, 0, None) == 1
     assert L.flexpool_sub_fwd(one, one, one, one, one, 1, 16, 17, 2, 8, 0, None) == 2               # Ns > N

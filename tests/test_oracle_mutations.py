@@ -11,6 +11,7 @@ import test_oracle_conv as tc
 import test_oracle_pool as tp
 import test_oracle_upsample as tu
 import test_oracle_pool_sub as ts
+import test_oracle_block as tb
 
 SRC = open(os.path.join(os.path.dirname(oracle.__file__), "oracle.c")).read()
 
@@ -30,6 +31,9 @@ UP_PINS = [tu.test_upsample_fwd_bruteforce_with_ties, tu.test_upsample_fwd_is_ze
 
 SUB_PINS = [ts.test_pool_sub_fwd_bruteforce_with_ties, ts.test_pool_sub_fwd_grid_is_3x3_maxpool_stride2,
             ts.test_pool_sub_bwd_bruteforce_mass_and_repeats, ts.test_pool_sub_bwd_is_directional_derivative]
+
+BLOCK_PINS = [tb.test_block_fwd_bruteforce_dense, tb.test_block_identity_1x1_is_plain_flexconv,
+              tb.test_block_bwd_finite_differences_full_jacobian]
 
 POS_PINS = [tc.test_bwd_pos_finite_differences, tc.test_bwd_pos_bruteforce_translation_and_self_edges]
 
@@ -66,6 +70,11 @@ MUTATIONS = [
     ("pool_sub_tie_by_slot", "if (v > bv || (v == bv && n < best))", "if (v > bv)", 2, SUB_PINS),
     ("pool_sub_bwd_to_kept_centre", "grad_feat[IDX3(b, c, m, C, N)] += gpooled[IDX3(b, c, l, C, N)];",
      "grad_feat[IDX3(b, c, l, C, N)] += gpooled[IDX3(b, c, l, C, N)];", 0, SUB_PINS),
+    ("block_1x1_transposed", "s += (double)W[(int64_t)c * Din0 + c0] * (double)feat[IDX3(b, c0, n, Din0, N)];\n                mid",
+     "s += (double)W[(int64_t)c0 * Dmid + c] * (double)feat[IDX3(b, c0, n, Din0, N)];\n                mid", 0, BLOCK_PINS),
+    ("block_grad_w_uses_centre_gradient", "gmid[IDX3(b, c, n, Dmid, N)] += s;", "gmid[IDX3(b, c, l, Dmid, N)] += s;", 0, BLOCK_PINS),
+    ("block_grad_feat_untransposed", "for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * gmid[IDX3(b, c, n, Dmid, N)];",
+     "for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * gmid[IDX3(b, c0 % Dmid, n, Dmid, N)];", 0, BLOCK_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
