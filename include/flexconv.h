@@ -56,7 +56,8 @@ typedef enum {
     FLEX_OP_INEDGES = 3,
     FLEX_OP_UPSAMPLE = 4,       /* flexupsample_fwd / flex_validate_selection; N = points of the larger layer */
     FLEX_OP_CONV_BWD_POS = 5,       /* flexconv_bwd_pos with caller-supplied in-edge lists */
-    FLEX_OP_CONV_BWD_POS_BUILD = 6  /* in-edge lists built inside the call */
+    FLEX_OP_CONV_BWD_POS_BUILD = 6, /* in-edge lists built inside the call */
+    FLEX_OP_IDISS = 7               /* flex_idiss_sample */
 } flex_op;
 
 /*
@@ -208,6 +209,30 @@ int flexpool_sub_bwd(const float *grad_out, const int32_t *argmax,
 int flex_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
                            int32_t *in_off, int32_t *in_src,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Inverse density importance sub-sampling, step 1 (Sec. 3.3): phi[b,l] = sum over the K
+ * neighbours n of ||pos[b,:,l] - pos[b,:,n]||, the paper's approximation of the inverse
+ * density.  pos [B,3,N], nbr int32 [B,K,N], phi fp32 [B,N] (overwritten).
+ */
+int flex_idiss_phi(const float *pos, const int32_t *nbr, float *phi, int B, int N, int K, void *stream);
+
+/*
+ * Inverse density importance sub-sampling, step 2: Ns points per cloud drawn with probability
+ * proportional to phi in one pass over the points.  The paper asks for proportional sampling
+ * in O(n) and fixes no procedure; the one used is stratified sampling on the running sum, in
+ * integer arithmetic so that the result does not depend on summation order:
+ *   q[l] = floor(phi[l] * (2^bits / max phi)) in fp32, bits = min(28, 51 - ceil(log2 N)); all 1
+ *          if the maximum is 0;  C = running sum of q (64 bit);  Q = its total;
+ *   stratum j of [0,Q) has Q / Ns units (+1 for the first Q mod Ns), threshold
+ *   t_j = start_j + floor(u[b,j] * len_j / 2^32), sel[b,j] = first l with C[l] > t_j.
+ * u uint32 [B,Ns] = the caller's random words (any generator; the library draws none).
+ * sel int32 [B,Ns], ascending; a point far heavier than a stratum is drawn for each threshold
+ * it spans (drawing with replacement), a point with q = 0 never.  phi must be finite and >= 0.
+ * N <= 2^25 per cloud, B <= 65535.  Workspace: flexconv_workspace_bytes(FLEX_OP_IDISS, B, N, ...).
+ */
+int flex_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, int N, int Ns,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Flex-upsampling forward (Sec. 4.1): the features of the smaller layer's points are copied

@@ -20,7 +20,7 @@ def build(force: bool = False) -> str:
     """Compile oracle.c with gcc (OpenMP) into oracle/liboracle.so."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared",
-               "-std=c11", "-Wall", "-o", _LIB, _SRC]
+               "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -242,3 +242,27 @@ def block_bwd(feat, pos, nbr, W, theta, bias, grad_out):
     _check(_load().oracle_block_bwd(_p(feat), _p(pos), _p(nbr), _p(W), _p(theta), _p(bias), _p(grad_out),
                                     _p(gf), _p(gW), _p(gt), _p(gb), B, N, K, Din0, Dmid, Dout), "oracle_block_bwd")
     return gf, gW, gt, gb
+
+
+def idiss_phi(pos, nbr):
+    """Sum of the distances to the K neighbours (Sec. 3.3).  Returns float64 [B,N]."""
+    pos, nbr = _f32(pos), _i32(nbr)
+    B, _, N = pos.shape
+    K = nbr.shape[1]
+    assert count_bad_neighbors(nbr, N) == 0
+    phi = np.zeros((B, N), np.float64)
+    _check(_load().oracle_idiss_phi(_p(pos), _p(nbr), _p(phi), B, N, K), "oracle_idiss_phi")
+    return phi
+
+
+def idiss_sample(phi, u):
+    """Stratified draw of Ns = u.shape[1] points per cloud proportional to phi float32 [B,N], with the
+    caller's random words u uint32 [B,Ns].  Returns sel int32 [B,Ns], ascending."""
+    phi = _f32(phi)
+    u = np.ascontiguousarray(u, dtype=np.uint32)
+    B, N = phi.shape
+    Ns = u.shape[1]
+    assert u.shape == (B, Ns)
+    sel = np.zeros((B, Ns), np.int32)
+    _check(_load().oracle_idiss_sample(_p(phi), _p(u), _p(sel), B, N, Ns), "oracle_idiss_sample")
+    return sel

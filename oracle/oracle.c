@@ -57,6 +57,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#include <math.h>
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -626,4 +627,88 @@ int oracle_block_bwd(const float *feat, const float *pos, const int32_t *nbr, co
             }
     free(mid); free(gmid);
     return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Inverse density importance sub-sampling (Sec. 3.3).
+ * Step 1: phi[b,l] = sum over the neighbourhood of the distances ||pos[l] - pos[n]|| (the
+ * paper's approximation of the inverse density).  phi is double [B,N].
+ * ------------------------------------------------------------------------- */
+int oracle_idiss_phi(const float *pos, const int32_t *nbr, double *phi, int B, int N, int K)
+{
+    if (!pos || !nbr || !phi) return 1;
+    if (B <= 0 || N <= 0 || K <= 0) return 2;
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const int n = nbr[IDX3(b, k, l, K, N)];
+                double d2 = 0.0;
+                for (int d = 0; d < 3; ++d) {
+                    const double t = (double)pos[IDX3(b, d, n, 3, N)] - (double)pos[IDX3(b, d, l, 3, N)];
+                    d2 += t * t;
+                }
+                s += sqrt(d2);
+            }
+            phi[(int64_t)b * N + l] = s;
+        }
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Step 2: draw Ns points of every cloud with probability proportional to phi, in one
+ * pass over the points (the paper states proportional sampling in O(n) and fixes no
+ * procedure; this is the reading taken: stratified sampling on the running sum).
+ * So that every decision is an integer comparison (the same on any machine, in any
+ * summation order), phi is first put on an integer scale:
+ *   q[l] = floor(phi[l] * (2^bits / max_l phi[l]))   in float arithmetic, one division and
+ *          one product, bits = min(28, 51 - ceil(log2 N));  all q = 1 if the maximum is 0
+ *   C[l] = q[0] + ... + q[l],  Q = C[N-1]
+ * The range [0,Q) is cut into Ns strata, stratum j = [start_j, start_j + len_j) with
+ * len_j = Q / Ns (+1 for the first Q mod Ns strata); the caller's random word u[b,j]
+ * places one threshold in it, t_j = start_j + floor(u[b,j] * len_j / 2^32), and
+ * sel[b,j] = the first point with C[l] > t_j.  sel is ascending; a point whose q spans
+ * several thresholds is drawn for each of them (drawing with replacement), a point with
+ * q = 0 is never drawn.  Returns 2 when Q < Ns (fewer units than strata).
+ * ------------------------------------------------------------------------- */
+int oracle_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, int N, int Ns)
+{
+    if (!phi || !u || !sel) return 1;
+    if (B <= 0 || N <= 0 || Ns <= 0 || Ns > N) return 2;
+    int lg = 0;
+    while (((int64_t)1 << lg) < N) ++lg;
+    const int bits = (51 - lg) < 28 ? (51 - lg) : 28;
+    if (bits < 1) return 2;
+    uint64_t *C = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)N);
+    if (!C) return 6;
+    int rc = 0;
+    for (int b = 0; b < B && rc == 0; ++b) {
+        const float *ph = phi + (int64_t)b * N;
+        float mx = 0.f;
+        for (int l = 0; l < N; ++l) {
+            if (!(ph[l] >= 0.f)) { rc = 2; break; }          /* negative or NaN */
+            if (ph[l] > mx) mx = ph[l];
+        }
+        if (rc) break;
+        const float scale = (mx > 0.f) ? (float)((int64_t)1 << bits) / mx : 0.f;
+        uint64_t run = 0;
+        for (int l = 0; l < N; ++l) {
+            const uint32_t q = (mx > 0.f) ? (uint32_t)(ph[l] * scale) : 1u;
+            run += q;
+            C[l] = run;
+        }
+        const uint64_t Q = run;
+        if (Q < (uint64_t)Ns) { rc = 2; break; }
+        const uint64_t width = Q / (uint64_t)Ns, rem = Q % (uint64_t)Ns;
+        int l = 0;
+        for (int j = 0; j < Ns; ++j) {
+            const uint64_t start = (uint64_t)j * width + ((uint64_t)j < rem ? (uint64_t)j : rem);
+            const uint64_t len = width + ((uint64_t)j < rem ? 1u : 0u);
+            const uint64_t t = start + (uint64_t)(((unsigned __int128)u[(int64_t)b * Ns + j] * len) >> 32);
+            while (C[l] <= t) ++l;                            /* thresholds ascend, so the walk never goes back */
+            sel[(int64_t)b * Ns + j] = l;
+        }
+    }
+    free(C);
+    return rc;
 }

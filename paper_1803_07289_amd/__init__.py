@@ -17,6 +17,7 @@ BCN = 0   # [B,C,N]  channel-major, the paper's form
 BNC = 1   # [B,N,C]  point-major, the library's native form
 OP_CONV_FWD, OP_CONV_BWD, OP_CONV_BWD_BUILD, OP_INEDGES, OP_UPSAMPLE = 0, 1, 2, 3, 4
 OP_CONV_BWD_POS, OP_CONV_BWD_POS_BUILD = 5, 6
+OP_IDISS = 7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexconv.so")
@@ -33,6 +34,8 @@ _SIGS = {
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexconv_compose_1x1": (_i, [_vp] * 5 + [_i] * 3 + [_vp]),
     "flexconv_compose_1x1_bwd": (_i, [_vp] * 8 + [_i] * 3 + [_vp]),
+    "flex_idiss_phi": (_i, [_vp] * 3 + [_i] * 3 + [_vp]),
+    "flex_idiss_sample": (_i, [_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp]),
     "flexpool_sub_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
     "flexpool_sub_bwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
     "flex_inedges_build_sub": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
@@ -289,6 +292,35 @@ def flexconv_compose_1x1_bwd(W, theta, bias, grad_theta_c, grad_bias_c):
                                           _ptr(gW), _ptr(gt), _ptr(gb), Din0, Dmid, Dout, _stream()),
            "flexconv_compose_1x1_bwd")
     return gW, gt, gb
+
+
+def flex_idiss_phi(pos, nbr):
+    """phi [B,N]: sum of the distances from every point to its K neighbours (Sec. 3.3)."""
+    _dev(pos, torch.float32, "pos"); _dev(nbr, torch.int32, "nbr")
+    B, K, N = nbr.shape
+    if tuple(pos.shape) != (B, 3, N):
+        raise ValueError("pos must be [B,3,N]")
+    phi = torch.empty((B, N), dtype=torch.float32, device=pos.device)
+    _check(lib().flex_idiss_phi(_ptr(pos.contiguous()), _ptr(nbr), _ptr(phi), B, N, K, _stream()), "flex_idiss_phi")
+    return phi
+
+
+def flex_idiss_sample(phi, u, workspace=None):
+    """Ns = u.shape[1] points per cloud drawn proportionally to phi [B,N] from the random words u (an int32 or
+    uint32-valued tensor [B,Ns], taken bit for bit).  Returns sel int32 [B,Ns], ascending."""
+    _dev(phi, torch.float32, "phi")
+    if not u.is_cuda or u.dtype not in (torch.int32, torch.uint32) or u.dim() != 2:
+        raise TypeError("u must be a CUDA int32 / uint32 tensor [B,Ns]")
+    B, N = phi.shape
+    Ns = u.shape[1]
+    if u.shape[0] != B:
+        raise ValueError("u must be [B,Ns]")
+    sel = torch.empty((B, Ns), dtype=torch.int32, device=phi.device)
+    need = workspace_bytes(OP_IDISS, B, N, 1, 1, 1, BCN)
+    ws = workspace if workspace is not None else _workspace(phi.device, need)
+    _check(lib().flex_idiss_sample(_ptr(phi.contiguous()), _ptr(u.contiguous()), _ptr(sel), B, N, Ns, _ptr(ws),
+                                   ws.numel(), _stream()), "flex_idiss_sample")
+    return sel
 
 
 def flexpool_sub_fwd(feat, nbr, sel, layout=BCN):

@@ -244,6 +244,12 @@ static bool sizes_ok(int64_t B, int64_t N, int64_t K, int64_t Din, int64_t Dout)
     return true;
 }
 
+// the draw's integer scale needs N <= 2^25 per cloud; one grid row per cloud
+static bool idiss_sizes_ok(int64_t B, int64_t N)
+{
+    return sizes_ok(B, N, 1, 1, 1) && N <= (1 << 25) && B <= 65535;
+}
+
 static bool ws_ok(const void *ws, size_t have, size_t need)
 {
     return ws != nullptr && (((uintptr_t)ws) & 255) == 0 && have >= need;
@@ -287,6 +293,7 @@ size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, 
     case FLEX_OP_CONV_BWD_POS: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, false).total : 0;
     case FLEX_OP_CONV_BWD_POS_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, true).total : 0;
     case FLEX_OP_UPSAMPLE: return sizes_ok(B, N, 1, 1, 1) ? align256(sizeof(int32_t) * (size_t)B * N) : 0;
+    case FLEX_OP_IDISS: return idiss_sizes_ok(B, N) ? idiss_ws_bytes(B, N) : 0;
     default: return 0;
     }
 }
@@ -433,6 +440,24 @@ int flexconv_compose_1x1_bwd(const float *W, const float *theta, const float *bi
         return FLEX_ERR_SHAPE;
     FLEX_HIP(launch_compose_1x1_bwd(W, theta, bias, grad_theta_c, grad_bias_c, grad_W, grad_theta, grad_bias, Din0,
                                     Dmid, Dout, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flex_idiss_phi(const float *pos, const int32_t *nbr, float *phi, int B, int N, int K, void *stream)
+{
+    if (!pos || !nbr || !phi) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, 1, 1)) return FLEX_ERR_SHAPE;
+    FLEX_HIP(launch_idiss_phi(pos, nbr, phi, B, N, K, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flex_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, int N, int Ns,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!phi || !u || !sel) return FLEX_ERR_NULL;
+    if (!idiss_sizes_ok(B, N) || Ns <= 0 || Ns > N) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, idiss_ws_bytes(B, N))) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_idiss_sample(phi, u, sel, B, N, Ns, workspace, (hipStream_t)stream));
     return FLEX_OK;
 }
 

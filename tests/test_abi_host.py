@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(L):
             "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
             "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
             "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub",
-            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd"} <= set(names)
+            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -86,6 +86,14 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
     assert L.flexconv_compose_1x1(one, one, one, one, one, 0, 8, 8, None) == 2
     assert L.flexconv_compose_1x1_bwd(one, one, one, one, one, one, one, none, 8, 8, 8, None) == 1
     assert L.flexconv_compose_1x1_bwd(one, one, one, one, one, one, one, one, 8, 1 << 20, 8, None) == 2
+    # flex_idiss_phi(pos, nbr, phi, B, N, K, stream); flex_idiss_sample(phi, u, sel, B, N, Ns, ws, ws_bytes, stream)
+    assert L.flex_idiss_phi(one, none, one, 1, 16, 4, None) == 1
+    assert L.flex_idiss_phi(one, one, one, 1, 16, 17, None) == 2
+    assert L.flex_idiss_sample(one, one, none, 1, 16, 4, one, big, None) == 1
+    assert L.flex_idiss_sample(one, one, one, 1, 16, 17, one, big, None) == 2
+    assert L.flex_idiss_sample(one, one, one, 1, (1 << 25) + 1, 4, one, big, None) == 2
+    assert L.flex_idiss_sample(one, one, one, 1, 4096, 4, one, 1024, None) == 4
+    assert L.flexconv_workspace_bytes(7, 1, 4096, 1, 1, 1, 0) == 8 * 4096 + 256 + 256
     # flexpool_sub_fwd(feat, nbr, sel, out, argmax, B, N, Ns, K, C, layout, stream)
     assert L.flexpool_sub_fwd(one, one, none, one, one, 1, 16, 4, 2, 8, 0, None) == 1
     assert L.flexpool_sub_fwd(one, one, one, one, one, 1, 16, 17, 2, 8, 0, None) == 2               # Ns > N

@@ -1,0 +1,96 @@
+"""Pins for the CPU oracle's inverse density importance sub-sampling (Sec. 3.3), CPU only."""
+from fractions import Fraction
+
+import numpy as np
+
+import oracle
+from helpers import grid2d
+
+
+def test_phi_bruteforce_and_grid_closed_form():
+    rng = np.random.default_rng(0)
+    B, N, K = 2, 29, 5
+    pos = rng.random((B, 3, N)).astype(np.float32)
+    nbr = rng.integers(0, N, size=(B, K, N)).astype(np.int32)
+    phi = oracle.idiss_phi(pos, nbr)
+    p = pos.astype(np.float64)
+    for b in range(B):
+        for l in range(N):
+            ref = sum(np.linalg.norm(p[b, :, nbr[b, k, l]] - p[b, :, l]) for k in range(K))
+            assert abs(phi[b, l] - ref) <= 1e-13 * max(1.0, ref)
+    # regular grid, the 3x3 offsets: four neighbours at h, four at h*sqrt(2), the point itself at 0
+    H, W, h = 7, 9, 0.5
+    gpos, gnbr, _ = grid2d(H, W, h)
+    gphi = oracle.idiss_phi(gpos, gnbr).reshape(H, W)
+    np.testing.assert_allclose(gphi[1:-1, 1:-1], 4 * h + 4 * h * np.sqrt(2.0), rtol=1e-12)
+
+
+def _reference_sample(phi, u):
+    """The same procedure with exact rationals / Python integers, written independently."""
+    N, Ns = len(phi), len(u)
+    lg = (N - 1).bit_length()
+    bits = min(28, 51 - lg)
+    mx = np.float32(phi.max())
+    if mx > 0:
+        scale = np.float32(np.float32(2.0 ** bits) / mx)
+        q = [int(np.float32(np.float32(x) * scale)) for x in phi]
+    else:
+        q = [1] * N
+    C = np.cumsum(np.array(q, dtype=object))
+    Q = int(C[-1])
+    out = []
+    for j in range(Ns):
+        # strata of whole units, lengths differing by at most one: the first Q mod Ns get the extra unit
+        width, rem = divmod(Q, Ns)
+        lens = [width + (1 if i < rem else 0) for i in range(Ns)]
+        assert sum(lens) == Q
+        start, ln = sum(lens[:j]), lens[j]
+        t = start + int(Fraction(int(u[j]), 2 ** 32) * ln)
+        out.append(next(i for i in range(N) if C[i] > t))
+    return out
+
+
+def test_sample_matches_exact_integer_reference():
+    rng = np.random.default_rng(1)
+    for N, Ns in ((50, 12), (64, 64), (33, 1), (200, 50)):
+        phi = rng.random((2, N)).astype(np.float32)
+        phi[0, ::7] = 0.0                                   # never drawn
+        phi[1, 3] = 40.0                                    # far heavier than a stratum: drawn several times
+        u = rng.integers(0, 2 ** 32, size=(2, Ns), dtype=np.uint64).astype(np.uint32)
+        sel = oracle.idiss_sample(phi, u)
+        for b in range(2):
+            assert list(sel[b]) == _reference_sample(phi[b], u[b])
+        assert (np.diff(sel, axis=1) >= 0).all()
+        assert not np.isin(sel[0], np.arange(0, N, 7)).any()
+    # few units (all-zero phi gives one unit per point): the strata's uneven lengths decide the draw
+    for N, Ns in ((10, 4), (7, 3), (23, 5)):
+        phi = np.zeros((1, N), np.float32)
+        for seed in range(20):
+            u = np.random.default_rng(seed).integers(0, 2 ** 32, size=(1, Ns), dtype=np.uint64).astype(np.uint32)
+            assert list(oracle.idiss_sample(phi, u)[0]) == _reference_sample(phi[0], u[0])
+
+
+def test_sample_uniform_density_is_one_point_per_block():
+    # equal phi: the strata are equal blocks of points, one point drawn from each
+    N, Ns = 4096, 1024
+    phi = np.full((1, N), 0.37, np.float32)
+    rng = np.random.default_rng(2)
+    u = rng.integers(0, 2 ** 32, size=(1, Ns), dtype=np.uint64).astype(np.uint32)
+    sel = oracle.idiss_sample(phi, u)[0]
+    assert np.array_equal(sel // 4, np.arange(Ns))
+    assert len(np.unique(sel % 4)) == 4                     # the random words move the draw inside a block
+    # all-zero phi (coincident points) falls back to the same uniform draw
+    assert np.array_equal(oracle.idiss_sample(np.zeros((1, N), np.float32), u)[0], sel)
+
+
+def test_sample_frequencies_are_proportional_to_phi():
+    rng = np.random.default_rng(3)
+    N, Ns, trials = 60, 15, 4000
+    phi = (0.2 + rng.random(N)).astype(np.float32)
+    counts = np.zeros(N)
+    for _ in range(trials):
+        u = rng.integers(0, 2 ** 32, size=(1, Ns), dtype=np.uint64).astype(np.uint32)
+        np.add.at(counts, oracle.idiss_sample(phi[None], u)[0], 1)
+    expect = trials * Ns * phi.astype(np.float64) / phi.astype(np.float64).sum()
+    assert np.abs(counts - expect).max() <= 5.0 * np.sqrt(expect.max())      # five sigma of a Poisson count
+    assert abs(counts.sum() - trials * Ns) == 0

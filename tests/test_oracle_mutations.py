@@ -12,6 +12,7 @@ import test_oracle_pool as tp
 import test_oracle_upsample as tu
 import test_oracle_pool_sub as ts
 import test_oracle_block as tb
+import test_oracle_idiss as ti
 
 SRC = open(os.path.join(os.path.dirname(oracle.__file__), "oracle.c")).read()
 
@@ -34,6 +35,9 @@ SUB_PINS = [ts.test_pool_sub_fwd_bruteforce_with_ties, ts.test_pool_sub_fwd_grid
 
 BLOCK_PINS = [tb.test_block_fwd_bruteforce_dense, tb.test_block_identity_1x1_is_plain_flexconv,
               tb.test_block_bwd_finite_differences_full_jacobian]
+
+IDISS_PINS = [ti.test_phi_bruteforce_and_grid_closed_form, ti.test_sample_matches_exact_integer_reference,
+              ti.test_sample_uniform_density_is_one_point_per_block]
 
 POS_PINS = [tc.test_bwd_pos_finite_differences, tc.test_bwd_pos_bruteforce_translation_and_self_edges]
 
@@ -75,6 +79,9 @@ MUTATIONS = [
     ("block_grad_w_uses_centre_gradient", "gmid[IDX3(b, c, n, Dmid, N)] += s;", "gmid[IDX3(b, c, l, Dmid, N)] += s;", 0, BLOCK_PINS),
     ("block_grad_feat_untransposed", "for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * gmid[IDX3(b, c, n, Dmid, N)];",
      "for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * gmid[IDX3(b, c0 % Dmid, n, Dmid, N)];", 0, BLOCK_PINS),
+    ("idiss_phi_squared_distance", "s += sqrt(d2);", "s += d2;", 0, IDISS_PINS),
+    ("idiss_threshold_inclusive", "while (C[l] <= t) ++l;", "while (C[l] < t) ++l;", 0, IDISS_PINS),
+    ("idiss_remainder_dropped", "const uint64_t len = width + ((uint64_t)j < rem ? 1u : 0u);", "const uint64_t len = width;", 0, IDISS_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
@@ -93,7 +100,7 @@ def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, which,
     src = tmp_path / "mut.c"
     lib = tmp_path / "libmut.so"
     src.write_text(_replace(SRC, old, new, which))
-    subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(lib), str(src)], check=True)
+    subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(lib), str(src), "-lm"], check=True)
     mut = ctypes.CDLL(str(lib))
     mut.oracle_count_bad_neighbors.restype = ctypes.c_int64
     oracle._load()
