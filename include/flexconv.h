@@ -57,7 +57,8 @@ typedef enum {
     FLEX_OP_UPSAMPLE = 4,       /* flexupsample_fwd / flex_validate_selection; N = points of the larger layer */
     FLEX_OP_CONV_BWD_POS = 5,       /* flexconv_bwd_pos with caller-supplied in-edge lists */
     FLEX_OP_CONV_BWD_POS_BUILD = 6, /* in-edge lists built inside the call */
-    FLEX_OP_IDISS = 7               /* flex_idiss_sample */
+    FLEX_OP_IDISS = 7,              /* flex_idiss_sample */
+    FLEX_OP_KNN = 8                 /* flex_knn */
 } flex_op;
 
 /*
@@ -209,6 +210,20 @@ int flexpool_sub_bwd(const float *grad_out, const int32_t *argmax,
 int flex_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
                            int32_t *in_off, int32_t *in_src,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * K nearest neighbours (Sec. 3: neighbourhoods are the k nearest points; Sec. 4.1: the index
+ * tensors of every resolution are computed ahead of the network.  The paper does not say how;
+ * this is an exact search on a uniform grid).  nbr[b,k,l] = the point with the k-th smallest
+ * squared distance to point l in cloud b, the point itself included (slot 0 unless an equal
+ * point has a lower index), ordered by (d2, index): equal distances go to the LOWER INDEX.
+ * d2 is evaluated in fp32 as ((dx*dx + dy*dy) + dz*dz), dx = pos[n] - pos[l], each operation
+ * rounded separately; the result is the exact ranking under that d2.
+ * pos [B,3,N] finite; nbr int32 [B,K,N] overwritten.  K in 1..10, 12, 16, 24 or 32, K <= N;
+ * B <= 65535.  Workspace: flexconv_workspace_bytes(FLEX_OP_KNN, B, N, K, ...).
+ */
+int flex_knn(const float *pos, int32_t *nbr, int B, int N, int K,
+             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Inverse density importance sub-sampling, step 1 (Sec. 3.3): phi[b,l] = sum over the K

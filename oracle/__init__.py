@@ -19,7 +19,7 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile oracle.c with gcc (OpenMP) into oracle/liboracle.so."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared",
+        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
                "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
@@ -266,3 +266,13 @@ def idiss_sample(phi, u):
     sel = np.zeros((B, Ns), np.int32)
     _check(_load().oracle_idiss_sample(_p(phi), _p(u), _p(sel), B, N, Ns), "oracle_idiss_sample")
     return sel
+
+
+def knn(pos, K):
+    """Exhaustive K nearest neighbours (self included), float32 distances, ties by lower index.
+    pos [B,3,N] -> nbr int32 [B,K,N]."""
+    pos = _f32(pos)
+    B, _, N = pos.shape
+    nbr = np.zeros((B, int(K), N), np.int32)
+    _check(_load().oracle_knn(_p(pos), _p(nbr), B, N, int(K)), "oracle_knn")
+    return nbr

@@ -712,3 +712,44 @@ int oracle_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B
     free(C);
     return rc;
 }
+
+/* ---------------------------------------------------------------------------
+ * K nearest neighbours by exhaustive search (Sec. 3: neighbourhoods are the k nearest
+ * points; the paper computes them beforehand and does not say how).  For every point l the
+ * K points of its cloud with the smallest squared distance, the point itself included,
+ * ordered by (d2 ascending, index ascending); equal d2 are broken by the LOWER INDEX.
+ * d2 is evaluated in float, exactly as ((dx*dx + dy*dy) + dz*dz) with dx = pos[n] - pos[l]
+ * and every operation rounded on its own (no fused multiply-add: build with
+ * -ffp-contract=off), because the ranking is an integer-valued decision that both this
+ * code and the library must take in the same precision.  nbr is int32 [B,K,N].
+ * ------------------------------------------------------------------------- */
+int oracle_knn(const float *pos, int32_t *nbr, int B, int N, int K)
+{
+    if (!pos || !nbr) return 1;
+    if (B <= 0 || N <= 0 || K <= 0 || K > N) return 2;
+    int rc = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 64)
+    for (int b = 0; b < B; ++b)
+        for (int l = 0; l < N; ++l) {
+            const float *px = pos + IDX3(b, 0, 0, 3, N), *py = px + N, *pz = py + N;
+            float *bd = (float *)malloc(sizeof(float) * (size_t)K);
+            int32_t *bi = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+            if (!bd || !bi) { rc = 6; free(bd); free(bi); continue; }
+            int have = 0;
+            for (int n = 0; n < N; ++n) {
+                const float dx = px[n] - px[l], dy = py[n] - py[l], dz = pz[n] - pz[l];
+                const float xx = dx * dx, yy = dy * dy, zz = dz * dz;
+                const float xy = xx + yy;
+                const float d2 = xy + zz;
+                /* n ascends, so among equal d2 the earlier (lower) index already sits in front */
+                if (have == K && !(d2 < bd[K - 1])) continue;
+                int at = have < K ? have : K - 1;
+                while (at > 0 && d2 < bd[at - 1]) { bd[at] = bd[at - 1]; bi[at] = bi[at - 1]; --at; }
+                bd[at] = d2; bi[at] = n;
+                if (have < K) ++have;
+            }
+            for (int k = 0; k < K; ++k) nbr[IDX3(b, k, l, K, N)] = bi[k];
+            free(bd); free(bi);
+        }
+    return rc;
+}

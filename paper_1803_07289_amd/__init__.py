@@ -18,6 +18,7 @@ BNC = 1   # [B,N,C]  point-major, the library's native form
 OP_CONV_FWD, OP_CONV_BWD, OP_CONV_BWD_BUILD, OP_INEDGES, OP_UPSAMPLE = 0, 1, 2, 3, 4
 OP_CONV_BWD_POS, OP_CONV_BWD_POS_BUILD = 5, 6
 OP_IDISS = 7
+OP_KNN = 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflexconv.so")
@@ -34,6 +35,7 @@ _SIGS = {
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexconv_compose_1x1": (_i, [_vp] * 5 + [_i] * 3 + [_vp]),
     "flexconv_compose_1x1_bwd": (_i, [_vp] * 8 + [_i] * 3 + [_vp]),
+    "flex_knn": (_i, [_vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
     "flex_idiss_phi": (_i, [_vp] * 3 + [_i] * 3 + [_vp]),
     "flex_idiss_sample": (_i, [_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp]),
     "flexpool_sub_fwd": (_i, [_vp] * 5 + [_i] * 6 + [_vp]),
@@ -292,6 +294,22 @@ def flexconv_compose_1x1_bwd(W, theta, bias, grad_theta_c, grad_bias_c):
                                           _ptr(gW), _ptr(gt), _ptr(gb), Din0, Dmid, Dout, _stream()),
            "flexconv_compose_1x1_bwd")
     return gW, gt, gb
+
+
+def flex_knn(pos, K, workspace=None):
+    """Exact K nearest neighbours of every point of pos [B,3,N] (itself included), ordered by (distance, index).
+    Returns nbr int32 [B,K,N]."""
+    _dev(pos, torch.float32, "pos")
+    if pos.dim() != 3 or pos.shape[1] != 3:
+        raise ValueError("pos must be [B,3,N]")
+    B, _, N = pos.shape
+    nbr = torch.empty((B, int(K), N), dtype=torch.int32, device=pos.device)
+    need = workspace_bytes(OP_KNN, B, N, int(K), 1, 1, BCN)
+    if need == 0:
+        raise ValueError(f"flex_knn does not take B={B}, N={N}, K={K}")
+    ws = workspace if workspace is not None else _workspace(pos.device, need)
+    _check(lib().flex_knn(_ptr(pos.contiguous()), _ptr(nbr), B, N, int(K), _ptr(ws), ws.numel(), _stream()), "flex_knn")
+    return nbr
 
 
 def flex_idiss_phi(pos, nbr):

@@ -250,6 +250,14 @@ static bool idiss_sizes_ok(int64_t B, int64_t N)
     return sizes_ok(B, N, 1, 1, 1) && N <= (1 << 25) && B <= 65535;
 }
 
+// cell offsets are int32 over all clouds' cells; one grid row per cloud
+static bool knn_sizes_ok(int64_t B, int64_t N, int64_t K)
+{
+    if (!sizes_ok(B, N, K, 1, 1) || B > 65535 || !knn_k_supported((int)K)) return false;
+    const int64_t per_cloud = 8 * N < (1ll << 24) ? 8 * N : (1ll << 24);
+    return B * per_cloud < 0x7fffffffLL;
+}
+
 static bool ws_ok(const void *ws, size_t have, size_t need)
 {
     return ws != nullptr && (((uintptr_t)ws) & 255) == 0 && have >= need;
@@ -294,6 +302,7 @@ size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, 
     case FLEX_OP_CONV_BWD_POS_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, true).total : 0;
     case FLEX_OP_UPSAMPLE: return sizes_ok(B, N, 1, 1, 1) ? align256(sizeof(int32_t) * (size_t)B * N) : 0;
     case FLEX_OP_IDISS: return idiss_sizes_ok(B, N) ? idiss_ws_bytes(B, N) : 0;
+    case FLEX_OP_KNN: return knn_sizes_ok(B, N, K) ? knn_ws_bytes(B, N) : 0;
     default: return 0;
     }
 }
@@ -458,6 +467,16 @@ int flex_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, 
     if (!idiss_sizes_ok(B, N) || Ns <= 0 || Ns > N) return FLEX_ERR_SHAPE;
     if (!ws_ok(workspace, workspace_bytes, idiss_ws_bytes(B, N))) return FLEX_ERR_WORKSPACE;
     FLEX_HIP(launch_idiss_sample(phi, u, sel, B, N, Ns, workspace, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flex_knn(const float *pos, int32_t *nbr, int B, int N, int K, void *workspace, size_t workspace_bytes,
+             void *stream)
+{
+    if (!pos || !nbr) return FLEX_ERR_NULL;
+    if (!knn_sizes_ok(B, N, K)) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, knn_ws_bytes(B, N))) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_knn(pos, nbr, B, N, K, workspace, (hipStream_t)stream));
     return FLEX_OK;
 }
 

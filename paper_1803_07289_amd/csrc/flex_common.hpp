@@ -103,6 +103,11 @@ hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t
 hipError_t launch_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
                                     int32_t *in_off, int32_t *in_src, void *ws, hipStream_t s);
 size_t inedges_ws_bytes(int64_t BN);
+size_t exclusive_scan_ws_bytes(int64_t n);
+hipError_t launch_exclusive_scan_i32(const int32_t *cnt, int32_t *off, int64_t n, void *ws, hipStream_t s);
+size_t knn_ws_bytes(int B, int N);
+bool knn_k_supported(int K);
+hipError_t launch_knn(const float *pos, int32_t *nbr, int B, int N, int K, void *ws, hipStream_t s);
 
 // Pooling.
 hipError_t launch_pool_fwd(const float *feat, const int32_t *nbr, float *out, int32_t *argmax,

@@ -210,6 +210,19 @@ __global__ __launch_bounds__(256) void inedge_sort_kernel(const int32_t *__restr
     }
 }
 
+// off[0..n] = exclusive running sum of cnt[0..n) (off[n] = total); ws: exclusive_scan_ws_bytes(n)
+size_t exclusive_scan_ws_bytes(int64_t n) { return align256(sizeof(int32_t) * (size_t)(cdiv64(n, SCAN_CHUNK) + 1)); }
+
+hipError_t launch_exclusive_scan_i32(const int32_t *cnt, int32_t *off, int64_t n, void *ws, hipStream_t s)
+{
+    const int nblk = (int)cdiv64(n, SCAN_CHUNK);
+    int32_t *bsum = (int32_t *)ws;
+    hipLaunchKernelGGL(scan_block_sums_kernel, dim3(nblk), dim3(256), 0, s, cnt, bsum, n);
+    hipLaunchKernelGGL(scan_of_sums_kernel, dim3(1), dim3(256), 0, s, bsum, nblk);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(nblk), dim3(256), 0, s, cnt, bsum, off, n, nblk);
+    return hipGetLastError();
+}
+
 size_t inedges_ws_bytes(int64_t BN)
 {
     const int64_t nblk = cdiv64(BN, SCAN_CHUNK);

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(L):
             "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
             "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
             "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub",
-            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample"} <= set(names)
+            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample", "flex_knn"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -94,6 +94,13 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
     assert L.flex_idiss_sample(one, one, one, 1, (1 << 25) + 1, 4, one, big, None) == 2
     assert L.flex_idiss_sample(one, one, one, 1, 4096, 4, one, 1024, None) == 4
     assert L.flexconv_workspace_bytes(7, 1, 4096, 1, 1, 1, 0) == 8 * 4096 + 256 + 256
+    # flex_knn(pos, nbr, B, N, K, ws, ws_bytes, stream)
+    assert L.flex_knn(one, none, 1, 100, 8, one, big, None) == 1
+    assert L.flex_knn(one, one, 1, 100, 11, one, big, None) == 2           # K without a kernel
+    assert L.flex_knn(one, one, 1, 4, 8, one, big, None) == 2              # K > N
+    assert L.flex_knn(one, one, 1, 100, 8, one, 64, None) == 4
+    assert L.flexconv_workspace_bytes(8, 1, 100, 8, 1, 1, 0) > 100 * 16
+    assert L.flexconv_workspace_bytes(8, 1, 100, 11, 1, 1, 0) == 0
     # flexpool_sub_fwd(feat, nbr, sel, out, argmax, B, N, Ns, K, C, layout, stream)
     assert L.flexpool_sub_fwd(one, one, none, one, one, 1, 16, 4, 2, 8, 0, None) == 1
     assert L.flexpool_sub_fwd(one, one, one, one, one, 1, 16, 17, 2, 8, 0, None) == 2               # Ns > N

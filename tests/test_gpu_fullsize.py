@@ -33,6 +33,15 @@ def test_full_size_config(ci):
     feat, pos, nbr, theta, bias = bnc(x.feat), dev(x.pos), dev(x.nbr), dev(x.theta), dev(x.bias)
     assert fx.flex_validate_neighbors(nbr) == 0
 
+    say("  k-nearest neighbours on the GPU")
+    # the workload's neighbour tensor comes from an independent exact search on the CPU (float64 distances): the
+    # neighbourhoods must agree as sets (a float32 / float64 rounding difference could swap a K-th neighbour)
+    knn = fx.flex_knn(pos, K)
+    agree = (torch.sort(knn, 1).values == torch.sort(nbr, 1).values).all(1).float().mean().item()
+    say(f"  neighbourhoods equal to the harness's: {agree:.6f}")
+    assert agree >= 0.99999
+    del knn
+
     say("  forward")
     out = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=fx.BNC)
     torch.cuda.synchronize()

@@ -13,6 +13,7 @@ import test_oracle_upsample as tu
 import test_oracle_pool_sub as ts
 import test_oracle_block as tb
 import test_oracle_idiss as ti
+import test_oracle_knn as tk
 
 SRC = open(os.path.join(os.path.dirname(oracle.__file__), "oracle.c")).read()
 
@@ -38,6 +39,9 @@ BLOCK_PINS = [tb.test_block_fwd_bruteforce_dense, tb.test_block_identity_1x1_is_
 
 IDISS_PINS = [ti.test_phi_bruteforce_and_grid_closed_form, ti.test_sample_matches_exact_integer_reference,
               ti.test_sample_uniform_density_is_one_point_per_block]
+
+KNN_PINS = [tk.test_knn_matches_float32_numpy_ranking_with_ties, tk.test_knn_agrees_with_a_kd_tree_on_generic_points,
+            tk.test_knn_k_equals_n_and_duplicates]
 
 POS_PINS = [tc.test_bwd_pos_finite_differences, tc.test_bwd_pos_bruteforce_translation_and_self_edges]
 
@@ -82,6 +86,8 @@ MUTATIONS = [
     ("idiss_phi_squared_distance", "s += sqrt(d2);", "s += d2;", 0, IDISS_PINS),
     ("idiss_threshold_inclusive", "while (C[l] <= t) ++l;", "while (C[l] < t) ++l;", 0, IDISS_PINS),
     ("idiss_remainder_dropped", "const uint64_t len = width + ((uint64_t)j < rem ? 1u : 0u);", "const uint64_t len = width;", 0, IDISS_PINS),
+    ("knn_ties_to_later_index", "while (at > 0 && d2 < bd[at - 1])", "while (at > 0 && d2 <= bd[at - 1])", 0, KNN_PINS),
+    ("knn_drops_z", "const float d2 = xy + zz;", "const float d2 = xy;", 0, KNN_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
@@ -100,7 +106,7 @@ def test_planted_mistake_is_caught(tmp_path, monkeypatch, name, old, new, which,
     src = tmp_path / "mut.c"
     lib = tmp_path / "libmut.so"
     src.write_text(_replace(SRC, old, new, which))
-    subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(lib), str(src), "-lm"], check=True)
+    subprocess.run(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off", "-std=c11", "-o", str(lib), str(src), "-lm"], check=True)
     mut = ctypes.CDLL(str(lib))
     mut.oracle_count_bad_neighbors.restype = ctypes.c_int64
     oracle._load()
