@@ -20,6 +20,15 @@ namespace flex {
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
 
+// 128 -> 128 layers as passes over 64-channel blocks (flex_tiled_inst.hip, shapes 64x128 and 64x64)
+bool split_ok_128_128(int N, int K, int csr);
+hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr, const int32_t *off,
+                                   const int32_t *src, const void *thetaP, float *out, int B, int N, int K, int csr,
+                                   int accumulate, hipStream_t s);
+hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr,
+                                   const float *g_half, float *partials, int B, int N, int K, int *n_wg,
+                                   hipStream_t s);
+
 hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,
                                   int Dout, float *grad_theta, float *grad_bias, hipStream_t s);
 
@@ -94,6 +103,60 @@ int lean_producer_mode()
         return 2;
     }();
     return mode;
+}
+
+// 128 -> 128 point-major layers run as passes of the 64-wide lean kernels over channel blocks
+// (FLEX_SPLIT=0 in the environment keeps them on the single-pass fp32 kernels, for comparisons)
+static bool use_split_128(int Din, int Dout, int layout, int N, int K, int csr)
+{
+    static const bool off = [] { const char *v = getenv("FLEX_SPLIT"); return v != nullptr && v[0] == '0'; }();
+    return !off && Din == 128 && Dout == 128 && layout == FLEX_LAYOUT_BNC && split_ok_128_128(N, K, csr);
+}
+
+// Forward (transpose == 0: passes over the input-channel halves) or feature gradient (transpose == 1: passes over
+// the halves of the upstream gradient's channels) of a 128 -> 128 layer.  scratch: theta_ws_bytes(128, 128).
+static hipError_t split_gather_contract_128(const float *rows, const float *pos, const int32_t *nbr,
+                                            const int32_t *off, const int32_t *src, const float *theta,
+                                            const float *bias, void *scratch, float *out, int B, int N, int K,
+                                            int transpose, hipStream_t s)
+{
+    float *blk_theta = (float *)scratch, *blk_bias = blk_theta + 3 * 64 * 128;
+    void *packed = (char *)scratch + sizeof(float) * 4 * 64 * 128;
+    for (int h = 0; h < 2; ++h) {
+        hipError_t e;
+        if (!transpose) {
+            e = launch_param_block((float *)theta, (float *)bias, blk_theta, blk_bias, 128, 128, 64 * h, 0, 64, 128, 0, s);
+            if (e != hipSuccess) return e;
+            e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 64, 128, 64, 128, 0, s);
+        } else {
+            e = launch_param_block((float *)theta, (float *)bias, blk_theta, blk_bias, 128, 128, 0, 64 * h, 128, 64, 0, s);
+            if (e != hipSuccess) return e;
+            e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 128, 64, 64, 128, 1, s);
+        }
+        if (e != hipSuccess) return e;
+        e = launch_gc_split_128_128(rows + 64 * h, pos, nbr, off, src, packed, out, B, N, K, transpose, h, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Parameter gradients of a 128 -> 128 layer: four [4*64 x 64] blocks.  scratch: room for one block.
+static hipError_t split_grad_theta_128(const float *rows, const float *pos, const int32_t *nbr, const float *g_rows,
+                                       float *partials, void *scratch, float *grad_theta, float *grad_bias, int B,
+                                       int N, int K, hipStream_t s)
+{
+    float *blk_theta = (float *)scratch, *blk_bias = blk_theta + 3 * 64 * 64;
+    for (int hi = 0; hi < 2; ++hi)
+        for (int ho = 0; ho < 2; ++ho) {
+            int n_wg = 0;
+            hipError_t e = launch_gt_split_128_128(rows + 64 * hi, pos, nbr, g_rows + 64 * ho, partials, B, N, K, &n_wg, s);
+            if (e != hipSuccess) return e;
+            e = launch_reduce_partials(partials, n_wg, 64, 64, 64, 64, blk_theta, blk_bias, s);
+            if (e != hipSuccess) return e;
+            e = launch_param_block(grad_theta, grad_bias, blk_theta, blk_bias, 128, 128, 64 * hi, 64 * ho, 64, 64, 1, s);
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
 }
 
 // Packs (theta, bias) for launch_gather_contract in the format that kernel wants.
@@ -324,6 +387,10 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
         return FLEX_OK;
     }
     void *thetaP = ws + p.thetaP;
+    if (use_split_128(Din, Dout, layout, N, K, 0)) {
+        FLEX_HIP(split_gather_contract_128(feat, pos, nbr, nullptr, nullptr, theta, bias, thetaP, out, B, N, K, 0, s));
+        return FLEX_OK;
+    }
     const int fmt = gather_contract_theta_format(Din, Dout, N, K, 0);
     FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 0, fmt, s));
     const float *rows = feat;
@@ -380,8 +447,12 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
         }
     }
     if (grad_theta) {
-        FLEX_HIP(launch_grad_theta(rows, pos, nbr, g_rows, (float *)(ws + p.partials), grad_theta,
-                                   grad_bias, B, N, K, Din, Dout, s));
+        if (use_split_128(Din, Dout, layout, N, K, 0))
+            FLEX_HIP(split_grad_theta_128(rows, pos, nbr, g_rows, (float *)(ws + p.partials), ws + p.thetaP,
+                                          grad_theta, grad_bias, B, N, K, s));
+        else
+            FLEX_HIP(launch_grad_theta(rows, pos, nbr, g_rows, (float *)(ws + p.partials), grad_theta,
+                                       grad_bias, B, N, K, Din, Dout, s));
     }
     if (grad_feat) {
         if (build) {
@@ -391,6 +462,11 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
             in_src = src;
         }
         void *thetaP = ws + p.thetaP;
+        if (use_split_128(Din, Dout, layout, N, K, 1)) {
+            FLEX_HIP(split_gather_contract_128(g_rows, pos, nullptr, in_off, in_src, theta, bias, thetaP, grad_feat,
+                                               B, N, K, 1, s));
+            return FLEX_OK;
+        }
         const int fmt = gather_contract_theta_format(Dout, Din, N, K, 1);
         FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 1, fmt, s));
         FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, thetaP, fmt, grad_feat, B, N,

@@ -578,4 +578,29 @@ hipError_t launch_compose_1x1_bwd(const float *W, const float *theta, const floa
     return hipGetLastError();
 }
 
+// ---- blocks of the parameter tensors (layers run as passes over channel blocks) ----------
+// extract (insert == 0): blk_theta[j][r][c] = theta[j][r0 + r][c0 + c], blk_bias likewise;
+// insert  (insert == 1): the other way round.  theta [3,R,C], bias [R,C]; block [3,nr,nc], [nr,nc].
+__global__ __launch_bounds__(256) void param_block_kernel(float *__restrict__ theta, float *__restrict__ bias,
+                                                          float *__restrict__ blk_theta, float *__restrict__ blk_bias,
+                                                          int R, int C, int r0, int c0, int nr, int nc, int insert)
+{
+    const int total = 4 * nr * nc;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const int c = i % nc, r = (i / nc) % nr, j = i / (nc * nr);
+        float *big = (j < 3 ? theta + (int64_t)j * R * C : bias) + (int64_t)(r0 + r) * C + c0 + c;
+        float *small = (j < 3 ? blk_theta + (int64_t)j * nr * nc : blk_bias) + (int64_t)r * nc + c;
+        if (insert) *big = *small; else *small = *big;
+    }
+}
+
+hipError_t launch_param_block(float *theta, float *bias, float *blk_theta, float *blk_bias, int R, int C, int r0,
+                              int c0, int nr, int nc, int insert, hipStream_t s)
+{
+    const int total = 4 * nr * nc;
+    hipLaunchKernelGGL(param_block_kernel, dim3((total + 255) / 256), dim3(256), 0, s, theta, bias, blk_theta, blk_bias,
+                       R, C, r0, c0, nr, nc, insert);
+    return hipGetLastError();
+}
+
 }  // namespace flex

@@ -174,6 +174,58 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     return hipGetLastError();
 }
 
+#if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 128
+// 128 -> 128 layers as two passes of this shape's lean kernels: each gathers one 64-channel half of the
+// 128-wide rows (row stride 128) and contracts it with its [4*64 x 128] block of the parameters; the second
+// pass adds to the first one's output.  Point-major tensors only.
+bool split_ok_128_128(int N, int K, int csr)
+{
+    if (contract_in_fp32() || lean_producer_mode() == 0) return false;
+    if ((int64_t)N * 128 * 4 >= (1ll << 32) || (int64_t)N * 12 >= (1ll << 32)) return false;
+    return csr || ((K % 8 == 0) && (int64_t)K * N * 4 < (1ll << 32));
+}
+
+hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr, const int32_t *off,
+                                   const int32_t *src, const void *thetaP, float *out, int B, int N, int K, int csr,
+                                   int accumulate, hipStream_t s)
+{
+    using W = WsGeom<S, 1>;
+    const int tpc = (N + W::T - 1) / W::T;
+    const int64_t tot64 = (int64_t)B * tpc;
+    if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int tot = (int)tot64;
+    const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
+    const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
+    if (!csr) {
+        if (accumulate) hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, 1, 128, 128, true>), g, blk, 0, s, rows_half, pos, nbr, thetaP, exp_off, out, N, K, tpc, tot);
+        else hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, 1, 128, 128, false>), g, blk, 0, s, rows_half, pos, nbr, thetaP, exp_off, out, N, K, tpc, tot);
+    } else {
+        if (accumulate) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1, 128, 128, true>), g, blk, 0, s, rows_half, pos, off, src, thetaP, exp_off, out, N, tpc, tot);
+        else hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1, 128, 128, false>), g, blk, 0, s, rows_half, pos, off, src, thetaP, exp_off, out, N, tpc, tot);
+    }
+    return hipGetLastError();
+}
+#endif
+
+#if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 64
+// One [4*64 x 64] block of the parameter gradient of a 128 -> 128 layer: the aggregate of a 64-channel half of
+// the 128-wide feature rows against a 64-channel half of the 128-wide upstream gradient rows.
+hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr,
+                                   const float *g_half, float *partials, int B, int N, int K, int *n_wg,
+                                   hipStream_t s)
+{
+    using WL = WsGeom<S, 2, 2>;
+    const int tpc = (N + WL::T - 1) / WL::T;
+    const int64_t tot64 = (int64_t)B * tpc;
+    if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int tot = (int)tot64;
+    *n_wg = persistent_grid(tot, 1);
+    hipLaunchKernelGGL((grad_theta_lean_kernel<S, 128, 128>), dim3(*n_wg), dim3(WL::NT), 0, s, rows_half, pos, nbr,
+                       g_half, partials, N, K, tpc, tot);
+    return hipGetLastError();
+}
+#endif
+
 // One term of the location gradient; false / hipErrorNotSupported when this shape has no kernel for it.
 bool FLEX_NAME(gp_ok, FLEX_DI, FLEX_DO)(int N, int K)
 {

@@ -509,7 +509,8 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 // ---------------------------------------------------------------------------
 // SUM == true: only the plain neighbour sum (component j = 3 of the aggregate) is formed; no positions
 // are read (used by the location-gradient kernels).
-template <class S, int PM, bool SUM = false>
+// RS = floats between consecutive rows of the gathered tensor (S::DI unless the rows are a column block of a wider one)
+template <class S, int PM, bool SUM = false, int RS = S::DI>
 struct LeanProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
@@ -606,7 +607,7 @@ struct LeanProducer {
 
     __device__ __forceinline__ void load_row(float (&fr)[S::VEC], int id, const char *rb) const
     {
-        const char *p = rb + ((unsigned)id * (4u * S::DI) + lane_off);
+        const char *p = rb + ((unsigned)id * (4u * RS) + lane_off);
         if constexpr (S::VEC == 4) {
             const v4f v = *reinterpret_cast<const v4f *>(p);
             fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
@@ -650,7 +651,7 @@ struct LeanProducer {
             // end of every iteration: the wait at the loop top (for positions and ids) is one instruction
             // for both ways in, and a load issued after the rows would turn it into a wait for the rows.
             __builtin_amdgcn_sched_barrier(0);
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * S::DI);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * RS);
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
             __builtin_amdgcn_sched_barrier(0);
@@ -674,7 +675,7 @@ struct LeanProducer {
             advance(walk);
             const Batch x2 = get(walk);
             load_ids(idn, x2);
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * S::DI);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * RS);
             const int nb = x1.b, nlw0 = x1.lw0;
             x1 = x2;
             float dpc[U];
@@ -727,7 +728,7 @@ struct LeanProducer {
 // Slots past a list's end gather the point's own row with dp = (0,0,0,0), i.e. add nothing.
 // The list bounds of the next tile are requested when a wave's id cursor enters a tile.
 // ---------------------------------------------------------------------------
-template <class S, int PM, bool SUM = false>
+template <class S, int PM, bool SUM = false, int RS = S::DI>
 struct LeanCsrProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
@@ -844,7 +845,7 @@ struct LeanCsrProducer {
     }
     __device__ __forceinline__ void load_row(float (&fr)[S::VEC], int id, const char *rb) const
     {
-        const char *p = rb + ((unsigned)id * (4u * S::DI) + lane_off);
+        const char *p = rb + ((unsigned)id * (4u * RS) + lane_off);
         if constexpr (S::VEC == 4) {
             const v4f v = *reinterpret_cast<const v4f *>(p);
             fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
@@ -882,7 +883,7 @@ struct LeanCsrProducer {
             pn[0] = pn[1] = pc = 0.f;
             if constexpr (!SUM) load_pos(pn, pc, id0, d0);
             __builtin_amdgcn_sched_barrier(0);      // rows youngest, as at the end of every iteration
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * S::DI);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * RS);
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
             __builtin_amdgcn_sched_barrier(0);
@@ -901,7 +902,7 @@ struct LeanCsrProducer {
 #pragma unroll
             for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
             if constexpr (!SUM) load_pos(pn, pc, idn, d1);
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * S::DI);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * RS);
             d0 = d1;
             fetch(c, idn, d1);
             float dpc[U];
@@ -947,7 +948,8 @@ struct LeanCsrProducer {
 
 // One consumer wave of the split-half contraction: out tile = A tile * Theta for every tile of
 // the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
-template <class S, class G, bool OUT_BCN>
+// OS = floats between consecutive output rows (point-major form), ACC: add to what out holds.
+template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false>
 __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ thetaP, int theta_exp_off,
                                              float *__restrict__ out, int N, const TileSchedule &sc,
                                              int tiles_per_cloud, const char *s_A, const int *s_E)
@@ -971,9 +973,12 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
                 for (int i = 0; i < 4; ++i)
                     if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
             } else {
-                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * S::DO + o;
+                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * OS + o;
                 if constexpr (S::DO % 4 == 0) {
-                    if (o < S::DO) *reinterpret_cast<v4f *>(dst) = d;
+                    if (o < S::DO) {
+                        if constexpr (ACC) d += *reinterpret_cast<const v4f *>(dst);
+                        *reinterpret_cast<v4f *>(dst) = d;
+                    }
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
@@ -1044,7 +1049,7 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
 // counts is how many rows the CU has in flight; the f16 contraction is cheap enough for a
 // quarter of the waves.
 // ---------------------------------------------------------------------------
-template <class S, bool OUT_BCN, int PM>
+template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                                  const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
@@ -1070,7 +1075,7 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
     }
 
     if (w < G::NP) {
-        LeanProducer<S, PM> P;
+        LeanProducer<S, PM, false, RS> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
@@ -1079,11 +1084,11 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
         });
         return;
     }
-    consumer_f16<S, G, OUT_BCN>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
+    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
 }
 
 // Feature gradient with the lean in-edge producers (same consumers as the forward kernel).
-template <class S, bool OUT_BCN, int PM>
+template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                            const int32_t *__restrict__ off, const int32_t *__restrict__ src,
@@ -1107,7 +1112,7 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
     }
 
     if (w < G::NP) {
-        LeanCsrProducer<S, PM> P;
+        LeanCsrProducer<S, PM, false, RS> P;
         P.init(rows, pos, off, src, N, w, sc, tiles_per_cloud);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
@@ -1116,7 +1121,7 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
         });
         return;
     }
-    consumer_f16<S, G, OUT_BCN>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
+    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
 }
 
 template <class S, bool CSR, bool OUT_BCN, bool F16>
@@ -1394,7 +1399,8 @@ __device__ __forceinline__ bf8 read_tr_frag(const char *tile, int stride, int p0
     return __builtin_bit_cast(bf8, v);
 }
 
-template <class S>
+// RS / GST = floats between consecutive rows of the gathered tensor / of the upstream gradient
+template <class S, int RS = S::DI, int GST = S::DO>
 __global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                             const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
@@ -1410,7 +1416,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
     const TileSchedule sc(total_tiles);
 
     if (w < G::NP) {
-        LeanProducer<S, 2> P;
+        LeanProducer<S, 2, false, RS> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         // grad_out tile: T*DOP/4 four-float chunks over the producer threads, one tile ahead in registers
         constexpr int CPR = S::DOP / 4;                      // chunks per point
@@ -1424,7 +1430,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
                 const int pt = ch / CPR, o = 4 * (ch % CPR);
                 gv[c] = v4f{0.f, 0.f, 0.f, 0.f};
                 if (ch < G::T * CPR && l0 + pt < N) {        // points past the cloud contribute nothing
-                    const float *src = g_rows + ((int64_t)b * N + l0 + pt) * S::DO + o;
+                    const float *src = g_rows + ((int64_t)b * N + l0 + pt) * GST + o;
                     if constexpr (S::DO % 4 == 0) {
                         if (o < S::DO) gv[c] = *reinterpret_cast<const v4f *>(src);
                     } else {
