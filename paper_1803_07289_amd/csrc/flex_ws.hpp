@@ -775,6 +775,7 @@ struct LeanCsrProducer {
         int b, lw0;      // cloud, first point of this wave in the tile
         bool last;       // last batch of its tile: the aggregate is complete after it
         bool real;       // false past the workgroup's last tile (loaded, never used)
+        bool upper;      // some point of the wave has an entry in slots 4..7 of this batch (else those rows are skipped)
         int valid0, valid1;   // entry layout: does this lane's entry (half 0 / 1) exist
     };
 
@@ -782,6 +783,7 @@ struct LeanCsrProducer {
     struct Cursor {
         int i, bi, nb;           // tile (index into the workgroup's tiles), batch in tile, batches of the tile
         int b, lw0;
+        int dmax;                // longest list among the wave's four points
         int lo, deg;             // this lane's point: start and length of its list
         int lo_n, hi_n;          // next tile: list bounds of this lane's point (in flight)
         TileWalk tw;             // the tile those bounds belong to (the last tile again past the end)
@@ -813,6 +815,7 @@ struct LeanCsrProducer {
         const int d = max(max(__builtin_amdgcn_readlane(c.deg, 0), __builtin_amdgcn_readlane(c.deg, 4)),
                           max(__builtin_amdgcn_readlane(c.deg, 8), __builtin_amdgcn_readlane(c.deg, 12)));
         c.nb = max(1, (d + U - 1) / U);
+        c.dmax = d;
         c.tw.next_clamped();
         request_bounds(c);
     }
@@ -822,6 +825,7 @@ struct LeanCsrProducer {
         d.b = c.b; d.lw0 = c.lw0;
         d.real = c.i < count;
         d.last = c.bi == c.nb - 1;
+        d.upper = U * c.bi + 4 < c.dmax;
         const int s0 = U * c.bi + e_k, s1 = s0 + 4;
         d.valid0 = d.real && s0 < c.deg;
         d.valid1 = d.real && s1 < c.deg;
@@ -885,7 +889,8 @@ struct LeanCsrProducer {
             __builtin_amdgcn_sched_barrier(0);      // rows youngest, as at the end of every iteration
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * RS);
 #pragma unroll
-            for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
+            for (int u = 0; u < U; ++u)
+                if (u < 4 || d0.upper) load_row(f[u], spread(id0, perm_id, u), rb);
             __builtin_amdgcn_sched_barrier(0);
         }
         int tile_i = 0;
@@ -897,6 +902,7 @@ struct LeanCsrProducer {
             int dpe[2];
             dp_entries(dpe, pn, pc, d0);
             const bool last = d0.last;
+            const bool cur_upper = d0.upper, next_upper = d1.upper;   // slots 4..7: accumulate / request them at all?
             // batch d1: positions and (below) rows go in flight; the cursor's batch: ids
             int idc[U];
 #pragma unroll
@@ -911,24 +917,26 @@ struct LeanCsrProducer {
 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                float fv[S::VEC];
+                if (u < 4 || cur_upper) {
+                    float fv[S::VEC];
 #pragma unroll
-                for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                if constexpr (SUM) {
+                    for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
+                    if constexpr (SUM) {
 #pragma unroll
-                    for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(dpc[u], fv[v], acc[v][3]);
-                } else {
-                    const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
-                    const float one = dpp_move<0xFF>(dpc[u]);    // 1 for a real entry, 0 for a missing one
+                        for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(dpc[u], fv[v], acc[v][3]);
+                    } else {
+                        const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
+                        const float one = dpp_move<0xFF>(dpc[u]);    // 1 for a real entry, 0 for a missing one
 #pragma unroll
-                    for (int v = 0; v < S::VEC; ++v) {
-                        acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
-                        acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
-                        acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
-                        acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                        for (int v = 0; v < S::VEC; ++v) {
+                            acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                            acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                            acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                            acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                        }
                     }
                 }
-                load_row(f[u], idc[u], rb);
+                if (u < 4 || next_upper) load_row(f[u], idc[u], rb);
                 // keep the loop's shape: the scheduler would otherwise collect the eight loads at the end
                 // of the iteration and wait for all of them at its start (no row would be in flight
                 // while the previous ones are accumulated)
