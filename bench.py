@@ -45,6 +45,8 @@ def main():
                     help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; upsample = flex-upsampling from a "
                          "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
                          "quarter of the points; none of them is part of the default step)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step into a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the feature tensor (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against them")
@@ -274,6 +276,27 @@ def main():
                         "kind": "oracle", "sample": f"centre points [0,{n_slice}) of each cloud of the same "
                         f"workload, all four ops, {t_slice:.1f}s", "os_cpu_count": os.cpu_count()}
 
+    graph_ms = None
+    if args.graph:
+        # the entry points only enqueue kernels, so a step can be captured whole; replays skip the launch path
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            step()
+        for _ in range(args.warmup):
+            gr.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
     direct_flop_pt = 8 * K * Din * Dout
     result = {
         "metric": "flex-conv fwd+bwd (+ flex-max-pool fwd+bwd) points/sec at N=7M,K=8",
@@ -296,6 +319,7 @@ def main():
         "rooflines_all": rooflines,
         "op_ms": op_ms,
         "inedges_build_ms": inedges_ms,
+        "graph_ms_per_step": graph_ms,
         "fwd_points_per_s": pts / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
         "fwd_effective_GFLOPs_direct_form": direct_flop_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else None,
         "fwd_bwd_points_per_s": pts / ((fwd_ms + bwd_ms) * 1e-3) if fwd_ms > 0 and bwd_ms > 0 else None,

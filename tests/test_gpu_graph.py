@@ -1,0 +1,52 @@
+"""The entry points enqueue kernels only (no allocation, no synchronisation, no memset nodes), so a whole
+layer step can be captured into a HIP graph and replayed.  Every replay is checked against the eager result,
+with eager work and synchronisations between replays."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1803_07289_amd as fx
+from gpu_util import dev, to_layout, say
+from workloads import CONFIGS, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cfg_i,n", [(1, None), (0, 3000)])
+def test_layer_step_replays_from_a_graph(cfg_i, n):
+    cfg = CONFIGS[cfg_i]
+    x = make_inputs(cfg, n_override=n)
+    say(f"graph capture {x.cfg.name} N={x.cfg.N}")
+    L = fx.BNC
+    feat, g = to_layout(x.feat, L), to_layout(x.grad_out, L)
+    pos, nbr, theta, bias = dev(x.pos), dev(x.nbr), dev(x.theta), dev(x.bias)
+    edges = fx.flex_inedges_build(nbr)
+    gpool = torch.randn_like(feat)
+
+    def step():
+        out = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=L)
+        gf, gt, gb = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=L, in_edges=edges)
+        po, pa = fx.flexpool_fwd(feat, nbr, layout=L)
+        pg = fx.flexpool_bwd(gpool, pa, layout=L, in_edges=edges)
+        return out, gf, gt, gb, po, pa, pg
+
+    eager = [t.clone() for t in step()]            # also sizes the cached workspaces before capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        captured = step()
+    for r in range(3):
+        for t in captured:
+            t.fill_(7) if t.dtype == torch.int32 else t.fill_(float("nan"))     # stale results must be overwritten
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(captured, eager):
+            assert torch.equal(a, b), f"replay {r}"
+        _ = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=L)            # eager work between the replays
+        torch.cuda.synchronize()
