@@ -3,6 +3,7 @@
 // pass gathers whole point-major rows (16 bytes per lane), the backward pass
 // scatters by the recorded index with fp32 atomic adds.
 #include "flex_common.hpp"
+#include <type_traits>
 
 namespace flex {
 
@@ -50,25 +51,29 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
         const v4f *rows = reinterpret_cast<const v4f *>(feat) + (int64_t)b * N * C4 + c4;
         float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
         int b0 = 0, b1 = 0, b2 = 0, b3 = 0;
-        for (int k0 = 0; k0 < K; k0 += U) {
-            int n[U];
-            v4f v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) n[u] = nb[(int64_t)min(k0 + u, K - 1) * N];   // past K: the last slot again
-#pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = rows[(int64_t)n[u] * C4];
-            if (k0 == 0) {
-                v0 = v[0].x; v1 = v[0].y; v2 = v[0].z; v3 = v[0].w;
-                b0 = b1 = b2 = b3 = n[0];
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {      // a repeated (value, index) pair never changes the winner
-                take(v[u].x, n[u], v0, b0);
-                take(v[u].y, n[u], v1, b1);
-                take(v[u].z, n[u], v2, b2);
-                take(v[u].w, n[u], v3, b3);
-            }
+        // slots k0 .. k0+W-1: ids, then rows, then the comparisons
+#define FLEX_POOL_SLOTS(W)                                                                                 \
+        {                                                                                                  \
+            int n[W];                                                                                      \
+            v4f v[W];                                                                                      \
+            _Pragma("unroll") for (int u = 0; u < W; ++u)                                                  \
+                n[u] = nb[(int64_t)min(k0 + u, K - 1) * N]; /* past K: the last slot again */              \
+            _Pragma("unroll") for (int u = 0; u < W; ++u) v[u] = rows[(int64_t)n[u] * C4];                 \
+            if (k0 == 0) {                                                                                 \
+                v0 = v[0].x; v1 = v[0].y; v2 = v[0].z; v3 = v[0].w;                                        \
+                b0 = b1 = b2 = b3 = n[0];                                                                  \
+            }                                                                                              \
+            _Pragma("unroll") for (int u = 0; u < W; ++u) { /* a repeated pair never changes the winner */ \
+                take(v[u].x, n[u], v0, b0);                                                                \
+                take(v[u].y, n[u], v1, b1);                                                                \
+                take(v[u].z, n[u], v2, b2);                                                                \
+                take(v[u].w, n[u], v3, b3);                                                                \
+            }                                                                                              \
         }
+        int k0 = 0;
+        for (; k0 + 4 < K; k0 += U) FLEX_POOL_SLOTS(U)
+        if (k0 < K) FLEX_POOL_SLOTS(4)      // a tail of up to four slots
+#undef FLEX_POOL_SLOTS
         const v4f bv = {v0, v1, v2, v3};
         reinterpret_cast<v4f *>(out)[gp * C4 + c4] = bv;
         reinterpret_cast<int4 *>(argmax)[gp * C4 + c4] = make_int4(b0, b1, b2, b3);

@@ -19,10 +19,11 @@ static constexpr int WG_PER_CU = (FLEX_OCC * 4) / FLEX_W > 0 ? (FLEX_OCC * 4) / 
 
 // 1 if this (shape, K, list form) runs the wave-specialised kernel with the split-half
 // contraction, i.e. wants the parameters from launch_pack_theta_f16; 0: fp32 ThetaP.
-// the lean fixed-K producers take this neighbour tensor: whole batches of 8, 32-bit byte offsets in a cloud
+// the lean fixed-K producers take this neighbour tensor: 32-bit byte offsets in a cloud (any K: batches of 8
+// slots, the last one of a tile masked past K)
 static bool lean_fixed_ok(int N, int K)
 {
-    return lean_producer_mode() != 0 && (K % 8 == 0) && (int64_t)K * N * 4 < (1ll << 32) &&
+    return lean_producer_mode() != 0 && (int64_t)K * N * 4 < (1ll << 32) &&
            (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32);
 }
 
@@ -61,7 +62,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
         if (theta_fmt) hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, true>), g, blk, 0, s, FLEX_WS_ARGS); \
         else hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, false>), g, blk, 0, s, FLEX_WS_ARGS);          \
     } while (0)
-            // lean producer: fixed-K tensor, K in whole batches of 8, 32-bit byte offsets inside a cloud
+            // lean producer: fixed-K tensor, 32-bit byte offsets inside a cloud
             const bool lean = !csr && theta_fmt && lean_fixed_ok(N, K);
             if (lean) {
                 // 3 producer waves per consumer wave where 16 waves hold them and the items divide evenly
@@ -74,10 +75,16 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
                 const int totl = B * tpcl;
                 const dim3 gl(persistent_grid(totl, wide ? WL::WG_PER_CU : W::WG_PER_CU)), bl(wide ? WL::NT : W::NT);
 #define FLEX_LEAN_ARGS rows, pos, nbr, thetaP, exp_off, out, N, K, tpcl, totl
-                if (wide && !out_bcn) hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
-                else if (wide) hipLaunchKernelGGL((gather_contract_lean_kernel<S, true, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
-                else if (!out_bcn) hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
-                else hipLaunchKernelGGL((gather_contract_lean_kernel<S, true, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
+#define FLEX_LEAN_LAUNCH(BCN_, PM_)                                                                              \
+    do {                                                                                                         \
+        if (K % 8 == 0) hipLaunchKernelGGL((gather_contract_lean_kernel<S, BCN_, PM_>), gl, bl, 0, s, FLEX_LEAN_ARGS); \
+        else hipLaunchKernelGGL((gather_contract_lean_kernel<S, BCN_, PM_, S::DI, S::DO, false, true>), gl, bl, 0, s, FLEX_LEAN_ARGS); \
+    } while (0)
+                if (wide && !out_bcn) FLEX_LEAN_LAUNCH(false, PMX);
+                else if (wide) FLEX_LEAN_LAUNCH(true, PMX);
+                else if (!out_bcn) FLEX_LEAN_LAUNCH(false, 1);
+                else FLEX_LEAN_LAUNCH(true, 1);
+#undef FLEX_LEAN_LAUNCH
 #undef FLEX_LEAN_ARGS
                 return hipGetLastError();
             }
@@ -145,13 +152,16 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     *n_wg = grid;
 #if FLEX_WS
     if constexpr (S::WAVES == 4 && S::T == 16) {
-        // lean producers + bf16 matrix cores: fixed-K tensor in whole batches of 8, 32-bit offsets in a cloud
+        // lean producers + bf16 matrix cores: fixed-K tensor, 32-bit offsets in a cloud
         using WL = WsGeom<S, 2, 2>;
         if (!contract_in_fp32() && lean_fixed_ok(N, K)) {
             const int tpc = (N + WL::T - 1) / WL::T;
             const int tot = B * tpc;
             *n_wg = persistent_grid(tot, 1);
-            hipLaunchKernelGGL((grad_theta_lean_kernel<S>), dim3(*n_wg), dim3(WL::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
+            if (K % 8 == 0)
+                hipLaunchKernelGGL((grad_theta_lean_kernel<S>), dim3(*n_wg), dim3(WL::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
+            else
+                hipLaunchKernelGGL((grad_theta_lean_kernel<S, S::DI, S::DO, true>), dim3(*n_wg), dim3(WL::NT), 0, s, rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
             return hipGetLastError();
         }
     }
@@ -231,7 +241,7 @@ bool FLEX_NAME(gp_ok, FLEX_DI, FLEX_DO)(int N, int K)
 {
 #if FLEX_WS
     if constexpr (S::WAVES == 4 && S::T == 16 && PosGeom<S>::FITS)
-        return !contract_in_fp32() && lean_fixed_ok(N, K);
+        return !contract_in_fp32() && (K % 8 == 0) && lean_fixed_ok(N, K);    // the plain-sum producers take whole batches
 #endif
     (void)N; (void)K;
     return false;

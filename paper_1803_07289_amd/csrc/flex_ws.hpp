@@ -510,12 +510,15 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 // SUM == true: only the plain neighbour sum (component j = 3 of the aggregate) is formed; no positions
 // are read (used by the location-gradient kernels).
 // RS = floats between consecutive rows of the gathered tensor (S::DI unless the rows are a column block of a wider one)
-template <class S, int PM, bool SUM = false, int RS = S::DI>
+// TAIL: K is not a multiple of 8; the last batch of a tile has slots past K, which are read from slot K-1 and
+// weighted 0 (the weight travels as the fourth position component), and its rows 4..7 are skipped when empty.
+template <class S, int PM, bool SUM = false, int RS = S::DI, bool TAIL = false>
 struct LeanProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
     static constexpr bool FULL = (S::LPR * S::VEC == S::DI);   // every lane of a group reads real channels
     static_assert(G::PW == 4, "entry layout below: 4 points x 8 neighbours per batch");
+    static_assert(!(SUM && TAIL), "the plain-sum mode takes whole batches only");
     // The aggregate runs on the vector ALU: the fp32 4x4x1 matrix op would need fewer issue slots, but
     // it holds both the vector ALU and the f16/bf16 matrix pipe of the SIMD while it executes, so the
     // consumers' matrix ops could never overlap the producers' work.
@@ -540,7 +543,7 @@ struct LeanProducer {
     __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *nbr_, int N_,
                                          int K_, int pw_, const TileSchedule &sc, int tiles_per_cloud_)
     {
-        rows = rows_; pos = pos_; nbr = nbr_; N = N_; K = K_; KB = K_ / U; pw = pw_;
+        rows = rows_; pos = pos_; nbr = nbr_; N = N_; K = K_; KB = (K_ + U - 1) / U; pw = pw_;
         const int lane = threadIdx.x & 63;
         grp = lane / S::LPR; t = lane % S::LPR;
         lane_on = (S::VEC * t) < S::DI;
@@ -586,9 +589,15 @@ struct LeanProducer {
     {
         const char *base = reinterpret_cast<const char *>(nbr + (int64_t)x.b * K * N);
         const unsigned l = (unsigned)min(x.lw0 + e_g, N - 1);
-        const unsigned o = 4u * ((unsigned)(x.k0 + e_k) * (unsigned)N + l);
-        id[0] = *reinterpret_cast<const int32_t *>(base + o);
-        id[1] = *reinterpret_cast<const int32_t *>(base + (o + 16u * (unsigned)N));
+        if constexpr (TAIL) {
+            const unsigned s0 = (unsigned)min(x.k0 + e_k, K - 1), s1 = (unsigned)min(x.k0 + e_k + 4, K - 1);
+            id[0] = *reinterpret_cast<const int32_t *>(base + 4u * (s0 * (unsigned)N + l));
+            id[1] = *reinterpret_cast<const int32_t *>(base + 4u * (s1 * (unsigned)N + l));
+        } else {
+            const unsigned o = 4u * ((unsigned)(x.k0 + e_k) * (unsigned)N + l);
+            id[0] = *reinterpret_cast<const int32_t *>(base + o);
+            id[1] = *reinterpret_cast<const int32_t *>(base + (o + 16u * (unsigned)N));
+        }
     }
     // entry layout: position component of the neighbours (both halves) and of the centre
     __device__ __forceinline__ void load_pos(float (&pn)[2], float &pc, const int (&id)[2], const Batch &x) const
@@ -653,11 +662,13 @@ struct LeanProducer {
             __builtin_amdgcn_sched_barrier(0);
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * RS);
 #pragma unroll
-            for (int u = 0; u < U; ++u) load_row(f[u], spread(id0, perm_id, u), rb);
+            for (int u = 0; u < U; ++u)
+                if (!TAIL || u < 4 || x0.k0 + 4 < K) load_row(f[u], spread(id0, perm_id, u), rb);
             __builtin_amdgcn_sched_barrier(0);
         }
         const int total = count * KB;
         int kb = 0, tile_i = 0;
+        int k0_cur = 0;          // first slot of the batch being accumulated
         v4f acc[S::VEC];
 #pragma unroll
         for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -667,6 +678,12 @@ struct LeanProducer {
             int dpe[2];
             dpe[0] = __float_as_int(fmaf(pn[0] - pc, e_mul, e_fix));
             dpe[1] = __float_as_int(fmaf(pn[1] - pc, e_mul, e_fix));
+            if constexpr (TAIL) {                    // slots past K weigh nothing
+                if (k0_cur + e_k >= K) dpe[0] = 0;
+                if (k0_cur + e_k + 4 >= K) dpe[1] = 0;
+            }
+            const bool cur_upper = !TAIL || k0_cur + 4 < K, next_upper = !TAIL || x1.k0 + 4 < K;
+            k0_cur = x1.k0;
             // ids of batch m+1 are here: their positions and (below) rows go in flight; ids of batch m+2 too
             int idc[U];
 #pragma unroll
@@ -684,26 +701,30 @@ struct LeanProducer {
 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                float fv[S::VEC];
+                if (!TAIL || u < 4 || cur_upper) {
+                    float fv[S::VEC];
 #pragma unroll
-                for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                if constexpr (SUM) {
+                    for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
+                    if constexpr (SUM) {
 #pragma unroll
-                    for (int v = 0; v < S::VEC; ++v) acc[v][3] += fv[v];
-                } else if constexpr (VALU_AGG) {
-                    // the four lanes of a block hold (dx, dy, dz, 1): broadcast inside the quad
-                    const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
+                        for (int v = 0; v < S::VEC; ++v) acc[v][3] += fv[v];
+                    } else if constexpr (VALU_AGG) {
+                        // the four lanes of a block hold (dx, dy, dz, 1): broadcast inside the quad
+                        const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
+                        const float one = TAIL ? dpp_move<0xFF>(dpc[u]) : 1.f;     // 0 for a slot past K
 #pragma unroll
-                    for (int v = 0; v < S::VEC; ++v) {
-                        acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
-                        acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
-                        acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
-                        acc[v][3] += fv[v];
+                        for (int v = 0; v < S::VEC; ++v) {
+                            acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                            acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                            acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                            if constexpr (TAIL) acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                            else acc[v][3] += fv[v];
+                        }
+                    } else {
+                        fma_row<S>(acc, dpc[u], fv);
                     }
-                } else {
-                    fma_row<S>(acc, dpc[u], fv);
                 }
-                load_row(f[u], idc[u], rb);     // row u of batch m+1 takes the freed registers
+                if (!TAIL || u < 4 || next_upper) load_row(f[u], idc[u], rb);     // row u of batch m+1 takes the freed registers
                 __builtin_amdgcn_sched_barrier(0);   // keep this shape: one row consumed, one requested
             }
 
@@ -1057,7 +1078,7 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
 // counts is how many rows the CU has in flight; the f16 contraction is cheap enough for a
 // quarter of the waves.
 // ---------------------------------------------------------------------------
-template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
+template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false, bool TAIL = false>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                                  const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
@@ -1083,7 +1104,7 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
     }
 
     if (w < G::NP) {
-        LeanProducer<S, PM, false, RS> P;
+        LeanProducer<S, PM, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
@@ -1408,7 +1429,7 @@ __device__ __forceinline__ bf8 read_tr_frag(const char *tile, int stride, int p0
 }
 
 // RS / GST = floats between consecutive rows of the gathered tensor / of the upstream gradient
-template <class S, int RS = S::DI, int GST = S::DO>
+template <class S, int RS = S::DI, int GST = S::DO, bool TAIL = false>
 __global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                             const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
@@ -1424,7 +1445,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
     const TileSchedule sc(total_tiles);
 
     if (w < G::NP) {
-        LeanProducer<S, 2, false, RS> P;
+        LeanProducer<S, 2, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         // grad_out tile: T*DOP/4 four-float chunks over the producer threads, one tile ahead in registers
         constexpr int CPR = S::DOP / 4;                      // chunks per point
