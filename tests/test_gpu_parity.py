@@ -46,6 +46,10 @@ SHAPES = [
     (3, 17, 8, 64, 64),        # three clouds, each a single ragged tile
     (1, 48, 16, 64, 64),       # exactly one tile of the widest kernel, two batches
     (2, 49, 8, 32, 32),        # one point past a tile
+    (1, 700, 9, 64, 64),       # the paper's profiling K: second batch of every tile masked past K, upper half skipped
+    (2, 333, 12, 64, 64),      # masked tail batch whose lower half is full
+    (1, 250, 20, 32, 64),      # three batches, the last one half empty
+    (1, 500, 13, 9, 64),       # masked tail, single-float lanes
     (2, 150, 6, 5, 7),         # no tiled kernel: generic path
     (1, 90, 4, 20, 16),        # generic path, Din % 4 == 0
 ]
