@@ -4,7 +4,7 @@
 One step = flexconv_fwd + flexconv_bwd + flexpool_fwd + flexpool_bwd over the
 7M-point hall workload (config 4: B=1, N=7,000,000, K=8, Din=Dout=64, fp32),
 inputs resident in HBM, neighbourhoods (and their transposed lists) static.
-Prints ONE JSON line; see the design doc for how each figure is defined.
+Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--n N] [--layout bnc|bcn]
 """
@@ -180,7 +180,7 @@ def main():
         op_ms[name] = {"mean": float(np.mean(ts)), "min": float(np.min(ts)), "median": float(np.median(ts))}
     pts = B * N
 
-    # ---- rooflines (algorithmic, touched-once figures) ----------
+    # ---- rooflines (algorithmic figures: every array touched once) ----------
     # Every kernel of the path is bound by HBM: the contractions run on the f16 / bf16 matrix cores in
     # split form (3 resp. 6 matrix ops per fp32-equivalent product), whose time at the published dense
     # peak (2.5 PFLOP/s) stays below the time the touched-once bytes need at 8 TB/s.
