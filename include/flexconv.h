@@ -250,6 +250,18 @@ int flex_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, 
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Repeats removed from an ascending selection, in place (for callers that cannot use a point
+ * twice: flexupsample_*, flex_inedges_build_sub with the list form of flexpool_sub_bwd).  The
+ * draw is kept and every repeated entry moves to the next free index:
+ *   sel[j] = max(sel[j], sel[j-1] + 1) for j = 1 .. Ns-1, then sel[j] = min(sel[j], N - Ns + j)
+ * (the second step packs the tail against the end of the cloud should the first run past it).
+ * sel int32 [B,Ns], ascending per cloud, entries in [0,N).  Workspace: at least
+ * flexconv_workspace_bytes(FLEX_OP_IDISS, B, N, ...) (far less is used).
+ */
+int flex_selection_make_distinct(int32_t *sel, int B, int N, int Ns,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Flex-upsampling forward (Sec. 4.1): the features of the smaller layer's points are copied
  * to their points in the larger layer, every other point of the larger layer starts at zero,
  * and flex-max-pooling runs over the larger layer's neighbourhoods:

@@ -276,3 +276,11 @@ def knn(pos, K):
     nbr = np.zeros((B, int(K), N), np.int32)
     _check(_load().oracle_knn(_p(pos), _p(nbr), B, N, int(K)), "oracle_knn")
     return nbr
+
+
+def selection_make_distinct(sel, N):
+    """Ascending selection int32 [B,Ns] with repeats -> distinct ascending (repeats moved to the next free index)."""
+    out = np.array(sel, dtype=np.int32, order="C", copy=True)
+    B, Ns = out.shape
+    _check(_load().oracle_selection_make_distinct(_p(out), B, int(N), Ns), "oracle_selection_make_distinct")
+    return out

@@ -753,3 +753,31 @@ int oracle_knn(const float *pos, int32_t *nbr, int B, int N, int K)
         }
     return rc;
 }
+
+/* ---------------------------------------------------------------------------
+ * Repeats removed from an ascending selection (the stratified draw above returns a point
+ * once per threshold it spans; the layers that copy features between resolutions need
+ * distinct points).  The paper does not say how its sampling treats repeats; the reading
+ * taken keeps the draw and moves every repeated entry to the next free index:
+ *   walking j = 1 .. Ns-1:  if sel[j] <= sel[j-1] then sel[j] = sel[j-1] + 1
+ * and, should that run past the end of the cloud, the tail is packed against it:
+ *   walking j = Ns-1 .. 0:  sel[j] = min(sel[j], N - Ns + j).
+ * In place, int32 [B,Ns]; input must be ascending with entries in [0,N).
+ * ------------------------------------------------------------------------- */
+int oracle_selection_make_distinct(int32_t *sel, int B, int N, int Ns)
+{
+    if (!sel) return 1;
+    if (B <= 0 || N <= 0 || Ns <= 0 || Ns > N) return 2;
+    for (int b = 0; b < B; ++b) {
+        int32_t *s = sel + (int64_t)b * Ns;
+        for (int j = 0; j < Ns; ++j) {
+            if (s[j] < 0 || s[j] >= N) return 2;
+            if (j > 0 && s[j] < s[j - 1]) return 2;              /* ascending input required */
+        }
+        for (int j = 1; j < Ns; ++j)
+            if (s[j] <= s[j - 1]) s[j] = s[j - 1] + 1;
+        for (int j = Ns - 1; j >= 0; --j)
+            if (s[j] > N - Ns + j) s[j] = N - Ns + j;
+    }
+    return 0;
+}

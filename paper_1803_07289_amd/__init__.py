@@ -35,6 +35,7 @@ _SIGS = {
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexconv_compose_1x1": (_i, [_vp] * 5 + [_i] * 3 + [_vp]),
     "flexconv_compose_1x1_bwd": (_i, [_vp] * 8 + [_i] * 3 + [_vp]),
+    "flex_selection_make_distinct": (_i, [_vp, _i, _i, _i, _vp, _sz, _vp]),
     "flex_knn": (_i, [_vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
     "flex_idiss_phi": (_i, [_vp] * 3 + [_i] * 3 + [_vp]),
     "flex_idiss_sample": (_i, [_vp] * 3 + [_i] * 3 + [_vp, _sz, _vp]),
@@ -338,6 +339,20 @@ def flex_idiss_sample(phi, u, workspace=None):
     ws = workspace if workspace is not None else _workspace(phi.device, need)
     _check(lib().flex_idiss_sample(_ptr(phi.contiguous()), _ptr(u.contiguous()), _ptr(sel), B, N, Ns, _ptr(ws),
                                    ws.numel(), _stream()), "flex_idiss_sample")
+    return sel
+
+
+def flex_selection_make_distinct(sel, N, workspace=None):
+    """In place: an ascending selection int32 [B,Ns] with repeats becomes distinct (a repeated entry moves to the
+    next free index).  Returns sel."""
+    _dev(sel, torch.int32, "sel")
+    if sel.dim() != 2 or not sel.is_contiguous():
+        raise ValueError("sel must be a contiguous [B,Ns] tensor")
+    B, Ns = sel.shape
+    need = workspace_bytes(OP_IDISS, B, N, 1, 1, 1, BCN)
+    ws = workspace if workspace is not None else _workspace(sel.device, need)
+    _check(lib().flex_selection_make_distinct(_ptr(sel), B, int(N), Ns, _ptr(ws), ws.numel(), _stream()),
+           "flex_selection_make_distinct")
     return sel
 
 

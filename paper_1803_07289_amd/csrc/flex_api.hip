@@ -546,6 +546,16 @@ int flex_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, 
     return FLEX_OK;
 }
 
+int flex_selection_make_distinct(int32_t *sel, int B, int N, int Ns, void *workspace, size_t workspace_bytes,
+                                 void *stream)
+{
+    if (!sel) return FLEX_ERR_NULL;
+    if (!idiss_sizes_ok(B, N) || Ns <= 0 || Ns > N) return FLEX_ERR_SHAPE;
+    if (!ws_ok(workspace, workspace_bytes, distinct_ws_bytes(B, Ns))) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_selection_make_distinct(sel, B, N, Ns, workspace, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
 int flex_knn(const float *pos, int32_t *nbr, int B, int N, int K, void *workspace, size_t workspace_bytes,
              void *stream)
 {

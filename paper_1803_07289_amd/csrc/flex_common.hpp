@@ -141,6 +141,8 @@ hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 hipError_t launch_param_block(float *theta, float *bias, float *blk_theta, float *blk_bias, int R, int C, int r0,
                               int c0, int nr, int nc, int insert, hipStream_t s);
 size_t idiss_ws_bytes(int B, int N);
+size_t distinct_ws_bytes(int B, int Ns);
+hipError_t launch_selection_make_distinct(int32_t *sel, int B, int N, int Ns, void *ws, hipStream_t s);
 hipError_t launch_idiss_phi(const float *pos, const int32_t *nbr, float *phi, int B, int N, int K, hipStream_t s);
 hipError_t launch_idiss_sample(const float *phi, const uint32_t *u, int32_t *sel, int B, int N, int Ns, void *ws,
                                hipStream_t s);

@@ -7,6 +7,7 @@
 // the same table), the strata and thresholds are integer expressions of the caller's random
 // words.
 #include "flex_common.hpp"
+#include <climits>
 
 namespace flex {
 
@@ -155,6 +156,103 @@ __global__ __launch_bounds__(256) void idiss_select_kernel(const unsigned long l
         }
         sel[(int64_t)b * Ns + j] = lo;
     }
+}
+
+// ---- repeats removed from an ascending selection ---------------------------------------------
+// Sequential rule: sel[j] = max(sel[j], sel[j-1] + 1), then sel[j] = min(sel[j], N - Ns + j).  The first is
+// a running maximum of sel[i] - i (plus j), so it runs as a three-kernel scan; the second is elementwise.
+__device__ __forceinline__ int block_inclusive_max(int v, int *s_wave, int &block_max)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d, 64);
+        if (lane >= d) x = max(x, y);
+    }
+    if (lane == 63) s_wave[w] = x;
+    __syncthreads();
+    int before = INT_MIN;
+    for (int i = 0; i < w; ++i) before = max(before, s_wave[i]);
+    block_max = max(max(s_wave[0], s_wave[1]), max(s_wave[2], s_wave[3]));
+    __syncthreads();
+    return max(before, x);
+}
+
+__global__ __launch_bounds__(256) void distinct_chunk_max_kernel(const int32_t *__restrict__ sel, int *__restrict__ cm,
+                                                                 int Ns, int nblk)
+{
+    __shared__ int s_wave[4];
+    const int b = blockIdx.y;
+    const int64_t base = (int64_t)blockIdx.x * IDISS_CHUNK + (int64_t)threadIdx.x * IDISS_ITEMS;
+    int v = INT_MIN;
+#pragma unroll
+    for (int i = 0; i < IDISS_ITEMS; ++i)
+        if (base + i < Ns) v = max(v, sel[(int64_t)b * Ns + base + i] - (int)(base + i));
+    int total;
+    block_inclusive_max(v, s_wave, total);
+    if (threadIdx.x == 0) cm[(int64_t)b * nblk + blockIdx.x] = total;
+}
+
+// one block per cloud: cm[blk] <- maximum over the chunks before blk (INT_MIN for the first)
+__global__ __launch_bounds__(256) void distinct_scan_max_kernel(int *__restrict__ cm, int nblk)
+{
+    __shared__ int s_wave[4];
+    __shared__ int s_inc[256];
+    int *row = cm + (int64_t)blockIdx.x * nblk;
+    int carry = INT_MIN;
+    for (int c0 = 0; c0 < nblk; c0 += 256) {
+        const int i = c0 + threadIdx.x;
+        const int v = (i < nblk) ? row[i] : INT_MIN;
+        int total;
+        s_inc[threadIdx.x] = block_inclusive_max(v, s_wave, total);
+        __syncthreads();
+        const int before = threadIdx.x > 0 ? s_inc[threadIdx.x - 1] : INT_MIN;
+        if (i < nblk) row[i] = max(carry, before);
+        carry = max(carry, total);
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void distinct_apply_kernel(int32_t *__restrict__ sel, const int *__restrict__ cm, int N,
+                                                             int Ns, int nblk)
+{
+    __shared__ int s_wave[4];
+    const int b = blockIdx.y;
+    const int64_t base = (int64_t)blockIdx.x * IDISS_CHUNK + (int64_t)threadIdx.x * IDISS_ITEMS;
+    int v[IDISS_ITEMS], mine = INT_MIN;
+#pragma unroll
+    for (int i = 0; i < IDISS_ITEMS; ++i) {
+        v[i] = (base + i < Ns) ? sel[(int64_t)b * Ns + base + i] - (int)(base + i) : INT_MIN;
+        mine = max(mine, v[i]);
+    }
+    int total;
+    const int inc = block_inclusive_max(mine, s_wave, total);       // includes this thread's items
+    // maximum over everything before this thread's first item
+    __shared__ int s_inc[256];
+    s_inc[threadIdx.x] = inc;
+    __syncthreads();
+    int run = max(cm[(int64_t)b * nblk + blockIdx.x], threadIdx.x > 0 ? s_inc[threadIdx.x - 1] : INT_MIN);
+#pragma unroll
+    for (int i = 0; i < IDISS_ITEMS; ++i) {
+        run = max(run, v[i]);
+        if (base + i < Ns) {
+            const int j = (int)(base + i);
+            sel[(int64_t)b * Ns + j] = min(run + j, N - Ns + j);
+        }
+    }
+}
+
+size_t distinct_ws_bytes(int B, int Ns) { return align256(sizeof(int) * (size_t)B * cdiv64(Ns, IDISS_CHUNK)); }
+
+hipError_t launch_selection_make_distinct(int32_t *sel, int B, int N, int Ns, void *ws, hipStream_t s)
+{
+    const int nblk = (int)cdiv64(Ns, IDISS_CHUNK);
+    int *cm = (int *)ws;
+    hipLaunchKernelGGL(distinct_chunk_max_kernel, dim3(nblk, B), dim3(256), 0, s, sel, cm, Ns, nblk);
+    hipLaunchKernelGGL(distinct_scan_max_kernel, dim3(B), dim3(256), 0, s, cm, nblk);
+    hipLaunchKernelGGL(distinct_apply_kernel, dim3(nblk, B), dim3(256), 0, s, sel, cm, N, Ns, nblk);
+    return hipGetLastError();
 }
 
 int idiss_bits(int N)

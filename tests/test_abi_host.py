@@ -31,7 +31,8 @@ def test_every_declared_symbol_is_exported(L):
             "flexconv_workspace_bytes", "flex_validate_neighbors", "flex_status_string",
             "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
             "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub",
-            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample", "flex_knn"} <= set(names)
+            "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample", "flex_knn",
+            "flex_selection_make_distinct"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -94,6 +95,10 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
     assert L.flex_idiss_sample(one, one, one, 1, (1 << 25) + 1, 4, one, big, None) == 2
     assert L.flex_idiss_sample(one, one, one, 1, 4096, 4, one, 1024, None) == 4
     assert L.flexconv_workspace_bytes(7, 1, 4096, 1, 1, 1, 0) == 8 * 4096 + 256 + 256
+    # flex_selection_make_distinct(sel, B, N, Ns, ws, ws_bytes, stream)
+    assert L.flex_selection_make_distinct(none, 1, 16, 4, one, big, None) == 1
+    assert L.flex_selection_make_distinct(one, 1, 16, 17, one, big, None) == 2
+    assert L.flex_selection_make_distinct(one, 1, 16, 4, none, 0, None) == 4
     # flex_knn(pos, nbr, B, N, K, ws, ws_bytes, stream)
     assert L.flex_knn(one, none, 1, 100, 8, one, big, None) == 1
     assert L.flex_knn(one, one, 1, 100, 11, one, big, None) == 2           # K without a kernel

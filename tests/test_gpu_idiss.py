@@ -73,3 +73,26 @@ def test_idiss_room_scale_end_to_end():
     assert np.array_equal(sel, oracle.idiss_sample(phi32, u))
     # sparse regions are favoured: the drawn points' mean phi exceeds the cloud's
     assert phi32[0][sel[0]].mean() > phi32.mean()
+
+
+@pytest.mark.parametrize("B,N,Ns", [(2, 1000, 400), (1, 10, 10), (3, 5000, 1), (1, 300_000, 75_000), (2, 4097, 4000)])
+def test_make_distinct_is_bit_exact(B, N, Ns):
+    say(f"make distinct B={B} N={N} Ns={Ns}")
+    rng = np.random.default_rng(N + Ns)
+    sel = np.sort(rng.integers(0, N, size=(B, Ns)), axis=1).astype(np.int32)
+    sel[0, Ns // 2:] = np.maximum(sel[0, Ns // 2:], N - 3)          # repeats piled up against the end
+    got = fx.flex_selection_make_distinct(dev(sel), N)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.selection_make_distinct(sel, N))
+
+
+def test_idiss_draw_made_distinct_feeds_upsampling():
+    rng = np.random.default_rng(5)
+    N, Ns = 20_000, 5_000
+    phi = rng.random((1, N)).astype(np.float32) ** 4                 # strongly uneven: many repeats
+    u = _words(rng, 1, Ns)
+    sel = fx.flex_idiss_sample(dev(phi), torch.from_numpy(u.view(np.int32)).cuda())
+    assert fx.flex_validate_selection(sel, N) > 0                    # the raw draw repeats points
+    fx.flex_selection_make_distinct(sel, N)
+    assert fx.flex_validate_selection(sel, N) == 0
+    assert np.array_equal(sel.cpu().numpy(), oracle.selection_make_distinct(oracle.idiss_sample(phi, u), N))

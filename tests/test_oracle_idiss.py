@@ -94,3 +94,30 @@ def test_sample_frequencies_are_proportional_to_phi():
     expect = trials * Ns * phi.astype(np.float64) / phi.astype(np.float64).sum()
     assert np.abs(counts - expect).max() <= 5.0 * np.sqrt(expect.max())      # five sigma of a Poisson count
     assert abs(counts.sum() - trials * Ns) == 0
+
+
+def test_make_distinct_bruteforce_and_properties():
+    rng = np.random.default_rng(9)
+    for N, Ns in ((30, 12), (10, 10), (50, 1), (40, 35), (1000, 400)):
+        for trial in range(20):
+            sel = np.sort(rng.integers(0, N, size=(2, Ns)), axis=1).astype(np.int32)
+            if trial % 3 == 0:
+                sel[0, Ns // 2:] = N - 1                      # a pile of repeats at the very end
+            out = oracle.selection_make_distinct(sel, N)
+            for b in range(2):
+                s = [int(v) for v in sel[b]]
+                for j in range(1, Ns):                         # the rule, in plain Python
+                    if s[j] <= s[j - 1]:
+                        s[j] = s[j - 1] + 1
+                for j in range(Ns - 1, -1, -1):
+                    s[j] = min(s[j], N - Ns + j)
+                assert list(out[b]) == s
+            assert (np.diff(out, axis=1) > 0).all() and out.min() >= 0 and out.max() < N
+            keep = np.ones_like(sel, bool)
+            keep[:, 1:] = sel[:, 1:] != sel[:, :-1]
+            # away from a packed tail, the first occurrence of every drawn point stays where it was unless an
+            # earlier run of repeats had spilled over it
+            untouched = (out == sel)
+            assert untouched[:, 0].all() or (sel[:, 0] > N - Ns).any()
+    distinct = np.array([[1, 4, 9, 20]], np.int32)
+    assert np.array_equal(oracle.selection_make_distinct(distinct, 25), distinct)   # nothing to do: unchanged

@@ -38,7 +38,7 @@ BLOCK_PINS = [tb.test_block_fwd_bruteforce_dense, tb.test_block_identity_1x1_is_
               tb.test_block_bwd_finite_differences_full_jacobian]
 
 IDISS_PINS = [ti.test_phi_bruteforce_and_grid_closed_form, ti.test_sample_matches_exact_integer_reference,
-              ti.test_sample_uniform_density_is_one_point_per_block]
+              ti.test_sample_uniform_density_is_one_point_per_block, ti.test_make_distinct_bruteforce_and_properties]
 
 KNN_PINS = [tk.test_knn_matches_float32_numpy_ranking_with_ties, tk.test_knn_agrees_with_a_kd_tree_on_generic_points,
             tk.test_knn_k_equals_n_and_duplicates]
@@ -88,6 +88,8 @@ MUTATIONS = [
     ("idiss_remainder_dropped", "const uint64_t len = width + ((uint64_t)j < rem ? 1u : 0u);", "const uint64_t len = width;", 0, IDISS_PINS),
     ("knn_ties_to_later_index", "while (at > 0 && d2 < bd[at - 1])", "while (at > 0 && d2 <= bd[at - 1])", 0, KNN_PINS),
     ("knn_drops_z", "const float d2 = xy + zz;", "const float d2 = xy;", 0, KNN_PINS),
+    ("distinct_keeps_equal_entries", "if (s[j] <= s[j - 1]) s[j] = s[j - 1] + 1;", "if (s[j] < s[j - 1]) s[j] = s[j - 1] + 1;", 0, IDISS_PINS),
+    ("distinct_tail_not_packed", "if (s[j] > N - Ns + j) s[j] = N - Ns + j;", "if (s[j] > N - 1) s[j] = N - 1;", 0, IDISS_PINS),
     ("pool_bwd_to_centre", "grad_feat[IDX3(b, c, m, C, N)] += (double)grad_out", "grad_feat[IDX3(b, c, l, C, N)] += (double)grad_out", 0, POOL_PINS),
 ]
 
