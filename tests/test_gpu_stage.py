@@ -32,7 +32,7 @@ def test_encoder_decoder_stage_matches_oracle_chain():
     o_nbr = oracle.knn(pos, K)
     o_f1 = oracle.flexconv_fwd(feat, pos, o_nbr, th1, b1).astype(np.float32)
     o_phi = oracle.idiss_phi(pos, o_nbr).astype(np.float32)
-    o_sel = np.unique(oracle.idiss_sample(o_phi, u)[0])[None].astype(np.int32)     # a point drawn twice is kept once
+    o_sel = oracle.selection_make_distinct(oracle.idiss_sample(o_phi, u), N)     # repeats move to the next free index
     o_pool, o_arg = oracle.flexpool_sub_fwd(o_f1, o_nbr, o_sel)
     o_pos_s = np.ascontiguousarray(pos[:, :, o_sel[0]])
     o_nbr_s = oracle.knn(o_pos_s, K)
@@ -50,7 +50,7 @@ def test_encoder_decoder_stage_matches_oracle_chain():
     # the draw is an integer procedure on phi's bits: both sides get the oracle's phi so that one rounding of phi
     # cannot send the two chains to different points
     sel_raw = fx.flex_idiss_sample(dev(o_phi), torch.from_numpy(u.view(np.int32)).cuda())
-    sel = torch.unique(sel_raw[0]).to(torch.int32)[None].contiguous()
+    sel = fx.flex_selection_make_distinct(sel_raw, N)
     assert np.array_equal(sel.cpu().numpy(), o_sel)
     assert fx.flex_validate_selection(sel, N) == 0
     pool, arg = fx.flexpool_sub_fwd(f1, nbr, sel, layout=L)
