@@ -219,6 +219,8 @@ int flex_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N,
  * point has a lower index), ordered by (d2, index): equal distances go to the LOWER INDEX.
  * d2 is evaluated in fp32 as ((dx*dx + dy*dy) + dz*dz), dx = pos[n] - pos[l], each operation
  * rounded separately; the result is the exact ranking under that d2.
+ * Cost: every query scans the cells around it, so M points at one location (or closer together than the
+ * cell edge, about the mean spacing) cost M*M distance evaluations; meant for clouds without such piles.
  * pos [B,3,N] finite; nbr int32 [B,K,N] overwritten.  K in 1..10, 12, 16, 24 or 32, K <= N;
  * B <= 65535.  Workspace: flexconv_workspace_bytes(FLEX_OP_KNN, B, N, K, ...).
  */
