@@ -24,8 +24,8 @@
  *   out, grad_out, grad_feat, pool out / argmax: same layout flag as feat.
  * The position difference is (neighbour - centre).
  *
- * Workspace: flexconv_fwd / flexconv_bwd / flex_inedges_build take a caller
- * buffer of at least flexconv_workspace_bytes(...) bytes, 256-byte aligned.
+ * Workspace: the entry points with a `workspace` argument take a caller
+ * buffer of at least flexconv_workspace_bytes(op, ...) bytes, 256-byte aligned.
  * Its contents are scratch; calls sharing one workspace must be stream-ordered.
  */
 #ifndef FLEXCONV_H
@@ -57,7 +57,7 @@ typedef enum {
     FLEX_OP_UPSAMPLE = 4,       /* flexupsample_fwd / flex_validate_selection; N = points of the larger layer */
     FLEX_OP_CONV_BWD_POS = 5,       /* flexconv_bwd_pos with caller-supplied in-edge lists */
     FLEX_OP_CONV_BWD_POS_BUILD = 6, /* in-edge lists built inside the call */
-    FLEX_OP_IDISS = 7,              /* flex_idiss_sample */
+    FLEX_OP_IDISS = 7,              /* flex_idiss_sample, flex_selection_make_distinct */
     FLEX_OP_KNN = 8                 /* flex_knn */
 } flex_op;
 
