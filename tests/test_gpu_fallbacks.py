@@ -1,0 +1,25 @@
+"""The kernels that only special sizes reach (LDS-staged producers: byte offsets past 32 bits; fp32 matrix-op
+contraction and single-pass 128-wide kernels: kept for comparisons) are selected here through the library's
+environment switches, which are read once per process: so each setting runs the parity file once in a child process
+(one at a time)."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.mark.parametrize("env", [{"FLEX_PRODUCER": "staged"}, {"FLEX_CONTRACT": "f32"}, {"FLEX_SPLIT": "0"}],
+                         ids=["staged_producers", "fp32_contraction", "single_pass_128"])
+def test_parity_file_under_switch(env):
+    child_env = dict(os.environ)
+    child_env.update(env)
+    r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.join(HERE, "test_gpu_parity.py"), "-x", "-q",
+                        "-m", "gpu", "--timeout", "120", "--timeout-method", "thread", "-p", "no:cacheprovider"],
+                       capture_output=True, text=True, env=child_env, cwd=os.path.dirname(HERE), timeout=600)
+    tail = "\n".join((r.stdout + r.stderr).splitlines()[-15:])
+    assert r.returncode == 0, tail
+    assert " passed" in r.stdout, tail
