@@ -7,6 +7,8 @@
 
 namespace flex {
 
+typedef int i4v __attribute__((ext_vector_type(4)));
+
 // (value desc, point index asc): the winner among equal values is the lowest index.
 __device__ __forceinline__ void take(float v, int n, float &bv, int &bn)
 {
@@ -75,12 +77,13 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
         if (k0 < K) FLEX_POOL_SLOTS(4)      // a tail of up to four slots
 #undef FLEX_POOL_SLOTS
         const v4f bv = {v0, v1, v2, v3};
-        reinterpret_cast<v4f *>(out)[gp * C4 + c4] = bv;
-        reinterpret_cast<int4 *>(argmax)[gp * C4 + c4] = make_int4(b0, b1, b2, b3);
+        // streaming stores: the outputs are not read again by this kernel and should not displace gathered rows in L2
+        __builtin_nontemporal_store(bv, &reinterpret_cast<v4f *>(out)[gp * C4 + c4]);
+        const i4v bi = {b0, b1, b2, b3};
+        __builtin_nontemporal_store(bi, &reinterpret_cast<i4v *>(argmax)[gp * C4 + c4]);
     }
 }
 
-// Any C, either layout: one thread per output element.
 // value of lane SRC of the caller's 16-lane row (all 16 lanes must be active)
 template <int SRC>
 __device__ __forceinline__ int row_bcast(int x)
@@ -220,7 +223,7 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
                 acc.w += (fresh && a[u].w == m) ? g[u].w : 0.f;
             }
         }
-        reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4] = acc;
+        __builtin_nontemporal_store(acc, &reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4]);
     }
 }
 
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
             if constexpr (U == 2) { FLEX_POOL_BATCH(4) FLEX_POOL_BATCH(5) FLEX_POOL_BATCH(6) FLEX_POOL_BATCH(7) }
 #undef FLEX_POOL_BATCH
         }
-        reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4] = acc;
+        __builtin_nontemporal_store(acc, &reinterpret_cast<v4f *>(grad_feat)[gp * C4 + c4]);
     }
 }
 
