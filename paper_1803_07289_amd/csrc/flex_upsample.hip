@@ -93,8 +93,11 @@ __global__ __launch_bounds__(256) void upsample_fwd_bnc4_kernel(const float *__r
             }
         }
         const v4f bv = {v0, v1, v2, v3};
-        reinterpret_cast<v4f *>(out)[gp * C4 + c4] = bv;
-        reinterpret_cast<int4 *>(argmax)[gp * C4 + c4] = make_int4(b0, b1, b2, b3);
+        // streaming stores, as in the pooling kernels
+        typedef int i4v __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(bv, &reinterpret_cast<v4f *>(out)[gp * C4 + c4]);
+        const i4v bi = {b0, b1, b2, b3};
+        __builtin_nontemporal_store(bi, &reinterpret_cast<i4v *>(argmax)[gp * C4 + c4]);
     }
 }
 
