@@ -22,8 +22,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense f16 / bf16 matrix
 # HBM bytes per launch of each entry point's kernel on the default workload (rocprofv3 counters,
 # profiles/flexconv_cfg4_hbm_traffic.md)
-MEASURED_TRAFFIC = {"fwd": 4.073e9, "bwd_params": 4.087e9, "bwd_feat": 4.095e9,
-                    "pool_fwd": 5.766e9, "pool_bwd": 5.954e9}
+MEASURED_TRAFFIC = {"fwd": 4.073e9, "bwd_params": 4.088e9, "bwd_feat": 4.095e9,
+                    "pool_fwd": 5.717e9, "pool_bwd": 5.918e9}
 
 
 def log(*a):
