@@ -241,7 +241,7 @@ bool FLEX_NAME(gp_ok, FLEX_DI, FLEX_DO)(int N, int K)
 {
 #if FLEX_WS
     if constexpr (S::WAVES == 4 && S::T == 16 && PosGeom<S>::FITS)
-        return !contract_in_fp32() && (K % 8 == 0) && lean_fixed_ok(N, K);    // the plain-sum producers take whole batches
+        return !contract_in_fp32() && lean_fixed_ok(N, K);
 #endif
     (void)N; (void)K;
     return false;
@@ -264,9 +264,12 @@ hipError_t FLEX_NAME(launch_gp, FLEX_DI, FLEX_DO)(const float *rows, const int32
         if (csr)
             hipLaunchKernelGGL((grad_pos_kernel<S, true, PMX>), g, blk, 0, s, rows, nbr, off, src, thetaF, exp_off,
                                dot_rows, grad_pos, sign, accumulate, N, K, tpc, tot);
-        else
+        else if (K % 8 == 0)
             hipLaunchKernelGGL((grad_pos_kernel<S, false, PMX>), g, blk, 0, s, rows, nbr, off, src, thetaF, exp_off,
                                dot_rows, grad_pos, sign, accumulate, N, K, tpc, tot);
+        else
+            hipLaunchKernelGGL((grad_pos_kernel<S, false, PMX, true>), g, blk, 0, s, rows, nbr, off, src, thetaF,
+                               exp_off, dot_rows, grad_pos, sign, accumulate, N, K, tpc, tot);
         return hipGetLastError();
     }
 #endif

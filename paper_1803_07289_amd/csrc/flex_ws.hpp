@@ -511,14 +511,14 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 // are read (used by the location-gradient kernels).
 // RS = floats between consecutive rows of the gathered tensor (S::DI unless the rows are a column block of a wider one)
 // TAIL: K is not a multiple of 8; the last batch of a tile has slots past K, which are read from slot K-1 and
-// weighted 0 (the weight travels as the fourth position component), and its rows 4..7 are skipped when empty.
+// weighted 0 (the weight travels as the fourth position component; in the plain-sum mode it is a wave-uniform
+// 0 / 1 per slot), and its rows 4..7 are skipped when empty.
 template <class S, int PM, bool SUM = false, int RS = S::DI, bool TAIL = false>
 struct LeanProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
     static constexpr bool FULL = (S::LPR * S::VEC == S::DI);   // every lane of a group reads real channels
     static_assert(G::PW == 4, "entry layout below: 4 points x 8 neighbours per batch");
-    static_assert(!(SUM && TAIL), "the plain-sum mode takes whole batches only");
     // The aggregate runs on the vector ALU: the fp32 4x4x1 matrix op would need fewer issue slots, but
     // it holds both the vector ALU and the f16/bf16 matrix pipe of the SIMD while it executes, so the
     // consumers' matrix ops could never overlap the producers' work.
@@ -683,6 +683,7 @@ struct LeanProducer {
                 if (k0_cur + e_k + 4 >= K) dpe[1] = 0;
             }
             const bool cur_upper = !TAIL || k0_cur + 4 < K, next_upper = !TAIL || x1.k0 + 4 < K;
+            const int k0_acc = k0_cur;
             k0_cur = x1.k0;
             // ids of batch m+1 are here: their positions and (below) rows go in flight; ids of batch m+2 too
             int idc[U];
@@ -705,7 +706,11 @@ struct LeanProducer {
                     float fv[S::VEC];
 #pragma unroll
                     for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                    if constexpr (SUM) {
+                    if constexpr (SUM && TAIL) {
+                        const float one = (k0_acc + u < K) ? 1.f : 0.f;            // 0 for a slot past K
+#pragma unroll
+                        for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                    } else if constexpr (SUM) {
 #pragma unroll
                         for (int v = 0; v < S::VEC; ++v) acc[v][3] += fv[v];
                     } else if constexpr (VALU_AGG) {
@@ -1619,7 +1624,7 @@ struct PosGeom {
     static constexpr bool FITS = NS * KS2 * 8 <= 64 && S::VEC == 4;   // Theta_d fragments of one wave in 64 VGPRs
 };
 
-template <class S, bool CSR, int PM>
+template <class S, bool CSR, int PM, bool TAIL = false>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__ nbr,
                      const int32_t *__restrict__ off, const int32_t *__restrict__ src,
@@ -1714,7 +1719,7 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
                 load_y(nb, nlw0 - P.pw * G::PW);
             });
         } else {
-            LeanProducer<S, PM, true> P;
+            LeanProducer<S, PM, true, S::DI, TAIL> P;
             P.init(rows, nullptr, nbr, N, K, w, sc, tiles_per_cloud);
             if (P.count > 0) {
                 int b0, lw00;
