@@ -205,11 +205,49 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
     }
 }
 
+// The same with 16-byte accesses on both sides (R, C multiples of 4, 16-byte aligned tensors): thread
+// (ty, tx) moves four consecutive floats of rows ty, ty+16, .. in, and of columns ty, ty+16, .. out.
+__global__ __launch_bounds__(256) void transpose_vec4_kernel(const float *__restrict__ src,
+                                                             float *__restrict__ dst, int R, int C,
+                                                             int tiles_r, int tiles_c)
+{
+    __shared__ float tile[64][65];
+    const int64_t t = blockIdx.x;
+    const int tc = (int)(t % tiles_c);
+    const int tr = (int)((t / tiles_c) % tiles_r);
+    const int64_t b = t / ((int64_t)tiles_c * tiles_r);
+    const float *s = src + b * (int64_t)R * C;
+    float *d = dst + b * (int64_t)R * C;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int r0 = tr * 64, c0 = tc * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int rl = ty + 16 * i, r = r0 + rl, c = c0 + 4 * tx;
+        v4f v = {0.f, 0.f, 0.f, 0.f};
+        if (r < R && c < C) v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(s + (int64_t)r * C + c));
+        tile[rl][4 * tx + 0] = v.x; tile[rl][4 * tx + 1] = v.y; tile[rl][4 * tx + 2] = v.z; tile[rl][4 * tx + 3] = v.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int cl = ty + 16 * i, c = c0 + cl, r = r0 + 4 * tx;
+        if (r < R && c < C) {
+            const v4f v = {tile[4 * tx + 0][cl], tile[4 * tx + 1][cl], tile[4 * tx + 2][cl], tile[4 * tx + 3][cl]};
+            *reinterpret_cast<v4f *>(d + (int64_t)c * R + r) = v;
+        }
+    }
+}
+
 static hipError_t launch_transpose(const float *src, float *dst, int B, int R, int C, hipStream_t s)
 {
     const int tiles_r = (R + 63) / 64, tiles_c = (C + 63) / 64;
     const int64_t blocks = (int64_t)B * tiles_r * tiles_c;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    if (R % 4 == 0 && C % 4 == 0 && ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) == 0) {
+        hipLaunchKernelGGL(transpose_vec4_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, R, C,
+                           tiles_r, tiles_c);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, R, C,
                        tiles_r, tiles_c);
     return hipGetLastError();

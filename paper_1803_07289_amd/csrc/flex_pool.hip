@@ -15,6 +15,14 @@ __device__ __forceinline__ void take(float v, int n, float &bv, int &bn)
     if (v > bv || (v == bv && n < bn)) { bv = v; bn = n; }
 }
 
+// Element at a 32-bit byte offset from a wave-uniform row pointer (scalar base + vector offset addressing);
+// rows of the channel-major kernels are shorter than 4 GiB (checked by their launchers).
+template <class T>
+__device__ __forceinline__ T at_byte(const T *row, unsigned byte_off)
+{
+    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(row) + byte_off);
+}
+
 // Blocks are dealt to the 8 XCDs round-robin by block id; giving each XCD one
 // contiguous eighth of the point tiles keeps a neighbourhood's rows in one L2.
 __device__ __forceinline__ int64_t xcd_tile(int64_t total_tiles)
@@ -91,6 +99,78 @@ __device__ __forceinline__ int row_bcast(int x)
     return __builtin_amdgcn_update_dpp(0, x, 0x150 + SRC, 0xf, 0xf, true);   // row_newbcast:SRC
 }
 
+// Channel-major ([B,C,N]) forward.  A block owns 64 consecutive centres of one cloud: lane = centre, so
+// the ids, the outputs and the winner table move as whole 256-byte rows, and the four waves split the
+// channels in chunks of CH.  A thread requests CH x 8 values (4 bytes each, from CH channel rows) before
+// it compares; the ids of the first eight slots are read once for all channels.
+// sel == nullptr: every point is a centre (L = N); else the centres are sel[b, 0..L).
+template <int CH>
+__global__ __launch_bounds__(256) void pool_fwd_bcn_kernel(const float *__restrict__ feat,
+                                                           const int32_t *__restrict__ nbr,
+                                                           const int32_t *__restrict__ sel,
+                                                           float *__restrict__ out,
+                                                           int32_t *__restrict__ argmax, int N, int L,
+                                                           int K, int C, int tiles_per_cloud,
+                                                           int64_t total_tiles)
+{
+    constexpr int U = 8;
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    const int64_t b = tile / tiles_per_cloud;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: channel rows get scalar base addresses
+    const int j = (int)(tile - b * tiles_per_cloud) * 64 + lane;
+    const bool on = j < L;
+    const int jc = min(j, L - 1);
+    const int l = sel ? min(max(sel[b * L + jc], 0), N - 1) : jc;
+    const int32_t *nb = nbr + b * K * N + l;
+    int n0[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) n0[u] = nb[(int64_t)min(u, K - 1) * N];      // past K: the last slot again
+    for (int c0 = w * CH; c0 < C; c0 += 4 * CH) {
+        const float *row[CH];
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) row[ch] = feat + (b * C + min(c0 + ch, C - 1)) * N;
+        float bv[CH];
+        int bn[CH];
+        {
+            float v[CH][U];
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch)
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[ch][u] = at_byte(row[ch], 4u * (unsigned)n0[u]);
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch) {
+                bv[ch] = v[ch][0];
+                bn[ch] = n0[0];
+#pragma unroll
+                for (int u = 1; u < U; ++u) take(v[ch][u], n0[u], bv[ch], bn[ch]);   // a repeated pair never changes the winner
+            }
+        }
+        for (int k0 = U; k0 < K; k0 += U) {
+            int n[U];
+            float v[CH][U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) n[u] = nb[(int64_t)min(k0 + u, K - 1) * N];
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch)
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[ch][u] = at_byte(row[ch], 4u * (unsigned)n[u]);
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch)
+#pragma unroll
+                for (int u = 0; u < U; ++u) take(v[ch][u], n[u], bv[ch], bn[ch]);
+        }
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch)
+            if (on && c0 + ch < C) {
+                const int64_t at = (b * C + c0 + ch) * L + j;
+                __builtin_nontemporal_store(bv[ch], &out[at]);
+                __builtin_nontemporal_store(bn[ch], &argmax[at]);
+            }
+    }
+}
+
 // sel == nullptr: every point is a centre (L = N); else the centres are sel[b, 0..L).
 __global__ __launch_bounds__(256) void pool_fwd_generic_kernel(const float *__restrict__ feat,
                                                                const int32_t *__restrict__ nbr,
@@ -128,6 +208,11 @@ hipError_t launch_pool_fwd(const float *feat, const int32_t *nbr, float *out, in
         const int64_t BN = (int64_t)B * N, tiles = (BN + PT - 1) / PT;
         hipLaunchKernelGGL(pool_fwd_bnc4_kernel<false>, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr,
                            (const int32_t *)nullptr, out, argmax, BN, N, N, K, C4, PT, tiles);
+    } else if (!bnc && N < (1 << 30)) {
+        const int tpc = (N + 63) / 64;
+        const int64_t tiles = (int64_t)B * tpc;
+        hipLaunchKernelGGL(pool_fwd_bcn_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr,
+                           (const int32_t *)nullptr, out, argmax, N, N, K, C, tpc, tiles);
     } else {
         const int64_t total = (int64_t)B * N * C;
         int64_t blocks = (total + 255) / 256;
@@ -148,6 +233,11 @@ hipError_t launch_pool_sub_fwd(const float *feat, const int32_t *nbr, const int3
         const int64_t BNs = (int64_t)B * Ns, tiles = (BNs + PT - 1) / PT;
         hipLaunchKernelGGL(pool_fwd_bnc4_kernel<true>, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr, sel,
                            out, argmax, BNs, N, Ns, K, C4, PT, tiles);
+    } else if (!bnc && N < (1 << 30)) {
+        const int tpc = (Ns + 63) / 64;
+        const int64_t tiles = (int64_t)B * tpc;
+        hipLaunchKernelGGL(pool_fwd_bcn_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, feat, nbr, sel, out,
+                           argmax, N, Ns, K, C, tpc, tiles);
     } else {
         const int64_t total = (int64_t)B * Ns * C;
         int64_t blocks = (total + 255) / 256;
@@ -292,6 +382,65 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
     }
 }
 
+// Channel-major ([B,C,N]) gather form: lane = point m of a block's 64 consecutive points, the four waves
+// split the channels in chunks of CH; a thread takes four list entries at a time and requests their
+// CH x 4 winner-table and gradient values (4 bytes each) together.  The lists are re-read per chunk.
+template <int CH>
+__global__ __launch_bounds__(256) void pool_bwd_gather_bcn_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
+    const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
+    float *__restrict__ grad_feat, int N, int L, int C, int tiles_per_cloud, int64_t total_tiles)
+{
+    constexpr int U = 4;
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    const int64_t b = tile / tiles_per_cloud;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: channel rows get scalar base addresses
+    const int m = (int)(tile - b * tiles_per_cloud) * 64 + lane;
+    const bool on = m < N;
+    const int64_t gp = b * N + min(m, N - 1);
+    const int e0 = in_off[gp], e1 = on ? in_off[gp + 1] : e0;      // lanes past the cloud: an empty list
+    for (int c0 = w * CH; c0 < C; c0 += 4 * CH) {
+        const int32_t *arow[CH];
+        const float *grow[CH];
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            const int64_t at = (b * C + min(c0 + ch, C - 1)) * L;
+            arow[ch] = argmax + at;
+            grow[ch] = grad_out + at;
+        }
+        float acc[CH];
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) acc[ch] = 0.f;
+        int prev = -1;
+        for (int e = e0; e < e1; e += U) {
+            int l[U], a[CH][U];
+            float g[CH][U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) l[u] = in_src[e + u < e1 ? e + u : e];   // past the end: entry e again
+#pragma unroll
+            for (int ch = 0; ch < CH; ++ch)
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    a[ch][u] = at_byte(arow[ch], 4u * (unsigned)l[u]);
+                    g[ch][u] = at_byte(grow[ch], 4u * (unsigned)l[u]);
+                }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                // a centre that lists m twice (adjacent entries) routes one gradient
+                const bool fresh = (e + u < e1) && l[u] != prev;
+                prev = l[u];
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) acc[ch] += (fresh && a[ch][u] == m) ? g[ch][u] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch)
+            if (on && c0 + ch < C) __builtin_nontemporal_store(acc[ch], &grad_feat[(b * C + c0 + ch) * N + m]);
+    }
+}
+
 __global__ __launch_bounds__(256) void pool_bwd_gather_generic_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
@@ -346,6 +495,11 @@ hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argm
         else
             hipLaunchKernelGGL(pool_bwd_gather_bnc4_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
                                argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tiles);
+    } else if (!bnc && L < (1 << 30)) {
+        const int tpc = (N + 63) / 64;
+        const int64_t tiles = (int64_t)B * tpc;
+        hipLaunchKernelGGL(pool_bwd_gather_bcn_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+                           argmax, in_off, in_src, grad_feat, N, L, C, tpc, tiles);
     } else {
         const int64_t total = (int64_t)B * N * C;
         int64_t blocks = (total + 255) / 256;

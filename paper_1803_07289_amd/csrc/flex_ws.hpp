@@ -1351,7 +1351,6 @@ void grad_theta_ws_kernel(const float *__restrict__ rows, const float *__restric
 
     TileWalk tw(sc, tiles_per_cloud);
     for (int k = 0; tw.valid(); ++k, tw.next()) {
-        const TileRef r{true, tw.b, tw.tic * G::T};
         __syncthreads();
         const float *sA = reinterpret_cast<const float *>(s_A + (k & 1) * (G::T * G::ROWB)), *sG = s_G[k & 1];
 #pragma unroll
@@ -1546,7 +1545,6 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
 
     TileWalk tw(sc, tiles_per_cloud);
     for (int k = 0; tw.valid(); ++k, tw.next()) {
-        const TileRef r{true, tw.b, tw.tic * G::T};
         if (k % FLUSH == 0 && k > 0) {
 #pragma unroll
             for (int c = 0; c < MBW; ++c)

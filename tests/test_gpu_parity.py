@@ -132,7 +132,8 @@ def test_degenerate_neighbourhoods():
         assert rel_err(gb.cpu().numpy(), rgb) <= TOL
 
 
-POOL_SHAPES = [(1, 1000, 8, 64), (2, 77, 3, 32), (1, 130, 16, 128), (2, 150, 6, 5), (1, 64, 1, 9)]
+POOL_SHAPES = [(1, 1000, 8, 64), (2, 77, 3, 32), (1, 130, 16, 128), (2, 150, 6, 5), (1, 64, 1, 9), (2, 200, 20, 12),
+               (1, 40, 9, 18)]
 
 
 @pytest.mark.parametrize("layout", [fx.BNC, fx.BCN], ids=["bnc", "bcn"])
