@@ -382,26 +382,39 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
     }
 }
 
-// Channel-major ([B,C,N]) gather form: lane = point m of a block's 64 consecutive points, the four waves
-// split the channels in chunks of CH; a thread takes four list entries at a time and requests their
-// CH x 4 winner-table and gradient values (4 bytes each) together.  The lists are re-read per chunk.
-template <int CH>
+// Channel-major ([B,C,N]) gather form.  A block owns 64 consecutive points, whose in-edge lists are one
+// contiguous range of entries.  The gathers run over that range with lane = entry (a lane per point would
+// idle until the longest of 64 lists is done): per chunk of ECH entries the block parks the entries and
+// the point each belongs to in LDS, every wave gathers winner-table and gradient values of its CH channels
+// for all entries (CH x 4 pairs in flight per lane) and parks what each entry routes, and then, with
+// lane = point, adds up each point's own stretch in list order.
+template <int ECH>
 __global__ __launch_bounds__(256) void pool_bwd_gather_bcn_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
     float *__restrict__ grad_feat, int N, int L, int C, int tiles_per_cloud, int64_t total_tiles)
 {
-    constexpr int U = 4;
+    constexpr int CH = 4, U = 4, J = ECH / 64;
+    static_assert(ECH % (64 * U) == 0, "a lane takes U entries of a chunk at a time");
+    __shared__ int s_off[65];
+    __shared__ int s_l[ECH];            // source row of each entry
+    __shared__ unsigned char s_t[ECH];  // its point (0..63), +64 unless it repeats the entry before it
+    // what the entry routes, per channel of the pass (rows private to a wave); entry i of point p sits at
+    // column i + p, so that the points' stretches, which start about K apart, begin in different banks
+    __shared__ float s_c[4 * CH][ECH + 64];
     const int64_t tile = xcd_tile(total_tiles);
     if (tile < 0) return;
     const int64_t b = tile / tiles_per_cloud;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: channel rows get scalar base addresses
-    const int m = (int)(tile - b * tiles_per_cloud) * 64 + lane;
-    const bool on = m < N;
-    const int64_t gp = b * N + min(m, N - 1);
-    const int e0 = in_off[gp], e1 = on ? in_off[gp + 1] : e0;      // lanes past the cloud: an empty list
-    for (int c0 = w * CH; c0 < C; c0 += 4 * CH) {
+    const int m0 = (int)(tile - b * tiles_per_cloud) * 64;
+    const int np = min(64, N - m0);
+    if (threadIdx.x <= 64) s_off[threadIdx.x] = in_off[b * N + m0 + min((int)threadIdx.x, np)];   // past the cloud: empty lists
+    __syncthreads();
+    const int E0 = s_off[0], E1 = s_off[64];
+    const int my0 = s_off[lane], my1 = s_off[lane + 1];
+    for (int cg = 0; cg < C; cg += 4 * CH) {
+        const int c0 = cg + w * CH;
         const int32_t *arow[CH];
         const float *grow[CH];
 #pragma unroll
@@ -413,31 +426,57 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bcn_kernel(
         float acc[CH];
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) acc[ch] = 0.f;
-        int prev = -1;
-        for (int e = e0; e < e1; e += U) {
-            int l[U], a[CH][U];
-            float g[CH][U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) l[u] = in_src[e + u < e1 ? e + u : e];   // past the end: entry e again
-#pragma unroll
-            for (int ch = 0; ch < CH; ++ch)
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    a[ch][u] = at_byte(arow[ch], 4u * (unsigned)l[u]);
-                    g[ch][u] = at_byte(grow[ch], 4u * (unsigned)l[u]);
+        for (int Ec = E0; Ec < E1; Ec += ECH) {         // the same trips for every thread of the block
+            const int nEc = min(ECH, E1 - Ec);
+            const int lo = max(my0, Ec) - Ec, hi = min(my1, Ec + nEc) - Ec;   // this lane's point, within the chunk
+            __syncthreads();                            // every wave is done with the chunk before
+            for (int i = threadIdx.x; i < nEc; i += 256) s_l[i] = in_src[Ec + i];
+            if (w == 0)
+                for (int i = lo; i < hi; ++i) {
+                    // a centre that lists the point twice (adjacent entries) routes one gradient
+                    const int e = Ec + i;
+                    const bool fresh = e == my0 || in_src[e] != in_src[e - 1];
+                    s_t[i] = (unsigned char)(lane + (fresh ? 64 : 0));
                 }
+            __syncthreads();
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                // a centre that lists m twice (adjacent entries) routes one gradient
-                const bool fresh = (e + u < e1) && l[u] != prev;
-                prev = l[u];
+            for (int j0 = 0; j0 < J; j0 += U) {
+                if (j0 * 64 < nEc) {
+                    int l[U], t[U], a[CH][U];
+                    float g[CH][U];
 #pragma unroll
-                for (int ch = 0; ch < CH; ++ch) acc[ch] += (fresh && a[ch][u] == m) ? g[ch][u] : 0.f;
+                    for (int u = 0; u < U; ++u) {
+                        const int i = (j0 + u) * 64 + lane;
+                        l[u] = s_l[i < nEc ? i : 0];
+                        t[u] = i < nEc ? s_t[i] : 0;    // past the end: routes nothing
+                    }
+#pragma unroll
+                    for (int ch = 0; ch < CH; ++ch)
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            a[ch][u] = at_byte(arow[ch], 4u * (unsigned)l[u]);
+                            g[ch][u] = at_byte(grow[ch], 4u * (unsigned)l[u]);
+                        }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int i = (j0 + u) * 64 + lane;
+                        const int m = m0 + (t[u] & 63);
+#pragma unroll
+                        for (int ch = 0; ch < CH; ++ch)
+                            if (i < nEc) s_c[w * CH + ch][i + (t[u] & 63)] = ((t[u] & 64) && a[ch][u] == m) ? g[ch][u] : 0.f;
+                    }
+                }
             }
+            // rows w*CH.. of s_c are written and read by this wave only, whose LDS operations keep their order
+#pragma unroll 1
+            for (int i = lo; i < hi; ++i)
+#pragma unroll
+                for (int ch = 0; ch < CH; ++ch) acc[ch] += s_c[w * CH + ch][i + lane];
         }
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch)
-            if (on && c0 + ch < C) __builtin_nontemporal_store(acc[ch], &grad_feat[(b * C + c0 + ch) * N + m]);
+            if (lane < np && c0 + ch < C)
+                __builtin_nontemporal_store(acc[ch], &grad_feat[(b * C + c0 + ch) * N + m0 + lane]);
     }
 }
 
@@ -498,7 +537,7 @@ hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argm
     } else if (!bnc && L < (1 << 30)) {
         const int tpc = (N + 63) / 64;
         const int64_t tiles = (int64_t)B * tpc;
-        hipLaunchKernelGGL(pool_bwd_gather_bcn_kernel<4>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
+        hipLaunchKernelGGL(pool_bwd_gather_bcn_kernel<512>, dim3(xcd_grid(tiles)), dim3(256), 0, s, grad_out,
                            argmax, in_off, in_src, grad_feat, N, L, C, tpc, tiles);
     } else {
         const int64_t total = (int64_t)B * N * C;
