@@ -267,8 +267,11 @@ def main():
             oracle.flexpool_bwd(x.grad_out if Din == Dout else x.feat, a_full, l_range=(l0, l1))
             return time.perf_counter() - t
 
-        # a short probe sizes the slice so that the timed pass is about 15 s of CPU work
+        # two short probes size the slice so that the timed pass is about 15 s of CPU work (the first one is
+        # dominated by thread start-up and cold pages, so it only sizes the second)
         probe = min(N, 20000)
+        per_pt = max(oracle_pass(0, probe) / probe, 1e-9)
+        probe = int(min(N, max(probe, 2.0 / per_pt)))
         per_pt = max(oracle_pass(0, probe) / probe, 1e-9)
         n_slice = int(min(N, max(probe, 15.0 / per_pt)))
         t_slice = oracle_pass(0, n_slice)

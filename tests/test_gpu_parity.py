@@ -162,6 +162,31 @@ def test_flexpool_matches_oracle_bit_exactly(B, N, K, C, layout):
     assert torch.equal(gf2, gf3)                                                          # fixed order
 
 
+@pytest.mark.parametrize("layout", [fx.BNC, fx.BCN], ids=["bnc", "bcn"])
+def test_flexpool_hub_point_and_unlisted_points(layout):
+    # one point that every centre lists (an in-edge list of N entries), many points that nobody lists
+    say(f"pool hub layout={layout}")
+    B, N, K, C = 2, 3000, 5, 20
+    rng = np.random.default_rng(77)
+    feat = rng.standard_normal((B, C, N)).astype(np.float32)
+    feat[:, ::2, 0] = 10.0                                   # the hub wins every other channel everywhere
+    nbr = rng.integers(0, N // 3, size=(B, K, N)).astype(np.int32)   # the upper two thirds are never listed
+    nbr[:, 0, :] = 0
+    nbr[:, 1, :] = 0                                         # listed twice by every centre
+    g = rng.standard_normal((B, C, N)).astype(np.float32)
+    ro, ra = oracle.flexpool_fwd(feat, nbr)
+    dnbr = dev(nbr)
+    out, arg = fx.flexpool_fwd(to_layout(feat, layout), dnbr, layout=layout)
+    gf = fx.flexpool_bwd(to_layout(g, layout), arg, layout=layout, in_edges=fx.flex_inedges_build(dnbr))
+    torch.cuda.synchronize()
+    assert np.array_equal(from_layout(arg, layout), ra)
+    assert np.array_equal(from_layout(out, layout).view(np.uint32), ro.view(np.uint32))
+    rgf = oracle.flexpool_bwd(g, ra)
+    got = from_layout(gf, layout)
+    assert rel_err(got, rgf) <= 1e-5
+    assert not got[:, :, N // 3:].any()
+
+
 def test_validate_neighbors_counts_out_of_range():
     nbr = np.zeros((2, 3, 50), np.int32)
     nbr[0, 1, 4] = 50
