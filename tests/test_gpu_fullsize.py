@@ -103,3 +103,13 @@ def test_full_size_config(ci):
         ref = oracle.flexpool_bwd(gp.transpose(1, 2).contiguous().cpu().numpy(), pa.transpose(1, 2).contiguous().cpu().numpy())
         cols = rng.integers(0, N, size=4000)
         assert rel_err(pg[:, torch.from_numpy(cols).cuda(), :].transpose(1, 2).cpu().numpy(), ref[:, :, cols]) <= 1e-5
+        # the channel-major kernels at this size: same winners, same bits; the gather sums in the same (list) order
+        say("  pooling, channel-major")
+        po_c, pa_c = fx.flexpool_fwd(feat.transpose(1, 2).contiguous(), nbr, layout=fx.BCN)
+        assert torch.equal(pa_c.transpose(1, 2), pa)
+        assert torch.equal(po_c.transpose(1, 2).view(torch.int32), po.view(torch.int32))
+        del po_c
+        pg_c = fx.flexpool_bwd(gp.transpose(1, 2).contiguous(), pa_c, layout=fx.BCN, in_edges=pool_edges)
+        torch.cuda.synchronize()
+        assert torch.equal(pg_c.transpose(1, 2), pg)
+        del pg_c, pa_c
