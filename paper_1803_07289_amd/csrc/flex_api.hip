@@ -29,6 +29,16 @@ hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, con
                                    const float *g_half, float *partials, int B, int N, int K, int *n_wg,
                                    hipStream_t s);
 
+// layers with both widths multiples of 128 as passes over column blocks (same file, same two shapes)
+bool split_wide_ok(int N, int K, int max_width);
+hipError_t launch_gc_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
+                                const int32_t *off, const int32_t *src, const void *thetaP, float *out_blk, int os,
+                                int B, int N, int K, int csr, int accumulate, hipStream_t s);
+hipError_t launch_gt_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
+                                const float *g_blk, int gst, float *partials, int B, int N, int K, int *n_wg,
+                                hipStream_t s);
+int split_wide_partials(int B, int N);
+
 hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,
                                   int Dout, float *grad_theta, float *grad_bias, hipStream_t s);
 
@@ -159,6 +169,76 @@ static hipError_t split_grad_theta_128(const float *rows, const float *pos, cons
     return hipSuccess;
 }
 
+// Wide layers (both widths multiples of 128, not 128 -> 128 itself): the paper's network doubles the feature
+// length at every resolution stage (Sec. 5), so its deeper stages are of this kind.  They run as passes of the
+// 64 -> 128 (forward, feature gradient) and 64 -> 64 (parameter gradients) lean kernels over column blocks of the
+// point-major tensors.
+static bool split_disabled()
+{
+    static const bool off = [] { const char *v = getenv("FLEX_SPLIT"); return v != nullptr && v[0] == '0'; }();
+    return off;
+}
+static bool wide_shape(int Din, int Dout)
+{
+    return !split_disabled() && Din % 128 == 0 && Dout % 128 == 0 && (Din > 128 || Dout > 128);
+}
+static size_t wide_param_scratch_bytes()
+{
+    return align256(sizeof(float) * 4 * 64 * 128) + theta_f16_bytes(64, 128);
+}
+
+// Forward (transpose == 0: rows = features [.., Din], out [.., Dout]) or feature gradient (transpose == 1:
+// rows = upstream gradient [.., Dout], out = grad_feat [.., Din]; in-edge lists) of a wide layer.
+static hipError_t wide_gather_contract(const float *rows, const float *pos, const int32_t *nbr, const int32_t *off,
+                                       const int32_t *src, const float *theta, const float *bias, void *scratch,
+                                       float *out, int B, int N, int K, int Din, int Dout, int transpose,
+                                       hipStream_t s)
+{
+    float *blk_theta = (float *)scratch, *blk_bias = blk_theta + 3 * 64 * 128;
+    void *packed = (char *)scratch + align256(sizeof(float) * 4 * 64 * 128);
+    const int w_in = transpose ? Dout : Din, w_out = transpose ? Din : Dout;   // gathered / written widths
+    for (int j = 0; j < w_out / 128; ++j)
+        for (int i = 0; i < w_in / 64; ++i) {
+            hipError_t e;
+            if (!transpose) {
+                e = launch_param_block((float *)theta, (float *)bias, blk_theta, blk_bias, Din, Dout, 64 * i, 128 * j,
+                                       64, 128, 0, s);
+                if (e != hipSuccess) return e;
+                e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 64, 128, 64, 128, 0, s);
+            } else {
+                e = launch_param_block((float *)theta, (float *)bias, blk_theta, blk_bias, Din, Dout, 128 * j, 64 * i,
+                                       128, 64, 0, s);
+                if (e != hipSuccess) return e;
+                e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 128, 64, 64, 128, 1, s);
+            }
+            if (e != hipSuccess) return e;
+            e = launch_gc_split_wide(rows + 64 * i, w_in, pos, nbr, off, src, packed, out + 128 * j, w_out, B, N, K,
+                                     transpose, i > 0, s);
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
+}
+
+// Parameter gradients of a wide layer: (Din/64) x (Dout/64) blocks of [4*64 x 64].  scratch: room for one block.
+static hipError_t wide_grad_theta(const float *rows, const float *pos, const int32_t *nbr, const float *g_rows,
+                                  float *partials, void *scratch, float *grad_theta, float *grad_bias, int B, int N,
+                                  int K, int Din, int Dout, hipStream_t s)
+{
+    float *blk_theta = (float *)scratch, *blk_bias = blk_theta + 3 * 64 * 64;
+    for (int hi = 0; hi < Din / 64; ++hi)
+        for (int ho = 0; ho < Dout / 64; ++ho) {
+            int n_wg = 0;
+            hipError_t e = launch_gt_split_wide(rows + 64 * hi, Din, pos, nbr, g_rows + 64 * ho, Dout, partials, B, N,
+                                                K, &n_wg, s);
+            if (e != hipSuccess) return e;
+            e = launch_reduce_partials(partials, n_wg, 64, 64, 64, 64, blk_theta, blk_bias, s);
+            if (e != hipSuccess) return e;
+            e = launch_param_block(grad_theta, grad_bias, blk_theta, blk_bias, Din, Dout, 64 * hi, 64 * ho, 64, 64, 1, s);
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
+}
+
 // Packs (theta, bias) for launch_gather_contract in the format that kernel wants.
 static hipError_t pack_for_contract(const float *theta, const float *bias, void *thetaP, int Din,
                                     int Dout, int transpose, int fmt, hipStream_t s)
@@ -226,22 +306,24 @@ hipError_t launch_grad_theta(const float *rows, const float *pos, const int32_t 
 
 // ---- workspace plans -----------------------------------------------------------
 struct FwdPlan {
-    bool tiled;
-    size_t thetaP, featT, total;   // byte offsets / total
+    bool tiled, wide;
+    size_t thetaP, featT, outT, total;   // byte offsets / total
 };
 struct BwdPlan {
-    bool tiled;
-    size_t thetaP, featT, gT, partials, in_off, in_src, inedge_ws, total;
+    bool tiled, wide;
+    size_t thetaP, featT, gT, gfT, partials, in_off, in_src, inedge_ws, total;
 };
 
 static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout)
 {
     FwdPlan p{};
     p.tiled = gather_contract_supported(Din, Dout);
+    p.wide = !p.tiled && wide_shape(Din, Dout);
     size_t at = 0;
-    if (p.tiled) {
-        p.thetaP = at; at += theta_ws_bytes(Din, Dout);
+    if (p.tiled || p.wide) {
+        p.thetaP = at; at += p.wide ? wide_param_scratch_bytes() : theta_ws_bytes(Din, Dout);
         if (layout == FLEX_LAYOUT_BCN) { p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din); }
+        if (layout == FLEX_LAYOUT_BCN && p.wide) { p.outT = at; at += align256(sizeof(float) * (size_t)(B * N) * Dout); }
     }
     p.total = at > 0 ? at : 256;
     return p;
@@ -251,14 +333,18 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
 {
     BwdPlan p{};
     p.tiled = gather_contract_supported(Din, Dout) && gather_contract_supported(Dout, Din);
+    p.wide = !p.tiled && wide_shape(Din, Dout);
     size_t at = 0;
-    if (p.tiled) {
-        p.thetaP = at; at += theta_ws_bytes(Dout, Din);
+    if (p.tiled || p.wide) {
+        p.thetaP = at; at += p.wide ? wide_param_scratch_bytes() : theta_ws_bytes(Dout, Din);
         if (layout == FLEX_LAYOUT_BCN) {
             p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din);
             p.gT = at;    at += align256(sizeof(float) * (size_t)(B * N) * Dout);
+            if (p.wide) { p.gfT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din); }
         }
-        p.partials = at; at += grad_theta_partial_bytes(B, N, Din, Dout);
+        p.partials = at;
+        at += p.wide ? align256(sizeof(float) * (size_t)split_wide_partials((int)B, (int)N) * 4 * 64 * 64)
+                     : grad_theta_partial_bytes(B, N, Din, Dout);
         if (build) {
             p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
             p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
@@ -351,7 +437,10 @@ const char *flex_status_string(int status)
     }
 }
 
-int flexconv_has_fast_path(int Din, int Dout) { return gather_contract_supported(Din, Dout) ? 1 : 0; }
+int flexconv_has_fast_path(int Din, int Dout)
+{
+    return (gather_contract_supported(Din, Dout) || wide_shape(Din, Dout)) ? 1 : 0;
+}
 
 size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, int layout)
 {
@@ -382,6 +471,19 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int bcn = (layout == FLEX_LAYOUT_BCN);
+    if (p.wide && split_wide_ok(N, K, Din > Dout ? Din : Dout)) {
+        const float *rows = feat;
+        float *dst = out;
+        if (bcn) {
+            FLEX_HIP(launch_bcn_to_bnc(feat, (float *)(ws + p.featT), B, Din, N, s));
+            rows = (float *)(ws + p.featT);
+            dst = (float *)(ws + p.outT);
+        }
+        FLEX_HIP(wide_gather_contract(rows, pos, nbr, nullptr, nullptr, theta, bias, ws + p.thetaP, dst, B, N, K, Din,
+                                      Dout, 0, s));
+        if (bcn) FLEX_HIP(launch_bnc_to_bcn(dst, out, B, Dout, N, s));
+        return FLEX_OK;
+    }
     if (!p.tiled) {
         FLEX_HIP(launch_generic_fwd(feat, pos, nbr, theta, bias, out, B, N, K, Din, Dout, !bcn, s));
         return FLEX_OK;
@@ -430,6 +532,33 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int bcn = (layout == FLEX_LAYOUT_BCN);
+    if (p.wide && split_wide_ok(N, K, Din > Dout ? Din : Dout)) {
+        const float *rows = feat, *g_rows = grad_out;
+        if (bcn) {
+            FLEX_HIP(launch_bcn_to_bnc(grad_out, (float *)(ws + p.gT), B, Dout, N, s));
+            g_rows = (float *)(ws + p.gT);
+            if (grad_theta) {
+                FLEX_HIP(launch_bcn_to_bnc(feat, (float *)(ws + p.featT), B, Din, N, s));
+                rows = (float *)(ws + p.featT);
+            }
+        }
+        if (grad_theta)
+            FLEX_HIP(wide_grad_theta(rows, pos, nbr, g_rows, (float *)(ws + p.partials), ws + p.thetaP, grad_theta,
+                                     grad_bias, B, N, K, Din, Dout, s));
+        if (grad_feat) {
+            if (build) {
+                int32_t *off = (int32_t *)(ws + p.in_off), *src = (int32_t *)(ws + p.in_src);
+                FLEX_HIP(launch_inedges_build(nbr, B, N, K, off, src, ws + p.inedge_ws, s));
+                in_off = off;
+                in_src = src;
+            }
+            float *dst = bcn ? (float *)(ws + p.gfT) : grad_feat;
+            FLEX_HIP(wide_gather_contract(g_rows, pos, nullptr, in_off, in_src, theta, bias, ws + p.thetaP, dst, B, N,
+                                          K, Din, Dout, 1, s));
+            if (bcn) FLEX_HIP(launch_bnc_to_bcn(dst, grad_feat, B, Din, N, s));
+        }
+        return FLEX_OK;
+    }
     if (!p.tiled) {
         FLEX_HIP(launch_generic_bwd(feat, pos, nbr, theta, bias, grad_out, grad_feat, grad_theta,
                                     grad_bias, B, N, K, Din, Dout, !bcn, s));

@@ -217,7 +217,74 @@ hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, con
 }
 #endif
 
+#if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 128
+// Layers whose widths are multiples of 128 (point-major) run as passes of this shape's lean kernels over column
+// blocks: 64 gathered channels (rows rs floats apart) against a [4*64 x 128] block of the parameters, into 128
+// output channels (rows os floats apart), adding to what is there when accumulate is set.
+bool split_wide_ok(int N, int K, int max_width)
+{
+    if (contract_in_fp32() || lean_producer_mode() == 0) return false;
+    return (int64_t)N * max_width * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32) &&
+           (int64_t)K * N * 4 < (1ll << 32);
+}
+
+hipError_t launch_gc_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
+                                const int32_t *off, const int32_t *src, const void *thetaP, float *out_blk, int os,
+                                int B, int N, int K, int csr, int accumulate, hipStream_t s)
+{
+    using W = WsGeom<S, 1>;
+    const int tpc = (N + W::T - 1) / W::T;
+    const int64_t tot64 = (int64_t)B * tpc;
+    if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int tot = (int)tot64;
+    const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
+    const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
+#define FLEX_GC_WIDE(ACC, TAIL)                                                                                   \
+    hipLaunchKernelGGL((gather_contract_lean_strided_kernel<S, 1, ACC, TAIL>), g, blk, 0, s, rows_blk, pos, nbr,  \
+                       thetaP, exp_off, out_blk, N, K, tpc, tot, rs, os)
+    if (!csr) {
+        const bool tail = (K % 8) != 0;
+        if (accumulate) { if (tail) FLEX_GC_WIDE(true, true); else FLEX_GC_WIDE(true, false); }
+        else            { if (tail) FLEX_GC_WIDE(false, true); else FLEX_GC_WIDE(false, false); }
+    } else {
+        if (accumulate) hipLaunchKernelGGL((grad_feat_lean_strided_kernel<S, 1, true>), g, blk, 0, s, rows_blk, pos, off, src, thetaP, exp_off, out_blk, N, tpc, tot, rs, os);
+        else hipLaunchKernelGGL((grad_feat_lean_strided_kernel<S, 1, false>), g, blk, 0, s, rows_blk, pos, off, src, thetaP, exp_off, out_blk, N, tpc, tot, rs, os);
+    }
+#undef FLEX_GC_WIDE
+    return hipGetLastError();
+}
+#endif
+
 #if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 64
+// One [4*64 x 64] block of the parameter gradient of a wide layer: the aggregate of 64 channels of the feature
+// rows (rs floats apart) against 64 channels of the upstream gradient rows (gst floats apart).
+hipError_t launch_gt_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
+                                const float *g_blk, int gst, float *partials, int B, int N, int K, int *n_wg,
+                                hipStream_t s)
+{
+    using WL = WsGeom<S, 2, 2>;
+    const int tpc = (N + WL::T - 1) / WL::T;
+    const int64_t tot64 = (int64_t)B * tpc;
+    if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int tot = (int)tot64;
+    *n_wg = persistent_grid(tot, 1);
+    if (K % 8 == 0)
+        hipLaunchKernelGGL((grad_theta_lean_strided_kernel<S, false>), dim3(*n_wg), dim3(WL::NT), 0, s, rows_blk, pos,
+                           nbr, g_blk, partials, N, K, tpc, tot, rs, gst);
+    else
+        hipLaunchKernelGGL((grad_theta_lean_strided_kernel<S, true>), dim3(*n_wg), dim3(WL::NT), 0, s, rows_blk, pos,
+                           nbr, g_blk, partials, N, K, tpc, tot, rs, gst);
+    return hipGetLastError();
+}
+
+// workgroups (= partial sums) that launch_gt_split_wide starts for this size
+int split_wide_partials(int B, int N)
+{
+    using WL = WsGeom<S, 2, 2>;
+    const int64_t tot = (int64_t)B * ((N + WL::T - 1) / WL::T);
+    return persistent_grid(tot > 0x7fffffff ? 0x7fffffff : (int)tot, 1);
+}
+
 // One [4*64 x 64] block of the parameter gradient of a 128 -> 128 layer: the aggregate of a 64-channel half of
 // the 128-wide feature rows against a 64-channel half of the 128-wide upstream gradient rows.
 hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr,

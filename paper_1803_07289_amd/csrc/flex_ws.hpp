@@ -509,7 +509,8 @@ __device__ __forceinline__ void producer_loop(Producer<S, CSR> &Pr, const TileSc
 // ---------------------------------------------------------------------------
 // SUM == true: only the plain neighbour sum (component j = 3 of the aggregate) is formed; no positions
 // are read (used by the location-gradient kernels).
-// RS = floats between consecutive rows of the gathered tensor (S::DI unless the rows are a column block of a wider one)
+// RS = floats between consecutive rows of the gathered tensor (S::DI unless the rows are a column block of a wider
+// one); RS == 0: the stride is the run-time value set with set_row_stride() (one multiply per row instead of a shift).
 // TAIL: K is not a multiple of 8; the last batch of a tile has slots past K, which are read from slot K-1 and
 // weighted 0 (the weight travels as the fourth position component; in the plain-sum mode it is a wave-uniform
 // 0 / 1 per slot), and its rows 4..7 are skipped when empty.
@@ -527,6 +528,9 @@ struct LeanProducer {
     const float *rows, *pos;
     const int32_t *nbr;
     int N, K, KB, pw;
+    unsigned rs_rt = 0;          // row stride in floats when RS == 0
+    __device__ __forceinline__ void set_row_stride(int rs) { rs_rt = (unsigned)rs; }
+    __device__ __forceinline__ unsigned row_stride() const { if constexpr (RS != 0) return RS; else return rs_rt; }
     int count, tiles_per_cloud;  // tiles of this workgroup
     TileSchedule sched;
     // compute layout: lane = (row group grp, lane t inside the row)
@@ -616,7 +620,7 @@ struct LeanProducer {
 
     __device__ __forceinline__ void load_row(float (&fr)[S::VEC], int id, const char *rb) const
     {
-        const char *p = rb + ((unsigned)id * (4u * RS) + lane_off);
+        const char *p = rb + ((unsigned)id * (4u * row_stride()) + lane_off);
         if constexpr (S::VEC == 4) {
             const v4f v = *reinterpret_cast<const v4f *>(p);
             fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
@@ -660,7 +664,7 @@ struct LeanProducer {
             // end of every iteration: the wait at the loop top (for positions and ids) is one instruction
             // for both ways in, and a load issued after the rows would turn it into a wait for the rows.
             __builtin_amdgcn_sched_barrier(0);
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * RS);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x0.b * N * row_stride());
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (!TAIL || u < 4 || x0.k0 + 4 < K) load_row(f[u], spread(id0, perm_id, u), rb);
@@ -693,7 +697,7 @@ struct LeanProducer {
             advance(walk);
             const Batch x2 = get(walk);
             load_ids(idn, x2);
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * RS);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * row_stride());
             const int nb = x1.b, nlw0 = x1.lw0;
             x1 = x2;
             float dpc[U];
@@ -764,6 +768,9 @@ struct LeanCsrProducer {
     const float *rows, *pos;
     const int32_t *off, *src;
     int N, pw;
+    unsigned rs_rt = 0;          // row stride in floats when RS == 0
+    __device__ __forceinline__ void set_row_stride(int rs) { rs_rt = (unsigned)rs; }
+    __device__ __forceinline__ unsigned row_stride() const { if constexpr (RS != 0) return RS; else return rs_rt; }
     int count, tiles_per_cloud;
     TileSchedule sched;
     int grp, t;
@@ -875,7 +882,7 @@ struct LeanCsrProducer {
     }
     __device__ __forceinline__ void load_row(float (&fr)[S::VEC], int id, const char *rb) const
     {
-        const char *p = rb + ((unsigned)id * (4u * RS) + lane_off);
+        const char *p = rb + ((unsigned)id * (4u * row_stride()) + lane_off);
         if constexpr (S::VEC == 4) {
             const v4f v = *reinterpret_cast<const v4f *>(p);
             fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
@@ -913,7 +920,7 @@ struct LeanCsrProducer {
             pn[0] = pn[1] = pc = 0.f;
             if constexpr (!SUM) load_pos(pn, pc, id0, d0);
             __builtin_amdgcn_sched_barrier(0);      // rows youngest, as at the end of every iteration
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * RS);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * row_stride());
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (u < 4 || d0.upper) load_row(f[u], spread(id0, perm_id, u), rb);
@@ -934,7 +941,7 @@ struct LeanCsrProducer {
 #pragma unroll
             for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
             if constexpr (!SUM) load_pos(pn, pc, idn, d1);
-            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * RS);
+            const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * row_stride());
             d0 = d1;
             fetch(c, idn, d1);
             float dpc[U];
@@ -982,12 +989,14 @@ struct LeanCsrProducer {
 
 // One consumer wave of the split-half contraction: out tile = A tile * Theta for every tile of
 // the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
-// OS = floats between consecutive output rows (point-major form), ACC: add to what out holds.
+// OS = floats between consecutive output rows (point-major form; 0: the run-time value os_rt), ACC: add to what
+// out holds.
 template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false>
 __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ thetaP, int theta_exp_off,
                                              float *__restrict__ out, int N, const TileSchedule &sc,
-                                             int tiles_per_cloud, const char *s_A, const int *s_E)
+                                             int tiles_per_cloud, const char *s_A, const int *s_E, int os_rt = 0)
 {
+    const int os = OS != 0 ? OS : os_rt;
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
     // item = (slice, block); consumer cw owns items cw, cw+NC, ... ; all share one slice
     static_assert(G::NS <= G::NC, "one parameter slice per consumer wave");
@@ -1007,7 +1016,7 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
                 for (int i = 0; i < 4; ++i)
                     if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
             } else {
-                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * OS + o;
+                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * os + o;
                 if constexpr (S::DO % 4 == 0) {
                     if (o < S::DO) {
                         if constexpr (ACC) d += *reinterpret_cast<const v4f *>(dst);
@@ -1083,12 +1092,12 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
 // counts is how many rows the CU has in flight; the f16 contraction is cheap enough for a
 // quarter of the waves.
 // ---------------------------------------------------------------------------
-template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false, bool TAIL = false>
-__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
-                                 const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
-                                 int theta_exp_off, float *__restrict__ out, int N, int K,
-                                 int tiles_per_cloud, int total_tiles)
+template <class S, bool OUT_BCN, int PM, int RS, int OS, bool ACC, bool TAIL>
+__device__ __forceinline__ void gather_contract_lean_body(const float *__restrict__ rows, const float *__restrict__ pos,
+                                                          const int32_t *__restrict__ nbr,
+                                                          const void *__restrict__ thetaP, int theta_exp_off,
+                                                          float *__restrict__ out, int N, int K, int tiles_per_cloud,
+                                                          int total_tiles, int rs_rt, int os_rt)
 {
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
@@ -1111,6 +1120,7 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
     if (w < G::NP) {
         LeanProducer<S, PM, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
+        P.set_row_stride(rs_rt);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
             store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
@@ -1118,16 +1128,42 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
         });
         return;
     }
-    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
+    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E,
+                                         os_rt);
+}
+
+template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false, bool TAIL = false>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                 const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
+                                 int theta_exp_off, float *__restrict__ out, int N, int K,
+                                 int tiles_per_cloud, int total_tiles)
+{
+    static_assert(RS != 0 && OS != 0, "run-time strides go through gather_contract_lean_strided_kernel");
+    gather_contract_lean_body<S, OUT_BCN, PM, RS, OS, ACC, TAIL>(rows, pos, nbr, thetaP, theta_exp_off, out, N, K,
+                                                                  tiles_per_cloud, total_tiles, 0, 0);
+}
+
+// The same kernel for column blocks of wider point-major tensors: rs / os = floats between consecutive rows of the
+// gathered tensor / of the output.
+template <class S, int PM, bool ACC, bool TAIL>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void gather_contract_lean_strided_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                         const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
+                                         int theta_exp_off, float *__restrict__ out, int N, int K,
+                                         int tiles_per_cloud, int total_tiles, int rs, int os)
+{
+    gather_contract_lean_body<S, false, PM, 0, 0, ACC, TAIL>(rows, pos, nbr, thetaP, theta_exp_off, out, N, K,
+                                                             tiles_per_cloud, total_tiles, rs, os);
 }
 
 // Feature gradient with the lean in-edge producers (same consumers as the forward kernel).
-template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
-__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
-                           const int32_t *__restrict__ off, const int32_t *__restrict__ src,
-                           const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
-                           int N, int tiles_per_cloud, int total_tiles)
+template <class S, bool OUT_BCN, int PM, int RS, int OS, bool ACC>
+__device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ rows, const float *__restrict__ pos,
+                                                    const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                                                    const void *__restrict__ thetaP, int theta_exp_off,
+                                                    float *__restrict__ out, int N, int tiles_per_cloud,
+                                                    int total_tiles, int rs_rt, int os_rt)
 {
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
@@ -1148,6 +1184,7 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
     if (w < G::NP) {
         LeanCsrProducer<S, PM, false, RS> P;
         P.init(rows, pos, off, src, N, w, sc, tiles_per_cloud);
+        P.set_row_stride(rs_rt);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
             store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
@@ -1155,7 +1192,31 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
         });
         return;
     }
-    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E);
+    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E,
+                                         os_rt);
+}
+
+template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                           const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                           const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
+                           int N, int tiles_per_cloud, int total_tiles)
+{
+    static_assert(RS != 0 && OS != 0, "run-time strides go through grad_feat_lean_strided_kernel");
+    grad_feat_lean_body<S, OUT_BCN, PM, RS, OS, ACC>(rows, pos, off, src, thetaP, theta_exp_off, out, N,
+                                                     tiles_per_cloud, total_tiles, 0, 0);
+}
+
+template <class S, int PM, bool ACC>
+__global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_feat_lean_strided_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                   const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                                   const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
+                                   int N, int tiles_per_cloud, int total_tiles, int rs, int os)
+{
+    grad_feat_lean_body<S, false, PM, 0, 0, ACC>(rows, pos, off, src, thetaP, theta_exp_off, out, N, tiles_per_cloud,
+                                                 total_tiles, rs, os);
 }
 
 template <class S, bool CSR, bool OUT_BCN, bool F16>
@@ -1433,12 +1494,14 @@ __device__ __forceinline__ bf8 read_tr_frag(const char *tile, int stride, int p0
 }
 
 // RS / GST = floats between consecutive rows of the gathered tensor / of the upstream gradient
-template <class S, int RS = S::DI, int GST = S::DO, bool TAIL = false>
-__global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
-                            const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
-                            float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles)
+template <class S, int RS, int GST, bool TAIL>
+__device__ __forceinline__ void grad_theta_lean_body(const float *__restrict__ rows, const float *__restrict__ pos,
+                                                     const int32_t *__restrict__ nbr,
+                                                     const float *__restrict__ g_rows, float *__restrict__ partials,
+                                                     int N, int K, int tiles_per_cloud, int total_tiles, int rs_rt,
+                                                     int gst_rt)
 {
+    const int gst = GST != 0 ? GST : gst_rt;
     using G = WsGeom<S, 2, 2>;
     static_assert(G::T == 32, "one 32-point depth step of the matrix op per tile");
     constexpr int AS = bf3_stride(S::KD), GS = bf3_stride(S::DOP);
@@ -1451,6 +1514,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
     if (w < G::NP) {
         LeanProducer<S, 2, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
+        P.set_row_stride(rs_rt);
         // grad_out tile: T*DOP/4 four-float chunks over the producer threads, one tile ahead in registers
         constexpr int CPR = S::DOP / 4;                      // chunks per point
         constexpr int NCH = cdiv_c(G::T * CPR, 64 * G::NP);  // chunks per thread
@@ -1463,7 +1527,7 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
                 const int pt = ch / CPR, o = 4 * (ch % CPR);
                 gv[c] = v4f{0.f, 0.f, 0.f, 0.f};
                 if (ch < G::T * CPR && l0 + pt < N) {        // points past the cloud contribute nothing
-                    const float *src = g_rows + ((int64_t)b * N + l0 + pt) * GST + o;
+                    const float *src = g_rows + ((int64_t)b * N + l0 + pt) * gst + o;
                     if constexpr (S::DO % 4 == 0) {
                         if (o < S::DO) gv[c] = *reinterpret_cast<const v4f *>(src);
                     } else {
@@ -1596,6 +1660,28 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
                 dst[(int64_t)(mb * 16 + 4 * q + i) * S::DOP + nb * 16 + r16] = sum[i];
         }
     }
+}
+
+// RS / GST = floats between consecutive rows of the gathered tensor / of the upstream gradient
+template <class S, int RS = S::DI, int GST = S::DO, bool TAIL = false>
+__global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                            const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
+                            float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles)
+{
+    static_assert(RS != 0 && GST != 0, "run-time strides go through grad_theta_lean_strided_kernel");
+    grad_theta_lean_body<S, RS, GST, TAIL>(rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total_tiles, 0, 0);
+}
+
+// The same for column blocks of wider point-major tensors (strides as run-time values).
+template <class S, bool TAIL>
+__global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_theta_lean_strided_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                    const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
+                                    float *__restrict__ partials, int N, int K, int tiles_per_cloud,
+                                    int total_tiles, int rs, int gst)
+{
+    grad_theta_lean_body<S, 0, 0, TAIL>(rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total_tiles, rs, gst);
 }
 
 // ---------------------------------------------------------------------------

@@ -50,6 +50,10 @@ SHAPES = [
     (2, 333, 12, 64, 64),      # masked tail batch whose lower half is full
     (1, 250, 20, 32, 64),      # three batches, the last one half empty
     (1, 500, 13, 9, 64),       # masked tail, single-float lanes
+    (1, 333, 8, 256, 256),     # wide layers: passes over 64- / 128-channel column blocks
+    (2, 150, 8, 128, 256),
+    (1, 200, 16, 256, 128),
+    (1, 130, 9, 384, 128),     # masked tail in the block passes
     (2, 150, 6, 5, 7),         # no tiled kernel: generic path
     (1, 90, 4, 20, 16),        # generic path, Din % 4 == 0
 ]
