@@ -102,7 +102,7 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
  * to grad_pos[b,d,n] with + and to grad_pos[b,d,l] with -.  grad_pos is [B,3,N] like pos,
  * overwritten.  Evaluated from plain neighbourhood sums (of feat over each point's neighbours, of
  * grad_out over the centres that list it) and one small contraction per point, without
- * floating-point atomics when the shape has a matrix-core kernel (flexconv_has_fast_path);
+ * floating-point atomics when both widths are among the tiled ones listed at flexconv_has_fast_path;
  * otherwise by a direct kernel with fp32 atomic adds (summation order, hence the last bits,
  * may vary).  in_off / in_src as for flexconv_bwd (NULL: built in the workspace).
  */
@@ -303,7 +303,10 @@ size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, 
 int flex_validate_neighbors(const int32_t *nbr, int B, int N, int K,
                             int32_t *bad_count_dev, void *stream);
 
-/* 1 if (Din,Dout) runs on the tiled matrix-core kernels, 0 if on the generic ones. */
+/* 1 if flexconv_fwd / flexconv_bwd run (Din,Dout) on the matrix-core kernels: the tiled widths 32->32, 64->64,
+ * 128->128, 9->64, 64->9, 32->64, 64->32, 64->128, 128->64, and every pair of multiples of 128 (run as passes over
+ * 64- / 128-channel column blocks; the deeper stages of the network of Sec. 5, whose feature length doubles from
+ * stage to stage).  0: the direct-form kernels (any widths, orders of magnitude slower). */
 int flexconv_has_fast_path(int Din, int Dout);
 
 const char *flex_status_string(int status);

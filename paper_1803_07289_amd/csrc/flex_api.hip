@@ -31,13 +31,15 @@ hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, con
 
 // layers with both widths multiples of 128 as passes over column blocks (same file, same two shapes)
 bool split_wide_ok(int N, int K, int max_width);
-hipError_t launch_gc_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
-                                const int32_t *off, const int32_t *src, const void *thetaP, float *out_blk, int os,
-                                int B, int N, int K, int csr, int accumulate, hipStream_t s);
-hipError_t launch_gt_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
-                                const float *g_blk, int gst, float *partials, int B, int N, int K, int *n_wg,
+hipError_t launch_gc_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const int32_t *off,
+                                const int32_t *src, const void *thetaP_all, float *out, int os, int n_in, int n_out,
+                                int B, int N, int K, int csr, hipStream_t s);
+hipError_t launch_gt_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const float *g_rows,
+                                int gst, float *partials, int n_hi, int n_ho, int chunks, int B, int N, int K,
                                 hipStream_t s);
-int split_wide_partials(int B, int N);
+int split_wide_gt_chunks(int B, int N, int blocks);
+hipError_t launch_reduce_partials_blocks(const float *partials, int n_wg, int first, int count, int n_ho, int Din,
+                                         int Dout, float *grad_theta, float *grad_bias, hipStream_t s);
 
 hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,
                                   int Dout, float *grad_theta, float *grad_bias, hipStream_t s);
@@ -180,63 +182,46 @@ static bool split_disabled()
 }
 static bool wide_shape(int Din, int Dout)
 {
-    return !split_disabled() && Din % 128 == 0 && Dout % 128 == 0 && (Din > 128 || Dout > 128);
+    return !split_disabled() && Din % 128 == 0 && Dout % 128 == 0 && (Din > 128 || Dout > 128) &&
+           (int64_t)(Din / 64) * (Dout / 64) <= 65535;      // one grid row of the reduction per block
 }
-static size_t wide_param_scratch_bytes()
+// packed parameter blocks of the whole layer (forward / feature gradient)
+static size_t wide_param_scratch_bytes(int Din, int Dout)
 {
-    return align256(sizeof(float) * 4 * 64 * 128) + theta_f16_bytes(64, 128);
+    const size_t blocks = (size_t)(Din / 64) * (Dout / 64) / 2;     // 64 x 128 each, either way round
+    return blocks * theta_f16_bytes(64, 128);
 }
 
 // Forward (transpose == 0: rows = features [.., Din], out [.., Dout]) or feature gradient (transpose == 1:
-// rows = upstream gradient [.., Dout], out = grad_feat [.., Din]; in-edge lists) of a wide layer.
+// rows = upstream gradient [.., Dout], out = grad_feat [.., Din]; in-edge lists) of a wide layer: two launches.
 static hipError_t wide_gather_contract(const float *rows, const float *pos, const int32_t *nbr, const int32_t *off,
                                        const int32_t *src, const float *theta, const float *bias, void *scratch,
                                        float *out, int B, int N, int K, int Din, int Dout, int transpose,
                                        hipStream_t s)
 {
-    float *blk_theta = (float *)scratch, *blk_bias = blk_theta + 3 * 64 * 128;
-    void *packed = (char *)scratch + align256(sizeof(float) * 4 * 64 * 128);
     const int w_in = transpose ? Dout : Din, w_out = transpose ? Din : Dout;   // gathered / written widths
-    for (int j = 0; j < w_out / 128; ++j)
-        for (int i = 0; i < w_in / 64; ++i) {
-            hipError_t e;
-            if (!transpose) {
-                e = launch_param_block((float *)theta, (float *)bias, blk_theta, blk_bias, Din, Dout, 64 * i, 128 * j,
-                                       64, 128, 0, s);
-                if (e != hipSuccess) return e;
-                e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 64, 128, 64, 128, 0, s);
-            } else {
-                e = launch_param_block((float *)theta, (float *)bias, blk_theta, blk_bias, Din, Dout, 128 * j, 64 * i,
-                                       128, 64, 0, s);
-                if (e != hipSuccess) return e;
-                e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 128, 64, 64, 128, 1, s);
-            }
-            if (e != hipSuccess) return e;
-            e = launch_gc_split_wide(rows + 64 * i, w_in, pos, nbr, off, src, packed, out + 128 * j, w_out, B, N, K,
-                                     transpose, i > 0, s);
-            if (e != hipSuccess) return e;
-        }
-    return hipSuccess;
+    const int n_in = w_in / 64, n_out = w_out / 128;
+    hipError_t e = launch_pack_theta_f16_blocks(theta, bias, scratch, Din, Dout, 64, 128, n_in, n_out, transpose, s);
+    if (e != hipSuccess) return e;
+    return launch_gc_split_wide(rows, w_in, pos, nbr, off, src, scratch, out, w_out, n_in, n_out, B, N, K, transpose, s);
 }
 
-// Parameter gradients of a wide layer: (Din/64) x (Dout/64) blocks of [4*64 x 64].  scratch: room for one block.
-static hipError_t wide_grad_theta(const float *rows, const float *pos, const int32_t *nbr, const float *g_rows,
-                                  float *partials, void *scratch, float *grad_theta, float *grad_bias, int B, int N,
-                                  int K, int Din, int Dout, hipStream_t s)
+// Parameter gradients of a wide layer: (Din/64) x (Dout/64) independent blocks of [4*64 x 64], two launches
+// (partial sums per block and workgroup, then their reduction in double).
+static size_t wide_partial_bytes(int B, int N, int Din, int Dout)
 {
-    float *blk_theta = (float *)scratch, *blk_bias = blk_theta + 3 * 64 * 64;
-    for (int hi = 0; hi < Din / 64; ++hi)
-        for (int ho = 0; ho < Dout / 64; ++ho) {
-            int n_wg = 0;
-            hipError_t e = launch_gt_split_wide(rows + 64 * hi, Din, pos, nbr, g_rows + 64 * ho, Dout, partials, B, N,
-                                                K, &n_wg, s);
-            if (e != hipSuccess) return e;
-            e = launch_reduce_partials(partials, n_wg, 64, 64, 64, 64, blk_theta, blk_bias, s);
-            if (e != hipSuccess) return e;
-            e = launch_param_block(grad_theta, grad_bias, blk_theta, blk_bias, Din, Dout, 64 * hi, 64 * ho, 64, 64, 1, s);
-            if (e != hipSuccess) return e;
-        }
-    return hipSuccess;
+    const int blocks = (Din / 64) * (Dout / 64);
+    return align256(sizeof(float) * (size_t)blocks * split_wide_gt_chunks(B, N, blocks) * 4 * 64 * 64);
+}
+
+static hipError_t wide_grad_theta(const float *rows, const float *pos, const int32_t *nbr, const float *g_rows,
+                                  float *partials, float *grad_theta, float *grad_bias, int B, int N, int K, int Din,
+                                  int Dout, hipStream_t s)
+{
+    const int n_hi = Din / 64, n_ho = Dout / 64, chunks = split_wide_gt_chunks(B, N, n_hi * n_ho);
+    hipError_t e = launch_gt_split_wide(rows, Din, pos, nbr, g_rows, Dout, partials, n_hi, n_ho, chunks, B, N, K, s);
+    if (e != hipSuccess) return e;
+    return launch_reduce_partials_blocks(partials, chunks, 0, n_hi * n_ho, n_ho, Din, Dout, grad_theta, grad_bias, s);
 }
 
 // Packs (theta, bias) for launch_gather_contract in the format that kernel wants.
@@ -321,7 +306,7 @@ static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout)
     p.wide = !p.tiled && wide_shape(Din, Dout);
     size_t at = 0;
     if (p.tiled || p.wide) {
-        p.thetaP = at; at += p.wide ? wide_param_scratch_bytes() : theta_ws_bytes(Din, Dout);
+        p.thetaP = at; at += p.wide ? wide_param_scratch_bytes(Din, Dout) : theta_ws_bytes(Din, Dout);
         if (layout == FLEX_LAYOUT_BCN) { p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din); }
         if (layout == FLEX_LAYOUT_BCN && p.wide) { p.outT = at; at += align256(sizeof(float) * (size_t)(B * N) * Dout); }
     }
@@ -336,15 +321,14 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
     p.wide = !p.tiled && wide_shape(Din, Dout);
     size_t at = 0;
     if (p.tiled || p.wide) {
-        p.thetaP = at; at += p.wide ? wide_param_scratch_bytes() : theta_ws_bytes(Dout, Din);
+        p.thetaP = at; at += p.wide ? wide_param_scratch_bytes(Din, Dout) : theta_ws_bytes(Dout, Din);
         if (layout == FLEX_LAYOUT_BCN) {
             p.featT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din);
             p.gT = at;    at += align256(sizeof(float) * (size_t)(B * N) * Dout);
             if (p.wide) { p.gfT = at; at += align256(sizeof(float) * (size_t)(B * N) * Din); }
         }
         p.partials = at;
-        at += p.wide ? align256(sizeof(float) * (size_t)split_wide_partials((int)B, (int)N) * 4 * 64 * 64)
-                     : grad_theta_partial_bytes(B, N, Din, Dout);
+        at += p.wide ? wide_partial_bytes((int)B, (int)N, Din, Dout) : grad_theta_partial_bytes(B, N, Din, Dout);
         if (build) {
             p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
             p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
@@ -543,8 +527,8 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
             }
         }
         if (grad_theta)
-            FLEX_HIP(wide_grad_theta(rows, pos, nbr, g_rows, (float *)(ws + p.partials), ws + p.thetaP, grad_theta,
-                                     grad_bias, B, N, K, Din, Dout, s));
+            FLEX_HIP(wide_grad_theta(rows, pos, nbr, g_rows, (float *)(ws + p.partials), grad_theta, grad_bias, B, N,
+                                     K, Din, Dout, s));
         if (grad_feat) {
             if (build) {
                 int32_t *off = (int32_t *)(ws + p.in_off), *src = (int32_t *)(ws + p.in_src);

@@ -39,6 +39,8 @@ hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *th
                                  int Dout, int RP, int CP, int transpose, hipStream_t s);
 size_t theta_f16_exp_offset(int RP, int CP);
 size_t theta_f16_bytes(int RP, int CP);
+hipError_t launch_pack_theta_f16_blocks(const float *theta, const float *bias, void *thetaF_all, int Din, int Dout,
+                                        int r_blk, int c_blk, int n_i, int n_j, int transpose, hipStream_t s);
 
 // Location gradient (flex_ws.hpp grad_pos_kernel): Theta_d fragments and one term of the gradient.
 // launch_grad_pos_term returns hipErrorNotSupported when (DI, DO, N, K) has no lean kernel.

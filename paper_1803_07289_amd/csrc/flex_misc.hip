@@ -109,6 +109,68 @@ __global__ __launch_bounds__(1024) void pack_theta_f16_kernel(const float *__res
     }
 }
 
+// The parameters of a wide layer as a grid of blocks, each packed like a whole layer's (same buffer layout, its own
+// exponent), one workgroup per block.  transpose == 0: block (i, j) = input channels r_blk*i.., output channels
+// c_blk*j.. (depth = input channel).  transpose == 1: block (i, j) = output channels r_blk*i.., input channels
+// c_blk*j.., packed transposed (depth = output channel).  Block (i, j) lands at index j * n_i + i.
+__global__ __launch_bounds__(1024) void pack_theta_f16_blocks_kernel(const float *__restrict__ theta,
+                                                                     const float *__restrict__ bias,
+                                                                     char *__restrict__ thetaF_all, int Din, int Dout,
+                                                                     int r_blk, int c_blk, int n_i, int transpose,
+                                                                     int block_bytes, int exp_offset_bytes)
+{
+    __shared__ float s_max[1024];
+    const int i_blk = blockIdx.x % n_i, j_blk = blockIdx.x / n_i;
+    _Float16 *thetaF = reinterpret_cast<_Float16 *>(thetaF_all + (size_t)blockIdx.x * block_bytes);
+    // the block's input / output channel ranges
+    const int ci0 = transpose ? c_blk * j_blk : r_blk * i_blk, co0 = transpose ? r_blk * i_blk : c_blk * j_blk;
+    const int nci = transpose ? c_blk : r_blk, nco = transpose ? r_blk : c_blk;
+    float m = 0.f;
+    for (int t = threadIdx.x; t < 4 * nci * nco; t += 1024) {
+        const int j = t / (nci * nco), ci = ci0 + (t / nco) % nci, co = co0 + t % nco;
+        m = fmaxf(m, fabsf(j < 3 ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co]));
+    }
+    s_max[threadIdx.x] = m;
+    __syncthreads();
+    for (int d = 512; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + d]);
+        __syncthreads();
+    }
+    m = s_max[0];
+    int ex = 0;
+    if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ex); ex = 15 - ex; }
+    if (threadIdx.x == 0) *reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes) = ex;
+
+    const int RP = r_blk, CP = c_blk;            // depth rows per component, columns (multiples of 4 / 16)
+    const int KD = 4 * RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
+    const int per_part = NS * KS * 64 * 8;
+    for (int t = threadIdx.x; t < per_part; t += 1024) {
+        const int e = t & 7, lane = (t >> 3) & 63, step = (t >> 9) % KS, slice = (t >> 9) / KS;
+        const int kd = 32 * step + 8 * (lane >> 4) + e, col = 16 * slice + (lane & 15);
+        float v = 0.f;
+        if (kd < KD) {
+            const int j = kd / RP, r = kd % RP;
+            const int ci = transpose ? c_blk * j_blk + col : r_blk * i_blk + r;
+            const int co = transpose ? r_blk * i_blk + r : c_blk * j_blk + col;
+            v = (j < 3) ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co];
+        }
+        const float vs = ldexpf(v, ex);
+        const _Float16 hi = (_Float16)vs;
+        const _Float16 lo = (_Float16)(vs - (float)hi);
+        thetaF[t] = hi;
+        thetaF[per_part + t] = lo;
+    }
+}
+
+hipError_t launch_pack_theta_f16_blocks(const float *theta, const float *bias, void *thetaF_all, int Din, int Dout,
+                                        int r_blk, int c_blk, int n_i, int n_j, int transpose, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_theta_f16_blocks_kernel, dim3((unsigned)(n_i * n_j)), dim3(1024), 0, s, theta, bias,
+                       (char *)thetaF_all, Din, Dout, r_blk, c_blk, n_i, transpose,
+                       (int)theta_f16_bytes(r_blk, c_blk), (int)theta_f16_exp_offset(r_blk, c_blk));
+    return hipGetLastError();
+}
+
 size_t theta_f16_exp_offset(int RP, int CP)
 {
     const int KDP = (4 * RP + 31) / 32 * 32;
@@ -288,6 +350,40 @@ __global__ void reduce_partials_kernel(const float *__restrict__ partials, int n
         if (j < 3) grad_theta[((int64_t)j * Din + c) * Dout + o] = v;
         else grad_bias[(int64_t)c * Dout + o] = v;
     }
+}
+
+// The same for a run of 64 x 64 blocks of a wider layer: block z of the launch (blockIdx.z) is block
+// p = first + z of the (Din / 64) x (Dout / 64) grid, its partials start at partials[z * n_wg], and its sums go to
+// rows 64 * (p / n_ho).., columns 64 * (p % n_ho).. of grad_theta [3,Din,Dout] / grad_bias [Din,Dout].
+__global__ void reduce_partials_blocks_kernel(const float *__restrict__ partials, int n_wg, int first, int n_ho,
+                                              int Din, int Dout, float *__restrict__ grad_theta,
+                                              float *__restrict__ grad_bias)
+{
+    __shared__ double red[4][64];
+    const int x = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int kd = blockIdx.y;                              // row of the block: j*64 + c
+    const int j = kd / 64, c = kd % 64;
+    const int p = first + blockIdx.z, hi = p / n_ho, ho = p - hi * n_ho;
+    const int64_t stride = (int64_t)4 * 64 * 64;
+    const float *src = partials + (int64_t)blockIdx.z * n_wg * stride + (int64_t)kd * 64 + x;
+    double sum = 0.0;
+    for (int g = part; g < n_wg; g += 4) sum += (double)src[g * stride];
+    red[part][x] = sum;
+    __syncthreads();
+    if (part == 0) {
+        const float v = (float)(red[0][x] + red[1][x] + red[2][x] + red[3][x]);
+        const int ci = 64 * hi + c, co = 64 * ho + x;
+        if (j < 3) grad_theta[((int64_t)j * Din + ci) * Dout + co] = v;
+        else grad_bias[(int64_t)ci * Dout + co] = v;
+    }
+}
+
+hipError_t launch_reduce_partials_blocks(const float *partials, int n_wg, int first, int count, int n_ho, int Din,
+                                         int Dout, float *grad_theta, float *grad_bias, hipStream_t s)
+{
+    hipLaunchKernelGGL(reduce_partials_blocks_kernel, dim3(1, 4 * 64, (unsigned)count), dim3(256), 0, s, partials,
+                       n_wg, first, n_ho, Din, Dout, grad_theta, grad_bias);
+    return hipGetLastError();
 }
 
 hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,

@@ -57,6 +57,13 @@ struct TileSchedule {
         end = min((xcd + 1) * per_xcd, total_tiles);
         step = gridDim.x >> 3;
     }
+    // plain strided share `part` of `parts` (for launches whose workgroups are split over several jobs)
+    __device__ __forceinline__ TileSchedule(int total_tiles, int part, int parts)
+    {
+        first = part;
+        end = total_tiles;
+        step = parts;
+    }
 };
 
 template <class S, int U, bool CSR>

@@ -219,8 +219,9 @@ hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, con
 
 #if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 128
 // Layers whose widths are multiples of 128 (point-major) run as passes of this shape's lean kernels over column
-// blocks: 64 gathered channels (rows rs floats apart) against a [4*64 x 128] block of the parameters, into 128
-// output channels (rows os floats apart), adding to what is there when accumulate is set.
+// blocks, all inside one launch: n_in blocks of 64 gathered channels (rows rs floats apart), each against a
+// [4*64 x 128] block of the parameters (thetaP_all, block j * n_in + i), into n_out blocks of 128 output channels
+// (rows os floats apart).
 bool split_wide_ok(int N, int K, int max_width)
 {
     if (contract_in_fp32() || lean_producer_mode() == 0) return false;
@@ -228,9 +229,9 @@ bool split_wide_ok(int N, int K, int max_width)
            (int64_t)K * N * 4 < (1ll << 32);
 }
 
-hipError_t launch_gc_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
-                                const int32_t *off, const int32_t *src, const void *thetaP, float *out_blk, int os,
-                                int B, int N, int K, int csr, int accumulate, hipStream_t s)
+hipError_t launch_gc_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const int32_t *off,
+                                const int32_t *src, const void *thetaP_all, float *out, int os, int n_in, int n_out,
+                                int B, int N, int K, int csr, hipStream_t s)
 {
     using W = WsGeom<S, 1>;
     const int tpc = (N + W::T - 1) / W::T;
@@ -238,51 +239,49 @@ hipError_t launch_gc_split_wide(const float *rows_blk, int rs, const float *pos,
     if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
     const int tot = (int)tot64;
     const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
-    const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
-#define FLEX_GC_WIDE(ACC, TAIL)                                                                                   \
-    hipLaunchKernelGGL((gather_contract_lean_strided_kernel<S, 1, ACC, TAIL>), g, blk, 0, s, rows_blk, pos, nbr,  \
-                       thetaP, exp_off, out_blk, N, K, tpc, tot, rs, os)
-    if (!csr) {
-        const bool tail = (K % 8) != 0;
-        if (accumulate) { if (tail) FLEX_GC_WIDE(true, true); else FLEX_GC_WIDE(true, false); }
-        else            { if (tail) FLEX_GC_WIDE(false, true); else FLEX_GC_WIDE(false, false); }
-    } else {
-        if (accumulate) hipLaunchKernelGGL((grad_feat_lean_strided_kernel<S, 1, true>), g, blk, 0, s, rows_blk, pos, off, src, thetaP, exp_off, out_blk, N, tpc, tot, rs, os);
-        else hipLaunchKernelGGL((grad_feat_lean_strided_kernel<S, 1, false>), g, blk, 0, s, rows_blk, pos, off, src, thetaP, exp_off, out_blk, N, tpc, tot, rs, os);
-    }
-#undef FLEX_GC_WIDE
+    const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP), blk_bytes = (int)theta_f16_bytes(S::DIP, S::DOP);
+    if (csr)
+        hipLaunchKernelGGL((grad_feat_lean_passes_kernel<S, 1>), g, blk, 0, s, rows, pos, off, src, thetaP_all,
+                           blk_bytes, exp_off, out, N, tpc, tot, rs, os, n_in, n_out);
+    else if (K % 8 == 0)
+        hipLaunchKernelGGL((gather_contract_lean_passes_kernel<S, 1, false>), g, blk, 0, s, rows, pos, nbr, thetaP_all,
+                           blk_bytes, exp_off, out, N, K, tpc, tot, rs, os, n_in, n_out);
+    else
+        hipLaunchKernelGGL((gather_contract_lean_passes_kernel<S, 1, true>), g, blk, 0, s, rows, pos, nbr, thetaP_all,
+                           blk_bytes, exp_off, out, N, K, tpc, tot, rs, os, n_in, n_out);
     return hipGetLastError();
 }
 #endif
 
 #if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 64
-// One [4*64 x 64] block of the parameter gradient of a wide layer: the aggregate of 64 channels of the feature
-// rows (rs floats apart) against 64 channels of the upstream gradient rows (gst floats apart).
-hipError_t launch_gt_split_wide(const float *rows_blk, int rs, const float *pos, const int32_t *nbr,
-                                const float *g_blk, int gst, float *partials, int B, int N, int K, int *n_wg,
+// Workgroups that share one [4*64 x 64] block of a wide layer's parameter gradient: enough to fill the device
+// when the blocks are few, one when they are many.
+int split_wide_gt_chunks(int B, int N, int blocks)
+{
+    using WL = WsGeom<S, 2, 2>;
+    const int64_t tot = (int64_t)B * ((N + WL::T - 1) / WL::T);
+    const int fill = persistent_grid(tot > 0x7fffffff ? 0x7fffffff : (int)tot, 1);
+    return fill / blocks > 1 ? fill / blocks : 1;
+}
+
+// All n_hi x n_ho blocks of the parameter gradient of a wide layer in one launch (block p = feature channels
+// 64 * (p / n_ho).., upstream-gradient channels 64 * (p % n_ho)..); partials[p * chunks + share].
+hipError_t launch_gt_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const float *g_rows,
+                                int gst, float *partials, int n_hi, int n_ho, int chunks, int B, int N, int K,
                                 hipStream_t s)
 {
     using WL = WsGeom<S, 2, 2>;
     const int tpc = (N + WL::T - 1) / WL::T;
-    const int64_t tot64 = (int64_t)B * tpc;
-    if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int64_t tot64 = (int64_t)B * tpc, grid = (int64_t)n_hi * n_ho * chunks;
+    if (tot64 > 0x7fffffff || grid > 0x7fffffff) return hipErrorInvalidValue;
     const int tot = (int)tot64;
-    *n_wg = persistent_grid(tot, 1);
     if (K % 8 == 0)
-        hipLaunchKernelGGL((grad_theta_lean_strided_kernel<S, false>), dim3(*n_wg), dim3(WL::NT), 0, s, rows_blk, pos,
-                           nbr, g_blk, partials, N, K, tpc, tot, rs, gst);
+        hipLaunchKernelGGL((grad_theta_lean_blocks_kernel<S, false>), dim3((unsigned)grid), dim3(WL::NT), 0, s, rows,
+                           pos, nbr, g_rows, partials, N, K, tpc, tot, rs, gst, chunks, n_ho);
     else
-        hipLaunchKernelGGL((grad_theta_lean_strided_kernel<S, true>), dim3(*n_wg), dim3(WL::NT), 0, s, rows_blk, pos,
-                           nbr, g_blk, partials, N, K, tpc, tot, rs, gst);
+        hipLaunchKernelGGL((grad_theta_lean_blocks_kernel<S, true>), dim3((unsigned)grid), dim3(WL::NT), 0, s, rows,
+                           pos, nbr, g_rows, partials, N, K, tpc, tot, rs, gst, chunks, n_ho);
     return hipGetLastError();
-}
-
-// workgroups (= partial sums) that launch_gt_split_wide starts for this size
-int split_wide_partials(int B, int N)
-{
-    using WL = WsGeom<S, 2, 2>;
-    const int64_t tot = (int64_t)B * ((N + WL::T - 1) / WL::T);
-    return persistent_grid(tot > 0x7fffffff ? 0x7fffffff : (int)tot, 1);
 }
 
 // One [4*64 x 64] block of the parameter gradient of a 128 -> 128 layer: the aggregate of a 64-channel half of

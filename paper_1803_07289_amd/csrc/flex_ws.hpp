@@ -989,12 +989,13 @@ struct LeanCsrProducer {
 
 // One consumer wave of the split-half contraction: out tile = A tile * Theta for every tile of
 // the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
-// OS = floats between consecutive output rows (point-major form; 0: the run-time value os_rt), ACC: add to what
-// out holds.
+// OS = floats between consecutive output rows (point-major form; 0: the run-time value os_rt), ACC (or the
+// run-time flag acc_rt): add to what out holds.
 template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false>
 __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ thetaP, int theta_exp_off,
                                              float *__restrict__ out, int N, const TileSchedule &sc,
-                                             int tiles_per_cloud, const char *s_A, const int *s_E, int os_rt = 0)
+                                             int tiles_per_cloud, const char *s_A, const int *s_E, int os_rt = 0,
+                                             bool acc_rt = false)
 {
     const int os = OS != 0 ? OS : os_rt;
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
@@ -1019,7 +1020,7 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
                 float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * os + o;
                 if constexpr (S::DO % 4 == 0) {
                     if (o < S::DO) {
-                        if constexpr (ACC) d += *reinterpret_cast<const v4f *>(dst);
+                        if (ACC || acc_rt) d += *reinterpret_cast<const v4f *>(dst);
                         *reinterpret_cast<v4f *>(dst) = d;
                     }
                 } else {
@@ -1097,7 +1098,7 @@ __device__ __forceinline__ void gather_contract_lean_body(const float *__restric
                                                           const int32_t *__restrict__ nbr,
                                                           const void *__restrict__ thetaP, int theta_exp_off,
                                                           float *__restrict__ out, int N, int K, int tiles_per_cloud,
-                                                          int total_tiles, int rs_rt, int os_rt)
+                                                          int total_tiles, int rs_rt, int os_rt, bool acc_rt)
 {
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
@@ -1129,7 +1130,7 @@ __device__ __forceinline__ void gather_contract_lean_body(const float *__restric
         return;
     }
     consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E,
-                                         os_rt);
+                                         os_rt, acc_rt);
 }
 
 template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false, bool TAIL = false>
@@ -1139,22 +1140,34 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
                                  int theta_exp_off, float *__restrict__ out, int N, int K,
                                  int tiles_per_cloud, int total_tiles)
 {
-    static_assert(RS != 0 && OS != 0, "run-time strides go through gather_contract_lean_strided_kernel");
+    static_assert(RS != 0 && OS != 0, "run-time strides go through gather_contract_lean_passes_kernel");
     gather_contract_lean_body<S, OUT_BCN, PM, RS, OS, ACC, TAIL>(rows, pos, nbr, thetaP, theta_exp_off, out, N, K,
-                                                                  tiles_per_cloud, total_tiles, 0, 0);
+                                                                  tiles_per_cloud, total_tiles, 0, 0, false);
 }
 
-// The same kernel for column blocks of wider point-major tensors: rs / os = floats between consecutive rows of the
-// gathered tensor / of the output.
-template <class S, int PM, bool ACC, bool TAIL>
+// A layer wider than this shape, point-major, as passes of the same kernel body inside one launch: pass (j, i)
+// gathers column block i (S::DI channels) of the rows (rs floats apart), contracts it with parameter block
+// j * n_in + i of thetaP_all (blocks theta_block_bytes apart, each packed like a whole layer's) and writes
+// (i == 0) or adds to (i > 0) column block j (S::DO channels) of the output (rows os floats apart).  A
+// workgroup owns the same tiles in every pass and a consumer lane the same output elements, so the adds need no
+// ordering beyond program order; the barrier between passes keeps a pass's first tile out of the LDS buffer the
+// consumers may still be reading.
+template <class S, int PM, bool TAIL>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void gather_contract_lean_strided_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
-                                         const int32_t *__restrict__ nbr, const void *__restrict__ thetaP,
-                                         int theta_exp_off, float *__restrict__ out, int N, int K,
-                                         int tiles_per_cloud, int total_tiles, int rs, int os)
+void gather_contract_lean_passes_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                        const int32_t *__restrict__ nbr, const void *__restrict__ thetaP_all,
+                                        int theta_block_bytes, int theta_exp_off, float *__restrict__ out, int N,
+                                        int K, int tiles_per_cloud, int total_tiles, int rs, int os, int n_in,
+                                        int n_out)
 {
-    gather_contract_lean_body<S, false, PM, 0, 0, ACC, TAIL>(rows, pos, nbr, thetaP, theta_exp_off, out, N, K,
-                                                             tiles_per_cloud, total_tiles, rs, os);
+    for (int j = 0; j < n_out; ++j)
+        for (int i = 0; i < n_in; ++i) {
+            const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
+            gather_contract_lean_body<S, false, PM, 0, 0, false, TAIL>(rows + S::DI * i, pos, nbr, th, theta_exp_off,
+                                                                       out + S::DO * j, N, K, tiles_per_cloud,
+                                                                       total_tiles, rs, os, i > 0);
+            __syncthreads();
+        }
 }
 
 // Feature gradient with the lean in-edge producers (same consumers as the forward kernel).
@@ -1163,7 +1176,7 @@ __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ ro
                                                     const int32_t *__restrict__ off, const int32_t *__restrict__ src,
                                                     const void *__restrict__ thetaP, int theta_exp_off,
                                                     float *__restrict__ out, int N, int tiles_per_cloud,
-                                                    int total_tiles, int rs_rt, int os_rt)
+                                                    int total_tiles, int rs_rt, int os_rt, bool acc_rt)
 {
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
@@ -1193,7 +1206,7 @@ __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ ro
         return;
     }
     consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E,
-                                         os_rt);
+                                         os_rt, acc_rt);
 }
 
 template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
@@ -1203,20 +1216,28 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
                            const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
                            int N, int tiles_per_cloud, int total_tiles)
 {
-    static_assert(RS != 0 && OS != 0, "run-time strides go through grad_feat_lean_strided_kernel");
+    static_assert(RS != 0 && OS != 0, "run-time strides go through grad_feat_lean_passes_kernel");
     grad_feat_lean_body<S, OUT_BCN, PM, RS, OS, ACC>(rows, pos, off, src, thetaP, theta_exp_off, out, N,
-                                                     tiles_per_cloud, total_tiles, 0, 0);
+                                                     tiles_per_cloud, total_tiles, 0, 0, false);
 }
 
-template <class S, int PM, bool ACC>
+// The feature gradient of a wider layer as passes inside one launch (see gather_contract_lean_passes_kernel).
+template <class S, int PM>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void grad_feat_lean_strided_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
-                                   const int32_t *__restrict__ off, const int32_t *__restrict__ src,
-                                   const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
-                                   int N, int tiles_per_cloud, int total_tiles, int rs, int os)
+void grad_feat_lean_passes_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                  const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                                  const void *__restrict__ thetaP_all, int theta_block_bytes, int theta_exp_off,
+                                  float *__restrict__ out, int N, int tiles_per_cloud, int total_tiles, int rs,
+                                  int os, int n_in, int n_out)
 {
-    grad_feat_lean_body<S, false, PM, 0, 0, ACC>(rows, pos, off, src, thetaP, theta_exp_off, out, N, tiles_per_cloud,
-                                                 total_tiles, rs, os);
+    for (int j = 0; j < n_out; ++j)
+        for (int i = 0; i < n_in; ++i) {
+            const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
+            grad_feat_lean_body<S, false, PM, 0, 0, false>(rows + S::DI * i, pos, off, src, th, theta_exp_off,
+                                                           out + S::DO * j, N, tiles_per_cloud, total_tiles, rs, os,
+                                                           i > 0);
+            __syncthreads();
+        }
 }
 
 template <class S, bool CSR, bool OUT_BCN, bool F16>
@@ -1497,10 +1518,11 @@ __device__ __forceinline__ bf8 read_tr_frag(const char *tile, int stride, int p0
 template <class S, int RS, int GST, bool TAIL>
 __device__ __forceinline__ void grad_theta_lean_body(const float *__restrict__ rows, const float *__restrict__ pos,
                                                      const int32_t *__restrict__ nbr,
-                                                     const float *__restrict__ g_rows, float *__restrict__ partials,
-                                                     int N, int K, int tiles_per_cloud, int total_tiles, int rs_rt,
-                                                     int gst_rt)
+                                                     const float *__restrict__ g_rows, float *__restrict__ partial,
+                                                     int N, int K, int tiles_per_cloud, const TileSchedule sc,
+                                                     int rs_rt, int gst_rt)
 {
+    // partial: where this workgroup's [KD x DOP] sums go; sc: the tiles it takes
     const int gst = GST != 0 ? GST : gst_rt;
     using G = WsGeom<S, 2, 2>;
     static_assert(G::T == 32, "one 32-point depth step of the matrix op per tile");
@@ -1509,7 +1531,6 @@ __device__ __forceinline__ void grad_theta_lean_body(const float *__restrict__ r
     __shared__ __attribute__((aligned(16))) char s_G[2][G::T * GS];
 
     const int w = threadIdx.x >> 6;
-    const TileSchedule sc(total_tiles);
 
     if (w < G::NP) {
         LeanProducer<S, 2, false, RS, TAIL> P;
@@ -1646,7 +1667,7 @@ __device__ __forceinline__ void grad_theta_lean_body(const float *__restrict__ r
         }
     }
 
-    float *dst = partials + (int64_t)blockIdx.x * S::KD * S::DOP;
+    float *dst = partial;
 #pragma unroll
     for (int c = 0; c < MBW; ++c) {
         const int mb = wm + c * WM;
@@ -1669,19 +1690,30 @@ void grad_theta_lean_kernel(const float *__restrict__ rows, const float *__restr
                             const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
                             float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles)
 {
-    static_assert(RS != 0 && GST != 0, "run-time strides go through grad_theta_lean_strided_kernel");
-    grad_theta_lean_body<S, RS, GST, TAIL>(rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total_tiles, 0, 0);
+    static_assert(RS != 0 && GST != 0, "run-time strides go through grad_theta_lean_blocks_kernel");
+    grad_theta_lean_body<S, RS, GST, TAIL>(rows, pos, nbr, g_rows, partials + (int64_t)blockIdx.x * S::KD * S::DOP, N, K,
+                                           tiles_per_cloud, TileSchedule(total_tiles), 0, 0);
 }
 
-// The same for column blocks of wider point-major tensors (strides as run-time values).
+// Parameter gradients of a layer wider than this shape, point-major, in one launch: the (Din / S::DI) x
+// (Dout / S::DO) blocks of the result are independent jobs, and each job's tiles are shared by `chunks`
+// workgroups (output-stationary: a deep, low-resolution layer has many blocks and few points, so a workgroup
+// walks all points for one block instead of all workgroups walking a few tiles each for every block).
+// Workgroup x serves block p = x / chunks = (hi, ho) = (p / n_ho, p % n_ho) as share x % chunks: column block hi
+// of the feature rows (rs floats apart) against column block ho of the upstream gradient rows (gst floats apart);
+// its partial goes to partials[x].
 template <class S, bool TAIL>
 __global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void grad_theta_lean_strided_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
-                                    const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
-                                    float *__restrict__ partials, int N, int K, int tiles_per_cloud,
-                                    int total_tiles, int rs, int gst)
+void grad_theta_lean_blocks_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
+                                   const int32_t *__restrict__ nbr, const float *__restrict__ g_rows,
+                                   float *__restrict__ partials, int N, int K, int tiles_per_cloud, int total_tiles,
+                                   int rs, int gst, int chunks, int n_ho)
 {
-    grad_theta_lean_body<S, 0, 0, TAIL>(rows, pos, nbr, g_rows, partials, N, K, tiles_per_cloud, total_tiles, rs, gst);
+    const int p = blockIdx.x / chunks, q = blockIdx.x - p * chunks;
+    const int hi = p / n_ho, ho = p - hi * n_ho;
+    grad_theta_lean_body<S, 0, 0, TAIL>(rows + S::DI * hi, pos, nbr, g_rows + S::DO * ho,
+                                        partials + (int64_t)blockIdx.x * S::KD * S::DOP, N, K, tiles_per_cloud,
+                                        TileSchedule(total_tiles, q, chunks), rs, gst);
 }
 
 // ---------------------------------------------------------------------------

@@ -54,6 +54,8 @@ SHAPES = [
     (2, 150, 8, 128, 256),
     (1, 200, 16, 256, 128),
     (1, 130, 9, 384, 128),     # masked tail in the block passes
+    (1, 500, 8, 512, 512),     # many parameter blocks, few tiles: one workgroup per block of the parameter gradient
+    (1, 4000, 8, 256, 256),    # several workgroups share a block
     (2, 150, 6, 5, 7),         # no tiled kernel: generic path
     (1, 90, 4, 20, 16),        # generic path, Din % 4 == 0
 ]
