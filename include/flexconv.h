@@ -306,7 +306,9 @@ int flex_validate_neighbors(const int32_t *nbr, int B, int N, int K,
 /* 1 if flexconv_fwd / flexconv_bwd run (Din,Dout) on the matrix-core kernels: the tiled widths 32->32, 64->64,
  * 128->128, 9->64, 64->9, 32->64, 64->32, 64->128, 128->64, and every pair of multiples of 128 (run as passes over
  * 64- / 128-channel column blocks; the deeper stages of the network of Sec. 5, whose feature length doubles from
- * stage to stage).  0: the direct-form kernels (any widths, orders of magnitude slower). */
+ * stage to stage).  2: any other widths, which run zero-padded at the nearest widths of that list (padded copies
+ * of the tensors live in the workspace, whose size flexconv_workspace_bytes reports).  0: the direct-form kernels
+ * (orders of magnitude slower; only with padding or block passes switched off in the environment). */
 int flexconv_has_fast_path(int Din, int Dout);
 
 const char *flex_status_string(int status);

@@ -486,4 +486,6 @@ def flex_validate_neighbors(nbr):
 
 
 def has_fast_path(Din, Dout):
+    """True if flexconv_fwd / flexconv_bwd run these widths on the matrix-core kernels (natively, as block passes or
+    zero-padded) rather than on the direct-form kernels."""
     return bool(lib().flexconv_has_fast_path(int(Din), int(Dout)))

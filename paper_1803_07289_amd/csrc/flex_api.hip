@@ -367,6 +367,59 @@ static PosPlan plan_pos(int64_t B, int64_t N, int K, int Din, int Dout, int layo
     return p;
 }
 
+// Widths with neither a tiled nor a wide path run on zero-padded copies at the nearest widths that have one
+// (FLEX_PAD=0 in the environment keeps them on the direct-form kernels, for comparisons): extra channels of the
+// features / upstream gradient and extra rows / columns of the parameters are zero, so they add nothing, and the
+// results are the leading channels / the leading block of what the padded layer returns.
+static bool padded_shape(int Din, int Dout, int *DIp, int *DOp)
+{
+    static const bool off = [] { const char *v = getenv("FLEX_PAD"); return v != nullptr && v[0] == '0'; }();
+    if (off || wide_shape(Din, Dout)) return false;
+    if (gather_contract_supported(Din, Dout) && gather_contract_supported(Dout, Din)) return false;
+    if (Din <= 128 && Dout <= 128) {
+        int64_t best = -1;
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS)                                                         \
+        if (DI_ >= Din && DO_ >= Dout && gather_contract_supported(DO_, DI_) &&                         \
+            (best < 0 || (int64_t)DI_ * DO_ < best)) {                                                  \
+            best = (int64_t)DI_ * DO_; *DIp = DI_; *DOp = DO_;                                          \
+        }
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+        return best > 0;
+    }
+    *DIp = (Din + 127) / 128 * 128;
+    *DOp = (Dout + 127) / 128 * 128;
+    return wide_shape(*DIp, *DOp);
+}
+
+static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout);
+static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layout, bool build);
+
+struct PadPlan {
+    size_t featP, gP, thetaP, outP, gfP, gtP, sub, sub_bytes, total;   // thetaP / gtP: [3,DIp,DOp] then [DIp,DOp]
+};
+static PadPlan plan_pad(int64_t B, int64_t N, int K, int DIp, int DOp, bool bwd, bool build)
+{
+    PadPlan p{};
+    size_t at = 0;
+    const size_t rows_in = align256(sizeof(float) * (size_t)(B * N) * DIp);
+    const size_t rows_out = align256(sizeof(float) * (size_t)(B * N) * DOp);
+    const size_t params = align256(sizeof(float) * (size_t)4 * DIp * DOp);
+    p.featP = at; at += rows_in;
+    p.thetaP = at; at += params;
+    if (!bwd) { p.outP = at; at += rows_out; }
+    else {
+        p.gP = at;  at += rows_out;
+        p.gfP = at; at += rows_in;
+        p.gtP = at; at += params;
+    }
+    p.sub = at;
+    p.sub_bytes = bwd ? plan_bwd(B, N, K, DIp, DOp, FLEX_LAYOUT_BNC, build).total
+                      : plan_fwd(B, N, DIp, DOp, FLEX_LAYOUT_BNC).total;
+    p.total = at + p.sub_bytes;
+    return p;
+}
+
 static bool sizes_ok(int64_t B, int64_t N, int64_t K, int64_t Din, int64_t Dout)
 {
     if (B <= 0 || N <= 0 || K <= 0 || Din <= 0 || Dout <= 0) return false;
@@ -423,16 +476,25 @@ const char *flex_status_string(int status)
 
 int flexconv_has_fast_path(int Din, int Dout)
 {
-    return (gather_contract_supported(Din, Dout) || wide_shape(Din, Dout)) ? 1 : 0;
+    int a, b;
+    if (gather_contract_supported(Din, Dout) || wide_shape(Din, Dout)) return 1;
+    return padded_shape(Din, Dout, &a, &b) ? 2 : 0;
 }
 
 size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, int layout)
 {
     if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return 0;
     switch (op) {
-    case FLEX_OP_CONV_FWD: return sizes_ok(B, N, K, Din, Dout) ? plan_fwd(B, N, Din, Dout, layout).total : 0;
-    case FLEX_OP_CONV_BWD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, false).total : 0;
-    case FLEX_OP_CONV_BWD_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_bwd(B, N, K, Din, Dout, layout, true).total : 0;
+    case FLEX_OP_CONV_FWD:
+    case FLEX_OP_CONV_BWD:
+    case FLEX_OP_CONV_BWD_BUILD: {
+        if (!sizes_ok(B, N, K, Din, Dout)) return 0;
+        int DIp, DOp;
+        if (padded_shape(Din, Dout, &DIp, &DOp))
+            return plan_pad(B, N, K, DIp, DOp, op != FLEX_OP_CONV_FWD, op == FLEX_OP_CONV_BWD_BUILD).total;
+        if (op == FLEX_OP_CONV_FWD) return plan_fwd(B, N, Din, Dout, layout).total;
+        return plan_bwd(B, N, K, Din, Dout, layout, op == FLEX_OP_CONV_BWD_BUILD).total;
+    }
     case FLEX_OP_INEDGES: return sizes_ok(B, N, K, 1, 1) ? inedges_ws_bytes((int64_t)B * N) : 0;
     case FLEX_OP_CONV_BWD_POS: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, false).total : 0;
     case FLEX_OP_CONV_BWD_POS_BUILD: return sizes_ok(B, N, K, Din, Dout) ? plan_pos(B, N, K, Din, Dout, layout, true).total : 0;
@@ -450,11 +512,26 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
     if (!feat || !pos || !nbr || !theta || !bias || !out) return FLEX_ERR_NULL;
     if (!sizes_ok(B, N, K, Din, Dout)) return FLEX_ERR_SHAPE;
     if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
-    const FwdPlan p = plan_fwd(B, N, Din, Dout, layout);
-    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int bcn = (layout == FLEX_LAYOUT_BCN);
+    int DIp, DOp;
+    if (padded_shape(Din, Dout, &DIp, &DOp)) {
+        const PadPlan pp = plan_pad(B, N, K, DIp, DOp, false, false);
+        if (!ws_ok(workspace, workspace_bytes, pp.total)) return FLEX_ERR_WORKSPACE;
+        float *featP = (float *)(ws + pp.featP), *thetaP = (float *)(ws + pp.thetaP), *biasP = thetaP + 3 * DIp * DOp;
+        float *outP = (float *)(ws + pp.outP);
+        FLEX_HIP(launch_copy_rows(feat, featP, B, N, Din, DIp, bcn, 0, s));
+        FLEX_HIP(launch_fill_zero(thetaP, sizeof(float) * (size_t)4 * DIp * DOp, s));
+        FLEX_HIP(launch_param_block(thetaP, biasP, (float *)theta, (float *)bias, DIp, DOp, 0, 0, Din, Dout, 1, s));
+        const int st = flexconv_fwd(featP, pos, nbr, thetaP, biasP, outP, B, N, K, DIp, DOp, FLEX_LAYOUT_BNC,
+                                    ws + pp.sub, pp.sub_bytes, stream);
+        if (st != FLEX_OK) return st;
+        FLEX_HIP(launch_copy_rows(outP, out, B, N, DOp, Dout, 0, bcn, s));
+        return FLEX_OK;
+    }
+    const FwdPlan p = plan_fwd(B, N, Din, Dout, layout);
+    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
     if (p.wide && split_wide_ok(N, K, Din > Dout ? Din : Dout)) {
         const float *rows = feat;
         float *dst = out;
@@ -511,11 +588,30 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
     if (!sizes_ok(B, N, K, Din, Dout)) return FLEX_ERR_SHAPE;
     if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
     const bool build = (in_off == nullptr) && (grad_feat != nullptr);
-    const BwdPlan p = plan_bwd(B, N, K, Din, Dout, layout, build);
-    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int bcn = (layout == FLEX_LAYOUT_BCN);
+    int DIp, DOp;
+    if (padded_shape(Din, Dout, &DIp, &DOp)) {
+        const PadPlan pp = plan_pad(B, N, K, DIp, DOp, true, build);
+        if (!ws_ok(workspace, workspace_bytes, pp.total)) return FLEX_ERR_WORKSPACE;
+        float *featP = (float *)(ws + pp.featP), *gP = (float *)(ws + pp.gP), *gfP = (float *)(ws + pp.gfP);
+        float *thetaP = (float *)(ws + pp.thetaP), *biasP = thetaP + 3 * DIp * DOp;
+        float *gtP = (float *)(ws + pp.gtP), *gbP = gtP + 3 * DIp * DOp;
+        FLEX_HIP(launch_copy_rows(feat, featP, B, N, Din, DIp, bcn, 0, s));
+        FLEX_HIP(launch_copy_rows(grad_out, gP, B, N, Dout, DOp, bcn, 0, s));
+        FLEX_HIP(launch_fill_zero(thetaP, sizeof(float) * (size_t)4 * DIp * DOp, s));
+        FLEX_HIP(launch_param_block(thetaP, biasP, (float *)theta, (float *)bias, DIp, DOp, 0, 0, Din, Dout, 1, s));
+        const int st = flexconv_bwd(featP, pos, nbr, thetaP, biasP, gP, grad_feat ? gfP : nullptr,
+                                    grad_theta ? gtP : nullptr, grad_theta ? gbP : nullptr, in_off, in_src, B, N, K,
+                                    DIp, DOp, FLEX_LAYOUT_BNC, ws + pp.sub, pp.sub_bytes, stream);
+        if (st != FLEX_OK) return st;
+        if (grad_feat) FLEX_HIP(launch_copy_rows(gfP, grad_feat, B, N, DIp, Din, 0, bcn, s));
+        if (grad_theta) FLEX_HIP(launch_param_block(gtP, gbP, grad_theta, grad_bias, DIp, DOp, 0, 0, Din, Dout, 0, s));
+        return FLEX_OK;
+    }
+    const BwdPlan p = plan_bwd(B, N, K, Din, Dout, layout, build);
+    if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
     if (p.wide && split_wide_ok(N, K, Din > Dout ? Din : Dout)) {
         const float *rows = feat, *g_rows = grad_out;
         if (bcn) {

@@ -58,6 +58,8 @@ hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const f
                                   int Dout, int bnc, hipStream_t s);
 
 // [B,C,N] -> [B,N,C] and back.
+hipError_t launch_copy_rows(const float *src, float *dst, int B, int N, int Cs, int Cd, int src_bcn, int dst_bcn,
+                            hipStream_t s);
 hipError_t launch_bcn_to_bnc(const float *src, float *dst, int B, int C, int N, hipStream_t s);
 hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, hipStream_t s);
 

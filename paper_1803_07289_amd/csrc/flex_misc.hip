@@ -737,4 +737,32 @@ hipError_t launch_param_block(float *theta, float *bias, float *blk_theta, float
     return hipGetLastError();
 }
 
+// Row copy between feature tensors of different widths and layouts: dst[b, n, c] = c < Cs ? src[b, n, c] : 0 for
+// c < Cd (so Cd > Cs pads with zero channels, Cd < Cs keeps the first Cd).  *_bcn: that tensor is channel-major.
+__global__ __launch_bounds__(256) void copy_rows_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                        int64_t total, int N, int Cs, int Cd, int src_bcn, int dst_bcn)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int64_t b;
+        int n, c;
+        if (dst_bcn) { n = (int)(i % N); const int64_t bc = i / N; c = (int)(bc % Cd); b = bc / Cd; }
+        else         { c = (int)(i % Cd); const int64_t bn = i / Cd; n = (int)(bn % N); b = bn / N; }
+        float v = 0.f;
+        if (c < Cs) v = src_bcn ? src[(b * Cs + c) * N + n] : src[(b * N + n) * Cs + c];
+        dst[i] = v;
+    }
+}
+
+hipError_t launch_copy_rows(const float *src, float *dst, int B, int N, int Cs, int Cd, int src_bcn, int dst_bcn,
+                            hipStream_t s)
+{
+    const int64_t total = (int64_t)B * N * Cd;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > (1 << 20)) blocks = 1 << 20;
+    hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, total, N, Cs, Cd, src_bcn,
+                       dst_bcn);
+    return hipGetLastError();
+}
+
 }  // namespace flex

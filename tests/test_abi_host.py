@@ -137,11 +137,13 @@ def test_workspace_sizes(L):
     packed = 4 * 64 * 64 * 4 + 256       # parameters (fp32 form = both f16 halves) + the exponent's slot
     assert w(0, 1, 4096, 8, 64, 64, 1) == packed                                 # packed parameters only
     assert w(0, 1, 4096, 8, 64, 64, 0) == packed + 4096 * 64 * 4                 # + transposed features
-    assert w(0, 1, 4096, 8, 5, 7, 0) == 256                                      # generic kernels need none
+    # widths without a kernel of their own: padded copies of the features, the parameters and the output + the 9 -> 64 plan
+    assert w(0, 1, 4096, 8, 5, 7, 0) == 4096 * 9 * 4 + 4 * 9 * 64 * 4 + 4096 * 64 * 4 + w(0, 1, 4096, 8, 9, 64, 1)
     assert w(2, 1, 4096, 8, 64, 64, 1) > w(1, 1, 4096, 8, 64, 64, 1) > 0
     assert w(0, 0, 4096, 8, 64, 64, 1) == 0 and w(9, 1, 4096, 8, 64, 64, 1) == 0
     assert w(0, 1, 4096, 8, 64, 64, 5) == 0
-    assert L.flexconv_has_fast_path(64, 64) == 1 and L.flexconv_has_fast_path(5, 7) == 0
+    assert L.flexconv_has_fast_path(64, 64) == 1 and L.flexconv_has_fast_path(256, 512) == 1
+    assert L.flexconv_has_fast_path(5, 7) == 2 and L.flexconv_has_fast_path(200, 300) == 2
 
 
 def test_binding_refuses_cpu_tensors():

@@ -1,5 +1,6 @@
 """The kernels that only special sizes reach (LDS-staged producers: byte offsets past 32 bits; fp32 matrix-op
-contraction and single-pass 128-wide kernels: kept for comparisons) are selected here through the library's
+contraction, single-pass 128-wide kernels and the direct-form kernels for arbitrary widths: kept for comparisons and
+as the last resort) are selected here through the library's
 environment switches, which are read once per process: so each setting runs the parity file once in a child process
 (one at a time)."""
 import os
@@ -12,8 +13,9 @@ pytestmark = pytest.mark.gpu
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 
-@pytest.mark.parametrize("env", [{"FLEX_PRODUCER": "staged"}, {"FLEX_CONTRACT": "f32"}, {"FLEX_SPLIT": "0"}],
-                         ids=["staged_producers", "fp32_contraction", "single_pass_128"])
+@pytest.mark.parametrize("env", [{"FLEX_PRODUCER": "staged"}, {"FLEX_CONTRACT": "f32"}, {"FLEX_SPLIT": "0"},
+                                 {"FLEX_PAD": "0"}],
+                         ids=["staged_producers", "fp32_contraction", "single_pass_128", "direct_form_kernels"])
 def test_parity_file_under_switch(env):
     child_env = dict(os.environ)
     child_env.update(env)

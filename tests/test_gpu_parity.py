@@ -56,8 +56,13 @@ SHAPES = [
     (1, 130, 9, 384, 128),     # masked tail in the block passes
     (1, 500, 8, 512, 512),     # many parameter blocks, few tiles: one workgroup per block of the parameter gradient
     (1, 4000, 8, 256, 256),    # several workgroups share a block
-    (2, 150, 6, 5, 7),         # no tiled kernel: generic path
-    (1, 90, 4, 20, 16),        # generic path, Din % 4 == 0
+    (2, 150, 6, 5, 7),         # widths without a kernel of their own: zero-padded to the nearest that has one
+    (1, 90, 4, 20, 16),
+    (1, 300, 8, 3, 64),        # colour-only input features
+    (1, 300, 8, 64, 13),       # class scores
+    (1, 200, 8, 100, 100),
+    (1, 150, 8, 200, 300),     # padded to a wide layer
+    (2, 150, 8, 64, 256),
 ]
 
 
