@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--n", type=int, default=None, help="override N (smaller trial runs)")
     ap.add_argument("--k", type=int, default=None, help="override K (neighbourhood-size sweeps)")
+    ap.add_argument("--din", type=int, default=None, help="override the input feature length (deeper-stage shapes)")
+    ap.add_argument("--dout", type=int, default=None, help="override the output feature length")
     ap.add_argument("--layout", default="bnc", choices=["bnc", "bcn"])
     ap.add_argument("--order", default="morton", choices=["morton", "generator", "shuffled"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -69,6 +71,9 @@ def main():
     cfg = CONFIGS[args.config]
     if args.k is not None:
         cfg = type(cfg)(**{**cfg.__dict__, "K": int(args.k), "name": cfg.name + f"_K{args.k}"})
+    if args.din is not None or args.dout is not None:
+        di, do = int(args.din or cfg.Din), int(args.dout or cfg.Dout)
+        cfg = type(cfg)(**{**cfg.__dict__, "Din": di, "Dout": do, "name": cfg.name + f"_{di}x{do}"})
     t0 = time.time()
     x = make_inputs(cfg, order=args.order, n_override=args.n)
     cfg = x.cfg
