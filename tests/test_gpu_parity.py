@@ -144,7 +144,7 @@ def test_degenerate_neighbourhoods():
 
 
 POOL_SHAPES = [(1, 1000, 8, 64), (2, 77, 3, 32), (1, 130, 16, 128), (2, 150, 6, 5), (1, 64, 1, 9), (2, 200, 20, 12),
-               (1, 40, 9, 18)]
+               (1, 40, 9, 18), (1, 300, 8, 1280), (2, 100, 5, 2052)]   # the last two: rows wider than a block
 
 
 @pytest.mark.parametrize("layout", [fx.BNC, fx.BCN], ids=["bnc", "bcn"])
