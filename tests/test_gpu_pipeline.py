@@ -55,3 +55,74 @@ def test_encoder_decoder_stage_matches_oracle():
                                                  bias.cpu().numpy())) <= TOL
     uo, ua = oracle.flexupsample_fwd(cm(h_s), sel_h, nbr_h)
     assert np.array_equal(cm(up_arg), ua) and np.array_equal(cm(up).view(np.uint32), uo.view(np.uint32))
+
+
+def test_stage_gradients_against_oracle_finite_differences():
+    """Backward through the same stage with the library's backward entry points; the gradient of a scalar loss with
+    respect to the first layer's parameters is compared with central differences of the ORACLE's forward chain (the
+    chain is piecewise linear in them, so the differences are exact up to rounding and to the few pooling winners that
+    change inside the step), and every gradient of the chain with the oracle's backward functions chained the same
+    way."""
+    say("pipeline gradients vs finite differences of the oracle chain")
+    B, N, K, C = 1, 640, 8, 32
+    rng = np.random.default_rng(11)
+    pos_h = rng.random((B, 3, N)).astype(np.float32)
+    feat_h = rng.standard_normal((B, C, N)).astype(np.float32)
+    th1 = (rng.standard_normal((3, C, C)) / np.sqrt(4 * C * K)).astype(np.float32) * 4
+    b1 = (rng.standard_normal((C, C)) / np.sqrt(4 * C * K)).astype(np.float32)
+    th2 = (rng.standard_normal((3, C, C)) / np.sqrt(4 * C * K)).astype(np.float32) * 4
+    b2 = (rng.standard_normal((C, C)) / np.sqrt(4 * C * K)).astype(np.float32)
+    R = rng.standard_normal((B, C, N)).astype(np.float32)            # loss = <upsampled output, R>
+    nbr_h = oracle.knn(pos_h, K)
+    Ns = N // 4
+    sel_h = np.sort(rng.permutation(N)[:Ns]).astype(np.int32)[None]
+    pos_s = np.ascontiguousarray(pos_h[:, :, sel_h[0]])
+    nbr_s = oracle.knn(pos_s, K)
+
+    def loss_oracle(feat, theta1):
+        h = oracle.flexconv_fwd(feat, pos_h, nbr_h, theta1, b1)
+        pooled, _ = oracle.flexpool_sub_fwd(h, nbr_h, sel_h)
+        hs = oracle.flexconv_fwd(pooled, pos_s, nbr_s, th2, b2)
+        up, _ = oracle.flexupsample_fwd(hs, sel_h, nbr_h)
+        return float((up.astype(np.float64) * R).sum())
+
+    # the library: forward, then backward with every backward entry point of the chain
+    d = lambda a: torch.from_numpy(a).cuda()
+    pm = lambda a: d(a).transpose(1, 2).contiguous()                  # [B,C,n] -> [B,n,C]
+    pos, nbr, sel, poss, nbrs = d(pos_h), d(nbr_h), d(sel_h), d(pos_s), d(nbr_s)
+    feat, t1, bb1, t2, bb2 = pm(feat_h), d(th1), d(b1), d(th2), d(b2)
+    edges, edges_s, edges_sub = fx.flex_inedges_build(nbr), fx.flex_inedges_build(nbrs), fx.flex_inedges_build_sub(nbr, sel)
+    h = fx.flexconv_fwd(feat, pos, nbr, t1, bb1, layout=fx.BNC)
+    pooled, arg = fx.flexpool_sub_fwd(h, nbr, sel, layout=fx.BNC)
+    hs = fx.flexconv_fwd(pooled, poss, nbrs, t2, bb2, layout=fx.BNC)
+    up, up_arg = fx.flexupsample_fwd(hs, sel, nbr, layout=fx.BNC)
+    g_hs = fx.flexupsample_bwd(pm(R), up_arg, sel, edges, layout=fx.BNC)
+    g_pooled, _, _ = fx.flexconv_bwd(pooled, poss, nbrs, t2, bb2, g_hs, layout=fx.BNC, in_edges=edges_s)
+    g_h = fx.flexpool_sub_bwd(g_pooled, arg, N, layout=fx.BNC, in_edges=edges_sub)
+    g_feat, g_t1, g_b1 = fx.flexconv_bwd(feat, pos, nbr, t1, bb1, g_h, layout=fx.BNC, in_edges=edges)
+    torch.cuda.synchronize()
+    assert abs(float((up.double() * pm(R).double()).sum()) - loss_oracle(feat_h, th1)) <= 1e-4 * np.abs(R).sum()
+
+    # a loose, independent check: every pooling winner that changes inside the step shifts the difference quotient by a
+    # whole slope (about 1 % of them do at 2e-3, which moved the quotient by 2 %), a smaller step loses to rounding
+    eps = 5e-4
+    D_t = rng.standard_normal(th1.shape).astype(np.float32) * np.abs(th1).mean()
+    fd = (loss_oracle(feat_h, th1 + eps * D_t) - loss_oracle(feat_h, th1 - eps * D_t)) / (2 * eps)
+    an = float((g_t1.double().cpu().numpy() * D_t).sum())
+    assert abs(fd - an) <= 2e-2 * max(abs(fd), abs(an), 1.0), (fd, an)
+    # the tight check: every gradient of the chain against the oracle's backward functions chained the same way
+    cm = lambda t: t.transpose(1, 2).contiguous().cpu().numpy()
+    o_h = oracle.flexconv_fwd(feat_h, pos_h, nbr_h, th1, b1)
+    o_pooled, o_arg = oracle.flexpool_sub_fwd(o_h, nbr_h, sel_h)
+    o_hs = oracle.flexconv_fwd(o_pooled, pos_s, nbr_s, th2, b2)
+    _, o_uarg = oracle.flexupsample_fwd(o_hs, sel_h, nbr_h)
+    assert np.array_equal(o_arg, cm(arg)) and np.array_equal(o_uarg, cm(up_arg))
+    o_ghs = oracle.flexupsample_bwd(R, o_uarg, sel_h)
+    o_gpooled, o_gt2, o_gb2 = oracle.flexconv_bwd(o_pooled, pos_s, nbr_s, th2, b2, o_ghs)
+    o_gh = oracle.flexpool_sub_bwd(o_gpooled, o_arg, sel_h, N)
+    o_gfeat, o_gt1, o_gb1 = oracle.flexconv_bwd(feat_h, pos_h, nbr_h, th1, b1, o_gh)
+    assert rel_err(cm(g_hs), o_ghs) <= 1e-5
+    assert rel_err(cm(g_pooled), o_gpooled) <= TOL
+    assert rel_err(cm(g_h), o_gh) <= TOL
+    assert rel_err(cm(g_feat), o_gfeat) <= TOL
+    assert rel_err(g_t1.cpu().numpy(), o_gt1) <= TOL and rel_err(g_b1.cpu().numpy(), o_gb1) <= TOL
