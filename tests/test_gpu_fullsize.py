@@ -113,3 +113,45 @@ def test_full_size_config(ci):
         torch.cuda.synchronize()
         assert torch.equal(pg_c.transpose(1, 2), pg)
         del pg_c, pa_c
+
+
+def test_wide_layer_at_a_deeper_stage_size():
+    """256 -> 256 on 200 000 room points (the shape of a deeper stage of the paper's network): the block-pass kernels
+    at a size where every workgroup walks many tiles in every pass."""
+    from workloads.configs import Config
+    base = CONFIGS[3]
+    cfg = Config(**{**base.__dict__, "N": 200_000, "Din": 256, "Dout": 256, "name": "room200k_256x256"})
+    say("wide layer: generating inputs")
+    x = make_inputs(cfg)
+    B, N, K, Din, Dout = cfg.B, cfg.N, cfg.K, cfg.Din, cfg.Dout
+    rng = np.random.default_rng(321)
+    feat, pos, nbr, theta, bias, g = bnc(x.feat), dev(x.pos), dev(x.nbr), dev(x.theta), dev(x.bias), bnc(x.grad_out)
+    edges = fx.flex_inedges_build(nbr)
+    out = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=fx.BNC)
+    gf, gt, gb = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=fx.BNC, in_edges=edges)
+    torch.cuda.synchronize()
+    say("  forward, sampled")
+    for (s0, s1) in sample_ranges(N, rng):
+        ref = oracle.flexconv_fwd(x.feat, x.pos, x.nbr, x.theta, x.bias, l_range=(s0, s1))
+        assert rel_err(out[:, s0:s1, :].transpose(1, 2).cpu().numpy(), ref) <= TOL
+    say("  feature gradient, sampled")
+    targets = np.unique(np.concatenate([rng.integers(0, B * N, size=300), [0, B * N - 1]])).astype(np.int64)
+    ref_rows = oracle.flexconv_grad_feat_at(x.pos, x.nbr, x.theta, x.bias, x.grad_out, targets)
+    assert rel_err(gf.reshape(B * N, Din)[torch.from_numpy(targets).cuda()].cpu().numpy(), ref_rows) <= TOL
+    say("  parameter gradients, block by block against the 64 -> 64 kernels on contiguous slices")
+    for (hi, ho) in [(0, 0), (3, 1), (2, 3)]:
+        f_blk = feat[:, :, 64 * hi:64 * hi + 64].contiguous()
+        g_blk = g[:, :, 64 * ho:64 * ho + 64].contiguous()
+        t_blk = theta[:, 64 * hi:64 * hi + 64, 64 * ho:64 * ho + 64].contiguous()
+        b_blk = bias[64 * hi:64 * hi + 64, 64 * ho:64 * ho + 64].contiguous()
+        _, rt, rb = fx.flexconv_bwd(f_blk, pos, nbr, t_blk, b_blk, g_blk, layout=fx.BNC, need_feat=False)
+        assert rel_err(gt[:, 64 * hi:64 * hi + 64, 64 * ho:64 * ho + 64].cpu().numpy(), rt.cpu().numpy()) <= TOL
+        assert rel_err(gb[64 * hi:64 * hi + 64, 64 * ho:64 * ho + 64].cpu().numpy(), rb.cpu().numpy()) <= TOL
+    # and one block against the oracle itself
+    say("  one parameter block against the oracle")
+    _, ot, ob = oracle.flexconv_bwd(np.ascontiguousarray(x.feat[:, 64:128]), x.pos, x.nbr,
+                                    np.ascontiguousarray(x.theta[:, 64:128, 128:192]),
+                                    np.ascontiguousarray(x.bias[64:128, 128:192]),
+                                    np.ascontiguousarray(x.grad_out[:, 128:192]), want_feat=False)
+    assert rel_err(gt[:, 64:128, 128:192].cpu().numpy(), ot) <= TOL
+    assert rel_err(gb[64:128, 128:192].cpu().numpy(), ob) <= TOL
