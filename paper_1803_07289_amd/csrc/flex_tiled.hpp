@@ -57,12 +57,22 @@ struct TileSchedule {
         end = min((xcd + 1) * per_xcd, total_tiles);
         step = gridDim.x >> 3;
     }
-    // plain strided share `part` of `parts` (for launches whose workgroups are split over several jobs)
+    // share `part` of `parts`, for launches whose workgroups are split over several jobs: the same XCD-aware walk
+    // when a job's workgroups are a multiple of 8 starting at a multiple of 8 (then part & 7 is the workgroup's
+    // XCD), a plain strided one otherwise
     __device__ __forceinline__ TileSchedule(int total_tiles, int part, int parts)
     {
-        first = part;
-        end = total_tiles;
-        step = parts;
+        if ((parts & 7) == 0) {
+            const int xcd = part & 7, slot = part >> 3;
+            const int per_xcd = (total_tiles + 7) >> 3;
+            first = xcd * per_xcd + slot;
+            end = min((xcd + 1) * per_xcd, total_tiles);
+            step = parts >> 3;
+        } else {
+            first = part;
+            end = total_tiles;
+            step = parts;
+        }
     }
 };
 

@@ -219,9 +219,9 @@ hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, con
 
 #if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 128
 // Layers whose widths are multiples of 128 (point-major) run as passes of this shape's lean kernels over column
-// blocks, all inside one launch: n_in blocks of 64 gathered channels (rows rs floats apart), each against a
-// [4*64 x 128] block of the parameters (thetaP_all, block j * n_in + i), into n_out blocks of 128 output channels
-// (rows os floats apart).
+// blocks, all inside one launch: n_out blocks of 128 output channels (rows os floats apart) as independent jobs,
+// each walking its tiles once per block of 64 gathered channels (n_in of them, rows rs floats apart) with its
+// [4*64 x 128] block of the parameters (thetaP_all, block j * n_in + i).
 bool split_wide_ok(int N, int K, int max_width)
 {
     if (contract_in_fp32() || lean_producer_mode() == 0) return false;
@@ -238,17 +238,21 @@ hipError_t launch_gc_split_wide(const float *rows, int rs, const float *pos, con
     const int64_t tot64 = (int64_t)B * tpc;
     if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
     const int tot = (int)tot64;
-    const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
+    // workgroups per output block: enough to fill the device when the blocks are few (whole multiples of 8, so
+    // that a share's number tells its XCD), one when they are many
+    int chunks = persistent_grid(tot, W::WG_PER_CU) / n_out;
+    chunks = chunks >= 8 ? chunks / 8 * 8 : (chunks > 1 ? chunks : 1);
+    const dim3 g((unsigned)(n_out * chunks)), blk(W::NT);
     const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP), blk_bytes = (int)theta_f16_bytes(S::DIP, S::DOP);
     if (csr)
         hipLaunchKernelGGL((grad_feat_lean_passes_kernel<S, 1>), g, blk, 0, s, rows, pos, off, src, thetaP_all,
-                           blk_bytes, exp_off, out, N, tpc, tot, rs, os, n_in, n_out);
+                           blk_bytes, exp_off, out, N, tpc, tot, rs, os, n_in, chunks);
     else if (K % 8 == 0)
         hipLaunchKernelGGL((gather_contract_lean_passes_kernel<S, 1, false>), g, blk, 0, s, rows, pos, nbr, thetaP_all,
-                           blk_bytes, exp_off, out, N, K, tpc, tot, rs, os, n_in, n_out);
+                           blk_bytes, exp_off, out, N, K, tpc, tot, rs, os, n_in, chunks);
     else
         hipLaunchKernelGGL((gather_contract_lean_passes_kernel<S, 1, true>), g, blk, 0, s, rows, pos, nbr, thetaP_all,
-                           blk_bytes, exp_off, out, N, K, tpc, tot, rs, os, n_in, n_out);
+                           blk_bytes, exp_off, out, N, K, tpc, tot, rs, os, n_in, chunks);
     return hipGetLastError();
 }
 #endif

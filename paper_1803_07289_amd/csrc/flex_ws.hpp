@@ -1098,14 +1098,13 @@ __device__ __forceinline__ void gather_contract_lean_body(const float *__restric
                                                           const int32_t *__restrict__ nbr,
                                                           const void *__restrict__ thetaP, int theta_exp_off,
                                                           float *__restrict__ out, int N, int K, int tiles_per_cloud,
-                                                          int total_tiles, int rs_rt, int os_rt, bool acc_rt)
+                                                          const TileSchedule sc, int rs_rt, int os_rt, bool acc_rt)
 {
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
     __shared__ int s_E[2 * G::T];
 
     const int w = threadIdx.x >> 6;
-    const TileSchedule sc(total_tiles);
 
     if constexpr (G::KDP > S::KD) {
         // depth padding of both tile buffers: never written again, must read as zero
@@ -1142,32 +1141,35 @@ void gather_contract_lean_kernel(const float *__restrict__ rows, const float *__
 {
     static_assert(RS != 0 && OS != 0, "run-time strides go through gather_contract_lean_passes_kernel");
     gather_contract_lean_body<S, OUT_BCN, PM, RS, OS, ACC, TAIL>(rows, pos, nbr, thetaP, theta_exp_off, out, N, K,
-                                                                  tiles_per_cloud, total_tiles, 0, 0, false);
+                                                                  tiles_per_cloud, TileSchedule(total_tiles), 0, 0,
+                                                                  false);
 }
 
-// A layer wider than this shape, point-major, as passes of the same kernel body inside one launch: pass (j, i)
-// gathers column block i (S::DI channels) of the rows (rs floats apart), contracts it with parameter block
-// j * n_in + i of thetaP_all (blocks theta_block_bytes apart, each packed like a whole layer's) and writes
-// (i == 0) or adds to (i > 0) column block j (S::DO channels) of the output (rows os floats apart).  A
-// workgroup owns the same tiles in every pass and a consumer lane the same output elements, so the adds need no
-// ordering beyond program order; the barrier between passes keeps a pass's first tile out of the LDS buffer the
-// consumers may still be reading.
+// A layer wider than this shape, point-major, in one launch.  The n_out column blocks (S::DO channels) of the
+// output are independent jobs, each shared by `chunks` workgroups: workgroup x serves block j = x / chunks as share
+// x % chunks of the tiles.  It walks its tiles once per column block i (S::DI channels) of the gathered rows (rs
+// floats apart): pass i contracts that block's aggregate with parameter block j * n_in + i of thetaP_all (blocks
+// theta_block_bytes apart, each packed like a whole layer's) and writes (i == 0) or adds to (i > 0) its part of
+// output block j (rows os floats apart).  A workgroup owns the same tiles in every pass and a consumer lane the
+// same output elements, so the adds need no ordering beyond program order; the barrier between passes keeps a
+// pass's first tile out of the LDS buffer the consumers may still be reading.
 template <class S, int PM, bool TAIL>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void gather_contract_lean_passes_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                                         const int32_t *__restrict__ nbr, const void *__restrict__ thetaP_all,
                                         int theta_block_bytes, int theta_exp_off, float *__restrict__ out, int N,
                                         int K, int tiles_per_cloud, int total_tiles, int rs, int os, int n_in,
-                                        int n_out)
+                                        int chunks)
 {
-    for (int j = 0; j < n_out; ++j)
-        for (int i = 0; i < n_in; ++i) {
-            const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
-            gather_contract_lean_body<S, false, PM, 0, 0, false, TAIL>(rows + S::DI * i, pos, nbr, th, theta_exp_off,
-                                                                       out + S::DO * j, N, K, tiles_per_cloud,
-                                                                       total_tiles, rs, os, i > 0);
-            __syncthreads();
-        }
+    const int j = blockIdx.x / chunks;
+    const TileSchedule sc(total_tiles, (int)blockIdx.x - j * chunks, chunks);
+    for (int i = 0; i < n_in; ++i) {
+        const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
+        gather_contract_lean_body<S, false, PM, 0, 0, false, TAIL>(rows + S::DI * i, pos, nbr, th, theta_exp_off,
+                                                                   out + S::DO * j, N, K, tiles_per_cloud, sc, rs, os,
+                                                                   i > 0);
+        __syncthreads();
+    }
 }
 
 // Feature gradient with the lean in-edge producers (same consumers as the forward kernel).
@@ -1176,14 +1178,13 @@ __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ ro
                                                     const int32_t *__restrict__ off, const int32_t *__restrict__ src,
                                                     const void *__restrict__ thetaP, int theta_exp_off,
                                                     float *__restrict__ out, int N, int tiles_per_cloud,
-                                                    int total_tiles, int rs_rt, int os_rt, bool acc_rt)
+                                                    const TileSchedule sc, int rs_rt, int os_rt, bool acc_rt)
 {
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
     __shared__ int s_E[2 * G::T];
 
     const int w = threadIdx.x >> 6;
-    const TileSchedule sc(total_tiles);
 
     if constexpr (G::KDP > S::KD) {
         constexpr int PADH = G::KDP - S::KD;
@@ -1218,26 +1219,26 @@ void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restri
 {
     static_assert(RS != 0 && OS != 0, "run-time strides go through grad_feat_lean_passes_kernel");
     grad_feat_lean_body<S, OUT_BCN, PM, RS, OS, ACC>(rows, pos, off, src, thetaP, theta_exp_off, out, N,
-                                                     tiles_per_cloud, total_tiles, 0, 0, false);
+                                                     tiles_per_cloud, TileSchedule(total_tiles), 0, 0, false);
 }
 
-// The feature gradient of a wider layer as passes inside one launch (see gather_contract_lean_passes_kernel).
+// The feature gradient of a wider layer in one launch (see gather_contract_lean_passes_kernel).
 template <class S, int PM>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_feat_lean_passes_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                                   const int32_t *__restrict__ off, const int32_t *__restrict__ src,
                                   const void *__restrict__ thetaP_all, int theta_block_bytes, int theta_exp_off,
                                   float *__restrict__ out, int N, int tiles_per_cloud, int total_tiles, int rs,
-                                  int os, int n_in, int n_out)
+                                  int os, int n_in, int chunks)
 {
-    for (int j = 0; j < n_out; ++j)
-        for (int i = 0; i < n_in; ++i) {
-            const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
-            grad_feat_lean_body<S, false, PM, 0, 0, false>(rows + S::DI * i, pos, off, src, th, theta_exp_off,
-                                                           out + S::DO * j, N, tiles_per_cloud, total_tiles, rs, os,
-                                                           i > 0);
-            __syncthreads();
-        }
+    const int j = blockIdx.x / chunks;
+    const TileSchedule sc(total_tiles, (int)blockIdx.x - j * chunks, chunks);
+    for (int i = 0; i < n_in; ++i) {
+        const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
+        grad_feat_lean_body<S, false, PM, 0, 0, false>(rows + S::DI * i, pos, off, src, th, theta_exp_off,
+                                                       out + S::DO * j, N, tiles_per_cloud, sc, rs, os, i > 0);
+        __syncthreads();
+    }
 }
 
 template <class S, bool CSR, bool OUT_BCN, bool F16>
