@@ -639,31 +639,73 @@ hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const f
 }
 
 // ---- 1x1 convolution composed into the flex-convolution parameters (Sec. 5 block) ----------
-// P = [theta; bias] as four [D x Dout] slabs j = 0..3.  Parameter-sized work (a few MFLOP): one thread
-// per output element, sums in double.
+// P = [theta; bias] as four [D x Dout] slabs j = 0..3.  Parameter-sized work, but cubic in the width (4 * 1024^3
+// multiply-adds for a 1024-wide layer), so it runs as small LDS-tiled matrix products: a 256-thread block owns a
+// 64 x 64 tile of the result, depth in steps of 16, 4 x 4 results per thread accumulated in double.
 __device__ __forceinline__ const float *slab(const float *theta, const float *bias, int j, int D, int Dout)
 {
     return j < 3 ? theta + (int64_t)j * D * Dout : bias;
 }
 
-// Pc[j][c0][o] = sum_c W[c][c0] * P[j][c][o]
+// acc[i][jn] += sum_k A(m0 + ty*4 + i, k) * B(k, n0 + tx*4 + jn), A(m,k) = A[m*sam + k*sak], B(k,n) = B[k*sbk + n*sbn];
+// elements outside M x K / K x N read as zero.  All 256 threads of the block must call it together.
+__device__ __forceinline__ void tile_product(double (&acc)[4][4], const float *__restrict__ A, int64_t sam, int64_t sak,
+                                             const float *__restrict__ B, int64_t sbk, int64_t sbn, int M, int N, int K,
+                                             int m0, int n0, float (&As)[16][65], float (&Bs)[16][65])
+{
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + 256 * e;
+            // the unit-stride index runs fastest over the threads
+            const int am = sam == 1 ? idx & 63 : idx >> 4, ak = sam == 1 ? idx >> 6 : idx & 15;
+            const int bn = sbn == 1 ? idx & 63 : idx >> 4, bk = sbn == 1 ? idx >> 6 : idx & 15;
+            As[ak][am] = (m0 + am < M && k0 + ak < K) ? A[(int64_t)(m0 + am) * sam + (int64_t)(k0 + ak) * sak] : 0.f;
+            Bs[bk][bn] = (n0 + bn < N && k0 + bk < K) ? B[(int64_t)(k0 + bk) * sbk + (int64_t)(n0 + bn) * sbn] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            double a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = (double)As[k][ty * 4 + i]; b[i] = (double)Bs[k][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jn = 0; jn < 4; ++jn) acc[i][jn] += a[i] * b[jn];
+        }
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ void tile_store(const double (&acc)[4][4], float *__restrict__ C, int64_t ldc, int M, int N,
+                                           int m0, int n0)
+{
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) {
+            const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + jn;
+            if (m < M && n < N) C[(int64_t)m * ldc + n] = (float)acc[i][jn];
+        }
+}
+
+// Pc[j][c0][o] = sum_c W[c][c0] * P[j][c][o]; grid (tiles over c0, tiles over o, 4 slabs)
 __global__ __launch_bounds__(256) void compose_1x1_kernel(const float *__restrict__ W, const float *__restrict__ theta,
                                                           const float *__restrict__ bias, float *__restrict__ theta_c,
                                                           float *__restrict__ bias_c, int Din0, int Dmid, int Dout)
 {
-    const int total = 4 * Din0 * Dout;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-        const int o = i % Dout, c0 = (i / Dout) % Din0, j = i / (Dout * Din0);
-        const float *P = slab(theta, bias, j, Dmid, Dout);
-        double s = 0.0;
-        for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * (double)P[(int64_t)c * Dout + o];
-        float *dst = j < 3 ? theta_c + (int64_t)j * Din0 * Dout : bias_c;
-        dst[(int64_t)c0 * Dout + o] = (float)s;
-    }
+    __shared__ float As[16][65], Bs[16][65];
+    const int j = blockIdx.z, m0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    double acc[4][4] = {};
+    tile_product(acc, W, 1, Din0, slab(theta, bias, j, Dmid, Dout), Dout, 1, Din0, Dout, Dmid, m0, n0, As, Bs);
+    tile_store(acc, j < 3 ? theta_c + (int64_t)j * Din0 * Dout : bias_c, Dout, Din0, Dout, m0, n0);
 }
 
-// gP[j][c][o] = sum_c0 W[c][c0] * gPc[j][c0][o]     (first 4*Dmid*Dout threads' worth of items)
-// gW[c][c0]   = sum_{j,o} P[j][c][o] * gPc[j][c0][o] (the Dmid*Din0 items after them)
+// blockIdx.z < 4: gP[j][c][o] = sum_c0 W[c][c0] * gPc[j][c0][o], j = blockIdx.z (tiles over c and o);
+// blockIdx.z == 4: gW[c][c0] = sum_{j,o} P[j][c][o] * gPc[j][c0][o] (tiles over c and c0).
 __global__ __launch_bounds__(256) void compose_1x1_bwd_kernel(const float *__restrict__ W, const float *__restrict__ theta,
                                                               const float *__restrict__ bias,
                                                               const float *__restrict__ gtheta_c,
@@ -671,34 +713,28 @@ __global__ __launch_bounds__(256) void compose_1x1_bwd_kernel(const float *__res
                                                               float *__restrict__ gtheta, float *__restrict__ gbias,
                                                               int Din0, int Dmid, int Dout)
 {
-    const int nP = 4 * Dmid * Dout, total = nP + Dmid * Din0;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-        if (i < nP) {
-            const int o = i % Dout, c = (i / Dout) % Dmid, j = i / (Dout * Dmid);
-            const float *G = slab(gtheta_c, gbias_c, j, Din0, Dout);
-            double s = 0.0;
-            for (int c0 = 0; c0 < Din0; ++c0) s += (double)W[(int64_t)c * Din0 + c0] * (double)G[(int64_t)c0 * Dout + o];
-            float *dst = j < 3 ? gtheta + (int64_t)j * Dmid * Dout : gbias;
-            dst[(int64_t)c * Dout + o] = (float)s;
-        } else {
-            const int k = i - nP, c0 = k % Din0, c = k / Din0;
-            double s = 0.0;
-            for (int j = 0; j < 4; ++j) {
-                const float *P = slab(theta, bias, j, Dmid, Dout) + (int64_t)c * Dout;
-                const float *G = slab(gtheta_c, gbias_c, j, Din0, Dout) + (int64_t)c0 * Dout;
-                for (int o = 0; o < Dout; ++o) s += (double)P[o] * (double)G[o];
-            }
-            gW[(int64_t)c * Din0 + c0] = (float)s;
-        }
+    __shared__ float As[16][65], Bs[16][65];
+    const int m0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    double acc[4][4] = {};
+    if (blockIdx.z < 4) {
+        const int j = blockIdx.z;
+        if (m0 >= Dmid || n0 >= Dout) return;          // the grid covers the larger of the two tilings
+        tile_product(acc, W, Din0, 1, slab(gtheta_c, gbias_c, j, Din0, Dout), Dout, 1, Dmid, Dout, Din0, m0, n0, As, Bs);
+        tile_store(acc, j < 3 ? gtheta + (int64_t)j * Dmid * Dout : gbias, Dout, Dmid, Dout, m0, n0);
+    } else {
+        if (m0 >= Dmid || n0 >= Din0) return;
+        for (int j = 0; j < 4; ++j)
+            tile_product(acc, slab(theta, bias, j, Dmid, Dout), Dout, 1, slab(gtheta_c, gbias_c, j, Din0, Dout), 1, Dout,
+                         Dmid, Din0, Dout, m0, n0, As, Bs);
+        tile_store(acc, gW, Din0, Dmid, Din0, m0, n0);
     }
 }
 
 hipError_t launch_compose_1x1(const float *W, const float *theta, const float *bias, float *theta_c, float *bias_c,
                               int Din0, int Dmid, int Dout, hipStream_t s)
 {
-    const int total = 4 * Din0 * Dout;
-    hipLaunchKernelGGL(compose_1x1_kernel, dim3((total + 255) / 256), dim3(256), 0, s, W, theta, bias, theta_c, bias_c,
-                       Din0, Dmid, Dout);
+    hipLaunchKernelGGL(compose_1x1_kernel, dim3((Din0 + 63) / 64, (Dout + 63) / 64, 4), dim3(256), 0, s, W, theta, bias,
+                       theta_c, bias_c, Din0, Dmid, Dout);
     return hipGetLastError();
 }
 
@@ -706,9 +742,9 @@ hipError_t launch_compose_1x1_bwd(const float *W, const float *theta, const floa
                                   const float *gbias_c, float *gW, float *gtheta, float *gbias, int Din0, int Dmid,
                                   int Dout, hipStream_t s)
 {
-    const int total = 4 * Dmid * Dout + Dmid * Din0;
-    hipLaunchKernelGGL(compose_1x1_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, W, theta, bias, gtheta_c,
-                       gbias_c, gW, gtheta, gbias, Din0, Dmid, Dout);
+    const int n_max = Dout > Din0 ? Dout : Din0;
+    hipLaunchKernelGGL(compose_1x1_bwd_kernel, dim3((Dmid + 63) / 64, (n_max + 63) / 64, 5), dim3(256), 0, s, W, theta,
+                       bias, gtheta_c, gbias_c, gW, gtheta, gbias, Din0, Dmid, Dout);
     return hipGetLastError();
 }
 

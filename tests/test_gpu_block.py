@@ -49,3 +49,25 @@ def test_block_matches_oracle(cfg_i, n, Din0, layout):
     assert rel_err(gW.cpu().numpy(), rW) <= TOL
     assert rel_err(gt.cpu().numpy(), rt) <= TOL
     assert rel_err(gb.cpu().numpy(), rb) <= TOL
+
+
+@pytest.mark.parametrize("Din0,Dmid,Dout", [(100, 130, 70), (200, 64, 257), (1, 5, 3), (64, 256, 128)])
+def test_compose_kernels_on_ragged_and_multi_tile_widths(Din0, Dmid, Dout):
+    """The composition and its transposes are plain matrix products over the channel indices: compared with their
+    definition (float64 einsum) at widths that span several 64 x 64 tiles and leave ragged edges."""
+    say(f"compose Din0={Din0} Dmid={Dmid} Dout={Dout}")
+    rng = np.random.default_rng(Din0 + Dout)
+    W = rng.standard_normal((Dmid, Din0)).astype(np.float32)
+    theta = rng.standard_normal((3, Dmid, Dout)).astype(np.float32)
+    bias = rng.standard_normal((Dmid, Dout)).astype(np.float32)
+    gtc = rng.standard_normal((3, Din0, Dout)).astype(np.float32)
+    gbc = rng.standard_normal((Din0, Dout)).astype(np.float32)
+    tc, bc = fx.flexconv_compose_1x1(dev(W), dev(theta), dev(bias))
+    gW, gt, gb = fx.flexconv_compose_1x1_bwd(dev(W), dev(theta), dev(bias), dev(gtc), dev(gbc))
+    torch.cuda.synchronize()
+    W64, t64, b64, gtc64, gbc64 = (a.astype(np.float64) for a in (W, theta, bias, gtc, gbc))
+    assert rel_err(tc.cpu().numpy(), np.einsum("ce,dco->deo", W64, t64)) <= 1e-6
+    assert rel_err(bc.cpu().numpy(), np.einsum("ce,co->eo", W64, b64)) <= 1e-6
+    assert rel_err(gt.cpu().numpy(), np.einsum("ce,deo->dco", W64, gtc64)) <= 1e-6
+    assert rel_err(gb.cpu().numpy(), np.einsum("ce,eo->co", W64, gbc64)) <= 1e-6
+    assert rel_err(gW.cpu().numpy(), np.einsum("dco,deo->ce", t64, gtc64) + np.einsum("co,eo->ce", b64, gbc64)) <= 1e-6
