@@ -102,9 +102,9 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr,
  * to grad_pos[b,d,n] with + and to grad_pos[b,d,l] with -.  grad_pos is [B,3,N] like pos,
  * overwritten.  Evaluated from plain neighbourhood sums (of feat over each point's neighbours, of
  * grad_out over the centres that list it) and one small contraction per point, without
- * floating-point atomics when both widths are among the tiled ones listed at flexconv_has_fast_path;
- * otherwise by a direct kernel with fp32 atomic adds (summation order, hence the last bits,
- * may vary).  in_off / in_src as for flexconv_bwd (NULL: built in the workspace).
+ * floating-point atomics (widths 32 / 64 directly; any other widths as the sum over 64 x 64 parameter
+ * blocks of the 64 -> 64 kernel's result on zero-padded 64-channel column blocks of the two tensors,
+ * copied into the workspace).  in_off / in_src as for flexconv_bwd (NULL: built in the workspace).
  */
 int flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *theta, const float *grad_out,
                      const int32_t *in_off, const int32_t *in_src, float *grad_pos,

@@ -340,10 +340,15 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
 }
 
 struct PosPlan {
-    bool lean;
-    size_t thetaC, thetaN, featT, gT, in_off, in_src, inedge_ws, total;
+    bool lean, blocked;
+    size_t thetaC, thetaN, featT, gT, thB, in_off, in_src, inedge_ws, total;
 };
 static inline int pad32(int x) { return (x + 31) / 32 * 32; }
+static bool pad_disabled()
+{
+    static const bool off = [] { const char *v = getenv("FLEX_PAD"); return v != nullptr && v[0] == '0'; }();
+    return off;
+}
 
 static PosPlan plan_pos(int64_t B, int64_t N, int K, int Din, int Dout, int layout, bool build)
 {
@@ -362,6 +367,21 @@ static PosPlan plan_pos(int64_t B, int64_t N, int K, int Din, int Dout, int layo
             p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
             p.inedge_ws = at; at += inedges_ws_bytes(B * N);
         }
+    } else if (!pad_disabled() && grad_pos_supported(64, 64, (int)N, K)) {
+        // other widths: the sum over 64 x 64 blocks of the parameters of the 64 -> 64 kernel's result on zero-padded
+        // point-major 64-channel column blocks of the two tensors (featT / gT hold those blocks, one after the other)
+        p.blocked = true;
+        const int n_hi = (Din + 63) / 64, n_ho = (Dout + 63) / 64;
+        p.thetaC = at; at += theta_pos_bytes(64, 64);
+        p.thetaN = at; at += theta_pos_bytes(64, 64);
+        p.thB = at;    at += align256(sizeof(float) * 3 * 64 * 64);
+        p.featT = at;  at += align256(sizeof(float) * (size_t)(B * N) * 64) * n_hi;
+        p.gT = at;     at += align256(sizeof(float) * (size_t)(B * N) * 64) * n_ho;
+        if (build) {
+            p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
+            p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
+            p.inedge_ws = at; at += inedges_ws_bytes(B * N);
+        }
     }
     p.total = at > 0 ? at : 256;
     return p;
@@ -373,8 +393,7 @@ static PosPlan plan_pos(int64_t B, int64_t N, int K, int Din, int Dout, int layo
 // results are the leading channels / the leading block of what the padded layer returns.
 static bool padded_shape(int Din, int Dout, int *DIp, int *DOp)
 {
-    static const bool off = [] { const char *v = getenv("FLEX_PAD"); return v != nullptr && v[0] == '0'; }();
-    if (off || wide_shape(Din, Dout)) return false;
+    if (pad_disabled() || wide_shape(Din, Dout)) return false;
     if (gather_contract_supported(Din, Dout) && gather_contract_supported(Dout, Din)) return false;
     if (Din <= 128 && Dout <= 128) {
         int64_t best = -1;
@@ -828,6 +847,35 @@ int flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *theta, 
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int bcn = (layout == FLEX_LAYOUT_BCN);
+    if (p.blocked) {
+        const int n_hi = (Din + 63) / 64, n_ho = (Dout + 63) / 64;
+        const size_t blk_bytes = align256(sizeof(float) * (size_t)B * N * 64);
+        for (int hi = 0; hi < n_hi; ++hi)
+            FLEX_HIP(launch_copy_rows(feat, (float *)(ws + p.featT + hi * blk_bytes), B, N, Din, 64, bcn, 0, s, 64 * hi));
+        for (int ho = 0; ho < n_ho; ++ho)
+            FLEX_HIP(launch_copy_rows(grad_out, (float *)(ws + p.gT + ho * blk_bytes), B, N, Dout, 64, bcn, 0, s, 64 * ho));
+        if (build) {
+            int32_t *off = (int32_t *)(ws + p.in_off), *src = (int32_t *)(ws + p.in_src);
+            FLEX_HIP(launch_inedges_build(nbr, B, N, K, off, src, ws + p.inedge_ws, s));
+            in_off = off;
+            in_src = src;
+        }
+        void *thC = ws + p.thetaC, *thN = ws + p.thetaN;
+        float *thB = (float *)(ws + p.thB);
+        for (int hi = 0; hi < n_hi; ++hi)
+            for (int ho = 0; ho < n_ho; ++ho) {
+                const float *f_blk = (const float *)(ws + p.featT + hi * blk_bytes);
+                const float *g_blk = (const float *)(ws + p.gT + ho * blk_bytes);
+                FLEX_HIP(launch_theta_block_padded(theta, thB, Din, Dout, 64 * hi, 64 * ho, 64, 64, s));
+                FLEX_HIP(launch_pack_theta_pos(thB, thC, 64, 64, 64, 64, 0, s));
+                FLEX_HIP(launch_pack_theta_pos(thB, thN, 64, 64, 64, 64, 1, s));
+                FLEX_HIP(launch_grad_pos_term(f_blk, nbr, nullptr, nullptr, thC, g_blk, grad_pos, -1.f,
+                                              (hi | ho) != 0, B, N, K, 64, 64, 0, s));
+                FLEX_HIP(launch_grad_pos_term(g_blk, nullptr, in_off, in_src, thN, f_blk, grad_pos, 1.f, 1, B, N, K, 64,
+                                              64, 1, s));
+            }
+        return FLEX_OK;
+    }
     if (!p.lean) {
         FLEX_HIP(launch_generic_bwd_pos(feat, nbr, theta, grad_out, grad_pos, B, N, K, Din, Dout, !bcn, s));
         return FLEX_OK;

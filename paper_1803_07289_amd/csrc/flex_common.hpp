@@ -59,7 +59,9 @@ hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const f
 
 // [B,C,N] -> [B,N,C] and back.
 hipError_t launch_copy_rows(const float *src, float *dst, int B, int N, int Cs, int Cd, int src_bcn, int dst_bcn,
-                            hipStream_t s);
+                            hipStream_t s, int c_off = 0);
+hipError_t launch_theta_block_padded(const float *theta, float *blk, int Din, int Dout, int r0, int c0, int nr, int nc,
+                                     hipStream_t s);
 hipError_t launch_bcn_to_bnc(const float *src, float *dst, int B, int C, int N, hipStream_t s);
 hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, hipStream_t s);
 

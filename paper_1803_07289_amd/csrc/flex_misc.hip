@@ -773,10 +773,12 @@ hipError_t launch_param_block(float *theta, float *bias, float *blk_theta, float
     return hipGetLastError();
 }
 
-// Row copy between feature tensors of different widths and layouts: dst[b, n, c] = c < Cs ? src[b, n, c] : 0 for
-// c < Cd (so Cd > Cs pads with zero channels, Cd < Cs keeps the first Cd).  *_bcn: that tensor is channel-major.
+// Row copy between feature tensors of different widths and layouts: dst[b, n, c] = src[b, n, c_off + c] where that
+// channel exists, else 0, for c < Cd (so it pads with zero channels, keeps the leading ones, or cuts a column block
+// out).  *_bcn: that tensor is channel-major.
 __global__ __launch_bounds__(256) void copy_rows_kernel(const float *__restrict__ src, float *__restrict__ dst,
-                                                        int64_t total, int N, int Cs, int Cd, int src_bcn, int dst_bcn)
+                                                        int64_t total, int N, int Cs, int Cd, int c_off, int src_bcn,
+                                                        int dst_bcn)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
@@ -785,19 +787,39 @@ __global__ __launch_bounds__(256) void copy_rows_kernel(const float *__restrict_
         if (dst_bcn) { n = (int)(i % N); const int64_t bc = i / N; c = (int)(bc % Cd); b = bc / Cd; }
         else         { c = (int)(i % Cd); const int64_t bn = i / Cd; n = (int)(bn % N); b = bn / N; }
         float v = 0.f;
-        if (c < Cs) v = src_bcn ? src[(b * Cs + c) * N + n] : src[(b * N + n) * Cs + c];
+        const int cs = c_off + c;
+        if (cs < Cs) v = src_bcn ? src[(b * Cs + cs) * N + n] : src[(b * N + n) * Cs + cs];
         dst[i] = v;
     }
 }
 
 hipError_t launch_copy_rows(const float *src, float *dst, int B, int N, int Cs, int Cd, int src_bcn, int dst_bcn,
-                            hipStream_t s)
+                            hipStream_t s, int c_off)
 {
     const int64_t total = (int64_t)B * N * Cd;
     int64_t blocks = (total + 255) / 256;
     if (blocks > (1 << 20)) blocks = 1 << 20;
-    hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, total, N, Cs, Cd, src_bcn,
-                       dst_bcn);
+    hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, dst, total, N, Cs, Cd, c_off,
+                       src_bcn, dst_bcn);
+    return hipGetLastError();
+}
+
+// blk[d][r][c] = theta[d][r0 + r][c0 + c] where that entry exists, else 0; blk is [3][nr][nc].
+__global__ __launch_bounds__(256) void theta_block_padded_kernel(const float *__restrict__ theta, float *__restrict__ blk,
+                                                                 int Din, int Dout, int r0, int c0, int nr, int nc)
+{
+    const int total = 3 * nr * nc;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const int c = c0 + i % nc, r = r0 + (i / nc) % nr, d = i / (nc * nr);
+        blk[i] = (r < Din && c < Dout) ? theta[((int64_t)d * Din + r) * Dout + c] : 0.f;
+    }
+}
+
+hipError_t launch_theta_block_padded(const float *theta, float *blk, int Din, int Dout, int r0, int c0, int nr, int nc,
+                                     hipStream_t s)
+{
+    hipLaunchKernelGGL(theta_block_padded_kernel, dim3((3 * nr * nc + 255) / 256), dim3(256), 0, s, theta, blk, Din,
+                       Dout, r0, c0, nr, nc);
     return hipGetLastError();
 }
 

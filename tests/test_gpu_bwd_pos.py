@@ -18,7 +18,10 @@ SHAPES = [
     (2, 77, 8, 32, 32),
     (1, 300, 16, 64, 32),
     (2, 100, 8, 32, 64),
-    (1, 257, 8, 9, 64),        # Din = 9: no matrix-core kernel for this width -> direct kernel
+    (1, 257, 8, 9, 64),        # widths without a location-gradient kernel of their own: 64-channel column blocks
+    (1, 300, 8, 256, 128),     # 4 x 2 blocks
+    (2, 200, 8, 100, 200),     # ragged last blocks
+    (1, 150, 9, 128, 128),
     (1, 130, 5, 64, 64),       # K not a multiple of 8: last batch of a tile has empty slots
     (2, 333, 9, 64, 64),
     (1, 500, 13, 32, 64),

@@ -19,7 +19,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 def test_parity_file_under_switch(env):
     child_env = dict(os.environ)
     child_env.update(env)
-    r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.join(HERE, "test_gpu_parity.py"), "-x", "-q",
+    files = [os.path.join(HERE, "test_gpu_parity.py")]
+    if "FLEX_PAD" in env:
+        files.append(os.path.join(HERE, "test_gpu_bwd_pos.py"))     # its direct-form kernel is reached the same way
+    r = subprocess.run([sys.executable, "-u", "-m", "pytest", *files, "-x", "-q",
                         "-m", "gpu", "--timeout", "120", "--timeout-method", "thread", "-p", "no:cacheprovider"],
                        capture_output=True, text=True, env=child_env, cwd=os.path.dirname(HERE), timeout=600)
     tail = "\n".join((r.stdout + r.stderr).splitlines()[-15:])
