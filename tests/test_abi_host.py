@@ -129,7 +129,9 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
     w = L.flexconv_workspace_bytes
     assert w(4, 2, 1000, 1, 1, 1, 0) == 8192                   # inverse map: 4 bytes per larger-layer point, 256-aligned
     assert w(6, 1, 4096, 8, 64, 64, 1) > w(5, 1, 4096, 8, 64, 64, 1) > 256    # lists built inside the call cost workspace
-    assert w(5, 1, 4096, 8, 5, 7, 1) == 256                    # direct kernel: nothing needed
+    # other widths: packed 64 x 64 parameter block (both orientations, 6 f16 planes + exponent slot each), its fp32
+    # source, and one zero-padded 64-channel column block of each tensor
+    assert w(5, 1, 4096, 8, 5, 7, 1) == 2 * (6 * 64 * 64 * 2 + 256) + 3 * 64 * 64 * 4 + 2 * 4096 * 64 * 4
 
 
 def test_workspace_sizes(L):
