@@ -46,7 +46,8 @@ def main():
     ap.add_argument("--only", default=None,
                     help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; upsample = flex-upsampling from a "
                          "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
-                         "quarter of the points; none of them is part of the default step)")
+                         "quarter of the points, idiss = importance sub-sampling of a quarter of the points, knn = the "
+                         "neighbour search; none of them is part of the default step)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture one step into a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -107,7 +108,11 @@ def main():
     names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos", "pool_sub") if n in ops]
     state = {}
     OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
-           "pool_sub_fwd", "pool_sub_bwd")
+           "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn")
+    if "idiss" in ops:
+        # random words for the stratified draw of a quarter of the points (Sec. 3.3), drawn once
+        u_words = torch.from_numpy(np.random.default_rng([cfg.seed, 400]).integers(
+            0, 2 ** 32, size=(B, max(1, N // 4)), dtype=np.uint64).astype(np.uint32).view(np.int32)).cuda()
     if "upsample" in ops or "pool_sub" in ops:
         # the smaller layer: a seeded quarter of the points (a decoder stage raises the resolution 4x)
         Ns = max(1, N // 4)
@@ -159,6 +164,15 @@ def main():
             state["pool_sub_grad"] = fx.flexpool_sub_bwd(g_small, state["pool_sub"][1], N, layout=layout,
                                                          in_edges=sub_edges)
         mark(10)
+        if "idiss" in ops:
+            state["phi"] = fx.flex_idiss_phi(pos, nbr)
+        mark(11)
+        if "idiss" in ops:
+            state["sel"] = fx.flex_selection_make_distinct(fx.flex_idiss_sample(state["phi"], u_words), N)
+        mark(12)
+        if "knn" in ops:
+            state["knn"] = fx.flex_knn(pos, K)
+        mark(13)
 
     if args.calibrate_copy:
         scratch = torch.empty_like(feat)
@@ -170,7 +184,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(11)] for _ in range(args.steps)]
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(14)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -237,7 +251,7 @@ def main():
             r["issued_matrix_frac_of_f16_peak"] = r["issued_matrix_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
         return r
 
-    rooflines = {n: roof(n) for n in OPS if op_ms[n]["mean"] > 1e-2}
+    rooflines = {n: roof(n) for n in OPS if n in bytes_pt and op_ms[n]["mean"] > 1e-2}
     dominant = max(rooflines, key=lambda n: rooflines[n]["kernel_ms"]) if rooflines else None
     roofline = rooflines.get(dominant)
     fwd_ms = op_ms["fwd"]["mean"]
