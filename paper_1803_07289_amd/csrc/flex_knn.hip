@@ -63,10 +63,18 @@ __global__ __launch_bounds__(256) void knn_bbox_kernel(const float *__restrict__
             mn[d] = min(mn[d], (unsigned)__shfl_xor((int)mn[d], s, 64));
             mx[d] = max(mx[d], (unsigned)__shfl_xor((int)mx[d], s, 64));
         }
-        if ((threadIdx.x & 63) == 0) {
-            atomicMin(&bbox[6 * b + d], mn[d]);
-            atomicMax(&bbox[6 * b + 3 + d], mx[d]);
-        }
+    }
+    // one pair of atomics per block and coordinate: thousands of atomics on the same six words serialise
+    __shared__ unsigned s_mn[4][3], s_mx[4][3];
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0)
+#pragma unroll
+        for (int d = 0; d < 3; ++d) { s_mn[w][d] = mn[d]; s_mx[w][d] = mx[d]; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        const int d = threadIdx.x;
+        atomicMin(&bbox[6 * b + d], min(min(s_mn[0][d], s_mn[1][d]), min(s_mn[2][d], s_mn[3][d])));
+        atomicMax(&bbox[6 * b + 3 + d], max(max(s_mx[0][d], s_mx[1][d]), max(s_mx[2][d], s_mx[3][d])));
     }
 }
 
@@ -248,7 +256,7 @@ hipError_t launch_knn(const float *pos, int32_t *nbr, int B, int N, int K, void 
     hipLaunchKernelGGL(knn_bbox_init_kernel, dim3((6 * B + 255) / 256), dim3(256), 0, s, bbox, B);
     int nb = (int)((N + 255) / 256);
     if (nb > 2048) nb = 2048;
-    hipLaunchKernelGGL(knn_bbox_kernel, dim3(nb, B), dim3(256), 0, s, pos, bbox, N);
+    hipLaunchKernelGGL(knn_bbox_kernel, dim3(nb < 512 ? nb : 512, B), dim3(256), 0, s, pos, bbox, N);
     hipError_t e = launch_fill_zero(cnt, sizeof(int32_t) * (size_t)cells, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(knn_count_kernel, dim3(nb, B), dim3(256), 0, s, pos, bbox, cell, cnt, N, cpc);
