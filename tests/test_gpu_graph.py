@@ -12,9 +12,12 @@ from workloads import CONFIGS, make_inputs
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg_i,n", [(1, None), (0, 3000)])
-def test_layer_step_replays_from_a_graph(cfg_i, n):
+@pytest.mark.parametrize("cfg_i,n,widths", [(1, None, None), (0, 3000, None), (0, 2000, (256, 128)), (0, 1500, (20, 13))],
+                         ids=["config1", "config0", "wide_256x128", "padded_20x13"])
+def test_layer_step_replays_from_a_graph(cfg_i, n, widths):
     cfg = CONFIGS[cfg_i]
+    if widths is not None:      # block passes / zero-padded copies: more kernels per entry point, still kernels only
+        cfg = type(cfg)(**{**cfg.__dict__, "Din": widths[0], "Dout": widths[1]})
     x = make_inputs(cfg, n_override=n)
     say(f"graph capture {x.cfg.name} N={x.cfg.N}")
     L = fx.BNC
