@@ -66,7 +66,8 @@ typedef enum {
  *   out[b,o,l] = sum_k sum_c ( <theta[:,c,o], pos[b,:,n]-pos[b,:,l]> + bias[c,o] ) * feat[b,c,n],
  *   n = nbr[b,k,l].
  * Computed in fp32 in the factored form (per-point 4*Din aggregate, then a
- * (4*Din x Dout) contraction on the matrix cores).
+ * (4*Din x Dout) contraction on the matrix cores).  Any Din, Dout: see
+ * flexconv_has_fast_path for how a pair of widths is run.
  */
 int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
                  const float *theta, const float *bias, float *out,
