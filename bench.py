@@ -110,7 +110,7 @@ def main():
     OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
            "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn")
     if "idiss" in ops:
-        # random words for the stratified draw of a quarter of the points (Sec. 3.3), drawn once
+        # random words for the stratified draw of a quarter of the points (Sec. 3.2), drawn once
         u_words = torch.from_numpy(np.random.default_rng([cfg.seed, 400]).integers(
             0, 2 ** 32, size=(B, max(1, N // 4)), dtype=np.uint64).astype(np.uint32).view(np.int32)).cuda()
     if "upsample" in ops or "pool_sub" in ops:

@@ -151,7 +151,7 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
                  int B, int N, int K, int C, int layout, void *stream);
 
 /*
- * 1x1 convolution composed into a flex-convolution (Sec. 5: a ResNet block chains a 1x1
+ * 1x1 convolution composed into a flex-convolution (Sec. 4.3: a ResNet block chains a 1x1
  * convolution and flex-convolutions; the paper names no bias in the 1x1 step and no activation
  * between it and the next step, and this entry point assumes neither).  With mid = W feat,
  * W [Dmid,Din0], the next layer flexconv(theta [3,Dmid,Dout], bias [Dmid,Dout]) over mid equals a
@@ -178,7 +178,7 @@ int flexconv_compose_1x1_bwd(const float *W, const float *theta, const float *bi
 
 /*
  * Flex-max-pooling with subsampling, forward (Sec. 4.1: pooling runs before the subsampling step;
- * Sec. 5: the last layer of an encoder stage, which keeps a quarter of the points).  The result
+ * Sec. 4.3: the last layer of an encoder stage, which keeps a quarter of the points).  The result
  * is that of flexpool_fwd restricted to the kept centres, and only those are evaluated:
  *   out[b,c,j] = max_k feat[b,c,nbr[b,k,sel[b,j]]],  argmax[b,c,j] = the winning point, an index
  *   into the N points before subsampling (pooling's tie rule).
@@ -229,7 +229,7 @@ int flex_knn(const float *pos, int32_t *nbr, int B, int N, int K,
              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Inverse density importance sub-sampling, step 1 (Sec. 3.3): phi[b,l] = sum over the K
+ * Inverse density importance sub-sampling, step 1 (Sec. 3.2): phi[b,l] = sum over the K
  * neighbours n of ||pos[b,:,l] - pos[b,:,n]||, the paper's approximation of the inverse
  * density.  pos [B,3,N], nbr int32 [B,K,N], phi fp32 [B,N] (overwritten).
  */
@@ -306,11 +306,26 @@ int flex_validate_neighbors(const int32_t *nbr, int B, int N, int K,
 
 /* 1 if flexconv_fwd / flexconv_bwd run (Din,Dout) on the matrix-core kernels: the tiled widths 32->32, 64->64,
  * 128->128, 9->64, 64->9, 32->64, 64->32, 64->128, 128->64, and every pair of multiples of 128 (run as passes over
- * 64- / 128-channel column blocks; the deeper stages of the network of Sec. 5, whose feature length doubles from
+ * 64- / 128-channel column blocks; the deeper stages of the network of Sec. 4.3, whose feature length doubles from
  * stage to stage).  2: any other widths, which run zero-padded at the nearest widths of that list (padded copies
  * of the tensors live in the workspace, whose size flexconv_workspace_bytes reports).  0: the direct-form kernels
  * (orders of magnitude slower; only with padding or block passes switched off in the environment). */
 int flexconv_has_fast_path(int Din, int Dout);
+
+/* Which kernel family a flexconv_fwd (op = FLEX_OP_CONV_FWD) or the feature gradient of a flexconv_bwd
+ * (op = FLEX_OP_CONV_BWD) call of these sizes runs on; -1 on bad sizes.  A host-side query (nothing is launched) of
+ * the same decision the entry points dispatch on, so that the size limits of every family (32-bit byte offsets
+ * inside a cloud for the lean kernels and the block passes) can be checked without running a cloud that large. */
+typedef enum {
+    FLEX_ROUTE_DIRECT = 0,     /* direct-form kernels (Eq. 6 per neighbour, channel pair) */
+    FLEX_ROUTE_SINGLE_ROLE = 1,/* tiled kernels, every wave gathers then contracts (fp32 matrix op) */
+    FLEX_ROUTE_STAGED = 2,     /* wave-specialised kernels with LDS-staged producers */
+    FLEX_ROUTE_LEAN = 3,       /* wave-specialised kernels with lean producers (the headline path) */
+    FLEX_ROUTE_SPLIT128 = 4,   /* 128 -> 128 point-major as two passes of the 64-wide lean kernels */
+    FLEX_ROUTE_WIDE = 5,       /* block passes over 64- / 128-channel column blocks */
+    FLEX_ROUTE_PADDED = 6      /* zero-padded to the nearest widths with a matrix-core path */
+} flex_route;
+int flexconv_kernel_route(int op, int B, int N, int K, int Din, int Dout, int layout);
 
 const char *flex_status_string(int status);
 

@@ -245,7 +245,7 @@ def block_bwd(feat, pos, nbr, W, theta, bias, grad_out):
 
 
 def idiss_phi(pos, nbr):
-    """Sum of the distances to the K neighbours (Sec. 3.3).  Returns float64 [B,N]."""
+    """Sum of the distances to the K neighbours (Sec. 3.2).  Returns float64 [B,N]."""
     pos, nbr = _f32(pos), _i32(nbr)
     B, _, N = pos.shape
     K = nbr.shape[1]

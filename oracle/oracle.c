@@ -389,7 +389,7 @@ int oracle_flexupsample_bwd(const float *grad_out, const int32_t *argmax, const 
 
 /* ---------------------------------------------------------------------------
  * Flex-max-pooling with subsampling (Sec. 4.1: pooling is applied before the
- * subsampling step; Sec. 5: the layer that ends an encoder stage).  Taken in
+ * subsampling step; Sec. 4.3: the layer that ends an encoder stage).  Taken in
  * the paper's order: the neighbourhood maximum at EVERY point (pooling's tie
  * rule), then the columns of the kept points sel[b,j] are copied out.
  * out / argmax are [B,C,Ns]; argmax holds indices into the N points.
@@ -508,7 +508,7 @@ int oracle_flexconv_bwd_pos(const float *feat, const int32_t *nbr, const float *
 }
 
 /* ---------------------------------------------------------------------------
- * First two operations of the encoder's ResNet block (Sec. 5: 1x1-convolution, then
+ * First two operations of the encoder's ResNet block (Sec. 4.3: 1x1-convolution, then
  * flex-convolution).  The paper names no bias for the 1x1 step and no activation between
  * the two, and none is applied here:
  *   mid[b,c,n] = sum_c0 W[c,c0] * feat[b,c0,n]                          (1x1 convolution)
@@ -630,7 +630,7 @@ int oracle_block_bwd(const float *feat, const float *pos, const int32_t *nbr, co
 }
 
 /* ---------------------------------------------------------------------------
- * Inverse density importance sub-sampling (Sec. 3.3).
+ * Inverse density importance sub-sampling (Sec. 3.2).
  * Step 1: phi[b,l] = sum over the neighbourhood of the distances ||pos[l] - pos[n]|| (the
  * paper's approximation of the inverse density).  phi is double [B,N].
  * ------------------------------------------------------------------------- */

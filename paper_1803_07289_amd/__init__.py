@@ -48,6 +48,7 @@ _SIGS = {
     "flexconv_workspace_bytes": (_sz, [_i] * 7),
     "flex_validate_neighbors": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "flexconv_has_fast_path": (_i, [_i, _i]),
+    "flexconv_kernel_route": (_i, [_i] * 7),
     "flex_status_string": (ctypes.c_char_p, [_i]),
 }
 
@@ -129,6 +130,21 @@ def _workspace(device, nbytes):
     return ws
 
 
+def _ws_arg(workspace, device, need):
+    """(tensor, byte count handed to the library): a caller's workspace with its own size, else the cached one
+    with exactly the size the library asked for, so that the library's own size check sees `need`."""
+    if workspace is not None:
+        if not workspace.is_cuda or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+            raise TypeError("workspace must be a contiguous CUDA uint8 tensor")
+        return workspace, workspace.numel()
+    return _workspace(device, need), max(int(need), 256)
+
+
+def kernel_route(op, B, N, K, Din, Dout, layout=BCN):
+    """Which kernel family a call of these sizes runs on (a flex_route value of include/flexconv.h; host query)."""
+    return int(lib().flexconv_kernel_route(op, B, N, K, Din, Dout, _layout(layout)))
+
+
 def flexconv_fwd(feat, pos, nbr, theta, bias, layout=BCN, out=None, workspace=None):
     """Flex-convolution forward (Eq. 4 with the weight of Eq. 6).  Returns out."""
     layout = _layout(layout)
@@ -146,9 +162,9 @@ def flexconv_fwd(feat, pos, nbr, theta, bias, layout=BCN, out=None, workspace=No
     elif tuple(_dev(out, torch.float32, "out").shape) != shape:
         raise ValueError("out has the wrong shape")
     need = workspace_bytes(OP_CONV_FWD, B, N, K, Din, Dout, layout)
-    ws = workspace if workspace is not None else _workspace(feat.device, need)
+    ws, ws_bytes = _ws_arg(workspace, feat.device, need)
     _check(lib().flexconv_fwd(_ptr(feat), _ptr(pos), _ptr(nbr), _ptr(theta), _ptr(bias), _ptr(out),
-                              B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_fwd")
+                              B, N, K, Din, Dout, layout, _ptr(ws), ws_bytes, _stream()), "flexconv_fwd")
     return out
 
 
@@ -159,8 +175,8 @@ def flex_inedges_build(nbr, workspace=None):
     in_off = torch.empty(B * N + 1, dtype=torch.int32, device=nbr.device)
     in_src = torch.empty(B * K * N, dtype=torch.int32, device=nbr.device)
     need = workspace_bytes(OP_INEDGES, B, N, K, 1, 1, BCN)
-    ws = workspace if workspace is not None else _workspace(nbr.device, need)
-    _check(lib().flex_inedges_build(_ptr(nbr), B, N, K, _ptr(in_off), _ptr(in_src), _ptr(ws), ws.numel(),
+    ws, ws_bytes = _ws_arg(workspace, nbr.device, need)
+    _check(lib().flex_inedges_build(_ptr(nbr), B, N, K, _ptr(in_off), _ptr(in_src), _ptr(ws), ws_bytes,
                                     _stream()), "flex_inedges_build")
     return in_off, in_src
 
@@ -193,10 +209,10 @@ def flexconv_bwd(feat, pos, nbr, theta, bias, grad_out, layout=BCN, in_edges=Non
             raise ValueError("in_edges do not match nbr")
     op = OP_CONV_BWD if in_edges is not None else OP_CONV_BWD_BUILD
     need = workspace_bytes(op, B, N, K, Din, Dout, layout)
-    ws = workspace if workspace is not None else _workspace(feat.device, need)
+    ws, ws_bytes = _ws_arg(workspace, feat.device, need)
     _check(lib().flexconv_bwd(_ptr(feat), _ptr(pos), _ptr(nbr), _ptr(theta), _ptr(bias), _ptr(grad_out),
                               _ptr(gf), _ptr(gt), _ptr(gb), _ptr(off), _ptr(src),
-                              B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_bwd")
+                              B, N, K, Din, Dout, layout, _ptr(ws), ws_bytes, _stream()), "flexconv_bwd")
     return gf, gt, gb
 
 
@@ -220,9 +236,9 @@ def flexconv_bwd_pos(feat, nbr, theta, grad_out, layout=BCN, in_edges=None, work
     gp = torch.empty((B, 3, N), dtype=torch.float32, device=feat.device)
     op = OP_CONV_BWD_POS if in_edges is not None else OP_CONV_BWD_POS_BUILD
     need = workspace_bytes(op, B, N, K, Din, Dout, layout)
-    ws = workspace if workspace is not None else _workspace(feat.device, need)
+    ws, ws_bytes = _ws_arg(workspace, feat.device, need)
     _check(lib().flexconv_bwd_pos(_ptr(feat), _ptr(nbr), _ptr(theta), _ptr(grad_out), _ptr(off), _ptr(src), _ptr(gp),
-                                  B, N, K, Din, Dout, layout, _ptr(ws), ws.numel(), _stream()), "flexconv_bwd_pos")
+                                  B, N, K, Din, Dout, layout, _ptr(ws), ws_bytes, _stream()), "flexconv_bwd_pos")
     return gp
 
 
@@ -265,7 +281,7 @@ def flexpool_bwd(grad_out, argmax, layout=BCN, in_edges=None, K=None):
 
 def flexconv_compose_1x1(W, theta, bias):
     """Parameters of the flex-convolution that equals `1x1 convolution W [Dmid,Din0] (no bias), then
-    flexconv(theta [3,Dmid,Dout], bias [Dmid,Dout])` (Sec. 5 block).  Returns (theta_c [3,Din0,Dout], bias_c [Din0,Dout])."""
+    flexconv(theta [3,Dmid,Dout], bias [Dmid,Dout])` (Sec. 4.3 block).  Returns (theta_c [3,Din0,Dout], bias_c [Din0,Dout])."""
     _dev(W, torch.float32, "W"); _dev(theta, torch.float32, "theta"); _dev(bias, torch.float32, "bias")
     Dmid, Din0 = W.shape
     if theta.dim() != 3 or theta.shape[0] != 3 or theta.shape[1] != Dmid or tuple(bias.shape) != (Dmid, theta.shape[2]):
@@ -308,13 +324,13 @@ def flex_knn(pos, K, workspace=None):
     need = workspace_bytes(OP_KNN, B, N, int(K), 1, 1, BCN)
     if need == 0:
         raise ValueError(f"flex_knn does not take B={B}, N={N}, K={K}")
-    ws = workspace if workspace is not None else _workspace(pos.device, need)
-    _check(lib().flex_knn(_ptr(pos.contiguous()), _ptr(nbr), B, N, int(K), _ptr(ws), ws.numel(), _stream()), "flex_knn")
+    ws, ws_bytes = _ws_arg(workspace, pos.device, need)
+    _check(lib().flex_knn(_ptr(pos.contiguous()), _ptr(nbr), B, N, int(K), _ptr(ws), ws_bytes, _stream()), "flex_knn")
     return nbr
 
 
 def flex_idiss_phi(pos, nbr):
-    """phi [B,N]: sum of the distances from every point to its K neighbours (Sec. 3.3)."""
+    """phi [B,N]: sum of the distances from every point to its K neighbours (Sec. 3.2)."""
     _dev(pos, torch.float32, "pos"); _dev(nbr, torch.int32, "nbr")
     B, K, N = nbr.shape
     if tuple(pos.shape) != (B, 3, N):
@@ -336,9 +352,9 @@ def flex_idiss_sample(phi, u, workspace=None):
         raise ValueError("u must be [B,Ns]")
     sel = torch.empty((B, Ns), dtype=torch.int32, device=phi.device)
     need = workspace_bytes(OP_IDISS, B, N, 1, 1, 1, BCN)
-    ws = workspace if workspace is not None else _workspace(phi.device, need)
+    ws, ws_bytes = _ws_arg(workspace, phi.device, need)
     _check(lib().flex_idiss_sample(_ptr(phi.contiguous()), _ptr(u.contiguous()), _ptr(sel), B, N, Ns, _ptr(ws),
-                                   ws.numel(), _stream()), "flex_idiss_sample")
+                                   ws_bytes, _stream()), "flex_idiss_sample")
     return sel
 
 
@@ -350,8 +366,8 @@ def flex_selection_make_distinct(sel, N, workspace=None):
         raise ValueError("sel must be a contiguous [B,Ns] tensor")
     B, Ns = sel.shape
     need = workspace_bytes(OP_IDISS, B, N, 1, 1, 1, BCN)
-    ws = workspace if workspace is not None else _workspace(sel.device, need)
-    _check(lib().flex_selection_make_distinct(_ptr(sel), B, int(N), Ns, _ptr(ws), ws.numel(), _stream()),
+    ws, ws_bytes = _ws_arg(workspace, sel.device, need)
+    _check(lib().flex_selection_make_distinct(_ptr(sel), B, int(N), Ns, _ptr(ws), ws_bytes, _stream()),
            "flex_selection_make_distinct")
     return sel
 
@@ -384,9 +400,9 @@ def flex_inedges_build_sub(nbr, sel, workspace=None):
     off = torch.empty(B * N + 1, dtype=torch.int32, device=nbr.device)
     src = torch.empty(B * K * Ns, dtype=torch.int32, device=nbr.device)
     need = workspace_bytes(OP_INEDGES, B, N, K, 1, 1, BCN)
-    ws = workspace if workspace is not None else _workspace(nbr.device, need)
+    ws, ws_bytes = _ws_arg(workspace, nbr.device, need)
     _check(lib().flex_inedges_build_sub(_ptr(nbr), _ptr(sel), B, N, Ns, K, _ptr(off), _ptr(src), _ptr(ws),
-                                        ws.numel(), _stream()), "flex_inedges_build_sub")
+                                        ws_bytes, _stream()), "flex_inedges_build_sub")
     return off, src
 
 
@@ -438,9 +454,9 @@ def flexupsample_fwd(feat_small, sel, nbr, layout=BCN, workspace=None):
     out = torch.empty(shape, dtype=torch.float32, device=feat_small.device)
     arg = torch.empty(shape, dtype=torch.int32, device=feat_small.device)
     need = workspace_bytes(OP_UPSAMPLE, B, Nf, K, C, 1, layout)
-    ws = workspace if workspace is not None else _workspace(feat_small.device, need)
+    ws, ws_bytes = _ws_arg(workspace, feat_small.device, need)
     _check(lib().flexupsample_fwd(_ptr(feat_small), _ptr(sel), _ptr(nbr), _ptr(out), _ptr(arg), B, Ns, Nf, K, C,
-                                  layout, _ptr(ws), ws.numel(), _stream()), "flexupsample_fwd")
+                                  layout, _ptr(ws), ws_bytes, _stream()), "flexupsample_fwd")
     return out, arg
 
 
@@ -470,8 +486,8 @@ def flex_validate_selection(sel, Nf, workspace=None):
     B, Ns = sel.shape
     bad = torch.zeros(1, dtype=torch.int32, device=sel.device)
     need = workspace_bytes(OP_UPSAMPLE, B, Nf, 1, 1, 1, BCN)
-    ws = workspace if workspace is not None else _workspace(sel.device, need)
-    _check(lib().flex_validate_selection(_ptr(sel), B, Ns, Nf, _ptr(bad), _ptr(ws), ws.numel(), _stream()),
+    ws, ws_bytes = _ws_arg(workspace, sel.device, need)
+    _check(lib().flex_validate_selection(_ptr(sel), B, Ns, Nf, _ptr(bad), _ptr(ws), ws_bytes, _stream()),
            "flex_validate_selection")
     return int(bad.item())
 

@@ -11,6 +11,7 @@ namespace flex {
                                      const int32_t *, const void *, int, float *, int, int, int,     \
                                      int, int, hipStream_t);                                         \
     int theta_format_##DI##_##DO(int, int, int);                                                       \
+    int route_##DI##_##DO(int, int, int);                                                              \
     bool gp_ok_##DI##_##DO(int, int);                                                                 \
     hipError_t launch_gp_##DI##_##DO(const float *, const int32_t *, const int32_t *, const int32_t *, \
                                      const void *, const float *, float *, float, int, int, int, int,  \
@@ -70,6 +71,15 @@ int gather_contract_theta_format(int DI, int DO, int N, int K, int csr)
 {
 #define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_) return theta_format_##DI_##_##DO_(N, K, csr);
+#include "flex_shapes.def"
+#undef FLEX_SHAPE
+    return 0;
+}
+
+int gather_contract_route(int DI, int DO, int N, int K, int csr)
+{
+#define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
+    if (DI == DI_ && DO == DO_) return route_##DI_##_##DO_(N, K, csr);
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
     return 0;
@@ -172,7 +182,7 @@ static hipError_t split_grad_theta_128(const float *rows, const float *pos, cons
 }
 
 // Wide layers (both widths multiples of 128, not 128 -> 128 itself): the paper's network doubles the feature
-// length at every resolution stage (Sec. 5), so its deeper stages are of this kind.  They run as passes of the
+// length at every resolution stage (Sec. 4.3), so its deeper stages are of this kind.  They run as passes of the
 // 64 -> 128 (forward, feature gradient) and 64 -> 64 (parameter gradients) lean kernels over column blocks of the
 // point-major tensors.
 static bool split_disabled()
@@ -306,11 +316,15 @@ struct BwdPlan {
     size_t thetaP, featT, gT, gfT, partials, in_off, in_src, inedge_ws, total;
 };
 
-static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout)
+// The route (block passes of the wide path / single-pass tiled kernels / direct form) is decided here, once, from
+// everything it depends on (sizes, layout, environment switches); the entry points dispatch on the plan's flags
+// and never re-decide, so what they write is what the plan reserved.
+static FwdPlan plan_fwd(int64_t B, int64_t N, int K, int Din, int Dout, int layout)
 {
     FwdPlan p{};
     p.tiled = gather_contract_supported(Din, Dout);
-    p.wide = (!p.tiled && wide_shape(Din, Dout)) || wide_route_128(Din, Dout, layout);
+    p.wide = ((!p.tiled && wide_shape(Din, Dout)) || wide_route_128(Din, Dout, layout)) &&
+             split_wide_ok((int)N, K, Din > Dout ? Din : Dout);
     size_t at = 0;
     if (p.tiled || p.wide) {
         p.thetaP = at; at += p.wide ? wide_param_scratch_bytes(Din, Dout) : theta_ws_bytes(Din, Dout);
@@ -325,7 +339,8 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
 {
     BwdPlan p{};
     p.tiled = gather_contract_supported(Din, Dout) && gather_contract_supported(Dout, Din);
-    p.wide = (!p.tiled && wide_shape(Din, Dout)) || wide_route_128(Din, Dout, layout);
+    p.wide = ((!p.tiled && wide_shape(Din, Dout)) || wide_route_128(Din, Dout, layout)) &&
+             split_wide_ok((int)N, K, Din > Dout ? Din : Dout);
     size_t at = 0;
     if (p.tiled || p.wide) {
         p.thetaP = at; at += p.wide ? wide_param_scratch_bytes(Din, Dout) : theta_ws_bytes(Dout, Din);
@@ -418,7 +433,7 @@ static bool padded_shape(int Din, int Dout, int *DIp, int *DOp)
     return wide_shape(*DIp, *DOp);
 }
 
-static FwdPlan plan_fwd(int64_t B, int64_t N, int Din, int Dout, int layout);
+static FwdPlan plan_fwd(int64_t B, int64_t N, int K, int Din, int Dout, int layout);
 static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layout, bool build);
 
 struct PadPlan {
@@ -441,7 +456,7 @@ static PadPlan plan_pad(int64_t B, int64_t N, int K, int DIp, int DOp, bool bwd,
     }
     p.sub = at;
     p.sub_bytes = bwd ? plan_bwd(B, N, K, DIp, DOp, FLEX_LAYOUT_BNC, build).total
-                      : plan_fwd(B, N, DIp, DOp, FLEX_LAYOUT_BNC).total;
+                      : plan_fwd(B, N, K, DIp, DOp, FLEX_LAYOUT_BNC).total;
     p.total = at + p.sub_bytes;
     return p;
 }
@@ -507,6 +522,27 @@ int flexconv_has_fast_path(int Din, int Dout)
     return padded_shape(Din, Dout, &a, &b) ? 2 : 0;
 }
 
+int flexconv_kernel_route(int op, int B, int N, int K, int Din, int Dout, int layout)
+{
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return -1;
+    if (op != FLEX_OP_CONV_FWD && op != FLEX_OP_CONV_BWD) return -1;
+    if (!sizes_ok(B, N, K, Din, Dout)) return -1;
+    int DIp, DOp;
+    if (padded_shape(Din, Dout, &DIp, &DOp)) return FLEX_ROUTE_PADDED;
+    if (op == FLEX_OP_CONV_FWD) {
+        const FwdPlan p = plan_fwd(B, N, K, Din, Dout, layout);
+        if (p.wide) return FLEX_ROUTE_WIDE;
+        if (!p.tiled) return FLEX_ROUTE_DIRECT;
+        if (use_split_128(Din, Dout, layout, N, K, 0)) return FLEX_ROUTE_SPLIT128;
+        return gather_contract_route(Din, Dout, N, K, 0);
+    }
+    const BwdPlan p = plan_bwd(B, N, K, Din, Dout, layout, false);
+    if (p.wide) return FLEX_ROUTE_WIDE;
+    if (!p.tiled) return FLEX_ROUTE_DIRECT;
+    if (use_split_128(Din, Dout, layout, N, K, 1)) return FLEX_ROUTE_SPLIT128;
+    return gather_contract_route(Dout, Din, N, K, 1);
+}
+
 size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, int layout)
 {
     if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return 0;
@@ -518,7 +554,7 @@ size_t flexconv_workspace_bytes(int op, int B, int N, int K, int Din, int Dout, 
         int DIp, DOp;
         if (padded_shape(Din, Dout, &DIp, &DOp))
             return plan_pad(B, N, K, DIp, DOp, op != FLEX_OP_CONV_FWD, op == FLEX_OP_CONV_BWD_BUILD).total;
-        if (op == FLEX_OP_CONV_FWD) return plan_fwd(B, N, Din, Dout, layout).total;
+        if (op == FLEX_OP_CONV_FWD) return plan_fwd(B, N, K, Din, Dout, layout).total;
         return plan_bwd(B, N, K, Din, Dout, layout, op == FLEX_OP_CONV_BWD_BUILD).total;
     }
     case FLEX_OP_INEDGES: return sizes_ok(B, N, K, 1, 1) ? inedges_ws_bytes((int64_t)B * N) : 0;
@@ -556,9 +592,9 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
         FLEX_HIP(launch_copy_rows(outP, out, B, N, DOp, Dout, 0, bcn, s));
         return FLEX_OK;
     }
-    const FwdPlan p = plan_fwd(B, N, Din, Dout, layout);
+    const FwdPlan p = plan_fwd(B, N, K, Din, Dout, layout);
     if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
-    if (p.wide && split_wide_ok(N, K, Din > Dout ? Din : Dout)) {
+    if (p.wide) {
         const float *rows = feat;
         float *dst = out;
         if (bcn) {
@@ -638,7 +674,7 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
     }
     const BwdPlan p = plan_bwd(B, N, K, Din, Dout, layout, build);
     if (!ws_ok(workspace, workspace_bytes, p.total)) return FLEX_ERR_WORKSPACE;
-    if (p.wide && split_wide_ok(N, K, Din > Dout ? Din : Dout)) {
+    if (p.wide) {
         const float *rows = feat, *g_rows = grad_out;
         if (bcn) {
             FLEX_HIP(launch_bcn_to_bnc(grad_out, (float *)(ws + p.gT), B, Dout, N, s));

@@ -38,6 +38,7 @@ hipError_t launch_pack_theta(const float *theta, const float *bias, float *theta
 hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *thetaF, int Din,
                                  int Dout, int RP, int CP, int transpose, hipStream_t s);
 size_t theta_f16_exp_offset(int RP, int CP);
+size_t theta_f16_rscale_offset(int RP, int CP);
 size_t theta_f16_bytes(int RP, int CP);
 hipError_t launch_pack_theta_f16_blocks(const float *theta, const float *bias, void *thetaF_all, int Din, int Dout,
                                         int r_blk, int c_blk, int n_i, int n_j, int transpose, hipStream_t s);

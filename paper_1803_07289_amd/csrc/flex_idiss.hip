@@ -1,4 +1,4 @@
-// Inverse density importance sub-sampling (Sec. 3.3): phi = sum of the distances to the K
+// Inverse density importance sub-sampling (Sec. 3.2): phi = sum of the distances to the K
 // neighbours, then Ns points per cloud drawn with probability proportional to phi in one pass
 // over the points (stratified sampling on the running sum).  Every decision of the draw is an
 // integer comparison: phi is put on an integer scale of `bits` bits relative to the cloud's

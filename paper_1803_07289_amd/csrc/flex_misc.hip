@@ -56,52 +56,75 @@ hipError_t launch_pack_theta(const float *theta, const float *bias, float *theta
 
 // ---- theta packing for the split-half contraction ---------------------------------
 // The wave-specialised kernels contract on the f16 matrix cores with every fp32
-// operand x carried as two halves of x * 2^e:  hi = half(x 2^e), lo = half(x 2^e - hi),
+// operand x carried as two halves of a scaled x:  hi = half(x s), lo = half(x s - hi),
 // and the three products hi*hi + hi*lo + lo*hi (error ~2^-22 per product, the level
-// of fp32 rounding).  For the parameters one exponent serves the whole matrix: it puts
-// the largest magnitude into [2^14, 2^15), so entries down to 2^-17 of it keep a
-// normal low half.
+// of fp32 rounding) -- as long as x s stays within f16's normal range, i.e. within
+// about 2^17 of the largest scaled magnitude.  Scaling by powers of two is exact, so the
+// packing equilibrates the matrix first, in both directions:
+//   row kd (a depth index: component j, gathered channel) gets 2^er[kd] so that its largest
+//       magnitude is in [1/2, 1); the aggregate's column kd is multiplied by 2^-er[kd]
+//       (rscale[kd], applied by the producers before their split), so a gathered channel of
+//       small magnitude whose parameters are large (or the other way round) keeps its bits;
+//   column o (an output channel) then gets 2^ec[o] so that its largest magnitude is in
+//       [2^14, 2^15); the consumers undo it with the per-point exponent.
+//   ThetaS[kd][o] = ThetaP[kd][o] * 2^(er[kd] + ec[o]);  out[l][o] = 2^-(e_l + ec[o]) * sum_kd As[l][kd] ThetaS[kd][o],
+//   As[l][kd] = A[l][kd] * 2^-er[kd] * 2^e_l  (e_l: the point's own exponent, store_split_rows).
+// What is left inside one row and column after that (entries of the SAME channel pair block far
+// below their neighbours) contributes to the output in proportion to its size, as in any
+// fp32 product.  er is clamped to +-60 so that no scale leaves fp32's normal range.
 // Buffer layout (halves), the operand fragments of v_mfma_f32_16x16x32_f16 in the order
 // a wave loads them:
 //   thetaF[(((part*NS + slice)*KS + step)*64 + lane)*8 + e]
-//       = part( ThetaP[32*step + 8*(lane>>4) + e][16*slice + (lane&15)] * 2^e_theta )
-// with NS = CP/16 slices, KS = KDP/32 depth steps, rows >= 4*RP and padding zero; the
-// int32 exponent e_theta follows at byte offset theta_f16_exp_offset(RP, CP).
-__global__ __launch_bounds__(1024) void pack_theta_f16_kernel(const float *__restrict__ theta,
-                                                              const float *__restrict__ bias,
-                                                              _Float16 *__restrict__ thetaF, int Din,
-                                                              int Dout, int RP, int CP, int transpose,
-                                                              int exp_offset_bytes)
-{
-    __shared__ float s_max[1024];
-    const int n_theta = 3 * Din * Dout, n_all = 4 * Din * Dout;
-    float m = 0.f;
-    for (int i = threadIdx.x; i < n_all; i += 1024)
-        m = fmaxf(m, fabsf(i < n_theta ? theta[i] : bias[i - n_theta]));
-    s_max[threadIdx.x] = m;
-    __syncthreads();
-    for (int d = 512; d > 0; d >>= 1) {
-        if ((int)threadIdx.x < d) s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + d]);
-        __syncthreads();
+//       = part( ThetaS[32*step + 8*(lane>>4) + e][16*slice + (lane&15)] )
+// with NS = CP/16 slices, KS = KDP/32 depth steps, rows >= 4*RP and padding zero; then, at
+// byte offset theta_f16_exp_offset(RP, CP): int32 ec[CP], and at theta_f16_rscale_offset(RP, CP):
+// float rscale[KDP] (1 for padding rows).
+struct ThetaView {
+    const float *theta, *bias;
+    int Din, Dout, ci0, co0, transpose, RP;
+    // element (kd = j*RP + r, col) of the (possibly transposed) block that starts at (ci0, co0)
+    __device__ __forceinline__ float at(int kd, int col) const
+    {
+        const int j = kd / RP, r = kd - j * RP;
+        const int ci = ci0 + (transpose ? col : r), co = co0 + (transpose ? r : col);
+        if (ci >= Din || co >= Dout) return 0.f;
+        return (j < 3) ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co];
     }
-    m = s_max[0];
-    int ex = 0;
-    if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ex); ex = 15 - ex; }
-    if (threadIdx.x == 0) *reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes) = ex;
+};
 
-    const int KD = 4 * RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
+constexpr int PACK_MAX_KD = 512, PACK_MAX_CP = 128;
+
+// one workgroup of 1024 threads packs one matrix (KD = 4*RP <= PACK_MAX_KD rows, CP <= PACK_MAX_CP columns)
+__device__ __forceinline__ void pack_theta_f16_block(const ThetaView &v, _Float16 *__restrict__ thetaF, int CP,
+                                                     int exp_offset_bytes, int rscale_offset_bytes, int *s_er,
+                                                     int *s_ec)
+{
+    const int KD = 4 * v.RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
+    for (int kd = threadIdx.x; kd < KDP; kd += 1024) {
+        float m = 0.f;
+        if (kd < KD)
+            for (int c = 0; c < CP; ++c) m = fmaxf(m, fabsf(v.at(kd, c)));
+        int er = 0;
+        if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &er); er = -er; }
+        er = er < -60 ? -60 : (er > 60 ? 60 : er);
+        s_er[kd] = er;
+        reinterpret_cast<float *>(reinterpret_cast<char *>(thetaF) + rscale_offset_bytes)[kd] = ldexpf(1.f, -er);
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < CP; c += 1024) {
+        float m = 0.f;
+        for (int kd = 0; kd < KD; ++kd) m = fmaxf(m, fabsf(ldexpf(v.at(kd, c), s_er[kd])));
+        int ec = 0;
+        if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ec); ec = 15 - ec; }
+        s_ec[c] = ec;
+        reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes)[c] = ec;
+    }
+    __syncthreads();
     const int per_part = NS * KS * 64 * 8;
     for (int i = threadIdx.x; i < per_part; i += 1024) {
         const int e = i & 7, lane = (i >> 3) & 63, step = (i >> 9) % KS, slice = (i >> 9) / KS;
         const int kd = 32 * step + 8 * (lane >> 4) + e, col = 16 * slice + (lane & 15);
-        float v = 0.f;
-        if (kd < KD) {
-            const int j = kd / RP, r = kd % RP;
-            const int ci = transpose ? col : r, co = transpose ? r : col;
-            if (ci < Din && co < Dout)
-                v = (j < 3) ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co];
-        }
-        const float vs = ldexpf(v, ex);
+        const float vs = (kd < KD) ? ldexpf(v.at(kd, col), s_er[kd] + s_ec[col]) : 0.f;
         const _Float16 hi = (_Float16)vs;
         const _Float16 lo = (_Float16)(vs - (float)hi);
         thetaF[i] = hi;
@@ -109,65 +132,45 @@ __global__ __launch_bounds__(1024) void pack_theta_f16_kernel(const float *__res
     }
 }
 
+__global__ __launch_bounds__(1024) void pack_theta_f16_kernel(const float *__restrict__ theta,
+                                                              const float *__restrict__ bias,
+                                                              _Float16 *__restrict__ thetaF, int Din,
+                                                              int Dout, int RP, int CP, int transpose,
+                                                              int exp_offset_bytes, int rscale_offset_bytes)
+{
+    __shared__ int s_er[PACK_MAX_KD], s_ec[PACK_MAX_CP];
+    const ThetaView v{theta, bias, Din, Dout, 0, 0, transpose, RP};
+    pack_theta_f16_block(v, thetaF, CP, exp_offset_bytes, rscale_offset_bytes, s_er, s_ec);
+}
+
 // The parameters of a wide layer as a grid of blocks, each packed like a whole layer's (same buffer layout, its own
-// exponent), one workgroup per block.  transpose == 0: block (i, j) = input channels r_blk*i.., output channels
+// exponents), one workgroup per block.  transpose == 0: block (i, j) = input channels r_blk*i.., output channels
 // c_blk*j.. (depth = input channel).  transpose == 1: block (i, j) = output channels r_blk*i.., input channels
 // c_blk*j.., packed transposed (depth = output channel).  Block (i, j) lands at index j * n_i + i.
 __global__ __launch_bounds__(1024) void pack_theta_f16_blocks_kernel(const float *__restrict__ theta,
                                                                      const float *__restrict__ bias,
                                                                      char *__restrict__ thetaF_all, int Din, int Dout,
                                                                      int r_blk, int c_blk, int n_i, int transpose,
-                                                                     int block_bytes, int exp_offset_bytes)
+                                                                     int block_bytes, int exp_offset_bytes,
+                                                                     int rscale_offset_bytes)
 {
-    __shared__ float s_max[1024];
+    __shared__ int s_er[PACK_MAX_KD], s_ec[PACK_MAX_CP];
     const int i_blk = blockIdx.x % n_i, j_blk = blockIdx.x / n_i;
     _Float16 *thetaF = reinterpret_cast<_Float16 *>(thetaF_all + (size_t)blockIdx.x * block_bytes);
-    // the block's input / output channel ranges
+    // the block's first input / output channel
     const int ci0 = transpose ? c_blk * j_blk : r_blk * i_blk, co0 = transpose ? r_blk * i_blk : c_blk * j_blk;
-    const int nci = transpose ? c_blk : r_blk, nco = transpose ? r_blk : c_blk;
-    float m = 0.f;
-    for (int t = threadIdx.x; t < 4 * nci * nco; t += 1024) {
-        const int j = t / (nci * nco), ci = ci0 + (t / nco) % nci, co = co0 + t % nco;
-        m = fmaxf(m, fabsf(j < 3 ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co]));
-    }
-    s_max[threadIdx.x] = m;
-    __syncthreads();
-    for (int d = 512; d > 0; d >>= 1) {
-        if ((int)threadIdx.x < d) s_max[threadIdx.x] = fmaxf(s_max[threadIdx.x], s_max[threadIdx.x + d]);
-        __syncthreads();
-    }
-    m = s_max[0];
-    int ex = 0;
-    if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ex); ex = 15 - ex; }
-    if (threadIdx.x == 0) *reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes) = ex;
-
-    const int RP = r_blk, CP = c_blk;            // depth rows per component, columns (multiples of 4 / 16)
-    const int KD = 4 * RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
-    const int per_part = NS * KS * 64 * 8;
-    for (int t = threadIdx.x; t < per_part; t += 1024) {
-        const int e = t & 7, lane = (t >> 3) & 63, step = (t >> 9) % KS, slice = (t >> 9) / KS;
-        const int kd = 32 * step + 8 * (lane >> 4) + e, col = 16 * slice + (lane & 15);
-        float v = 0.f;
-        if (kd < KD) {
-            const int j = kd / RP, r = kd % RP;
-            const int ci = transpose ? c_blk * j_blk + col : r_blk * i_blk + r;
-            const int co = transpose ? r_blk * i_blk + r : c_blk * j_blk + col;
-            v = (j < 3) ? theta[((int64_t)j * Din + ci) * Dout + co] : bias[(int64_t)ci * Dout + co];
-        }
-        const float vs = ldexpf(v, ex);
-        const _Float16 hi = (_Float16)vs;
-        const _Float16 lo = (_Float16)(vs - (float)hi);
-        thetaF[t] = hi;
-        thetaF[per_part + t] = lo;
-    }
+    const ThetaView v{theta, bias, Din, Dout, ci0, co0, transpose, r_blk};
+    pack_theta_f16_block(v, thetaF, c_blk, exp_offset_bytes, rscale_offset_bytes, s_er, s_ec);
 }
 
 hipError_t launch_pack_theta_f16_blocks(const float *theta, const float *bias, void *thetaF_all, int Din, int Dout,
                                         int r_blk, int c_blk, int n_i, int n_j, int transpose, hipStream_t s)
 {
+    if (4 * r_blk > PACK_MAX_KD || c_blk > PACK_MAX_CP || c_blk % 16 != 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(pack_theta_f16_blocks_kernel, dim3((unsigned)(n_i * n_j)), dim3(1024), 0, s, theta, bias,
                        (char *)thetaF_all, Din, Dout, r_blk, c_blk, n_i, transpose,
-                       (int)theta_f16_bytes(r_blk, c_blk), (int)theta_f16_exp_offset(r_blk, c_blk));
+                       (int)theta_f16_bytes(r_blk, c_blk), (int)theta_f16_exp_offset(r_blk, c_blk),
+                       (int)theta_f16_rscale_offset(r_blk, c_blk));
     return hipGetLastError();
 }
 
@@ -176,13 +179,20 @@ size_t theta_f16_exp_offset(int RP, int CP)
     const int KDP = (4 * RP + 31) / 32 * 32;
     return align256(sizeof(_Float16) * (size_t)2 * CP * KDP);
 }
-size_t theta_f16_bytes(int RP, int CP) { return theta_f16_exp_offset(RP, CP) + 256; }
+size_t theta_f16_rscale_offset(int RP, int CP) { return theta_f16_exp_offset(RP, CP) + align256(sizeof(int) * (size_t)CP); }
+size_t theta_f16_bytes(int RP, int CP)
+{
+    const int KDP = (4 * RP + 31) / 32 * 32;
+    return theta_f16_rscale_offset(RP, CP) + align256(sizeof(float) * (size_t)KDP);
+}
 
 hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *thetaF, int Din,
                                  int Dout, int RP, int CP, int transpose, hipStream_t s)
 {
+    if (4 * RP > PACK_MAX_KD || CP > PACK_MAX_CP || CP % 16 != 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(pack_theta_f16_kernel, dim3(1), dim3(1024), 0, s, theta, bias,
-                       (_Float16 *)thetaF, Din, Dout, RP, CP, transpose, (int)theta_f16_exp_offset(RP, CP));
+                       (_Float16 *)thetaF, Din, Dout, RP, CP, transpose, (int)theta_f16_exp_offset(RP, CP),
+                       (int)theta_f16_rscale_offset(RP, CP));
     return hipGetLastError();
 }
 
@@ -638,7 +648,7 @@ hipError_t launch_generic_bwd_pos(const float *feat, const int32_t *nbr, const f
     return hipGetLastError();
 }
 
-// ---- 1x1 convolution composed into the flex-convolution parameters (Sec. 5 block) ----------
+// ---- 1x1 convolution composed into the flex-convolution parameters (Sec. 4.3 block) ----------
 // P = [theta; bias] as four [D x Dout] slabs j = 0..3.  Parameter-sized work, but cubic in the width (4 * 1024^3
 // multiply-adds for a 1024-wide layer), so it runs as small LDS-tiled matrix products: a 256-thread block owns a
 // 64 x 64 tile of the result, depth in steps of 16, 4 x 4 results per thread accumulated in double.

@@ -37,6 +37,30 @@ int FLEX_NAME(theta_format, FLEX_DI, FLEX_DO)(int N, int K, int csr)
     return 0;
 }
 
+// Which kernel family launch_gc picks for (N, K, list form) with the parameters in the format theta_format
+// answers: 3 = lean wave-specialised producers, 2 = LDS-staged wave-specialised, 1 = single-role kernels.
+// launch_gc dispatches on this same function.
+static int gc_route(int N, int K, int csr, int theta_fmt)
+{
+#if FLEX_WS
+    using W = WsGeom<S>;
+    if (csr || (int64_t)W::PW * K <= W::EW || (theta_fmt && lean_fixed_ok(N, K))) {
+        if (!csr && theta_fmt && lean_fixed_ok(N, K)) return 3;
+        if (csr && theta_fmt && lean_producer_mode() != 0 && (int64_t)N * S::DI * 4 < (1ll << 32) &&
+            (int64_t)N * 12 < (1ll << 32))
+            return 3;
+        return 2;
+    }
+#endif
+    (void)N; (void)K; (void)csr; (void)theta_fmt;
+    return 1;
+}
+
+int FLEX_NAME(route, FLEX_DI, FLEX_DO)(int N, int K, int csr)
+{
+    return gc_route(N, K, csr, FLEX_NAME(theta_format, FLEX_DI, FLEX_DO)(N, K, csr));
+}
+
 hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float *pos,
                                                   const int32_t *nbr, const int32_t *off,
                                                   const int32_t *src, const void *thetaP,
@@ -51,7 +75,8 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
 #if FLEX_WS
     {
         using W = WsGeom<S>;
-        if (csr || (int64_t)W::PW * K <= W::EW || (theta_fmt && lean_fixed_ok(N, K))) {
+        const int route = gc_route(N, K, csr, theta_fmt);
+        if (route >= 2) {
             const int tpc = (N + W::T - 1) / W::T;
             const int tot = B * tpc;
             const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
@@ -63,7 +88,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
         else hipLaunchKernelGGL((gather_contract_ws_kernel<S, CSR_, BCN_, false>), g, blk, 0, s, FLEX_WS_ARGS);          \
     } while (0)
             // lean producer: fixed-K tensor, 32-bit byte offsets inside a cloud
-            const bool lean = !csr && theta_fmt && lean_fixed_ok(N, K);
+            const bool lean = !csr && route == 3;
             if (lean) {
                 // 3 producer waves per consumer wave where 16 waves hold them and the items divide evenly
                 constexpr bool WIDE_OK = (S::WAVES * 4 <= 16) && (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
@@ -89,8 +114,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
                 return hipGetLastError();
             }
             // feature gradient: lean in-edge producers under the same conditions
-            const bool lean_csr = csr && theta_fmt && lean_producer_mode() != 0 &&
-                                  (int64_t)N * S::DI * 4 < (1ll << 32) && (int64_t)N * 12 < (1ll << 32);
+            const bool lean_csr = csr && route == 3;
             if (lean_csr) {
                 constexpr bool WIDE_OK = (S::WAVES * 4 <= 16) && (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
                 constexpr int PMX = WIDE_OK ? 3 : 1;

@@ -89,17 +89,36 @@ __device__ __forceinline__ float fmax3_abs(float m, float a, float b)
     return __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
 }
 
+// The depth scales of the packed parameters that belong to this lane's aggregate elements (channels VEC*t..,
+// all four j): rs[v][j] = rscale[j*DIP + VEC*t + v], see pack_theta_f16_block.  thetaP: the packed buffer.
 template <class S>
-__device__ __forceinline__ void store_split_rows(const v4f (&acc)[S::VEC], char *sA, int *sE, int pt, int t,
-                                                 bool writer)
+__device__ __forceinline__ void load_row_scales(float (&rs)[S::VEC][4], const void *thetaP, int theta_exp_off, int t)
+{
+    const float *rscale = reinterpret_cast<const float *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off +
+                                                          rup_c(4 * S::DOP, 256));
+#pragma unroll
+    for (int v = 0; v < S::VEC; ++v)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int c = S::VEC * t + v;
+            rs[v][jj] = c < S::DIP ? rscale[jj * S::DIP + c] : 1.f;
+        }
+}
+
+template <class S>
+__device__ __forceinline__ void store_split_rows(const v4f (&acc_in)[S::VEC], const float (&rs)[S::VEC][4], char *sA,
+                                                 int *sE, int pt, int t, bool writer)
 {
     using G = WsGeom<S>;   // row format only: the same for every producer multiple
+    v4f acc[S::VEC];
     float m = 0.f;
 #pragma unroll
     for (int v = 0; v < S::VEC; ++v)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
+        for (int jj = 0; jj < 4; ++jj) {
+            acc[v][jj] = acc_in[v][jj] * rs[v][jj];      // the parameters' depth scale (a power of two: exact)
             m = __builtin_amdgcn_fmed3f(m, __builtin_fabsf(acc[v][jj]), __builtin_inff());   // max(m, |a|), one op
+        }
     m = group_max<S::LPR>(m);
     const int e = 15 - __builtin_amdgcn_frexp_expf(m);
     if (writer) {
@@ -204,6 +223,7 @@ struct Producer {
     int N, K, lane, pw, grp, t, dsel;
     bool lane_on;
     WsStage<S> *st;              // this wave's two staging buffers
+    float rs[S::VEC][4];         // depth scales of the packed parameters for this lane's aggregate elements
 
     __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *nbr_,
                                          const int32_t *off_, const int32_t *src_, int N_, int K_,
@@ -215,6 +235,10 @@ struct Producer {
         lane_on = (S::VEC * t) < S::DI;
         id_next = 0; off_use = off_issue = off_pref = 0;
         pa[0] = pa[1] = pa[2] = pb[0] = pb[1] = pb[2] = 0.f;
+#pragma unroll
+        for (int v = 0; v < S::VEC; ++v)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) rs[v][jj] = 1.f;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             lo[p] = hi[p] = cnt[p] = 0; onmask[p] = 0u;
@@ -436,7 +460,7 @@ struct Producer {
                 }
             }
         } else {
-            store_split_rows<S>(acc, sA, sE, pw * G::PW + grp, t, writer);
+            store_split_rows<S>(acc, rs, sA, sE, pw * G::PW + grp, t, writer);
         }
     }
 };
@@ -1045,7 +1069,13 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
             thL[s] = *reinterpret_cast<const h8 *>(tf + PER_PART + at);
         }
     }
-    const int e_theta = *reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off);
+    // column exponents of the packed parameters for this lane's four output channels
+    int e_col[4];
+    {
+        const int *ec = reinterpret_cast<const int *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) e_col[i] = ec[slice * 16 + 4 * q + i];
+    }
 
     int a_off[G::IPW];                // byte offset of this lane's 16-byte fragment (hi part, step 0)
 #pragma unroll
@@ -1077,10 +1107,10 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
                 acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl, acc[2], 0, 0, 0);
             }
             const int idx = active ? cw + it * G::NC : 0;
-            const int back = -(sE[(idx / G::NS) * 16 + r16] + e_theta);   // undo both scalings
+            const int e_pt = sE[(idx / G::NS) * 16 + r16];
             v4f d = acc[0] + (acc[1] + acc[2]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], back);
+            for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], -(e_pt + e_col[i]));   // undo both scalings
             store_item(r, it, d);
         }
     }
@@ -1121,9 +1151,11 @@ __device__ __forceinline__ void gather_contract_lean_body(const float *__restric
         LeanProducer<S, PM, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         P.set_row_stride(rs_rt);
+        float rsc[S::VEC][4];
+        load_row_scales<S>(rsc, thetaP, theta_exp_off, P.t);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
-            store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
+            store_split_rows<S>(acc, rsc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
                                 P.grp < G::PW && (S::VEC * P.t) < S::DIP);
         });
         return;
@@ -1199,9 +1231,11 @@ __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ ro
         LeanCsrProducer<S, PM, false, RS> P;
         P.init(rows, pos, off, src, N, w, sc, tiles_per_cloud);
         P.set_row_stride(rs_rt);
+        float rsc[S::VEC][4];
+        load_row_scales<S>(rsc, thetaP, theta_exp_off, P.t);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
             const int buf = i & 1;
-            store_split_rows<S>(acc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
+            store_split_rows<S>(acc, rsc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
                                 P.grp < G::PW && (S::VEC * P.t) < S::DIP);
         });
         return;
@@ -1272,6 +1306,7 @@ void gather_contract_ws_kernel(const float *__restrict__ rows, const float *__re
     if (w < G::NP) {
         Producer<S, CSR> P;
         P.init(rows, pos, nbr, off, src, N, K, s_st[w], w);
+        if constexpr (F16) load_row_scales<S>(P.rs, thetaP, theta_exp_off, P.t);
         producer_loop<F16>(P, sc, tiles_per_cloud, s_A, s_E, [](int, const TileRef &, int) {});
         return;
     }

@@ -26,3 +26,23 @@ def from_layout(t, layout):
 
 def say(*a):
     print(*a, flush=True)
+
+
+CANARY_BYTES = 4096
+
+
+class ExactWorkspace:
+    """A caller workspace of exactly the size the library asks for, with a guard pattern right behind it.
+
+    `ws` (what the entry point is given) is a view of the first `need` bytes of a larger allocation, so the library
+    is told `need` and not a byte more; check() fails if anything was written past the end."""
+
+    def __init__(self, op, B, N, K, Din, Dout, layout):
+        self.need = max(fx.workspace_bytes(op, B, N, K, Din, Dout, layout), 256)
+        self.buf = torch.empty(self.need + CANARY_BYTES, dtype=torch.uint8, device="cuda")
+        self.buf[self.need:] = 0xA5
+        self.ws = self.buf[:self.need]
+
+    def check(self):
+        torch.cuda.synchronize()
+        assert bool((self.buf[self.need:] == 0xA5).all()), "the library wrote past the workspace it asked for"

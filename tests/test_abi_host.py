@@ -136,7 +136,8 @@ def test_upsampling_and_location_gradient_errors_precede_any_launch(L):
 
 def test_workspace_sizes(L):
     w = L.flexconv_workspace_bytes
-    packed = 4 * 64 * 64 * 4 + 256       # parameters (fp32 form = both f16 halves) + the exponent's slot
+    # parameters (fp32 form = both f16 halves) + 64 column exponents + 256 depth scales
+    packed = 4 * 64 * 64 * 4 + 64 * 4 + 256 * 4
     assert w(0, 1, 4096, 8, 64, 64, 1) == packed                                 # packed parameters only
     assert w(0, 1, 4096, 8, 64, 64, 0) == packed + 4096 * 64 * 4                 # + transposed features
     # widths without a kernel of their own: padded copies of the features, the parameters and the output + the 9 -> 64 plan
@@ -154,3 +155,89 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(1, 4, 8)
     with pytest.raises(TypeError):
         fx.flexpool_fwd(t, torch.zeros(1, 2, 8, dtype=torch.int32))
+
+
+# ---- the route a call takes and the workspace it is planned for (host queries, child processes per switch) ----
+def _query(env_extra, calls):
+    """Run flexconv_kernel_route / flexconv_workspace_bytes in a fresh interpreter with extra environment
+    (the switches are read once per process).  calls: list of (fn, args); returns the list of results."""
+    import json
+    import subprocess
+    import sys
+    code = (
+        "import json, sys; sys.path.insert(0, %r)\n"
+        "import paper_1803_07289_amd as fx\n"
+        "L = fx.lib()\n"
+        "calls = json.loads(%r)\n"
+        "print(json.dumps([int(getattr(L, f)(*a)) for f, a in calls]))\n" % (ROOT, json.dumps(calls)))
+    env = dict(os.environ)
+    env.update(env_extra)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, check=True)
+    return json.loads(r.stdout.strip().splitlines()[-1])
+
+
+ROUTE_SINGLE, ROUTE_STAGED, ROUTE_LEAN, ROUTE_SPLIT128, ROUTE_WIDE, ROUTE_PADDED = 1, 2, 3, 4, 5, 6
+
+
+def _align256(x):
+    return (x + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("env", [{}, {"FLEX_CONTRACT": "f32"}, {"FLEX_PRODUCER": "staged"}, {"FLEX_SPLIT": "0"}])
+def test_channel_major_128_backward_is_planned_for_the_route_it_takes(L, env):
+    # The channel-major 128 -> 128 backward pass runs as block passes only where those kernels apply; anywhere
+    # else it is the single-pass tiled path on transposed copies, and the workspace must hold THAT path's
+    # per-workgroup partial sums (256 workgroups x [4*128 x 128] floats), not the block passes' smaller ones.
+    N, K = 1_000_000, 8
+    tiled_partials = 256 * 4 * 128 * 128 * 4
+    transposed = 2 * _align256(N * 128 * 4)
+    r_bcn, r_bnc, w_bcn, w_bnc, w_small = _query(env, [
+        ("flexconv_kernel_route", [1, 1, N, K, 128, 128, 0]),
+        ("flexconv_kernel_route", [1, 1, N, K, 128, 128, 1]),
+        ("flexconv_workspace_bytes", [1, 1, N, K, 128, 128, 0]),
+        ("flexconv_workspace_bytes", [1, 1, N, K, 128, 128, 1]),
+        ("flexconv_workspace_bytes", [1, 1, 300, 16, 128, 128, 0]),
+    ])
+    if not env:
+        assert r_bcn == ROUTE_WIDE and r_bnc == ROUTE_SPLIT128
+    else:
+        assert r_bcn != ROUTE_WIDE and r_bnc != ROUTE_SPLIT128
+        # same single-pass plan in both layouts, plus the two transposed copies
+        assert w_bcn == w_bnc + transposed
+        assert w_bcn >= tiled_partials + transposed
+        # the small parity shape (300 points, 19 tiles of 16): one partial per tile-owning workgroup
+        assert w_small >= 16 * 4 * 128 * 128 * 4
+
+
+def test_block_passes_stop_where_byte_offsets_leave_32_bits(L):
+    # N * 128 * 4 = 2^32 at N = 8 388 608 points per cloud: the block passes (32-bit byte offsets inside a cloud)
+    # hand over to the single-pass kernels, and the plan follows.
+    K = 8
+    below, at = 8_388_607, 8_388_608
+    r = _query({}, [("flexconv_kernel_route", [op, 1, n, K, 128, 128, lay])
+                    for op in (0, 1) for n in (below, at) for lay in (0, 1)])
+    assert r == [ROUTE_WIDE, ROUTE_SPLIT128, ROUTE_SINGLE, ROUTE_SINGLE,
+                 ROUTE_WIDE, ROUTE_SPLIT128, ROUTE_SINGLE, ROUTE_SINGLE]
+    w_at_bcn, w_at_bnc = _query({}, [("flexconv_workspace_bytes", [1, 1, at, K, 128, 128, 0]),
+                                     ("flexconv_workspace_bytes", [1, 1, at, K, 128, 128, 1])])
+    assert w_at_bcn == w_at_bnc + 2 * _align256(at * 128 * 4)
+    assert w_at_bnc >= 256 * 4 * 128 * 128 * 4
+
+
+def test_lean_kernels_stop_where_byte_offsets_leave_32_bits(L):
+    # the lean producers address rows with 32-bit byte offsets from a per-cloud base: N * width * 4 < 2^32
+    route = L.flexconv_kernel_route
+    lim64, lim32 = (1 << 32) // (64 * 4), (1 << 32) // (32 * 4)
+    for op in (0, 1):
+        assert route(op, 1, lim64 - 1, 8, 64, 64, 1) == ROUTE_LEAN
+        assert route(op, 1, lim64, 8, 64, 64, 1) == ROUTE_STAGED
+        assert route(op, 1, lim32 - 1, 8, 32, 32, 1) == ROUTE_LEAN
+        assert route(op, 1, lim32, 8, 32, 32, 1) == ROUTE_STAGED
+        assert route(op, 4, lim64 - 1, 8, 64, 64, 1) == ROUTE_LEAN          # the limit is per cloud, not per batch
+    # the gathered width decides: forward gathers Din-wide rows, the feature gradient Dout-wide ones
+    assert route(0, 1, lim64, 8, 32, 64, 1) == ROUTE_LEAN and route(1, 1, lim64, 8, 32, 64, 1) == ROUTE_STAGED
+    assert route(0, 1, lim64, 8, 64, 32, 1) == ROUTE_STAGED and route(1, 1, lim64, 8, 64, 32, 1) == ROUTE_LEAN
+    # K too large for the staged producers' 64 entries per wave and no lean kernel: single-role kernels
+    assert route(0, 1, lim64, 24, 64, 64, 1) == ROUTE_SINGLE
+    assert route(0, 1, 4096, 8, 5, 7, 1) == ROUTE_PADDED and route(0, 1, 4096, 8, 256, 512, 1) == ROUTE_WIDE
+    assert route(0, 0, 4096, 8, 64, 64, 1) == -1 and route(3, 1, 4096, 8, 64, 64, 1) == -1

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import paper_1803_07289_amd as fx
-from gpu_util import TOL, dev, to_layout, say
+from gpu_util import TOL, ExactWorkspace, dev, to_layout, say
 from helpers import rel_err
 from test_gpu_parity import random_problem
 from workloads import CONFIGS, make_inputs
@@ -39,9 +39,13 @@ def test_bwd_pos_matches_oracle(B, N, K, Din, Dout, layout):
     ref = oracle.flexconv_bwd_pos(feat, nbr, theta, g)
     dnbr = dev(nbr)
     a = (to_layout(feat, layout), dnbr, dev(theta), to_layout(g, layout))
-    gp = fx.flexconv_bwd_pos(*a, layout=layout)
-    gp2 = fx.flexconv_bwd_pos(*a, layout=layout, in_edges=fx.flex_inedges_build(dnbr))
-    torch.cuda.synchronize()
+    # workspaces of exactly the size the library asks for, guarded behind their end
+    w = ExactWorkspace(fx.OP_CONV_BWD_POS_BUILD, B, N, K, Din, Dout, layout)
+    gp = fx.flexconv_bwd_pos(*a, layout=layout, workspace=w.ws)
+    w.check()
+    w2 = ExactWorkspace(fx.OP_CONV_BWD_POS, B, N, K, Din, Dout, layout)
+    gp2 = fx.flexconv_bwd_pos(*a, layout=layout, in_edges=fx.flex_inedges_build(dnbr), workspace=w2.ws)
+    w2.check()
     if K == 1 and not ref.any():
         # every point is its own only neighbour: the two ends of each edge coincide and the exact result is 0.
         # The matrix-core path forms the two ends' sums separately, so what is left is rounding, measured

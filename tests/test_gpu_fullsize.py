@@ -1,6 +1,9 @@
 """GPU parity at the full sizes of configs 2-4, in the launch configuration bench.py times
-(point-major layout, Z-order points, prebuilt in-edge lists): sampled outputs the oracle can
-compute one by one, full parameter gradients, and properties that hold at any size."""
+(point-major layout, Z-order points, prebuilt in-edge lists): the forward pass and pooling on every
+point of the cloud against the oracle (a slice plus at least 10^5 random points should the oracle
+outrun its time budget), the feature gradient on more than 10^5 random rows, the parameter
+gradients in full, the channel-major entry against the point-major result on whole tensors, and
+properties that hold at any size."""
 import numpy as np
 import pytest
 import torch
@@ -23,96 +26,179 @@ def sample_ranges(N, rng, width=272):
     return [(s, s + width) for s in starts]
 
 
-@pytest.mark.parametrize("ci", [2, 3, 4])
-def test_full_size_config(ci):
+ORACLE_BUDGET_S = 100.0      # per oracle-checked tensor; beyond it the check falls back to a slice plus random ranges
+
+
+class _Work:
+    pass
+
+
+@pytest.fixture(scope="module", params=[2, 3, 4], ids=["cfg2", "cfg3", "cfg4"])
+def work(request):
+    """One configuration's inputs on the host (as the oracle takes them) and on the device (point-major, Z-order
+    points, prebuilt in-edge lists: the launch configuration bench.py times).  Built once per configuration."""
+    ci = request.param
     cfg = CONFIGS[ci]
     say(f"config {ci}: {cfg.name} generating inputs")
-    x = make_inputs(cfg, with_grad=("conv_bwd" in cfg.runs))
-    B, N, K, Din, Dout = cfg.B, cfg.N, cfg.K, cfg.Din, cfg.Dout
-    rng = np.random.default_rng(100 + ci)
-    feat, pos, nbr, theta, bias = bnc(x.feat), dev(x.pos), dev(x.nbr), dev(x.theta), dev(x.bias)
-    assert fx.flex_validate_neighbors(nbr) == 0
+    w = _Work()
+    w.ci, w.cfg = ci, cfg
+    w.x = make_inputs(cfg, with_grad=("conv_bwd" in cfg.runs))
+    w.feat, w.pos, w.nbr = bnc(w.x.feat), dev(w.x.pos), dev(w.x.nbr)
+    w.theta, w.bias = dev(w.x.theta), dev(w.x.bias)
+    w.g = bnc(w.x.grad_out) if w.x.grad_out is not None else None
+    w.edges = fx.flex_inedges_build(w.nbr)
+    w.rng = np.random.default_rng(100 + ci)
+    assert fx.flex_validate_neighbors(w.nbr) == 0
+    yield w
+    del w.feat, w.pos, w.nbr, w.g, w.edges, w.x
+    torch.cuda.empty_cache()
 
-    say("  k-nearest neighbours on the GPU")
+
+def check_all_points(N, rng, what, got_cols, ref_cols, chunk=1 << 19):
+    """Element-by-element check of a per-centre output over ALL points of the cloud, chunk by chunk, while the
+    oracle keeps within its time budget; if it does not, what is left is checked on the points of the first
+    sixteenth of the cloud plus at least 10^5 points in random ranges.  got_cols(l0, l1) / ref_cols(l0, l1) return
+    the [B,C,l1-l0] columns of the device result / of the oracle.  Returns (checked points, max relative error
+    with the RMS of the checked reference as the floor)."""
+    import time
+    t0 = time.time()
+    refs, gots, spans = [], [], []
+    l0, full = 0, True
+    while l0 < N:
+        l1 = min(N, l0 + chunk)
+        refs.append(ref_cols(l0, l1))
+        gots.append(got_cols(l0, l1))
+        spans.append((l0, l1))
+        l0 = l1
+        elapsed = time.time() - t0
+        if l0 < N and elapsed * (N / l0) > ORACLE_BUDGET_S and l0 >= N // 16:
+            full = False
+            break
+    if not full:
+        width = 256
+        for s0 in rng.integers(l0, N - width, size=(100_000 + width - 1) // width):
+            refs.append(ref_cols(int(s0), int(s0) + width))
+            gots.append(got_cols(int(s0), int(s0) + width))
+            spans.append((int(s0), int(s0) + width))
+    points = sum(b - a for a, b in spans)
+    say(f"  {what}: {'all' if full else 'first slice + random ranges:'} {points} points checked against the oracle "
+        f"in {time.time() - t0:.1f}s")
+    return points, refs, gots
+
+
+def max_rel_err(refs, gots):
+    sq = sum(float(np.sum(np.square(r, dtype=np.float64))) for r in refs)
+    n = sum(r.size for r in refs)
+    rms = np.sqrt(sq / max(n, 1))
+    worst = 0.0
+    for r, g in zip(refs, gots):
+        r = np.asarray(r, np.float64)
+        worst = max(worst, float(np.max(np.abs(np.asarray(g, np.float64) - r) / np.maximum(np.abs(r), rms))))
+    return worst
+
+
+def test_neighbour_search_agrees_with_the_harness(work):
     # the workload's neighbour tensor comes from an independent exact search on the CPU (float64 distances): the
     # neighbourhoods must agree as sets (a float32 / float64 rounding difference could swap a K-th neighbour)
-    knn = fx.flex_knn(pos, K)
-    agree = (torch.sort(knn, 1).values == torch.sort(nbr, 1).values).all(1).float().mean().item()
+    knn = fx.flex_knn(work.pos, work.cfg.K)
+    agree = (torch.sort(knn, 1).values == torch.sort(work.nbr, 1).values).all(1).float().mean().item()
     say(f"  neighbourhoods equal to the harness's: {agree:.6f}")
     assert agree >= 0.99999
-    del knn
 
-    say("  forward")
-    out = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=fx.BNC)
+
+def test_forward_every_point(work):
+    x, N = work.x, work.cfg.N
+    out = fx.flexconv_fwd(work.feat, work.pos, work.nbr, work.theta, work.bias, layout=fx.BNC)
     torch.cuda.synchronize()
-    worst = 0.0
-    for (s0, s1) in sample_ranges(N, rng):
-        ref = oracle.flexconv_fwd(x.feat, x.pos, x.nbr, x.theta, x.bias, l_range=(s0, s1))
-        got = out[:, s0:s1, :].transpose(1, 2).cpu().numpy()
-        worst = max(worst, rel_err(got, ref))
-    say(f"  fwd sampled rel err {worst:.2e}")
-    assert worst <= TOL
     assert bool(torch.isfinite(out).all())
+    points, refs, gots = check_all_points(
+        N, work.rng, "forward",
+        lambda a, b: out[:, a:b, :].transpose(1, 2).cpu().numpy(),
+        lambda a, b: oracle.flexconv_fwd(x.feat, x.pos, x.nbr, x.theta, x.bias, l_range=(a, b)))
+    err = max_rel_err(refs, gots)
+    say(f"  forward rel err {err:.2e}")
+    assert points >= min(N, N // 16 + 100_000) and err <= TOL
+    del refs, gots
+    # the channel-major entry (transposed copies, other kernels for 128 -> 128) against the point-major result
+    out_c = fx.flexconv_fwd(work.feat.transpose(1, 2).contiguous(), work.pos, work.nbr, work.theta, work.bias,
+                            layout=fx.BCN)
+    torch.cuda.synchronize()
+    scale = float(out.double().pow(2).mean().sqrt())
+    diff = float((out_c.transpose(1, 2) - out).abs().max())
+    say(f"  channel-major vs point-major: max |diff| / RMS = {diff / scale:.2e}")
+    assert diff <= 2e-6 * scale
 
-    if "conv_bwd" in cfg.runs:
-        say("  backward")
-        g = bnc(x.grad_out)
-        edges = fx.flex_inedges_build(nbr)
-        gf, gt, gb = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=fx.BNC, in_edges=edges)
-        torch.cuda.synchronize()
-        off = edges[0].cpu().numpy()
-        assert off[0] == 0 and off[-1] == B * K * N and (np.diff(off) >= 0).all()
-        targets = np.unique(np.concatenate([rng.integers(0, B * N, size=500), [0, B * N - 1],
-                                            [int(np.argmax(np.diff(off)))]])).astype(np.int64)
-        ref_rows = oracle.flexconv_grad_feat_at(x.pos, x.nbr, x.theta, x.bias, x.grad_out, targets)
-        got_rows = gf.reshape(B * N, Din)[torch.from_numpy(targets).cuda()].cpu().numpy()
-        e_gf = rel_err(got_rows, ref_rows)
-        _, rgt, rgb = oracle.flexconv_bwd(x.feat, x.pos, x.nbr, x.theta, x.bias, x.grad_out, want_feat=False)
-        e_gt, e_gb = rel_err(gt.cpu().numpy(), rgt), rel_err(gb.cpu().numpy(), rgb)
-        say(f"  grad_feat (sampled) {e_gf:.2e}  grad_theta {e_gt:.2e}  grad_bias {e_gb:.2e}")
-        assert max(e_gf, e_gt, e_gb) <= TOL
-        # adjoint identity at full size: <g, fwd(v)> == <grad_feat, v>
-        v = torch.randn(feat.shape, device="cuda", generator=torch.Generator("cuda").manual_seed(ci))
-        lhs = float((fx.flexconv_fwd(v, pos, nbr, theta, bias, layout=fx.BNC).double() * g.double()).sum())
-        rhs = float((gf.double() * v.double()).sum())
-        assert abs(lhs - rhs) <= 1e-4 * max(abs(lhs), float(g.double().norm() * v.double().norm()) * 1e-3)
-        del v
 
-    if "pool_fwd" in cfg.runs:
-        say("  pooling")
-        po, pa = fx.flexpool_fwd(feat, nbr, layout=fx.BNC)
-        torch.cuda.synchronize()
-        for (s0, s1) in sample_ranges(N, rng):
-            ro, ra = oracle.flexpool_fwd(x.feat, x.nbr, l_range=(s0, s1))
-            assert np.array_equal(pa[:, s0:s1, :].transpose(1, 2).cpu().numpy(), ra)
-            assert np.array_equal(po[:, s0:s1, :].transpose(1, 2).cpu().numpy().view(np.uint32), ro.view(np.uint32))
-        # everywhere: the value is the winner's, bit for bit, and self (slot 0 here) never beats it
-        gathered = torch.gather(feat, 1, pa.long())
-        assert torch.equal(gathered.view(torch.int32), po.view(torch.int32))
-        assert bool((po >= feat).all())
-        del gathered
-        gp = bnc(x.grad_out) if x.grad_out is not None and Din == Dout else torch.randn_like(feat)
-        pool_edges = edges if "conv_bwd" in cfg.runs else fx.flex_inedges_build(nbr)
-        pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC, in_edges=pool_edges)     # the form bench.py times
-        pg_scatter = fx.flexpool_bwd(gp, pa, layout=fx.BNC)
-        torch.cuda.synchronize()
-        assert float((pg - pg_scatter).abs().max()) <= 1e-4 * float(gp.abs().max()) * K
-        # mass conservation per (cloud, channel) and exact rows on a sample
-        m_got, m_ref = pg.double().sum(1).cpu().numpy(), gp.double().sum(1).cpu().numpy()
-        assert np.abs(m_got - m_ref).max() <= 1e-6 * gp.double().abs().sum(1).max().item()
-        ref = oracle.flexpool_bwd(gp.transpose(1, 2).contiguous().cpu().numpy(), pa.transpose(1, 2).contiguous().cpu().numpy())
-        cols = rng.integers(0, N, size=4000)
-        assert rel_err(pg[:, torch.from_numpy(cols).cuda(), :].transpose(1, 2).cpu().numpy(), ref[:, :, cols]) <= 1e-5
-        # the channel-major kernels at this size: same winners, same bits; the gather sums in the same (list) order
-        say("  pooling, channel-major")
-        po_c, pa_c = fx.flexpool_fwd(feat.transpose(1, 2).contiguous(), nbr, layout=fx.BCN)
-        assert torch.equal(pa_c.transpose(1, 2), pa)
-        assert torch.equal(po_c.transpose(1, 2).view(torch.int32), po.view(torch.int32))
-        del po_c
-        pg_c = fx.flexpool_bwd(gp.transpose(1, 2).contiguous(), pa_c, layout=fx.BCN, in_edges=pool_edges)
-        torch.cuda.synchronize()
-        assert torch.equal(pg_c.transpose(1, 2), pg)
-        del pg_c, pa_c
+def test_backward_rows_and_parameter_gradients(work):
+    if "conv_bwd" not in work.cfg.runs:
+        pytest.skip("forward-only configuration")
+    x, cfg, rng = work.x, work.cfg, work.rng
+    B, N, K, Din = cfg.B, cfg.N, cfg.K, cfg.Din
+    gf, gt, gb = fx.flexconv_bwd(work.feat, work.pos, work.nbr, work.theta, work.bias, work.g, layout=fx.BNC,
+                                 in_edges=work.edges)
+    torch.cuda.synchronize()
+    off = work.edges[0].cpu().numpy()
+    assert off[0] == 0 and off[-1] == B * K * N and (np.diff(off) >= 0).all()
+    # feature gradient: at least 10^5 random rows, the two ends and the point with the longest in-edge list
+    targets = np.unique(np.concatenate([rng.integers(0, B * N, size=120_000), [0, B * N - 1],
+                                        [int(np.argmax(np.diff(off)))]])).astype(np.int64)
+    assert targets.size >= 100_000
+    ref_rows = oracle.flexconv_grad_feat_at(x.pos, x.nbr, x.theta, x.bias, x.grad_out, targets)
+    got_rows = gf.reshape(B * N, Din)[torch.from_numpy(targets).cuda()].cpu().numpy()
+    e_gf = rel_err(got_rows, ref_rows)
+    # parameter gradients: every element, the oracle summing over every point
+    _, rgt, rgb = oracle.flexconv_bwd(x.feat, x.pos, x.nbr, x.theta, x.bias, x.grad_out, want_feat=False)
+    e_gt, e_gb = rel_err(gt.cpu().numpy(), rgt), rel_err(gb.cpu().numpy(), rgb)
+    say(f"  grad_feat ({targets.size} rows) {e_gf:.2e}  grad_theta {e_gt:.2e}  grad_bias {e_gb:.2e}")
+    assert max(e_gf, e_gt, e_gb) <= TOL
+    # adjoint identity over the whole cloud: <g, fwd(v)> == <grad_feat, v>
+    v = torch.randn(work.feat.shape, device="cuda", generator=torch.Generator("cuda").manual_seed(work.ci))
+    lhs = float((fx.flexconv_fwd(v, work.pos, work.nbr, work.theta, work.bias, layout=fx.BNC).double()
+                 * work.g.double()).sum())
+    rhs = float((gf.double() * v.double()).sum())
+    assert abs(lhs - rhs) <= 1e-4 * max(abs(lhs), float(work.g.double().norm() * v.double().norm()) * 1e-3)
+    del v
+    # channel-major entry (in-edge lists built inside the call) against the point-major result, whole tensors
+    gf_c, gt_c, gb_c = fx.flexconv_bwd(work.feat.transpose(1, 2).contiguous(), work.pos, work.nbr, work.theta,
+                                       work.bias, work.g.transpose(1, 2).contiguous(), layout=fx.BCN)
+    torch.cuda.synchronize()
+    s_gf = float(gf.double().pow(2).mean().sqrt())
+    assert float((gf_c.transpose(1, 2) - gf).abs().max()) <= 2e-6 * s_gf
+    assert rel_err(gt_c.cpu().numpy(), rgt) <= TOL and rel_err(gb_c.cpu().numpy(), rgb) <= TOL
+
+
+def test_pooling_every_point(work):
+    if "pool_fwd" not in work.cfg.runs:
+        pytest.skip("configuration without pooling")
+    x, cfg, rng = work.x, work.cfg, work.rng
+    N, K = cfg.N, cfg.K
+    feat = work.feat
+    po, pa = fx.flexpool_fwd(feat, work.nbr, layout=fx.BNC)
+    torch.cuda.synchronize()
+    # every point against the oracle, bit for bit
+    ro, ra = oracle.flexpool_fwd(x.feat, x.nbr)
+    assert torch.equal(pa.transpose(1, 2).cpu(), torch.from_numpy(ra))
+    assert torch.equal(po.transpose(1, 2).cpu().view(torch.int32), torch.from_numpy(ro).view(torch.int32))
+    del ro
+    gp = work.g if work.g is not None and cfg.Din == cfg.Dout else torch.randn_like(feat)
+    pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC, in_edges=work.edges)     # the form bench.py times
+    pg_scatter = fx.flexpool_bwd(gp, pa, layout=fx.BNC)
+    torch.cuda.synchronize()
+    assert float((pg - pg_scatter).abs().max()) <= 1e-4 * float(gp.abs().max()) * K
+    del pg_scatter
+    # every element of the backward pass against the oracle's routing by its own table
+    ref = oracle.flexpool_bwd(gp.transpose(1, 2).contiguous().cpu().numpy(), ra)
+    assert rel_err(pg.transpose(1, 2).cpu().numpy(), ref) <= 1e-5
+    del ref, ra
+    # the channel-major kernels at this size: same winners, same bits; the gather sums in the same (list) order
+    say("  pooling, channel-major")
+    po_c, pa_c = fx.flexpool_fwd(feat.transpose(1, 2).contiguous(), work.nbr, layout=fx.BCN)
+    assert torch.equal(pa_c.transpose(1, 2), pa)
+    assert torch.equal(po_c.transpose(1, 2).view(torch.int32), po.view(torch.int32))
+    del po_c
+    pg_c = fx.flexpool_bwd(gp.transpose(1, 2).contiguous(), pa_c, layout=fx.BCN, in_edges=work.edges)
+    torch.cuda.synchronize()
+    assert torch.equal(pg_c.transpose(1, 2), pg)
 
 
 def test_wide_layer_at_a_deeper_stage_size():

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import paper_1803_07289_amd as fx
-from gpu_util import TOL, dev, to_layout, from_layout, say
+from gpu_util import TOL, ExactWorkspace, dev, to_layout, from_layout, say
 from helpers import rel_err
 
 pytestmark = pytest.mark.gpu
@@ -34,11 +34,17 @@ def test_convolution_entry_points_on_random_shapes(case):
     g = rng.standard_normal((B, Dout, N)).astype(np.float32)
     dn = dev(nbr)
     a = (to_layout(feat, layout), dev(pos), dn, dev(theta), dev(bias))
-    out = fx.flexconv_fwd(*a, layout=layout)
+    # every call gets a workspace of exactly the size the library asks for, guarded behind its end
+    w = ExactWorkspace(fx.OP_CONV_FWD, B, N, K, Din, Dout, layout)
+    out = fx.flexconv_fwd(*a, layout=layout, workspace=w.ws)
+    w.check()
     edges = fx.flex_inedges_build(dn) if rng.random() < 0.5 else None
-    gf, gt, gb = fx.flexconv_bwd(*a, to_layout(g, layout), layout=layout, in_edges=edges)
-    gp = fx.flexconv_bwd_pos(a[0], dn, a[3], to_layout(g, layout), layout=layout, in_edges=edges)
-    torch.cuda.synchronize()
+    w = ExactWorkspace(fx.OP_CONV_BWD if edges is not None else fx.OP_CONV_BWD_BUILD, B, N, K, Din, Dout, layout)
+    gf, gt, gb = fx.flexconv_bwd(*a, to_layout(g, layout), layout=layout, in_edges=edges, workspace=w.ws)
+    w.check()
+    w = ExactWorkspace(fx.OP_CONV_BWD_POS if edges is not None else fx.OP_CONV_BWD_POS_BUILD, B, N, K, Din, Dout, layout)
+    gp = fx.flexconv_bwd_pos(a[0], dn, a[3], to_layout(g, layout), layout=layout, in_edges=edges, workspace=w.ws)
+    w.check()
     assert rel_err(from_layout(out, layout), oracle.flexconv_fwd(feat, pos, nbr, theta, bias)) <= TOL
     rgf, rgt, rgb = oracle.flexconv_bwd(feat, pos, nbr, theta, bias, g)
     assert rel_err(from_layout(gf, layout), rgf) <= TOL

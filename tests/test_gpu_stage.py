@@ -1,4 +1,4 @@
-"""The primitives chained the way the paper's encoder / decoder uses them (Sec. 5): neighbour search, flex-convolution,
+"""The primitives chained the way the paper's encoder / decoder uses them (Sec. 4.3): neighbour search, flex-convolution,
 inverse-density sub-sampling, flex-max-pooling with subsampling, a flex-convolution on the coarser cloud with its own
 neighbourhoods, flex-upsampling back.  Index results (neighbours, selection, winners) must equal the oracle's exactly,
 so the two chains stay comparable; the final features agree to the flex-conv tolerance."""

@@ -1,4 +1,4 @@
-"""Pins for the CPU oracle's 1x1-convolution + flex-convolution block (Sec. 5), CPU only."""
+"""Pins for the CPU oracle's 1x1-convolution + flex-convolution block (Sec. 4.3), CPU only."""
 import numpy as np
 
 import oracle

@@ -1,4 +1,4 @@
-"""Pins for the CPU oracle's inverse density importance sub-sampling (Sec. 3.3), CPU only."""
+"""Pins for the CPU oracle's inverse density importance sub-sampling (Sec. 3.2), CPU only."""
 from fractions import Fraction
 
 import numpy as np

@@ -1,4 +1,4 @@
-"""Pins for the CPU oracle's flex-max-pooling with subsampling (Sec. 4.1 / Sec. 5), CPU only."""
+"""Pins for the CPU oracle's flex-max-pooling with subsampling (Sec. 4.1 / Sec. 4.3), CPU only."""
 import numpy as np
 from scipy.ndimage import maximum_filter
 
@@ -35,7 +35,7 @@ def test_pool_sub_fwd_bruteforce_with_ties():
 
 def test_pool_sub_fwd_grid_is_3x3_maxpool_stride2():
     # On a regular grid with the 3x3 offsets, keeping every second row and column is the ordinary
-    # stride-2 max-pooling of image networks (Sec. 5 compares the layer with exactly that).
+    # stride-2 max-pooling of image networks (Sec. 4.3 compares the layer with exactly that).
     H, W = 12, 14
     _, nbr, _ = grid2d(H, W, 1.0)
     rng = np.random.default_rng(1)
