@@ -44,7 +44,8 @@ typedef enum {
     FLEX_ERR_SHAPE = 2,       /* non-positive size, K > N, B*N too large, bad layout/op */
     FLEX_ERR_UNSUPPORTED = 3, /* reserved */
     FLEX_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or too small */
-    FLEX_ERR_HIP = 5          /* a HIP launch reported an error */
+    FLEX_ERR_HIP = 5,         /* a HIP launch reported an error */
+    FLEX_ERR_TOO_LARGE = 6    /* flexconv_fwd_noalloc: the call needs more scratch than the static buffer holds */
 } flex_status;
 
 typedef enum { FLEX_LAYOUT_BCN = 0, FLEX_LAYOUT_BNC = 1 } flex_layout;
@@ -73,6 +74,24 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
                  const float *theta, const float *bias, float *out,
                  int B, int N, int K, int Din, int Dout, int layout,
                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * flexconv_fwd for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments and result as flexconv_fwd without the
+ * workspace pair: the scratch memory (the packed parameters; for channel-major tensors or widths that run
+ * zero-padded also the copies flexconv_workspace_bytes(FLEX_OP_CONV_FWD, ...) counts) is a static device array
+ * of FLEX_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.  A call whose
+ * plan needs more returns FLEX_ERR_TOO_LARGE before anything is launched (point-major layers of every tiled
+ * width and wide layers up to 256 x 256 always fit; channel-major tensors only while the transposed copy does).
+ * The call allocates nothing and frees nothing.  The first call on a device looks the array's address up (make
+ * that call outside a graph capture).  All calls on one GPU share the array: calls that overlap on one GPU
+ * (different streams, or graphs replayed concurrently) race; stream-ordered calls do not.  The array keeps the
+ * last call's contents; nothing in it has to start at zero.
+ */
+#define FLEX_NOALLOC_SCRATCH_BYTES (2u << 20)
+int flexconv_fwd_noalloc(const float *feat, const float *pos, const int32_t *nbr,
+                         const float *theta, const float *bias, float *out,
+                         int B, int N, int K, int Din, int Dout, int layout, void *stream);
 
 /*
  * Flex-convolution backward (gradients of the forward map above, Sec. 3.1

@@ -28,6 +28,7 @@ _workspaces = {}
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _SIGS = {
     "flexconv_fwd": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _sz, _vp]),
+    "flexconv_fwd_noalloc": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "flexconv_bwd": (_i, [_vp] * 11 + [_i] * 6 + [_vp, _sz, _vp]),
     "flex_inedges_build": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
@@ -165,6 +166,26 @@ def flexconv_fwd(feat, pos, nbr, theta, bias, layout=BCN, out=None, workspace=No
     ws, ws_bytes = _ws_arg(workspace, feat.device, need)
     _check(lib().flexconv_fwd(_ptr(feat), _ptr(pos), _ptr(nbr), _ptr(theta), _ptr(bias), _ptr(out),
                               B, N, K, Din, Dout, layout, _ptr(ws), ws_bytes, _stream()), "flexconv_fwd")
+    return out
+
+
+def flexconv_fwd_noalloc(feat, pos, nbr, theta, bias, out, layout=BCN):
+    """flexconv_fwd into the caller's `out`, with the library's static scratch memory instead of a workspace:
+    neither this wrapper nor the library allocates.  Raises FlexError (status 6) when the call needs more
+    scratch than the static buffer holds."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(pos, torch.float32, "pos"); _dev(nbr, torch.int32, "nbr")
+    _dev(theta, torch.float32, "theta"); _dev(bias, torch.float32, "bias"); _dev(out, torch.float32, "out")
+    B, N, K, Din = _dims(feat, nbr, layout)
+    if theta.dim() != 3 or theta.shape[0] != 3 or theta.shape[1] != Din:
+        raise ValueError("theta must be [3,Din,Dout]")
+    Dout = theta.shape[2]
+    if tuple(bias.shape) != (Din, Dout) or tuple(pos.shape) != (B, 3, N):
+        raise ValueError("bias must be [Din,Dout] and pos [B,3,N]")
+    if tuple(out.shape) != ((B, Dout, N) if layout == BCN else (B, N, Dout)):
+        raise ValueError("out has the wrong shape")
+    _check(lib().flexconv_fwd_noalloc(_ptr(feat), _ptr(pos), _ptr(nbr), _ptr(theta), _ptr(bias), _ptr(out),
+                                      B, N, K, Din, Dout, layout, _stream()), "flexconv_fwd_noalloc")
     return out
 
 

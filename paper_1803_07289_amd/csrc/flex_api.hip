@@ -1,6 +1,7 @@
 // C-ABI entry points of libflexconv: validation, workspace carving, dispatch.
 #include "flex_common.hpp"
 #include <stdlib.h>
+#include <mutex>
 #include "../../include/flexconv.h"
 
 namespace flex {
@@ -511,6 +512,7 @@ const char *flex_status_string(int status)
     case FLEX_ERR_UNSUPPORTED: return "unsupported";
     case FLEX_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case FLEX_ERR_HIP: return "HIP launch error";
+    case FLEX_ERR_TOO_LARGE: return "call needs more scratch memory than the library's static buffer holds";
     default: return "unknown status";
     }
 }
@@ -627,6 +629,56 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
     FLEX_HIP(launch_gather_contract(rows, pos, nbr, nullptr, nullptr, thetaP, fmt, out, B, N, K, Din,
                                     Dout, 0, bcn, s));
     return FLEX_OK;
+}
+
+}  // extern "C"
+
+// ---- flexconv_fwd_noalloc: the forward pass with the library's own static scratch memory -------------------
+// The scratch (packed parameters; for other layouts / widths also the copies the plan asks for) lives in a
+// file-scope device array instead of a caller workspace.  In host code the array's name is only a handle: the
+// device address is looked up once per device (with that device current) and kept; every later use goes through
+// the kept pointer.  Each GPU holds its own copy of the array at its own address.
+static __device__ __align__(256) unsigned char scratch[FLEX_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];       // device address of `scratch` on each device, nullptr until looked up
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return FLEX_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FLEX_ERR_HIP;
+        if ((reinterpret_cast<uintptr_t>(p) & 255) != 0) return FLEX_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return FLEX_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int flexconv_fwd_noalloc(const float *feat, const float *pos, const int32_t *nbr, const float *theta,
+                         const float *bias, float *out, int B, int N, int K, int Din, int Dout, int layout,
+                         void *stream)
+{
+    if (!feat || !pos || !nbr || !theta || !bias || !out) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, Din, Dout)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    const size_t need = flexconv_workspace_bytes(FLEX_OP_CONV_FWD, B, N, K, Din, Dout, layout);
+    if (need == 0) return FLEX_ERR_SHAPE;
+    if (need > (size_t)FLEX_NOALLOC_SCRATCH_BYTES) return FLEX_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    const int st = static_scratch(&ws);
+    if (st != FLEX_OK) return st;
+    // Every byte of the plan that a kernel reads is written earlier in the same call (packed parameters with their
+    // padding, exponent tables, padded copies after an explicit zero fill), so nothing has to be cleared here.
+    return flexconv_fwd(feat, pos, nbr, theta, bias, out, B, N, K, Din, Dout, layout, ws, need, stream);
 }
 
 int flex_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t *in_off, int32_t *in_src,
