@@ -9,7 +9,7 @@ namespace flex {
 // ---- per-shape launchers generated from flex_shapes.def ------------------------
 #define FLEX_SHAPE(DI, DO, W, T, OCC, WS)                                                             \
     hipError_t launch_gc_##DI##_##DO(const float *, const float *, const int32_t *, const int32_t *, \
-                                     const int32_t *, const void *, int, float *, int, int, int,     \
+                                     const int32_t *, const int32_t *, const void *, int, float *, int, int, int, \
                                      int, int, hipStream_t);                                         \
     int theta_format_##DI##_##DO(int, int, int);                                                       \
     int route_##DI##_##DO(int, int, int);                                                              \
@@ -25,8 +25,8 @@ namespace flex {
 // 128 -> 128 layers as passes over 64-channel blocks (flex_tiled_inst.hip, shapes 64x128 and 64x64)
 bool split_ok_128_128(int N, int K, int csr);
 hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr, const int32_t *off,
-                                   const int32_t *src, const void *thetaP, float *out, int B, int N, int K, int csr,
-                                   int accumulate, hipStream_t s);
+                                   const int32_t *src, const int32_t *order, const void *thetaP, float *out, int B,
+                                   int N, int K, int csr, int accumulate, hipStream_t s);
 hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr,
                                    const float *g_half, float *partials, int B, int N, int K, int *n_wg,
                                    hipStream_t s);
@@ -34,8 +34,8 @@ hipError_t launch_gt_split_128_128(const float *rows_half, const float *pos, con
 // layers with both widths multiples of 128 as passes over column blocks (same file, same two shapes)
 bool split_wide_ok(int N, int K, int max_width);
 hipError_t launch_gc_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const int32_t *off,
-                                const int32_t *src, const void *thetaP_all, float *out, int os, int n_in, int n_out,
-                                int B, int N, int K, int csr, hipStream_t s);
+                                const int32_t *src, const int32_t *order, const void *thetaP_all, float *out, int os,
+                                int n_in, int n_out, int B, int N, int K, int csr, hipStream_t s);
 hipError_t launch_gt_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const float *g_rows,
                                 int gst, float *partials, int n_hi, int n_ho, int chunks, int B, int N, int K,
                                 hipStream_t s);
@@ -56,13 +56,13 @@ bool gather_contract_supported(int DI, int DO)
 }
 
 hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
-                                  const int32_t *off, const int32_t *src, const void *thetaP,
+                                  const int32_t *off, const int32_t *src, const int32_t *order, const void *thetaP,
                                   int theta_fmt, float *out, int B, int N, int K, int DI, int DO,
                                   int csr, int out_bcn, hipStream_t s)
 {
 #define FLEX_SHAPE(DI_, DO_, W, T, OCC, WS) \
     if (DI == DI_ && DO == DO_)         \
-        return launch_gc_##DI_##_##DO_(rows, pos, nbr, off, src, thetaP, theta_fmt, out, B, N, K, csr, out_bcn, s);
+        return launch_gc_##DI_##_##DO_(rows, pos, nbr, off, src, order, thetaP, theta_fmt, out, B, N, K, csr, out_bcn, s);
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
     return hipErrorNotSupported;
@@ -139,7 +139,8 @@ static bool use_split_128(int Din, int Dout, int layout, int N, int K, int csr)
 // Forward (transpose == 0: passes over the input-channel halves) or feature gradient (transpose == 1: passes over
 // the halves of the upstream gradient's channels) of a 128 -> 128 layer.  scratch: theta_ws_bytes(128, 128).
 static hipError_t split_gather_contract_128(const float *rows, const float *pos, const int32_t *nbr,
-                                            const int32_t *off, const int32_t *src, const float *theta,
+                                            const int32_t *off, const int32_t *src, const int32_t *order,
+                                            const float *theta,
                                             const float *bias, void *scratch, float *out, int B, int N, int K,
                                             int transpose, hipStream_t s)
 {
@@ -157,7 +158,7 @@ static hipError_t split_gather_contract_128(const float *rows, const float *pos,
             e = launch_pack_theta_f16(blk_theta, blk_bias, packed, 128, 64, 64, 128, 1, s);
         }
         if (e != hipSuccess) return e;
-        e = launch_gc_split_128_128(rows + 64 * h, pos, nbr, off, src, packed, out, B, N, K, transpose, h, s);
+        e = launch_gc_split_128_128(rows + 64 * h, pos, nbr, off, src, order, packed, out, B, N, K, transpose, h, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -213,7 +214,8 @@ static size_t wide_param_scratch_bytes(int Din, int Dout)
 // Forward (transpose == 0: rows = features [.., Din], out [.., Dout]) or feature gradient (transpose == 1:
 // rows = upstream gradient [.., Dout], out = grad_feat [.., Din]; in-edge lists) of a wide layer: two launches.
 static hipError_t wide_gather_contract(const float *rows, const float *pos, const int32_t *nbr, const int32_t *off,
-                                       const int32_t *src, const float *theta, const float *bias, void *scratch,
+                                       const int32_t *src, const int32_t *order, const float *theta,
+                                       const float *bias, void *scratch,
                                        float *out, int B, int N, int K, int Din, int Dout, int transpose,
                                        hipStream_t s)
 {
@@ -221,7 +223,7 @@ static hipError_t wide_gather_contract(const float *rows, const float *pos, cons
     const int n_in = w_in / 64, n_out = w_out / 128;
     hipError_t e = launch_pack_theta_f16_blocks(theta, bias, scratch, Din, Dout, 64, 128, n_in, n_out, transpose, s);
     if (e != hipSuccess) return e;
-    return launch_gc_split_wide(rows, w_in, pos, nbr, off, src, scratch, out, w_out, n_in, n_out, B, N, K, transpose, s);
+    return launch_gc_split_wide(rows, w_in, pos, nbr, off, src, order, scratch, out, w_out, n_in, n_out, B, N, K, transpose, s);
 }
 
 // Parameter gradients of a wide layer: (Din/64) x (Dout/64) independent blocks of [4*64 x 64], two launches
@@ -314,7 +316,7 @@ struct FwdPlan {
 };
 struct BwdPlan {
     bool tiled, wide;
-    size_t thetaP, featT, gT, gfT, partials, in_off, in_src, inedge_ws, total;
+    size_t thetaP, featT, gT, gfT, partials, order, in_off, in_src, inedge_ws, total;
 };
 
 // The route (block passes of the wide path / single-pass tiled kernels / direct form) is decided here, once, from
@@ -352,6 +354,7 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
         }
         p.partials = at;
         at += p.wide ? wide_partial_bytes((int)B, (int)N, Din, Dout) : grad_theta_partial_bytes(B, N, Din, Dout);
+        p.order = at; at += inedges_order_bytes(B * N);      // walking order of the feature gradient's gather
         if (build) {
             p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
             p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
@@ -604,8 +607,8 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
             rows = (float *)(ws + p.featT);
             dst = (float *)(ws + p.outT);
         }
-        FLEX_HIP(wide_gather_contract(rows, pos, nbr, nullptr, nullptr, theta, bias, ws + p.thetaP, dst, B, N, K, Din,
-                                      Dout, 0, s));
+        FLEX_HIP(wide_gather_contract(rows, pos, nbr, nullptr, nullptr, nullptr, theta, bias, ws + p.thetaP, dst, B, N, K,
+                                      Din, Dout, 0, s));
         if (bcn) FLEX_HIP(launch_bnc_to_bcn(dst, out, B, Dout, N, s));
         return FLEX_OK;
     }
@@ -615,7 +618,8 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
     }
     void *thetaP = ws + p.thetaP;
     if (use_split_128(Din, Dout, layout, N, K, 0)) {
-        FLEX_HIP(split_gather_contract_128(feat, pos, nbr, nullptr, nullptr, theta, bias, thetaP, out, B, N, K, 0, s));
+        FLEX_HIP(split_gather_contract_128(feat, pos, nbr, nullptr, nullptr, nullptr, theta, bias, thetaP, out, B, N, K, 0,
+                                           s));
         return FLEX_OK;
     }
     const int fmt = gather_contract_theta_format(Din, Dout, N, K, 0);
@@ -626,7 +630,7 @@ int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr, const 
         FLEX_HIP(launch_bcn_to_bnc(feat, featT, B, Din, N, s));
         rows = featT;
     }
-    FLEX_HIP(launch_gather_contract(rows, pos, nbr, nullptr, nullptr, thetaP, fmt, out, B, N, K, Din,
+    FLEX_HIP(launch_gather_contract(rows, pos, nbr, nullptr, nullptr, nullptr, thetaP, fmt, out, B, N, K, Din,
                                     Dout, 0, bcn, s));
     return FLEX_OK;
 }
@@ -747,8 +751,10 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
                 in_src = src;
             }
             float *dst = bcn ? (float *)(ws + p.gfT) : grad_feat;
-            FLEX_HIP(wide_gather_contract(g_rows, pos, nullptr, in_off, in_src, theta, bias, ws + p.thetaP, dst, B, N,
-                                          K, Din, Dout, 1, s));
+            int32_t *order = (int32_t *)(ws + p.order);
+            FLEX_HIP(launch_inedges_order(in_off, B, N, order, s));
+            FLEX_HIP(wide_gather_contract(g_rows, pos, nullptr, in_off, in_src, order, theta, bias, ws + p.thetaP, dst,
+                                          B, N, K, Din, Dout, 1, s));
             if (bcn) FLEX_HIP(launch_bnc_to_bcn(dst, grad_feat, B, Din, N, s));
         }
         return FLEX_OK;
@@ -785,14 +791,16 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
             in_src = src;
         }
         void *thetaP = ws + p.thetaP;
+        int32_t *order = (int32_t *)(ws + p.order);
+        FLEX_HIP(launch_inedges_order(in_off, B, N, order, s));
         if (use_split_128(Din, Dout, layout, N, K, 1)) {
-            FLEX_HIP(split_gather_contract_128(g_rows, pos, nullptr, in_off, in_src, theta, bias, thetaP, grad_feat,
-                                               B, N, K, 1, s));
+            FLEX_HIP(split_gather_contract_128(g_rows, pos, nullptr, in_off, in_src, order, theta, bias, thetaP,
+                                               grad_feat, B, N, K, 1, s));
             return FLEX_OK;
         }
         const int fmt = gather_contract_theta_format(Dout, Din, N, K, 1);
         FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 1, fmt, s));
-        FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, thetaP, fmt, grad_feat, B, N,
+        FLEX_HIP(launch_gather_contract(g_rows, pos, nullptr, in_off, in_src, order, thetaP, fmt, grad_feat, B, N,
                                         K, Dout, Din, 1, bcn, s));
     }
     return FLEX_OK;

@@ -73,10 +73,11 @@ hipError_t launch_bnc_to_bcn(const float *src, float *dst, int B, int C, int N, 
 //   theta_fmt: what thetaP holds, as answered by gather_contract_theta_format for the same
 //   (DI, DO, N, K, csr): 0 = fp32 ThetaP (launch_pack_theta), 1 = split-half fragments
 //   (launch_pack_theta_f16).
+//   order (csr == 1 only): the walking order from launch_inedges_order for these lists
 hipError_t launch_gather_contract(const float *rows, const float *pos, const int32_t *nbr,
-                                  const int32_t *off, const int32_t *src, const void *thetaP,
-                                  int theta_fmt, float *out, int B, int N, int K, int DI, int DO,
-                                  int csr, int out_bcn, hipStream_t s);
+                                  const int32_t *off, const int32_t *src, const int32_t *order,
+                                  const void *thetaP, int theta_fmt, float *out, int B, int N, int K, int DI,
+                                  int DO, int csr, int out_bcn, hipStream_t s);
 bool gather_contract_supported(int DI, int DO);
 int gather_contract_theta_format(int DI, int DO, int N, int K, int csr);
 // true when the environment asks for the fp32 matrix op in the wave-specialised kernels
@@ -110,6 +111,10 @@ hipError_t launch_inedges_build(const int32_t *nbr, int B, int N, int K, int32_t
 hipError_t launch_inedges_build_sub(const int32_t *nbr, const int32_t *sel, int B, int N, int Ns, int K,
                                     int32_t *in_off, int32_t *in_src, void *ws, hipStream_t s);
 size_t inedges_ws_bytes(int64_t BN);
+// order[b*N + p] = point at position p: the cloud's points sorted by in-edge list length inside windows of nearby
+// points (the walking order of the gather kernels over in-edge lists)
+size_t inedges_order_bytes(int64_t BN);
+hipError_t launch_inedges_order(const int32_t *in_off, int B, int N, int32_t *order, hipStream_t s);
 size_t exclusive_scan_ws_bytes(int64_t n);
 hipError_t launch_exclusive_scan_i32(const int32_t *cnt, int32_t *off, int64_t n, void *ws, hipStream_t s);
 size_t knn_ws_bytes(int B, int N);

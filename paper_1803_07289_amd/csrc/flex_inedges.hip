@@ -210,6 +210,85 @@ __global__ __launch_bounds__(256) void inedge_sort_kernel(const int32_t *__restr
     }
 }
 
+// ---- walking order for the gathers over in-edge lists -----------------------------------------
+// order[b*N + p] = the point that stands at position p of cloud b: inside every window of ORDER_WINDOW consecutive
+// positions the window's points, sorted by the length of their in-edge list (lengths past 31 count as 31), points
+// of equal length in index order.  A wave of the gather kernels takes four consecutive positions and a tile a few
+// dozen, so their lists have (nearly) one length: no slot of a batch stays empty and no wave waits for a longer
+// list at the tile's barrier, while a window is small enough for its gathered rows to stay in the caches.
+// One workgroup per window: lengths -> per (length, 64-point chunk) counts by ballots -> running sum in
+// (length, chunk) order -> every point's place.
+// The window is 13 tiles of 48 points: the persistent kernels deal tiles to workgroups with a stride that is a
+// power of two, and a window of a power-of-two number of tiles would hand a workgroup the same place in every
+// window, i.e. always the short or always the long lists.
+static constexpr int ORDER_WINDOW = 624;
+static constexpr int ORDER_CHUNKS = (ORDER_WINDOW + 63) / 64;  // 64-point chunks of a window
+static constexpr int ORDER_ROUNDS = (ORDER_CHUNKS + 3) / 4;    // chunks per wave (4 waves)
+static constexpr int ORDER_BUCKETS = 32;
+
+__global__ __launch_bounds__(256) void inedge_order_kernel(const int32_t *__restrict__ off, int32_t *__restrict__ order,
+                                                           int N, int windows_per_cloud)
+{
+    __shared__ int s_cnt[ORDER_BUCKETS * ORDER_CHUNKS];        // [length][chunk], then its exclusive running sum
+    const int b = blockIdx.x / windows_per_cloud, w = blockIdx.x - b * windows_per_cloud;
+    const int p0 = w * ORDER_WINDOW, n = min(ORDER_WINDOW, N - p0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    int len[ORDER_ROUNDS], rank[ORDER_ROUNDS];
+#pragma unroll
+    for (int r = 0; r < ORDER_ROUNDS; ++r) {
+        const int chunk = r * 4 + wave, i = chunk * 64 + lane;
+        len[r] = -1;
+        if (i < n) {
+            const int64_t g = (int64_t)b * N + p0 + i;
+            len[r] = min(off[g + 1] - off[g], ORDER_BUCKETS - 1);
+        }
+        rank[r] = 0;
+        if (chunk < ORDER_CHUNKS) {                             // wave-uniform
+            for (int d = 0; d < ORDER_BUCKETS; ++d) {
+                const uint64_t m = __ballot(len[r] == d);
+                if (len[r] == d) rank[r] = __popcll(m & lt);
+                if (lane == 0) s_cnt[d * ORDER_CHUNKS + chunk] = __popcll(m);
+            }
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // exclusive running sum of the ORDER_BUCKETS * ORDER_CHUNKS counts: PER consecutive entries per lane
+        constexpr int PER = ORDER_BUCKETS * ORDER_CHUNKS / 64;
+        int v[PER], sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { v[i] = s_cnt[lane * PER + i]; sum += v[i]; }
+        int x = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(x, d, 64);
+            if (lane >= d) x += y;
+        }
+        int run = x - sum;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { s_cnt[lane * PER + i] = run; run += v[i]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < ORDER_ROUNDS; ++r) {
+        const int chunk = r * 4 + wave, i = chunk * 64 + lane;
+        if (i < n) order[(int64_t)b * N + p0 + s_cnt[len[r] * ORDER_CHUNKS + chunk] + rank[r]] = p0 + i;
+    }
+}
+
+size_t inedges_order_bytes(int64_t BN) { return align256(sizeof(int32_t) * (size_t)BN); }
+
+hipError_t launch_inedges_order(const int32_t *in_off, int B, int N, int32_t *order, hipStream_t s)
+{
+    static_assert((ORDER_BUCKETS * ORDER_CHUNKS) % 64 == 0, "order kernel: whole entries per lane in the running sum");
+    const int wpc = (N + ORDER_WINDOW - 1) / ORDER_WINDOW;
+    const int64_t blocks = (int64_t)B * wpc;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(inedge_order_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in_off, order, N, wpc);
+    return hipGetLastError();
+}
+
 // off[0..n] = exclusive running sum of cnt[0..n) (off[n] = total); ws: exclusive_scan_ws_bytes(n)
 size_t exclusive_scan_ws_bytes(int64_t n) { return align256(sizeof(int32_t) * (size_t)(cdiv64(n, SCAN_CHUNK) + 1)); }
 

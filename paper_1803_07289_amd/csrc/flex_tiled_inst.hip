@@ -63,7 +63,7 @@ int FLEX_NAME(route, FLEX_DI, FLEX_DO)(int N, int K, int csr)
 
 hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float *pos,
                                                   const int32_t *nbr, const int32_t *off,
-                                                  const int32_t *src, const void *thetaP,
+                                                  const int32_t *src, const int32_t *order, const void *thetaP,
                                                   int theta_fmt, float *out, int B, int N, int K,
                                                   int csr, int out_bcn, hipStream_t s)
 {
@@ -116,6 +116,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
             // feature gradient: lean in-edge producers under the same conditions
             const bool lean_csr = csr && route == 3;
             if (lean_csr) {
+                if (order == nullptr) return hipErrorInvalidValue;
                 constexpr bool WIDE_OK = (S::WAVES * 4 <= 16) && (((S::DOP / 16) * (S::T * 3 / 16)) % S::WAVES == 0);
                 constexpr int PMX = WIDE_OK ? 3 : 1;
                 const bool wide = PMX > 1 && lean_producer_mode() != 1;
@@ -124,7 +125,7 @@ hipError_t FLEX_NAME(launch_gc, FLEX_DI, FLEX_DO)(const float *rows, const float
                 const int tpcl = (N + tl - 1) / tl;
                 const int totl = B * tpcl;
                 const dim3 gl(persistent_grid(totl, wide ? WL::WG_PER_CU : W::WG_PER_CU)), bl(wide ? WL::NT : W::NT);
-#define FLEX_LEAN_ARGS rows, pos, off, src, thetaP, exp_off, out, N, tpcl, totl
+#define FLEX_LEAN_ARGS rows, pos, off, src, order, thetaP, exp_off, out, N, tpcl, totl
                 if (wide && !out_bcn) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
                 else if (wide) hipLaunchKernelGGL((grad_feat_lean_kernel<S, true, PMX>), gl, bl, 0, s, FLEX_LEAN_ARGS);
                 else if (!out_bcn) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1>), gl, bl, 0, s, FLEX_LEAN_ARGS);
@@ -220,8 +221,8 @@ bool split_ok_128_128(int N, int K, int csr)
 }
 
 hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr, const int32_t *off,
-                                   const int32_t *src, const void *thetaP, float *out, int B, int N, int K, int csr,
-                                   int accumulate, hipStream_t s)
+                                   const int32_t *src, const int32_t *order, const void *thetaP, float *out, int B,
+                                   int N, int K, int csr, int accumulate, hipStream_t s)
 {
     using W = WsGeom<S, 1>;
     const int tpc = (N + W::T - 1) / W::T;
@@ -230,12 +231,13 @@ hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, con
     const int tot = (int)tot64;
     const dim3 g(persistent_grid(tot, W::WG_PER_CU)), blk(W::NT);
     const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
+    if (csr && order == nullptr) return hipErrorInvalidValue;
     if (!csr) {
         if (accumulate) hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, 1, 128, 128, true>), g, blk, 0, s, rows_half, pos, nbr, thetaP, exp_off, out, N, K, tpc, tot);
         else hipLaunchKernelGGL((gather_contract_lean_kernel<S, false, 1, 128, 128, false>), g, blk, 0, s, rows_half, pos, nbr, thetaP, exp_off, out, N, K, tpc, tot);
     } else {
-        if (accumulate) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1, 128, 128, true>), g, blk, 0, s, rows_half, pos, off, src, thetaP, exp_off, out, N, tpc, tot);
-        else hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1, 128, 128, false>), g, blk, 0, s, rows_half, pos, off, src, thetaP, exp_off, out, N, tpc, tot);
+        if (accumulate) hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1, 128, 128, true>), g, blk, 0, s, rows_half, pos, off, src, order, thetaP, exp_off, out, N, tpc, tot);
+        else hipLaunchKernelGGL((grad_feat_lean_kernel<S, false, 1, 128, 128, false>), g, blk, 0, s, rows_half, pos, off, src, order, thetaP, exp_off, out, N, tpc, tot);
     }
     return hipGetLastError();
 }
@@ -254,8 +256,8 @@ bool split_wide_ok(int N, int K, int max_width)
 }
 
 hipError_t launch_gc_split_wide(const float *rows, int rs, const float *pos, const int32_t *nbr, const int32_t *off,
-                                const int32_t *src, const void *thetaP_all, float *out, int os, int n_in, int n_out,
-                                int B, int N, int K, int csr, hipStream_t s)
+                                const int32_t *src, const int32_t *order, const void *thetaP_all, float *out, int os,
+                                int n_in, int n_out, int B, int N, int K, int csr, hipStream_t s)
 {
     using W = WsGeom<S, 1>;
     const int tpc = (N + W::T - 1) / W::T;
@@ -268,8 +270,9 @@ hipError_t launch_gc_split_wide(const float *rows, int rs, const float *pos, con
     chunks = chunks >= 8 ? chunks / 8 * 8 : (chunks > 1 ? chunks : 1);
     const dim3 g((unsigned)(n_out * chunks)), blk(W::NT);
     const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP), blk_bytes = (int)theta_f16_bytes(S::DIP, S::DOP);
+    if (csr && order == nullptr) return hipErrorInvalidValue;
     if (csr)
-        hipLaunchKernelGGL((grad_feat_lean_passes_kernel<S, 1>), g, blk, 0, s, rows, pos, off, src, thetaP_all,
+        hipLaunchKernelGGL((grad_feat_lean_passes_kernel<S, 1>), g, blk, 0, s, rows, pos, off, src, order, thetaP_all,
                            blk_bytes, exp_off, out, N, tpc, tot, rs, os, n_in, chunks);
     else if (K % 8 == 0)
         hipLaunchKernelGGL((gather_contract_lean_passes_kernel<S, 1, false>), g, blk, 0, s, rows, pos, nbr, thetaP_all,

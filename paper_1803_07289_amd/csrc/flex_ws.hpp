@@ -31,6 +31,11 @@
 #ifndef FLEX_LEAN_VALU_AGG
 #define FLEX_LEAN_VALU_AGG 1
 #endif
+// 1: the position differences reach the compute lanes as (dx, dy, dz, w) through a wave-private LDS array (one
+// 16-byte read per row); 0: one component per lane by ds_bpermute, then three quad broadcasts per row
+#ifndef FLEX_DP_LDS
+#define FLEX_DP_LDS 1
+#endif
 
 namespace flex {
 
@@ -567,6 +572,9 @@ struct LeanProducer {
     int e_g, e_k;                // point and slot (within half 0) of this lane's entry
     unsigned e_col;              // position component to read: x, y, z (lane 3 reads z, value unused)
     float e_mul, e_fix;          // dp component = (pn - pc)*e_mul + e_fix   (component lane 3: the constant 1)
+    float *s_dp = nullptr;       // this wave's LDS array of 32 entries x (dx, dy, dz, w), entry = 4 * slot + point
+    int dp_rd = 0;               // float offset of this lane's entry of slot 0 in it
+    __device__ __forceinline__ void set_dp_stage(float *p) { s_dp = p; dp_rd = 4 * (grp % G::PW); }
 
     __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *nbr_, int N_,
                                          int K_, int pw_, const TileSchedule &sc, int tiles_per_cloud_)
@@ -724,36 +732,71 @@ struct LeanProducer {
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * row_stride());
             const int nb = x1.b, nlw0 = x1.lw0;
             x1 = x2;
-            float dpc[U];
+            constexpr bool DP_LDS = FLEX_DP_LDS && VALU_AGG && !SUM;
+            float dpc[DP_LDS ? 1 : U];
+            v4f dpv[DP_LDS ? 3 : 1];
+            if constexpr (DP_LDS) {
+                // entry (16 h + e), component c sits at float 4 * (16 h + e) + c = 64 h + lane
+                const int lane = threadIdx.x & 63;
+                s_dp[lane] = __int_as_float(dpe[0]);
+                s_dp[64 + lane] = __int_as_float(dpe[1]);
+                wave_lds_sync();
+                dpv[0] = *reinterpret_cast<const v4f *>(s_dp + dp_rd);          // rows 0 and 1 now, row u + 2 while
+                dpv[1] = *reinterpret_cast<const v4f *>(s_dp + 16 + dp_rd);     // row u is accumulated
+            } else {
 #pragma unroll
-            for (int u = 0; u < U; ++u) dpc[u] = SUM ? 0.f : __int_as_float(spread(dpe, perm_dp, u));
+                for (int u = 0; u < U; ++u) dpc[u] = SUM ? 0.f : __int_as_float(spread(dpe, perm_dp, u));
+            }
+            const bool first = (kb == 0);            // first batch of a tile: its first row starts the sums
 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if constexpr (DP_LDS)
+                    if (u + 2 < U) dpv[(u + 2) % 3] = *reinterpret_cast<const v4f *>(s_dp + 16 * (u + 2) + dp_rd);
                 if (!TAIL || u < 4 || cur_upper) {
                     float fv[S::VEC];
 #pragma unroll
                     for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
-                    if constexpr (SUM && TAIL) {
-                        const float one = (k0_acc + u < K) ? 1.f : 0.f;            // 0 for a slot past K
+                    if constexpr (SUM) {
+                        const float one = (!TAIL || k0_acc + u < K) ? 1.f : 0.f;   // 0 for a slot past K
+                        if (u == 0 && first) {
 #pragma unroll
-                        for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(one, fv[v], acc[v][3]);
-                    } else if constexpr (SUM) {
+                            for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, TAIL ? one * fv[v] : fv[v]};
+                        } else {
 #pragma unroll
-                        for (int v = 0; v < S::VEC; ++v) acc[v][3] += fv[v];
+                            for (int v = 0; v < S::VEC; ++v) {
+                                if constexpr (TAIL) acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                                else acc[v][3] += fv[v];
+                            }
+                        }
                     } else if constexpr (VALU_AGG) {
-                        // the four lanes of a block hold (dx, dy, dz, 1): broadcast inside the quad
-                        const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
-                        const float one = TAIL ? dpp_move<0xFF>(dpc[u]) : 1.f;     // 0 for a slot past K
+                        float dx, dy, dz, one;
+                        if constexpr (DP_LDS) {
+                            dx = dpv[u % 3][0]; dy = dpv[u % 3][1]; dz = dpv[u % 3][2]; one = dpv[u % 3][3];
+                        } else {
+                            // the four lanes of a block hold (dx, dy, dz, 1): broadcast inside the quad
+                            dx = dpp_move<0x00>(dpc[u]); dy = dpp_move<0x55>(dpc[u]); dz = dpp_move<0xAA>(dpc[u]);
+                            one = TAIL ? dpp_move<0xFF>(dpc[u]) : 1.f;             // 0 for a slot past K
+                        }
+                        if (u == 0 && first) {
 #pragma unroll
-                        for (int v = 0; v < S::VEC; ++v) {
-                            acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
-                            acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
-                            acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
-                            if constexpr (TAIL) acc[v][3] = fmaf(one, fv[v], acc[v][3]);
-                            else acc[v][3] += fv[v];
+                            for (int v = 0; v < S::VEC; ++v)
+                                acc[v] = v4f{dx * fv[v], dy * fv[v], dz * fv[v], TAIL ? one * fv[v] : fv[v]};
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < S::VEC; ++v) {
+                                acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                                acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                                acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                                if constexpr (TAIL) acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                                else acc[v][3] += fv[v];
+                            }
                         }
                     } else {
+                        if (u == 0 && first) {
+#pragma unroll
+                            for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                        }
                         fma_row<S>(acc, dpc[u], fv);
                     }
                 }
@@ -764,8 +807,6 @@ struct LeanProducer {
             if (++kb == KB) {
                 kb = 0;
                 fin(acc, tile_i, nb, nlw0);
-#pragma unroll
-                for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
                 ++tile_i;
                 __syncthreads();        // tile complete in buffer tile_i & 1
             }
@@ -782,7 +823,12 @@ struct LeanProducer {
 // Slots past a list's end gather the point's own row with dp = (0,0,0,0), i.e. add nothing.
 // The list bounds of the next tile are requested when a wave's id cursor enters a tile.
 // ---------------------------------------------------------------------------
-template <class S, int PM, bool SUM = false, int RS = S::DI>
+// ORD: the tiles walk the cloud in the order given by `order` (order[b*N + p] = the point at position p, a
+// permutation of the cloud's points that puts points of equal list length next to each other inside windows of
+// nearby points, see inedge_order_kernel): the four points of a wave then have lists of (nearly) the same length
+// and so have the twelve waves of a tile, so hardly any slot of a batch is empty and no wave waits at the tile's
+// barrier for one with a longer list.  The points' ids travel with the tile (s_P) to the consumers' stores.
+template <class S, int PM, bool SUM = false, int RS = S::DI, bool ORD = false>
 struct LeanCsrProducer {
     using G = WsGeom<S, PM>;
     static constexpr int U = 8;
@@ -791,6 +837,7 @@ struct LeanCsrProducer {
 
     const float *rows, *pos;
     const int32_t *off, *src;
+    const int32_t *order = nullptr;
     int N, pw;
     unsigned rs_rt = 0;          // row stride in floats when RS == 0
     __device__ __forceinline__ void set_row_stride(int rs) { rs_rt = (unsigned)rs; }
@@ -804,6 +851,9 @@ struct LeanCsrProducer {
     int e_g, e_k;
     unsigned e_col;
     float e_mul, e_fix;
+    float *s_dp = nullptr;       // this wave's LDS array of 32 entries x (dx, dy, dz, w), entry = 4 * slot + point
+    int dp_rd = 0;               // float offset of this lane's entry of slot 0 in it
+    __device__ __forceinline__ void set_dp_stage(float *p) { s_dp = p; dp_rd = 4 * (grp % G::PW); }
 
     __device__ __forceinline__ void init(const float *rows_, const float *pos_, const int32_t *off_,
                                          const int32_t *src_, int N_, int pw_, const TileSchedule &sc,
@@ -829,10 +879,12 @@ struct LeanCsrProducer {
 
     // what the later pipeline stages need to know about a batch
     struct Desc {
-        int b, lw0;      // cloud, first point of this wave in the tile
+        int b, lw0;      // cloud, first position of this wave in the tile
+        int pid;         // entry layout: this lane's point (its position's point under ORD)
+        bool first;      // first batch of its tile: its first row starts the sums
         bool last;       // last batch of its tile: the aggregate is complete after it
         bool real;       // false past the workgroup's last tile (loaded, never used)
-        bool upper;      // some point of the wave has an entry in slots 4..7 of this batch (else those rows are skipped)
+        int nrows;       // slots 0 .. nrows-1 of this batch hold an entry of some point of the wave (the rest is skipped)
         int valid0, valid1;   // entry layout: does this lane's entry (half 0 / 1) exist
     };
 
@@ -842,9 +894,12 @@ struct LeanCsrProducer {
         int b, lw0;
         int dmax;                // longest list among the wave's four points
         int lo, deg;             // this lane's point: start and length of its list
-        int lo_n, hi_n;          // next tile: list bounds of this lane's point (in flight)
+        int pid;                 // this lane's point
+        int lo_n, hi_n, pid_n;   // next tile: this lane's point and its list bounds (in flight)
+        int pid_nn;              // ORD: this lane's point in the tile after the next (in flight)
         TileWalk tw;             // the tile those bounds belong to (the last tile again past the end)
-        __device__ __forceinline__ Cursor(const TileSchedule &sc, int tpc) : tw(sc, tpc) {}
+        TileWalk tw2;            // ORD: the tile pid_nn belongs to
+        __device__ __forceinline__ Cursor(const TileSchedule &sc, int tpc) : tw(sc, tpc), tw2(sc, tpc) {}
     };
 
     __device__ __forceinline__ void first_coords(int &b, int &lw0) const
@@ -853,40 +908,67 @@ struct LeanCsrProducer {
         b = tw.b;
         lw0 = tw.tic * G::T + pw * G::PW;
     }
-    // list bounds of this lane's point in the walk's tile
+    // this lane's point at its position in the walk's tile (positions past the cloud: the last one)
+    __device__ __forceinline__ int point_at(const TileWalk &tw) const
+    {
+        const int p = min(tw.tic * G::T + pw * G::PW + e_g, N - 1);
+        if constexpr (ORD) return order[(int64_t)tw.b * N + p];
+        else return p;
+    }
+    // list bounds of this lane's point (c.pid_n) in the walk's tile
     __device__ __forceinline__ void request_bounds(Cursor &c) const
     {
-        const int64_t gp = (int64_t)c.tw.b * N + min(c.tw.tic * G::T + pw * G::PW + e_g, N - 1);
+        const int64_t gp = (int64_t)c.tw.b * N + c.pid_n;
         c.lo_n = off[gp];
         c.hi_n = off[gp + 1];
     }
     // the cursor takes the bounds requested for tile i (in lo_n / hi_n, the walk stands on that tile) and
-    // requests tile i+1's
+    // requests tile i+1's (and, under ORD, the points of tile i+2)
     __device__ __forceinline__ void enter_tile(Cursor &c, int i) const
     {
         c.i = i; c.bi = 0;
         c.b = c.tw.b;
         c.lw0 = c.tw.tic * G::T + pw * G::PW;
         c.lo = c.lo_n;
-        c.deg = (c.lw0 + e_g < N) ? c.hi_n - c.lo_n : 0;      // points past the cloud have no list
+        c.pid = c.pid_n;
+        c.deg = (c.lw0 + e_g < N) ? c.hi_n - c.lo_n : 0;      // positions past the cloud have no list
         const int d = max(max(__builtin_amdgcn_readlane(c.deg, 0), __builtin_amdgcn_readlane(c.deg, 4)),
                           max(__builtin_amdgcn_readlane(c.deg, 8), __builtin_amdgcn_readlane(c.deg, 12)));
         c.nb = max(1, (d + U - 1) / U);
         c.dmax = d;
         c.tw.next_clamped();
+        if constexpr (ORD) {
+            c.pid_n = c.pid_nn;
+            c.tw2.next_clamped();
+            c.pid_nn = point_at(c.tw2);
+        } else {
+            c.pid_n = point_at(c.tw);
+        }
+        request_bounds(c);
+    }
+    // before the first enter_tile: the points of tile 0 (and 1 under ORD) and tile 0's bounds go in flight
+    __device__ __forceinline__ void start(Cursor &c) const
+    {
+        c.pid_n = point_at(c.tw);
+        if constexpr (ORD) {
+            c.tw2.next_clamped();
+            c.pid_nn = point_at(c.tw2);
+        }
         request_bounds(c);
     }
     // entry-layout ids of the cursor's batch + its descriptor; then the cursor moves on
     __device__ __forceinline__ void fetch(Cursor &c, int (&id)[2], Desc &d) const
     {
         d.b = c.b; d.lw0 = c.lw0;
+        d.pid = c.pid;
         d.real = c.i < count;
+        d.first = c.bi == 0;
         d.last = c.bi == c.nb - 1;
-        d.upper = U * c.bi + 4 < c.dmax;
+        d.nrows = min(U, max(1, c.dmax - U * c.bi));
         const int s0 = U * c.bi + e_k, s1 = s0 + 4;
         d.valid0 = d.real && s0 < c.deg;
         d.valid1 = d.real && s1 < c.deg;
-        const int self = min(c.lw0 + e_g, N - 1);
+        const int self = c.pid;
         id[0] = self; id[1] = self;
         if (d.valid0) id[0] = src[c.lo + s0];
         if (d.valid1) id[1] = src[c.lo + s1];
@@ -898,7 +980,7 @@ struct LeanCsrProducer {
         const unsigned col = e_col * (unsigned)N;
         pn[0] = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)id[0]));
         pn[1] = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)id[1]));
-        pc = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)min(d.lw0 + e_g, N - 1)));
+        pc = *reinterpret_cast<const float *>(pb + 4u * (col + (unsigned)d.pid));
     }
     __device__ __forceinline__ int spread(const int (&v)[2], int base, int u) const
     {
@@ -936,7 +1018,7 @@ struct LeanCsrProducer {
         Desc d0, d1;             // batch whose rows are in flight; batch of idn
         Cursor c(sched, tiles_per_cloud);
         {
-            request_bounds(c);
+            start(c);
             enter_tile(c, 0);
             int id0[2];
             fetch(c, id0, d0);
@@ -947,7 +1029,7 @@ struct LeanCsrProducer {
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d0.b * N * row_stride());
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (u < 4 || d0.upper) load_row(f[u], spread(id0, perm_id, u), rb);
+                if (u < d0.nrows) load_row(f[u], spread(id0, perm_id, u), rb);
             __builtin_amdgcn_sched_barrier(0);
         }
         int tile_i = 0;
@@ -958,8 +1040,9 @@ struct LeanCsrProducer {
         while (d0.real) {
             int dpe[2];
             dp_entries(dpe, pn, pc, d0);
-            const bool last = d0.last;
-            const bool cur_upper = d0.upper, next_upper = d1.upper;   // slots 4..7: accumulate / request them at all?
+            const bool first = d0.first, last = d0.last;
+            const int cur_rows = d0.nrows, next_rows = d1.nrows;      // slots to accumulate / to request
+            const int pid_cur = d0.pid;
             // batch d1: positions and (below) rows go in flight; the cursor's batch: ids
             int idc[U];
 #pragma unroll
@@ -968,32 +1051,62 @@ struct LeanCsrProducer {
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)d1.b * N * row_stride());
             d0 = d1;
             fetch(c, idn, d1);
-            float dpc[U];
+            constexpr bool DP_LDS = FLEX_DP_LDS && !SUM;
+            float dpc[DP_LDS ? 1 : U];
+            v4f dpv[DP_LDS ? 3 : 1];
+            if constexpr (DP_LDS) {
+                // entry (16 h + e), component c sits at float 4 * (16 h + e) + c = 64 h + lane
+                const int lane = threadIdx.x & 63;
+                s_dp[lane] = __int_as_float(dpe[0]);
+                s_dp[64 + lane] = __int_as_float(dpe[1]);
+                wave_lds_sync();
+                dpv[0] = *reinterpret_cast<const v4f *>(s_dp + dp_rd);          // rows 0 and 1 now, row u + 2 while
+                dpv[1] = *reinterpret_cast<const v4f *>(s_dp + 16 + dp_rd);     // row u is accumulated
+            } else {
 #pragma unroll
-            for (int u = 0; u < U; ++u) dpc[u] = __int_as_float(spread(dpe, perm_dp, u));
+                for (int u = 0; u < U; ++u) dpc[u] = __int_as_float(spread(dpe, perm_dp, u));
+            }
 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (u < 4 || cur_upper) {
+                if constexpr (DP_LDS)
+                    if (u + 2 < U) dpv[(u + 2) % 3] = *reinterpret_cast<const v4f *>(s_dp + 16 * (u + 2) + dp_rd);
+                if (u < cur_rows) {
                     float fv[S::VEC];
 #pragma unroll
                     for (int v = 0; v < S::VEC; ++v) fv[v] = (FULL || lane_on) ? f[u][v] : 0.f;
                     if constexpr (SUM) {
+                        if (u == 0 && first) {
 #pragma unroll
-                        for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(dpc[u], fv[v], acc[v][3]);
+                            for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, dpc[u] * fv[v]};
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < S::VEC; ++v) acc[v][3] = fmaf(dpc[u], fv[v], acc[v][3]);
+                        }
                     } else {
-                        const float dx = dpp_move<0x00>(dpc[u]), dy = dpp_move<0x55>(dpc[u]), dz = dpp_move<0xAA>(dpc[u]);
-                        const float one = dpp_move<0xFF>(dpc[u]);    // 1 for a real entry, 0 for a missing one
+                        float dx, dy, dz, one;           // one: 1 for a real entry, 0 for a missing one
+                        if constexpr (DP_LDS) {
+                            dx = dpv[u % 3][0]; dy = dpv[u % 3][1]; dz = dpv[u % 3][2]; one = dpv[u % 3][3];
+                        } else {
+                            dx = dpp_move<0x00>(dpc[u]); dy = dpp_move<0x55>(dpc[u]); dz = dpp_move<0xAA>(dpc[u]);
+                            one = dpp_move<0xFF>(dpc[u]);
+                        }
+                        if (u == 0 && first) {
 #pragma unroll
-                        for (int v = 0; v < S::VEC; ++v) {
-                            acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
-                            acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
-                            acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
-                            acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                            for (int v = 0; v < S::VEC; ++v)
+                                acc[v] = v4f{dx * fv[v], dy * fv[v], dz * fv[v], one * fv[v]};
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < S::VEC; ++v) {
+                                acc[v][0] = fmaf(dx, fv[v], acc[v][0]);
+                                acc[v][1] = fmaf(dy, fv[v], acc[v][1]);
+                                acc[v][2] = fmaf(dz, fv[v], acc[v][2]);
+                                acc[v][3] = fmaf(one, fv[v], acc[v][3]);
+                            }
                         }
                     }
                 }
-                if (u < 4 || next_upper) load_row(f[u], idc[u], rb);
+                if (u < next_rows) load_row(f[u], idc[u], rb);
                 // keep the loop's shape: the scheduler would otherwise collect the eight loads at the end
                 // of the iteration and wait for all of them at its start (no row would be in flight
                 // while the previous ones are accumulated)
@@ -1001,9 +1114,7 @@ struct LeanCsrProducer {
             }
 
             if (last) {
-                fin(acc, tile_i, d0.b, d0.lw0);      // d0: first batch of the next tile by now
-#pragma unroll
-                for (int v = 0; v < S::VEC; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                fin(acc, tile_i, d0.b, d0.lw0, pid_cur);      // d0: first batch of the next tile by now
                 ++tile_i;
                 __syncthreads();        // tile complete in buffer tile_i & 1
             }
@@ -1015,11 +1126,12 @@ struct LeanCsrProducer {
 // the workgroup.  cw = consumer index; G = the workgroup geometry; barriers pair with the producers'.
 // OS = floats between consecutive output rows (point-major form; 0: the run-time value os_rt), ACC (or the
 // run-time flag acc_rt): add to what out holds.
-template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false>
+// ORD: tile slot pt holds the point s_P[pt] (the producers walk the cloud in a given order), not position l0 + pt.
+template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false, bool ORD = false>
 __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ thetaP, int theta_exp_off,
                                              float *__restrict__ out, int N, const TileSchedule &sc,
                                              int tiles_per_cloud, const char *s_A, const int *s_E, int os_rt = 0,
-                                             bool acc_rt = false)
+                                             bool acc_rt = false, const int *s_P = nullptr)
 {
     const int os = OS != 0 ? OS : os_rt;
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
@@ -1028,20 +1140,22 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
     const int slice = cw % G::NS;
     const bool active = cw < G::NITEMS;   // consumers beyond the item count only keep the barriers company
 
-    auto store_item = [&](const TileRef &r, int it, v4f d) {
+    auto store_item = [&](const TileRef &r, int it, v4f d, const int *sP) {
         const int idx = cw + it * G::NC;
         if (idx >= G::NITEMS) return;
         const int npts = min(G::T, N - r.l0);
         const int pt = (idx / G::NS) * 16 + r16;
         const int o = slice * 16 + 4 * q;
         if (pt < npts) {
+            int l = r.l0 + pt;
+            if constexpr (ORD) l = sP[pt];
             if constexpr (OUT_BCN) {
-                float *dst = out + ((int64_t)r.b * S::DO + o) * N + (r.l0 + pt);
+                float *dst = out + ((int64_t)r.b * S::DO + o) * N + l;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     if (o + i < S::DO) dst[(int64_t)i * N] = d[i];
             } else {
-                float *dst = out + ((int64_t)r.b * N + r.l0 + pt) * os + o;
+                float *dst = out + ((int64_t)r.b * N + l) * os + o;
                 if constexpr (S::DO % 4 == 0) {
                     if (o < S::DO) {
                         if (ACC || acc_rt) d += *reinterpret_cast<const v4f *>(dst);
@@ -1111,7 +1225,7 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
             v4f d = acc[0] + (acc[1] + acc[2]);
 #pragma unroll
             for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], -(e_pt + e_col[i]));   // undo both scalings
-            store_item(r, it, d);
+            store_item(r, it, d, ORD ? s_P + (k & 1) * G::T : nullptr);
         }
     }
 }
@@ -1133,6 +1247,7 @@ __device__ __forceinline__ void gather_contract_lean_body(const float *__restric
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
     __shared__ int s_E[2 * G::T];
+    __shared__ __attribute__((aligned(16))) float s_D[G::NP][128];     // per producer wave: a batch's position differences
 
     const int w = threadIdx.x >> 6;
 
@@ -1151,6 +1266,7 @@ __device__ __forceinline__ void gather_contract_lean_body(const float *__restric
         LeanProducer<S, PM, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         P.set_row_stride(rs_rt);
+        P.set_dp_stage(s_D[w]);
         float rsc[S::VEC][4];
         load_row_scales<S>(rsc, thetaP, theta_exp_off, P.t);
         P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
@@ -1208,6 +1324,7 @@ void gather_contract_lean_passes_kernel(const float *__restrict__ rows, const fl
 template <class S, bool OUT_BCN, int PM, int RS, int OS, bool ACC>
 __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ rows, const float *__restrict__ pos,
                                                     const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                                                    const int32_t *__restrict__ order,
                                                     const void *__restrict__ thetaP, int theta_exp_off,
                                                     float *__restrict__ out, int N, int tiles_per_cloud,
                                                     const TileSchedule sc, int rs_rt, int os_rt, bool acc_rt)
@@ -1215,6 +1332,8 @@ __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ ro
     using G = WsGeom<S, PM>;
     __shared__ __attribute__((aligned(16))) char s_A[2 * G::T * G::ROWB];
     __shared__ int s_E[2 * G::T];
+    __shared__ int s_P[2 * G::T];       // the point in every tile slot (the tiles walk the cloud in `order`)
+    __shared__ __attribute__((aligned(16))) float s_D[G::NP][128];     // per producer wave: a batch's position differences
 
     const int w = threadIdx.x >> 6;
 
@@ -1228,31 +1347,36 @@ __device__ __forceinline__ void grad_feat_lean_body(const float *__restrict__ ro
     }
 
     if (w < G::NP) {
-        LeanCsrProducer<S, PM, false, RS> P;
+        LeanCsrProducer<S, PM, false, RS, true> P;
         P.init(rows, pos, off, src, N, w, sc, tiles_per_cloud);
+        P.order = order;
         P.set_row_stride(rs_rt);
+        P.set_dp_stage(s_D[w]);
         float rsc[S::VEC][4];
         load_row_scales<S>(rsc, thetaP, theta_exp_off, P.t);
-        P.run([&](const v4f (&acc)[S::VEC], int i, int, int) {
+        const bool id_writer = (threadIdx.x & 0x33) == 0;        // entry lanes (slot 0, component 0) of the four points
+        P.run([&](const v4f (&acc)[S::VEC], int i, int, int, int pid) {
             const int buf = i & 1;
             store_split_rows<S>(acc, rsc, s_A + buf * (G::T * G::ROWB), s_E + buf * G::T, P.pw * G::PW + P.grp, P.t,
                                 P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+            if (id_writer) s_P[buf * G::T + P.pw * G::PW + P.e_g] = pid;
         });
         return;
     }
-    consumer_f16<S, G, OUT_BCN, OS, ACC>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E,
-                                         os_rt, acc_rt);
+    consumer_f16<S, G, OUT_BCN, OS, ACC, true>(w - G::NP, thetaP, theta_exp_off, out, N, sc, tiles_per_cloud, s_A, s_E,
+                                               os_rt, acc_rt, s_P);
 }
 
 template <class S, bool OUT_BCN, int PM, int RS = S::DI, int OS = S::DO, bool ACC = false>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_feat_lean_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                            const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                           const int32_t *__restrict__ order,
                            const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ out,
                            int N, int tiles_per_cloud, int total_tiles)
 {
     static_assert(RS != 0 && OS != 0, "run-time strides go through grad_feat_lean_passes_kernel");
-    grad_feat_lean_body<S, OUT_BCN, PM, RS, OS, ACC>(rows, pos, off, src, thetaP, theta_exp_off, out, N,
+    grad_feat_lean_body<S, OUT_BCN, PM, RS, OS, ACC>(rows, pos, off, src, order, thetaP, theta_exp_off, out, N,
                                                      tiles_per_cloud, TileSchedule(total_tiles), 0, 0, false);
 }
 
@@ -1261,6 +1385,7 @@ template <class S, int PM>
 __global__ __launch_bounds__((WsGeom<S, PM>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void grad_feat_lean_passes_kernel(const float *__restrict__ rows, const float *__restrict__ pos,
                                   const int32_t *__restrict__ off, const int32_t *__restrict__ src,
+                                  const int32_t *__restrict__ order,
                                   const void *__restrict__ thetaP_all, int theta_block_bytes, int theta_exp_off,
                                   float *__restrict__ out, int N, int tiles_per_cloud, int total_tiles, int rs,
                                   int os, int n_in, int chunks)
@@ -1269,7 +1394,7 @@ void grad_feat_lean_passes_kernel(const float *__restrict__ rows, const float *_
     const TileSchedule sc(total_tiles, (int)blockIdx.x - j * chunks, chunks);
     for (int i = 0; i < n_in; ++i) {
         const void *th = reinterpret_cast<const char *>(thetaP_all) + (size_t)(j * n_in + i) * theta_block_bytes;
-        grad_feat_lean_body<S, false, PM, 0, 0, false>(rows + S::DI * i, pos, off, src, th, theta_exp_off,
+        grad_feat_lean_body<S, false, PM, 0, 0, false>(rows + S::DI * i, pos, off, src, order, th, theta_exp_off,
                                                        out + S::DO * j, N, tiles_per_cloud, sc, rs, os, i > 0);
         __syncthreads();
     }
@@ -1565,6 +1690,7 @@ __device__ __forceinline__ void grad_theta_lean_body(const float *__restrict__ r
     constexpr int AS = bf3_stride(S::KD), GS = bf3_stride(S::DOP);
     __shared__ __attribute__((aligned(16))) char s_A[2][G::T * AS];
     __shared__ __attribute__((aligned(16))) char s_G[2][G::T * GS];
+    __shared__ __attribute__((aligned(16))) float s_D[G::NP][128];     // per producer wave: a batch's position differences
 
     const int w = threadIdx.x >> 6;
 
@@ -1572,6 +1698,7 @@ __device__ __forceinline__ void grad_theta_lean_body(const float *__restrict__ r
         LeanProducer<S, 2, false, RS, TAIL> P;
         P.init(rows, pos, nbr, N, K, w, sc, tiles_per_cloud);
         P.set_row_stride(rs_rt);
+        P.set_dp_stage(s_D[w]);
         // grad_out tile: T*DOP/4 four-float chunks over the producer threads, one tile ahead in registers
         constexpr int CPR = S::DOP / 4;                      // chunks per point
         constexpr int NCH = cdiv_c(G::T * CPR, 64 * G::NP);  // chunks per thread
@@ -1865,7 +1992,7 @@ void grad_pos_kernel(const float *__restrict__ rows, const int32_t *__restrict__
                 P.first_coords(b0, lw00);
                 load_y(b0, lw00 - P.pw * G::PW);
             }
-            P.run([&](const v4f (&acc)[S::VEC], int i, int nb, int nlw0) {
+            P.run([&](const v4f (&acc)[S::VEC], int i, int nb, int nlw0, int) {
                 park(acc, i, P.pw * G::PW + P.grp, P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
                 park_y(i);
                 load_y(nb, nlw0 - P.pw * G::PW);
