@@ -20,14 +20,37 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense f16 / bf16 matrix
-# HBM bytes per launch of each entry point's kernel on the default workload (rocprofv3 counters,
-# profiles/flexconv_cfg4_hbm_traffic.md)
-MEASURED_TRAFFIC = {"fwd": 4.073e9, "bwd_params": 4.088e9, "bwd_feat": 4.095e9,
-                    "pool_fwd": 5.717e9, "pool_bwd": 5.918e9}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "flexconv_cfg4_hbm_traffic.md")
+DTYPE = "f32 (HBM tensors and accumulation fp32; contractions as split f16 / three-piece bf16 matrix ops)"
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def kernel_source_hash():
+    """sha256 over the HIP sources of the library: ties a counter measurement to the kernels it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_1803_07289_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        h.update(name.encode())
+        h.update(open(os.path.join(src, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic():
+    """HBM bytes per launch of each entry point's kernel on the default workload, as measured with
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and recorded in the profile summary together with the hash of the
+    kernel sources it was measured on.  ({}, why) when there is no record or the sources have changed since."""
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+        rec = json.loads(text.split("traffic-json:", 1)[1].splitlines()[0])
+    except (OSError, IndexError, ValueError):
+        return {}, "no machine-readable record in profiles/flexconv_cfg4_hbm_traffic.md"
+    if rec.get("kernel_source_sha256") != kernel_source_hash():
+        return {}, "kernel sources changed since the counters were read (profiles/flexconv_cfg4_hbm_traffic.md)"
+    return {k: float(v) for k, v in rec["traffic_bytes"].items()}, "profiles/flexconv_cfg4_hbm_traffic.md"
 
 
 def main():
@@ -53,6 +76,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the feature tensor (known size) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against them")
+    ap.add_argument("--no-calibrate", action="store_true",
+                    help="skip the two microbenchmarks (plain copy, pure f16 matrix-op loop) whose results give "
+                         "every roofline entry its fraction of the MEASURED peak beside the published one")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no multi-GPU path exists); use --gpus 1")
@@ -174,6 +200,31 @@ def main():
             state["knn"] = fx.flex_knn(pos, K)
         mark(13)
 
+    # ---- measured peaks of this device: plain copy kernel, pure f16 matrix-op loop ----------
+    measured_peaks = None
+    if not args.no_calibrate:
+        src_buf = feat if feat.numel() * 4 >= (1 << 28) else torch.empty(1 << 26, device="cuda")   # >= 256 MB
+        dst_buf = torch.empty_like(src_buf)
+        sink = torch.zeros(1, device="cuda")
+        nbytes = src_buf.numel() * 4
+        best_copy = best_mfma = 0.0
+        for it in range(6):
+            c0, c1, c2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            c0.record()
+            fx.flex_calibrate_copy(src_buf, dst_buf)
+            c1.record()
+            flop = fx.flex_calibrate_mfma_f16(20000, sink)
+            c2.record()
+            torch.cuda.synchronize()
+            if it > 0:         # the first round warms up
+                best_copy = max(best_copy, 2 * nbytes / (c0.elapsed_time(c1) * 1e-3) / 1e9)
+                best_mfma = max(best_mfma, flop / (c1.elapsed_time(c2) * 1e-3) / 1e12)
+        measured_peaks = {"copy_GBs": best_copy, "copy_bytes_each_way": nbytes, "mfma_f16_TFLOPs": best_mfma,
+                          "how": "flex_calibrate_copy (bytes read + written / time) and flex_calibrate_mfma_f16 "
+                                 "(16 waves per CU, 4 chains of v_mfma_f32_16x16x32_f16), best of 5"}
+        del dst_buf, sink
+        log(f"[bench] measured peaks: copy {best_copy:.0f} GB/s, f16 matrix ops {best_mfma:.0f} TFLOP/s")
+
     if args.calibrate_copy:
         scratch = torch.empty_like(feat)
         for _ in range(3):
@@ -234,21 +285,26 @@ def main():
                  "pool_sub_bwd": "pool_bwd_gather_row16_kernel<2> (flexpool_sub_bwd)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
-    measured_traffic = MEASURED_TRAFFIC
+    traffic_rec, traffic_src = measured_traffic()
     default_workload = (cfg.index == 4 and N == 7_000_000 and K == 8 and layout == fx.BNC and x.order == "morton")
 
     def roof(name):
         ms = op_ms[name]["mean"]
         if ms <= 0:
             return None
-        traffic = measured_traffic.get(name) if default_workload else None
+        traffic = traffic_rec.get(name) if default_workload else None
         gbs = bytes_pt[name] * pts / (ms * 1e-3) / 1e9
         r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-             "traffic": traffic, "kernel": kernel_of[name], "kernel_ms": ms}
+             "traffic": traffic, "traffic_source": traffic_src if default_workload else "not the default workload",
+             "kernel": kernel_of[name], "kernel_ms": ms}
+        if measured_peaks:
+            r["frac_of_measured_peak"] = gbs / measured_peaks["copy_GBs"]
         if name in issued_matrix_flop_pt:
             r["fp32_equivalent_TFLOPs"] = conv_flop_pt * pts / (ms * 1e-3) / 1e12
             r["issued_matrix_TFLOPs"] = issued_matrix_flop_pt[name] * pts / (ms * 1e-3) / 1e12
             r["issued_matrix_frac_of_f16_peak"] = r["issued_matrix_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
+            if measured_peaks:
+                r["issued_matrix_frac_of_measured_f16_peak"] = r["issued_matrix_TFLOPs"] / measured_peaks["mfma_f16_TFLOPs"]
         return r
 
     rooflines = {n: roof(n) for n in OPS if n in bytes_pt and op_ms[n]["mean"] > 1e-2}
@@ -331,13 +387,15 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": DTYPE,
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "B": B, "N": N, "K": K, "Din": Din,
                    "Dout": Dout, "layout": args.layout, "point_order": x.order, "ops": names,
                    "in_edges": "prebuilt once (static neighbourhoods)"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "measured_peaks": measured_peaks,
+        "kernel_source_sha256": kernel_source_hash(),
         "rooflines_all": rooflines,
         "op_ms": op_ms,
         "inedges_build_ms": inedges_ms,

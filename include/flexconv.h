@@ -346,6 +346,15 @@ typedef enum {
 } flex_route;
 int flexconv_kernel_route(int op, int B, int N, int K, int Din, int Dout, int layout);
 
+/* Measurement aids for benchmarks (not part of the layers): what this device reaches on a plain copy and on a pure
+ * f16 matrix-op loop, so that kernel figures can be quoted against measured peaks beside the published ones.
+ * flex_calibrate_copy: dst = src, `bytes` (a multiple of 16, both pointers 16-byte aligned) read and written once.
+ * flex_calibrate_mfma_f16: every compute unit runs iters x 4 v_mfma_f32_16x16x32_f16 per wave on 16 waves;
+ * *flop_out (host, may be NULL) = the flop count of the launch; sink: one device float, never written in practice.
+ * Both only enqueue the kernel on `stream`; time them with events. */
+int flex_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream);
+int flex_calibrate_mfma_f16(int iters, float *sink, double *flop_out, void *stream);
+
 const char *flex_status_string(int status);
 
 #ifdef __cplusplus

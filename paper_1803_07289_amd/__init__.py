@@ -51,6 +51,8 @@ _SIGS = {
     "flexconv_has_fast_path": (_i, [_i, _i]),
     "flexconv_kernel_route": (_i, [_i] * 7),
     "flex_status_string": (ctypes.c_char_p, [_i]),
+    "flex_calibrate_copy": (_i, [_vp, _vp, _sz, _vp]),
+    "flex_calibrate_mfma_f16": (_i, [_i, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
 }
 
 
@@ -520,6 +522,25 @@ def flex_validate_neighbors(nbr):
     bad = torch.zeros(1, dtype=torch.int32, device=nbr.device)
     _check(lib().flex_validate_neighbors(_ptr(nbr), B, N, K, _ptr(bad), _stream()), "flex_validate_neighbors")
     return int(bad.item())
+
+
+def flex_calibrate_copy(src, dst):
+    """Measurement aid: dst = src by a plain copy kernel (time it with events)."""
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()) or \
+            src.numel() * src.element_size() != dst.numel() * dst.element_size():
+        raise ValueError("src and dst must be contiguous CUDA tensors of equal byte size")
+    _check(lib().flex_calibrate_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()),
+           "flex_calibrate_copy")
+    return dst
+
+
+def flex_calibrate_mfma_f16(iters, sink):
+    """Measurement aid: a pure f16 matrix-op loop on every compute unit; returns the launch's flop count."""
+    _dev(sink, torch.float32, "sink")
+    flop = ctypes.c_double(0.0)
+    _check(lib().flex_calibrate_mfma_f16(int(iters), _ptr(sink), ctypes.byref(flop), _stream()),
+           "flex_calibrate_mfma_f16")
+    return float(flop.value)
 
 
 def has_fast_path(Din, Dout):

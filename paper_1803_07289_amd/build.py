@@ -34,7 +34,8 @@ def shapes():
 
 def _jobs():
     jobs = []
-    for name in ("flex_api", "flex_misc", "flex_pool", "flex_inedges", "flex_upsample", "flex_idiss", "flex_knn"):
+    for name in ("flex_api", "flex_misc", "flex_pool", "flex_inedges", "flex_upsample", "flex_idiss", "flex_knn",
+                 "flex_calibrate"):
         jobs.append((os.path.join(CSRC, name + ".hip"), os.path.join(OBJ, name + ".o"), []))
     for (di, do, w, t, occ, ws) in shapes():
         jobs.append((os.path.join(CSRC, "flex_tiled_inst.hip"),

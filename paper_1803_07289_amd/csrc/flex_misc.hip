@@ -100,22 +100,34 @@ __device__ __forceinline__ void pack_theta_f16_block(const ThetaView &v, _Float1
                                                      int *s_ec)
 {
     const int KD = 4 * v.RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
+    // largest magnitude of every row, then (rows scaled) of every column: maxima of non-negative floats taken as
+    // integers with LDS atomics, all threads sharing the elements
+    for (int i = threadIdx.x; i < KDP; i += 1024) s_er[i] = 0;
+    for (int i = threadIdx.x; i < CP; i += 1024) s_ec[i] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < KD * CP; i += 1024) {
+        const float a = fabsf(v.at(i / CP, i % CP));
+        if (a > 0.f && a < __builtin_inff()) atomicMax(&s_er[i / CP], __float_as_int(a));
+    }
+    __syncthreads();
     for (int kd = threadIdx.x; kd < KDP; kd += 1024) {
-        float m = 0.f;
-        if (kd < KD)
-            for (int c = 0; c < CP; ++c) m = fmaxf(m, fabsf(v.at(kd, c)));
+        const float m = __int_as_float(s_er[kd]);
         int er = 0;
-        if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &er); er = -er; }
+        if (m > 0.f) { (void)frexpf(m, &er); er = -er; }
         er = er < -60 ? -60 : (er > 60 ? 60 : er);
         s_er[kd] = er;
         reinterpret_cast<float *>(reinterpret_cast<char *>(thetaF) + rscale_offset_bytes)[kd] = ldexpf(1.f, -er);
     }
     __syncthreads();
+    for (int i = threadIdx.x; i < KD * CP; i += 1024) {
+        const float a = fabsf(ldexpf(v.at(i / CP, i % CP), s_er[i / CP]));
+        if (a > 0.f && a < __builtin_inff()) atomicMax(&s_ec[i % CP], __float_as_int(a));
+    }
+    __syncthreads();
     for (int c = threadIdx.x; c < CP; c += 1024) {
-        float m = 0.f;
-        for (int kd = 0; kd < KD; ++kd) m = fmaxf(m, fabsf(ldexpf(v.at(kd, c), s_er[kd])));
+        const float m = __int_as_float(s_ec[c]);
         int ec = 0;
-        if (m > 0.f && m < __builtin_inff()) { (void)frexpf(m, &ec); ec = 15 - ec; }
+        if (m > 0.f) { (void)frexpf(m, &ec); ec = 15 - ec; }
         s_ec[c] = ec;
         reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes)[c] = ec;
     }

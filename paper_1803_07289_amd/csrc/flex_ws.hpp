@@ -661,6 +661,18 @@ struct LeanProducer {
         }
     }
 
+    // the row at byte offset `off` from the cloud's first row
+    __device__ __forceinline__ void load_row_at(float (&fr)[S::VEC], unsigned off, const char *rb) const
+    {
+        const char *p = rb + (off + lane_off);
+        if constexpr (S::VEC == 4) {
+            const v4f v = *reinterpret_cast<const v4f *>(p);
+            fr[0] = v.x; fr[1] = v.y; fr[2] = v.z; fr[3] = v.w;
+        } else {
+            fr[0] = *reinterpret_cast<const float *>(p);
+        }
+    }
+
     // cloud and first point (of this wave) of the workgroup's first tile
     __device__ __forceinline__ void first_coords(int &b, int &lw0) const
     {
@@ -722,9 +734,20 @@ struct LeanProducer {
             const int k0_acc = k0_cur;
             k0_cur = x1.k0;
             // ids of batch m+1 are here: their positions and (below) rows go in flight; ids of batch m+2 too
-            int idc[U];
+            constexpr bool DP_LDS = FLEX_DP_LDS && VALU_AGG && !SUM;
+            // with a full last batch the fourth component of an entry (the constant 1) is not needed as a weight:
+            // it carries the byte offset of the NEXT batch's row instead, which saves that batch's id permutes
+            constexpr bool ID_LDS = DP_LDS && !TAIL;
+            int idc[ID_LDS ? 1 : U];
+            if constexpr (ID_LDS) {
+                if ((threadIdx.x & 3) == 3) {
+                    dpe[0] = (int)((unsigned)idn[0] * (4u * row_stride()));
+                    dpe[1] = (int)((unsigned)idn[1] * (4u * row_stride()));
+                }
+            } else {
 #pragma unroll
-            for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
+                for (int u = 0; u < U; ++u) idc[u] = spread(idn, perm_id, u);
+            }
             if constexpr (!SUM) load_pos(pn, pc, idn, x1);
             advance(walk);
             const Batch x2 = get(walk);
@@ -732,7 +755,6 @@ struct LeanProducer {
             const char *rb = reinterpret_cast<const char *>(rows + (int64_t)x1.b * N * row_stride());
             const int nb = x1.b, nlw0 = x1.lw0;
             x1 = x2;
-            constexpr bool DP_LDS = FLEX_DP_LDS && VALU_AGG && !SUM;
             float dpc[DP_LDS ? 1 : U];
             v4f dpv[DP_LDS ? 3 : 1];
             if constexpr (DP_LDS) {
@@ -800,7 +822,12 @@ struct LeanProducer {
                         fma_row<S>(acc, dpc[u], fv);
                     }
                 }
-                if (!TAIL || u < 4 || next_upper) load_row(f[u], idc[u], rb);     // row u of batch m+1 takes the freed registers
+                // row u of batch m+1 takes the freed registers
+                if constexpr (ID_LDS) {
+                    load_row_at(f[u], __float_as_uint(dpv[u % 3][3]), rb);
+                } else {
+                    if (!TAIL || u < 4 || next_upper) load_row(f[u], idc[u], rb);
+                }
                 __builtin_amdgcn_sched_barrier(0);   // keep this shape: one row consumed, one requested
             }
 
@@ -1206,23 +1233,41 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
         const char *sA = s_A + (k & 1) * (G::T * G::ROWB);
         const int *sE = s_E + (k & 1) * G::T;
 
-        // items one after the other; three independent accumulation chains each: hi*hi, lo*hi, hi*lo
+        // The wave's items advance together, one 32-deep step at a time: the fragments of all items for a step
+        // are requested at once (one LDS round trip per step instead of one per item and step) and the next
+        // step's are requested as soon as the matrix ops that read the registers have been issued.  Two
+        // accumulation chains per item: hi*hi and the two cross terms lo*hi + hi*lo.
+        v4f accA[G::IPW], accB[G::IPW];
+        h8 bh[G::IPW], bl[G::IPW];
 #pragma unroll
         for (int it = 0; it < G::IPW; ++it) {
-            v4f acc[3];
+            accA[it] = v4f{0.f, 0.f, 0.f, 0.f};
+            accB[it] = v4f{0.f, 0.f, 0.f, 0.f};
+            bh[it] = *reinterpret_cast<const h8 *>(sA + a_off[it]);
+            bl[it] = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP);
+        }
 #pragma unroll
-            for (int c = 0; c < 3; ++c) acc[c] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < KS2; ++s) {
 #pragma unroll
-            for (int s = 0; s < KS2; ++s) {
-                const h8 bh = *reinterpret_cast<const h8 *>(sA + a_off[it] + 64 * s);
-                const h8 bl = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP + 64 * s);
-                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bh, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[s], bh, acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl, acc[2], 0, 0, 0);
+            for (int it = 0; it < G::IPW; ++it)
+                accA[it] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bh[it], accA[it], 0, 0, 0);
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it)
+                accB[it] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[s], bh[it], accB[it], 0, 0, 0);
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it) {
+                if (s + 1 < KS2) bh[it] = *reinterpret_cast<const h8 *>(sA + a_off[it] + 64 * (s + 1));
+                accB[it] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl[it], accB[it], 0, 0, 0);
             }
+#pragma unroll
+            for (int it = 0; it < G::IPW; ++it)
+                if (s + 1 < KS2) bl[it] = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP + 64 * (s + 1));
+        }
+#pragma unroll
+        for (int it = 0; it < G::IPW; ++it) {
             const int idx = active ? cw + it * G::NC : 0;
             const int e_pt = sE[(idx / G::NS) * 16 + r16];
-            v4f d = acc[0] + (acc[1] + acc[2]);
+            v4f d = accA[it] + accB[it];
 #pragma unroll
             for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], -(e_pt + e_col[i]));   // undo both scalings
             store_item(r, it, d, ORD ? s_P + (k & 1) * G::T : nullptr);
