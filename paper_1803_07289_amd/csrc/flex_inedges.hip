@@ -244,12 +244,20 @@ __global__ __launch_bounds__(256) void inedge_order_kernel(const int32_t *__rest
             len[r] = min(off[g + 1] - off[g], ORDER_BUCKETS - 1);
         }
         rank[r] = 0;
-        if (chunk < ORDER_CHUNKS) {                             // wave-uniform
-            for (int d = 0; d < ORDER_BUCKETS; ++d) {
-                const uint64_t m = __ballot(len[r] == d);
-                if (len[r] == d) rank[r] = __popcll(m & lt);
-                if (lane == 0) s_cnt[d * ORDER_CHUNKS + chunk] = __popcll(m);
-            }
+    }
+    for (int i = threadIdx.x; i < ORDER_BUCKETS * ORDER_CHUNKS; i += 256) s_cnt[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < ORDER_ROUNDS; ++r) {
+        const int chunk = r * 4 + wave;
+        // one round per length that occurs in the chunk (about ten of the 32)
+        uint64_t todo = __ballot(len[r] >= 0);
+        while (todo) {
+            const int d = __shfl(len[r], __ffsll((long long)todo) - 1, 64);     // wave-uniform
+            const uint64_t m = __ballot(len[r] == d);
+            if (len[r] == d) rank[r] = __popcll(m & lt);
+            if (lane == 0) s_cnt[d * ORDER_CHUNKS + chunk] = __popcll(m);
+            todo &= ~m;
         }
     }
     __syncthreads();
@@ -270,11 +278,15 @@ __global__ __launch_bounds__(256) void inedge_order_kernel(const int32_t *__rest
         for (int i = 0; i < PER; ++i) { s_cnt[lane * PER + i] = run; run += v[i]; }
     }
     __syncthreads();
+    // every point's place, through LDS so that the window leaves as one contiguous write
+    __shared__ int s_ord[ORDER_WINDOW];
 #pragma unroll
     for (int r = 0; r < ORDER_ROUNDS; ++r) {
         const int chunk = r * 4 + wave, i = chunk * 64 + lane;
-        if (i < n) order[(int64_t)b * N + p0 + s_cnt[len[r] * ORDER_CHUNKS + chunk] + rank[r]] = p0 + i;
+        if (i < n) s_ord[s_cnt[len[r] * ORDER_CHUNKS + chunk] + rank[r]] = p0 + i;
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += 256) order[(int64_t)b * N + p0 + i] = s_ord[i];
 }
 
 size_t inedges_order_bytes(int64_t BN) { return align256(sizeof(int32_t) * (size_t)BN); }

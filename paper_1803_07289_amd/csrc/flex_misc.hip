@@ -94,20 +94,41 @@ struct ThetaView {
 
 constexpr int PACK_MAX_KD = 512, PACK_MAX_CP = 128;
 
-// one workgroup of 1024 threads packs one matrix (KD = 4*RP <= PACK_MAX_KD rows, CP <= PACK_MAX_CP columns)
+// one workgroup of 1024 threads packs one matrix (KD = 4*RP <= PACK_MAX_KD rows, CP <= PACK_MAX_CP columns).
+// Every thread keeps its share of the matrix in registers, taken in the order of the fragment buffer it will
+// write (element i = tid + 1024 * j), so the parameters are read once; the row / column maxima are maxima of
+// non-negative floats taken as integers with LDS atomics.
 __device__ __forceinline__ void pack_theta_f16_block(const ThetaView &v, _Float16 *__restrict__ thetaF, int CP,
                                                      int exp_offset_bytes, int rscale_offset_bytes, int *s_er,
                                                      int *s_ec)
 {
+    constexpr int MAXE = PACK_MAX_KD * PACK_MAX_CP / 1024;      // elements per thread at the largest shape
     const int KD = 4 * v.RP, KDP = (KD + 31) / 32 * 32, KS = KDP / 32, NS = CP / 16;
-    // largest magnitude of every row, then (rows scaled) of every column: maxima of non-negative floats taken as
-    // integers with LDS atomics, all threads sharing the elements
+    const int per_part = NS * KS * 64 * 8;                      // = KDP * CP, a multiple of 512
+    const int n_mine = (per_part - (int)threadIdx.x + 1023) / 1024;   // elements tid, tid + 1024, ...
+    float x[MAXE];
     for (int i = threadIdx.x; i < KDP; i += 1024) s_er[i] = 0;
     for (int i = threadIdx.x; i < CP; i += 1024) s_ec[i] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < KD * CP; i += 1024) {
-        const float a = fabsf(v.at(i / CP, i % CP));
-        if (a > 0.f && a < __builtin_inff()) atomicMax(&s_er[i / CP], __float_as_int(a));
+    // fragment element i = ((slice * KS + step) * 64 + lane) * 8 + e holds (kd, col) = (32 step + 8 (lane >> 4) + e,
+    // 16 slice + (lane & 15)); i = tid + 1024 j walks (slice, step) two steps at a time from tid >> 9
+    const int kd_lo = 8 * (((int)threadIdx.x >> 7) & 3) + ((int)threadIdx.x & 7), col_lo = ((int)threadIdx.x >> 3) & 15;
+    struct Walk {
+        int step, slice, KS;
+        __device__ __forceinline__ void next() { step += 2; while (step >= KS) { step -= KS; ++slice; } }
+    };
+    auto start = [&]() { Walk w{(int)threadIdx.x >> 9, 0, KS}; while (w.step >= KS) { w.step -= KS; ++w.slice; } return w; };
+    {
+        Walk w = start();
+#pragma unroll
+        for (int j = 0; j < MAXE; ++j) {
+            if (j >= n_mine) break;
+            const int kd = 32 * w.step + kd_lo, col = 16 * w.slice + col_lo;
+            x[j] = (kd < KD) ? v.at(kd, col) : 0.f;
+            const float a = fabsf(x[j]);
+            if (a > 0.f && a < __builtin_inff()) atomicMax(&s_er[kd], __float_as_int(a));
+            w.next();
+        }
     }
     __syncthreads();
     for (int kd = threadIdx.x; kd < KDP; kd += 1024) {
@@ -119,9 +140,16 @@ __device__ __forceinline__ void pack_theta_f16_block(const ThetaView &v, _Float1
         reinterpret_cast<float *>(reinterpret_cast<char *>(thetaF) + rscale_offset_bytes)[kd] = ldexpf(1.f, -er);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < KD * CP; i += 1024) {
-        const float a = fabsf(ldexpf(v.at(i / CP, i % CP), s_er[i / CP]));
-        if (a > 0.f && a < __builtin_inff()) atomicMax(&s_ec[i % CP], __float_as_int(a));
+    {
+        Walk w = start();
+#pragma unroll
+        for (int j = 0; j < MAXE; ++j) {
+            if (j >= n_mine) break;
+            x[j] = ldexpf(x[j], s_er[32 * w.step + kd_lo]);
+            const float a = fabsf(x[j]);
+            if (a > 0.f && a < __builtin_inff()) atomicMax(&s_ec[16 * w.slice + col_lo], __float_as_int(a));
+            w.next();
+        }
     }
     __syncthreads();
     for (int c = threadIdx.x; c < CP; c += 1024) {
@@ -132,15 +160,18 @@ __device__ __forceinline__ void pack_theta_f16_block(const ThetaView &v, _Float1
         reinterpret_cast<int *>(reinterpret_cast<char *>(thetaF) + exp_offset_bytes)[c] = ec;
     }
     __syncthreads();
-    const int per_part = NS * KS * 64 * 8;
-    for (int i = threadIdx.x; i < per_part; i += 1024) {
-        const int e = i & 7, lane = (i >> 3) & 63, step = (i >> 9) % KS, slice = (i >> 9) / KS;
-        const int kd = 32 * step + 8 * (lane >> 4) + e, col = 16 * slice + (lane & 15);
-        const float vs = (kd < KD) ? ldexpf(v.at(kd, col), s_er[kd] + s_ec[col]) : 0.f;
-        const _Float16 hi = (_Float16)vs;
-        const _Float16 lo = (_Float16)(vs - (float)hi);
-        thetaF[i] = hi;
-        thetaF[per_part + i] = lo;
+    {
+        Walk w = start();
+#pragma unroll
+        for (int j = 0; j < MAXE; ++j) {
+            if (j >= n_mine) break;
+            const float vs = ldexpf(x[j], s_ec[16 * w.slice + col_lo]);
+            const _Float16 hi = (_Float16)vs;
+            const _Float16 lo = (_Float16)(vs - (float)hi);
+            thetaF[threadIdx.x + 1024 * j] = hi;
+            thetaF[per_part + threadIdx.x + 1024 * j] = lo;
+            w.next();
+        }
     }
 }
 
