@@ -69,6 +69,17 @@ typedef enum {
  * Computed in fp32 in the factored form (per-point 4*Din aggregate, then a
  * (4*Din x Dout) contraction on the matrix cores).  Any Din, Dout: see
  * flexconv_has_fast_path for how a pair of widths is run.
+ * Accuracy and dynamic range: on the matrix-core routes every fp32 operand of the contraction is
+ * carried as two f16 halves (22 bits) after exact power-of-two scalings: the parameters per
+ * (component, input channel) row and per output channel, a point's aggregate by the same row
+ * scales and by its own largest magnitude.  Result: within 1e-4 of the fp64 value relative to
+ * max(|value|, RMS of the same output channel), also when input channels (with the parameters
+ * compensating) or output channels differ in scale by up to 2^24 (measured about 1e-6).  Not
+ * covered: one input channel whose own values differ by more than 2^24 between the neighbours and
+ * points that meet in one aggregate row; inputs with NaN / Inf.  The same holds for grad_feat of
+ * flexconv_bwd; grad_theta / grad_bias carry their operands exactly (three bf16 pieces) and sum in
+ * fp32.  flexconv_bwd_pos still scales the parameters by ONE power of two for the whole matrix:
+ * channel scales more than about 2^10 apart cost it bits.
  */
 int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
                  const float *theta, const float *bias, float *out,
