@@ -22,6 +22,13 @@ namespace flex {
 #include "flex_shapes.def"
 #undef FLEX_SHAPE
 
+// 64 -> 64 layers: feature and parameter gradients in one pass over the in-edge lists (flex_tiled_inst.hip, shape 64x64)
+bool bwd_fused_ok_64_64(int N, int K);
+hipError_t launch_bwd_fused_64_64(const float *g_rows, const float *own_rows, const float *pos, const int32_t *nbr,
+                                  const int32_t *off, const int32_t *src, const int32_t *order, const void *thetaP,
+                                  float *grad_feat, float *partials, int *overflow, int B, int N, int K, int out_bcn,
+                                  int *n_wg, hipStream_t s);
+
 // 128 -> 128 layers as passes over 64-channel blocks (flex_tiled_inst.hip, shapes 64x128 and 64x64)
 bool split_ok_128_128(int N, int K, int csr);
 hipError_t launch_gc_split_128_128(const float *rows_half, const float *pos, const int32_t *nbr, const int32_t *off,
@@ -316,7 +323,8 @@ struct FwdPlan {
 };
 struct BwdPlan {
     bool tiled, wide;
-    size_t thetaP, featT, gT, gfT, partials, order, in_off, in_src, inedge_ws, total;
+    bool fused;      // feature and parameter gradients, when both are asked for, come from the one-pass kernel
+    size_t thetaP, featT, gT, gfT, partials, order, flag, in_off, in_src, inedge_ws, total;
 };
 
 // The route (block passes of the wide path / single-pass tiled kernels / direct form) is decided here, once, from
@@ -355,6 +363,8 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
         p.partials = at;
         at += p.wide ? wide_partial_bytes((int)B, (int)N, Din, Dout) : grad_theta_partial_bytes(B, N, Din, Dout);
         p.order = at; at += inedges_order_bytes(B * N);      // walking order of the feature gradient's gather
+        p.fused = p.tiled && !p.wide && Din == 64 && Dout == 64 && bwd_fused_ok_64_64((int)N, K);
+        if (p.fused) { p.flag = at; at += 256; }             // the one-pass kernel's overflow flag
         if (build) {
             p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
             p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
@@ -774,6 +784,26 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
             FLEX_HIP(launch_bcn_to_bnc(feat, featT, B, Din, N, s));
             rows = featT;
         }
+    }
+    if (p.fused && grad_theta && grad_feat) {
+        if (build) {
+            int32_t *off = (int32_t *)(ws + p.in_off), *src = (int32_t *)(ws + p.in_src);
+            FLEX_HIP(launch_inedges_build(nbr, B, N, K, off, src, ws + p.inedge_ws, s));
+            in_off = off;
+            in_src = src;
+        }
+        void *thetaP = ws + p.thetaP;
+        int32_t *order = (int32_t *)(ws + p.order);
+        int *flag = (int *)(ws + p.flag);
+        float *partials = (float *)(ws + p.partials);
+        FLEX_HIP(launch_inedges_order(in_off, B, N, order, s));
+        FLEX_HIP(launch_fill_zero(flag, 256, s));
+        FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 1, 1, s));
+        int n_wg = 0;
+        FLEX_HIP(launch_bwd_fused_64_64(g_rows, rows, pos, nbr, in_off, in_src, order, thetaP, grad_feat, partials,
+                                        flag, B, N, K, bcn, &n_wg, s));
+        FLEX_HIP(launch_reduce_partials(partials, n_wg, pad4(Din), pad16(Dout), Din, Dout, grad_theta, grad_bias, s));
+        return FLEX_OK;
     }
     if (grad_theta) {
         if (use_split_128(Din, Dout, layout, N, K, 0))

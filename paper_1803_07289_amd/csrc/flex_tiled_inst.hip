@@ -209,6 +209,51 @@ hipError_t FLEX_NAME(launch_gt, FLEX_DI, FLEX_DO)(const float *rows, const float
     return hipGetLastError();
 }
 
+#if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 64
+// The 64 -> 64 layer's feature gradient and parameter gradients as one pass over the in-edge lists
+// (bwd_fused_lean_kernel), followed by the stand-alone parameter-gradient kernel in its run-if-flagged form.
+// Taken when both of those would run their lean kernels anyway (FLEX_FUSED_BWD=0 in the environment keeps the
+// two separate kernels, for comparisons).
+bool bwd_fused_ok_64_64(int N, int K)
+{
+    static const bool off = [] { const char *v = getenv("FLEX_FUSED_BWD"); return v != nullptr && v[0] == '0'; }();
+    return !off && !contract_in_fp32() && lean_fixed_ok(N, K) && gc_route(N, K, 1, 1) == 3;
+}
+
+// g_rows / own_rows: upstream gradient and features, point-major; partials: *n_wg blocks of [4*64 x 64];
+// overflow: one int the caller has zeroed on the stream.
+hipError_t launch_bwd_fused_64_64(const float *g_rows, const float *own_rows, const float *pos, const int32_t *nbr,
+                                  const int32_t *off, const int32_t *src, const int32_t *order, const void *thetaP,
+                                  float *grad_feat, float *partials, int *overflow, int B, int N, int K, int out_bcn,
+                                  int *n_wg, hipStream_t s)
+{
+    using F = FusedGeom<S>;
+    using WL = WsGeom<S, 2, 2>;
+    static_assert(WL::T == F::G::T, "the fall-back kernel leaves one partial per workgroup of the same grid");
+    if (!bwd_fused_ok_64_64(N, K)) return hipErrorInvalidValue;
+    const int tpc = (N + F::G::T - 1) / F::G::T;
+    const int64_t tot64 = (int64_t)B * tpc;
+    if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
+    const int tot = (int)tot64;
+    *n_wg = persistent_grid(tot, 1);
+    const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
+    const dim3 g(*n_wg);
+#define FLEX_FUSED_ARGS g_rows, own_rows, pos, off, src, order, thetaP, exp_off, grad_feat, partials, overflow, N, tpc, tot
+    if (out_bcn) hipLaunchKernelGGL((bwd_fused_lean_kernel<S, true>), g, dim3(F::NT), 0, s, FLEX_FUSED_ARGS);
+    else hipLaunchKernelGGL((bwd_fused_lean_kernel<S, false>), g, dim3(F::NT), 0, s, FLEX_FUSED_ARGS);
+#undef FLEX_FUSED_ARGS
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (K % 8 == 0)
+        hipLaunchKernelGGL((grad_theta_lean_if_kernel<S, false>), g, dim3(WL::NT), 0, s, overflow, own_rows, pos, nbr,
+                           g_rows, partials, N, K, tpc, tot);
+    else
+        hipLaunchKernelGGL((grad_theta_lean_if_kernel<S, true>), g, dim3(WL::NT), 0, s, overflow, own_rows, pos, nbr,
+                           g_rows, partials, N, K, tpc, tot);
+    return hipGetLastError();
+}
+#endif
+
 #if FLEX_WS && FLEX_DI == 64 && FLEX_DO == 128
 // 128 -> 128 layers as two passes of this shape's lean kernels: each gathers one 64-channel half of the
 // 128-wide rows (row stride 128) and contracts it with its [4*64 x 128] block of the parameters; the second

@@ -110,11 +110,18 @@ __device__ __forceinline__ void load_row_scales(float (&rs)[S::VEC][4], const vo
         }
 }
 
-template <class S>
+// The swizzled form of the split-half tile (SWZ): rows exactly 4*KDP bytes apart and, inside every 128-byte block
+// of a row, the 16-byte chunk index XORed with tile_swizzle(row).  Both ways the tile is read are then free of
+// bank conflicts: 16-byte fragments of 8 consecutive rows at one column (the contraction with the parameters) and
+// 32-byte runs of 4 consecutive rows (the transposing reads of the contraction over the tile's points).
+__device__ __forceinline__ int tile_swizzle(int row) { return (2 * (row & 3) + ((row >> 2) & 1)) << 4; }
+
+template <class S, bool SWZ = false>
 __device__ __forceinline__ void store_split_rows(const v4f (&acc_in)[S::VEC], const float (&rs)[S::VEC][4], char *sA,
                                                  int *sE, int pt, int t, bool writer)
 {
     using G = WsGeom<S>;   // row format only: the same for every producer multiple
+    static_assert(!SWZ || (S::VEC == 4 && (2 * S::DIP) % 128 == 0 && G::KDP == S::KD), "swizzle inside 128-byte blocks");
     v4f acc[S::VEC];
     float m = 0.f;
 #pragma unroll
@@ -128,7 +135,7 @@ __device__ __forceinline__ void store_split_rows(const v4f (&acc_in)[S::VEC], co
     const int e = 15 - __builtin_amdgcn_frexp_expf(m);
     if (writer) {
         if (t == 0) sE[pt] = e;
-        char *row = sA + pt * G::ARS + 2 * S::VEC * t;
+        char *row = SWZ ? sA + pt * (4 * G::KDP) + ((2 * S::VEC * t) ^ tile_swizzle(pt)) : sA + pt * G::ARS + 2 * S::VEC * t;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             if constexpr (S::VEC == 4) {
@@ -1154,11 +1161,19 @@ struct LeanCsrProducer {
 // OS = floats between consecutive output rows (point-major form; 0: the run-time value os_rt), ACC (or the
 // run-time flag acc_rt): add to what out holds.
 // ORD: tile slot pt holds the point s_P[pt] (the producers walk the cloud in a given order), not position l0 + pt.
-template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false, bool ORD = false>
+// NBUF: tile buffers the producers cycle through (tile k sits in buffer k % NBUF).
+// hook.begin(k, kb, b) runs right after tile k's barrier (kb = its buffer, b = its cloud), hook.end(k) after the
+// wave's stores of tile k: extra per-tile work a kernel hangs on its consumer waves.
+struct NoTileHook {
+    __device__ __forceinline__ void begin(int, int, int) {}
+    __device__ __forceinline__ void end(int) {}
+};
+template <class S, class G, bool OUT_BCN, int OS = S::DO, bool ACC = false, bool ORD = false, int NBUF = 2,
+          class Hook = NoTileHook, bool SWZ = false>
 __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ thetaP, int theta_exp_off,
                                              float *__restrict__ out, int N, const TileSchedule &sc,
                                              int tiles_per_cloud, const char *s_A, const int *s_E, int os_rt = 0,
-                                             bool acc_rt = false, const int *s_P = nullptr)
+                                             bool acc_rt = false, const int *s_P = nullptr, Hook hook = Hook())
 {
     const int os = OS != 0 ? OS : os_rt;
     const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
@@ -1218,20 +1233,33 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
         for (int i = 0; i < 4; ++i) e_col[i] = ec[slice * 16 + 4 * q + i];
     }
 
+    constexpr int RSTR = SWZ ? 4 * G::KDP : G::ARS;                    // bytes between tile rows
+    constexpr int BUFB = SWZ ? G::T * 4 * G::KDP : G::T * G::ROWB;     // bytes per tile buffer
     int a_off[G::IPW];                // byte offset of this lane's 16-byte fragment (hi part, step 0)
+    int a_odd[G::IPW];                // SWZ: the same for step 1 minus 64 (the XOR reaches into bit 6)
 #pragma unroll
     for (int it = 0; it < G::IPW; ++it) {
         const int idx = active ? cw + it * G::NC : 0;
-        a_off[it] = ((idx / G::NS) * 16 + r16) * G::ARS + 16 * q;
+        const int row = (idx / G::NS) * 16 + r16;
+        if constexpr (SWZ) {
+            a_off[it] = row * RSTR + ((16 * q) ^ tile_swizzle(row));
+            a_odd[it] = row * RSTR + ((16 * q + 64) ^ tile_swizzle(row)) - 64;
+        } else {
+            a_off[it] = row * RSTR + 16 * q;
+            a_odd[it] = a_off[it];
+        }
     }
+    auto frag_off = [&](int it, int st) { return ((SWZ && (st & 1)) ? a_odd[it] : a_off[it]) + 64 * st; };
 
     TileWalk tw(sc, tiles_per_cloud);
-    for (int k = 0; tw.valid(); ++k, tw.next()) {
+    int kb = 0;                       // k % NBUF
+    for (int k = 0; tw.valid(); ++k, tw.next(), kb = (kb + 1 == NBUF) ? 0 : kb + 1) {
         const TileRef r{true, tw.b, tw.tic * G::T};
-        __syncthreads();              // tile k is complete in buffer k&1
-        if (!active) continue;
-        const char *sA = s_A + (k & 1) * (G::T * G::ROWB);
-        const int *sE = s_E + (k & 1) * G::T;
+        __syncthreads();              // tile k is complete in buffer kb
+        hook.begin(k, kb, tw.b);
+        if (!active) { hook.end(k); continue; }
+        const char *sA = s_A + kb * BUFB;
+        const int *sE = s_E + kb * G::T;
 
         // The wave's items advance together, one 32-deep step at a time: the fragments of all items for a step
         // are requested at once (one LDS round trip per step instead of one per item and step) and the next
@@ -1243,8 +1271,8 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
         for (int it = 0; it < G::IPW; ++it) {
             accA[it] = v4f{0.f, 0.f, 0.f, 0.f};
             accB[it] = v4f{0.f, 0.f, 0.f, 0.f};
-            bh[it] = *reinterpret_cast<const h8 *>(sA + a_off[it]);
-            bl[it] = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP);
+            bh[it] = *reinterpret_cast<const h8 *>(sA + frag_off(it, 0));
+            bl[it] = *reinterpret_cast<const h8 *>(sA + frag_off(it, 0) + 2 * G::KDP);
         }
 #pragma unroll
         for (int s = 0; s < KS2; ++s) {
@@ -1256,12 +1284,12 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
                 accB[it] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thL[s], bh[it], accB[it], 0, 0, 0);
 #pragma unroll
             for (int it = 0; it < G::IPW; ++it) {
-                if (s + 1 < KS2) bh[it] = *reinterpret_cast<const h8 *>(sA + a_off[it] + 64 * (s + 1));
+                if (s + 1 < KS2) bh[it] = *reinterpret_cast<const h8 *>(sA + frag_off(it, s + 1));
                 accB[it] = __builtin_amdgcn_mfma_f32_16x16x32_f16(thH[s], bl[it], accB[it], 0, 0, 0);
             }
 #pragma unroll
             for (int it = 0; it < G::IPW; ++it)
-                if (s + 1 < KS2) bl[it] = *reinterpret_cast<const h8 *>(sA + a_off[it] + 2 * G::KDP + 64 * (s + 1));
+                if (s + 1 < KS2) bl[it] = *reinterpret_cast<const h8 *>(sA + frag_off(it, s + 1) + 2 * G::KDP);
         }
 #pragma unroll
         for (int it = 0; it < G::IPW; ++it) {
@@ -1270,8 +1298,9 @@ __device__ __forceinline__ void consumer_f16(int cw, const void *__restrict__ th
             v4f d = accA[it] + accB[it];
 #pragma unroll
             for (int i = 0; i < 4; ++i) d[i] = __builtin_ldexpf(d[i], -(e_pt + e_col[i]));   // undo both scalings
-            store_item(r, it, d, ORD ? s_P + (k & 1) * G::T : nullptr);
+            store_item(r, it, d, ORD ? s_P + kb * G::T : nullptr);
         }
+        hook.end(k);
     }
 }
 
@@ -1922,6 +1951,323 @@ void grad_theta_lean_blocks_kernel(const float *__restrict__ rows, const float *
     grad_theta_lean_body<S, 0, 0, TAIL>(rows + S::DI * hi, pos, nbr, g_rows + S::DO * ho,
                                         partials + (int64_t)blockIdx.x * S::KD * S::DOP, N, K, tiles_per_cloud,
                                         TileSchedule(total_tiles, q, chunks), rs, gst);
+}
+
+// ---------------------------------------------------------------------------
+// Feature gradient and parameter gradients of a layer in ONE pass over the in-edge lists.
+// With Bagg[m, (j,o)] = sum over the centres l that list m of dp_j(l,m) * grad_out[l,o] (dp_3 = 1), the aggregate
+// the feature gradient contracts with Theta^T, the parameter gradients are
+//   grad_theta[j,c,o] (j < 3), grad_bias[c,o] (j = 3)  =  sum_m Bagg[m, (j,o)] * feat[m, c]:
+// regrouping the sum over edges (l, k) by the listed point m instead of by the centre l.  feat[m,:] is the
+// point's OWN row (no gather), so the second gather pass of a separate parameter-gradient kernel disappears.
+//
+// Workgroup = 8 in-edge producer waves (32-point tiles, split-half f16 aggregate tile in LDS, exactly as for
+// grad_feat_lean_kernel), 4 waves contracting the tile with Theta^T (consumer_f16) and 4 waves ("T waves", wave j
+// owns component j) contracting it over the tile's 32 points with the points' own rows, all on
+// v_mfma_f32_16x16x32_f16.  The tile rows are scaled per point (2^e_m), which a sum over points cannot factor out,
+// so the own rows carry the inverse: own'[m,c] = feat[m,c] * 2^(cs_c + E - e_m), split into f16 halves like the
+// tile.  E is the running minimum of e_m over the workgroup's tiles so far (this tile included: the factor
+// 2^(E - e_m) is <= 1 and points with small aggregates just contribute small terms); when E drops, the T waves
+// rescale their accumulators.  cs_c puts channel c's magnitude near 2^7: it comes from the largest |feat[.,c]| among
+// 256 rows sampled across the workgroup's tiles at kernel start.  A row that exceeds the sampled maximum by more than
+// 2^8 would overflow f16: the kernel then raises *overflow and the host side runs the stand-alone parameter-gradient
+// kernel, which checks that flag (results stay correct, that call is slower).
+// Pipeline: producers fill tile k+1 while the Theta^T waves contract tile k and the T waves fetch and split the own
+// rows of tile k (ids and exponents are known only once the tile is complete) and contract tile k-1; hence three
+// tile buffers and one trailing barrier.  The matrix op accumulates with round-toward-zero, so the T waves add their
+// accumulators to the workgroup's partial in global memory (each lane its own elements, so no ordering issue) every
+// FLUSH tiles.  Partial layout = that of grad_theta_lean_kernel: [(j, c)][o], one per workgroup.
+// S = (gathered width = the layer's Dout, output width = the layer's Din).
+// ---------------------------------------------------------------------------
+template <class S>
+struct FusedGeom {
+    using G = WsGeom<S, 2, 1>;
+    static constexpr int NTW = 4;                       // T waves
+    static constexpr int NT = 64 * (G::NP + G::NC + NTW);
+    static constexpr int NBUF = 3;
+    static constexpr int FS = 4 * S::DO + 32;           // own' row: [hi: DO halves][lo: DO halves], = 32 mod 128 bytes
+    static constexpr int ARS = 4 * G::KDP;              // aggregate tile rows, swizzled form
+    static constexpr int RB = S::DI / 16, CB = S::DO / 16;
+    static constexpr int FLUSH = 16;
+    static constexpr int LPO = S::DO / 4;               // lanes per own row
+    static_assert(S::DI == 64 && S::DO == 64 && S::VEC == 4 && S::LPR == 16, "64 -> 64 layers");
+    static_assert(G::NP == 8 && G::NC == 4 && G::T == 32 && NT == 1024 && G::KDP == S::KD, "wave roles");
+};
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+template <int CTRL>
+__device__ __forceinline__ int dpp_movi(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+// minimum over each half of the wave (lanes 0..31 / 32..63), in every lane
+__device__ __forceinline__ int wave_min32(int v)
+{
+    v = min(v, dpp_movi<0xB1>(v));      // quad_perm [1,0,3,2]
+    v = min(v, dpp_movi<0x4E>(v));      // quad_perm [2,3,0,1]
+    v = min(v, dpp_movi<0x141>(v));     // row_half_mirror
+    v = min(v, dpp_movi<0x140>(v));     // row_mirror
+    return min(v, __shfl_xor(v, 16));
+}
+
+__device__ __forceinline__ h8 read_tr_frag_h(const char *tile, int stride, int p0, int byte_col0, int j16)
+{
+    return __builtin_bit_cast(h8, read_tr_frag(tile, stride, p0, byte_col0, j16));
+}
+// the same from a swizzled tile (store_split_rows<S, true>); byte_col0 a multiple of 32
+__device__ __forceinline__ h8 read_tr_frag_swz(const char *tile, int stride, int p0, int byte_col0, int j16)
+{
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+    const int row = p0 + (j16 >> 2), in_row = byte_col0 + 8 * (j16 & 3);
+    const char *a0 = tile + row * stride + (in_row ^ tile_swizzle(row));
+    const char *a1 = tile + (row + 4) * stride + (in_row ^ tile_swizzle(row + 4));
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(__attribute__((address_space(3))) char *)a0);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(__attribute__((address_space(3))) char *)a1);
+    const v8s v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(h8, v);
+}
+
+template <class S, bool OUT_BCN>
+__global__ __launch_bounds__((FusedGeom<S>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__restrict__ own_rows,
+                           const float *__restrict__ pos, const int32_t *__restrict__ off,
+                           const int32_t *__restrict__ src, const int32_t *__restrict__ order,
+                           const void *__restrict__ thetaP, int theta_exp_off, float *__restrict__ grad_feat,
+                           float *__restrict__ partials, int *__restrict__ overflow, int N, int tiles_per_cloud,
+                           int total_tiles)
+{
+    using F = FusedGeom<S>;
+    using G = typename F::G;
+    __shared__ __attribute__((aligned(128))) char s_A[F::NBUF * G::T * F::ARS];
+    __shared__ __attribute__((aligned(16))) char s_F[2 * G::T * F::FS];
+    __shared__ int s_E[F::NBUF * G::T];
+    __shared__ int s_P[F::NBUF * G::T];
+    __shared__ __attribute__((aligned(16))) float s_D[G::NP][128];
+    __shared__ __attribute__((aligned(16))) int s_cs[S::DO];
+
+    const TileSchedule sc(total_tiles);
+    const int w = threadIdx.x >> 6;
+    const bool any = sc.first < sc.end;
+    const int count = any ? (sc.end - sc.first + sc.step - 1) / sc.step : 0;
+
+    // ---- channel exponents of the own rows from a sample of the workgroup's region ----
+    for (int i = threadIdx.x; i < S::DO; i += F::NT) s_cs[i] = 0;
+    __syncthreads();
+    if (any) {
+        constexpr int RPP = F::NT / F::LPO;               // rows per pass
+        const int qw = threadIdx.x / F::LPO, t = threadIdx.x % F::LPO;
+        v4f m = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int si = 0; si < 4; ++si) {
+            const int idx = 4 * qw + si;
+            const int tile = sc.first + sc.step * (int)(((int64_t)idx * count) / (4 * RPP));
+            const int b = tile / tiles_per_cloud;
+            const int p = min((tile - b * tiles_per_cloud) * G::T + (idx % G::T), N - 1);
+            const v4f x = *reinterpret_cast<const v4f *>(own_rows + ((int64_t)b * N + p) * S::DO + 4 * t);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) m[v] = fmaxf(m[v], __builtin_fabsf(x[v]));
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) atomicMax(&s_cs[4 * t + v], __float_as_int(m[v]));   // non-negative floats order as ints
+    }
+    __syncthreads();
+    int csv = 0;
+    if (threadIdx.x < S::DO) {
+        const float mx = __int_as_float(s_cs[threadIdx.x]);
+        if (mx > 0.f && mx < __builtin_inff()) csv = 7 - __builtin_amdgcn_frexp_expf(mx);
+    }
+    __syncthreads();
+    if (threadIdx.x < S::DO) s_cs[threadIdx.x] = csv;
+    __syncthreads();
+
+    if (w < G::NP) {
+        LeanCsrProducer<S, 2, false, S::DI, true> P;
+        P.init(g_rows, pos, off, src, N, w, sc, tiles_per_cloud);
+        P.order = order;
+        P.set_dp_stage(s_D[w]);
+        float rsc[S::VEC][4];
+        load_row_scales<S>(rsc, thetaP, theta_exp_off, P.t);
+        const bool id_writer = (threadIdx.x & 0x33) == 0;
+        int buf = 0;
+        P.run([&](const v4f (&acc)[S::VEC], int, int, int, int pid) {
+            store_split_rows<S, true>(acc, rsc, s_A + buf * (G::T * F::ARS), s_E + buf * G::T, P.pw * G::PW + P.grp,
+                                      P.t, P.grp < G::PW && (S::VEC * P.t) < S::DIP);
+            if (id_writer) s_P[buf * G::T + P.pw * G::PW + P.e_g] = pid;
+            buf = (buf + 1 == F::NBUF) ? 0 : buf + 1;
+        });
+        if (any) __syncthreads();         // the T waves' last contraction
+        return;
+    }
+    if (w < G::NP + G::NC) {
+        // These waves also bring in the own rows: wave cw those of tile slots 8 cw .. 8 cw + 7, requested when the tile
+        // is complete (ids and exponents known), scaled, split and parked for the T waves after the wave's own items.
+        struct OwnRows {
+            const float *own_rows; const int *s_P, *s_E, *s_cs; char *s_F; int *overflow;
+            int N, cw, lane;
+            int E_run = 1 << 20;
+            v4f x0, x1;
+            int sh0, sh1;
+            __device__ __forceinline__ void begin(int, int kb, int b)
+            {
+                const int slot = 8 * cw + (lane >> 4), r16 = lane & 15;
+                const int p0 = s_P[kb * G::T + slot], p1 = s_P[kb * G::T + slot + 4];
+                const float *ob = own_rows + (int64_t)b * N * S::DO + 4 * r16;
+                x0 = *reinterpret_cast<const v4f *>(ob + (int64_t)p0 * S::DO);
+                x1 = *reinterpret_cast<const v4f *>(ob + (int64_t)p1 * S::DO);
+                E_run = min(E_run, wave_min32(s_E[kb * G::T + (lane & 31)]));
+                sh0 = E_run - s_E[kb * G::T + slot];
+                sh1 = E_run - s_E[kb * G::T + slot + 4];
+            }
+            __device__ __forceinline__ void park(int fb, int slot, v4f x, int sh) const
+            {
+                const int r16 = lane & 15;
+                const v4i ce = *reinterpret_cast<const v4i *>(s_cs + 4 * r16);
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                float m = 0.f;
+                h2 h[2], l[2];
+#pragma unroll
+                for (int p2 = 0; p2 < 2; ++p2) {
+                    const f2 y = {__builtin_ldexpf(x[2 * p2], ce[2 * p2] + sh),
+                                  __builtin_ldexpf(x[2 * p2 + 1], ce[2 * p2 + 1] + sh)};
+                    m = fmax3_abs(m, y[0], y[1]);
+                    h[p2] = __builtin_convertvector(y, h2);
+                    const f2 back = __builtin_convertvector(h[p2], f2);
+                    l[p2] = __builtin_convertvector(y - back, h2);
+                }
+                if (!(m < 65504.f)) *overflow = 1;      // also a NaN: the stand-alone kernel takes over
+                char *row = s_F + (fb * G::T + slot) * F::FS + 8 * r16;
+                *reinterpret_cast<h4 *>(row) = h4{h[0][0], h[0][1], h[1][0], h[1][1]};
+                *reinterpret_cast<h4 *>(row + 2 * S::DO) = h4{l[0][0], l[0][1], l[1][0], l[1][1]};
+            }
+            __device__ __forceinline__ void end(int k)
+            {
+                const int slot = 8 * cw + (lane >> 4);
+                park(k & 1, slot, x0, sh0);
+                park(k & 1, slot + 4, x1, sh1);
+            }
+        };
+        OwnRows hook;
+        hook.own_rows = own_rows; hook.s_P = s_P; hook.s_E = s_E; hook.s_cs = s_cs; hook.s_F = s_F;
+        hook.overflow = overflow; hook.N = N; hook.cw = w - G::NP; hook.lane = threadIdx.x & 63;
+        consumer_f16<S, G, OUT_BCN, S::DO, false, true, F::NBUF, OwnRows &, true>(w - G::NP, thetaP, theta_exp_off,
+                                                                                  grad_feat, N, sc, tiles_per_cloud,
+                                                                                  s_A, s_E, 0, false, s_P, hook);
+        if (any) __syncthreads();
+        return;
+    }
+
+    // ---- T waves ----
+    const int j = w - G::NP - G::NC;
+    const int lane = threadIdx.x & 63, q = lane >> 4, r16 = lane & 15;
+    float *partial = partials + (int64_t)blockIdx.x * (4 * S::DO) * S::DI;
+    const float *rscale = reinterpret_cast<const float *>(reinterpret_cast<const char *>(thetaP) + theta_exp_off +
+                                                          rup_c(4 * S::DOP, 256));
+    v4f acc[F::RB][F::CB];
+#pragma unroll
+    for (int rb = 0; rb < F::RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < F::CB; ++cb) acc[rb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
+    int E_run = 1 << 20, E_acc = 0, E_prev = 0, since = 0;
+    bool fresh = true, have_prev = false;
+
+    auto flush = [&]() __attribute__((always_inline)) {
+        // addresses are formed here, every time: sixteen of them kept across the tile loop would cost registers
+        float *pl = partial + (int64_t)(j * S::DO + r16) * S::DI + 4 * q;
+        const float *rl = rscale + j * S::DIP + 4 * q;
+        asm volatile("" : "+v"(pl), "+v"(rl));
+#pragma unroll
+        for (int cb = 0; cb < F::CB; ++cb) {
+            const int c = 16 * cb + r16;
+            const int ce = s_cs[c];
+#pragma unroll
+            for (int rb = 0; rb < F::RB; ++rb) {
+                const v4f rs = *reinterpret_cast<const v4f *>(rl + 16 * rb);
+                v4f val;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)     // rs = 2^k exactly: frexp exponent = k + 1
+                    val[i] = __builtin_ldexpf(acc[rb][cb][i], -(E_acc + ce + __builtin_amdgcn_frexp_expf(rs[i]) - 1));
+                float *dst = pl + 16 * cb * S::DI + 16 * rb;
+                if (have_prev) val += *reinterpret_cast<const v4f *>(dst);
+                *reinterpret_cast<v4f *>(dst) = val;
+                acc[rb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        have_prev = true; fresh = true; since = 0;
+    };
+    // contraction of the tile in buffer kbp with the own' rows in buffer fb, which carry the scale 2^E_t
+    auto mma_tile = [&](int kbp, int fb, int E_t) __attribute__((always_inline)) {
+        if (fresh) { E_acc = E_t; fresh = false; }
+        else if (E_t != E_acc) {
+            const int d = E_t - E_acc;      // < 0: the running minimum only falls
+#pragma unroll
+            for (int rb = 0; rb < F::RB; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < F::CB; ++cb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[rb][cb][i] = __builtin_ldexpf(acc[rb][cb][i], d);
+            E_acc = E_t;
+        }
+        const char *sA = s_A + kbp * (G::T * F::ARS), *sF = s_F + fb * (G::T * F::FS);
+        // two passes over the tile's row blocks, so that only one half (hi, then lo) of the own' fragments is held
+        {
+            h8 fh[F::CB];
+#pragma unroll
+            for (int cb = 0; cb < F::CB; ++cb) fh[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * 16 * cb, r16);
+#pragma unroll
+            for (int rb = 0; rb < F::RB; ++rb) {
+                const int col = 2 * (S::DIP * j + 16 * rb);
+                const h8 bl = read_tr_frag_swz(sA, F::ARS, 8 * q, col + 2 * G::KDP, r16);
+                const h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * q, col, r16);
+#pragma unroll
+                for (int cb = 0; cb < F::CB; ++cb)     // small terms first
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bl, fh[cb], acc[rb][cb], 0, 0, 0);
+#pragma unroll
+                for (int cb = 0; cb < F::CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bh, fh[cb], acc[rb][cb], 0, 0, 0);
+            }
+        }
+        {
+            h8 fl[F::CB];
+#pragma unroll
+            for (int cb = 0; cb < F::CB; ++cb) fl[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * S::DO + 2 * 16 * cb, r16);
+#pragma unroll
+            for (int rb = 0; rb < F::RB; ++rb) {
+                const h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * q, 2 * (S::DIP * j + 16 * rb), r16);
+#pragma unroll
+                for (int cb = 0; cb < F::CB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bh, fl[cb], acc[rb][cb], 0, 0, 0);
+            }
+        }
+        if (++since == F::FLUSH) flush();
+    };
+    // iteration k: contraction of tile k-1, whose own' rows the other consumer waves parked during iteration k-1 with
+    // the scale 2^E (E = the running minimum of the tile exponents through tile k-1, recomputed here the same way)
+    int kb = 0, kb_prev = 0;
+    for (int k = 0; any && k <= count; ++k) {
+        __syncthreads();                  // tile k is complete in buffer kb (k = count: only the own' rows of the last tile)
+        if (k > 0) mma_tile(kb_prev, (k - 1) & 1, E_prev);
+        if (k < count) {
+            E_run = min(E_run, wave_min32(s_E[kb * G::T + (lane & 31)]));
+            E_prev = E_run;
+            kb_prev = kb;
+            kb = (kb + 1 == F::NBUF) ? 0 : kb + 1;
+        }
+    }
+    if (!fresh || !have_prev) flush();    // a workgroup without tiles still writes its (zero) partial
+}
+
+// The stand-alone parameter-gradient kernel as the fused kernel's fall-back: runs only if *overflow is set.
+template <class S, bool TAIL>
+__global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void grad_theta_lean_if_kernel(const int *__restrict__ overflow, const float *__restrict__ rows,
+                               const float *__restrict__ pos, const int32_t *__restrict__ nbr,
+                               const float *__restrict__ g_rows, float *__restrict__ partials, int N, int K,
+                               int tiles_per_cloud, int total_tiles)
+{
+    if (*overflow == 0) return;
+    grad_theta_lean_body<S, S::DI, S::DO, TAIL>(rows, pos, nbr, g_rows, partials + (int64_t)blockIdx.x * S::KD * S::DOP,
+                                                N, K, tiles_per_cloud, TileSchedule(total_tiles), 0, 0);
 }
 
 // ---------------------------------------------------------------------------

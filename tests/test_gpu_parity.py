@@ -119,8 +119,14 @@ def test_flexconv_bwd_partial_outputs_and_prebuilt_inedges():
     assert none_t is None and none_b is None and none_f is None
     assert rel_err(from_layout(gf, fx.BNC), rgf) <= TOL and rel_err(gt.cpu().numpy(), rgt) <= TOL
     assert torch.equal(gf, gf2)                      # gather form: bit-reproducible
-    assert torch.equal(gt, gt2) and torch.equal(gb, gb2)
+    # the parameter gradients alone come from their own kernel, together with the feature gradient from the
+    # one-pass kernel: two routes, each held to the oracle, and each bit-reproducible from call to call
+    assert rel_err(gt2.cpu().numpy(), rgt) <= TOL and rel_err(gb2.cpu().numpy(), rgb) <= TOL
     assert rel_err(gb.cpu().numpy(), rgb) <= TOL
+    gf3, gt3, gb3 = fx.flexconv_bwd(*args, in_edges=edges, **d)
+    _, gt4, gb4 = fx.flexconv_bwd(*args, need_feat=False, **d)
+    assert torch.equal(gf, gf3) and torch.equal(gt, gt3) and torch.equal(gb, gb3)
+    assert torch.equal(gt2, gt4) and torch.equal(gb2, gb4)
 
 
 def test_inedges_are_the_transposed_graph():
