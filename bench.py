@@ -67,7 +67,8 @@ def main():
     ap.add_argument("--order", default="morton", choices=["morton", "generator", "shuffled"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default=None,
-                    help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; upsample = flex-upsampling from a "
+                    help="comma list of ops to run (fwd,bwd,pool_fwd,pool_bwd; bwd_params / bwd_feat = flexconv_bwd asked "
+                         "for the parameter gradients / the feature gradient alone; upsample = flex-upsampling from a "
                          "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
                          "quarter of the points, idiss = importance sub-sampling of a quarter of the points, knn = the "
                          "neighbour search; none of them is part of the default step)")
@@ -133,8 +134,8 @@ def main():
 
     names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos", "pool_sub") if n in ops]
     state = {}
-    OPS = ("fwd", "bwd_params", "bwd_feat", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
-           "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn")
+    OPS = ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
+           "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn", "bwd_params", "bwd_feat")
     if "idiss" in ops:
         # random words for the stratified draw of a quarter of the points (Sec. 3.2), drawn once
         u_words = torch.from_numpy(np.random.default_rng([cfg.seed, 400]).integers(
@@ -150,55 +151,61 @@ def main():
         sub_edges = fx.flex_inedges_build_sub(nbr, sel) if "pool_sub" in ops else None
 
     def step(events=None):
-        """One pass of the hot path.  flexconv_bwd is issued as two calls (parameter gradients,
-        then feature gradient: the same kernels as one call) so that each gets its own events."""
-        def mark(i):
+        """One pass of the hot path: flexconv_fwd, flexconv_bwd (all three gradients, one call), flexpool_fwd,
+        flexpool_bwd; then whatever --only added."""
+        slot = [0]
+
+        def mark():
             if events is not None:
-                events[i].record()
-        mark(0)
+                events[slot[0]].record()
+            slot[0] += 1
+        mark()
         if "fwd" in ops:
             state["out"] = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=layout, out=state.get("out"))
-        mark(1)
+        mark()
         if "bwd" in ops:
-            _, gt, gb = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
-                                        need_feat=False)
-        mark(2)
-        if "bwd" in ops:
-            gf, _, _ = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
-                                       need_params=False)
-            state["grads"] = (gf, gt, gb)
-        mark(3)
+            state["grads"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges)
+        mark()
         if "pool_fwd" in ops or "pool_bwd" in ops:
             state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
-        mark(4)
+        mark()
         if "pool_bwd" in ops:
             state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
-        mark(5)
+        mark()
         if "upsample" in ops:
             state["up"] = fx.flexupsample_fwd(feat_small, sel, nbr, layout=layout)
-        mark(6)
+        mark()
         if "upsample" in ops:
             state["up_grad"] = fx.flexupsample_bwd(gpool, state["up"][1], sel, in_edges, layout=layout)
-        mark(7)
+        mark()
         if "bwd_pos" in ops:
             state["grad_pos"] = fx.flexconv_bwd_pos(feat, nbr, theta, g, layout=layout, in_edges=in_edges)
-        mark(8)
+        mark()
         if "pool_sub" in ops:
             state["pool_sub"] = fx.flexpool_sub_fwd(feat, nbr, sel, layout=layout)
-        mark(9)
+        mark()
         if "pool_sub" in ops:
             state["pool_sub_grad"] = fx.flexpool_sub_bwd(g_small, state["pool_sub"][1], N, layout=layout,
                                                          in_edges=sub_edges)
-        mark(10)
+        mark()
         if "idiss" in ops:
             state["phi"] = fx.flex_idiss_phi(pos, nbr)
-        mark(11)
+        mark()
         if "idiss" in ops:
             state["sel"] = fx.flex_selection_make_distinct(fx.flex_idiss_sample(state["phi"], u_words), N)
-        mark(12)
+        mark()
         if "knn" in ops:
             state["knn"] = fx.flex_knn(pos, K)
-        mark(13)
+        mark()
+        # the two halves of flexconv_bwd as calls of their own (each runs its stand-alone kernel)
+        if "bwd_params" in ops:
+            state["gp"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
+                                          need_feat=False)
+        mark()
+        if "bwd_feat" in ops:
+            state["gfeat"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
+                                             need_params=False)
+        mark()
 
     # ---- measured peaks of this device: plain copy kernel, pure f16 matrix-op loop ----------
     measured_peaks = None
@@ -235,7 +242,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(14)] for _ in range(args.steps)]
+    per_step_events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(OPS) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -255,9 +262,18 @@ def main():
     # split form (3 resp. 6 matrix ops per fp32-equivalent product), whose time at the published dense
     # peak (2.5 PFLOP/s) stays below the time the touched-once bytes need at 8 TB/s.
     conv_flop_pt = 8 * K * Din + 2 * 4 * Din * Dout          # factored form, fp32-equivalent
+    route_bwd = fx.kernel_route(fx.OP_CONV_BWD, B, N, K, Din, Dout, layout)
+    fused_bwd = route_bwd == 7          # FLEX_ROUTE_LEAN_FUSED: one pass over the in-edge lists for all gradients
     issued_matrix_flop_pt = {"fwd": 3 * 2 * 4 * Din * Dout, "bwd_params": 6 * 2 * 4 * Din * Dout,
-                             "bwd_feat": 3 * 2 * 4 * Din * Dout}
+                             "bwd_feat": 3 * 2 * 4 * Din * Dout,
+                             "bwd": (3 + 3 if fused_bwd else 6 + 3) * 2 * 4 * Din * Dout}
+    fp32_flop_pt = {"fwd": conv_flop_pt, "bwd_params": conv_flop_pt, "bwd_feat": conv_flop_pt,
+                    # one aggregate and two contractions when fused, else two of each
+                    "bwd": (8 * K * Dout + 2 * 2 * 4 * Din * Dout) if fused_bwd else 2 * conv_flop_pt}
     bytes_pt = {"fwd": 4 * Din + 12 + 4 * K + 4 * Dout,
+                # every array of the call touched once: features, upstream gradient, feature gradient, positions,
+                # in-edge lists (fused: the neighbour tensor is not read; separate kernels: it is, + 4 K)
+                "bwd": 4 * Din + 4 * Dout + 4 * Din + 12 + 4 * (K + 1) + (0 if fused_bwd else 4 * K),
                 "bwd_params": 4 * Din + 12 + 4 * K + 4 * Dout,
                 "bwd_feat": 4 * Dout + 12 + 4 * (K + 1) + 4 * Din,
                 "pool_fwd": 4 * Din + 4 * K + 8 * Din,
@@ -274,6 +290,8 @@ def main():
                 "pool_sub_fwd": 4 * Din + K + 1 + 2 * Din,
                 "pool_sub_bwd": 2 * Din + (K + 4) + 4 * Din}
     kernel_of = {"fwd": "gather_contract_lean_kernel (flexconv_fwd)",
+                 "bwd": ("bwd_fused_lean_kernel (flexconv_bwd: feature and parameter gradients in one pass)" if fused_bwd
+                         else "grad_theta kernel + grad_feat kernel (flexconv_bwd)"),
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
@@ -300,7 +318,7 @@ def main():
         if measured_peaks:
             r["frac_of_measured_peak"] = gbs / measured_peaks["copy_GBs"]
         if name in issued_matrix_flop_pt:
-            r["fp32_equivalent_TFLOPs"] = conv_flop_pt * pts / (ms * 1e-3) / 1e12
+            r["fp32_equivalent_TFLOPs"] = fp32_flop_pt[name] * pts / (ms * 1e-3) / 1e12
             r["issued_matrix_TFLOPs"] = issued_matrix_flop_pt[name] * pts / (ms * 1e-3) / 1e12
             r["issued_matrix_frac_of_f16_peak"] = r["issued_matrix_TFLOPs"] / MFMA_F16_PEAK_TFLOPS
             if measured_peaks:
@@ -311,7 +329,7 @@ def main():
     dominant = max(rooflines, key=lambda n: rooflines[n]["kernel_ms"]) if rooflines else None
     roofline = rooflines.get(dominant)
     fwd_ms = op_ms["fwd"]["mean"]
-    bwd_ms = op_ms["bwd_params"]["mean"] + op_ms["bwd_feat"]["mean"]
+    bwd_ms = op_ms["bwd"]["mean"]
 
     # ---- sampled parity at this size, in this launch configuration -------------
     parity = None

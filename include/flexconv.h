@@ -353,7 +353,10 @@ typedef enum {
     FLEX_ROUTE_LEAN = 3,       /* wave-specialised kernels with lean producers (the headline path) */
     FLEX_ROUTE_SPLIT128 = 4,   /* 128 -> 128 point-major as two passes of the 64-wide lean kernels */
     FLEX_ROUTE_WIDE = 5,       /* block passes over 64- / 128-channel column blocks */
-    FLEX_ROUTE_PADDED = 6      /* zero-padded to the nearest widths with a matrix-core path */
+    FLEX_ROUTE_PADDED = 6,     /* zero-padded to the nearest widths with a matrix-core path */
+    FLEX_ROUTE_LEAN_FUSED = 7  /* flexconv_bwd only: lean kernels, and when grad_feat and grad_theta / grad_bias are
+                                  all asked for, ONE kernel makes one pass over the in-edge lists for all of them
+                                  (64 -> 64 layers); a call for a subset runs the FLEX_ROUTE_LEAN kernels */
 } flex_route;
 int flexconv_kernel_route(int op, int B, int N, int K, int Din, int Dout, int layout);
 

@@ -555,6 +555,7 @@ int flexconv_kernel_route(int op, int B, int N, int K, int Din, int Dout, int la
     if (p.wide) return FLEX_ROUTE_WIDE;
     if (!p.tiled) return FLEX_ROUTE_DIRECT;
     if (use_split_128(Din, Dout, layout, N, K, 1)) return FLEX_ROUTE_SPLIT128;
+    if (p.fused) return FLEX_ROUTE_LEAN_FUSED;
     return gather_contract_route(Dout, Din, N, K, 1);
 }
 

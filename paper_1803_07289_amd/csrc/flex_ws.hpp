@@ -2209,35 +2209,39 @@ void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__rest
             E_acc = E_t;
         }
         const char *sA = s_A + kbp * (G::T * F::ARS), *sF = s_F + fb * (G::T * F::FS);
-        // two passes over the tile's row blocks, so that only one half (hi, then lo) of the own' fragments is held
-        {
-            h8 fh[F::CB];
+        // the fragment addresses (one per row block and half, because of the swizzle) are formed anew for every
+        // tile: a few integer ops, where sixteen loop-invariant registers would not fit beside the accumulators
+        int r16v = r16;
+        asm volatile("" : "+v"(r16v));
+        // the next row block's fragments are requested before the current one's matrix ops are issued, so the wave
+        // waits for LDS once per tile and not once per row block
+        h8 fh[F::CB], fl[F::CB];
 #pragma unroll
-            for (int cb = 0; cb < F::CB; ++cb) fh[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * 16 * cb, r16);
+        for (int cb = 0; cb < F::CB; ++cb) fh[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * 16 * cb, r16v);
+        h8 bl = read_tr_frag_swz(sA, F::ARS, 8 * q, 2 * (S::DIP * j) + 2 * G::KDP, r16v);
+        h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * q, 2 * (S::DIP * j), r16v);
 #pragma unroll
-            for (int rb = 0; rb < F::RB; ++rb) {
-                const int col = 2 * (S::DIP * j + 16 * rb);
-                const h8 bl = read_tr_frag_swz(sA, F::ARS, 8 * q, col + 2 * G::KDP, r16);
-                const h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * q, col, r16);
+        for (int cb = 0; cb < F::CB; ++cb) fl[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * S::DO + 2 * 16 * cb, r16v);
 #pragma unroll
-                for (int cb = 0; cb < F::CB; ++cb)     // small terms first
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bl, fh[cb], acc[rb][cb], 0, 0, 0);
-#pragma unroll
-                for (int cb = 0; cb < F::CB; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bh, fh[cb], acc[rb][cb], 0, 0, 0);
+        for (int rb = 0; rb < F::RB; ++rb) {
+            h8 bl_n = bl, bh_n = bh;
+            if (rb + 1 < F::RB) {
+                const int col = 2 * (S::DIP * j + 16 * (rb + 1));
+                bl_n = read_tr_frag_swz(sA, F::ARS, 8 * q, col + 2 * G::KDP, r16v);
+                bh_n = read_tr_frag_swz(sA, F::ARS, 8 * q, col, r16v);
             }
-        }
-        {
-            h8 fl[F::CB];
+            __builtin_amdgcn_sched_barrier(0);      // keep the requests ahead of the matrix ops
 #pragma unroll
-            for (int cb = 0; cb < F::CB; ++cb) fl[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * S::DO + 2 * 16 * cb, r16);
+            for (int cb = 0; cb < F::CB; ++cb)     // small terms first
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bl, fh[cb], acc[rb][cb], 0, 0, 0);
 #pragma unroll
-            for (int rb = 0; rb < F::RB; ++rb) {
-                const h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * q, 2 * (S::DIP * j + 16 * rb), r16);
+            for (int cb = 0; cb < F::CB; ++cb)
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bh, fl[cb], acc[rb][cb], 0, 0, 0);
 #pragma unroll
-                for (int cb = 0; cb < F::CB; ++cb)
-                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bh, fl[cb], acc[rb][cb], 0, 0, 0);
-            }
+            for (int cb = 0; cb < F::CB; ++cb)
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bh, fh[cb], acc[rb][cb], 0, 0, 0);
+            bl = bl_n; bh = bh_n;
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (++since == F::FLUSH) flush();
     };

@@ -176,7 +176,7 @@ def _query(env_extra, calls):
     return json.loads(r.stdout.strip().splitlines()[-1])
 
 
-ROUTE_SINGLE, ROUTE_STAGED, ROUTE_LEAN, ROUTE_SPLIT128, ROUTE_WIDE, ROUTE_PADDED = 1, 2, 3, 4, 5, 6
+ROUTE_SINGLE, ROUTE_STAGED, ROUTE_LEAN, ROUTE_SPLIT128, ROUTE_WIDE, ROUTE_PADDED, ROUTE_LEAN_FUSED = 1, 2, 3, 4, 5, 6, 7
 
 
 def _align256(x):
@@ -224,16 +224,31 @@ def test_block_passes_stop_where_byte_offsets_leave_32_bits(L):
     assert w_at_bnc >= 256 * 4 * 128 * 128 * 4
 
 
+def test_one_pass_backward_is_planned_only_where_it_runs():
+    # plan and route agree, the switch restores the two separate kernels, the plan holds the flag's 256 bytes
+    N, K = 100_000, 8
+    q = [("flexconv_kernel_route", [1, 1, N, K, 64, 64, 1]), ("flexconv_workspace_bytes", [1, 1, N, K, 64, 64, 1]),
+         ("flexconv_kernel_route", [1, 1, N, K, 64, 64, 0]), ("flexconv_kernel_route", [1, 1, N, K, 32, 32, 1]),
+         ("flexconv_kernel_route", [1, 1, N, 12, 64, 64, 1])]
+    r_on, w_on, r_bcn, r32, r_k12 = _query({}, q)
+    r_off, w_off, _, _, _ = _query({"FLEX_FUSED_BWD": "0"}, q)
+    assert r_on == ROUTE_LEAN_FUSED and r_bcn == ROUTE_LEAN_FUSED and r_k12 == ROUTE_LEAN_FUSED and r32 == ROUTE_LEAN
+    assert r_off == ROUTE_LEAN and w_on == w_off + 256
+    for env in ({"FLEX_CONTRACT": "f32"}, {"FLEX_PRODUCER": "staged"}):
+        assert _query(env, q[:1])[0] != ROUTE_LEAN_FUSED
+
+
 def test_lean_kernels_stop_where_byte_offsets_leave_32_bits(L):
     # the lean producers address rows with 32-bit byte offsets from a per-cloud base: N * width * 4 < 2^32
     route = L.flexconv_kernel_route
     lim64, lim32 = (1 << 32) // (64 * 4), (1 << 32) // (32 * 4)
     for op in (0, 1):
-        assert route(op, 1, lim64 - 1, 8, 64, 64, 1) == ROUTE_LEAN
+        lean64 = ROUTE_LEAN_FUSED if op == 1 else ROUTE_LEAN    # 64 -> 64 backward: one pass for all gradients
+        assert route(op, 1, lim64 - 1, 8, 64, 64, 1) == lean64
         assert route(op, 1, lim64, 8, 64, 64, 1) == ROUTE_STAGED
         assert route(op, 1, lim32 - 1, 8, 32, 32, 1) == ROUTE_LEAN
         assert route(op, 1, lim32, 8, 32, 32, 1) == ROUTE_STAGED
-        assert route(op, 4, lim64 - 1, 8, 64, 64, 1) == ROUTE_LEAN          # the limit is per cloud, not per batch
+        assert route(op, 4, lim64 - 1, 8, 64, 64, 1) == lean64              # the limit is per cloud, not per batch
     # the gathered width decides: forward gathers Din-wide rows, the feature gradient Dout-wide ones
     assert route(0, 1, lim64, 8, 32, 64, 1) == ROUTE_LEAN and route(1, 1, lim64, 8, 32, 64, 1) == ROUTE_STAGED
     assert route(0, 1, lim64, 8, 64, 32, 1) == ROUTE_STAGED and route(1, 1, lim64, 8, 64, 32, 1) == ROUTE_LEAN
