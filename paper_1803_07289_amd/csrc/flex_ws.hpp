@@ -2211,24 +2211,25 @@ void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__rest
         const char *sA = s_A + kbp * (G::T * F::ARS), *sF = s_F + fb * (G::T * F::FS);
         // the fragment addresses (one per row block and half, because of the swizzle) are formed anew for every
         // tile: a few integer ops, where sixteen loop-invariant registers would not fit beside the accumulators
-        int r16v = r16;
-        asm volatile("" : "+v"(r16v));
+        int lanev = threadIdx.x;
+        asm volatile("" : "+v"(lanev));
+        const int r16v = lanev & 15, qv = (lanev >> 4) & 3;
         // the next row block's fragments are requested before the current one's matrix ops are issued, so the wave
         // waits for LDS once per tile and not once per row block
         h8 fh[F::CB], fl[F::CB];
 #pragma unroll
-        for (int cb = 0; cb < F::CB; ++cb) fh[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * 16 * cb, r16v);
-        h8 bl = read_tr_frag_swz(sA, F::ARS, 8 * q, 2 * (S::DIP * j) + 2 * G::KDP, r16v);
-        h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * q, 2 * (S::DIP * j), r16v);
+        for (int cb = 0; cb < F::CB; ++cb) fh[cb] = read_tr_frag_h(sF, F::FS, 8 * qv, 2 * 16 * cb, r16v);
+        h8 bl = read_tr_frag_swz(sA, F::ARS, 8 * qv, 2 * (S::DIP * j) + 2 * G::KDP, r16v);
+        h8 bh = read_tr_frag_swz(sA, F::ARS, 8 * qv, 2 * (S::DIP * j), r16v);
 #pragma unroll
-        for (int cb = 0; cb < F::CB; ++cb) fl[cb] = read_tr_frag_h(sF, F::FS, 8 * q, 2 * S::DO + 2 * 16 * cb, r16v);
+        for (int cb = 0; cb < F::CB; ++cb) fl[cb] = read_tr_frag_h(sF, F::FS, 8 * qv, 2 * S::DO + 2 * 16 * cb, r16v);
 #pragma unroll
         for (int rb = 0; rb < F::RB; ++rb) {
             h8 bl_n = bl, bh_n = bh;
             if (rb + 1 < F::RB) {
                 const int col = 2 * (S::DIP * j + 16 * (rb + 1));
-                bl_n = read_tr_frag_swz(sA, F::ARS, 8 * q, col + 2 * G::KDP, r16v);
-                bh_n = read_tr_frag_swz(sA, F::ARS, 8 * q, col, r16v);
+                bl_n = read_tr_frag_swz(sA, F::ARS, 8 * qv, col + 2 * G::KDP, r16v);
+                bh_n = read_tr_frag_swz(sA, F::ARS, 8 * qv, col, r16v);
             }
             __builtin_amdgcn_sched_barrier(0);      // keep the requests ahead of the matrix ops
 #pragma unroll
@@ -2259,6 +2260,59 @@ void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__rest
         }
     }
     if (!fresh || !have_prev) flush();    // a workgroup without tiles still writes its (zero) partial
+
+    // ---- does the partial stand clear of what the f16 halves can resolve? ----
+    // Whatever the scales, a term of the sum is off by at most 2^-25 (half the smallest f16 step) times its tile
+    // entry (< 2^15), i.e. 2^-10 in the units of the accumulators; the running exponent only falls, so in the units
+    // of the last one, E_run, no term is off by more, and n terms of random sign by about sqrt(n) * 2^-10.  Every row
+    // (j, o) over its channels c and every column (j, c) over its o must have an RMS at least 2^16 times that, or
+    // the workgroup cannot vouch for its share (a result that is small because the points with large features had
+    // tiny aggregates, or the reverse, which the per-channel and per-point scales cannot both follow): the flag
+    // then hands the parameter gradients to the stand-alone kernel.  Rows and columns that are exactly zero (a dead
+    // channel, a channel without gradient) are exact.
+    if (any) {
+        const float need = 262144.f * 32.f * (float)count;        // 64 elements * 2^12 * n
+        float *pl = partial + (int64_t)(j * S::DO + r16) * S::DI + 4 * q;
+        const float *rl = rscale + j * S::DIP + 4 * q;
+        float rowsq[F::RB][4], colsq[F::CB];
+#pragma unroll
+        for (int cb = 0; cb < F::CB; ++cb) colsq[cb] = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < F::RB; ++rb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rowsq[rb][i] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < F::CB; ++cb) {
+            const int ce = s_cs[16 * cb + r16];
+#pragma unroll
+            for (int rb = 0; rb < F::RB; ++rb) {
+                const v4f rs = *reinterpret_cast<const v4f *>(rl + 16 * rb);
+                const v4f p = *reinterpret_cast<const v4f *>(pl + 16 * cb * S::DI + 16 * rb);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = __builtin_ldexpf(p[i], E_prev + ce + __builtin_amdgcn_frexp_expf(rs[i]) - 1);
+                    rowsq[rb][i] = fmaf(v, v, rowsq[rb][i]);
+                    colsq[cb] = fmaf(v, v, colsq[cb]);
+                }
+            }
+        }
+        bool bad = false;
+#pragma unroll
+        for (int rb = 0; rb < F::RB; ++rb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {      // a row's 64 channels: this lane's 4 column blocks, 16 lanes
+                float t = rowsq[rb][i];
+                t += dpp_move<0xB1>(t); t += dpp_move<0x4E>(t); t += dpp_move<0x141>(t); t += dpp_move<0x140>(t);
+                bad |= !(t >= need || t == 0.f);
+            }
+#pragma unroll
+        for (int cb = 0; cb < F::CB; ++cb) {   // a column's 64 rows of this component: 16 in this lane, 4 lane groups
+            float t = colsq[cb];
+            t += __shfl_xor(t, 16); t += __shfl_xor(t, 32);
+            bad |= !(t >= need || t == 0.f);
+        }
+        if (bad) *overflow = 1;
+    }
 }
 
 // The stand-alone parameter-gradient kernel as the fused kernel's fall-back: runs only if *overflow is set.

@@ -1,6 +1,6 @@
 """The kernels that only special sizes reach (LDS-staged producers: byte offsets past 32 bits; fp32 matrix-op
 contraction, single-pass 128-wide kernels and the direct-form kernels for arbitrary widths: kept for comparisons and
-as the last resort) are selected here through the library's
+as the last resort; the separate feature- and parameter-gradient kernels of a full 64 -> 64 backward call) are selected here through the library's
 environment switches, which are read once per process: so each setting runs the parity file once in a child process
 (one at a time)."""
 import os
@@ -14,8 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 @pytest.mark.parametrize("env", [{"FLEX_PRODUCER": "staged"}, {"FLEX_CONTRACT": "f32"}, {"FLEX_SPLIT": "0"},
-                                 {"FLEX_PAD": "0"}],
-                         ids=["staged_producers", "fp32_contraction", "single_pass_128", "direct_form_kernels"])
+                                 {"FLEX_PAD": "0"}, {"FLEX_FUSED_BWD": "0"}],
+                         ids=["staged_producers", "fp32_contraction", "single_pass_128", "direct_form_kernels",
+                              "separate_backward_kernels"])
 def test_parity_file_under_switch(env):
     child_env = dict(os.environ)
     child_env.update(env)
