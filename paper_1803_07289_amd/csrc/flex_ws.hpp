@@ -1988,7 +1988,7 @@ struct FusedGeom {
     static constexpr int FS = 4 * S::DO + 32;           // own' row: [hi: DO halves][lo: DO halves], = 32 mod 128 bytes
     static constexpr int ARS = 4 * G::KDP;              // aggregate tile rows, swizzled form
     static constexpr int RB = S::DI / 16, CB = S::DO / 16;
-    static constexpr int FLUSH = 16;
+    static constexpr int FLUSH = 64;
     static constexpr int LPO = S::DO / 4;               // lanes per own row
     static_assert(S::DI == 64 && S::DO == 64 && S::VEC == 4 && S::LPR == 16, "64 -> 64 layers");
     static_assert(G::NP == 8 && G::NC == 4 && G::T == 32 && NT == 1024 && G::KDP == S::KD, "wave roles");
@@ -2176,20 +2176,28 @@ void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__rest
         float *pl = partial + (int64_t)(j * S::DO + r16) * S::DI + 4 * q;
         const float *rl = rscale + j * S::DIP + 4 * q;
         asm volatile("" : "+v"(pl), "+v"(rl));
+        int re[F::RB][4];                         // rs = 2^k exactly: frexp exponent = k + 1
+#pragma unroll
+        for (int rb = 0; rb < F::RB; ++rb) {
+            const v4f rs = *reinterpret_cast<const v4f *>(rl + 16 * rb);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) re[rb][i] = __builtin_amdgcn_frexp_expf(rs[i]) - 1;
+        }
 #pragma unroll
         for (int cb = 0; cb < F::CB; ++cb) {
-            const int c = 16 * cb + r16;
-            const int ce = s_cs[c];
+            const int ce = s_cs[16 * cb + r16];
+            // a column block's four reads go out together: one round trip to memory, not four
+            v4f old[F::RB];
+#pragma unroll
+            for (int rb = 0; rb < F::RB; ++rb)
+                old[rb] = have_prev ? *reinterpret_cast<const v4f *>(pl + 16 * cb * S::DI + 16 * rb) : v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int rb = 0; rb < F::RB; ++rb) {
-                const v4f rs = *reinterpret_cast<const v4f *>(rl + 16 * rb);
                 v4f val;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)     // rs = 2^k exactly: frexp exponent = k + 1
-                    val[i] = __builtin_ldexpf(acc[rb][cb][i], -(E_acc + ce + __builtin_amdgcn_frexp_expf(rs[i]) - 1));
-                float *dst = pl + 16 * cb * S::DI + 16 * rb;
-                if (have_prev) val += *reinterpret_cast<const v4f *>(dst);
-                *reinterpret_cast<v4f *>(dst) = val;
+                for (int i = 0; i < 4; ++i)
+                    val[i] = __builtin_ldexpf(acc[rb][cb][i], -(E_acc + ce + re[rb][i])) + old[rb][i];
+                *reinterpret_cast<v4f *>(pl + 16 * cb * S::DI + 16 * rb) = val;
                 acc[rb][cb] = v4f{0.f, 0.f, 0.f, 0.f};
             }
         }
