@@ -26,8 +26,11 @@ namespace flex {
 bool bwd_fused_ok_64_64(int N, int K);
 hipError_t launch_bwd_fused_64_64(const float *g_rows, const float *own_rows, const float *pos, const int32_t *nbr,
                                   const int32_t *off, const int32_t *src, const int32_t *order, const void *thetaP,
-                                  float *grad_feat, float *partials, int *overflow, int B, int N, int K, int out_bcn,
+                                  float *grad_feat, float *partials, int *control, int B, int N, int K, int out_bcn,
                                   int *n_wg, hipStream_t s);
+hipError_t launch_bwd_fused_late_64_64(const float *g_rows, const float *own_rows, const float *pos,
+                                       const int32_t *nbr, float *partials, const int *control, int B, int N, int K,
+                                       hipStream_t s);
 
 // 128 -> 128 layers as passes over 64-channel blocks (flex_tiled_inst.hip, shapes 64x128 and 64x64)
 bool split_ok_128_128(int N, int K, int csr);
@@ -364,7 +367,7 @@ static BwdPlan plan_bwd(int64_t B, int64_t N, int K, int Din, int Dout, int layo
         at += p.wide ? wide_partial_bytes((int)B, (int)N, Din, Dout) : grad_theta_partial_bytes(B, N, Din, Dout);
         p.order = at; at += inedges_order_bytes(B * N);      // walking order of the feature gradient's gather
         p.fused = p.tiled && !p.wide && Din == 64 && Dout == 64 && bwd_fused_ok_64_64((int)N, K);
-        if (p.fused) { p.flag = at; at += 256; }             // the one-pass kernel's overflow flag
+        if (p.fused) { p.flag = at; at += align256(fused_control_bytes()); }   // the one-pass kernel's flag and records
         if (build) {
             p.in_off = at;    at += align256(sizeof(int32_t) * (size_t)(B * N + 1));
             p.in_src = at;    at += align256(sizeof(int32_t) * (size_t)(B * N) * K);
@@ -798,12 +801,20 @@ int flexconv_bwd(const float *feat, const float *pos, const int32_t *nbr, const 
         int *flag = (int *)(ws + p.flag);
         float *partials = (float *)(ws + p.partials);
         FLEX_HIP(launch_inedges_order(in_off, B, N, order, s));
-        FLEX_HIP(launch_fill_zero(flag, 256, s));
+        FLEX_HIP(launch_fill_zero(flag, sizeof(int) * FUSED_FLAG_INTS, s));
         FLEX_HIP(pack_for_contract(theta, bias, thetaP, Din, Dout, 1, 1, s));
         int n_wg = 0;
         FLEX_HIP(launch_bwd_fused_64_64(g_rows, rows, pos, nbr, in_off, in_src, order, thetaP, grad_feat, partials,
                                         flag, B, N, K, bcn, &n_wg, s));
         FLEX_HIP(launch_reduce_partials(partials, n_wg, pad4(Din), pad16(Dout), Din, Dout, grad_theta, grad_bias, s));
+        // is the result resolved by the f16 halves?  if not (decided on the device), the stand-alone kernel and a
+        // second reduction run; both return at once otherwise
+        const float *rscale = reinterpret_cast<const float *>(reinterpret_cast<const char *>(thetaP) +
+                                                              theta_f16_rscale_offset(pad4(Dout), pad16(Din)));
+        FLEX_HIP(launch_fused_bwd_check(flag, n_wg, rscale, grad_theta, grad_bias, s));
+        FLEX_HIP(launch_bwd_fused_late_64_64(g_rows, rows, pos, nbr, partials, flag, B, N, K, s));
+        FLEX_HIP(launch_reduce_partials_if(flag, FUSED_UNRESOLVED, partials, n_wg, pad4(Din), pad16(Dout), Din, Dout,
+                                           grad_theta, grad_bias, s));
         return FLEX_OK;
     }
     if (grad_theta) {

@@ -40,6 +40,19 @@ hipError_t launch_pack_theta_f16(const float *theta, const float *bias, void *th
 size_t theta_f16_exp_offset(int RP, int CP);
 size_t theta_f16_rscale_offset(int RP, int CP);
 size_t theta_f16_bytes(int RP, int CP);
+
+// Control words of the one-pass backward kernel (bwd_fused_lean_kernel) in the workspace: the flag (0: its parameter
+// gradients stand; FUSED_OVERFLOW: a feature row overflowed f16 while the kernel ran; FUSED_UNRESOLVED: the check after
+// the reduction found the result too small for the f16 halves to resolve; either way the stand-alone kernel
+// recomputes them), then one record per workgroup: its last running exponent, its number of terms, its DO channel
+// exponents.
+constexpr int FUSED_FLAG_INTS = 64, FUSED_RECORD_INTS = 128, FUSED_MAX_WG = 1024;
+constexpr int FUSED_OVERFLOW = 1, FUSED_UNRESOLVED = 2;
+constexpr size_t fused_control_bytes() { return sizeof(int) * (size_t)(FUSED_FLAG_INTS + FUSED_RECORD_INTS * FUSED_MAX_WG); }
+hipError_t launch_fused_bwd_check(int *control, int n_wg, const float *rscale, const float *grad_theta,
+                                  const float *grad_bias, hipStream_t s);
+hipError_t launch_reduce_partials_if(const int *flag, int want, const float *partials, int n_wg, int DIP, int DOP,
+                                     int Din, int Dout, float *grad_theta, float *grad_bias, hipStream_t s);
 hipError_t launch_pack_theta_f16_blocks(const float *theta, const float *bias, void *thetaF_all, int Din, int Dout,
                                         int r_blk, int c_blk, int n_i, int n_j, int transpose, hipStream_t s);
 

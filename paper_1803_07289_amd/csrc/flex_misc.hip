@@ -439,6 +439,104 @@ hipError_t launch_reduce_partials_blocks(const float *partials, int n_wg, int fi
     return hipGetLastError();
 }
 
+// The same, run only if *flag == want (the second reduction of the one-pass backward after a late hand-over).
+__global__ void reduce_partials_if_kernel(const int *__restrict__ flag, int want, const float *__restrict__ partials,
+                                          int n_wg, int DIP, int DOP, int Din, int Dout,
+                                          float *__restrict__ grad_theta, float *__restrict__ grad_bias)
+{
+    if (*flag != want) return;
+    __shared__ double red[4][64];
+    const int o = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int part = threadIdx.x >> 6;
+    const int kd = blockIdx.y;
+    const int j = kd / DIP, c = kd % DIP;
+    double sum = 0.0;
+    if (o < DOP) {
+        const int64_t stride = (int64_t)4 * DIP * DOP;
+        const float *p = partials + (int64_t)kd * DOP + o;
+        for (int g = part; g < n_wg; g += 4) sum += (double)p[g * stride];
+    }
+    red[part][threadIdx.x & 63] = sum;
+    __syncthreads();
+    if (part == 0 && o < Dout && c < Din) {
+        const int x = threadIdx.x & 63;
+        const float v = (float)(red[0][x] + red[1][x] + red[2][x] + red[3][x]);
+        if (j < 3) grad_theta[((int64_t)j * Din + c) * Dout + o] = v;
+        else grad_bias[(int64_t)c * Dout + o] = v;
+    }
+}
+
+hipError_t launch_reduce_partials_if(const int *flag, int want, const float *partials, int n_wg, int DIP, int DOP,
+                                     int Din, int Dout, float *grad_theta, float *grad_bias, hipStream_t s)
+{
+    hipLaunchKernelGGL(reduce_partials_if_kernel, dim3((DOP + 63) / 64, 4 * DIP), dim3(256), 0, s, flag, want,
+                       partials, n_wg, DIP, DOP, Din, Dout, grad_theta, grad_bias);
+    return hipGetLastError();
+}
+
+// Do the one-pass backward kernel's parameter gradients (64 -> 64: grad_theta [3,64,64], grad_bias [64,64], already
+// reduced) stand clear of what its f16 halves can resolve?  A term of its sum over points -- tile entry times own'
+// element -- is off by at most 2^-25 (half the smallest f16 step) times the tile entry (< 2^15), i.e. 2^-10 in the
+// units of the workgroup's accumulators, which are 2^-(E + cs_c) / rs_(j,o) true units (E: the workgroup's last
+// running exponent, the smallest it had; cs_c: its channel exponent; rs: the row scale of the packed parameters).
+// Errors of random sign add in quadrature: err^2[(j,c),o] = Q_c / rs_(j,o)^2 with
+// Q_c = sum over workgroups of n_wg * 2^(-20 - 2 (E_wg + cs_wg,c)).  Every row (j,c) over o and every column (j,o)
+// over c of the result must have a sum of squares at least 2^32 times that of its error bound (RMS 2^16 times: a
+// relative error of 1.5e-5, where ordinary data stands some 2^8 clear of the bar); rows and columns that are exactly
+// zero -- a dead channel, a channel without gradient -- are exact and exempt.  Else the flag goes to
+// FUSED_UNRESOLVED and the stand-alone kernel recomputes the parameter gradients.  Does nothing if the flag is set
+// already (those were recomputed before the reduction).  One block of 512 threads, sums in double (the exponents
+// span more than fp32 holds).
+__global__ __launch_bounds__(512) void fused_bwd_check_kernel(int *__restrict__ control, int n_wg,
+                                                              const float *__restrict__ rscale,
+                                                              const float *__restrict__ grad_theta,
+                                                              const float *__restrict__ grad_bias)
+{
+    constexpr int C = 64;
+    __shared__ double s_Q[C];
+    __shared__ double s_Qsum;
+    if (control[0] != 0) return;
+    const int t = threadIdx.x;
+    if (t < C) {
+        double q = 0.0;
+        for (int g = 0; g < n_wg; ++g) {
+            const int *rec = control + FUSED_FLAG_INTS + (int64_t)g * FUSED_RECORD_INTS;
+            const int n = rec[1];
+            if (n > 0) q += __builtin_ldexp((double)n, -20 - 2 * (rec[0] + rec[2 + t]));
+        }
+        s_Q[t] = q;
+    }
+    __syncthreads();
+    if (t == 0) {
+        double a = 0.0;
+        for (int c = 0; c < C; ++c) a += s_Q[c];
+        s_Qsum = a;
+    }
+    __syncthreads();
+    const int j = (t & 255) / C, x = t % C;          // x: the channel c (t < 256) or the output channel o (t >= 256)
+    auto value = [&](int c, int o) -> double {
+        return (double)(j < 3 ? grad_theta[((int64_t)j * C + c) * C + o] : grad_bias[(int64_t)c * C + o]);
+    };
+    auto inv_rs2 = [&](int o) -> double { const double r = (double)rscale[j * C + o]; return 1.0 / (r * r); };
+    double sq = 0.0, bound = 0.0;
+    if (t < 256) {                                   // (j, c = x) over o
+        for (int o = 0; o < C; ++o) { const double v = value(x, o); sq += v * v; bound += inv_rs2(o); }
+        bound *= s_Q[x];
+    } else {                                         // (j, o = x) over c
+        for (int c = 0; c < C; ++c) { const double v = value(c, x); sq += v * v; }
+        bound = inv_rs2(x) * s_Qsum;
+    }
+    if (!(sq == 0.0 || sq >= 4294967296.0 * bound)) control[0] = FUSED_UNRESOLVED;
+}
+
+hipError_t launch_fused_bwd_check(int *control, int n_wg, const float *rscale, const float *grad_theta,
+                                  const float *grad_bias, hipStream_t s)
+{
+    if (n_wg > FUSED_MAX_WG) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fused_bwd_check_kernel, dim3(1), dim3(512), 0, s, control, n_wg, rscale, grad_theta, grad_bias);
+    return hipGetLastError();
+}
+
 hipError_t launch_reduce_partials(const float *partials, int n_wg, int DIP, int DOP, int Din,
                                   int Dout, float *grad_theta, float *grad_bias, hipStream_t s)
 {

@@ -220,11 +220,28 @@ bool bwd_fused_ok_64_64(int N, int K)
     return !off && !contract_in_fp32() && lean_fixed_ok(N, K) && gc_route(N, K, 1, 1) == 3;
 }
 
+// The stand-alone parameter-gradient kernel over the same grid, run on the device only if *control == want.
+static hipError_t launch_gt_if(const int *control, int want, const float *own_rows, const float *pos,
+                               const int32_t *nbr, const float *g_rows, float *partials, int N, int K, int tpc, int tot,
+                               int n_wg, hipStream_t s)
+{
+    using WL = WsGeom<S, 2, 2>;
+    if (K % 8 == 0)
+        hipLaunchKernelGGL((grad_theta_lean_if_kernel<S, false>), dim3(n_wg), dim3(WL::NT), 0, s, control, want,
+                           own_rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
+    else
+        hipLaunchKernelGGL((grad_theta_lean_if_kernel<S, true>), dim3(n_wg), dim3(WL::NT), 0, s, control, want,
+                           own_rows, pos, nbr, g_rows, partials, N, K, tpc, tot);
+    return hipGetLastError();
+}
+
 // g_rows / own_rows: upstream gradient and features, point-major; partials: *n_wg blocks of [4*64 x 64];
-// overflow: one int the caller has zeroed on the stream.
+// control: fused_control_bytes() whose flag word the caller has zeroed on the stream.  Leaves the partials of the
+// parameter gradients (the one-pass kernel's, or the stand-alone kernel's if a row overflowed) and the workgroups'
+// records for the check after the reduction.
 hipError_t launch_bwd_fused_64_64(const float *g_rows, const float *own_rows, const float *pos, const int32_t *nbr,
                                   const int32_t *off, const int32_t *src, const int32_t *order, const void *thetaP,
-                                  float *grad_feat, float *partials, int *overflow, int B, int N, int K, int out_bcn,
+                                  float *grad_feat, float *partials, int *control, int B, int N, int K, int out_bcn,
                                   int *n_wg, hipStream_t s)
 {
     using F = FusedGeom<S>;
@@ -236,21 +253,28 @@ hipError_t launch_bwd_fused_64_64(const float *g_rows, const float *own_rows, co
     if (tot64 > 0x7fffffff) return hipErrorInvalidValue;
     const int tot = (int)tot64;
     *n_wg = persistent_grid(tot, 1);
+    if (*n_wg > FUSED_MAX_WG) return hipErrorInvalidValue;
     const int exp_off = (int)theta_f16_exp_offset(S::DIP, S::DOP);
     const dim3 g(*n_wg);
-#define FLEX_FUSED_ARGS g_rows, own_rows, pos, off, src, order, thetaP, exp_off, grad_feat, partials, overflow, N, tpc, tot
+#define FLEX_FUSED_ARGS g_rows, own_rows, pos, off, src, order, thetaP, exp_off, grad_feat, partials, control, N, tpc, tot
     if (out_bcn) hipLaunchKernelGGL((bwd_fused_lean_kernel<S, true>), g, dim3(F::NT), 0, s, FLEX_FUSED_ARGS);
     else hipLaunchKernelGGL((bwd_fused_lean_kernel<S, false>), g, dim3(F::NT), 0, s, FLEX_FUSED_ARGS);
 #undef FLEX_FUSED_ARGS
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (K % 8 == 0)
-        hipLaunchKernelGGL((grad_theta_lean_if_kernel<S, false>), g, dim3(WL::NT), 0, s, overflow, own_rows, pos, nbr,
-                           g_rows, partials, N, K, tpc, tot);
-    else
-        hipLaunchKernelGGL((grad_theta_lean_if_kernel<S, true>), g, dim3(WL::NT), 0, s, overflow, own_rows, pos, nbr,
-                           g_rows, partials, N, K, tpc, tot);
-    return hipGetLastError();
+    return launch_gt_if(control, FUSED_OVERFLOW, own_rows, pos, nbr, g_rows, partials, N, K, tpc, tot, *n_wg, s);
+}
+
+// The hand-over after the check: the stand-alone kernel again, run only if the check set FUSED_UNRESOLVED.
+hipError_t launch_bwd_fused_late_64_64(const float *g_rows, const float *own_rows, const float *pos,
+                                       const int32_t *nbr, float *partials, const int *control, int B, int N, int K,
+                                       hipStream_t s)
+{
+    using F = FusedGeom<S>;
+    const int tpc = (N + F::G::T - 1) / F::G::T;
+    const int tot = B * tpc;
+    return launch_gt_if(control, FUSED_UNRESOLVED, own_rows, pos, nbr, g_rows, partials, N, K, tpc, tot,
+                        persistent_grid(tot, 1), s);
 }
 #endif
 

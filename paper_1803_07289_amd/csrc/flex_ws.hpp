@@ -1970,11 +1970,14 @@ void grad_theta_lean_blocks_kernel(const float *__restrict__ rows, const float *
 // 2^(E - e_m) is <= 1 and points with small aggregates just contribute small terms); when E drops, the T waves
 // rescale their accumulators.  cs_c puts channel c's magnitude near 2^7: it comes from the largest |feat[.,c]| among
 // 256 rows sampled across the workgroup's tiles at kernel start.  A row that exceeds the sampled maximum by more than
-// 2^8 would overflow f16: the kernel then raises *overflow and the host side runs the stand-alone parameter-gradient
-// kernel, which checks that flag (results stay correct, that call is slower).
-// Pipeline: producers fill tile k+1 while the Theta^T waves contract tile k and the T waves fetch and split the own
-// rows of tile k (ids and exponents are known only once the tile is complete) and contract tile k-1; hence three
-// tile buffers and one trailing barrier.  The matrix op accumulates with round-toward-zero, so the T waves add their
+// 2^8 would overflow f16: the kernel then raises the flag (FUSED_OVERFLOW) and the stand-alone parameter-gradient
+// kernel, launched behind it in its run-if-flagged form, recomputes the partials (results stay correct, that call is
+// slower).  What the halves cannot RESOLVE -- a result far below the product of the largest aggregate and the largest
+// feature -- is judged after the reduction, on the whole result, from the records the workgroups leave
+// (fused_bwd_check_kernel).
+// Pipeline: producers fill tile k+1 while the Theta^T waves contract tile k and fetch, scale and split the own rows
+// of tile k (ids and exponents are known only once the tile is complete) and the T waves contract tile k-1; hence
+// three tile buffers and one trailing barrier.  The matrix op accumulates with round-toward-zero, so the T waves add their
 // accumulators to the workgroup's partial in global memory (each lane its own elements, so no ordering issue) every
 // FLUSH tiles.  Partial layout = that of grad_theta_lean_kernel: [(j, c)][o], one per workgroup.
 // S = (gathered width = the layer's Dout, output width = the layer's Din).
@@ -2135,7 +2138,7 @@ void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__rest
                     const f2 back = __builtin_convertvector(h[p2], f2);
                     l[p2] = __builtin_convertvector(y - back, h2);
                 }
-                if (!(m < 65504.f)) *overflow = 1;      // also a NaN: the stand-alone kernel takes over
+                if (!(m < 65504.f)) *overflow = FUSED_OVERFLOW;      // also a NaN: the stand-alone kernel takes over
                 char *row = s_F + (fb * G::T + slot) * F::FS + 8 * r16;
                 *reinterpret_cast<h4 *>(row) = h4{h[0][0], h[0][1], h[1][0], h[1][1]};
                 *reinterpret_cast<h4 *>(row + 2 * S::DO) = h4{l[0][0], l[0][1], l[1][0], l[1][1]};
@@ -2269,69 +2272,25 @@ void bwd_fused_lean_kernel(const float *__restrict__ g_rows, const float *__rest
     }
     if (!fresh || !have_prev) flush();    // a workgroup without tiles still writes its (zero) partial
 
-    // ---- does the partial stand clear of what the f16 halves can resolve? ----
-    // Whatever the scales, a term of the sum is off by at most 2^-25 (half the smallest f16 step) times its tile
-    // entry (< 2^15), i.e. 2^-10 in the units of the accumulators; the running exponent only falls, so in the units
-    // of the last one, E_run, no term is off by more, and n terms of random sign by about sqrt(n) * 2^-10.  Every row
-    // (j, o) over its channels c and every column (j, c) over its o must have an RMS at least 2^16 times that, or
-    // the workgroup cannot vouch for its share (a result that is small because the points with large features had
-    // tiny aggregates, or the reverse, which the per-channel and per-point scales cannot both follow): the flag
-    // then hands the parameter gradients to the stand-alone kernel.  Rows and columns that are exactly zero (a dead
-    // channel, a channel without gradient) are exact.
-    if (any) {
-        const float need = 262144.f * 32.f * (float)count;        // 64 elements * 2^12 * n
-        float *pl = partial + (int64_t)(j * S::DO + r16) * S::DI + 4 * q;
-        const float *rl = rscale + j * S::DIP + 4 * q;
-        float rowsq[F::RB][4], colsq[F::CB];
-#pragma unroll
-        for (int cb = 0; cb < F::CB; ++cb) colsq[cb] = 0.f;
-#pragma unroll
-        for (int rb = 0; rb < F::RB; ++rb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) rowsq[rb][i] = 0.f;
-#pragma unroll
-        for (int cb = 0; cb < F::CB; ++cb) {
-            const int ce = s_cs[16 * cb + r16];
-#pragma unroll
-            for (int rb = 0; rb < F::RB; ++rb) {
-                const v4f rs = *reinterpret_cast<const v4f *>(rl + 16 * rb);
-                const v4f p = *reinterpret_cast<const v4f *>(pl + 16 * cb * S::DI + 16 * rb);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float v = __builtin_ldexpf(p[i], E_prev + ce + __builtin_amdgcn_frexp_expf(rs[i]) - 1);
-                    rowsq[rb][i] = fmaf(v, v, rowsq[rb][i]);
-                    colsq[cb] = fmaf(v, v, colsq[cb]);
-                }
-            }
-        }
-        bool bad = false;
-#pragma unroll
-        for (int rb = 0; rb < F::RB; ++rb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {      // a row's 64 channels: this lane's 4 column blocks, 16 lanes
-                float t = rowsq[rb][i];
-                t += dpp_move<0xB1>(t); t += dpp_move<0x4E>(t); t += dpp_move<0x141>(t); t += dpp_move<0x140>(t);
-                bad |= !(t >= need || t == 0.f);
-            }
-#pragma unroll
-        for (int cb = 0; cb < F::CB; ++cb) {   // a column's 64 rows of this component: 16 in this lane, 4 lane groups
-            float t = colsq[cb];
-            t += __shfl_xor(t, 16); t += __shfl_xor(t, 32);
-            bad |= !(t >= need || t == 0.f);
-        }
-        if (bad) *overflow = 1;
+    // ---- what the check after the reduction needs from this workgroup (fused_bwd_check_kernel) ----
+    // its last running exponent, its number of terms and its channel exponents: words 0, 1 and 2 .. 2 + DO of its
+    // record, FUSED_RECORD_INTS apart, behind the flag
+    if (j == 0) {
+        int *rec = overflow + FUSED_FLAG_INTS + (int64_t)blockIdx.x * FUSED_RECORD_INTS;
+        if (lane == 0) { rec[0] = E_prev; rec[1] = G::T * count; }
+        if (lane < S::DO) rec[2 + lane] = s_cs[lane];
     }
 }
 
-// The stand-alone parameter-gradient kernel as the fused kernel's fall-back: runs only if *overflow is set.
+// The stand-alone parameter-gradient kernel as the fused kernel's fall-back: runs only if *overflow == want.
 template <class S, bool TAIL>
 __global__ __launch_bounds__((WsGeom<S, 2, 2>::NT)) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void grad_theta_lean_if_kernel(const int *__restrict__ overflow, const float *__restrict__ rows,
+void grad_theta_lean_if_kernel(const int *__restrict__ overflow, int want, const float *__restrict__ rows,
                                const float *__restrict__ pos, const int32_t *__restrict__ nbr,
                                const float *__restrict__ g_rows, float *__restrict__ partials, int N, int K,
                                int tiles_per_cloud, int total_tiles)
 {
-    if (*overflow == 0) return;
+    if (*overflow != want) return;
     grad_theta_lean_body<S, S::DI, S::DO, TAIL>(rows, pos, nbr, g_rows, partials + (int64_t)blockIdx.x * S::KD * S::DOP,
                                                 N, K, tiles_per_cloud, TileSchedule(total_tiles), 0, 0);
 }

@@ -233,7 +233,7 @@ def test_one_pass_backward_is_planned_only_where_it_runs():
     r_on, w_on, r_bcn, r32, r_k12 = _query({}, q)
     r_off, w_off, _, _, _ = _query({"FLEX_FUSED_BWD": "0"}, q)
     assert r_on == ROUTE_LEAN_FUSED and r_bcn == ROUTE_LEAN_FUSED and r_k12 == ROUTE_LEAN_FUSED and r32 == ROUTE_LEAN
-    assert r_off == ROUTE_LEAN and w_on == w_off + 256
+    assert r_off == ROUTE_LEAN and w_on == w_off + 4 * (64 + 128 * 1024)      # flag block + 1024 workgroup records
     for env in ({"FLEX_CONTRACT": "f32"}, {"FLEX_PRODUCER": "staged"}):
         assert _query(env, q[:1])[0] != ROUTE_LEAN_FUSED
 
