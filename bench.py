@@ -348,6 +348,16 @@ def main():
                 den = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)))
                 worst = max(worst, float(np.max(np.abs(got - ref) / den)))
             parity = {"fwd_sampled_max_rel_err": worst, "points": 300 * len(starts)}
+        if "bwd" in ops and "grads" in state and hasattr(oracle, "flexconv_grad_feat_at"):
+            # feature-gradient rows of the timed call at sampled points (the oracle evaluates single rows)
+            targets = np.unique(rng.integers(0, B * N, size=2000)).astype(np.int64)
+            ref = oracle.flexconv_grad_feat_at(x.pos, x.nbr, x.theta, x.bias, x.grad_out, targets)
+            gfeat = state["grads"][0]
+            rows_g = (gfeat.reshape(B * N, Din) if layout == fx.BNC
+                      else gfeat.transpose(1, 2).reshape(B * N, Din))[torch.from_numpy(targets).cuda()].cpu().numpy()
+            den = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)))
+            parity = dict(parity or {}, grad_feat_sampled_max_rel_err=float(np.max(np.abs(rows_g - ref) / den)),
+                          grad_feat_rows=int(targets.size))
 
         # ---- CPU baseline: the oracle on a bounded slice of the same workload ----
         def oracle_pass(l0, l1):

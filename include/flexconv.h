@@ -77,8 +77,13 @@ typedef enum {
  * compensating) or output channels differ in scale by up to 2^24 (measured about 1e-6).  Not
  * covered: one input channel whose own values differ by more than 2^24 between the neighbours and
  * points that meet in one aggregate row; inputs with NaN / Inf.  The same holds for grad_feat of
- * flexconv_bwd; grad_theta / grad_bias carry their operands exactly (three bf16 pieces) and sum in
- * fp32.  flexconv_bwd_pos still scales the parameters by ONE power of two for the whole matrix:
+ * flexconv_bwd.  grad_theta / grad_bias from the stand-alone kernel carry their operands exactly
+ * (three bf16 pieces) and sum in fp32; on the one-pass route (FLEX_ROUTE_LEAN_FUSED) they are
+ * contracted from the same f16 halves, with per-channel and per-point power-of-two scales, and the
+ * call checks on the device whether the halves resolved the result (an overflowing feature row, or a
+ * result more than 2^16 times closer to the representation error than ordinary data ever comes):
+ * if not, the stand-alone kernel recomputes them inside the same call (correct, about 1.7 x the time).
+ * flexconv_bwd_pos still scales the parameters by ONE power of two for the whole matrix:
  * channel scales more than about 2^10 apart cost it bits.
  */
 int flexconv_fwd(const float *feat, const float *pos, const int32_t *nbr,
