@@ -485,25 +485,45 @@ hipError_t launch_reduce_partials_if(const int *flag, int want, const float *par
 // relative error of 1.5e-5, where ordinary data stands some 2^8 clear of the bar); rows and columns that are exactly
 // zero -- a dead channel, a channel without gradient -- are exact and exempt.  Else the flag goes to
 // FUSED_UNRESOLVED and the stand-alone kernel recomputes the parameter gradients.  Does nothing if the flag is set
-// already (those were recomputed before the reduction).  One block of 512 threads, sums in double (the exponents
-// span more than fp32 holds).
-__global__ __launch_bounds__(512) void fused_bwd_check_kernel(int *__restrict__ control, int n_wg,
-                                                              const float *__restrict__ rscale,
-                                                              const float *__restrict__ grad_theta,
-                                                              const float *__restrict__ grad_bias)
+// already (those were recomputed before the reduction).  One block, sums in double (the exponents span more than
+// fp32 holds).
+__global__ __launch_bounds__(1024) void fused_bwd_check_kernel(int *__restrict__ control, int n_wg,
+                                                               const float *__restrict__ rscale,
+                                                               const float *__restrict__ grad_theta,
+                                                               const float *__restrict__ grad_bias)
 {
-    constexpr int C = 64;
-    __shared__ double s_Q[C];
+    constexpr int C = 64, PARTS = 1024 / C;
+    __shared__ __attribute__((aligned(16))) float s_P[4 * C * C];      // the result, [j][c][o]
+    __shared__ double s_Qp[PARTS][C];
+    __shared__ double s_Q[C], s_irs2[4 * C];
     __shared__ double s_Qsum;
     if (control[0] != 0) return;
     const int t = threadIdx.x;
+    // the result into LDS (grad_theta is [3][C][C], grad_bias [C][C]: together [4][C][C])
+    for (int i = t; i < 4 * C * C; i += 1024) s_P[i] = i < 3 * C * C ? grad_theta[i] : grad_bias[i - 3 * C * C];
+    {   // Q_c, the workgroups shared out over PARTS thread groups
+        const int c = t % C, part = t / C;
+        double q = 0.0;
+        constexpr int UN = 8;                        // records requested together
+        for (int g0 = part; g0 < n_wg; g0 += PARTS * UN) {
+            int e[UN], n[UN], ce[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int g = min(g0 + u * PARTS, n_wg - 1);
+                const int *rec = control + FUSED_FLAG_INTS + (int64_t)g * FUSED_RECORD_INTS;
+                e[u] = rec[0]; n[u] = (g0 + u * PARTS < n_wg) ? rec[1] : 0; ce[u] = rec[2 + c];
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+                if (n[u] > 0) q += __builtin_ldexp((double)n[u], -20 - 2 * (e[u] + ce[u]));
+        }
+        s_Qp[part][c] = q;
+    }
+    if (t < 4 * C) s_irs2[t] = __builtin_ldexp(1.0, -2 * (__builtin_amdgcn_frexp_expf(rscale[t]) - 1));   // rs = 2^k exactly
+    __syncthreads();
     if (t < C) {
         double q = 0.0;
-        for (int g = 0; g < n_wg; ++g) {
-            const int *rec = control + FUSED_FLAG_INTS + (int64_t)g * FUSED_RECORD_INTS;
-            const int n = rec[1];
-            if (n > 0) q += __builtin_ldexp((double)n, -20 - 2 * (rec[0] + rec[2 + t]));
-        }
+        for (int p2 = 0; p2 < PARTS; ++p2) q += s_Qp[p2][t];
         s_Q[t] = q;
     }
     __syncthreads();
@@ -513,18 +533,20 @@ __global__ __launch_bounds__(512) void fused_bwd_check_kernel(int *__restrict__ 
         s_Qsum = a;
     }
     __syncthreads();
-    const int j = (t & 255) / C, x = t % C;          // x: the channel c (t < 256) or the output channel o (t >= 256)
-    auto value = [&](int c, int o) -> double {
-        return (double)(j < 3 ? grad_theta[((int64_t)j * C + c) * C + o] : grad_bias[(int64_t)c * C + o]);
-    };
-    auto inv_rs2 = [&](int o) -> double { const double r = (double)rscale[j * C + o]; return 1.0 / (r * r); };
+    if (t >= 2 * 4 * C) return;
+    const int j = (t % (4 * C)) / C, x = t % C;      // x: the channel c (t < 256) or the output channel o (t >= 256)
     double sq = 0.0, bound = 0.0;
-    if (t < 256) {                                   // (j, c = x) over o
-        for (int o = 0; o < C; ++o) { const double v = value(x, o); sq += v * v; bound += inv_rs2(o); }
+    if (t < 4 * C) {                                 // row (j, c = x) over o, started at o = x to spread the LDS banks
+        for (int i = 0; i < C; ++i) {
+            const int o = (i + x) % C;
+            const double v = (double)s_P[(j * C + x) * C + o];
+            sq += v * v;
+            bound += s_irs2[j * C + o];
+        }
         bound *= s_Q[x];
-    } else {                                         // (j, o = x) over c
-        for (int c = 0; c < C; ++c) { const double v = value(c, x); sq += v * v; }
-        bound = inv_rs2(x) * s_Qsum;
+    } else {                                         // column (j, o = x) over c
+        for (int c = 0; c < C; ++c) { const double v = (double)s_P[(j * C + c) * C + x]; sq += v * v; }
+        bound = s_irs2[j * C + x] * s_Qsum;
     }
     if (!(sq == 0.0 || sq >= 4294967296.0 * bound)) control[0] = FUSED_UNRESOLVED;
 }
@@ -533,7 +555,7 @@ hipError_t launch_fused_bwd_check(int *control, int n_wg, const float *rscale, c
                                   const float *grad_bias, hipStream_t s)
 {
     if (n_wg > FUSED_MAX_WG) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fused_bwd_check_kernel, dim3(1), dim3(512), 0, s, control, n_wg, rscale, grad_theta, grad_bias);
+    hipLaunchKernelGGL(fused_bwd_check_kernel, dim3(1), dim3(1024), 0, s, control, n_wg, rscale, grad_theta, grad_bias);
     return hipGetLastError();
 }
 
