@@ -2,6 +2,7 @@
 from fractions import Fraction
 
 import numpy as np
+import pytest
 
 import oracle
 from helpers import grid2d
@@ -68,6 +69,59 @@ def test_sample_matches_exact_integer_reference():
         for seed in range(20):
             u = np.random.default_rng(seed).integers(0, 2 ** 32, size=(1, Ns), dtype=np.uint64).astype(np.uint32)
             assert list(oracle.idiss_sample(phi, u)[0]) == _reference_sample(phi[0], u[0])
+
+
+def _reference_sample_integers(k, kmax, u, bits):
+    """The draw for weights phi_l = k_l / 2^27 in integer arithmetic alone: q_l = floor(k_l 2^bits / kmax).  Nothing of
+    the procedure's float32 steps is retyped; on such weights, with kmax a power of two, those steps are exact, so the
+    oracle must return exactly this."""
+    q = [(int(v) << bits) // int(kmax) for v in k]
+    C = np.cumsum(np.array(q, dtype=object)) if len(q) < 4096 else np.cumsum(np.array(q, dtype=np.int64))
+    Q, Ns = int(C[-1]), len(u)
+    assert Q < 2 ** 62
+    width, rem = divmod(Q, Ns)
+    out = []
+    for j in range(Ns):
+        start = j * width + min(j, rem)
+        ln = width + (1 if j < rem else 0)
+        t = start + ((int(u[j]) * ln) >> 32)
+        out.append(int(np.searchsorted(C, t, side="right")))
+    return out
+
+
+@pytest.mark.parametrize("N,Ns,log2_top", [(40, 10, 27), (97, 31, 26), (64, 16, 28), (300, 75, 27), (2 ** 23 + 1, 64, 27)])
+def test_quantisation_against_integer_arithmetic_on_dyadic_weights(N, Ns, log2_top):
+    # weights k / 2^27 with 24-bit k and a power of two as the largest: the procedure's float32 quotient 2^bits / max and
+    # its products are exact, so its integer weights must be floor(k 2^bits / kmax) computed in integers.  Largest
+    # weight 2 (log2_top = 28) leaves half-integers for the floor to act on; N above 2^23 lowers the resolution to
+    # 2^27, below it the resolution is 2^28.
+    rng = np.random.default_rng(N)
+    bits = min(28, 51 - (N - 1).bit_length())
+    assert bits == (27 if N > 2 ** 23 else 28)
+    k = rng.integers(1, 2 ** 24, size=N, dtype=np.int64) | 1
+    k[::9] = 0
+    k[int(rng.integers(0, N))] = 2 ** log2_top
+    phi = (k.astype(np.float64) * 2.0 ** -27).astype(np.float32)
+    assert np.array_equal(phi.astype(np.float64) * 2.0 ** 27, k.astype(np.float64))
+    u = rng.integers(0, 2 ** 32, size=(1, Ns), dtype=np.uint64).astype(np.uint32)
+    # half of the draws are aimed at the last unit of one point's share and the first unit of the next one's, where an
+    # integer weight that is off by one anywhere before them changes the point drawn
+    q = [(int(v) << bits) // 2 ** log2_top for v in k]
+    C = np.cumsum(np.array(q, dtype=np.int64))
+    width, rem = divmod(int(C[-1]), Ns)
+    aimed = 0
+    for j in range(0, Ns, 2):
+        start, ln = j * width + min(j, rem), width + (1 if j < rem else 0)
+        inside = np.flatnonzero((C > start) & (C < start + ln))
+        if len(inside) == 0 or ln >= 2 ** 32:
+            continue
+        x = int(C[inside[len(inside) // 2]]) - start - (j // 2) % 2
+        u[0, j] = -((-x << 32) // ln)                        # the least u with floor(u ln / 2^32) = x
+        assert (int(u[0, j]) * ln) >> 32 == x
+        aimed += 1
+    assert aimed >= min(Ns, 8) // 2 - 1 or width >= 2 ** 32   # (a stratum wider than 2^32 cannot be hit to the unit)
+    got = [int(v) for v in oracle.idiss_sample(phi[None], u)[0]]
+    assert got == _reference_sample_integers(k, 2 ** log2_top, u[0], bits)
 
 
 def test_sample_uniform_density_is_one_point_per_block():

@@ -37,7 +37,13 @@ SUB_PINS = [ts.test_pool_sub_fwd_bruteforce_with_ties, ts.test_pool_sub_fwd_grid
 BLOCK_PINS = [tb.test_block_fwd_bruteforce_dense, tb.test_block_identity_1x1_is_plain_flexconv,
               tb.test_block_bwd_finite_differences_full_jacobian]
 
+def _idiss_quantisation_pin():
+    for N, Ns, log2_top in ((40, 10, 27), (97, 31, 26), (64, 16, 28), (300, 75, 27)):
+        ti.test_quantisation_against_integer_arithmetic_on_dyadic_weights(N, Ns, log2_top)
+
+
 IDISS_PINS = [ti.test_phi_bruteforce_and_grid_closed_form, ti.test_sample_matches_exact_integer_reference,
+              _idiss_quantisation_pin,
               ti.test_sample_uniform_density_is_one_point_per_block, ti.test_make_distinct_bruteforce_and_properties]
 
 KNN_PINS = [tk.test_knn_matches_float32_numpy_ranking_with_ties, tk.test_knn_agrees_with_a_kd_tree_on_generic_points,
@@ -85,6 +91,8 @@ MUTATIONS = [
      "for (int c = 0; c < Dmid; ++c) s += (double)W[(int64_t)c * Din0 + c0] * gmid[IDX3(b, c0 % Dmid, n, Dmid, N)];", 0, BLOCK_PINS),
     ("idiss_phi_squared_distance", "s += sqrt(d2);", "s += d2;", 0, IDISS_PINS),
     ("idiss_threshold_inclusive", "while (C[l] <= t) ++l;", "while (C[l] < t) ++l;", 0, IDISS_PINS),
+    ("idiss_weights_rounded_up", "(uint32_t)(ph[l] * scale)", "(uint32_t)(ph[l] * scale + 0.999f)", 0, IDISS_PINS),
+    ("idiss_scale_by_sum_not_max", "if (ph[l] > mx) mx = ph[l];", "mx += ph[l];", 0, IDISS_PINS),
     ("idiss_remainder_dropped", "const uint64_t len = width + ((uint64_t)j < rem ? 1u : 0u);", "const uint64_t len = width;", 0, IDISS_PINS),
     ("knn_ties_to_later_index", "while (at > 0 && d2 < bd[at - 1])", "while (at > 0 && d2 <= bd[at - 1])", 0, KNN_PINS),
     ("knn_drops_z", "const float d2 = xy + zz;", "const float d2 = xy;", 0, KNN_PINS),
