@@ -325,11 +325,11 @@ def main():
                 r["issued_matrix_frac_of_measured_f16_peak"] = r["issued_matrix_TFLOPs"] / measured_peaks["mfma_f16_TFLOPs"]
         return r
 
-    rooflines = {n: roof(n) for n in OPS if n in bytes_pt and op_ms[n]["mean"] > 1e-2}
+    rooflines = {n: roof(n) for n in OPS if n in ops and n in bytes_pt and op_ms[n]["mean"] > 1e-2}
     dominant = max(rooflines, key=lambda n: rooflines[n]["kernel_ms"]) if rooflines else None
     roofline = rooflines.get(dominant)
-    fwd_ms = op_ms["fwd"]["mean"]
-    bwd_ms = op_ms["bwd"]["mean"]
+    fwd_ms = op_ms["fwd"]["mean"] if "fwd" in ops else 0.0
+    bwd_ms = op_ms["bwd"]["mean"] if "bwd" in ops else 0.0
 
     # ---- sampled parity at this size, in this launch configuration -------------
     parity = None
@@ -425,7 +425,7 @@ def main():
         "measured_peaks": measured_peaks,
         "kernel_source_sha256": kernel_source_hash(),
         "rooflines_all": rooflines,
-        "op_ms": op_ms,
+        "op_ms": {n: v for n, v in op_ms.items() if n in ops},      # entry points outside this run's step are not listed
         "inedges_build_ms": inedges_ms,
         "graph_ms_per_step": graph_ms,
         "fwd_points_per_s": pts / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
