@@ -72,6 +72,8 @@ def main():
                          "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
                          "quarter of the points, idiss = importance sub-sampling of a quarter of the points, knn = the "
                          "neighbour search; none of them is part of the default step)")
+    ap.add_argument("--no-pool-plan", action="store_true",
+                    help="flexpool_bwd through the in-edge lists alone instead of the static gather plan")
     ap.add_argument("--graph", action="store_true",
                     help="also capture one step into a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -131,6 +133,16 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     inedges_ms = ev0.elapsed_time(ev1)
+    # and the gather plan of the pooling backward pass (which rows a tile of 32 points needs): also once per cloud
+    pool_plan, pool_plan_ms = None, None
+    if "pool_bwd" in ops and not args.no_pool_plan:
+        pool_plan = fx.flexpool_plan_build(in_edges, B, N)
+        torch.cuda.synchronize()
+        ev0.record()
+        pool_plan = fx.flexpool_plan_build(in_edges, B, N)
+        ev1.record()
+        torch.cuda.synchronize()
+        pool_plan_ms = ev0.elapsed_time(ev1)
 
     names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos", "pool_sub") if n in ops]
     state = {}
@@ -170,7 +182,10 @@ def main():
             state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
         mark()
         if "pool_bwd" in ops:
-            state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
+            if pool_plan is not None:
+                state["pool_grad"] = fx.flexpool_bwd_planned(gpool, state["pool"][1], in_edges, pool_plan, layout=layout)
+            else:
+                state["pool_grad"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
         mark()
         if "upsample" in ops:
             state["up"] = fx.flexupsample_fwd(feat_small, sel, nbr, layout=layout)
@@ -295,7 +310,9 @@ def main():
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
-                 "pool_bwd": "pool_bwd_gather_row16_kernel (flexpool_bwd)",
+                 "pool_bwd": ("pool_bwd_planned64_kernel (flexpool_bwd_planned)"
+                              if pool_plan is not None and layout == fx.BNC and Din == 64 and K <= 12
+                              else "pool_bwd_gather_row16_kernel (flexpool_bwd)"),
                  "upsample_fwd": "upsample_fwd_bnc4_kernel (flexupsample_fwd)",
                  "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)",
                  "bwd_pos": "grad_pos_kernel x2 (flexconv_bwd_pos: centre term, neighbour term)",
@@ -359,6 +376,14 @@ def main():
             parity = dict(parity or {}, grad_feat_sampled_max_rel_err=float(np.max(np.abs(rows_g - ref) / den)),
                           grad_feat_rows=int(targets.size))
 
+        if "pool_bwd" in ops and pool_plan is not None and "pool_grad" in state:
+            # the planned pooling backward of the timed call against the list form (which the full-size GPU tests
+            # compare with the oracle element by element): the same sums in the same order, so the same bits
+            listed = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
+            parity = dict(parity or {}, pool_bwd_planned_equals_list_form=bool(
+                torch.equal(listed.view(torch.int32), state["pool_grad"].view(torch.int32))))
+            del listed
+
         # ---- CPU baseline: the oracle on a bounded slice of the same workload ----
         def oracle_pass(l0, l1):
             t = time.perf_counter()
@@ -419,7 +444,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "B": B, "N": N, "K": K, "Din": Din,
                    "Dout": Dout, "layout": args.layout, "point_order": x.order, "ops": names,
-                   "in_edges": "prebuilt once (static neighbourhoods)"},
+                   "in_edges": "prebuilt once (static neighbourhoods)",
+                   "pool_plan": ("prebuilt once (static neighbourhoods)" if pool_plan is not None else "not used")},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "measured_peaks": measured_peaks,
@@ -427,6 +453,8 @@ def main():
         "rooflines_all": rooflines,
         "op_ms": {n: v for n, v in op_ms.items() if n in ops},      # entry points outside this run's step are not listed
         "inedges_build_ms": inedges_ms,
+        "pool_plan_build_ms": pool_plan_ms,
+        "pool_plan_bytes": int(pool_plan.numel()) if pool_plan is not None else None,
         "graph_ms_per_step": graph_ms,
         "fwd_points_per_s": pts / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
         "fwd_effective_GFLOPs_direct_form": direct_flop_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else None,

@@ -186,6 +186,32 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
                  int B, int N, int K, int C, int layout, void *stream);
 
 /*
+ * Flex-max-pooling backward with a static gather plan (Sec. 4.1: the neighbourhoods are computed once and kept
+ * fixed, so which rows of grad_out / argmax a group of neighbouring points needs is fixed too; Table 1: the
+ * backward pass reads the upstream gradient and the recorded table).  The plan lists, for every tile of 32
+ * consecutive points, the distinct centres that list any of them, and for every entry of in_src the place of its
+ * centre in that list; the kernel fetches each listed row once per tile instead of once per entry.
+ *   flexpool_plan_bytes   size of the plan for (B, N, K) in bytes (0 for sizes flexconv would reject);
+ *   flexpool_plan_build   writes the plan for the lists (in_off, in_src) flex_inedges_build made with the same
+ *                         (B, N, K); plan: device memory, 256-byte aligned, owned by the caller, valid as long
+ *                         as the lists are; FLEX_ERR_WORKSPACE if plan_bytes is too small;
+ *   flexpool_bwd_planned  grad_feat of flexpool_bwd's list form, bit for bit (same sums in the same order);
+ *                         point-major C == 64 with K <= FLEX_POOL_PLAN_MAX_K runs the planned kernel, every
+ *                         other width, layout or K the list form itself.  grad_out / argmax / grad_feat as for
+ *                         flexpool_bwd.
+ * The plan depends on the lists only, not on the tensors: build it once per cloud.  It is dimensioned for the
+ * paper's neighbourhood sizes (K = 8 or 9): a tile's plan holds up to 127 distinct centres and covers up to 512
+ * list entries; what exceeds that is fetched entry by entry, correctly but without the saving.
+ */
+#define FLEX_POOL_PLAN_MAX_K 12
+size_t flexpool_plan_bytes(int B, int N, int K);
+int flexpool_plan_build(const int32_t *in_off, const int32_t *in_src, int B, int N, int K,
+                        void *plan, size_t plan_bytes, void *stream);
+int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *grad_feat,
+                         const int32_t *in_off, const int32_t *in_src, const void *plan, size_t plan_bytes,
+                         int B, int N, int K, int C, int layout, void *stream);
+
+/*
  * 1x1 convolution composed into a flex-convolution (Sec. 4.3: a ResNet block chains a 1x1
  * convolution and flex-convolutions; the paper names no bias in the 1x1 step and no activation
  * between it and the next step, and this entry point assumes neither).  With mid = W feat,

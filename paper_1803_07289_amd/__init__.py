@@ -33,6 +33,9 @@ _SIGS = {
     "flex_inedges_build": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "flexpool_fwd": (_i, [_vp] * 4 + [_i] * 5 + [_vp]),
     "flexpool_bwd": (_i, [_vp] * 5 + [_i] * 5 + [_vp]),
+    "flexpool_plan_bytes": (_sz, [_i] * 3),
+    "flexpool_plan_build": (_i, [_vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
+    "flexpool_bwd_planned": (_i, [_vp] * 6 + [_sz] + [_i] * 5 + [_vp]),
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexconv_compose_1x1": (_i, [_vp] * 5 + [_i] * 3 + [_vp]),
     "flexconv_compose_1x1_bwd": (_i, [_vp] * 8 + [_i] * 3 + [_vp]),
@@ -299,6 +302,42 @@ def flexpool_bwd(grad_out, argmax, layout=BCN, in_edges=None, K=None):
     gf = torch.empty_like(grad_out)
     _check(lib().flexpool_bwd(_ptr(grad_out), _ptr(argmax), _ptr(gf), _ptr(off), _ptr(src), B, N, k, C, layout,
                               _stream()), "flexpool_bwd")
+    return gf
+
+
+def flexpool_plan_build(in_edges, B, N):
+    """Static gather plan of the pooling backward pass for the lists in_edges = (in_off, in_src) of B clouds of N
+    points: a uint8 device tensor to pass to flexpool_bwd_planned.  Depends on the lists only: build once per cloud."""
+    off, src = in_edges
+    _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src")
+    if off.numel() != B * N + 1 or src.numel() % (B * N) != 0:
+        raise ValueError("in_edges do not match (B, N)")
+    K = src.numel() // (B * N)
+    need = int(lib().flexpool_plan_bytes(B, N, K))
+    if need == 0:
+        raise ValueError("sizes out of range")
+    plan = torch.empty(need, dtype=torch.uint8, device=off.device)
+    _check(lib().flexpool_plan_build(_ptr(off), _ptr(src), B, N, K, _ptr(plan), need, _stream()), "flexpool_plan_build")
+    return plan
+
+
+def flexpool_bwd_planned(grad_out, argmax, in_edges, plan, layout=BCN):
+    """Flex-max-pooling backward through the static gather plan: the result of flexpool_bwd(..., in_edges=...), bit
+    for bit.  Returns grad_feat."""
+    layout = _layout(layout)
+    _dev(grad_out, torch.float32, "grad_out"); _dev(argmax, torch.int32, "argmax")
+    if grad_out.dim() != 3 or grad_out.shape != argmax.shape:
+        raise ValueError("grad_out and argmax must be 3-D and equal in shape")
+    B = grad_out.shape[0]
+    C, N = (grad_out.shape[1], grad_out.shape[2]) if layout == BCN else (grad_out.shape[2], grad_out.shape[1])
+    off, src = in_edges
+    _dev(off, torch.int32, "in_off"); _dev(src, torch.int32, "in_src"); _dev(plan, torch.uint8, "plan")
+    if off.numel() != B * N + 1 or src.numel() % (B * N) != 0:
+        raise ValueError("in_edges do not match the tensors")
+    K = src.numel() // (B * N)
+    gf = torch.empty_like(grad_out)
+    _check(lib().flexpool_bwd_planned(_ptr(grad_out), _ptr(argmax), _ptr(gf), _ptr(off), _ptr(src), _ptr(plan),
+                                      plan.numel(), B, N, K, C, layout, _stream()), "flexpool_bwd_planned")
     return gf
 
 

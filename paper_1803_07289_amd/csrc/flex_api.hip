@@ -876,6 +876,39 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
     return FLEX_OK;
 }
 
+size_t flexpool_plan_bytes(int B, int N, int K)
+{
+    if (!sizes_ok(B, N, K, 1, 1)) return 0;
+    return pool_plan_bytes(B, N, K);
+}
+
+int flexpool_plan_build(const int32_t *in_off, const int32_t *in_src, int B, int N, int K, void *plan,
+                        size_t plan_bytes, void *stream)
+{
+    if (!in_off || !in_src || !plan) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, 1, 1)) return FLEX_ERR_SHAPE;
+    if (plan_bytes < pool_plan_bytes(B, N, K) || (reinterpret_cast<uintptr_t>(plan) & 255)) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_pool_plan_build(in_off, in_src, plan, B, N, K, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *grad_feat, const int32_t *in_off,
+                         const int32_t *in_src, const void *plan, size_t plan_bytes, int B, int N, int K, int C,
+                         int layout, void *stream)
+{
+    if (!grad_out || !argmax || !grad_feat || !in_off || !in_src || !plan) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, C, 1)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    if (plan_bytes < pool_plan_bytes(B, N, K) || (reinterpret_cast<uintptr_t>(plan) & 255)) return FLEX_ERR_WORKSPACE;
+    if (layout == FLEX_LAYOUT_BNC && C == 64 && K <= FLEX_POOL_PLAN_MAX_K)
+        FLEX_HIP(launch_pool_bwd_planned(grad_out, argmax, in_off, in_src, plan, grad_feat, B, N, K,
+                                         (hipStream_t)stream));
+    else        // widths, layouts and list lengths the plan has no kernel for: the list form, same sums
+        FLEX_HIP(launch_pool_bwd_gather(grad_out, argmax, in_off, in_src, grad_feat, B, N, C,
+                                        layout == FLEX_LAYOUT_BNC, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
 int flexconv_compose_1x1(const float *W, const float *theta, const float *bias, float *theta_c, float *bias_c,
                          int Din0, int Dmid, int Dout, void *stream)
 {

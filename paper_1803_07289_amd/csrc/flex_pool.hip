@@ -382,6 +382,340 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
     }
 }
 
+// ---- gather form with a static plan (C == 64, point-major) ---------------------------------------------------
+// Neighbouring points are listed by mostly the same centres: the 32 consecutive points of a tile have about 256
+// list entries but only about 94 distinct source rows, and the kernels above ask the texture path for a row's
+// 512 bytes (winner table + gradient) once per entry.  The neighbourhoods are static (Sec. 4.1), so which rows a
+// tile needs and where each list entry finds its row can be written down once per cloud: the plan.
+//   cnt  int32 [tiles]            distinct source rows of the tile that are listed (at most RMAX - 1), + PLAN_HAS_DIRECT
+//                                 if some entry's row is not among them; or -1: a tile with more than EMAX list
+//                                 entries, which the kernel serves entry by entry
+//   rows int32 [tiles][RMAX]      those rows (unused places: row 0)
+//   slot uint16 [entries]         per list entry (the order of in_src): the place of its row in the tile's list;
+//                                 PLAN_NULL if the entry repeats the one before it in the same list (it routes
+//                                 nothing: the kernel keeps a row that matches no point at that place);
+//                                 PLAN_DIRECT if its row is not listed (fetch it by in_src)
+// A row listed twice (two entries of one tile that lost each other in the hash table) costs bandwidth only.
+constexpr int PLAN_T = 32, PLAN_RMAX = 128, PLAN_EMAX = 512, PLAN_HASH = 2048;
+constexpr unsigned PLAN_NULL = PLAN_RMAX - 1, PLAN_DIRECT = 0x7fffu;
+constexpr int PLAN_HAS_DIRECT = 1 << 30;
+
+struct PoolPlanLayout {
+    size_t cnt_off, rows_off, slot_off, bytes;
+    int tiles_per_cloud;
+    int64_t tiles;
+};
+static PoolPlanLayout pool_plan_layout(int B, int N, int K)
+{
+    PoolPlanLayout l;
+    l.tiles_per_cloud = (N + PLAN_T - 1) / PLAN_T;
+    l.tiles = (int64_t)B * l.tiles_per_cloud;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    l.cnt_off = 0;
+    l.rows_off = up(sizeof(int32_t) * (size_t)l.tiles);
+    l.slot_off = l.rows_off + up(sizeof(int32_t) * (size_t)l.tiles * PLAN_RMAX);
+    l.bytes = l.slot_off + up(sizeof(unsigned short) * (size_t)B * K * N);
+    return l;
+}
+size_t pool_plan_bytes(int B, int N, int K) { return pool_plan_layout(B, N, K).bytes; }
+
+// One block per tile.  Every entry writes its own number into a table slot chosen by a hash of its row, reads back
+// which entry kept the slot and follows it if that one names the same row (else it stays its own leader); the
+// leaders are numbered by a prefix sum over the block.
+__global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__restrict__ in_off,
+                                                              const int32_t *__restrict__ in_src,
+                                                              int32_t *__restrict__ plan_cnt,
+                                                              int32_t *__restrict__ plan_rows,
+                                                              unsigned short *__restrict__ plan_slot, int N,
+                                                              int tiles_per_cloud)
+{
+    constexpr int T = PLAN_T, RMAX = PLAN_RMAX, EMAX = PLAN_EMAX, HASH = PLAN_HASH;
+    __shared__ int s_off[T + 1];
+    __shared__ int s_l[EMAX];
+    __shared__ unsigned short s_rank[EMAX];
+    __shared__ unsigned short s_tab[HASH];
+    __shared__ unsigned char s_start[EMAX];
+    __shared__ int s_cnt[8];
+    const int64_t tile = blockIdx.x;
+    const int64_t b = tile / tiles_per_cloud;
+    const int m0 = (int)(tile - b * tiles_per_cloud) * T;
+    const int np = min(T, N - m0);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (tid <= T) s_off[tid] = in_off[b * N + m0 + min(tid, np)];   // past the cloud: empty lists
+    s_start[tid] = 0;
+    s_start[tid + 256] = 0;
+    __syncthreads();
+    const int E0 = s_off[0], E = s_off[T] - E0;
+    if (E > EMAX) {
+        for (int r = tid; r < RMAX; r += 256) plan_rows[tile * RMAX + r] = 0;
+        if (tid == 0) plan_cnt[tile] = -1;
+        return;
+    }
+    if (tid < T && s_off[tid + 1] > s_off[tid]) s_start[s_off[tid] - E0] = 1;
+    int l[2], lead[2], rank[2];
+    unsigned h[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + 256 * r;
+        l[r] = i < E ? in_src[E0 + i] : -1;
+        h[r] = ((unsigned)l[r] * 0x9E3779B1u) >> 21;
+        if (i < E) { s_l[i] = l[r]; s_tab[h[r]] = (unsigned short)i; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + 256 * r;
+        bool leader = false;
+        lead[r] = i;
+        if (i < E) {
+            const int j = s_tab[h[r]];
+            if (s_l[j] == l[r]) lead[r] = j;
+            leader = lead[r] == i;
+        }
+        const unsigned long long bal = __ballot(leader);
+        rank[r] = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) s_cnt[r * 4 + w] = __popcll(bal);
+    }
+    __syncthreads();
+    int R = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int c = s_cnt[q];
+        if (q < w) rank[0] += c;
+        if (q < 4 + w) rank[1] += c;
+        R += c;
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + 256 * r;
+        if (i < E && lead[r] == i) {
+            s_rank[i] = (unsigned short)rank[r];
+            if (rank[r] < RMAX - 1) plan_rows[tile * RMAX + rank[r]] = l[r];
+        }
+    }
+    __syncthreads();
+    bool direct = false;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = tid + 256 * r;
+        if (i < E) {
+            const unsigned place = s_rank[lead[r]];
+            const bool repeat = i > 0 && !s_start[i] && s_l[i - 1] == l[r];
+            const bool listed = place < (unsigned)(RMAX - 1);
+            direct |= !repeat && !listed;
+            plan_slot[(size_t)E0 + i] = (unsigned short)(repeat ? PLAN_NULL : listed ? place : PLAN_DIRECT);
+        }
+    }
+    const int any_direct = __syncthreads_or(direct);
+    const int listed_rows = min(R, RMAX - 1);
+    for (int r = listed_rows + tid; r < RMAX; r += 256) plan_rows[tile * RMAX + r] = 0;
+    if (tid == 0) plan_cnt[tile] = listed_rows | (any_direct ? PLAN_HAS_DIRECT : 0);
+}
+
+hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, void *plan, int B, int N, int K,
+                                  hipStream_t s)
+{
+    const PoolPlanLayout l = pool_plan_layout(B, N, K);
+    if (l.tiles > 0x7fffffff) return hipErrorInvalidValue;
+    char *base = reinterpret_cast<char *>(plan);
+    hipLaunchKernelGGL(pool_plan_build_kernel, dim3((unsigned)l.tiles), dim3(256), 0, s, in_off, in_src,
+                       reinterpret_cast<int32_t *>(base + l.cnt_off), reinterpret_cast<int32_t *>(base + l.rows_off),
+                       reinterpret_cast<unsigned short *>(base + l.slot_off), N, l.tiles_per_cloud);
+    return hipGetLastError();
+}
+
+// The sums of one point, entry by entry from memory (tiles and entries the plan does not cover).
+__device__ __forceinline__ void pool_bwd_entry_direct(v4f &acc, const v4f *g4, const int4 *a4, int l, bool fresh, int m)
+{
+    const int4 a = a4[(int64_t)l * 16];
+    const v4f g = g4[(int64_t)l * 16];
+    acc.x += (fresh && a.x == m) ? g.x : 0.f;
+    acc.y += (fresh && a.y == m) ? g.y : 0.f;
+    acc.z += (fresh && a.z == m) ? g.z : 0.f;
+    acc.w += (fresh && a.w == m) ? g.w : 0.f;
+}
+
+// Persistent workgroups of 512 threads; a workgroup walks its tiles with three stages in flight: the list bounds of
+// tile i + 3, the plan (row list, the lane's slot word) of tile i + 2, the rows of tile i + 1 (in registers), while
+// tile i is summed from LDS.  16 lanes own one point (4 channels each) and, for staging, rows r = 32 q + group.
+// The sums run in list order with the same operations as the kernels above: bit-identical results.
+__global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
+    const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_cnt, const int32_t *__restrict__ plan_rows,
+    const unsigned short *__restrict__ plan_slot, float *__restrict__ grad_feat, int N, int L, int tiles_per_cloud,
+    int total_tiles)
+{
+    constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 32;
+    // a staged row: 16 x 16 bytes of the winner table, then 16 x 16 bytes of the gradient; place PLAN_NULL holds a
+    // row that no point wins (index -1)
+    __shared__ i4v s_r[RMAX * 32];
+    const int tid = threadIdx.x, c4 = tid & 15, t16 = tid & 15, p = tid >> 4;
+    if (tid < 32) s_r[PLAN_NULL * 32 + tid] = tid < 16 ? i4v{-1, -1, -1, -1} : i4v{0, 0, 0, 0};
+    // XCD x (= block id mod 8) owns a contiguous eighth of the tiles; its workgroups take them in turn
+    const int per_xcd = (total_tiles + 7) >> 3;
+    const int xbeg = (int)(blockIdx.x & 7) * per_xcd;
+    const int xend = min(xbeg + per_xcd, total_tiles);
+    const int step = (int)(gridDim.x >> 3);
+    const int first = xbeg + (int)(blockIdx.x >> 3);
+    if (first >= xend) return;
+    const int count = (xend - first + step - 1) / step;
+
+    // tile coordinates advance by additions (a division per stage and tile would cost more than the sums)
+    struct Tc { int b, tic, k; };
+    const int step_b = step / tiles_per_cloud, step_t = step - step_b * tiles_per_cloud;
+    auto next_tile = [&](const Tc &c) __attribute__((always_inline)) {
+        if (c.k + 1 >= count) return c;                    // past the end: the last tile again
+        Tc n{c.b + step_b, c.tic + step_t, c.k + 1};
+        if (n.tic >= tiles_per_cloud) { n.tic -= tiles_per_cloud; ++n.b; }
+        return n;
+    };
+    struct Bounds { int e0, n; };
+    auto load_bounds = [&](const Tc &c) __attribute__((always_inline)) {
+        const int m0 = c.tic * T;
+        const int np = min(T, N - m0);
+        const int32_t *o = in_off + ((int64_t)c.b * N + m0);
+        const int lo = o[min(p, np)], hi = o[min(p + 1, np)];
+        return Bounds{lo, hi - lo};
+    };
+    int cnt0, cnt1, rid1[TRIPS];
+    unsigned sw0, sw1;
+    i4v a[TRIPS], g[TRIPS];
+    auto load_plan = [&](const Tc &c, const Bounds &bd, int &cnt, int (&rid)[TRIPS], unsigned &sw) __attribute__((always_inline)) {
+        const int tile = c.b * tiles_per_cloud + c.tic;
+        cnt = plan_cnt[tile];
+        const int32_t *rows = plan_rows + (int64_t)tile * RMAX + p;
+#pragma unroll
+        for (int q = 0; q < TRIPS; ++q) rid[q] = rows[q * 32];
+        // lanes past the list take the row that matches nothing
+        sw = t16 < bd.n ? plan_slot[(size_t)bd.e0 + t16] : PLAN_NULL;
+    };
+    auto issue_rows = [&](const Tc &c, int cnt, const int (&rid)[TRIPS]) __attribute__((always_inline)) {
+        const i4v *gb = reinterpret_cast<const i4v *>(grad_out) + (int64_t)c.b * L * 16 + c4;
+        const i4v *ab = reinterpret_cast<const i4v *>(argmax) + (int64_t)c.b * L * 16 + c4;
+        const int rows = cnt < 0 ? 0 : (cnt & (PLAN_HAS_DIRECT - 1));
+#pragma unroll
+        for (int q = 0; q < TRIPS; ++q)
+            if (q * 32 + p < rows) {
+                a[q] = ab[(int64_t)rid[q] * 16];
+                g[q] = gb[(int64_t)rid[q] * 16];
+            }
+    };
+    Tc t0;
+    {
+        const int b0 = first / tiles_per_cloud;
+        t0 = Tc{b0, first - b0 * tiles_per_cloud, 0};
+    }
+    Tc t1 = next_tile(t0), t2 = next_tile(t1), t3 = next_tile(t2);
+    Bounds bd0 = load_bounds(t0), bd1 = load_bounds(t1), bd2 = load_bounds(t2);
+    {
+        int rid0[TRIPS];
+        load_plan(t0, bd0, cnt0, rid0, sw0);
+        load_plan(t1, bd1, cnt1, rid1, sw1);
+        issue_rows(t0, cnt0, rid0);
+    }
+    const int lane_base = c4 * 16;          // byte offset of this lane's chunk inside a half row
+
+    for (int i = 0; i < count; ++i) {
+        const int b = t0.b, m0 = t0.tic * T;
+        const int np = min(T, N - m0);
+        const int rows0 = cnt0 < 0 ? 0 : (cnt0 & (PLAN_HAS_DIRECT - 1));
+        // rows of tile i: registers -> LDS
+#pragma unroll
+        for (int q = 0; q < TRIPS; ++q) {
+            const int r = q * 32 + p;
+            if (r < rows0) {
+                s_r[r * 32 + c4] = a[q];
+                s_r[r * 32 + 16 + c4] = g[q];
+            }
+        }
+        __syncthreads();
+        // the next stages go in flight behind the sums of tile i
+        const Bounds bd = bd0;
+        const unsigned sw = sw0;
+        const int cnt = cnt0;
+        issue_rows(t1, cnt1, rid1);
+        cnt0 = cnt1;
+        sw0 = sw1;
+        bd0 = bd1;
+        bd1 = bd2;
+        load_plan(t2, bd1, cnt1, rid1, sw1);
+        bd2 = load_bounds(t3);
+        t0 = t1;
+        t1 = t2;
+        t2 = t3;
+        t3 = next_tile(t3);
+
+        if (p < np) {
+            v4f acc = {0.f, 0.f, 0.f, 0.f};
+            const int m = m0 + p;
+            const char *sb = reinterpret_cast<const char *>(s_r) + lane_base;
+            auto take_staged = [&](unsigned place) __attribute__((always_inline)) {
+                const i4v aa = *reinterpret_cast<const i4v *>(sb + place * 512u);
+                const v4f gg = *reinterpret_cast<const v4f *>(sb + place * 512u + 256u);
+                acc.x += aa.x == m ? gg.x : 0.f;
+                acc.y += aa.y == m ? gg.y : 0.f;
+                acc.z += aa.z == m ? gg.z : 0.f;
+                acc.w += aa.w == m ? gg.w : 0.f;
+            };
+            if (cnt >= 0 && !(cnt & PLAN_HAS_DIRECT)) {
+                // every entry's row is staged: four entries at a time, no case distinctions
+#define FLEX_PLAN_BATCH(J)                                                                                      \
+                if ((J) < bd.n) {                                                                                   \
+                    const unsigned w0 = (unsigned)row_bcast<(J)>((int)sw), w1 = (unsigned)row_bcast<(J) + 1>((int)sw),  \
+                                   w2 = (unsigned)row_bcast<(J) + 2>((int)sw), w3 = (unsigned)row_bcast<(J) + 3>((int)sw); \
+                    const i4v a0 = *reinterpret_cast<const i4v *>(sb + w0 * 512u), a1 = *reinterpret_cast<const i4v *>(sb + w1 * 512u), \
+                               a2 = *reinterpret_cast<const i4v *>(sb + w2 * 512u), a3 = *reinterpret_cast<const i4v *>(sb + w3 * 512u); \
+                    const v4f g0 = *reinterpret_cast<const v4f *>(sb + w0 * 512u + 256u), g1 = *reinterpret_cast<const v4f *>(sb + w1 * 512u + 256u), \
+                              g2 = *reinterpret_cast<const v4f *>(sb + w2 * 512u + 256u), g3 = *reinterpret_cast<const v4f *>(sb + w3 * 512u + 256u); \
+                    acc.x += a0.x == m ? g0.x : 0.f; acc.y += a0.y == m ? g0.y : 0.f; acc.z += a0.z == m ? g0.z : 0.f; acc.w += a0.w == m ? g0.w : 0.f; \
+                    acc.x += a1.x == m ? g1.x : 0.f; acc.y += a1.y == m ? g1.y : 0.f; acc.z += a1.z == m ? g1.z : 0.f; acc.w += a1.w == m ? g1.w : 0.f; \
+                    acc.x += a2.x == m ? g2.x : 0.f; acc.y += a2.y == m ? g2.y : 0.f; acc.z += a2.z == m ? g2.z : 0.f; acc.w += a2.w == m ? g2.w : 0.f; \
+                    acc.x += a3.x == m ? g3.x : 0.f; acc.y += a3.y == m ? g3.y : 0.f; acc.z += a3.z == m ? g3.z : 0.f; acc.w += a3.w == m ? g3.w : 0.f; \
+                }
+                FLEX_PLAN_BATCH(0) FLEX_PLAN_BATCH(4) FLEX_PLAN_BATCH(8) FLEX_PLAN_BATCH(12)
+#undef FLEX_PLAN_BATCH
+                for (int j = 16; j < bd.n; ++j)       // a list longer than the lanes' sixteen slot words
+                    take_staged(plan_slot[(size_t)bd.e0 + j]);
+            } else {
+                // a tile the plan covers in part or not at all: entry by entry
+                const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + (int64_t)b * L * 16 + c4;
+                const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + (int64_t)b * L * 16 + c4;
+                int prev = -1;
+                for (int j = 0; j < bd.n; ++j) {
+                    const unsigned place = cnt < 0 ? PLAN_DIRECT : plan_slot[(size_t)bd.e0 + j];
+                    if (place < (unsigned)RMAX) {
+                        take_staged(place);
+                    } else {
+                        const int l = in_src[bd.e0 + j];
+                        pool_bwd_entry_direct(acc, g4, a4, l, l != prev, m);
+                        prev = l;
+                    }
+                }
+            }
+            __builtin_nontemporal_store(acc, &reinterpret_cast<v4f *>(grad_feat)[((int64_t)b * N + m) * 16 + c4]);
+        }
+        __syncthreads();        // every sum of tile i is done before the rows of tile i + 1 replace it
+    }
+}
+
+hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
+                                   const int32_t *in_src, const void *plan, float *grad_feat, int B, int N, int K,
+                                   hipStream_t s)
+{
+    const PoolPlanLayout l = pool_plan_layout(B, N, K);
+    if (l.tiles > 0x7fffffff) return hipErrorInvalidValue;
+    const char *base = reinterpret_cast<const char *>(plan);
+    // two workgroups per CU by LDS and registers; fewer when there are fewer tiles than that
+    int64_t wgs = 2 * 256;
+    if (wgs > ((l.tiles + 7) & ~(int64_t)7)) wgs = (l.tiles + 7) & ~(int64_t)7;
+    hipLaunchKernelGGL(pool_bwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, grad_out, argmax, in_off,
+                       in_src, reinterpret_cast<const int32_t *>(base + l.cnt_off),
+                       reinterpret_cast<const int32_t *>(base + l.rows_off),
+                       reinterpret_cast<const unsigned short *>(base + l.slot_off), grad_feat, N, N,
+                       l.tiles_per_cloud, (int)l.tiles);
+    return hipGetLastError();
+}
+
 // Channel-major ([B,C,N]) gather form.  A block owns 64 consecutive points, whose in-edge lists are one
 // contiguous range of entries.  The gathers run over that range with lane = entry (a lane per point would
 // idle until the longest of 64 lists is done): per chunk of ECH entries the block parks the entries and

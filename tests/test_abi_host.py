@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(L):
             "flexconv_has_fast_path", "flexupsample_fwd", "flexupsample_bwd", "flex_validate_selection",
             "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub",
             "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample", "flex_knn",
-            "flex_selection_make_distinct"} <= set(names)
+            "flex_selection_make_distinct", "flexpool_plan_bytes", "flexpool_plan_build",
+            "flexpool_bwd_planned"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -67,6 +68,28 @@ def test_null_and_shape_errors_precede_any_launch(L):
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, none, 0, None) == 4
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, ctypes.c_void_p(260), 1 << 20, None) == 4
     assert L.flexconv_fwd(one, one, one, one, one, one, 1, 64, 2, 64, 64, 1, one, 512, None) == 4
+
+
+def test_pooling_plan_size_and_errors_precede_any_launch(L):
+    one, none = ctypes.c_void_p(256), None
+    up = lambda x: (x + 255) // 256 * 256
+    for B, N, K in ((1, 1, 1), (2, 33, 8), (1, 7_000_000, 8), (3, 4097, 16)):
+        tiles = B * ((N + 31) // 32)
+        # distinct-row counts, 128 row places per tile of 32 points, one 16-bit place per list entry
+        assert L.flexpool_plan_bytes(B, N, K) == up(4 * tiles) + up(4 * tiles * 128) + up(2 * B * K * N)
+    assert L.flexpool_plan_bytes(1, 8, 9) == 0 and L.flexpool_plan_bytes(0, 8, 1) == 0
+    need = L.flexpool_plan_bytes(1, 64, 2)
+    assert L.flexpool_plan_build(none, one, 1, 64, 2, one, need, None) == 1
+    assert L.flexpool_plan_build(one, one, 1, 64, 2, none, need, None) == 1
+    assert L.flexpool_plan_build(one, one, 1, 64, 65, one, need, None) == 2
+    assert L.flexpool_plan_build(one, one, 1, 64, 2, one, need - 1, None) == 4
+    assert L.flexpool_plan_build(one, one, 1, 64, 2, ctypes.c_void_p(260), need, None) == 4
+    assert L.flexpool_bwd_planned(one, one, one, one, one, none, need, 1, 64, 2, 64, 1, None) == 1
+    assert L.flexpool_bwd_planned(one, one, none, one, one, one, need, 1, 64, 2, 64, 1, None) == 1
+    assert L.flexpool_bwd_planned(one, one, one, one, one, one, need, 1, 64, 2, 64, 5, None) == 2
+    assert L.flexpool_bwd_planned(one, one, one, one, one, one, need, 1, 64, 2, 0, 1, None) == 2
+    assert L.flexpool_bwd_planned(one, one, one, one, one, one, need - 1, 1, 64, 2, 64, 1, None) == 4
+    assert L.flexpool_bwd_planned(one, one, one, one, one, ctypes.c_void_p(260), need, 1, 64, 2, 64, 1, None) == 4
 
 
 def test_upsampling_and_location_gradient_errors_precede_any_launch(L):

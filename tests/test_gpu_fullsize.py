@@ -181,9 +181,14 @@ def test_pooling_every_point(work):
     assert torch.equal(po.transpose(1, 2).cpu().view(torch.int32), torch.from_numpy(ro).view(torch.int32))
     del ro
     gp = work.g if work.g is not None and cfg.Din == cfg.Dout else torch.randn_like(feat)
-    pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC, in_edges=work.edges)     # the form bench.py times
+    pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC, in_edges=work.edges)
     pg_scatter = fx.flexpool_bwd(gp, pa, layout=fx.BNC)
+    # the form bench.py times: through the static gather plan; the same sums in the same order as the list form
+    plan = fx.flexpool_plan_build(work.edges, cfg.B, N)
+    pg_planned = fx.flexpool_bwd_planned(gp, pa, work.edges, plan, layout=fx.BNC)
     torch.cuda.synchronize()
+    assert torch.equal(pg_planned.view(torch.int32), pg.view(torch.int32))
+    del pg_planned, plan
     assert float((pg - pg_scatter).abs().max()) <= 1e-4 * float(gp.abs().max()) * K
     del pg_scatter
     # every element of the backward pass against the oracle's routing by its own table

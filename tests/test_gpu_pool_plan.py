@@ -1,0 +1,112 @@
+"""GPU parity for the flex-max-pooling backward pass through the static gather plan (flexpool_plan_build,
+flexpool_bwd_planned): the result must equal the list form of flexpool_bwd bit for bit (same sums, same order) and
+the CPU oracle within the pooling-backward tolerance.  The cases reach every branch of the planned kernel: tiles
+whose rows are all staged, tiles with more distinct rows than the plan lists (entries fetched directly), tiles with
+more entries than the plan covers (served entry by entry), lists longer than a row group's sixteen slot words,
+repeated entries, ragged tails, several clouds, fewer tiles than workgroups; and the widths and layouts the plan
+has no kernel for, which run the list form.  (The 7M-point configuration: test_gpu_fullsize.py.)"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1803_07289_amd as fx
+from gpu_util import dev, to_layout, from_layout, say
+from helpers import rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def lists(kind, rng, B, N, K):
+    if kind == "random":                 # no locality: a tile of 32 points is listed by up to 32 K distinct centres
+        return rng.integers(0, N, size=(B, K, N)).astype(np.int32)
+    near = ((np.arange(N)[None, None, :] + rng.integers(-20, 21, size=(B, K, N))) % N).astype(np.int32)
+    if kind == "local":
+        return near
+    if kind == "hub":                    # one point listed by half the cloud: its tile has far more than 512 entries
+        near[:, 0, : N // 2] = min(7, N - 1)
+        return near
+    if kind == "long_list":              # one point listed by 40 centres: more than sixteen entries, tile still covered
+        near[:, 0, 100:140] = 105
+        return near
+    if kind == "repeats":                # every centre lists its first neighbour twice
+        near[:, K - 1, :] = near[:, 0, :]
+        return near
+    raise ValueError(kind)
+
+
+def run_case(seed, B, N, K, C, layout, kind):
+    rng = np.random.default_rng(seed)
+    feat = rng.integers(-2, 3, size=(B, C, N)).astype(np.float32)            # many ties
+    feat[:, :, ::3] = rng.standard_normal(feat[:, :, ::3].shape).astype(np.float32)
+    g = rng.standard_normal((B, C, N)).astype(np.float32)
+    nbr = lists(kind, rng, B, N, K)
+    dn = dev(nbr)
+    out, arg = fx.flexpool_fwd(to_layout(feat, layout), dn, layout=layout)
+    edges = fx.flex_inedges_build(dn)
+    plan = fx.flexpool_plan_build(edges, B, N)
+    dg = to_layout(g, layout)
+    ref = fx.flexpool_bwd(dg, arg, layout=layout, in_edges=edges)
+    got = fx.flexpool_bwd_planned(dg, arg, edges, plan, layout=layout)
+    again = fx.flexpool_bwd_planned(dg, arg, edges, plan, layout=layout)
+    torch.cuda.synchronize()
+    assert torch.equal(ref.view(torch.int32), got.view(torch.int32)), float((ref - got).abs().max())
+    assert torch.equal(got.view(torch.int32), again.view(torch.int32))
+    _, ra = oracle.flexpool_fwd(feat, nbr)
+    assert np.array_equal(from_layout(arg, layout), ra)
+    # fp32 sums in list order against the oracle's fp64: 1e-5 for neighbourhood-sized lists; the hub point adds up
+    # N / 2 terms one after the other (about n 2^-24 of the sum of magnitudes: the list form's own accuracy)
+    assert rel_err(from_layout(got, layout), oracle.flexpool_bwd(g, ra)) <= (1e-4 if kind == "hub" else 1e-5)
+    return plan
+
+
+@pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "repeats"])
+@pytest.mark.parametrize("B,N,K", [(1, 1, 1), (1, 31, 4), (2, 33, 8), (3, 1000, 8), (1, 5000, 16), (2, 4097, 9),
+                                   (1, 70000, 8)])
+def test_planned_backward_equals_the_list_form(B, N, K, kind):
+    if kind in ("hub", "long_list") and N < 1000:
+        pytest.skip("needs a cloud with room for the construction")
+    say(f"pool plan: B={B} N={N} K={K} lists={kind}")
+    plan = run_case(100 * N + K, B, N, K, 64, fx.BNC, kind)
+    # what the plan says about its tiles: every branch of the kernel is reached by some case
+    tiles = B * ((N + 31) // 32)
+    cnt = plan[:4 * tiles].view(torch.int32).cpu().numpy()
+    say(f"  tiles {tiles}: not covered {int((cnt < 0).sum())}, with direct entries {int(((cnt >= 0) & (cnt >= 2 ** 30)).sum())}")
+    if kind == "hub":
+        assert (cnt < 0).any()
+    if kind == "random" and N >= 1000:
+        assert ((cnt >= 0) & (cnt >= 2 ** 30)).any()
+    if kind == "local" and K <= 9:       # the paper's neighbourhood sizes: every row of every tile is staged
+        assert (cnt >= 0).all() and (cnt < 2 ** 30).all()
+
+
+@pytest.mark.parametrize("C,layout,K", [(64, fx.BCN, 8), (32, fx.BNC, 8), (128, fx.BNC, 8), (5, fx.BCN, 8),
+                                        (64, fx.BNC, 13), (64, fx.BNC, 20)])
+def test_widths_layouts_and_list_lengths_without_a_planned_kernel_run_the_list_form(C, layout, K):
+    say(f"pool plan, list form behind it: C={C} layout={layout} K={K}")
+    run_case(7 + C + K, 2, 700, K, C, layout, "local")
+
+
+def test_plan_arguments_are_checked():
+    L = fx.lib()
+    B, N, K = 1, 500, 8
+    rng = np.random.default_rng(0)
+    dn = dev(lists("local", rng, B, N, K))
+    off, src = fx.flex_inedges_build(dn)
+    need = int(L.flexpool_plan_bytes(B, N, K))
+    assert need > 0 and need % 256 == 0
+    assert int(L.flexpool_plan_bytes(B, N, N + 1)) == 0 and int(L.flexpool_plan_bytes(0, N, K)) == 0
+    plan = torch.empty(need, dtype=torch.uint8, device="cuda")
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert L.flexpool_plan_build(p(off), p(src), B, N, K, p(plan), need - 1, None) == 4        # FLEX_ERR_WORKSPACE
+    assert L.flexpool_plan_build(None, p(src), B, N, K, p(plan), need, None) == 1               # FLEX_ERR_NULL
+    assert L.flexpool_plan_build(p(off), p(src), B, N, K, p(plan), need, None) == 0
+    g = torch.zeros(B, N, 64, device="cuda")
+    arg = torch.zeros(B, N, 64, dtype=torch.int32, device="cuda")
+    out = torch.empty_like(g)
+    assert L.flexpool_bwd_planned(p(g), p(arg), p(out), p(off), p(src), p(plan), need - 1, B, N, K, 64, fx.BNC, None) == 4
+    assert L.flexpool_bwd_planned(p(g), p(arg), p(out), p(off), p(src), None, need, B, N, K, 64, fx.BNC, None) == 1
+    assert L.flexpool_bwd_planned(p(g), p(arg), p(out), p(off), p(src), p(plan), need, B, N, K, 64, 7, None) == 2
+    torch.cuda.synchronize()
