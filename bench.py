@@ -71,7 +71,8 @@ def main():
                          "for the parameter gradients / the feature gradient alone; upsample = flex-upsampling from a "
                          "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
                          "quarter of the points, idiss = importance sub-sampling of a quarter of the points, knn = the "
-                         "neighbour search; none of them is part of the default step)")
+                         "neighbour search, pool_bwd_list = flexpool_bwd over the in-edge lists alone; none of them is part "
+                         "of the default step)")
     ap.add_argument("--no-pool-plan", action="store_true",
                     help="flexpool_bwd through the in-edge lists alone instead of the static gather plan")
     ap.add_argument("--graph", action="store_true",
@@ -147,7 +148,8 @@ def main():
     names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos", "pool_sub") if n in ops]
     state = {}
     OPS = ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
-           "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn", "bwd_params", "bwd_feat")
+           "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn", "bwd_params", "bwd_feat",
+           "pool_bwd_list")
     if "idiss" in ops:
         # random words for the stratified draw of a quarter of the points (Sec. 3.2), drawn once
         u_words = torch.from_numpy(np.random.default_rng([cfg.seed, 400]).integers(
@@ -178,7 +180,7 @@ def main():
         if "bwd" in ops:
             state["grads"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges)
         mark()
-        if "pool_fwd" in ops or "pool_bwd" in ops:
+        if "pool_fwd" in ops or "pool_bwd" in ops or "pool_bwd_list" in ops:
             state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
         mark()
         if "pool_bwd" in ops:
@@ -220,6 +222,10 @@ def main():
         if "bwd_feat" in ops:
             state["gfeat"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges,
                                              need_params=False)
+        mark()
+        # the pooling backward pass over the lists alone, beside the planned form of the step
+        if "pool_bwd_list" in ops:
+            state["pool_grad_list"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
         mark()
 
     # ---- measured peaks of this device: plain copy kernel, pure f16 matrix-op loop ----------
@@ -293,6 +299,7 @@ def main():
                 "bwd_feat": 4 * Dout + 12 + 4 * (K + 1) + 4 * Din,
                 "pool_fwd": 4 * Din + 4 * K + 8 * Din,
                 "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din,
+                "pool_bwd_list": 8 * Din + 4 * (K + 1) + 4 * Din,
                 # per point of the larger layer, smaller layer = a quarter of it: rows of the smaller layer,
                 # sel, inverse map (written, read), ids, out + winners / gradient + winners, lists, smaller rows
                 "upsample_fwd": Din + 1 + 8 + 4 * K + 8 * Din,
@@ -317,6 +324,7 @@ def main():
                  "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)",
                  "bwd_pos": "grad_pos_kernel x2 (flexconv_bwd_pos: centre term, neighbour term)",
                  "pool_sub_fwd": "pool_fwd_bnc4_kernel<true> (flexpool_sub_fwd)",
+                 "pool_bwd_list": "pool_bwd_gather_row16_kernel (flexpool_bwd)",
                  "pool_sub_bwd": "pool_bwd_gather_row16_kernel<2> (flexpool_sub_bwd)"}
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/flexconv_cfg4_hbm_traffic.md); only known for the default workload
