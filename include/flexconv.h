@@ -199,6 +199,8 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  *                         point-major C == 64 with K <= FLEX_POOL_PLAN_MAX_K runs the planned kernel, every
  *                         other width, layout or K the list form itself.  grad_out / argmax / grad_feat as for
  *                         flexpool_bwd.
+ * The plan's last 2 KB are scratch of the kernel (the tile counters its workgroups draw from, cleared at
+ * every call): calls that share a plan must not overlap in time; nothing else of it is written after the build.
  * The plan depends on the lists only, not on the tensors: build it once per cloud.  It is dimensioned for the
  * paper's neighbourhood sizes (K = 8 or 9): a tile's plan holds up to 127 distinct centres and covers up to 512
  * list entries; what exceeds that is fetched entry by entry, correctly but without the saving.
@@ -208,7 +210,7 @@ size_t flexpool_plan_bytes(int B, int N, int K);
 int flexpool_plan_build(const int32_t *in_off, const int32_t *in_src, int B, int N, int K,
                         void *plan, size_t plan_bytes, void *stream);
 int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *grad_feat,
-                         const int32_t *in_off, const int32_t *in_src, const void *plan, size_t plan_bytes,
+                         const int32_t *in_off, const int32_t *in_src, void *plan, size_t plan_bytes,
                          int B, int N, int K, int C, int layout, void *stream);
 
 /*

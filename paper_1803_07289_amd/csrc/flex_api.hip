@@ -893,7 +893,7 @@ int flexpool_plan_build(const int32_t *in_off, const int32_t *in_src, int B, int
 }
 
 int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *grad_feat, const int32_t *in_off,
-                         const int32_t *in_src, const void *plan, size_t plan_bytes, int B, int N, int K, int C,
+                         const int32_t *in_src, void *plan, size_t plan_bytes, int B, int N, int K, int C,
                          int layout, void *stream)
 {
     if (!grad_out || !argmax || !grad_feat || !in_off || !in_src || !plan) return FLEX_ERR_NULL;

@@ -154,7 +154,7 @@ size_t pool_plan_bytes(int B, int N, int K);
 hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, void *plan, int B, int N, int K,
                                   hipStream_t s);
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
-                                   const int32_t *in_src, const void *plan, float *grad_feat, int B, int N, int K,
+                                   const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K,
                                    hipStream_t s);
 hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
                                       const int32_t *in_src, float *grad_feat, int B, int N, int L, int C,

@@ -4,6 +4,7 @@
 // scatters by the recorded index with fp32 atomic adds.
 #include "flex_common.hpp"
 #include <type_traits>
+#include <cstdlib>
 
 namespace flex {
 
@@ -395,13 +396,17 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
 //                                 PLAN_NULL if the entry repeats the one before it in the same list (it routes
 //                                 nothing: the kernel keeps a row that matches no point at that place);
 //                                 PLAN_DIRECT if its row is not listed (fetch it by in_src)
+//   ctr  int32 [8][64]           scratch of the kernel: the next tile of each XCD's share, one counter per
+//                                 256-byte block (cleared at every launch)
 // A row listed twice (two entries of one tile that lost each other in the hash table) costs bandwidth only.
 constexpr int PLAN_T = 32, PLAN_RMAX = 128, PLAN_EMAX = 512, PLAN_HASH = 2048;
 constexpr unsigned PLAN_NULL = PLAN_RMAX - 1, PLAN_DIRECT = 0x7fffu;
 constexpr int PLAN_HAS_DIRECT = 1 << 30;
+constexpr int PLAN_CTR_STRIDE = 64;     // ints between the XCDs' counters: a 256-byte block each
+constexpr int PLAN_DRAW = 4;            // tiles a workgroup draws at a time
 
 struct PoolPlanLayout {
-    size_t cnt_off, rows_off, slot_off, bytes;
+    size_t cnt_off, rows_off, slot_off, ctr_off, bytes;
     int tiles_per_cloud;
     int64_t tiles;
 };
@@ -414,7 +419,8 @@ static PoolPlanLayout pool_plan_layout(int B, int N, int K)
     l.cnt_off = 0;
     l.rows_off = up(sizeof(int32_t) * (size_t)l.tiles);
     l.slot_off = l.rows_off + up(sizeof(int32_t) * (size_t)l.tiles * PLAN_RMAX);
-    l.bytes = l.slot_off + up(sizeof(unsigned short) * (size_t)B * K * N);
+    l.ctr_off = l.slot_off + up(sizeof(unsigned short) * (size_t)B * K * N);
+    l.bytes = l.ctr_off + 8 * PLAN_CTR_STRIDE * sizeof(int32_t);   // tile counters of the kernel, one per XCD
     return l;
 }
 size_t pool_plan_bytes(int B, int N, int K) { return pool_plan_layout(B, N, K).bytes; }
@@ -542,8 +548,8 @@ __device__ __forceinline__ void pool_bwd_entry_direct(v4f &acc, const v4f *g4, c
 __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
     const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_cnt, const int32_t *__restrict__ plan_rows,
-    const unsigned short *__restrict__ plan_slot, float *__restrict__ grad_feat, int N, int L, int tiles_per_cloud,
-    int total_tiles)
+    const unsigned short *__restrict__ plan_slot, int *__restrict__ tile_ctr, float *__restrict__ grad_feat, int N,
+    int L, int tiles_per_cloud, int total_tiles)
 {
     constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 32;
     // a staged row: 16 x 16 bytes of the winner table, then 16 x 16 bytes of the gradient; place PLAN_NULL holds a
@@ -551,24 +557,31 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
     __shared__ i4v s_r[RMAX * 32];
     const int tid = threadIdx.x, c4 = tid & 15, t16 = tid & 15, p = tid >> 4;
     if (tid < 32) s_r[PLAN_NULL * 32 + tid] = tid < 16 ? i4v{-1, -1, -1, -1} : i4v{0, 0, 0, 0};
-    // XCD x (= block id mod 8) owns a contiguous eighth of the tiles; its workgroups take them in turn
+    // XCD x (= block id mod 8) owns a contiguous eighth of the tiles.  Its workgroups draw them from a counter, in
+    // order, four at a time and well ahead of the tile they sum: whatever the pace of each workgroup, the tiles
+    // being staged at any moment are a short run of neighbours, whose shared rows meet in the XCD's L2.  (Dealt out
+    // in fixed turns the workgroups drift apart over their four hundred tiles and rows are fetched from HBM 1.9
+    // times; one draw per tile, with all counters in one cache line, made the counter the bottleneck.)
+    constexpr int DRAW = PLAN_DRAW, AHEAD = (5 + DRAW - 1) / DRAW, RING = 8;   // draws in flight: tile i + 4 is looked up in iteration i
+    static_assert(AHEAD + 2 <= RING, "a draw is published one iteration after it is made");
+    __shared__ int s_draw[RING];        // first tile of the workgroup's draw m at [m % RING]
     const int per_xcd = (total_tiles + 7) >> 3;
     const int xbeg = (int)(blockIdx.x & 7) * per_xcd;
-    const int xend = min(xbeg + per_xcd, total_tiles);
-    const int step = (int)(gridDim.x >> 3);
-    const int first = xbeg + (int)(blockIdx.x >> 3);
-    if (first >= xend) return;
-    const int count = (xend - first + step - 1) / step;
-
-    // tile coordinates advance by additions (a division per stage and tile would cost more than the sums)
-    struct Tc { int b, tic, k; };
-    const int step_b = step / tiles_per_cloud, step_t = step - step_b * tiles_per_cloud;
-    auto next_tile = [&](const Tc &c) __attribute__((always_inline)) {
-        if (c.k + 1 >= count) return c;                    // past the end: the last tile again
-        Tc n{c.b + step_b, c.tic + step_t, c.k + 1};
-        if (n.tic >= tiles_per_cloud) { n.tic -= tiles_per_cloud; ++n.b; }
-        return n;
+    const int xcount = min(per_xcd, total_tiles - xbeg);
+    if (xcount <= 0) return;
+    int *ctr = tile_ctr + (blockIdx.x & 7) * PLAN_CTR_STRIDE;
+    struct Tc { int b, tic; bool valid; };
+    auto tile_at = [&](int k) __attribute__((always_inline)) {       // the workgroup's k-th tile; past the share: its last tile, not summed
+        const int j = __builtin_amdgcn_readfirstlane(s_draw[(k / DRAW) % RING]) + k % DRAW;
+        const int t = xbeg + min(j, xcount - 1);
+        const int b = t / tiles_per_cloud;
+        return Tc{b, t - b * tiles_per_cloud, j < xcount};
     };
+    if (tid == 0) {
+#pragma unroll
+        for (int m = 0; m < AHEAD; ++m) s_draw[m] = atomicAdd(ctr, DRAW);
+    }
+    __syncthreads();
     struct Bounds { int e0, n; };
     auto load_bounds = [&](const Tc &c) __attribute__((always_inline)) {
         const int m0 = c.tic * T;
@@ -600,12 +613,7 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
                 g[q] = gb[(int64_t)rid[q] * 16];
             }
     };
-    Tc t0;
-    {
-        const int b0 = first / tiles_per_cloud;
-        t0 = Tc{b0, first - b0 * tiles_per_cloud, 0};
-    }
-    Tc t1 = next_tile(t0), t2 = next_tile(t1), t3 = next_tile(t2);
+    Tc t0 = tile_at(0), t1 = tile_at(1), t2 = tile_at(2), t3 = tile_at(3);
     Bounds bd0 = load_bounds(t0), bd1 = load_bounds(t1), bd2 = load_bounds(t2);
     {
         int rid0[TRIPS];
@@ -615,8 +623,10 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
     }
     const int lane_base = c4 * 16;          // byte offset of this lane's chunk inside a half row
 
-    for (int i = 0; i < count; ++i) {
+    int drawn = 0;                          // thread 0: the draw made in the iteration before, not yet published
+    for (int i = 0; t0.valid; ++i) {
         const int b = t0.b, m0 = t0.tic * T;
+        if (tid == 0 && i > 0 && (i - 1) % DRAW == 0) s_draw[((i - 1) / DRAW + AHEAD) % RING] = drawn;
         const int np = min(T, N - m0);
         const int rows0 = cnt0 < 0 ? 0 : (cnt0 & (PLAN_HAS_DIRECT - 1));
         // rows of tile i: registers -> LDS
@@ -629,7 +639,9 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
             }
         }
         __syncthreads();
-        // the next stages go in flight behind the sums of tile i
+        // the next stages go in flight behind the sums of tile i (first of all, every DRAW-th tile, a draw: it is
+        // published at the top of the next iteration and first looked up AHEAD * DRAW - 4 iterations from now)
+        if (tid == 0 && i % DRAW == 0) drawn = atomicAdd(ctr, DRAW);
         const Bounds bd = bd0;
         const unsigned sw = sw0;
         const int cnt = cnt0;
@@ -643,7 +655,7 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
         t0 = t1;
         t1 = t2;
         t2 = t3;
-        t3 = next_tile(t3);
+        t3 = tile_at(i + 4);
 
         if (p < np) {
             v4f acc = {0.f, 0.f, 0.f, 0.f};
@@ -699,20 +711,22 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
 }
 
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
-                                   const int32_t *in_src, const void *plan, float *grad_feat, int B, int N, int K,
+                                   const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K,
                                    hipStream_t s)
 {
     const PoolPlanLayout l = pool_plan_layout(B, N, K);
     if (l.tiles > 0x7fffffff) return hipErrorInvalidValue;
-    const char *base = reinterpret_cast<const char *>(plan);
+    char *base = reinterpret_cast<char *>(plan);
+    const hipError_t e = launch_fill_zero(base + l.ctr_off, 8 * PLAN_CTR_STRIDE * sizeof(int32_t), s);
+    if (e != hipSuccess) return e;
     // two workgroups per CU by LDS and registers; fewer when there are fewer tiles than that
     int64_t wgs = 2 * 256;
     if (wgs > ((l.tiles + 7) & ~(int64_t)7)) wgs = (l.tiles + 7) & ~(int64_t)7;
     hipLaunchKernelGGL(pool_bwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, grad_out, argmax, in_off,
                        in_src, reinterpret_cast<const int32_t *>(base + l.cnt_off),
                        reinterpret_cast<const int32_t *>(base + l.rows_off),
-                       reinterpret_cast<const unsigned short *>(base + l.slot_off), grad_feat, N, N,
-                       l.tiles_per_cloud, (int)l.tiles);
+                       reinterpret_cast<const unsigned short *>(base + l.slot_off),
+                       reinterpret_cast<int *>(base + l.ctr_off), grad_feat, N, N, l.tiles_per_cloud, (int)l.tiles);
     return hipGetLastError();
 }
 
