@@ -203,7 +203,8 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  * every call): calls that share a plan must not overlap in time; nothing else of it is written after the build.
  * The plan depends on the lists only, not on the tensors: build it once per cloud.  It is dimensioned for the
  * paper's neighbourhood sizes (K = 8 or 9): a tile's plan holds up to 127 distinct centres and covers up to 512
- * list entries; what exceeds that is fetched entry by entry, correctly but without the saving.
+ * list entries; what exceeds that is fetched entry by entry, correctly but without the saving, and where more
+ * than an eighth of the tiles exceed it (point orders without locality) the call runs the list form instead.
  */
 #define FLEX_POOL_PLAN_MAX_K 12
 size_t flexpool_plan_bytes(int B, int N, int K);

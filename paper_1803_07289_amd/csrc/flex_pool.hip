@@ -325,14 +325,12 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_bnc4_kernel(
 // round (the same change does nothing for the forward pass, which is bound by HBM, not by instructions).
 // U = entries whose rows are requested together.
 template <int U>
-__global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
+__device__ __forceinline__ void pool_bwd_gather_row16_tile(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
-    float *__restrict__ grad_feat, int64_t BN, int N, int L, int C4, int PT, int64_t total_tiles)
+    float *__restrict__ grad_feat, int64_t BN, int N, int L, int C4, int PT, int64_t tile)
 {
     static_assert(U == 2 || U == 4, "batches tile the 16 entries of one load");
-    const int64_t tile = xcd_tile(total_tiles);
-    if (tile < 0) return;
     const int t16 = threadIdx.x & 15;
     for (int i = threadIdx.x; i < PT * C4; i += 256) {
         const int c4 = i % C4;
@@ -383,11 +381,26 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
     }
 }
 
+template <int U>
+__global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax,
+    const int32_t *__restrict__ in_off, const int32_t *__restrict__ in_src,
+    float *__restrict__ grad_feat, int64_t BN, int N, int L, int C4, int PT, int64_t total_tiles)
+{
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    pool_bwd_gather_row16_tile<U>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tile);
+}
+
 // ---- gather form with a static plan (C == 64, point-major) ---------------------------------------------------
 // Neighbouring points are listed by mostly the same centres: the 32 consecutive points of a tile have about 256
 // list entries but only about 94 distinct source rows, and the kernels above ask the texture path for a row's
 // 512 bytes (winner table + gradient) once per entry.  The neighbourhoods are static (Sec. 4.1), so which rows a
 // tile needs and where each list entry finds its row can be written down once per cloud: the plan.
+//   hdr  int32 [1] (+ padding)   the number of tiles the plan does not cover in full (the two kinds below).  Where
+//                                 they are more than an eighth of all tiles (a cloud whose point order has no
+//                                 locality: every tile of 32 points is listed by some 250 distinct centres) the
+//                                 planned kernel returns at once and the list form runs in its place
 //   cnt  int32 [tiles]            distinct source rows of the tile that are listed (at most RMAX - 1), + PLAN_HAS_DIRECT
 //                                 if some entry's row is not among them; or -1: a tile with more than EMAX list
 //                                 entries, which the kernel serves entry by entry
@@ -404,9 +417,14 @@ constexpr unsigned PLAN_NULL = PLAN_RMAX - 1, PLAN_DIRECT = 0x7fffu;
 constexpr int PLAN_HAS_DIRECT = 1 << 30;
 constexpr int PLAN_CTR_STRIDE = 64;     // ints between the XCDs' counters: a 256-byte block each
 constexpr int PLAN_DRAW = 4;            // tiles a workgroup draws at a time
+// the plan pays where most tiles are covered in full
+__device__ __forceinline__ bool pool_plan_pays(const int32_t *plan_hdr, int total_tiles)
+{
+    return (int64_t)plan_hdr[0] * 8 <= total_tiles;
+}
 
 struct PoolPlanLayout {
-    size_t cnt_off, rows_off, slot_off, ctr_off, bytes;
+    size_t hdr_off, cnt_off, rows_off, slot_off, ctr_off, bytes;
     int tiles_per_cloud;
     int64_t tiles;
 };
@@ -416,8 +434,9 @@ static PoolPlanLayout pool_plan_layout(int B, int N, int K)
     l.tiles_per_cloud = (N + PLAN_T - 1) / PLAN_T;
     l.tiles = (int64_t)B * l.tiles_per_cloud;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    l.cnt_off = 0;
-    l.rows_off = up(sizeof(int32_t) * (size_t)l.tiles);
+    l.hdr_off = 0;
+    l.cnt_off = 256;
+    l.rows_off = l.cnt_off + up(sizeof(int32_t) * (size_t)l.tiles);
     l.slot_off = l.rows_off + up(sizeof(int32_t) * (size_t)l.tiles * PLAN_RMAX);
     l.ctr_off = l.slot_off + up(sizeof(unsigned short) * (size_t)B * K * N);
     l.bytes = l.ctr_off + 8 * PLAN_CTR_STRIDE * sizeof(int32_t);   // tile counters of the kernel, one per XCD
@@ -430,6 +449,7 @@ size_t pool_plan_bytes(int B, int N, int K) { return pool_plan_layout(B, N, K).b
 // leaders are numbered by a prefix sum over the block.
 __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__restrict__ in_off,
                                                               const int32_t *__restrict__ in_src,
+                                                              int32_t *__restrict__ plan_hdr,
                                                               int32_t *__restrict__ plan_cnt,
                                                               int32_t *__restrict__ plan_rows,
                                                               unsigned short *__restrict__ plan_slot, int N,
@@ -454,7 +474,10 @@ __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__r
     const int E0 = s_off[0], E = s_off[T] - E0;
     if (E > EMAX) {
         for (int r = tid; r < RMAX; r += 256) plan_rows[tile * RMAX + r] = 0;
-        if (tid == 0) plan_cnt[tile] = -1;
+        if (tid == 0) {
+            plan_cnt[tile] = -1;
+            atomicAdd(plan_hdr, 1);
+        }
         return;
     }
     if (tid < T && s_off[tid + 1] > s_off[tid]) s_start[s_off[tid] - E0] = 1;
@@ -515,7 +538,10 @@ __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__r
     const int any_direct = __syncthreads_or(direct);
     const int listed_rows = min(R, RMAX - 1);
     for (int r = listed_rows + tid; r < RMAX; r += 256) plan_rows[tile * RMAX + r] = 0;
-    if (tid == 0) plan_cnt[tile] = listed_rows | (any_direct ? PLAN_HAS_DIRECT : 0);
+    if (tid == 0) {
+        plan_cnt[tile] = listed_rows | (any_direct ? PLAN_HAS_DIRECT : 0);
+        if (any_direct) atomicAdd(plan_hdr, 1);
+    }
 }
 
 hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, void *plan, int B, int N, int K,
@@ -524,8 +550,10 @@ hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, 
     const PoolPlanLayout l = pool_plan_layout(B, N, K);
     if (l.tiles > 0x7fffffff) return hipErrorInvalidValue;
     char *base = reinterpret_cast<char *>(plan);
+    const hipError_t e = launch_fill_zero(base + l.hdr_off, 256, s);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(pool_plan_build_kernel, dim3((unsigned)l.tiles), dim3(256), 0, s, in_off, in_src,
-                       reinterpret_cast<int32_t *>(base + l.cnt_off), reinterpret_cast<int32_t *>(base + l.rows_off),
+                       reinterpret_cast<int32_t *>(base + l.hdr_off), reinterpret_cast<int32_t *>(base + l.cnt_off), reinterpret_cast<int32_t *>(base + l.rows_off),
                        reinterpret_cast<unsigned short *>(base + l.slot_off), N, l.tiles_per_cloud);
     return hipGetLastError();
 }
@@ -547,11 +575,12 @@ __device__ __forceinline__ void pool_bwd_entry_direct(v4f &acc, const v4f *g4, c
 // The sums run in list order with the same operations as the kernels above: bit-identical results.
 __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
-    const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_cnt, const int32_t *__restrict__ plan_rows,
-    const unsigned short *__restrict__ plan_slot, int *__restrict__ tile_ctr, float *__restrict__ grad_feat, int N,
-    int L, int tiles_per_cloud, int total_tiles)
+    const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, const int32_t *__restrict__ plan_cnt,
+    const int32_t *__restrict__ plan_rows, const unsigned short *__restrict__ plan_slot, int *__restrict__ tile_ctr,
+    float *__restrict__ grad_feat, int N, int L, int tiles_per_cloud, int total_tiles)
 {
     constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 32;
+    if (!pool_plan_pays(plan_hdr, total_tiles)) return;      // (the same in every thread) the list form runs instead
     // a staged row: 16 x 16 bytes of the winner table, then 16 x 16 bytes of the gradient; place PLAN_NULL holds a
     // row that no point wins (index -1)
     __shared__ i4v s_r[RMAX * 32];
@@ -710,6 +739,20 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
     }
 }
 
+// The list form for the clouds whose plan does not pay: the same sums by the same code as flexpool_bwd's kernel, as a
+// grid of resident blocks that walk the tiles (a block that has nothing to do costs nothing to launch).
+__global__ __launch_bounds__(256) void pool_bwd_gather_row16_unplanned_kernel(
+    const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
+    const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, int plan_tiles,
+    float *__restrict__ grad_feat, int64_t BN, int N, int64_t total_tiles)
+{
+    if (pool_plan_pays(plan_hdr, plan_tiles)) return;
+    const int64_t per_xcd = (total_tiles + 7) >> 3;
+    const int64_t xbeg = (int64_t)(blockIdx.x & 7) * per_xcd, xend = min(xbeg + per_xcd, total_tiles);
+    for (int64_t tile = xbeg + (blockIdx.x >> 3); tile < xend; tile += gridDim.x >> 3)
+        pool_bwd_gather_row16_tile<4>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, N, 16, 16, tile);
+}
+
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
                                    const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K,
                                    hipStream_t s)
@@ -722,11 +765,19 @@ hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax,
     // two workgroups per CU by LDS and registers; fewer when there are fewer tiles than that
     int64_t wgs = 2 * 256;
     if (wgs > ((l.tiles + 7) & ~(int64_t)7)) wgs = (l.tiles + 7) & ~(int64_t)7;
+    const int32_t *hdr = reinterpret_cast<const int32_t *>(base + l.hdr_off);
     hipLaunchKernelGGL(pool_bwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, grad_out, argmax, in_off,
-                       in_src, reinterpret_cast<const int32_t *>(base + l.cnt_off),
+                       in_src, hdr, reinterpret_cast<const int32_t *>(base + l.cnt_off),
                        reinterpret_cast<const int32_t *>(base + l.rows_off),
                        reinterpret_cast<const unsigned short *>(base + l.slot_off),
                        reinterpret_cast<int *>(base + l.ctr_off), grad_feat, N, N, l.tiles_per_cloud, (int)l.tiles);
+    {
+        const int64_t BN = (int64_t)B * N, list_tiles = (BN + 15) / 16;
+        int64_t blocks = 8 * 256;
+        if (blocks > ((list_tiles + 7) & ~(int64_t)7)) blocks = (list_tiles + 7) & ~(int64_t)7;
+        hipLaunchKernelGGL(pool_bwd_gather_row16_unplanned_kernel, dim3((unsigned)blocks), dim3(256), 0, s, grad_out,
+                           argmax, in_off, in_src, hdr, (int)l.tiles, grad_feat, BN, N, list_tiles);
+    }
     return hipGetLastError();
 }
 

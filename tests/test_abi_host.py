@@ -75,9 +75,9 @@ def test_pooling_plan_size_and_errors_precede_any_launch(L):
     up = lambda x: (x + 255) // 256 * 256
     for B, N, K in ((1, 1, 1), (2, 33, 8), (1, 7_000_000, 8), (3, 4097, 16)):
         tiles = B * ((N + 31) // 32)
-        # distinct-row counts, 128 row places per tile of 32 points, one 16-bit place per list entry
+        # a header, distinct-row counts, 128 row places per tile of 32 points, one 16-bit place per list entry
         # ... and 2 KB of tile counters for the kernel
-        assert L.flexpool_plan_bytes(B, N, K) == up(4 * tiles) + up(4 * tiles * 128) + up(2 * B * K * N) + 2048
+        assert L.flexpool_plan_bytes(B, N, K) == 256 + up(4 * tiles) + up(4 * tiles * 128) + up(2 * B * K * N) + 2048
     assert L.flexpool_plan_bytes(1, 8, 9) == 0 and L.flexpool_plan_bytes(0, 8, 1) == 0
     need = L.flexpool_plan_bytes(1, 64, 2)
     assert L.flexpool_plan_build(none, one, 1, 64, 2, one, need, None) == 1

@@ -3,8 +3,9 @@ flexpool_bwd_planned): the result must equal the list form of flexpool_bwd bit f
 the CPU oracle within the pooling-backward tolerance.  The cases reach every branch of the planned kernel: tiles
 whose rows are all staged, tiles with more distinct rows than the plan lists (entries fetched directly), tiles with
 more entries than the plan covers (served entry by entry), lists longer than a row group's sixteen slot words,
-repeated entries, ragged tails, several clouds, fewer tiles than workgroups; and the widths and layouts the plan
-has no kernel for, which run the list form.  (The 7M-point configuration: test_gpu_fullsize.py.)"""
+repeated entries, ragged tails, several clouds, fewer tiles than workgroups; clouds without locality, where the
+plan does not pay and the list form runs in the planned kernel's place; and the widths and layouts the plan has no
+kernel for, which run the list form.  (The 7M-point configuration: test_gpu_fullsize.py.)"""
 import ctypes
 
 import numpy as np
@@ -30,6 +31,11 @@ def lists(kind, rng, B, N, K):
         return near
     if kind == "long_list":              # one point listed by 40 centres: more than sixteen entries, tile still covered
         near[:, 0, 100:140] = 105
+        return near
+    if kind == "scattered":              # 150 centres from all over the cloud list points of one tile: more distinct
+        for b in range(B):               # rows than the plan lists, fewer entries than it covers
+            who = rng.choice(N, 150, replace=False)
+            near[b, 1, who] = rng.integers(320, 352, size=150)
         return near
     if kind == "repeats":                # every centre lists its first neighbour twice
         near[:, K - 1, :] = near[:, 0, :]
@@ -62,22 +68,27 @@ def run_case(seed, B, N, K, C, layout, kind):
     return plan
 
 
-@pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "repeats"])
+@pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "scattered", "repeats"])
 @pytest.mark.parametrize("B,N,K", [(1, 1, 1), (1, 31, 4), (2, 33, 8), (3, 1000, 8), (1, 5000, 16), (2, 4097, 9),
                                    (1, 70000, 8)])
 def test_planned_backward_equals_the_list_form(B, N, K, kind):
-    if kind in ("hub", "long_list") and N < 1000:
+    if kind in ("hub", "long_list", "scattered") and N < 1000:
         pytest.skip("needs a cloud with room for the construction")
     say(f"pool plan: B={B} N={N} K={K} lists={kind}")
     plan = run_case(100 * N + K, B, N, K, 64, fx.BNC, kind)
     # what the plan says about its tiles: every branch of the kernel is reached by some case
     tiles = B * ((N + 31) // 32)
-    cnt = plan[:4 * tiles].view(torch.int32).cpu().numpy()
-    say(f"  tiles {tiles}: not covered {int((cnt < 0).sum())}, with direct entries {int(((cnt >= 0) & (cnt >= 2 ** 30)).sum())}")
-    if kind == "hub":
-        assert (cnt < 0).any()
-    if kind == "random" and N >= 1000:
-        assert ((cnt >= 0) & (cnt >= 2 ** 30)).any()
+    cnt = plan[256:256 + 4 * tiles].view(torch.int32).cpu().numpy()
+    uncovered = int(plan[:4].view(torch.int32).item())
+    say(f"  tiles {tiles}: not covered {int((cnt < 0).sum())}, with direct entries {int(((cnt >= 0) & (cnt >= 2 ** 30)).sum())}"
+        f" -> {'list form' if uncovered * 8 > tiles else 'planned kernel'}")
+    assert uncovered == int(((cnt < 0) | (cnt >= 2 ** 30)).sum())
+    if kind == "hub":                    # a few tiles served entry by entry inside the planned kernel
+        assert (cnt < 0).any() and (K > 9 or uncovered * 8 <= tiles)
+    if kind == "scattered" and K <= 9:   # a few tiles with entries fetched directly inside the planned kernel
+        assert ((cnt >= 0) & (cnt >= 2 ** 30)).any() and uncovered * 8 <= tiles
+    if kind == "random" and N >= 1000:   # no locality at all: the plan does not pay, the list form runs
+        assert uncovered * 8 > tiles
     if kind == "local" and K <= 9:       # the paper's neighbourhood sizes: every row of every tile is staged
         assert (cnt >= 0).all() and (cnt < 2 ** 30).all()
 
