@@ -740,17 +740,29 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
 }
 
 // The list form for the clouds whose plan does not pay: the same sums by the same code as flexpool_bwd's kernel, as a
-// grid of resident blocks that walk the tiles (a block that has nothing to do costs nothing to launch).
+// grid of resident blocks (a block that has nothing to do costs nothing to launch) which draw the tiles of their
+// XCD's share in order, eight at a time, from a counter of their own beside the planned kernel's.
 __global__ __launch_bounds__(256) void pool_bwd_gather_row16_unplanned_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
     const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, int plan_tiles,
-    float *__restrict__ grad_feat, int64_t BN, int N, int64_t total_tiles)
+    int *__restrict__ tile_ctr, float *__restrict__ grad_feat, int64_t BN, int N, int total_tiles)
 {
+    constexpr int DRAW = 8;
     if (pool_plan_pays(plan_hdr, plan_tiles)) return;
-    const int64_t per_xcd = (total_tiles + 7) >> 3;
-    const int64_t xbeg = (int64_t)(blockIdx.x & 7) * per_xcd, xend = min(xbeg + per_xcd, total_tiles);
-    for (int64_t tile = xbeg + (blockIdx.x >> 3); tile < xend; tile += gridDim.x >> 3)
-        pool_bwd_gather_row16_tile<4>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, N, 16, 16, tile);
+    __shared__ int s_first;
+    const int per_xcd = (total_tiles + 7) >> 3;
+    const int xbeg = (int)(blockIdx.x & 7) * per_xcd;
+    const int xcount = min(per_xcd, total_tiles - xbeg);
+    int *ctr = tile_ctr + (blockIdx.x & 7) * PLAN_CTR_STRIDE + PLAN_CTR_STRIDE / 2;
+    for (;;) {
+        if (threadIdx.x == 0) s_first = atomicAdd(ctr, DRAW);
+        __syncthreads();
+        const int j0 = s_first;
+        __syncthreads();                 // everyone has read the draw before the next one replaces it
+        if (j0 >= xcount) return;
+        for (int j = j0; j < min(j0 + DRAW, xcount); ++j)
+            pool_bwd_gather_row16_tile<4>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, N, 16, 16, xbeg + j);
+    }
 }
 
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
@@ -773,10 +785,12 @@ hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax,
                        reinterpret_cast<int *>(base + l.ctr_off), grad_feat, N, N, l.tiles_per_cloud, (int)l.tiles);
     {
         const int64_t BN = (int64_t)B * N, list_tiles = (BN + 15) / 16;
+        if (list_tiles > 0x7fffffff - 64) return hipErrorInvalidValue;
         int64_t blocks = 8 * 256;
         if (blocks > ((list_tiles + 7) & ~(int64_t)7)) blocks = (list_tiles + 7) & ~(int64_t)7;
         hipLaunchKernelGGL(pool_bwd_gather_row16_unplanned_kernel, dim3((unsigned)blocks), dim3(256), 0, s, grad_out,
-                           argmax, in_off, in_src, hdr, (int)l.tiles, grad_feat, BN, N, list_tiles);
+                           argmax, in_off, in_src, hdr, (int)l.tiles, reinterpret_cast<int *>(base + l.ctr_off),
+                           grad_feat, BN, N, (int)list_tiles);
     }
     return hipGetLastError();
 }
