@@ -196,9 +196,10 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  *                         (B, N, K); plan: device memory, 256-byte aligned, owned by the caller, valid as long
  *                         as the lists are; FLEX_ERR_WORKSPACE if plan_bytes is too small;
  *   flexpool_bwd_planned  grad_feat of flexpool_bwd's list form, bit for bit (same sums in the same order);
- *                         point-major C == 64 with K <= FLEX_POOL_PLAN_MAX_K runs the planned kernel, every
- *                         other width, layout or K the list form itself.  grad_out / argmax / grad_feat as for
- *                         flexpool_bwd.
+ *                         point-major C == 64 with K <= FLEX_POOL_PLAN_MAX_K and at least
+ *                         FLEX_POOL_PLAN_MIN_POINTS points in all runs the planned kernel (that is where it is
+ *                         the faster one), everything else the list form itself.  grad_out / argmax / grad_feat
+ *                         as for flexpool_bwd.
  * The plan's last 2 KB are scratch of the kernel (the tile counters its workgroups draw from, cleared at
  * every call): calls that share a plan must not overlap in time; nothing else of it is written after the build.
  * The plan depends on the lists only, not on the tensors: build it once per cloud.  It is dimensioned for the
@@ -206,7 +207,8 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  * list entries; what exceeds that is fetched entry by entry, correctly but without the saving, and where more
  * than an eighth of the tiles exceed it (point orders without locality) the call runs the list form instead.
  */
-#define FLEX_POOL_PLAN_MAX_K 12
+#define FLEX_POOL_PLAN_MAX_K 10
+#define FLEX_POOL_PLAN_MIN_POINTS (1 << 19)
 size_t flexpool_plan_bytes(int B, int N, int K);
 int flexpool_plan_build(const int32_t *in_off, const int32_t *in_src, int B, int N, int K,
                         void *plan, size_t plan_bytes, void *stream);

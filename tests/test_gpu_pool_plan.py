@@ -5,7 +5,8 @@ whose rows are all staged, tiles with more distinct rows than the plan lists (en
 more entries than the plan covers (served entry by entry), lists longer than a row group's sixteen slot words,
 repeated entries, ragged tails, several clouds, fewer tiles than workgroups; clouds without locality, where the
 plan does not pay and the list form runs in the planned kernel's place; and the widths and layouts the plan has no
-kernel for, which run the list form.  (The 7M-point configuration: test_gpu_fullsize.py.)"""
+kernel for, which run the list form.  The planned kernel is chosen from 2^19 points on (the last two sizes);
+test_gpu_fallbacks.py runs this file once more with FLEX_POOL_PLAN=1, which selects it at every size.  (The 7M-point configuration: test_gpu_fullsize.py.)"""
 import ctypes
 
 import numpy as np
@@ -26,8 +27,8 @@ def lists(kind, rng, B, N, K):
     near = ((np.arange(N)[None, None, :] + rng.integers(-20, 21, size=(B, K, N))) % N).astype(np.int32)
     if kind == "local":
         return near
-    if kind == "hub":                    # one point listed by half the cloud: its tile has far more than 512 entries
-        near[:, 0, : N // 2] = min(7, N - 1)
+    if kind == "hub":                    # one point listed by half the cloud (at most 5000 centres): its tile has far more than 512 entries
+        near[:, 0, : min(N // 2, 5000)] = min(7, N - 1)
         return near
     if kind == "long_list":              # one point listed by 40 centres: more than sixteen entries, tile still covered
         near[:, 0, 100:140] = 105
@@ -70,7 +71,7 @@ def run_case(seed, B, N, K, C, layout, kind):
 
 @pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "scattered", "repeats"])
 @pytest.mark.parametrize("B,N,K", [(1, 1, 1), (1, 31, 4), (2, 33, 8), (3, 1000, 8), (1, 5000, 16), (2, 4097, 9),
-                                   (1, 70000, 8)])
+                                   (1, 70000, 8), (2, 300_001, 8), (1, 600_000, 9)])
 def test_planned_backward_equals_the_list_form(B, N, K, kind):
     if kind in ("hub", "long_list", "scattered") and N < 1000:
         pytest.skip("needs a cloud with room for the construction")
