@@ -53,3 +53,43 @@ def test_layer_step_replays_from_a_graph(cfg_i, n, widths):
             assert torch.equal(a, b), f"replay {r}"
         _ = fx.flexconv_fwd(feat, pos, nbr, theta, bias, layout=L)            # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_planned_pooling_backward_replays_from_a_graph():
+    """flexpool_bwd_planned = a fill kernel (its tile counters) and two kernels: capturable like the rest; a cloud
+    large enough for the planned kernel to be the one that runs."""
+    B, N, K, C = 1, 600_000, 8, 64
+    say(f"graph capture of the planned pooling backward, N={N}")
+    rng = np.random.default_rng(1)
+    nbr = dev(((np.arange(N)[None, None, :] + rng.integers(-20, 21, size=(B, K, N))) % N).astype(np.int32))
+    feat = torch.randn(B, N, C, device="cuda")
+    gpool = torch.randn_like(feat)
+    edges = fx.flex_inedges_build(nbr)
+    plan = fx.flexpool_plan_build(edges, B, N)
+
+    def step():
+        po, pa = fx.flexpool_fwd(feat, nbr, layout=fx.BNC)
+        return po, pa, fx.flexpool_bwd_planned(gpool, pa, edges, plan, layout=fx.BNC)
+
+    eager = [t.clone() for t in step()]
+    listed = fx.flexpool_bwd(gpool, eager[1], layout=fx.BNC, in_edges=edges)
+    torch.cuda.synchronize()
+    assert torch.equal(listed.view(torch.int32), eager[2].view(torch.int32))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        captured = step()
+    for r in range(3):
+        for t in captured:
+            t.fill_(7) if t.dtype == torch.int32 else t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(captured, eager):
+            assert torch.equal(a, b), f"replay {r}"
+        _ = fx.flexpool_bwd_planned(gpool, eager[1], edges, plan, layout=fx.BNC)    # eager work between the replays
+        torch.cuda.synchronize()

@@ -71,7 +71,7 @@ def run_case(seed, B, N, K, C, layout, kind):
 
 @pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "scattered", "repeats"])
 @pytest.mark.parametrize("B,N,K", [(1, 1, 1), (1, 31, 4), (2, 33, 8), (3, 1000, 8), (1, 5000, 16), (2, 4097, 9),
-                                   (1, 70000, 8), (2, 300_001, 8), (1, 600_000, 9)])
+                                   (1, 70000, 8), (2, 300_001, 8), (1, 600_000, 9), (64, 9001, 8)])
 def test_planned_backward_equals_the_list_form(B, N, K, kind):
     if kind in ("hub", "long_list", "scattered") and N < 1000:
         pytest.skip("needs a cloud with room for the construction")
