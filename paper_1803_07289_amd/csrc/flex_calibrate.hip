@@ -5,12 +5,15 @@
 
 namespace flex {
 
-// dst[i] = src[i], 16 bytes per lane and step, grid-stride: reads n16 * 16 bytes and writes as many
+// dst[i] = src[i], 16 bytes per thread, one block per 4 KB: reads n16 * 16 bytes and writes as many.  Blocks that
+// each move one piece and are dispatched in order keep the accesses of the whole chip in one narrow, advancing
+// window of memory: 6.2 TB/s on this part, where a resident grid striding over the buffer reaches 4.8-5.0 TB/s
+// (its blocks drift apart) and the runtime's own device-to-device copy 5.0 TB/s.
 __global__ __launch_bounds__(256) void calibrate_copy_kernel(const v4f *__restrict__ src, v4f *__restrict__ dst,
                                                              int64_t n16)
 {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
 }
 
 // iters x 4 independent chains of v_mfma_f32_16x16x32_f16 per wave, operands in registers: 16 waves per CU keep the
@@ -45,9 +48,10 @@ int flex_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream)
 {
     if (!src || !dst) return FLEX_ERR_NULL;
     if (bytes == 0 || (bytes & 15) != 0 || (((uintptr_t)src | (uintptr_t)dst) & 15) != 0) return FLEX_ERR_SHAPE;
-    const int grid = device_cu_count() * 8;
-    hipLaunchKernelGGL(calibrate_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const v4f *)src,
-                       (v4f *)dst, (int64_t)(bytes / 16));
+    const int64_t n16 = (int64_t)(bytes / 16), blocks = (n16 + 255) / 256;
+    if (blocks > 0x7fffffff) return FLEX_ERR_SHAPE;
+    hipLaunchKernelGGL(calibrate_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const v4f *)src, (v4f *)dst, n16);
     return hipGetLastError() == hipSuccess ? FLEX_OK : FLEX_ERR_HIP;
 }
 
