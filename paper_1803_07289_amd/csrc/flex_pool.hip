@@ -1,10 +1,12 @@
 // Flex-max-pooling (Sec. 4.1): per-neighbourhood maximum with the winning
 // point's index recorded for the backward pass.  Bandwidth-bound: the forward
-// pass gathers whole point-major rows (16 bytes per lane), the backward pass
-// scatters by the recorded index with fp32 atomic adds.
+// pass gathers whole point-major rows (16 bytes per lane); the backward pass
+// has three forms: a scatter by the recorded index with fp32 atomic adds (no
+// lists needed), a gather over the transposed neighbour lists (no atomics,
+// fixed order), and that gather through a static per-tile plan that fetches
+// every listing row once per 32 points.
 #include "flex_common.hpp"
 #include <type_traits>
-#include <cstdlib>
 
 namespace flex {
 
