@@ -196,7 +196,7 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  *                         (B, N, K); plan: device memory, 256-byte aligned, owned by the caller, valid as long
  *                         as the lists are; FLEX_ERR_WORKSPACE if plan_bytes is too small;
  *   flexpool_bwd_planned  grad_feat of flexpool_bwd's list form, bit for bit (same sums in the same order);
- *                         point-major C == 64 with K <= FLEX_POOL_PLAN_MAX_K and at least
+ *                         point-major C = 64, 128 or 256 with K <= FLEX_POOL_PLAN_MAX_K and at least
  *                         FLEX_POOL_PLAN_MIN_POINTS points in all runs the planned kernel (that is where it is
  *                         the faster one), everything else the list form itself.  grad_out / argmax / grad_feat
  *                         as for flexpool_bwd.

@@ -902,10 +902,10 @@ int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *gr
     if (plan_bytes < pool_plan_bytes(B, N, K) || (reinterpret_cast<uintptr_t>(plan) & 255)) return FLEX_ERR_WORKSPACE;
     // FLEX_POOL_PLAN=1: the planned kernel wherever it can run (any size, any K); =0: never; unset: where it is faster
     static const int mode = [] { const char *e = getenv("FLEX_POOL_PLAN"); return !e ? -1 : e[0] == '0' ? 0 : 1; }();
-    const bool can = layout == FLEX_LAYOUT_BNC && C == 64;
+    const bool can = layout == FLEX_LAYOUT_BNC && (C == 64 || C == 128 || C == 256);
     const bool pays = K <= FLEX_POOL_PLAN_MAX_K && (int64_t)B * N >= FLEX_POOL_PLAN_MIN_POINTS;
     if (can && (mode == 1 || (mode == -1 && pays)))
-        FLEX_HIP(launch_pool_bwd_planned(grad_out, argmax, in_off, in_src, plan, grad_feat, B, N, K,
+        FLEX_HIP(launch_pool_bwd_planned(grad_out, argmax, in_off, in_src, plan, grad_feat, B, N, K, C,
                                          (hipStream_t)stream));
     else        // widths and layouts the plan has no kernel for, sizes and list lengths it does not pay for: the list form, same sums
         FLEX_HIP(launch_pool_bwd_gather(grad_out, argmax, in_off, in_src, grad_feat, B, N, C,

@@ -149,12 +149,12 @@ hipError_t launch_pool_sub_fwd(const float *feat, const int32_t *nbr, const int3
                                int32_t *argmax, int B, int N, int Ns, int K, int C, int bnc, hipStream_t s);
 hipError_t launch_pool_sub_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat, int B,
                                int N, int L, int C, int bnc, hipStream_t s);
-// static gather plan of the pooling backward pass (point-major, C == 64)
+// static gather plan of the pooling backward pass (point-major, C = 64, 128 or 256)
 size_t pool_plan_bytes(int B, int N, int K);
 hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, void *plan, int B, int N, int K,
                                   hipStream_t s);
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
-                                   const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K,
+                                   const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K, int C,
                                    hipStream_t s);
 hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
                                       const int32_t *in_src, float *grad_feat, int B, int N, int L, int C,

@@ -561,10 +561,11 @@ hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, 
 }
 
 // The sums of one point, entry by entry from memory (tiles and entries the plan does not cover).
-__device__ __forceinline__ void pool_bwd_entry_direct(v4f &acc, const v4f *g4, const int4 *a4, int l, bool fresh, int m)
+__device__ __forceinline__ void pool_bwd_entry_direct(v4f &acc, const v4f *g4, const int4 *a4, int l, bool fresh, int m,
+                                                      int rc)
 {
-    const int4 a = a4[(int64_t)l * 16];
-    const v4f g = g4[(int64_t)l * 16];
+    const int4 a = a4[(int64_t)l * rc];
+    const v4f g = g4[(int64_t)l * rc];
     acc.x += (fresh && a.x == m) ? g.x : 0.f;
     acc.y += (fresh && a.y == m) ? g.y : 0.f;
     acc.z += (fresh && a.z == m) ? g.z : 0.f;
@@ -579,8 +580,9 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
     const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, const int32_t *__restrict__ plan_cnt,
     const int32_t *__restrict__ plan_rows, const unsigned short *__restrict__ plan_slot, int *__restrict__ tile_ctr,
-    float *__restrict__ grad_feat, int N, int L, int tiles_per_cloud, int total_tiles)
+    float *__restrict__ grad_feat, int N, int L, int tiles_per_cloud, int total_tiles, int rc, int chunk0)
 {
+    // rc: 16-byte chunks per row of the tensors (C / 4); chunk0: first chunk of the 64-channel block this launch serves
     constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 32;
     if (!pool_plan_pays(plan_hdr, total_tiles)) return;      // (the same in every thread) the list form runs instead
     // a staged row: 16 x 16 bytes of the winner table, then 16 x 16 bytes of the gradient; place PLAN_NULL holds a
@@ -634,14 +636,14 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
         sw = t16 < bd.n ? plan_slot[(size_t)bd.e0 + t16] : PLAN_NULL;
     };
     auto issue_rows = [&](const Tc &c, int cnt, const int (&rid)[TRIPS]) __attribute__((always_inline)) {
-        const i4v *gb = reinterpret_cast<const i4v *>(grad_out) + (int64_t)c.b * L * 16 + c4;
-        const i4v *ab = reinterpret_cast<const i4v *>(argmax) + (int64_t)c.b * L * 16 + c4;
+        const i4v *gb = reinterpret_cast<const i4v *>(grad_out) + (int64_t)c.b * L * rc + chunk0 + c4;
+        const i4v *ab = reinterpret_cast<const i4v *>(argmax) + (int64_t)c.b * L * rc + chunk0 + c4;
         const int rows = cnt < 0 ? 0 : (cnt & (PLAN_HAS_DIRECT - 1));
 #pragma unroll
         for (int q = 0; q < TRIPS; ++q)
             if (q * 32 + p < rows) {
-                a[q] = ab[(int64_t)rid[q] * 16];
-                g[q] = gb[(int64_t)rid[q] * 16];
+                a[q] = ab[(int64_t)rid[q] * rc];
+                g[q] = gb[(int64_t)rid[q] * rc];
             }
     };
     Tc t0 = tile_at(0), t1 = tile_at(1), t2 = tile_at(2), t3 = tile_at(3);
@@ -721,8 +723,8 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
                     take_staged(plan_slot[(size_t)bd.e0 + j]);
             } else {
                 // a tile the plan covers in part or not at all: entry by entry
-                const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + (int64_t)b * L * 16 + c4;
-                const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + (int64_t)b * L * 16 + c4;
+                const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + (int64_t)b * L * rc + chunk0 + c4;
+                const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + (int64_t)b * L * rc + chunk0 + c4;
                 int prev = -1;
                 for (int j = 0; j < bd.n; ++j) {
                     const unsigned place = cnt < 0 ? PLAN_DIRECT : plan_slot[(size_t)bd.e0 + j];
@@ -730,12 +732,12 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
                         take_staged(place);
                     } else {
                         const int l = in_src[bd.e0 + j];
-                        pool_bwd_entry_direct(acc, g4, a4, l, l != prev, m);
+                        pool_bwd_entry_direct(acc, g4, a4, l, l != prev, m, rc);
                         prev = l;
                     }
                 }
             }
-            __builtin_nontemporal_store(acc, &reinterpret_cast<v4f *>(grad_feat)[((int64_t)b * N + m) * 16 + c4]);
+            __builtin_nontemporal_store(acc, &reinterpret_cast<v4f *>(grad_feat)[((int64_t)b * N + m) * rc + chunk0 + c4]);
         }
         __syncthreads();        // every sum of tile i is done before the rows of tile i + 1 replace it
     }
@@ -747,7 +749,7 @@ __global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
 __global__ __launch_bounds__(256) void pool_bwd_gather_row16_unplanned_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
     const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, int plan_tiles,
-    int *__restrict__ tile_ctr, float *__restrict__ grad_feat, int64_t BN, int N, int total_tiles)
+    int *__restrict__ tile_ctr, float *__restrict__ grad_feat, int64_t BN, int N, int C4, int PT, int total_tiles)
 {
     constexpr int DRAW = 8;
     if (pool_plan_pays(plan_hdr, plan_tiles)) return;
@@ -763,36 +765,42 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_unplanned_kernel(
         __syncthreads();                 // everyone has read the draw before the next one replaces it
         if (j0 >= xcount) return;
         for (int j = j0; j < min(j0 + DRAW, xcount); ++j)
-            pool_bwd_gather_row16_tile<4>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, N, 16, 16, xbeg + j);
+            pool_bwd_gather_row16_tile<4>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, N, C4, PT, xbeg + j);
     }
 }
 
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
-                                   const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K,
+                                   const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K, int C,
                                    hipStream_t s)
 {
+    // C: 64, 128 or 256 (a multiple of 64 whose row fits one block of the list form); the planned kernel serves one
+    // 64-channel block of the rows per launch, each launch drawing its tiles afresh
     const PoolPlanLayout l = pool_plan_layout(B, N, K);
-    if (l.tiles > 0x7fffffff) return hipErrorInvalidValue;
+    if (l.tiles > 0x7fffffff || C % 64 != 0 || C > 256) return hipErrorInvalidValue;
     char *base = reinterpret_cast<char *>(plan);
-    const hipError_t e = launch_fill_zero(base + l.ctr_off, 8 * PLAN_CTR_STRIDE * sizeof(int32_t), s);
-    if (e != hipSuccess) return e;
+    const int32_t *hdr = reinterpret_cast<const int32_t *>(base + l.hdr_off);
     // two workgroups per CU by LDS and registers; fewer when there are fewer tiles than that
     int64_t wgs = 2 * 256;
     if (wgs > ((l.tiles + 7) & ~(int64_t)7)) wgs = (l.tiles + 7) & ~(int64_t)7;
-    const int32_t *hdr = reinterpret_cast<const int32_t *>(base + l.hdr_off);
-    hipLaunchKernelGGL(pool_bwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, grad_out, argmax, in_off,
-                       in_src, hdr, reinterpret_cast<const int32_t *>(base + l.cnt_off),
-                       reinterpret_cast<const int32_t *>(base + l.rows_off),
-                       reinterpret_cast<const unsigned short *>(base + l.slot_off),
-                       reinterpret_cast<int *>(base + l.ctr_off), grad_feat, N, N, l.tiles_per_cloud, (int)l.tiles);
+    for (int blk = 0; blk < C / 64; ++blk) {
+        const hipError_t e = launch_fill_zero(base + l.ctr_off, 8 * PLAN_CTR_STRIDE * sizeof(int32_t), s);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(pool_bwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, grad_out, argmax, in_off,
+                           in_src, hdr, reinterpret_cast<const int32_t *>(base + l.cnt_off),
+                           reinterpret_cast<const int32_t *>(base + l.rows_off),
+                           reinterpret_cast<const unsigned short *>(base + l.slot_off),
+                           reinterpret_cast<int *>(base + l.ctr_off), grad_feat, N, N, l.tiles_per_cloud, (int)l.tiles,
+                           C / 4, 16 * blk);
+    }
     {
-        const int64_t BN = (int64_t)B * N, list_tiles = (BN + 15) / 16;
+        const int C4 = C / 4, PT = 256 / C4;
+        const int64_t BN = (int64_t)B * N, list_tiles = (BN + PT - 1) / PT;
         if (list_tiles > 0x7fffffff - 64) return hipErrorInvalidValue;
         int64_t blocks = 8 * 256;
         if (blocks > ((list_tiles + 7) & ~(int64_t)7)) blocks = (list_tiles + 7) & ~(int64_t)7;
         hipLaunchKernelGGL(pool_bwd_gather_row16_unplanned_kernel, dim3((unsigned)blocks), dim3(256), 0, s, grad_out,
                            argmax, in_off, in_src, hdr, (int)l.tiles, reinterpret_cast<int *>(base + l.ctr_off),
-                           grad_feat, BN, N, (int)list_tiles);
+                           grad_feat, BN, N, C4, PT, (int)list_tiles);
     }
     return hipGetLastError();
 }

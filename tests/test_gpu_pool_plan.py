@@ -94,11 +94,18 @@ def test_planned_backward_equals_the_list_form(B, N, K, kind):
         assert (cnt >= 0).all() and (cnt < 2 ** 30).all()
 
 
-@pytest.mark.parametrize("C,layout,K", [(64, fx.BCN, 8), (32, fx.BNC, 8), (128, fx.BNC, 8), (5, fx.BCN, 8),
+@pytest.mark.parametrize("C,layout,K", [(64, fx.BCN, 8), (32, fx.BNC, 8), (192, fx.BNC, 8), (5, fx.BCN, 8),
                                         (64, fx.BNC, 13), (64, fx.BNC, 20)])
 def test_widths_layouts_and_list_lengths_without_a_planned_kernel_run_the_list_form(C, layout, K):
     say(f"pool plan, list form behind it: C={C} layout={layout} K={K}")
     run_case(7 + C + K, 2, 700, K, C, layout, "local")
+
+
+@pytest.mark.parametrize("kind", ["local", "hub", "scattered", "random"])
+@pytest.mark.parametrize("B,N,C", [(1, 3000, 128), (2, 1001, 256), (1, 530_000, 128)])
+def test_wider_rows_run_the_planned_kernel_once_per_64_channels(B, N, C, kind):
+    say(f"pool plan: B={B} N={N} C={C} lists={kind}")
+    run_case(N + C, B, N, 8, C, fx.BNC, kind)
 
 
 def test_plan_arguments_are_checked():
