@@ -71,10 +71,12 @@ def main():
                          "for the parameter gradients / the feature gradient alone; upsample = flex-upsampling from a "
                          "quarter of the points, bwd_pos = location gradient, pool_sub = pooling with subsampling to a "
                          "quarter of the points, idiss = importance sub-sampling of a quarter of the points, knn = the "
-                         "neighbour search, pool_bwd_list = flexpool_bwd over the in-edge lists alone; none of them is part "
+                         "neighbour search, pool_bwd_list = flexpool_bwd over the in-edge lists alone, pool_fwd_plain = flexpool_fwd "
+                         "without its gather plan; none of them is part "
                          "of the default step)")
     ap.add_argument("--no-pool-plan", action="store_true",
-                    help="flexpool_bwd through the in-edge lists alone instead of the static gather plan")
+                    help="flexpool_fwd and flexpool_bwd without their static gather plans (neighbour lists / in-edge "
+                         "lists alone)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture one step into a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -144,12 +146,22 @@ def main():
         ev1.record()
         torch.cuda.synchronize()
         pool_plan_ms = ev0.elapsed_time(ev1)
+    # ... and of the pooling forward pass (the same over the neighbour lists themselves)
+    pool_fwd_plan, pool_fwd_plan_ms = None, None
+    if ("pool_fwd" in ops or "pool_bwd" in ops) and not args.no_pool_plan:
+        pool_fwd_plan = fx.flexpool_fwd_plan_build(nbr)
+        torch.cuda.synchronize()
+        ev0.record()
+        pool_fwd_plan = fx.flexpool_fwd_plan_build(nbr)
+        ev1.record()
+        torch.cuda.synchronize()
+        pool_fwd_plan_ms = ev0.elapsed_time(ev1)
 
     names = [n for n in ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample", "bwd_pos", "pool_sub") if n in ops]
     state = {}
     OPS = ("fwd", "bwd", "pool_fwd", "pool_bwd", "upsample_fwd", "upsample_bwd", "bwd_pos",
            "pool_sub_fwd", "pool_sub_bwd", "idiss_phi", "idiss_sample", "knn", "bwd_params", "bwd_feat",
-           "pool_bwd_list")
+           "pool_bwd_list", "pool_fwd_plain")
     if "idiss" in ops:
         # random words for the stratified draw of a quarter of the points (Sec. 3.2), drawn once
         u_words = torch.from_numpy(np.random.default_rng([cfg.seed, 400]).integers(
@@ -181,7 +193,10 @@ def main():
             state["grads"] = fx.flexconv_bwd(feat, pos, nbr, theta, bias, g, layout=layout, in_edges=in_edges)
         mark()
         if "pool_fwd" in ops or "pool_bwd" in ops or "pool_bwd_list" in ops:
-            state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
+            if pool_fwd_plan is not None:
+                state["pool"] = fx.flexpool_fwd_planned(feat, nbr, pool_fwd_plan, layout=layout)
+            else:
+                state["pool"] = fx.flexpool_fwd(feat, nbr, layout=layout)
         mark()
         if "pool_bwd" in ops:
             if pool_plan is not None:
@@ -226,6 +241,9 @@ def main():
         # the pooling backward pass over the lists alone, beside the planned form of the step
         if "pool_bwd_list" in ops:
             state["pool_grad_list"] = fx.flexpool_bwd(gpool, state["pool"][1], layout=layout, in_edges=in_edges)
+        mark()
+        if "pool_fwd_plain" in ops:
+            state["pool_plain"] = fx.flexpool_fwd(feat, nbr, layout=layout)
         mark()
 
     # ---- measured peaks of this device: plain copy kernel, pure f16 matrix-op loop ----------
@@ -300,6 +318,7 @@ def main():
                 "pool_fwd": 4 * Din + 4 * K + 8 * Din,
                 "pool_bwd": 8 * Din + 4 * (K + 1) + 4 * Din,
                 "pool_bwd_list": 8 * Din + 4 * (K + 1) + 4 * Din,
+                "pool_fwd_plain": 4 * Din + 4 * K + 8 * Din,
                 # per point of the larger layer, smaller layer = a quarter of it: rows of the smaller layer,
                 # sel, inverse map (written, read), ids, out + winners / gradient + winners, lists, smaller rows
                 "upsample_fwd": Din + 1 + 8 + 4 * K + 8 * Din,
@@ -316,7 +335,10 @@ def main():
                          else "grad_theta kernel + grad_feat kernel (flexconv_bwd)"),
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
-                 "pool_fwd": "pool_fwd_bnc4_kernel (flexpool_fwd)",
+                 "pool_fwd": ("pool_fwd_planned64_kernel (flexpool_fwd_planned)"
+                              if pool_fwd_plan is not None and layout == fx.BNC and Din in (64, 128, 256) and K <= 10 and B * N >= (1 << 19)
+                              else "pool_fwd_bnc4_kernel (flexpool_fwd)"),
+                 "pool_fwd_plain": "pool_fwd_bnc4_kernel (flexpool_fwd)",
                  "pool_bwd": ("pool_bwd_planned64_kernel (flexpool_bwd_planned)"
                               if pool_plan is not None and layout == fx.BNC and Din in (64, 128, 256) and K <= 10 and B * N >= (1 << 19)
                               else "pool_bwd_gather_row16_kernel (flexpool_bwd)"),
@@ -384,6 +406,14 @@ def main():
             parity = dict(parity or {}, grad_feat_sampled_max_rel_err=float(np.max(np.abs(rows_g - ref) / den)),
                           grad_feat_rows=int(targets.size))
 
+        if pool_fwd_plan is not None and "pool" in state:
+            # the planned pooling forward of the timed call against the plain kernel (which the full-size GPU tests
+            # compare with the oracle element by element): the same comparisons in the same order, so the same bits
+            plain = fx.flexpool_fwd(feat, nbr, layout=layout)
+            parity = dict(parity or {}, pool_fwd_planned_equals_plain=bool(
+                torch.equal(plain[0].view(torch.int32), state["pool"][0].view(torch.int32))
+                and torch.equal(plain[1], state["pool"][1])))
+            del plain
         if "pool_bwd" in ops and pool_plan is not None and "pool_grad" in state:
             # the planned pooling backward of the timed call against the list form (which the full-size GPU tests
             # compare with the oracle element by element): the same sums in the same order, so the same bits
@@ -453,7 +483,8 @@ def main():
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "B": B, "N": N, "K": K, "Din": Din,
                    "Dout": Dout, "layout": args.layout, "point_order": x.order, "ops": names,
                    "in_edges": "prebuilt once (static neighbourhoods)",
-                   "pool_plan": ("prebuilt once (static neighbourhoods)" if pool_plan is not None else "not used")},
+                   "pool_plan": ("prebuilt once (static neighbourhoods)" if pool_plan is not None else "not used"),
+                   "pool_fwd_plan": ("prebuilt once (static neighbourhoods)" if pool_fwd_plan is not None else "not used")},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "measured_peaks": measured_peaks,
@@ -463,6 +494,8 @@ def main():
         "inedges_build_ms": inedges_ms,
         "pool_plan_build_ms": pool_plan_ms,
         "pool_plan_bytes": int(pool_plan.numel()) if pool_plan is not None else None,
+        "pool_fwd_plan_build_ms": pool_fwd_plan_ms,
+        "pool_fwd_plan_bytes": int(pool_fwd_plan.numel()) if pool_fwd_plan is not None else None,
         "graph_ms_per_step": graph_ms,
         "fwd_points_per_s": pts / (fwd_ms * 1e-3) if fwd_ms > 0 else None,
         "fwd_effective_GFLOPs_direct_form": direct_flop_pt * pts / (fwd_ms * 1e-3) / 1e9 if fwd_ms > 0 else None,

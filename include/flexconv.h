@@ -209,6 +209,29 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  */
 #define FLEX_POOL_PLAN_MAX_K 10
 #define FLEX_POOL_PLAN_MIN_POINTS (1 << 19)
+
+/*
+ * Flex-max-pooling forward with a static gather plan: the same idea for the forward pass (Sec. 4.1; Table 1: it
+ * writes the output and the same-sized winner table).  The plan is over the neighbour lists themselves: per tile of
+ * 32 consecutive centres the distinct points they list (about three per centre where a centre lists eight), per
+ * (centre, slot) the place of its point among them; the kernel fetches each distinct row once per tile.  Same size
+ * and layout as the backward plan (flexpool_plan_bytes serves both), different content: a plan serves only the pass
+ * whose build call wrote it.
+ *   flexpool_fwd_plan_build  writes the plan for nbr [B,K,N] (device; entries in [0,N): flex_validate_neighbors);
+ *                            plan: device, 256-byte aligned, plan_bytes >= flexpool_plan_bytes(B,N,K), owned by the
+ *                            caller, valid while nbr is unchanged.
+ *   flexpool_fwd_planned     out / argmax of flexpool_fwd, bit for bit (the same comparisons in the same slot order);
+ *                            arguments as flexpool_fwd, plus the plan.  The planned kernel runs under the conditions
+ *                            of flexpool_bwd_planned (point-major, C = 64 / 128 / 256, K <= FLEX_POOL_PLAN_MAX_K,
+ *                            B N >= FLEX_POOL_PLAN_MIN_POINTS, a cloud whose tiles the plan covers), else
+ *                            flexpool_fwd's own kernels.  The call only reads the plan: forward calls that
+ *                            share one may overlap.
+ * Errors: FLEX_ERR_NULL, FLEX_ERR_SHAPE as flexpool_fwd; FLEX_ERR_WORKSPACE for a plan that is too small or
+ * misaligned; nothing is launched then.
+ */
+int flexpool_fwd_plan_build(const int32_t *nbr, int B, int N, int K, void *plan, size_t plan_bytes, void *stream);
+int flexpool_fwd_planned(const float *feat, const int32_t *nbr, float *out, int32_t *argmax,
+                         void *plan, size_t plan_bytes, int B, int N, int K, int C, int layout, void *stream);
 size_t flexpool_plan_bytes(int B, int N, int K);
 int flexpool_plan_build(const int32_t *in_off, const int32_t *in_src, int B, int N, int K,
                         void *plan, size_t plan_bytes, void *stream);

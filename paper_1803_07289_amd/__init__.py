@@ -36,6 +36,8 @@ _SIGS = {
     "flexpool_plan_bytes": (_sz, [_i] * 3),
     "flexpool_plan_build": (_i, [_vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
     "flexpool_bwd_planned": (_i, [_vp] * 6 + [_sz] + [_i] * 5 + [_vp]),
+    "flexpool_fwd_plan_build": (_i, [_vp, _i, _i, _i, _vp, _sz, _vp]),
+    "flexpool_fwd_planned": (_i, [_vp] * 5 + [_sz] + [_i] * 5 + [_vp]),
     "flexconv_bwd_pos": (_i, [_vp] * 7 + [_i] * 6 + [_vp, _sz, _vp]),
     "flexconv_compose_1x1": (_i, [_vp] * 5 + [_i] * 3 + [_vp]),
     "flexconv_compose_1x1_bwd": (_i, [_vp] * 8 + [_i] * 3 + [_vp]),
@@ -319,6 +321,36 @@ def flexpool_plan_build(in_edges, B, N):
     plan = torch.empty(need, dtype=torch.uint8, device=off.device)
     _check(lib().flexpool_plan_build(_ptr(off), _ptr(src), B, N, K, _ptr(plan), need, _stream()), "flexpool_plan_build")
     return plan
+
+
+def flexpool_fwd_plan_build(nbr):
+    """Static gather plan of the pooling forward pass for nbr [B,K,N]: a uint8 device tensor to pass to
+    flexpool_fwd_planned.  Depends on nbr only: build once per cloud."""
+    _dev(nbr, torch.int32, "nbr")
+    B, K, N = nbr.shape
+    need = int(lib().flexpool_plan_bytes(B, N, K))
+    if need == 0:
+        raise ValueError("sizes out of range")
+    plan = torch.empty(need, dtype=torch.uint8, device=nbr.device)
+    _check(lib().flexpool_fwd_plan_build(_ptr(nbr), B, N, K, _ptr(plan), need, _stream()), "flexpool_fwd_plan_build")
+    return plan
+
+
+def flexpool_fwd_planned(feat, nbr, plan, layout=BCN):
+    """Flex-max-pooling forward through the static gather plan: (out, argmax) of flexpool_fwd, bit for bit."""
+    layout = _layout(layout)
+    _dev(feat, torch.float32, "feat"); _dev(nbr, torch.int32, "nbr"); _dev(plan, torch.uint8, "plan")
+    if feat.dim() != 3 or nbr.dim() != 3 or nbr.shape[0] != feat.shape[0]:
+        raise ValueError("feat must be 3-D and nbr [B,K,N]")
+    B, K, N = nbr.shape
+    C = feat.shape[1] if layout == BCN else feat.shape[2]
+    if (feat.shape[2] if layout == BCN else feat.shape[1]) != N:
+        raise ValueError("feat and nbr disagree about N")
+    out = torch.empty_like(feat)
+    argmax = torch.empty(feat.shape, dtype=torch.int32, device=feat.device)
+    _check(lib().flexpool_fwd_planned(_ptr(feat), _ptr(nbr), _ptr(out), _ptr(argmax), _ptr(plan), plan.numel(),
+                                      B, N, K, C, layout, _stream()), "flexpool_fwd_planned")
+    return out, argmax
 
 
 def flexpool_bwd_planned(grad_out, argmax, in_edges, plan, layout=BCN):

@@ -876,6 +876,13 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
     return FLEX_OK;
 }
 
+// FLEX_POOL_PLAN=1: the planned kernels wherever they can run (any size, any K); =0: never; unset: where they are faster
+static int pool_plan_mode()
+{
+    static const int mode = [] { const char *e = getenv("FLEX_POOL_PLAN"); return !e ? -1 : e[0] == '0' ? 0 : 1; }();
+    return mode;
+}
+
 size_t flexpool_plan_bytes(int B, int N, int K)
 {
     if (!sizes_ok(B, N, K, 1, 1)) return 0;
@@ -900,8 +907,7 @@ int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *gr
     if (!sizes_ok(B, N, K, C, 1)) return FLEX_ERR_SHAPE;
     if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
     if (plan_bytes < pool_plan_bytes(B, N, K) || (reinterpret_cast<uintptr_t>(plan) & 255)) return FLEX_ERR_WORKSPACE;
-    // FLEX_POOL_PLAN=1: the planned kernel wherever it can run (any size, any K); =0: never; unset: where it is faster
-    static const int mode = [] { const char *e = getenv("FLEX_POOL_PLAN"); return !e ? -1 : e[0] == '0' ? 0 : 1; }();
+    const int mode = pool_plan_mode();
     const bool can = layout == FLEX_LAYOUT_BNC && (C == 64 || C == 128 || C == 256);
     const bool pays = K <= FLEX_POOL_PLAN_MAX_K && (int64_t)B * N >= FLEX_POOL_PLAN_MIN_POINTS;
     if (can && (mode == 1 || (mode == -1 && pays)))
@@ -910,6 +916,32 @@ int flexpool_bwd_planned(const float *grad_out, const int32_t *argmax, float *gr
     else        // widths and layouts the plan has no kernel for, sizes and list lengths it does not pay for: the list form, same sums
         FLEX_HIP(launch_pool_bwd_gather(grad_out, argmax, in_off, in_src, grad_feat, B, N, C,
                                         layout == FLEX_LAYOUT_BNC, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexpool_fwd_plan_build(const int32_t *nbr, int B, int N, int K, void *plan, size_t plan_bytes, void *stream)
+{
+    if (!nbr || !plan) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, 1, 1)) return FLEX_ERR_SHAPE;
+    if (plan_bytes < pool_plan_bytes(B, N, K) || (reinterpret_cast<uintptr_t>(plan) & 255)) return FLEX_ERR_WORKSPACE;
+    FLEX_HIP(launch_pool_fwd_plan_build(nbr, plan, B, N, K, (hipStream_t)stream));
+    return FLEX_OK;
+}
+
+int flexpool_fwd_planned(const float *feat, const int32_t *nbr, float *out, int32_t *argmax, void *plan,
+                         size_t plan_bytes, int B, int N, int K, int C, int layout, void *stream)
+{
+    if (!feat || !nbr || !out || !argmax || !plan) return FLEX_ERR_NULL;
+    if (!sizes_ok(B, N, K, C, 1)) return FLEX_ERR_SHAPE;
+    if (layout != FLEX_LAYOUT_BCN && layout != FLEX_LAYOUT_BNC) return FLEX_ERR_SHAPE;
+    if (plan_bytes < pool_plan_bytes(B, N, K) || (reinterpret_cast<uintptr_t>(plan) & 255)) return FLEX_ERR_WORKSPACE;
+    const int mode = pool_plan_mode();
+    const bool can = layout == FLEX_LAYOUT_BNC && (C == 64 || C == 128 || C == 256);
+    const bool pays = K <= FLEX_POOL_PLAN_MAX_K && (int64_t)B * N >= FLEX_POOL_PLAN_MIN_POINTS;
+    if (can && (mode == 1 || (mode == -1 && pays)))
+        FLEX_HIP(launch_pool_fwd_planned(feat, nbr, plan, out, argmax, B, N, K, C, (hipStream_t)stream));
+    else
+        FLEX_HIP(launch_pool_fwd(feat, nbr, out, argmax, B, N, K, C, layout == FLEX_LAYOUT_BNC, (hipStream_t)stream));
     return FLEX_OK;
 }
 

@@ -156,6 +156,9 @@ hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, 
 hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
                                    const int32_t *in_src, void *plan, float *grad_feat, int B, int N, int K, int C,
                                    hipStream_t s);
+hipError_t launch_pool_fwd_plan_build(const int32_t *nbr, void *plan, int B, int N, int K, hipStream_t s);
+hipError_t launch_pool_fwd_planned(const float *feat, const int32_t *nbr, void *plan, float *out, int32_t *argmax,
+                                   int B, int N, int K, int C, hipStream_t s);
 hipError_t launch_pool_sub_bwd_gather(const float *grad_out, const int32_t *argmax, const int32_t *in_off,
                                       const int32_t *in_src, float *grad_feat, int B, int N, int L, int C,
                                       int bnc, hipStream_t s);

@@ -42,17 +42,12 @@ static inline unsigned xcd_grid(int64_t total_tiles) { return (unsigned)(((total
 // rows (16 bytes each), and only then compares: 8 rows per lane are in flight instead of one.
 // SUB: pooling with subsampling, only the kept centres sel[b,j] are evaluated (BN = B*Ns output rows).
 template <bool SUB>
-__global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restrict__ feat,
-                                                            const int32_t *__restrict__ nbr,
-                                                            const int32_t *__restrict__ sel,
-                                                            float *__restrict__ out,
-                                                            int32_t *__restrict__ argmax, int64_t BN,
-                                                            int N, int Ns, int K, int C4, int PT,
-                                                            int64_t total_tiles)
+__device__ __forceinline__ void pool_fwd_bnc4_tile(const float *__restrict__ feat, const int32_t *__restrict__ nbr,
+                                                   const int32_t *__restrict__ sel, float *__restrict__ out,
+                                                   int32_t *__restrict__ argmax, int64_t BN, int N, int Ns, int K,
+                                                   int C4, int PT, int64_t tile)
 {
     constexpr int U = 8;
-    const int64_t tile = xcd_tile(total_tiles);
-    if (tile < 0) return;
     for (int i = threadIdx.x; i < PT * C4; i += 256) {
         const int c4 = i % C4;
         const int64_t gp = tile * PT + i / C4;
@@ -93,6 +88,20 @@ __global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restr
         const i4v bi = {b0, b1, b2, b3};
         __builtin_nontemporal_store(bi, &reinterpret_cast<i4v *>(argmax)[gp * C4 + c4]);
     }
+}
+
+template <bool SUB>
+__global__ __launch_bounds__(256) void pool_fwd_bnc4_kernel(const float *__restrict__ feat,
+                                                            const int32_t *__restrict__ nbr,
+                                                            const int32_t *__restrict__ sel,
+                                                            float *__restrict__ out,
+                                                            int32_t *__restrict__ argmax, int64_t BN,
+                                                            int N, int Ns, int K, int C4, int PT,
+                                                            int64_t total_tiles)
+{
+    const int64_t tile = xcd_tile(total_tiles);
+    if (tile < 0) return;
+    pool_fwd_bnc4_tile<SUB>(feat, nbr, sel, out, argmax, BN, N, Ns, K, C4, PT, tile);
 }
 
 // value of lane SRC of the caller's 16-lane row (all 16 lanes must be active)
@@ -449,12 +458,16 @@ size_t pool_plan_bytes(int B, int N, int K) { return pool_plan_layout(B, N, K).b
 // One block per tile.  Every entry writes its own number into a table slot chosen by a hash of its row, reads back
 // which entry kept the slot and follows it if that one names the same row (else it stays its own leader); the
 // leaders are numbered by a prefix sum over the block.
+// FWD == false: the tile's entries are the in-edge lists of its points (in_off / in_src; the pooling backward pass).
+// FWD == true: they are the neighbour lists themselves, entry p * K + k = nbr[b, k, m0 + p] (in_src = nbr, in_off
+// unused; the pooling forward pass): K entries per point, no repeats to mark (a maximum does not mind them).
+template <bool FWD>
 __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__restrict__ in_off,
                                                               const int32_t *__restrict__ in_src,
                                                               int32_t *__restrict__ plan_hdr,
                                                               int32_t *__restrict__ plan_cnt,
                                                               int32_t *__restrict__ plan_rows,
-                                                              unsigned short *__restrict__ plan_slot, int N,
+                                                              unsigned short *__restrict__ plan_slot, int N, int K,
                                                               int tiles_per_cloud)
 {
     constexpr int T = PLAN_T, RMAX = PLAN_RMAX, EMAX = PLAN_EMAX, HASH = PLAN_HASH;
@@ -469,11 +482,13 @@ __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__r
     const int m0 = (int)(tile - b * tiles_per_cloud) * T;
     const int np = min(T, N - m0);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    if (tid <= T) s_off[tid] = in_off[b * N + m0 + min(tid, np)];   // past the cloud: empty lists
+    if (tid <= T) s_off[tid] = FWD ? min(tid, np) * K : in_off[b * N + m0 + min(tid, np)];   // past the cloud: empty lists
     s_start[tid] = 0;
     s_start[tid + 256] = 0;
     __syncthreads();
-    const int E0 = s_off[0], E = s_off[T] - E0;
+    // first entry of the tile in the plan's slot array (backward: the lists' own order; forward: point by point)
+    const int64_t E0 = FWD ? (b * N + m0) * K : s_off[0];
+    const int E = s_off[T] - s_off[0];
     if (E > EMAX) {
         for (int r = tid; r < RMAX; r += 256) plan_rows[tile * RMAX + r] = 0;
         if (tid == 0) {
@@ -482,13 +497,14 @@ __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__r
         }
         return;
     }
-    if (tid < T && s_off[tid + 1] > s_off[tid]) s_start[s_off[tid] - E0] = 1;
+    if (tid < T && s_off[tid + 1] > s_off[tid]) s_start[s_off[tid] - s_off[0]] = 1;
     int l[2], lead[2], rank[2];
     unsigned h[2];
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const int i = tid + 256 * r;
-        l[r] = i < E ? in_src[E0 + i] : -1;
+        if constexpr (FWD) l[r] = i < E ? in_src[(b * K + i % K) * N + m0 + i / K] : -1;
+        else l[r] = i < E ? in_src[E0 + i] : -1;
         h[r] = ((unsigned)l[r] * 0x9E3779B1u) >> 21;
         if (i < E) { s_l[i] = l[r]; s_tab[h[r]] = (unsigned short)i; }
     }
@@ -531,10 +547,10 @@ __global__ __launch_bounds__(256) void pool_plan_build_kernel(const int32_t *__r
         const int i = tid + 256 * r;
         if (i < E) {
             const unsigned place = s_rank[lead[r]];
-            const bool repeat = i > 0 && !s_start[i] && s_l[i - 1] == l[r];
+            const bool repeat = !FWD && i > 0 && !s_start[i] && s_l[i - 1] == l[r];
             const bool listed = place < (unsigned)(RMAX - 1);
             direct |= !repeat && !listed;
-            plan_slot[(size_t)E0 + i] = (unsigned short)(repeat ? PLAN_NULL : listed ? place : PLAN_DIRECT);
+            plan_slot[E0 + i] = (unsigned short)(repeat ? PLAN_NULL : listed ? place : PLAN_DIRECT);
         }
     }
     const int any_direct = __syncthreads_or(direct);
@@ -554,9 +570,25 @@ hipError_t launch_pool_plan_build(const int32_t *in_off, const int32_t *in_src, 
     char *base = reinterpret_cast<char *>(plan);
     const hipError_t e = launch_fill_zero(base + l.hdr_off, 256, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(pool_plan_build_kernel, dim3((unsigned)l.tiles), dim3(256), 0, s, in_off, in_src,
-                       reinterpret_cast<int32_t *>(base + l.hdr_off), reinterpret_cast<int32_t *>(base + l.cnt_off), reinterpret_cast<int32_t *>(base + l.rows_off),
-                       reinterpret_cast<unsigned short *>(base + l.slot_off), N, l.tiles_per_cloud);
+    hipLaunchKernelGGL(pool_plan_build_kernel<false>, dim3((unsigned)l.tiles), dim3(256), 0, s, in_off, in_src,
+                       reinterpret_cast<int32_t *>(base + l.hdr_off), reinterpret_cast<int32_t *>(base + l.cnt_off),
+                       reinterpret_cast<int32_t *>(base + l.rows_off),
+                       reinterpret_cast<unsigned short *>(base + l.slot_off), N, K, l.tiles_per_cloud);
+    return hipGetLastError();
+}
+
+// the plan of the forward pass: the same layout, over the neighbour lists themselves
+hipError_t launch_pool_fwd_plan_build(const int32_t *nbr, void *plan, int B, int N, int K, hipStream_t s)
+{
+    const PoolPlanLayout l = pool_plan_layout(B, N, K);
+    if (l.tiles > 0x7fffffff) return hipErrorInvalidValue;
+    char *base = reinterpret_cast<char *>(plan);
+    const hipError_t e = launch_fill_zero(base + l.hdr_off, 256, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(pool_plan_build_kernel<true>, dim3((unsigned)l.tiles), dim3(256), 0, s,
+                       (const int32_t *)nullptr, nbr, reinterpret_cast<int32_t *>(base + l.hdr_off),
+                       reinterpret_cast<int32_t *>(base + l.cnt_off), reinterpret_cast<int32_t *>(base + l.rows_off),
+                       reinterpret_cast<unsigned short *>(base + l.slot_off), N, K, l.tiles_per_cloud);
     return hipGetLastError();
 }
 
@@ -802,6 +834,185 @@ hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax,
                            argmax, in_off, in_src, hdr, (int)l.tiles, reinterpret_cast<int *>(base + l.ctr_off),
                            grad_feat, BN, N, C4, PT, (int)list_tiles);
     }
+    return hipGetLastError();
+}
+
+// ---- forward pass through a static plan (point-major, 64-channel blocks of the rows) ---------------------------
+// The same idea one pass earlier: the 32 consecutive centres of a tile list 32 K neighbours but only about 94
+// distinct ones; the plan (pool_plan_build_kernel<true>) names them and gives every (centre, slot) its place.  The
+// kernel stages each distinct feature row once in LDS together with its point index, and every centre takes the
+// (value desc, index asc) maximum over its K places: the comparisons of pool_fwd_bnc4_kernel in the same slot order,
+// so values and winners are the same bits.
+// Unlike the backward kernel this one is not resident: one workgroup per POOL_FWD_PLAN_TPW consecutive tiles,
+// dispatched in order (block index -> XCD share, position in it), four workgroups per CU (64 registers, 33 KB of
+// LDS each).  The chain plan -> rows -> LDS is two memory latencies deep and a tile's comparisons are short, so what
+// counts is how many tiles a CU has in flight: a workgroup asks for the plan and then the rows of both its tiles up
+// front (the second tile's rows wait in registers while the first is compared) and the four workgroups of a CU
+// cover each other's waits.  (A resident form with rows of two tiles ahead in registers, two workgroups per CU:
+// 1.68 ms at 7M points against 1.18 ms; one tile per workgroup 1.34 ms; three tiles at three workgroups 1.27 ms;
+// runs of four tile pairs per workgroup spill and take 2.1 ms.)
+// A cloud whose plan does not pay (pool_plan_pays) is served by the same workgroups with the plain kernel's steps,
+// a row group per centre; 7% slower there than pool_fwd_bnc4_kernel (2.39 against 2.22 ms in generator order), whose
+// workgroups are half as large and end after one tile.  The kernel only reads the plan.
+constexpr int POOL_FWD_PLAN_TPW = 2;
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(8, 8))) void pool_fwd_planned64_kernel(
+    const float *__restrict__ feat, const int32_t *__restrict__ nbr, const int32_t *__restrict__ plan_hdr,
+    const int32_t *__restrict__ plan_cnt, const int32_t *__restrict__ plan_rows,
+    const unsigned short *__restrict__ plan_slot, float *__restrict__ out,
+    int32_t *__restrict__ argmax, int N, int K, int tiles_per_cloud, int total_tiles, int rc, int chunk0)
+{
+    constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 32, U = POOL_FWD_PLAN_TPW;
+    __shared__ v4f s_v[RMAX * 16];
+    __shared__ int s_id[U][RMAX];
+    const int tid = threadIdx.x, c4 = tid & 15, t16 = tid & 15, p = tid >> 4;
+    const int per_xcd = (total_tiles + 7) >> 3;
+    const int xbeg = (int)(blockIdx.x & 7) * per_xcd;
+    const int xcount = min(per_xcd, total_tiles - xbeg);
+    const int j0 = (int)(blockIdx.x >> 3) * U;
+    if (j0 >= xcount) return;
+    const int uncovered = plan_hdr[0];               // asked for first, looked at once the plan's loads are under way
+    int tb[U], tm0[U], cnt[U], rid[U][TRIPS];
+    unsigned sw[U];
+    i4v v[U][TRIPS];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int tile = xbeg + min(j0 + u, xcount - 1);
+        tb[u] = tile / tiles_per_cloud;
+        tm0[u] = (tile - tb[u] * tiles_per_cloud) * T;
+        cnt[u] = plan_cnt[tile];
+        const int32_t *rows = plan_rows + (int64_t)tile * RMAX + p;
+#pragma unroll
+        for (int q = 0; q < TRIPS; ++q) rid[u][q] = rows[q * 32];     // (every place of the table is allocated: no wait for the count)
+        const int m = min(tm0[u] + p, N - 1);
+        sw[u] = plan_slot[((int64_t)tb[u] * N + m) * K + (t16 < K ? t16 : 0)];
+    }
+    if ((int64_t)uncovered * 8 > total_tiles) {          // pool_plan_pays()
+        // (the same in every thread) a cloud whose tiles the plan does not cover: the plain kernel's steps for the
+        // workgroup's centres, a row group per centre: eight ids, their eight rows, then the comparisons
+        for (int u = 0; u < U && j0 + u < xcount; ++u) {
+            const int tile = xbeg + j0 + u, b = tile / tiles_per_cloud, m = (tile - b * tiles_per_cloud) * T + p;
+            if (m >= N) continue;
+            const int32_t *nb = nbr + (int64_t)b * K * N + m;
+            const v4f *frow = reinterpret_cast<const v4f *>(feat) + (int64_t)b * N * rc + chunk0 + c4;
+            float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+            int b0 = 0, b1 = 0, b2 = 0, b3 = 0;
+            for (int k0 = 0; k0 < K; k0 += 8) {
+                int n[8];
+                v4f x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) n[i] = nb[(int64_t)min(k0 + i, K - 1) * N];     // past K: the last slot again
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = frow[(int64_t)n[i] * rc];
+                if (k0 == 0) {
+                    v0 = x[0].x; v1 = x[0].y; v2 = x[0].z; v3 = x[0].w;
+                    b0 = b1 = b2 = b3 = n[0];
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {       // a repeated pair never changes the winner
+                    take(x[i].x, n[i], v0, b0);
+                    take(x[i].y, n[i], v1, b1);
+                    take(x[i].z, n[i], v2, b2);
+                    take(x[i].w, n[i], v3, b3);
+                }
+            }
+            const int64_t at = ((int64_t)b * N + m) * rc + chunk0 + c4;
+            __builtin_nontemporal_store(v4f{v0, v1, v2, v3}, &reinterpret_cast<v4f *>(out)[at]);
+            __builtin_nontemporal_store(i4v{b0, b1, b2, b3}, &reinterpret_cast<i4v *>(argmax)[at]);
+        }
+        return;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int rows0 = cnt[u] < 0 ? 0 : (cnt[u] & (PLAN_HAS_DIRECT - 1));
+        const i4v *fb = reinterpret_cast<const i4v *>(feat) + (int64_t)tb[u] * N * rc + chunk0 + c4;
+#pragma unroll
+        for (int q = 0; q < TRIPS; ++q)
+            if (q * 32 + p < rows0) {
+                v[u][q] = fb[(int64_t)rid[u][q] * rc];
+                if (c4 == 0) s_id[u][q * 32 + p] = rid[u][q];
+            }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (j0 + u >= xcount) break;                 // (the same in every thread)
+        if (u > 0) __syncthreads();                  // every centre of the tile before is done with its rows
+        const int rows0 = cnt[u] < 0 ? 0 : (cnt[u] & (PLAN_HAS_DIRECT - 1));
+#pragma unroll
+        for (int q = 0; q < TRIPS; ++q) {
+            const int r = q * 32 + p;
+            if (r < rows0) {
+                s_v[r * 16 + c4] = __builtin_bit_cast(v4f, v[u][q]);
+            }
+        }
+        __syncthreads();
+        const int b = tb[u], m0 = tm0[u], np = min(T, N - m0), m = m0 + p;
+        if (p < np) {
+            const v4f *frow = reinterpret_cast<const v4f *>(feat) + (int64_t)b * N * rc + chunk0 + c4;
+            const int32_t *nb = nbr + (int64_t)b * K * N + m;
+            float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+            int b0 = 0, b1 = 0, b2 = 0, b3 = 0;
+            auto sel = [](float x, int n, float &bv, int &bn) __attribute__((always_inline)) {
+                const bool better = (x > bv) | ((x == bv) & (n < bn));
+                bv = better ? x : bv;
+                bn = better ? n : bn;
+            };
+            auto take_row = [&](const v4f &x, int n, bool first) __attribute__((always_inline)) {
+                if (first) {
+                    v0 = x.x; v1 = x.y; v2 = x.z; v3 = x.w; b0 = b1 = b2 = b3 = n;
+                } else {
+                    sel(x.x, n, v0, b0);
+                    sel(x.y, n, v1, b1);
+                    sel(x.z, n, v2, b2);
+                    sel(x.w, n, v3, b3);
+                }
+            };
+            const unsigned swu = sw[u];
+            if (cnt[u] >= 0 && !(cnt[u] & PLAN_HAS_DIRECT) && K <= 16) {
+#define FLEX_PLAN_FWD_BATCH(J)                                                                                  \
+                if ((J) < K) {                                                                                      \
+                    const unsigned w0 = (unsigned)row_bcast<(J)>((int)swu), w1 = (unsigned)row_bcast<((J) + 1) & 15>((int)swu), \
+                                   w2 = (unsigned)row_bcast<((J) + 2) & 15>((int)swu), w3 = (unsigned)row_bcast<((J) + 3) & 15>((int)swu); \
+                    const v4f x0 = s_v[w0 * 16 + c4], x1 = s_v[w1 * 16 + c4], x2 = s_v[w2 * 16 + c4], x3 = s_v[w3 * 16 + c4]; \
+                    const int n0 = s_id[u][w0], n1 = s_id[u][w1], n2 = s_id[u][w2], n3 = s_id[u][w3];                          \
+                    take_row(x0, n0, (J) == 0);                                                                     \
+                    if ((J) + 1 < K) take_row(x1, n1, false);                                                       \
+                    if ((J) + 2 < K) take_row(x2, n2, false);                                                       \
+                    if ((J) + 3 < K) take_row(x3, n3, false);                                                       \
+                }
+                FLEX_PLAN_FWD_BATCH(0) FLEX_PLAN_FWD_BATCH(4) FLEX_PLAN_FWD_BATCH(8) FLEX_PLAN_FWD_BATCH(12)
+#undef FLEX_PLAN_FWD_BATCH
+            } else {
+                for (int k = 0; k < K; ++k) {
+                    const unsigned place = cnt[u] < 0 ? PLAN_DIRECT : plan_slot[((int64_t)b * N + m) * K + k];
+                    if (place < (unsigned)RMAX) {
+                        take_row(s_v[place * 16 + c4], s_id[u][place], k == 0);
+                    } else {
+                        const int n = nb[(int64_t)k * N];
+                        take_row(frow[(int64_t)n * rc], n, k == 0);
+                    }
+                }
+            }
+            const int64_t at = ((int64_t)b * N + m) * rc + chunk0 + c4;
+            __builtin_nontemporal_store(v4f{v0, v1, v2, v3}, &reinterpret_cast<v4f *>(out)[at]);
+            __builtin_nontemporal_store(i4v{b0, b1, b2, b3}, &reinterpret_cast<i4v *>(argmax)[at]);
+        }
+    }
+}
+
+hipError_t launch_pool_fwd_planned(const float *feat, const int32_t *nbr, void *plan, float *out, int32_t *argmax,
+                                   int B, int N, int K, int C, hipStream_t s)
+{
+    const PoolPlanLayout l = pool_plan_layout(B, N, K);
+    if (l.tiles > 0x7fffffff - 64 || C % 64 != 0 || C > 256) return hipErrorInvalidValue;
+    char *base = reinterpret_cast<char *>(plan);
+    const int32_t *hdr = reinterpret_cast<const int32_t *>(base + l.hdr_off);
+    const int64_t per_xcd = (l.tiles + 7) >> 3, wgs = 8 * ((per_xcd + POOL_FWD_PLAN_TPW - 1) / POOL_FWD_PLAN_TPW);
+    for (int blk = 0; blk < C / 64; ++blk)
+        hipLaunchKernelGGL(pool_fwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, feat, nbr, hdr,
+                           reinterpret_cast<const int32_t *>(base + l.cnt_off),
+                           reinterpret_cast<const int32_t *>(base + l.rows_off),
+                           reinterpret_cast<const unsigned short *>(base + l.slot_off), out, argmax, N, K,
+                           l.tiles_per_cloud, (int)l.tiles, C / 4, 16 * blk);
     return hipGetLastError();
 }
 

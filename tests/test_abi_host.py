@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(L):
             "flexconv_bwd_pos", "flexpool_sub_fwd", "flexpool_sub_bwd", "flex_inedges_build_sub",
             "flexconv_compose_1x1", "flexconv_compose_1x1_bwd", "flex_idiss_phi", "flex_idiss_sample", "flex_knn",
             "flex_selection_make_distinct", "flexpool_plan_bytes", "flexpool_plan_build",
-            "flexpool_bwd_planned"} <= set(names)
+            "flexpool_bwd_planned", "flexpool_fwd_plan_build", "flexpool_fwd_planned"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -91,6 +91,19 @@ def test_pooling_plan_size_and_errors_precede_any_launch(L):
     assert L.flexpool_bwd_planned(one, one, one, one, one, one, need, 1, 64, 2, 0, 1, None) == 2
     assert L.flexpool_bwd_planned(one, one, one, one, one, one, need - 1, 1, 64, 2, 64, 1, None) == 4
     assert L.flexpool_bwd_planned(one, one, one, one, one, ctypes.c_void_p(260), need, 1, 64, 2, 64, 1, None) == 4
+    # flexpool_fwd_plan_build(nbr, B, N, K, plan, plan_bytes, stream)
+    assert L.flexpool_fwd_plan_build(none, 1, 64, 2, one, need, None) == 1
+    assert L.flexpool_fwd_plan_build(one, 1, 64, 2, none, need, None) == 1
+    assert L.flexpool_fwd_plan_build(one, 1, 64, 65, one, need, None) == 2
+    assert L.flexpool_fwd_plan_build(one, 1, 64, 2, one, need - 1, None) == 4
+    assert L.flexpool_fwd_plan_build(one, 1, 64, 2, ctypes.c_void_p(260), need, None) == 4
+    # flexpool_fwd_planned(feat, nbr, out, argmax, plan, plan_bytes, B, N, K, C, layout, stream)
+    assert L.flexpool_fwd_planned(one, one, one, one, none, need, 1, 64, 2, 64, 1, None) == 1
+    assert L.flexpool_fwd_planned(one, one, none, one, one, need, 1, 64, 2, 64, 1, None) == 1
+    assert L.flexpool_fwd_planned(one, one, one, one, one, need, 1, 64, 2, 64, 5, None) == 2
+    assert L.flexpool_fwd_planned(one, one, one, one, one, need, 1, 64, 2, 0, 1, None) == 2
+    assert L.flexpool_fwd_planned(one, one, one, one, one, need - 1, 1, 64, 2, 64, 1, None) == 4
+    assert L.flexpool_fwd_planned(one, one, one, one, ctypes.c_void_p(260), need, 1, 64, 2, 64, 1, None) == 4
 
 
 def test_upsampling_and_location_gradient_errors_precede_any_launch(L):

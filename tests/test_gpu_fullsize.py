@@ -180,6 +180,12 @@ def test_pooling_every_point(work):
     assert torch.equal(pa.transpose(1, 2).cpu(), torch.from_numpy(ra))
     assert torch.equal(po.transpose(1, 2).cpu().view(torch.int32), torch.from_numpy(ro).view(torch.int32))
     del ro
+    # the form bench.py times: through the static gather plan; the same comparisons in the same order
+    fplan = fx.flexpool_fwd_plan_build(work.nbr)
+    ppo, ppa = fx.flexpool_fwd_planned(feat, work.nbr, fplan, layout=fx.BNC)
+    torch.cuda.synchronize()
+    assert torch.equal(ppa, pa) and torch.equal(ppo.view(torch.int32), po.view(torch.int32))
+    del ppo, ppa, fplan
     gp = work.g if work.g is not None and cfg.Din == cfg.Dout else torch.randn_like(feat)
     pg = fx.flexpool_bwd(gp, pa, layout=fx.BNC, in_edges=work.edges)
     pg_scatter = fx.flexpool_bwd(gp, pa, layout=fx.BNC)

@@ -55,25 +55,28 @@ def test_layer_step_replays_from_a_graph(cfg_i, n, widths):
         torch.cuda.synchronize()
 
 
-def test_planned_pooling_backward_replays_from_a_graph():
-    """flexpool_bwd_planned = a fill kernel (its tile counters) and two kernels: capturable like the rest; a cloud
-    large enough for the planned kernel to be the one that runs."""
+def test_planned_pooling_replays_from_a_graph():
+    """flexpool_fwd_planned and flexpool_bwd_planned = a fill kernel (the tile counters) and two kernels each:
+    capturable like the rest; a cloud large enough for the planned kernels to be the ones that run."""
     B, N, K, C = 1, 600_000, 8, 64
-    say(f"graph capture of the planned pooling backward, N={N}")
+    say(f"graph capture of the planned pooling passes, N={N}")
     rng = np.random.default_rng(1)
     nbr = dev(((np.arange(N)[None, None, :] + rng.integers(-20, 21, size=(B, K, N))) % N).astype(np.int32))
     feat = torch.randn(B, N, C, device="cuda")
     gpool = torch.randn_like(feat)
     edges = fx.flex_inedges_build(nbr)
     plan = fx.flexpool_plan_build(edges, B, N)
+    fplan = fx.flexpool_fwd_plan_build(nbr)
 
     def step():
-        po, pa = fx.flexpool_fwd(feat, nbr, layout=fx.BNC)
+        po, pa = fx.flexpool_fwd_planned(feat, nbr, fplan, layout=fx.BNC)
         return po, pa, fx.flexpool_bwd_planned(gpool, pa, edges, plan, layout=fx.BNC)
 
     eager = [t.clone() for t in step()]
+    plain = fx.flexpool_fwd(feat, nbr, layout=fx.BNC)
     listed = fx.flexpool_bwd(gpool, eager[1], layout=fx.BNC, in_edges=edges)
     torch.cuda.synchronize()
+    assert torch.equal(plain[0].view(torch.int32), eager[0].view(torch.int32)) and torch.equal(plain[1], eager[1])
     assert torch.equal(listed.view(torch.int32), eager[2].view(torch.int32))
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())

@@ -1,6 +1,7 @@
-"""GPU parity for the flex-max-pooling backward pass through the static gather plan (flexpool_plan_build,
+"""GPU parity for flex-max-pooling through the static gather plans.  Backward (flexpool_plan_build,
 flexpool_bwd_planned): the result must equal the list form of flexpool_bwd bit for bit (same sums, same order) and
-the CPU oracle within the pooling-backward tolerance.  The cases reach every branch of the planned kernel: tiles
+the CPU oracle within the pooling-backward tolerance.  Forward (flexpool_fwd_plan_build, flexpool_fwd_planned): values
+and winners must equal flexpool_fwd's bit for bit, and the oracle's.  The cases reach every branch of the planned kernels: tiles
 whose rows are all staged, tiles with more distinct rows than the plan lists (entries fetched directly), tiles with
 more entries than the plan covers (served entry by entry), lists longer than a row group's sixteen slot words,
 repeated entries, ragged tails, several clouds, fewer tiles than workgroups; clouds without locality, where the
@@ -41,6 +42,10 @@ def lists(kind, rng, B, N, K):
     if kind == "repeats":                # every centre lists its first neighbour twice
         near[:, K - 1, :] = near[:, 0, :]
         return near
+    if kind == "far":                    # the centres of one tile list points from all over the cloud: more distinct
+        if K >= 6:                       # rows than the forward plan lists, fewer entries than it covers
+            near[:, 1:6, 320:352] = rng.integers(0, N, size=(B, 5, 32))
+        return near
     raise ValueError(kind)
 
 
@@ -51,7 +56,15 @@ def run_case(seed, B, N, K, C, layout, kind):
     g = rng.standard_normal((B, C, N)).astype(np.float32)
     nbr = lists(kind, rng, B, N, K)
     dn = dev(nbr)
-    out, arg = fx.flexpool_fwd(to_layout(feat, layout), dn, layout=layout)
+    df = to_layout(feat, layout)
+    out, arg = fx.flexpool_fwd(df, dn, layout=layout)
+    fplan = fx.flexpool_fwd_plan_build(dn)
+    for _ in range(2):
+        pout, parg = fx.flexpool_fwd_planned(df, dn, fplan, layout=layout)
+        torch.cuda.synchronize()
+        assert torch.equal(arg, parg) and torch.equal(out.view(torch.int32), pout.view(torch.int32))
+    ro, ra = oracle.flexpool_fwd(feat, nbr)
+    assert np.array_equal(from_layout(pout, layout), ro.astype(np.float32))
     edges = fx.flex_inedges_build(dn)
     plan = fx.flexpool_plan_build(edges, B, N)
     dg = to_layout(g, layout)
@@ -61,22 +74,21 @@ def run_case(seed, B, N, K, C, layout, kind):
     torch.cuda.synchronize()
     assert torch.equal(ref.view(torch.int32), got.view(torch.int32)), float((ref - got).abs().max())
     assert torch.equal(got.view(torch.int32), again.view(torch.int32))
-    _, ra = oracle.flexpool_fwd(feat, nbr)
     assert np.array_equal(from_layout(arg, layout), ra)
     # fp32 sums in list order against the oracle's fp64: 1e-5 for neighbourhood-sized lists; the hub point adds up
     # N / 2 terms one after the other (about n 2^-24 of the sum of magnitudes: the list form's own accuracy)
     assert rel_err(from_layout(got, layout), oracle.flexpool_bwd(g, ra)) <= (1e-4 if kind == "hub" else 1e-5)
-    return plan
+    return plan, fplan
 
 
-@pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "scattered", "repeats"])
+@pytest.mark.parametrize("kind", ["local", "random", "hub", "long_list", "scattered", "repeats", "far"])
 @pytest.mark.parametrize("B,N,K", [(1, 1, 1), (1, 31, 4), (2, 33, 8), (3, 1000, 8), (1, 5000, 16), (2, 4097, 9),
                                    (1, 70000, 8), (2, 300_001, 8), (1, 600_000, 9), (64, 9001, 8)])
 def test_planned_backward_equals_the_list_form(B, N, K, kind):
-    if kind in ("hub", "long_list", "scattered") and N < 1000:
+    if kind in ("hub", "long_list", "scattered", "far") and N < 1000:
         pytest.skip("needs a cloud with room for the construction")
     say(f"pool plan: B={B} N={N} K={K} lists={kind}")
-    plan = run_case(100 * N + K, B, N, K, 64, fx.BNC, kind)
+    plan, fplan = run_case(100 * N + K, B, N, K, 64, fx.BNC, kind)
     # what the plan says about its tiles: every branch of the kernel is reached by some case
     tiles = B * ((N + 31) // 32)
     cnt = plan[256:256 + 4 * tiles].view(torch.int32).cpu().numpy()
@@ -92,6 +104,18 @@ def test_planned_backward_equals_the_list_form(B, N, K, kind):
         assert uncovered * 8 > tiles
     if kind == "local" and K <= 9:       # the paper's neighbourhood sizes: every row of every tile is staged
         assert (cnt >= 0).all() and (cnt < 2 ** 30).all()
+    # the forward plan: the same header over the neighbour lists themselves
+    fcnt = fplan[256:256 + 4 * tiles].view(torch.int32).cpu().numpy()
+    funcovered = int(fplan[:4].view(torch.int32).item())
+    say(f"  forward: not covered {int((fcnt < 0).sum())}, with direct entries {int(((fcnt >= 0) & (fcnt >= 2 ** 30)).sum())}"
+        f" -> {'plain kernel' if funcovered * 8 > tiles else 'planned kernel'}")
+    assert funcovered == int(((fcnt < 0) | (fcnt >= 2 ** 30)).sum())
+    if kind == "far" and 6 <= K <= 9:    # one tile per cloud fetches rows directly inside the planned kernel
+        assert ((fcnt >= 0) & (fcnt >= 2 ** 30)).sum() >= B and funcovered * 8 <= tiles
+    if kind == "random" and N >= 1000:
+        assert funcovered * 8 > tiles
+    if kind in ("local", "hub", "long_list", "scattered", "repeats") and K <= 9:
+        assert (fcnt >= 0).all() and (fcnt < 2 ** 30).all()
 
 
 @pytest.mark.parametrize("C,layout,K", [(64, fx.BCN, 8), (32, fx.BNC, 8), (192, fx.BNC, 8), (5, fx.BCN, 8),
@@ -128,4 +152,11 @@ def test_plan_arguments_are_checked():
     assert L.flexpool_bwd_planned(p(g), p(arg), p(out), p(off), p(src), p(plan), need - 1, B, N, K, 64, fx.BNC, None) == 4
     assert L.flexpool_bwd_planned(p(g), p(arg), p(out), p(off), p(src), None, need, B, N, K, 64, fx.BNC, None) == 1
     assert L.flexpool_bwd_planned(p(g), p(arg), p(out), p(off), p(src), p(plan), need, B, N, K, 64, 7, None) == 2
+    assert L.flexpool_fwd_plan_build(p(dn), B, N, K, p(plan), need - 1, None) == 4
+    assert L.flexpool_fwd_plan_build(None, B, N, K, p(plan), need, None) == 1
+    assert L.flexpool_fwd_plan_build(p(dn), B, N, K, p(plan), need, None) == 0
+    assert L.flexpool_fwd_planned(p(g), p(dn), p(out), p(arg), p(plan), need - 1, B, N, K, 64, fx.BNC, None) == 4
+    assert L.flexpool_fwd_planned(p(g), p(dn), p(out), p(arg), None, need, B, N, K, 64, fx.BNC, None) == 1
+    assert L.flexpool_fwd_planned(p(g), p(dn), p(out), p(arg), p(plan), need, B, N, K, 64, 7, None) == 2
+    assert L.flexpool_fwd_planned(p(g), p(dn), p(out), p(arg), p(plan), need, B, N, K, 64, fx.BNC, None) == 0
     torch.cuda.synchronize()
