@@ -223,9 +223,10 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  *   flexpool_fwd_planned     out / argmax of flexpool_fwd, bit for bit (the same comparisons in the same slot order);
  *                            arguments as flexpool_fwd, plus the plan.  The planned kernel runs under the conditions
  *                            of flexpool_bwd_planned (point-major, C = 64 / 128 / 256, K <= FLEX_POOL_PLAN_MAX_K,
- *                            B N >= FLEX_POOL_PLAN_MIN_POINTS, a cloud whose tiles the plan covers), else
- *                            flexpool_fwd's own kernels.  The call only reads the plan: forward calls that
- *                            share one may overlap.
+ *                            B N >= FLEX_POOL_PLAN_MIN_POINTS), else flexpool_fwd's own kernels; on a cloud whose
+ *                            tiles the plan does not cover (stored without locality) the planned kernel itself
+ *                            takes flexpool_fwd's steps, a few per cent slower than flexpool_fwd would.  The call
+ *                            only reads the plan: forward calls that share one may overlap.
  * Errors: FLEX_ERR_NULL, FLEX_ERR_SHAPE as flexpool_fwd; FLEX_ERR_WORKSPACE for a plan that is too small or
  * misaligned; nothing is launched then.
  */
