@@ -160,3 +160,15 @@ def test_plan_arguments_are_checked():
     assert L.flexpool_fwd_planned(p(g), p(dn), p(out), p(arg), p(plan), need, B, N, K, 64, 7, None) == 2
     assert L.flexpool_fwd_planned(p(g), p(dn), p(out), p(arg), p(plan), need, B, N, K, 64, fx.BNC, None) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_planned_passes_on_random_shapes(case):
+    """Seeded random cloud counts, sizes, K and widths with a planned kernel, lists with and without locality
+    (under FLEX_POOL_PLAN=1 every case runs the planned kernels; without it the sizes here run the plain ones)."""
+    rng = np.random.default_rng(7100 + case)
+    B, N = int(rng.integers(1, 4)), int(rng.integers(2, 3000))
+    K, C = int(rng.integers(1, min(N, 20) + 1)), int(rng.choice([64, 128, 256]))
+    kind = str(rng.choice(["local", "random", "repeats"]))
+    say(f"random planned case {case}: B={B} N={N} K={K} C={C} lists={kind}")
+    run_case(7100 + case, B, N, K, C, fx.BNC, kind)
