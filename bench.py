@@ -336,11 +336,11 @@ def main():
                  "bwd_params": "grad_theta_lean_kernel (flexconv_bwd, parameter gradients)",
                  "bwd_feat": "grad_feat_lean_kernel (flexconv_bwd, feature gradient)",
                  "pool_fwd": ("pool_fwd_planned64_kernel (flexpool_fwd_planned)"
-                              if pool_fwd_plan is not None and layout == fx.BNC and Din in (64, 128, 256) and K <= 10 and B * N >= (1 << 19)
+                              if pool_fwd_plan is not None and layout == fx.BNC and Din in (64, 128, 256) and K <= 10 and B * N >= (1 << 18)
                               else "pool_fwd_bnc4_kernel (flexpool_fwd)"),
                  "pool_fwd_plain": "pool_fwd_bnc4_kernel (flexpool_fwd)",
                  "pool_bwd": ("pool_bwd_planned64_kernel (flexpool_bwd_planned)"
-                              if pool_plan is not None and layout == fx.BNC and Din in (64, 128, 256) and K <= 10 and B * N >= (1 << 19)
+                              if pool_plan is not None and layout == fx.BNC and Din in (64, 128, 256) and K <= 10 and B * N >= (1 << 18)
                               else "pool_bwd_gather_row16_kernel (flexpool_bwd)"),
                  "upsample_fwd": "upsample_fwd_bnc4_kernel (flexupsample_fwd)",
                  "upsample_bwd": "upsample_bwd_bnc4_kernel (flexupsample_bwd)",

@@ -200,15 +200,16 @@ int flexpool_bwd(const float *grad_out, const int32_t *argmax, float *grad_feat,
  *                         FLEX_POOL_PLAN_MIN_POINTS points in all runs the planned kernel (that is where it is
  *                         the faster one), everything else the list form itself.  grad_out / argmax / grad_feat
  *                         as for flexpool_bwd.
- * The plan's last 2 KB are scratch of the kernel (the tile counters its workgroups draw from, cleared at
- * every call): calls that share a plan must not overlap in time; nothing else of it is written after the build.
+ * The plan's last 2 KB are scratch of the call (tile counters of the list form that runs in the planned kernel's
+ * place on clouds without locality, cleared at every call): calls that share a plan must not overlap in time;
+ * nothing else of it is written after the build.
  * The plan depends on the lists only, not on the tensors: build it once per cloud.  It is dimensioned for the
  * paper's neighbourhood sizes (K = 8 or 9): a tile's plan holds up to 127 distinct centres and covers up to 512
  * list entries; what exceeds that is fetched entry by entry, correctly but without the saving, and where more
  * than an eighth of the tiles exceed it (point orders without locality) the call runs the list form instead.
  */
 #define FLEX_POOL_PLAN_MAX_K 10
-#define FLEX_POOL_PLAN_MIN_POINTS (1 << 19)
+#define FLEX_POOL_PLAN_MIN_POINTS (1 << 18)
 
 /*
  * Flex-max-pooling forward with a static gather plan: the same idea for the forward pass (Sec. 4.1; Table 1: it

@@ -403,7 +403,7 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
     pool_bwd_gather_row16_tile<U>(grad_out, argmax, in_off, in_src, grad_feat, BN, N, L, C4, PT, tile);
 }
 
-// ---- gather form with a static plan (C == 64, point-major) ---------------------------------------------------
+// ---- gather form with a static plan (point-major, 64-channel blocks of the rows) ---------------------------------------------------
 // Neighbouring points are listed by mostly the same centres: the 32 consecutive points of a tile have about 256
 // list entries but only about 94 distinct source rows, and the kernels above ask the texture path for a row's
 // 512 bytes (winner table + gradient) once per entry.  The neighbourhoods are static (Sec. 4.1), so which rows a
@@ -420,14 +420,13 @@ __global__ __launch_bounds__(256) void pool_bwd_gather_row16_kernel(
 //                                 PLAN_NULL if the entry repeats the one before it in the same list (it routes
 //                                 nothing: the kernel keeps a row that matches no point at that place);
 //                                 PLAN_DIRECT if its row is not listed (fetch it by in_src)
-//   ctr  int32 [8][64]           scratch of the kernel: the next tile of each XCD's share, one counter per
-//                                 256-byte block (cleared at every launch)
+//   ctr  int32 [8][64]           scratch of the list-form kernel that runs where the plan does not pay: the next
+//                                 tile of each XCD's share, one counter per 256-byte block (cleared at every call)
 // A row listed twice (two entries of one tile that lost each other in the hash table) costs bandwidth only.
 constexpr int PLAN_T = 32, PLAN_RMAX = 128, PLAN_EMAX = 512, PLAN_HASH = 2048;
 constexpr unsigned PLAN_NULL = PLAN_RMAX - 1, PLAN_DIRECT = 0x7fffu;
 constexpr int PLAN_HAS_DIRECT = 1 << 30;
 constexpr int PLAN_CTR_STRIDE = 64;     // ints between the XCDs' counters: a 256-byte block each
-constexpr int PLAN_DRAW = 4;            // tiles a workgroup draws at a time
 // the plan pays where most tiles are covered in full
 __device__ __forceinline__ bool pool_plan_pays(const int32_t *plan_hdr, int total_tiles)
 {
@@ -450,7 +449,7 @@ static PoolPlanLayout pool_plan_layout(int B, int N, int K)
     l.rows_off = l.cnt_off + up(sizeof(int32_t) * (size_t)l.tiles);
     l.slot_off = l.rows_off + up(sizeof(int32_t) * (size_t)l.tiles * PLAN_RMAX);
     l.ctr_off = l.slot_off + up(sizeof(unsigned short) * (size_t)B * K * N);
-    l.bytes = l.ctr_off + 8 * PLAN_CTR_STRIDE * sizeof(int32_t);   // tile counters of the kernel, one per XCD
+    l.bytes = l.ctr_off + 8 * PLAN_CTR_STRIDE * sizeof(int32_t);   // tile counters of the list-form kernel, one per XCD
     return l;
 }
 size_t pool_plan_bytes(int B, int N, int K) { return pool_plan_layout(B, N, K).bytes; }
@@ -593,191 +592,142 @@ hipError_t launch_pool_fwd_plan_build(const int32_t *nbr, void *plan, int B, int
 }
 
 // The sums of one point, entry by entry from memory (tiles and entries the plan does not cover).
-__device__ __forceinline__ void pool_bwd_entry_direct(v4f &acc, const v4f *g4, const int4 *a4, int l, bool fresh, int m,
-                                                      int rc)
-{
-    const int4 a = a4[(int64_t)l * rc];
-    const v4f g = g4[(int64_t)l * rc];
-    acc.x += (fresh && a.x == m) ? g.x : 0.f;
-    acc.y += (fresh && a.y == m) ? g.y : 0.f;
-    acc.z += (fresh && a.z == m) ? g.z : 0.f;
-    acc.w += (fresh && a.w == m) ? g.w : 0.f;
-}
-
-// Persistent workgroups of 512 threads; a workgroup walks its tiles with three stages in flight: the list bounds of
-// tile i + 3, the plan (row list, the lane's slot word) of tile i + 2, the rows of tile i + 1 (in registers), while
-// tile i is summed from LDS.  16 lanes own one point (4 channels each) and, for staging, rows r = 32 q + group.
-// The sums run in list order with the same operations as the kernels above: bit-identical results.
-__global__ __launch_bounds__(512) void pool_bwd_planned64_kernel(
+// One workgroup of 512 threads per (POOL_BWD_PLAN_TPW consecutive tiles, half of the block's 64 channels), dispatched
+// in order (block index -> XCD share, position in it, channel half), four workgroups per CU (58 registers, 32 KB of
+// LDS).  A staged half row is 8 x 16 bytes of the winner table and 8 x 16 bytes of the gradient, kept as they are in
+// memory, in two planes; place PLAN_NULL holds a row that no point wins (index -1).  A workgroup asks for list
+// bounds and plan, then for the rows of both its tiles (the second tile's wait in registers while the first is summed);
+// 8 lanes stage a row half, 16 lanes own a point (2 channels each).  The sums run in list order with the same
+// operations as the kernels above: bit-identical results.
+typedef int i2v __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+constexpr int POOL_BWD_PLAN_TPW = 2;
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(8, 8))) void pool_bwd_planned64_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
     const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, const int32_t *__restrict__ plan_cnt,
-    const int32_t *__restrict__ plan_rows, const unsigned short *__restrict__ plan_slot, int *__restrict__ tile_ctr,
+    const int32_t *__restrict__ plan_rows, const unsigned short *__restrict__ plan_slot,
     float *__restrict__ grad_feat, int N, int L, int tiles_per_cloud, int total_tiles, int rc, int chunk0)
 {
-    // rc: 16-byte chunks per row of the tensors (C / 4); chunk0: first chunk of the 64-channel block this launch serves
-    constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 32;
-    if (!pool_plan_pays(plan_hdr, total_tiles)) return;      // (the same in every thread) the list form runs instead
-    // a staged row: 16 x 16 bytes of the winner table, then 16 x 16 bytes of the gradient; place PLAN_NULL holds a
-    // row that no point wins (index -1)
-    __shared__ i4v s_r[RMAX * 32];
-    const int tid = threadIdx.x, c4 = tid & 15, t16 = tid & 15, p = tid >> 4;
-    if (tid < 32) s_r[PLAN_NULL * 32 + tid] = tid < 16 ? i4v{-1, -1, -1, -1} : i4v{0, 0, 0, 0};
-    // XCD x (= block id mod 8) owns a contiguous eighth of the tiles.  Its workgroups draw them from a counter, in
-    // order, four at a time and well ahead of the tile they sum: whatever the pace of each workgroup, the tiles
-    // being staged at any moment are a short run of neighbours, whose shared rows meet in the XCD's L2.  (Dealt out
-    // in fixed turns the workgroups drift apart over their four hundred tiles and rows are fetched from HBM 1.9
-    // times; one draw per tile, with all counters in one cache line, made the counter the bottleneck.)
-    constexpr int DRAW = PLAN_DRAW, AHEAD = (5 + DRAW - 1) / DRAW, RING = 8;   // draws in flight: tile i + 4 is looked up in iteration i
-    static_assert(AHEAD + 2 <= RING, "a draw is published one iteration after it is made");
-    __shared__ int s_draw[RING];        // first tile of the workgroup's draw m at [m % RING]
+    constexpr int T = PLAN_T, RMAX = PLAN_RMAX, TRIPS = RMAX / 64, U = POOL_BWD_PLAN_TPW;
+    __shared__ i4v s_a[RMAX * 8];       // staged half rows of the winner table: 8 x 16 bytes each
+    __shared__ i4v s_g[RMAX * 8];       // ... and of the gradient
+    const int tid = threadIdx.x, c8 = tid & 7, pr = tid >> 3;        // staging: 64 row groups of 8 lanes
+    const int c2 = tid & 15, t16 = tid & 15, p = tid >> 4;           // sums: 16 lanes (2 channels each) per point
     const int per_xcd = (total_tiles + 7) >> 3;
     const int xbeg = (int)(blockIdx.x & 7) * per_xcd;
     const int xcount = min(per_xcd, total_tiles - xbeg);
-    if (xcount <= 0) return;
-    int *ctr = tile_ctr + (blockIdx.x & 7) * PLAN_CTR_STRIDE;
-    struct Tc { int b, tic; bool valid; };
-    auto tile_at = [&](int k) __attribute__((always_inline)) {       // the workgroup's k-th tile; past the share: its last tile, not summed
-        const int j = __builtin_amdgcn_readfirstlane(s_draw[(k / DRAW) % RING]) + k % DRAW;
-        const int t = xbeg + min(j, xcount - 1);
-        const int b = t / tiles_per_cloud;
-        return Tc{b, t - b * tiles_per_cloud, j < xcount};
-    };
-    if (tid == 0) {
+    const int wgx = (int)(blockIdx.x >> 3);
+    const int half = wgx & 1;
+    const int j0 = (wgx >> 1) * U;
+    if (j0 >= xcount) return;
+    if (!pool_plan_pays(plan_hdr, total_tiles)) return;      // (the same in every thread) the list form runs instead
+    if (tid < 8) s_a[PLAN_NULL * 8 + tid] = i4v{-1, -1, -1, -1};
+    else if (tid < 16) s_g[PLAN_NULL * 8 + tid - 8] = i4v{0, 0, 0, 0};
+    const int ch0 = chunk0 + 8 * half;                       // first 16-byte chunk of this pass's 32 channels
+    int tb[U], tm0[U], cnt[U], e0[U], en[U], rid[U][TRIPS];
+    unsigned sw[U];
+    i4v a[U][TRIPS], g[U][TRIPS];
 #pragma unroll
-        for (int m = 0; m < AHEAD; ++m) s_draw[m] = atomicAdd(ctr, DRAW);
-    }
-    __syncthreads();
-    struct Bounds { int e0, n; };
-    auto load_bounds = [&](const Tc &c) __attribute__((always_inline)) {
-        const int m0 = c.tic * T;
-        const int np = min(T, N - m0);
-        const int32_t *o = in_off + ((int64_t)c.b * N + m0);
+    for (int u = 0; u < U; ++u) {
+        const int tile = xbeg + min(j0 + u, xcount - 1);
+        tb[u] = tile / tiles_per_cloud;
+        tm0[u] = (tile - tb[u] * tiles_per_cloud) * T;
+        const int np = min(T, N - tm0[u]);
+        const int32_t *o = in_off + ((int64_t)tb[u] * N + tm0[u]);
         const int lo = o[min(p, np)], hi = o[min(p + 1, np)];
-        return Bounds{lo, hi - lo};
-    };
-    int cnt0, cnt1, rid1[TRIPS];
-    unsigned sw0, sw1;
-    i4v a[TRIPS], g[TRIPS];
-    auto load_plan = [&](const Tc &c, const Bounds &bd, int &cnt, int (&rid)[TRIPS], unsigned &sw) __attribute__((always_inline)) {
-        const int tile = c.b * tiles_per_cloud + c.tic;
-        cnt = plan_cnt[tile];
-        const int32_t *rows = plan_rows + (int64_t)tile * RMAX + p;
+        e0[u] = lo;
+        en[u] = hi - lo;
+        cnt[u] = plan_cnt[tile];
+        const int32_t *rows = plan_rows + (int64_t)tile * RMAX + pr;
 #pragma unroll
-        for (int q = 0; q < TRIPS; ++q) rid[q] = rows[q * 32];
-        // lanes past the list take the row that matches nothing
-        sw = t16 < bd.n ? plan_slot[(size_t)bd.e0 + t16] : PLAN_NULL;
-    };
-    auto issue_rows = [&](const Tc &c, int cnt, const int (&rid)[TRIPS]) __attribute__((always_inline)) {
-        const i4v *gb = reinterpret_cast<const i4v *>(grad_out) + (int64_t)c.b * L * rc + chunk0 + c4;
-        const i4v *ab = reinterpret_cast<const i4v *>(argmax) + (int64_t)c.b * L * rc + chunk0 + c4;
-        const int rows = cnt < 0 ? 0 : (cnt & (PLAN_HAS_DIRECT - 1));
+        for (int q = 0; q < TRIPS; ++q) rid[u][q] = rows[q * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        sw[u] = t16 < en[u] ? plan_slot[(size_t)e0[u] + t16] : PLAN_NULL;      // lanes past the list: the row that matches nothing
+        const i4v *gb = reinterpret_cast<const i4v *>(grad_out) + (int64_t)tb[u] * L * rc + ch0 + c8;
+        const i4v *ab = reinterpret_cast<const i4v *>(argmax) + (int64_t)tb[u] * L * rc + ch0 + c8;
+        const int rows0 = cnt[u] < 0 ? 0 : (cnt[u] & (PLAN_HAS_DIRECT - 1));
 #pragma unroll
         for (int q = 0; q < TRIPS; ++q)
-            if (q * 32 + p < rows) {
-                a[q] = ab[(int64_t)rid[q] * rc];
-                g[q] = gb[(int64_t)rid[q] * rc];
+            if (q * 64 + pr < rows0) {
+                a[u][q] = ab[(int64_t)rid[u][q] * rc];
+                g[u][q] = gb[(int64_t)rid[u][q] * rc];
             }
-    };
-    Tc t0 = tile_at(0), t1 = tile_at(1), t2 = tile_at(2), t3 = tile_at(3);
-    Bounds bd0 = load_bounds(t0), bd1 = load_bounds(t1), bd2 = load_bounds(t2);
-    {
-        int rid0[TRIPS];
-        load_plan(t0, bd0, cnt0, rid0, sw0);
-        load_plan(t1, bd1, cnt1, rid1, sw1);
-        issue_rows(t0, cnt0, rid0);
     }
-    const int lane_base = c4 * 16;          // byte offset of this lane's chunk inside a half row
-
-    int drawn = 0;                          // thread 0: the draw made in the iteration before, not yet published
-    for (int i = 0; t0.valid; ++i) {
-        const int b = t0.b, m0 = t0.tic * T;
-        if (tid == 0 && i > 0 && (i - 1) % DRAW == 0) s_draw[((i - 1) / DRAW + AHEAD) % RING] = drawn;
-        const int np = min(T, N - m0);
-        const int rows0 = cnt0 < 0 ? 0 : (cnt0 & (PLAN_HAS_DIRECT - 1));
-        // rows of tile i: registers -> LDS
+    const int lane_base = c2 * 8;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (j0 + u >= xcount) break;                 // (the same in every thread)
+        if (u > 0) __syncthreads();                  // every sum of the tile before is done with its rows
+        const int rows0 = cnt[u] < 0 ? 0 : (cnt[u] & (PLAN_HAS_DIRECT - 1));
 #pragma unroll
         for (int q = 0; q < TRIPS; ++q) {
-            const int r = q * 32 + p;
+            const int r = q * 64 + pr;
             if (r < rows0) {
-                s_r[r * 32 + c4] = a[q];
-                s_r[r * 32 + 16 + c4] = g[q];
+                s_a[r * 8 + c8] = a[u][q];
+                s_g[r * 8 + c8] = g[u][q];
             }
         }
         __syncthreads();
-        // the next stages go in flight behind the sums of tile i (first of all, every DRAW-th tile, a draw: it is
-        // published at the top of the next iteration and first looked up AHEAD * DRAW - 4 iterations from now)
-        if (tid == 0 && i % DRAW == 0) drawn = atomicAdd(ctr, DRAW);
-        const Bounds bd = bd0;
-        const unsigned sw = sw0;
-        const int cnt = cnt0;
-        issue_rows(t1, cnt1, rid1);
-        cnt0 = cnt1;
-        sw0 = sw1;
-        bd0 = bd1;
-        bd1 = bd2;
-        load_plan(t2, bd1, cnt1, rid1, sw1);
-        bd2 = load_bounds(t3);
-        t0 = t1;
-        t1 = t2;
-        t2 = t3;
-        t3 = tile_at(i + 4);
-
+        const int b = tb[u], m0 = tm0[u], np = min(T, N - m0), n_e = en[u], cn = cnt[u];
+        const size_t eb = (size_t)e0[u];
+        const unsigned swu = sw[u];
         if (p < np) {
-            v4f acc = {0.f, 0.f, 0.f, 0.f};
+            v2f acc = {0.f, 0.f};
             const int m = m0 + p;
-            const char *sb = reinterpret_cast<const char *>(s_r) + lane_base;
+            const char *sa = reinterpret_cast<const char *>(s_a) + lane_base;
+            const char *sg = reinterpret_cast<const char *>(s_g) + lane_base;
             auto take_staged = [&](unsigned place) __attribute__((always_inline)) {
-                const i4v aa = *reinterpret_cast<const i4v *>(sb + place * 512u);
-                const v4f gg = *reinterpret_cast<const v4f *>(sb + place * 512u + 256u);
+                const i2v aa = *reinterpret_cast<const i2v *>(sa + place * 128u);
+                const v2f gg = *reinterpret_cast<const v2f *>(sg + place * 128u);
                 acc.x += aa.x == m ? gg.x : 0.f;
                 acc.y += aa.y == m ? gg.y : 0.f;
-                acc.z += aa.z == m ? gg.z : 0.f;
-                acc.w += aa.w == m ? gg.w : 0.f;
             };
-            if (cnt >= 0 && !(cnt & PLAN_HAS_DIRECT)) {
-                // every entry's row is staged: four entries at a time, no case distinctions
+            if (cn >= 0 && !(cn & PLAN_HAS_DIRECT)) {
 #define FLEX_PLAN_BATCH(J)                                                                                      \
-                if ((J) < bd.n) {                                                                                   \
-                    const unsigned w0 = (unsigned)row_bcast<(J)>((int)sw), w1 = (unsigned)row_bcast<(J) + 1>((int)sw),  \
-                                   w2 = (unsigned)row_bcast<(J) + 2>((int)sw), w3 = (unsigned)row_bcast<(J) + 3>((int)sw); \
-                    const i4v a0 = *reinterpret_cast<const i4v *>(sb + w0 * 512u), a1 = *reinterpret_cast<const i4v *>(sb + w1 * 512u), \
-                               a2 = *reinterpret_cast<const i4v *>(sb + w2 * 512u), a3 = *reinterpret_cast<const i4v *>(sb + w3 * 512u); \
-                    const v4f g0 = *reinterpret_cast<const v4f *>(sb + w0 * 512u + 256u), g1 = *reinterpret_cast<const v4f *>(sb + w1 * 512u + 256u), \
-                              g2 = *reinterpret_cast<const v4f *>(sb + w2 * 512u + 256u), g3 = *reinterpret_cast<const v4f *>(sb + w3 * 512u + 256u); \
-                    acc.x += a0.x == m ? g0.x : 0.f; acc.y += a0.y == m ? g0.y : 0.f; acc.z += a0.z == m ? g0.z : 0.f; acc.w += a0.w == m ? g0.w : 0.f; \
-                    acc.x += a1.x == m ? g1.x : 0.f; acc.y += a1.y == m ? g1.y : 0.f; acc.z += a1.z == m ? g1.z : 0.f; acc.w += a1.w == m ? g1.w : 0.f; \
-                    acc.x += a2.x == m ? g2.x : 0.f; acc.y += a2.y == m ? g2.y : 0.f; acc.z += a2.z == m ? g2.z : 0.f; acc.w += a2.w == m ? g2.w : 0.f; \
-                    acc.x += a3.x == m ? g3.x : 0.f; acc.y += a3.y == m ? g3.y : 0.f; acc.z += a3.z == m ? g3.z : 0.f; acc.w += a3.w == m ? g3.w : 0.f; \
+                if ((J) < n_e) {                                                                                    \
+                    const unsigned w0 = (unsigned)row_bcast<(J)>((int)swu), w1 = (unsigned)row_bcast<(J) + 1>((int)swu),  \
+                                   w2 = (unsigned)row_bcast<(J) + 2>((int)swu), w3 = (unsigned)row_bcast<(J) + 3>((int)swu); \
+                    const i2v a0 = *reinterpret_cast<const i2v *>(sa + w0 * 128u), a1 = *reinterpret_cast<const i2v *>(sa + w1 * 128u), \
+                               a2 = *reinterpret_cast<const i2v *>(sa + w2 * 128u), a3 = *reinterpret_cast<const i2v *>(sa + w3 * 128u); \
+                    const v2f g0 = *reinterpret_cast<const v2f *>(sg + w0 * 128u), g1 = *reinterpret_cast<const v2f *>(sg + w1 * 128u), \
+                              g2 = *reinterpret_cast<const v2f *>(sg + w2 * 128u), g3 = *reinterpret_cast<const v2f *>(sg + w3 * 128u); \
+                    acc.x += a0.x == m ? g0.x : 0.f; acc.y += a0.y == m ? g0.y : 0.f; \
+                    acc.x += a1.x == m ? g1.x : 0.f; acc.y += a1.y == m ? g1.y : 0.f; \
+                    acc.x += a2.x == m ? g2.x : 0.f; acc.y += a2.y == m ? g2.y : 0.f; \
+                    acc.x += a3.x == m ? g3.x : 0.f; acc.y += a3.y == m ? g3.y : 0.f; \
                 }
                 FLEX_PLAN_BATCH(0) FLEX_PLAN_BATCH(4) FLEX_PLAN_BATCH(8) FLEX_PLAN_BATCH(12)
 #undef FLEX_PLAN_BATCH
-                for (int j = 16; j < bd.n; ++j)       // a list longer than the lanes' sixteen slot words
-                    take_staged(plan_slot[(size_t)bd.e0 + j]);
+                for (int j = 16; j < n_e; ++j) take_staged(plan_slot[eb + j]);
             } else {
-                // a tile the plan covers in part or not at all: entry by entry
-                const int4 *a4 = reinterpret_cast<const int4 *>(argmax) + (int64_t)b * L * rc + chunk0 + c4;
-                const v4f *g4 = reinterpret_cast<const v4f *>(grad_out) + (int64_t)b * L * rc + chunk0 + c4;
+                const i2v *a2p = reinterpret_cast<const i2v *>(argmax) + ((int64_t)b * L * rc + ch0) * 2 + c2;
+                const v2f *g2p = reinterpret_cast<const v2f *>(grad_out) + ((int64_t)b * L * rc + ch0) * 2 + c2;
                 int prev = -1;
-                for (int j = 0; j < bd.n; ++j) {
-                    const unsigned place = cnt < 0 ? PLAN_DIRECT : plan_slot[(size_t)bd.e0 + j];
+                for (int j = 0; j < n_e; ++j) {
+                    const unsigned place = cn < 0 ? PLAN_DIRECT : plan_slot[eb + j];
                     if (place < (unsigned)RMAX) {
                         take_staged(place);
                     } else {
-                        const int l = in_src[bd.e0 + j];
-                        pool_bwd_entry_direct(acc, g4, a4, l, l != prev, m, rc);
+                        const int l = in_src[eb + j];
+                        const i2v aa = a2p[(int64_t)l * rc * 2];
+                        const v2f gg = g2p[(int64_t)l * rc * 2];
+                        const bool fresh = l != prev;
+                        acc.x += (fresh && aa.x == m) ? gg.x : 0.f;
+                        acc.y += (fresh && aa.y == m) ? gg.y : 0.f;
                         prev = l;
                     }
                 }
             }
-            __builtin_nontemporal_store(acc, &reinterpret_cast<v4f *>(grad_feat)[((int64_t)b * N + m) * rc + chunk0 + c4]);
+            __builtin_nontemporal_store(acc, &reinterpret_cast<v2f *>(grad_feat)[(((int64_t)b * N + m) * rc + ch0) * 2 + c2]);
         }
-        __syncthreads();        // every sum of tile i is done before the rows of tile i + 1 replace it
     }
 }
 
 // The list form for the clouds whose plan does not pay: the same sums by the same code as flexpool_bwd's kernel, as a
 // grid of resident blocks (a block that has nothing to do costs nothing to launch) which draw the tiles of their
-// XCD's share in order, eight at a time, from a counter of their own beside the planned kernel's.
+// XCD's share in order, eight at a time, from a counter per XCD in the plan's last 2 KB.
 __global__ __launch_bounds__(256) void pool_bwd_gather_row16_unplanned_kernel(
     const float *__restrict__ grad_out, const int32_t *__restrict__ argmax, const int32_t *__restrict__ in_off,
     const int32_t *__restrict__ in_src, const int32_t *__restrict__ plan_hdr, int plan_tiles,
@@ -806,23 +756,23 @@ hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax,
                                    hipStream_t s)
 {
     // C: 64, 128 or 256 (a multiple of 64 whose row fits one block of the list form); the planned kernel serves one
-    // 64-channel block of the rows per launch, each launch drawing its tiles afresh
+    // 64-channel block of the rows per launch
     const PoolPlanLayout l = pool_plan_layout(B, N, K);
     if (l.tiles > 0x7fffffff || C % 64 != 0 || C > 256) return hipErrorInvalidValue;
     char *base = reinterpret_cast<char *>(plan);
     const int32_t *hdr = reinterpret_cast<const int32_t *>(base + l.hdr_off);
-    // two workgroups per CU by LDS and registers; fewer when there are fewer tiles than that
-    int64_t wgs = 2 * 256;
-    if (wgs > ((l.tiles + 7) & ~(int64_t)7)) wgs = (l.tiles + 7) & ~(int64_t)7;
-    for (int blk = 0; blk < C / 64; ++blk) {
-        const hipError_t e = launch_fill_zero(base + l.ctr_off, 8 * PLAN_CTR_STRIDE * sizeof(int32_t), s);
-        if (e != hipSuccess) return e;
+    const int64_t per_xcd = (l.tiles + 7) >> 3, wgs = 8 * 2 * ((per_xcd + POOL_BWD_PLAN_TPW - 1) / POOL_BWD_PLAN_TPW);
+    if (wgs > 0x7fffffff) return hipErrorInvalidValue;
+    for (int blk = 0; blk < C / 64; ++blk)
         hipLaunchKernelGGL(pool_bwd_planned64_kernel, dim3((unsigned)wgs), dim3(512), 0, s, grad_out, argmax, in_off,
                            in_src, hdr, reinterpret_cast<const int32_t *>(base + l.cnt_off),
                            reinterpret_cast<const int32_t *>(base + l.rows_off),
-                           reinterpret_cast<const unsigned short *>(base + l.slot_off),
-                           reinterpret_cast<int *>(base + l.ctr_off), grad_feat, N, N, l.tiles_per_cloud, (int)l.tiles,
-                           C / 4, 16 * blk);
+                           reinterpret_cast<const unsigned short *>(base + l.slot_off), grad_feat, N, N,
+                           l.tiles_per_cloud, (int)l.tiles, C / 4, 16 * blk);
+    {
+        // the list form's tile counters (the plan's last 2 KB)
+        const hipError_t e = launch_fill_zero(base + l.ctr_off, 8 * PLAN_CTR_STRIDE * sizeof(int32_t), s);
+        if (e != hipSuccess) return e;
     }
     {
         const int C4 = C / 4, PT = 256 / C4;
@@ -843,7 +793,7 @@ hipError_t launch_pool_bwd_planned(const float *grad_out, const int32_t *argmax,
 // kernel stages each distinct feature row once in LDS together with its point index, and every centre takes the
 // (value desc, index asc) maximum over its K places: the comparisons of pool_fwd_bnc4_kernel in the same slot order,
 // so values and winners are the same bits.
-// Unlike the backward kernel this one is not resident: one workgroup per POOL_FWD_PLAN_TPW consecutive tiles,
+// Like the backward kernel this one is not resident: one workgroup per POOL_FWD_PLAN_TPW consecutive tiles,
 // dispatched in order (block index -> XCD share, position in it), four workgroups per CU (64 registers, 33 KB of
 // LDS each).  The chain plan -> rows -> LDS is two memory latencies deep and a tile's comparisons are short, so what
 // counts is how many tiles a CU has in flight: a workgroup asks for the plan and then the rows of both its tiles up

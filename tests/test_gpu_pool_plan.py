@@ -6,7 +6,7 @@ whose rows are all staged, tiles with more distinct rows than the plan lists (en
 more entries than the plan covers (served entry by entry), lists longer than a row group's sixteen slot words,
 repeated entries, ragged tails, several clouds, fewer tiles than workgroups; clouds without locality, where the
 plans do not pay and the plain steps run in the planned ones' place (backward: a second kernel; forward: a branch of
-the planned kernel); and the widths and layouts the plans have no kernel for, which run the plain kernels.  The planned kernel is chosen from 2^19 points on (the last two sizes);
+the planned kernel); and the widths and layouts the plans have no kernel for, which run the plain kernels.  The planned kernels are chosen from 2^18 points on (the last three sizes);
 test_gpu_fallbacks.py runs this file once more with FLEX_POOL_PLAN=1, which selects it at every size.  (The 7M-point configuration: test_gpu_fullsize.py.)"""
 import ctypes
 
